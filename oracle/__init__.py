@@ -1,0 +1,130 @@
+"""ctypes front end of the fp64 CPU oracle (oracle/sinkhorn_oracle.c).
+
+TEST INFRASTRUCTURE ONLY: the tests, the smoke check and the benchmark's
+cpu_baseline leg may import this; the product package never does.
+
+The C file is compiled with gcc on first use if the shared object is missing
+or older than its source.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+import subprocess
+
+import numpy as np
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+_SRC = os.path.join(_HERE, "sinkhorn_oracle.c")
+_LIB = os.path.join(_HERE, "libska_oracle.so")
+_lib = None
+
+
+def build(force: bool = False) -> str:
+    stale = (not os.path.exists(_LIB)) or os.path.getmtime(_LIB) < os.path.getmtime(_SRC)
+    if force or stale:
+        subprocess.check_call(["gcc", "-O2", "-fopenmp", "-shared", "-fPIC", "-Wall", "-o", _LIB,
+                               _SRC, "-lm"])
+    return _LIB
+
+
+def _load():
+    global _lib
+    if _lib is None:
+        lib = ctypes.CDLL(build())
+        c_d = ctypes.POINTER(ctypes.c_double)
+        i64, i32 = ctypes.c_int64, ctypes.c_int
+        lib.ska_oracle_threads.restype = i32
+        lib.ska_oracle_core.restype = i32
+        lib.ska_oracle_core.argtypes = [i64, i64, i64, ctypes.c_void_p, ctypes.c_void_p, c_d, c_d,
+                                        c_d, i32, i32, i32, c_d, c_d, c_d, c_d, c_d, c_d, c_d, c_d]
+        lib.ska_oracle_band.restype = i32
+        lib.ska_oracle_band.argtypes = [c_d, c_d, c_d, c_d, i64, i32, i64, i32, i32,
+                                        ctypes.c_double, i32, ctypes.c_double, c_d, c_d, c_d, c_d,
+                                        c_d, c_d, c_d, c_d]
+        _lib = lib
+    return _lib
+
+
+def threads() -> int:
+    return int(_load().ska_oracle_threads())
+
+
+def _p(a):
+    return None if a is None else a.ctypes.data_as(ctypes.POINTER(ctypes.c_double))
+
+
+def _f64(a):
+    return None if a is None else np.ascontiguousarray(a, dtype=np.float64)
+
+
+def core(rptr, col, S, V, G, T, R, v0_fixed=None):
+    """Support-generic solve on explicit edge scores.
+
+    rptr[m+1], col[nnz] describe the active support row by row; S[nnz] are the
+    effective scores.  Returns a dict with O, U[(R+1),m], Vp[(R+1),n] and, when
+    G is given, Sbar[nnz], dV, ubar, vbar.
+    """
+    lib = _load()
+    rptr = np.ascontiguousarray(rptr, dtype=np.int64)
+    col = np.ascontiguousarray(col, dtype=np.int32)
+    S, V, G, v0_fixed = _f64(S), _f64(V), _f64(G), _f64(v0_fixed)
+    m, nnz = len(rptr) - 1, len(col)
+    n, dv = V.shape
+    assert rptr[-1] == nnz and S.shape == (nnz,)
+    assert col.size == 0 or (col.min() >= 0 and col.max() < n)
+    out = {"O": np.empty((m, dv)), "U": np.empty((R + 1, m)), "Vp": np.empty((R + 1, n))}
+    if G is not None:
+        assert G.shape == (m, dv)
+        out.update(Sbar=np.empty(nnz), dV=np.empty((n, dv)), ubar=np.empty((R + 1, m)),
+                   vbar=np.empty((R + 1, n)))
+    rc = lib.ska_oracle_core(m, n, nnz, rptr.ctypes.data, col.ctypes.data, _p(S), _p(V), _p(G), dv,
+                             T, R, _p(v0_fixed), _p(out["O"]), _p(out["U"]), _p(out["Vp"]),
+                             _p(out.get("Sbar")), _p(out.get("dV")), _p(out.get("ubar")),
+                             _p(out.get("vbar")))
+    if rc:
+        raise RuntimeError(f"ska_oracle_core failed ({rc})")
+    return out
+
+
+def band(Q, K, V, G, W, T, R, eps, dustbin=False, dustbin_score=0.0, v0_fixed=None,
+         want_sbar=False):
+    """Banded operator for one problem; Q, K, V, G are [L, d] arrays (G may be None).
+
+    Returns a dict: O[L,d], UV[2(R+1), Lp] ordered u0,v0,u1,v1,...; with G also
+    dQ, dK, dV [L,d], bars[2(R+1), Lp] (same order) and, if want_sbar,
+    Sbar[L, 2W+1] indexed [i, j-i+W].
+    """
+    lib = _load()
+    Q, K, V, G, v0_fixed = _f64(Q), _f64(K), _f64(V), _f64(G), _f64(v0_fixed)
+    L, d = Q.shape
+    assert K.shape == (L, d) and V.shape == (L, d) and (G is None or G.shape == (L, d))
+    Lp = L + (1 if dustbin else 0)
+    assert v0_fixed is None or v0_fixed.shape == (Lp,)
+    out = {"O": np.empty((L, d)), "UV": np.empty((2 * (R + 1), Lp))}
+    if G is not None:
+        out.update(dQ=np.empty((L, d)), dK=np.empty((L, d)), dV=np.empty((L, d)),
+                   bars=np.empty((2 * (R + 1), Lp)))
+        if want_sbar:
+            out["Sbar"] = np.empty((L, 2 * W + 1))
+    rc = lib.ska_oracle_band(_p(Q), _p(K), _p(V), _p(G), L, d, W, T, R, float(eps),
+                             1 if dustbin else 0, float(dustbin_score), _p(v0_fixed), _p(out["O"]),
+                             _p(out["UV"]), _p(out.get("dQ")), _p(out.get("dK")), _p(out.get("dV")),
+                             _p(out.get("bars")), _p(out.get("Sbar")))
+    if rc:
+        raise RuntimeError(f"ska_oracle_band failed ({rc})")
+    return out
+
+
+def band_batched(Q, K, V, G, W, T, R, eps, dustbin=False, dustbin_score=0.0):
+    """[B,H,L,d] inputs, one independent problem per (b,h). Returns stacked arrays."""
+    B, H, L, d = Q.shape
+    keys = ("O", "UV") + (("dQ", "dK", "dV") if G is not None else ())
+    acc = {k: [] for k in keys}
+    for b in range(B):
+        for h in range(H):
+            r = band(Q[b, h], K[b, h], V[b, h], None if G is None else G[b, h], W, T, R, eps,
+                     dustbin, dustbin_score)
+            for k in keys:
+                acc[k].append(r[k])
+    return {k: np.stack(v).reshape((B, H) + v[0].shape) for k, v in acc.items()}
