@@ -1,0 +1,97 @@
+/*
+ * sinkhorn_attn.h -- C ABI of the MI355X (gfx950) banded Sinkhorn attention library.
+ *
+ * The operator (paper: "Block-Wise Differentiable Sinkhorn Attention"):
+ *   scores      S_ij = <Q_i, K_j> / (eps * sqrt(d))  on the band |i-j| <= W     (Section 2.1)
+ *   half-steps  u_i = -log sum_j exp(S_ij + v_j),  v_j = -log sum_i exp(S_ij + u_i)
+ *                                                                      (Eq. 1, Eq. 2)
+ *   base        T steps (row half-step, then column half-step) from v = 0; the result
+ *               (u0, v0) is a constant for differentiation              (Section 2.2)
+ *   tail        R = 2 further steps giving (u1, v1), (u2, v2)            (Section 2.2)
+ *   output      O_i = sum_j exp(S_ij + u2_i + v2_j) V_j, no renormalisation
+ *                                                                      (Section 2.2)
+ *   backward    exact adjoint of the tail + output (Prop. 1), evaluated from the
+ *               single plan P22 = exp(S + u2 + v2) and vector modifiers (Prop. 2)
+ *   dustbin     optional: one extra row d_q and column d_k joined to every token
+ *               by an edge of constant score `dustbin_score`; all L+1 row and
+ *               column targets are one; V at d_k is zero and the d_q output row is
+ *               not returned (Section 2.3, sparse-spoke support)
+ *
+ * Conventions common to every entry point
+ *   - Every pointer is a DEVICE pointer owned by the caller unless stated.  The
+ *     library allocates nothing, frees nothing and keeps no pointer after return.
+ *   - Work is enqueued on `stream` (a hipStream_t passed as void*, NULL = the
+ *     null stream) and is asynchronous with respect to the host.
+ *   - Tensors Q, K, V, O, dO, dQ, dK, dV are [B, H, L, d], contiguous, row-major,
+ *     of the element type `dtype` (SKA_F32: float; SKA_BF16: bfloat16).  All
+ *     scaling vectors and all accumulation are fp32.
+ *   - UV is [B, H, 6, Lp] fp32 with Lp = L + (dustbin ? 1 : 0), the six vectors
+ *     ordered u0, v0, u1, v1, u2, v2 (natural-log potentials, ungauged; element
+ *     L is the dustbin token when present).
+ *   - Return value: SKA_OK or a negative ska_status.  Arguments are checked
+ *     before anything is launched; nothing is written on an argument error.
+ *   - Supported: d in {32, 64, 128}; R == 2; any L >= 1, W >= 0 (W >= L-1 is the
+ *     dense problem), T >= 0, eps > 0 and finite.
+ */
+#ifndef SINKHORN_ATTN_H
+#define SINKHORN_ATTN_H
+
+#include <stddef.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum { SKA_F32 = 0, SKA_BF16 = 1 } ska_dtype;
+
+typedef enum {
+    SKA_OK = 0,
+    SKA_EINVAL = -1,       /* null required pointer, non-positive size, bad eps        */
+    SKA_EUNSUPPORTED = -2, /* R != 2, unsupported d, unknown dtype                      */
+    SKA_EWORKSPACE = -3,   /* workspace smaller than sinkhorn_attn_workspace_bytes()    */
+    SKA_EHIP = -4          /* a HIP launch failed (hipGetLastError)                     */
+} ska_status;
+
+/*
+ * Bytes of device scratch that sinkhorn_attn_bwd needs for these sizes (the
+ * forward needs none).  Host-only, no GPU call.  Returns 0 on invalid sizes.
+ */
+size_t sinkhorn_attn_workspace_bytes(int B, int H, int L, int d, int W, int T, int R, int dustbin,
+                                     int dtype);
+
+/*
+ * Forward: stopped T-step base solve, R = 2 tail, plan-weighted V
+ * (Section 2.1-2.2, Eq. 1-2; Section 2.3 when dustbin != 0).
+ *   in : Q, K, V [B,H,L,d]
+ *   out: O [B,H,L,d]; UV [B,H,6,Lp] (all six vectors are written)
+ * workspace may be NULL (workspace_bytes is ignored by the forward).
+ */
+int sinkhorn_attn_fwd(const void *Q, const void *K, const void *V, void *O, float *UV, int B, int H,
+                      int L, int d, int W, int T, int R, float eps, int dustbin,
+                      float dustbin_score, int dtype, void *workspace, size_t workspace_bytes,
+                      void *stream);
+
+/*
+ * Backward: exact VJP of the stopped-base surrogate for an arbitrary output
+ * cotangent dO (Prop. 1), scheduled from the one reference plan P22 and the
+ * modifiers alpha = exp(u1-u2), beta = exp(v1-v2), delta = exp(v0-v2) (Prop. 2).
+ *   in : Q, K, V, O (as returned by the forward), dO [B,H,L,d]; UV from the forward
+ *   out: dQ, dK, dV [B,H,L,d], overwritten
+ *        eta0 [B,H,Lp] fp32 or NULL: the base cotangent vbar^(0) that the
+ *        stop-gradient discards (Prop. 5 calls it eta_R)
+ * workspace: at least sinkhorn_attn_workspace_bytes(...) bytes, 16-byte aligned;
+ * its contents are scratch before and after the call.
+ */
+int sinkhorn_attn_bwd(const void *Q, const void *K, const void *V, const void *O, const void *dO,
+                      const float *UV, void *dQ, void *dK, void *dV, float *eta0, int B, int H,
+                      int L, int d, int W, int T, int R, float eps, int dustbin,
+                      float dustbin_score, int dtype, void *workspace, size_t workspace_bytes,
+                      void *stream);
+
+/* Static, human-readable text for a ska_status value. Never NULL. */
+const char *sinkhorn_attn_strerror(int status);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* SINKHORN_ATTN_H */

@@ -1,0 +1,7 @@
+"""MI355X-native banded Sinkhorn attention (forward + exact surrogate backward).
+
+`binding` is the thin ctypes layer over the C ABI of include/sinkhorn_attn.h;
+`workloads` holds the seeded synthetic inputs; `build` compiles the library.
+"""
+from .binding import (SinkhornAttnError, sinkhorn_attn_bwd, sinkhorn_attn_fwd,  # noqa: F401
+                      sinkhorn_attn_strerror, sinkhorn_attn_workspace_bytes)

@@ -1,0 +1,125 @@
+"""Thin Python binding of the C ABI in include/sinkhorn_attn.h.
+
+Argument marshalling only: torch supplies device memory and the current HIP
+stream; every step of the operator runs in the library's kernels.  There is no
+CPU or eager fallback: if the shared library is missing, loading raises.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+
+import torch
+
+_PKG = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_PKG, "libsinkhorn_attn.so")
+
+SKA_F32, SKA_BF16 = 0, 1
+SKA_OK, SKA_EINVAL, SKA_EUNSUPPORTED, SKA_EWORKSPACE, SKA_EHIP = 0, -1, -2, -3, -4
+
+_lib = None
+
+
+def load():
+    """dlopen the in-tree library (raises if it has not been built)."""
+    global _lib
+    if _lib is None:
+        if not os.path.exists(LIB_PATH):
+            raise RuntimeError(
+                f"{LIB_PATH} is missing: build it with "
+                "`python -c 'import __graft_entry__ as g; g.build()'` (needs hipcc)")
+        lib = ctypes.CDLL(LIB_PATH)
+        vp, i, f, sz = ctypes.c_void_p, ctypes.c_int, ctypes.c_float, ctypes.c_size_t
+        lib.sinkhorn_attn_workspace_bytes.restype = sz
+        lib.sinkhorn_attn_workspace_bytes.argtypes = [i] * 9
+        lib.sinkhorn_attn_fwd.restype = i
+        lib.sinkhorn_attn_fwd.argtypes = [vp, vp, vp, vp, vp, i, i, i, i, i, i, i, f, i, f, i, vp, sz, vp]
+        lib.sinkhorn_attn_bwd.restype = i
+        lib.sinkhorn_attn_bwd.argtypes = [vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, i, i, i, i, i, i, i, f,
+                                          i, f, i, vp, sz, vp]
+        lib.sinkhorn_attn_strerror.restype = ctypes.c_char_p
+        lib.sinkhorn_attn_strerror.argtypes = [i]
+        _lib = lib
+    return _lib
+
+
+class SinkhornAttnError(RuntimeError):
+    def __init__(self, status: int):
+        self.status = status
+        super().__init__(f"sinkhorn_attn status {status}: {sinkhorn_attn_strerror(status)}")
+
+
+def sinkhorn_attn_strerror(status: int) -> str:
+    return load().sinkhorn_attn_strerror(int(status)).decode()
+
+
+def sinkhorn_attn_workspace_bytes(B, H, L, d, W, T, R=2, dustbin=False, dtype=SKA_BF16) -> int:
+    return int(load().sinkhorn_attn_workspace_bytes(B, H, L, d, W, T, R, int(bool(dustbin)), dtype))
+
+
+def _dtype_code(t: torch.Tensor) -> int:
+    if t.dtype == torch.float32:
+        return SKA_F32
+    if t.dtype == torch.bfloat16:
+        return SKA_BF16
+    raise TypeError(f"unsupported dtype {t.dtype}")
+
+
+def _check(x: torch.Tensor, shape, dtype, name):
+    if not x.is_cuda:
+        raise ValueError(f"{name} must live on the GPU")
+    if tuple(x.shape) != tuple(shape) or x.dtype != dtype or not x.is_contiguous():
+        raise ValueError(f"{name}: expected contiguous {tuple(shape)} {dtype}, got {tuple(x.shape)} {x.dtype}")
+
+
+def _stream_ptr() -> int:
+    return int(torch.cuda.current_stream().cuda_stream)
+
+
+def sinkhorn_attn_fwd(Q, K, V, W, T, R=2, eps=1.0, dustbin=False, dustbin_score=0.0, O=None, UV=None):
+    """Forward. Q, K, V: [B,H,L,d] CUDA tensors (float32 or bfloat16).
+    Returns (O [B,H,L,d], UV [B,H,6,L+dustbin] float32)."""
+    B, H, L, d = Q.shape
+    for n, x in (("Q", Q), ("K", K), ("V", V)):
+        _check(x, (B, H, L, d), Q.dtype, n)
+    Lp = L + int(bool(dustbin))
+    if O is None:
+        O = torch.empty_like(Q)
+    if UV is None:
+        UV = torch.empty((B, H, 6, Lp), device=Q.device, dtype=torch.float32)
+    _check(O, (B, H, L, d), Q.dtype, "O")
+    _check(UV, (B, H, 6, Lp), torch.float32, "UV")
+    rc = load().sinkhorn_attn_fwd(Q.data_ptr(), K.data_ptr(), V.data_ptr(), O.data_ptr(), UV.data_ptr(),
+                                  B, H, L, d, W, T, R, float(eps), int(bool(dustbin)),
+                                  float(dustbin_score), _dtype_code(Q), None, 0, _stream_ptr())
+    if rc != SKA_OK:
+        raise SinkhornAttnError(rc)
+    return O, UV
+
+
+def sinkhorn_attn_bwd(Q, K, V, O, dO, UV, W, T, R=2, eps=1.0, dustbin=False, dustbin_score=0.0,
+                      want_eta0=False, workspace=None, dQ=None, dK=None, dV=None):
+    """Backward. Returns (dQ, dK, dV[, eta0])."""
+    B, H, L, d = Q.shape
+    for n, x in (("Q", Q), ("K", K), ("V", V), ("O", O), ("dO", dO)):
+        _check(x, (B, H, L, d), Q.dtype, n)
+    Lp = L + int(bool(dustbin))
+    _check(UV, (B, H, 6, Lp), torch.float32, "UV")
+    dQ = torch.empty_like(Q) if dQ is None else dQ
+    dK = torch.empty_like(Q) if dK is None else dK
+    dV = torch.empty_like(Q) if dV is None else dV
+    for n, x in (("dQ", dQ), ("dK", dK), ("dV", dV)):
+        _check(x, (B, H, L, d), Q.dtype, n)
+    code = _dtype_code(Q)
+    need = sinkhorn_attn_workspace_bytes(B, H, L, d, W, T, R, dustbin, code)
+    if workspace is None:
+        workspace = torch.empty(max(need, 16), device=Q.device, dtype=torch.uint8)
+    eta0 = torch.empty((B, H, Lp), device=Q.device, dtype=torch.float32) if want_eta0 else None
+    rc = load().sinkhorn_attn_bwd(Q.data_ptr(), K.data_ptr(), V.data_ptr(), O.data_ptr(), dO.data_ptr(),
+                                  UV.data_ptr(), dQ.data_ptr(), dK.data_ptr(), dV.data_ptr(),
+                                  eta0.data_ptr() if want_eta0 else None, B, H, L, d, W, T, R, float(eps),
+                                  int(bool(dustbin)), float(dustbin_score), code, workspace.data_ptr(),
+                                  workspace.numel() * workspace.element_size(), _stream_ptr())
+    if rc != SKA_OK:
+        raise SinkhornAttnError(rc)
+    return (dQ, dK, dV, eta0) if want_eta0 else (dQ, dK, dV)

@@ -1,0 +1,921 @@
+// Banded Sinkhorn attention for gfx950 (MI355X): band-sweep kernels and the C ABI.
+//
+// Every step of the operator is a "band sweep": for each owner index o (a row of
+// the plan for row-oriented sweeps, a column for column-oriented ones) reduce over
+// the other index t with |o - t| <= W.  Because the band is symmetric, a column
+// sweep is the row sweep of the transposed problem, i.e. the same kernel with the
+// roles of Q and K exchanged, so nothing is ever read transposed from memory.
+//
+//   score tile   T[t, o] = <Y_t, X_o>            MFMA, recomputed in every sweep and
+//                                                 never stored (Section 2.1; Prop. 2)
+//   E[t, o]      = exp2(c2 * T[t, o] + y'_t + m') c2 = log2(e)/(eps sqrt d),
+//                                                 y' = other-side potential * log2(e),
+//                                                 m' = one stabiliser per workgroup
+//   LSE          x_o  = -log sum_t exp(S_ot + y_t)            (Eq. 1 / Eq. 2)
+//   MATVEC       out_o = pre_o - exp(x_o) sum_t exp(S_ot + y_t) w_t   (Prop. 1 recurrences)
+//   APPLY        out_o = exp(x_o) sum_t exp(S_ot + y_t) Pay_t  (output map; dV)
+//   FINAL        out_o = c exp(x_o) sum_t exp(S_ot + y_t) [<A_o, B_t> - sum_k p_k,o q_k,t] Y_t
+//                                                 (Prop. 2: one reference tile + modifiers)
+//
+// MFMA tile layout (32x32 accumulators): lane l holds owner o = l & 31; register r
+// holds other index t = 8*(r>>2) + 4*(l>>5) + (r&3).  Sums over t are therefore
+// in-lane register sums plus one exchange between the two lane halves.
+#include <hip/hip_runtime.h>
+#include <math.h>
+#include <stdint.h>
+
+#include "sinkhorn_attn.h"
+
+namespace {
+
+typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8;
+typedef __attribute__((ext_vector_type(4))) __bf16 bf16x4;
+typedef __attribute__((ext_vector_type(16))) float f32x16;
+
+constexpr int NTHREADS = 256;
+constexpr int NWAVES = 4;
+constexpr int TT = 32;  // other-side rows per tile
+constexpr float LOG2E = 1.4426950408889634f;
+constexpr float LN2 = 0.6931471805599453f;
+
+enum Mode { M_LSE_FIRST = 0, M_LSE = 1, M_MATVEC = 2, M_APPLY = 3, M_FINAL = 4 };
+
+struct Vec {          // one fp32 vector per problem
+    const float *p;
+    long stride;      // elements between consecutive problems
+};
+struct VecOut {
+    float *p;
+    long stride;
+};
+
+struct SweepArgs {
+    const void *X;    // owner-side matrix      [N][L][D]
+    const void *Y;    // other-side matrix      [N][L][D]
+    const void *A;    // FINAL: owner-side factor of Z (dO for rows, V for columns)
+    const void *Bm;   // FINAL: other-side factor of Z
+    const void *Pay;  // APPLY: other-side payload (V for the output, dO for dV)
+    void *out_mat;    // APPLY / FINAL result   [N][L][D]
+    Vec yt;           // other-side potential (natural log units), length Lp
+    Vec xs;           // owner-side potential / previous iterate (stabiliser), length Lp
+    Vec w;            // MATVEC weights on the other side
+    Vec pre;          // MATVEC additive term on the owner side (may be null)
+    VecOut out_vec;   // LSE / MATVEC result
+    const float4 *po; // FINAL: owner-side modifier pack   [N][ldp]
+    const float4 *qt; // FINAL: other-side modifier pack   [N][ldp]
+    long ldp;
+    const void *dot_mat;  // APPLY: if set, dot_out_o = <dot_mat_o, out_o> (fp32 accumulators)
+    VecOut dot_out;
+    int L, W;
+    float c2;         // log2(e) / (eps sqrt d)
+    float cs;         // 1 / (eps sqrt d)
+    int dustbin;
+    float sdb2;       // dustbin score * log2(e)
+    int nbp;          // workgroups per problem
+    int nb_total;
+};
+
+// ------------------------------------------------------------------ element traits
+template <typename T> struct Elem;
+template <> struct Elem<float> {
+    static constexpr int BYTES = 4;
+};
+template <> struct Elem<__bf16> {
+    static constexpr int BYTES = 2;
+};
+
+__device__ __forceinline__ float fast_exp2(float x) { return __builtin_amdgcn_exp2f(x); }
+__device__ __forceinline__ float fast_log2(float x) { return __builtin_amdgcn_logf(x); }
+
+__device__ __forceinline__ bf16x8 pack8(const float *e)
+{
+    bf16x8 r;
+#pragma unroll
+    for (int i = 0; i < 8; ++i) r[i] = (__bf16)e[i];
+    return r;
+}
+
+// LDS layouts -------------------------------------------------------------------
+// bf16 row-major tile [32][D]: 16-byte chunks XOR-swizzled so that the 32 lanes of
+// an A-fragment read (one chunk per lane, consecutive rows) spread over all banks.
+template <int D> __device__ __forceinline__ int bf16_chunk_off(int row, int chunk)
+{
+    constexpr int CH = D / 8;                       // chunks per row
+    constexpr int RPB = (CH >= 8) ? 1 : 8 / CH;     // rows per 128-byte line
+    constexpr int MASK = (CH >= 8) ? 7 : CH - 1;
+    return (row * CH + (chunk ^ ((row / RPB) & MASK))) * 16;
+}
+// bf16 transposed payload tile [D][32 + 4] (t contiguous, 72-byte rows)
+constexpr int PT_STRIDE = 72;
+// fp32 row-major tile [32][D + 4]
+template <int D> constexpr int f32_row_floats() { return D + 4; }
+
+template <typename T, int D> struct Tile {
+    static constexpr bool IS_BF16 = (Elem<T>::BYTES == 2);
+    static constexpr int RM_BYTES = IS_BF16 ? 32 * D * 2 : 32 * f32_row_floats<D>() * 4;
+    static constexpr int PT_BYTES = IS_BF16 ? D * PT_STRIDE : RM_BYTES;
+    static constexpr int CHUNKS = 32 * D * Elem<T>::BYTES / 16;       // 16-byte pieces per tile
+    static constexpr int CPT = (CHUNKS + NTHREADS - 1) / NTHREADS;    // per thread
+    static constexpr int CPR = D * Elem<T>::BYTES / 16;               // per row
+};
+
+template <typename T, int D> using TileRegs = uint4[Tile<T, D>::CPT];
+
+// ------------------------------------------------------------------ staging
+// Global -> registers for one 32-row tile of a [L][D] matrix (rows beyond L read as 0).
+template <typename T, int D>
+__device__ __forceinline__ void tile_load(TileRegs<T, D> &reg, const T *base, int t0, int L)
+{
+    using TL = Tile<T, D>;
+#pragma unroll
+    for (int c = 0; c < TL::CPT; ++c) {
+        int idx = threadIdx.x + c * NTHREADS;
+        int row = idx / TL::CPR, ch = idx % TL::CPR;
+        uint4 v = make_uint4(0, 0, 0, 0);
+        if (idx < TL::CHUNKS && t0 + row < L)
+            v = *reinterpret_cast<const uint4 *>(base + (long)(t0 + row) * D + ch * (16 / Elem<T>::BYTES));
+        reg[c] = v;
+    }
+}
+
+// registers -> LDS, row-major (A-operand of the score / Z products)
+template <typename T, int D>
+__device__ __forceinline__ void tile_store_rm(const TileRegs<T, D> &reg, unsigned char *lds)
+{
+    using TL = Tile<T, D>;
+#pragma unroll
+    for (int c = 0; c < TL::CPT; ++c) {
+        int idx = threadIdx.x + c * NTHREADS;
+        if (idx < TL::CHUNKS) {
+            int row = idx / TL::CPR, ch = idx % TL::CPR;
+            if constexpr (TL::IS_BF16)
+                *reinterpret_cast<uint4 *>(lds + bf16_chunk_off<D>(row, ch)) = reg[c];
+            else
+                *reinterpret_cast<uint4 *>(lds + (row * f32_row_floats<D>() + ch * 4) * 4) = reg[c];
+        }
+    }
+}
+
+// registers -> LDS in the layout the second product wants: bf16 transposed [dv][t],
+// fp32 row-major.
+template <typename T, int D>
+__device__ __forceinline__ void tile_store_pay(const TileRegs<T, D> &reg, unsigned char *lds)
+{
+    using TL = Tile<T, D>;
+    if constexpr (!TL::IS_BF16) {
+        tile_store_rm<T, D>(reg, lds);
+    } else {
+#pragma unroll
+        for (int c = 0; c < TL::CPT; ++c) {
+            int idx = threadIdx.x + c * NTHREADS;
+            if (idx < TL::CHUNKS) {
+                int row = idx / TL::CPR, ch = idx % TL::CPR;
+                const unsigned int wds[4] = {reg[c].x, reg[c].y, reg[c].z, reg[c].w};
+#pragma unroll
+                for (int e = 0; e < 8; ++e) {
+                    unsigned short v = (unsigned short)(wds[e >> 1] >> ((e & 1) * 16));
+                    *reinterpret_cast<unsigned short *>(lds + (ch * 8 + e) * PT_STRIDE + row * 2) = v;
+                }
+            }
+        }
+    }
+}
+
+// ------------------------------------------------------------------ fragments
+// Owner-side fragment kept in registers for the whole sweep (B operand, columns o).
+template <typename T, int D> struct OwnerFrag;
+template <int D> struct OwnerFrag<__bf16, D> {
+    bf16x8 v[D / 16];
+    __device__ __forceinline__ void load(const __bf16 *base, int o, int L, int h)
+    {
+#pragma unroll
+        for (int s = 0; s < D / 16; ++s) {
+            uint4 z = make_uint4(0, 0, 0, 0);
+            if (o < L) z = *reinterpret_cast<const uint4 *>(base + (long)o * D + (2 * s + h) * 8);
+            v[s] = *reinterpret_cast<bf16x8 *>(&z);
+        }
+    }
+};
+template <int D> struct OwnerFrag<float, D> {
+    float v[D / 2];   // feature k = h*D/2 + s
+    __device__ __forceinline__ void load(const float *base, int o, int L, int h)
+    {
+#pragma unroll
+        for (int q = 0; q < D / 8; ++q) {
+            float4 z = make_float4(0.f, 0.f, 0.f, 0.f);
+            if (o < L) z = *reinterpret_cast<const float4 *>(base + (long)o * D + h * (D / 2) + 4 * q);
+            v[4 * q + 0] = z.x; v[4 * q + 1] = z.y; v[4 * q + 2] = z.z; v[4 * q + 3] = z.w;
+        }
+    }
+};
+
+// acc[t, o] += sum_k tile[t][k] * frag[o][k]
+template <int D>
+__device__ __forceinline__ f32x16 tile_dot(const unsigned char *tile, const OwnerFrag<__bf16, D> &x,
+                                           int lane, f32x16 acc)
+{
+    const int t = lane & 31, h = lane >> 5;
+#pragma unroll
+    for (int s = 0; s < D / 16; ++s) {
+        bf16x8 a = *reinterpret_cast<const bf16x8 *>(tile + bf16_chunk_off<D>(t, 2 * s + h));
+        acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, x.v[s], acc, 0, 0, 0);
+    }
+    return acc;
+}
+template <int D>
+__device__ __forceinline__ f32x16 tile_dot(const unsigned char *tile, const OwnerFrag<float, D> &x,
+                                           int lane, f32x16 acc)
+{
+    const int t = lane & 31, h = lane >> 5;
+    const float *row = reinterpret_cast<const float *>(tile) + t * f32_row_floats<D>() + h * (D / 2);
+#pragma unroll
+    for (int q = 0; q < D / 8; ++q) {
+        float4 a = *reinterpret_cast<const float4 *>(row + 4 * q);
+        acc = __builtin_amdgcn_mfma_f32_32x32x2f32(a.x, x.v[4 * q + 0], acc, 0, 0, 0);
+        acc = __builtin_amdgcn_mfma_f32_32x32x2f32(a.y, x.v[4 * q + 1], acc, 0, 0, 0);
+        acc = __builtin_amdgcn_mfma_f32_32x32x2f32(a.z, x.v[4 * q + 2], acc, 0, 0, 0);
+        acc = __builtin_amdgcn_mfma_f32_32x32x2f32(a.w, x.v[4 * q + 3], acc, 0, 0, 0);
+    }
+    return acc;
+}
+
+// out[dvt][dv, o] += sum_t pay[t][dv] * e[t, o]   (e in the accumulator layout)
+template <typename T, int D>
+__device__ __forceinline__ void tile_accum(f32x16 (&out)[D / 32], const unsigned char *pay,
+                                           const float (&e)[16], int lane)
+{
+    const int c = lane & 31, h = lane >> 5;
+    if constexpr (Elem<T>::BYTES == 2) {
+#pragma unroll
+        for (int m = 0; m < 2; ++m) {
+            bf16x8 pf = pack8(&e[8 * m]);
+#pragma unroll
+            for (int dvt = 0; dvt < D / 32; ++dvt) {
+                const unsigned char *rowp = pay + (32 * dvt + c) * PT_STRIDE;
+                uint2 lo = *reinterpret_cast<const uint2 *>(rowp + (16 * m + 4 * h) * 2);
+                uint2 hi = *reinterpret_cast<const uint2 *>(rowp + (16 * m + 8 + 4 * h) * 2);
+                uint4 both = make_uint4(lo.x, lo.y, hi.x, hi.y);
+                bf16x8 af = *reinterpret_cast<bf16x8 *>(&both);
+                out[dvt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af, pf, out[dvt], 0, 0, 0);
+            }
+        }
+    } else {
+        const float *p = reinterpret_cast<const float *>(pay);
+#pragma unroll
+        for (int r = 0; r < 16; ++r) {
+            const int t = 8 * (r >> 2) + 4 * h + (r & 3);
+#pragma unroll
+            for (int dvt = 0; dvt < D / 32; ++dvt) {
+                float a = p[t * f32_row_floats<D>() + 32 * dvt + c];
+                out[dvt] = __builtin_amdgcn_mfma_f32_32x32x2f32(a, e[r], out[dvt], 0, 0, 0);
+            }
+        }
+    }
+}
+
+template <typename T> __device__ __forceinline__ void store4(T *dst, float a, float b, float c, float d);
+template <> __device__ __forceinline__ void store4<float>(float *dst, float a, float b, float c, float d)
+{
+    *reinterpret_cast<float4 *>(dst) = make_float4(a, b, c, d);
+}
+template <> __device__ __forceinline__ void store4<__bf16>(__bf16 *dst, float a, float b, float c, float d)
+{
+    bf16x4 v = {(__bf16)a, (__bf16)b, (__bf16)c, (__bf16)d};
+    *reinterpret_cast<bf16x4 *>(dst) = v;
+}
+template <typename T> __device__ __forceinline__ void load4(const T *src, float (&f)[4]);
+template <> __device__ __forceinline__ void load4<float>(const float *src, float (&f)[4])
+{
+    float4 v = *reinterpret_cast<const float4 *>(src);
+    f[0] = v.x; f[1] = v.y; f[2] = v.z; f[3] = v.w;
+}
+template <> __device__ __forceinline__ void load4<__bf16>(const __bf16 *src, float (&f)[4])
+{
+    bf16x4 v = *reinterpret_cast<const bf16x4 *>(src);
+#pragma unroll
+    for (int i = 0; i < 4; ++i) f[i] = (float)v[i];
+}
+
+// ------------------------------------------------------------------ the sweep kernel
+template <typename T, int D, int MODE> struct Stage {
+    using TL = Tile<T, D>;
+    static constexpr bool HAS_B = (MODE == M_FINAL);
+    static constexpr bool HAS_PAY = (MODE == M_APPLY) || (MODE == M_FINAL && TL::IS_BF16);
+    static constexpr int OFF_Y = 0;
+    static constexpr int OFF_B = OFF_Y + TL::RM_BYTES;
+    static constexpr int OFF_PAY = OFF_B + (HAS_B ? TL::RM_BYTES : 0);
+    static constexpr int OFF_VY = OFF_PAY + (HAS_PAY ? TL::PT_BYTES : 0);
+    static constexpr int OFF_VW = OFF_VY + TT * 4;
+    static constexpr int OFF_VQ = OFF_VW + TT * 4;
+    static constexpr int BYTES = ((OFF_VQ + TT * 16) + 15) / 16 * 16;
+};
+
+template <typename T, int D, int MODE, int FR>
+__global__ __launch_bounds__(NTHREADS) void sweep_kernel(const SweepArgs a)
+{
+    using TL = Tile<T, D>;
+    using ST = Stage<T, D, MODE>;
+    constexpr int BM = NWAVES * FR * 32;
+    constexpr bool MAT_OUT = (MODE == M_APPLY || MODE == M_FINAL);
+
+    extern __shared__ __align__(16) unsigned char smem[];   // two stages of ST::BYTES
+    __shared__ float red[NWAVES];
+
+    // XCD-aware placement: hardware deals workgroups round-robin over the 8 XCDs, so
+    // give each XCD one contiguous eighth of the (problem, block) sequence; neighbours
+    // that share band rows then meet in the same L2.
+    const int chunk = (a.nb_total + 7) >> 3;
+    const int lb = (blockIdx.x & 7) * chunk + (blockIdx.x >> 3);
+    if (lb >= a.nb_total) return;
+    const int n = lb / a.nbp;
+    const int o_blk = (lb % a.nbp) * BM;
+
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int c = lane & 31, h = lane >> 5;
+    const int L = a.L, W = a.W;
+    const long moff = (long)n * L * D;
+    const T *Xb = reinterpret_cast<const T *>(a.X) + moff;
+    const T *Yb = reinterpret_cast<const T *>(a.Y) + moff;
+    const float *ytp = a.yt.p + n * a.yt.stride;
+    const float *xsp = (MODE == M_LSE_FIRST) ? nullptr : a.xs.p + n * a.xs.stride;
+
+    // workgroup stabiliser: largest owner-side potential in this block
+    float mblk = 0.f;
+    if constexpr (MODE != M_LSE_FIRST) {
+        float m = -INFINITY;
+        for (int i = tid; i < BM; i += NTHREADS)
+            if (o_blk + i < L) m = fmaxf(m, xsp[o_blk + i]);
+#pragma unroll
+        for (int s = 32; s >= 1; s >>= 1) m = fmaxf(m, __shfl_xor(m, s));
+        if (lane == 0) red[wave] = m;
+        __syncthreads();
+        mblk = fmaxf(fmaxf(red[0], red[1]), fmaxf(red[2], red[3]));
+    }
+    const float m2 = mblk * LOG2E;
+
+    // owner-side fragments
+    OwnerFrag<T, D> xf[FR];
+    OwnerFrag<T, D> af[MODE == M_FINAL ? FR : 1];
+    float4 pof[FR];
+    int o_frag[FR];
+#pragma unroll
+    for (int f = 0; f < FR; ++f) {
+        o_frag[f] = o_blk + (wave * FR + f) * 32;
+        xf[f].load(Xb, o_frag[f] + c, L, h);
+        if constexpr (MODE == M_FINAL) {
+            af[f].load(reinterpret_cast<const T *>(a.A) + moff, o_frag[f] + c, L, h);
+            pof[f] = (o_frag[f] + c < L) ? a.po[n * a.ldp + o_frag[f] + c] : make_float4(0, 0, 0, 0);
+        }
+    }
+
+    // accumulators
+    float sum[FR], mx[FR];
+    f32x16 outm[MAT_OUT ? FR : 1][D / 32];
+#pragma unroll
+    for (int f = 0; f < FR; ++f) {
+        sum[f] = 0.f;
+        mx[f] = -INFINITY;
+        if constexpr (MAT_OUT)
+#pragma unroll
+            for (int j = 0; j < D / 32; ++j)
+#pragma unroll
+                for (int r = 0; r < 16; ++r) outm[f][j][r] = 0.f;
+    }
+
+    // other-side tile range of the whole block (tiles aligned to multiples of 32)
+    int lo = o_blk - W;            // the host clamps W to L, so none of this overflows
+    if (lo < 0) lo = 0;
+    int hi = o_blk + BM - 1 + W;
+    if (hi > L - 1) hi = L - 1;
+    const int k_lo = lo / TT, k_hi = hi / TT;
+
+    // staging registers
+    uint4 ry[TL::CPT], rb[ST::HAS_B ? TL::CPT : 1], rp[MODE == M_APPLY ? TL::CPT : 1];
+    float rvy = 0.f, rvw = 0.f;
+    float4 rvq = make_float4(0, 0, 0, 0);
+
+    auto g_load = [&](int k) {
+        const int t0 = k * TT;
+        tile_load<T, D>(ry, Yb, t0, L);
+        if constexpr (ST::HAS_B) tile_load<T, D>(rb, reinterpret_cast<const T *>(a.Bm) + moff, t0, L);
+        if constexpr (MODE == M_APPLY) tile_load<T, D>(rp, reinterpret_cast<const T *>(a.Pay) + moff, t0, L);
+        if (tid < TT) {
+            const int t = t0 + tid;
+            rvy = (t < L) ? ytp[t] * LOG2E + m2 : -INFINITY;
+            if constexpr (MODE == M_MATVEC) rvw = (t < L) ? a.w.p[n * a.w.stride + t] : 0.f;
+            if constexpr (MODE == M_FINAL) rvq = (t < L) ? a.qt[n * a.ldp + t] : make_float4(0, 0, 0, 0);
+        }
+    };
+    auto s_store = [&](int buf) {
+        unsigned char *s = smem + buf * ST::BYTES;
+        tile_store_rm<T, D>(ry, s + ST::OFF_Y);
+        if constexpr (ST::HAS_B) tile_store_rm<T, D>(rb, s + ST::OFF_B);
+        if constexpr (MODE == M_APPLY) tile_store_pay<T, D>(rp, s + ST::OFF_PAY);
+        if constexpr (MODE == M_FINAL && TL::IS_BF16) tile_store_pay<T, D>(ry, s + ST::OFF_PAY);
+        if (tid < TT) {
+            reinterpret_cast<float *>(s + ST::OFF_VY)[tid] = rvy;
+            if constexpr (MODE == M_MATVEC) reinterpret_cast<float *>(s + ST::OFF_VW)[tid] = rvw;
+            if constexpr (MODE == M_FINAL) reinterpret_cast<float4 *>(s + ST::OFF_VQ)[tid] = rvq;
+        }
+    };
+
+    g_load(k_lo);
+    s_store(0);
+    __syncthreads();
+
+    for (int k = k_lo; k <= k_hi; ++k) {
+        const int buf = (k - k_lo) & 1;
+        if (k < k_hi) g_load(k + 1);
+        const unsigned char *s = smem + buf * ST::BYTES;
+        const int t0 = k * TT;
+
+#pragma unroll
+        for (int f = 0; f < FR; ++f) {
+            const int of = o_frag[f];
+            // does this tile meet the band of this fragment at all?
+            if (of >= L || (long)t0 + TT - 1 < (long)of - W || (long)t0 > (long)of + 31 + W) continue;
+            const bool interior = ((long)of + 31 - t0 <= W) && ((long)t0 + TT - 1 - of <= W);
+
+            f32x16 acc;
+#pragma unroll
+            for (int r = 0; r < 16; ++r) acc[r] = 0.f;
+            acc = tile_dot<D>(s + ST::OFF_Y, xf[f], lane, acc);
+
+            float yv[16];
+#pragma unroll
+            for (int q = 0; q < 4; ++q) {
+                float4 v4 = *reinterpret_cast<const float4 *>(s + ST::OFF_VY + (8 * q + 4 * h) * 4);
+                yv[4 * q + 0] = v4.x; yv[4 * q + 1] = v4.y; yv[4 * q + 2] = v4.z; yv[4 * q + 3] = v4.w;
+            }
+            float e[16];
+#pragma unroll
+            for (int r = 0; r < 16; ++r) e[r] = fmaf(acc[r], a.c2, yv[r]);
+            if (!interior) {
+                const int o = of + c;
+#pragma unroll
+                for (int r = 0; r < 16; ++r) {
+                    const int t = t0 + 8 * (r >> 2) + 4 * h + (r & 3);
+                    const int dlt = o > t ? o - t : t - o;
+                    if (dlt > W) e[r] = -INFINITY;
+                }
+            }
+
+            if constexpr (MODE == M_LSE_FIRST) {
+                float tm = e[0];
+#pragma unroll
+                for (int r = 1; r < 16; ++r) tm = fmaxf(tm, e[r]);
+                const float mn = fmaxf(mx[f], tm);
+                const float ms = (mn == -INFINITY) ? 0.f : mn;
+                float sacc = sum[f] * fast_exp2(mx[f] - ms);
+#pragma unroll
+                for (int r = 0; r < 16; ++r) sacc += fast_exp2(e[r] - ms);
+                sum[f] = sacc;
+                mx[f] = mn;
+            } else {
+#pragma unroll
+                for (int r = 0; r < 16; ++r) e[r] = fast_exp2(e[r]);
+                if constexpr (MODE == M_LSE) {
+#pragma unroll
+                    for (int r = 0; r < 16; ++r) sum[f] += e[r];
+                } else if constexpr (MODE == M_MATVEC) {
+#pragma unroll
+                    for (int q = 0; q < 4; ++q) {
+                        float4 w4 = *reinterpret_cast<const float4 *>(s + ST::OFF_VW + (8 * q + 4 * h) * 4);
+                        sum[f] = fmaf(e[4 * q + 0], w4.x, sum[f]);
+                        sum[f] = fmaf(e[4 * q + 1], w4.y, sum[f]);
+                        sum[f] = fmaf(e[4 * q + 2], w4.z, sum[f]);
+                        sum[f] = fmaf(e[4 * q + 3], w4.w, sum[f]);
+                    }
+                } else if constexpr (MODE == M_APPLY) {
+                    tile_accum<T, D>(outm[f], s + ST::OFF_PAY, e, lane);
+                } else {  // M_FINAL
+                    f32x16 z;
+#pragma unroll
+                    for (int r = 0; r < 16; ++r) z[r] = 0.f;
+                    z = tile_dot<D>(s + ST::OFF_B, af[f], lane, z);
+#pragma unroll
+                    for (int r = 0; r < 16; ++r) {
+                        const int tl = 8 * (r >> 2) + 4 * h + (r & 3);
+                        float4 q4 = *reinterpret_cast<const float4 *>(s + ST::OFF_VQ + tl * 16);
+                        float md = z[r];
+                        md = fmaf(-pof[f].x, q4.x, md);
+                        md = fmaf(-pof[f].y, q4.y, md);
+                        md = fmaf(-pof[f].z, q4.z, md);
+                        md = fmaf(-pof[f].w, q4.w, md);
+                        e[r] *= md;
+                    }
+                    tile_accum<T, D>(outm[f], TL::IS_BF16 ? s + ST::OFF_PAY : s + ST::OFF_Y, e, lane);
+                }
+            }
+        }
+
+        if (k < k_hi) s_store(buf ^ 1);
+        __syncthreads();
+    }
+
+    // ---------------------------------------------------------------- epilogue
+#pragma unroll
+    for (int f = 0; f < FR; ++f) {
+        const int o = o_frag[f] + c;
+        if constexpr (MODE == M_LSE_FIRST) {
+            float mo = __shfl_xor(mx[f], 32), so = __shfl_xor(sum[f], 32);
+            float mn = fmaxf(mx[f], mo);
+            float tot = sum[f] * fast_exp2(mx[f] - mn) + so * fast_exp2(mo - mn);
+            if (a.dustbin) {   // spoke edge (o, dustbin): score sdb, other-side potential yt[L]
+                float xd = a.sdb2 + ytp[L] * LOG2E;
+                float m3 = fmaxf(mn, xd);
+                tot = tot * fast_exp2(mn - m3) + fast_exp2(xd - m3);
+                mn = m3;
+            }
+            if (h == 0 && o < L) a.out_vec.p[n * a.out_vec.stride + o] = -LN2 * (mn + fast_log2(tot));
+        } else if constexpr (MODE == M_LSE || MODE == M_MATVEC) {
+            float tot = sum[f] + __shfl_xor(sum[f], 32);
+            if (a.dustbin) {
+                float ed = fast_exp2(a.sdb2 + ytp[L] * LOG2E + m2);
+                tot += (MODE == M_MATVEC) ? ed * a.w.p[n * a.w.stride + L] : ed;
+            }
+            if (h == 0 && o < L) {
+                float r;
+                if constexpr (MODE == M_LSE) {
+                    r = mblk - LN2 * fast_log2(tot);
+                } else {
+                    float pre = a.pre.p ? a.pre.p[n * a.pre.stride + o] : 0.f;
+                    r = pre - fast_exp2((xsp[o] - mblk) * LOG2E) * tot;
+                }
+                a.out_vec.p[n * a.out_vec.stride + o] = r;
+            }
+        } else {
+            float fac = 0.f;
+            if (o < L) fac = fast_exp2((xsp[o] - mblk) * LOG2E);
+            if constexpr (MODE == M_FINAL) fac *= a.cs;
+            T *orow = reinterpret_cast<T *>(a.out_mat) + moff + (long)o * D;
+            const T *drow = a.dot_mat ? reinterpret_cast<const T *>(a.dot_mat) + moff + (long)o * D : nullptr;
+            float dot = 0.f;
+#pragma unroll
+            for (int j = 0; j < D / 32; ++j)
+#pragma unroll
+                for (int q = 0; q < 4; ++q) {
+                    const int dv = 32 * j + 8 * q + 4 * h;
+                    float v0 = outm[f][j][4 * q + 0] * fac, v1 = outm[f][j][4 * q + 1] * fac;
+                    float v2 = outm[f][j][4 * q + 2] * fac, v3 = outm[f][j][4 * q + 3] * fac;
+                    if (o < L) {
+                        store4<T>(orow + dv, v0, v1, v2, v3);
+                        if constexpr (MODE == M_APPLY) {
+                            if (drow) {
+                                float dd[4];
+                                load4<T>(drow + dv, dd);
+                                dot += dd[0] * v0 + dd[1] * v1 + dd[2] * v2 + dd[3] * v3;
+                            }
+                        }
+                    }
+                }
+            if constexpr (MODE == M_APPLY) {
+                if (a.dot_mat) {
+                    dot += __shfl_xor(dot, 32);
+                    if (h == 0 && o < L) a.dot_out.p[n * a.dot_out.stride + o] = dot;
+                }
+            }
+        }
+    }
+}
+
+// ------------------------------------------------------------------ small kernels
+__global__ void fill_kernel(float *p, long per, long stride, int nprob, float val)
+{
+    long i = (long)blockIdx.x * blockDim.x + threadIdx.x;
+    if (i < per * nprob) p[(i / per) * stride + (i % per)] = val;
+}
+
+// g_o = <A_o, B_o> for o < L; g[L..Lp) = 0
+template <typename T, int D>
+__global__ void rowdot_kernel(const T *A, const T *Bm, float *g, long gstride, int L, int Lp)
+{
+    const int n = blockIdx.y;
+    const int o = blockIdx.x * blockDim.x + threadIdx.x;
+    if (o >= Lp) return;
+    float acc = 0.f;
+    if (o < L) {
+        const T *pa = A + ((long)n * L + o) * D, *pb = Bm + ((long)n * L + o) * D;
+#pragma unroll
+        for (int k = 0; k < D; k += 4) {
+            float x[4], y[4];
+            load4<T>(pa + k, x);
+            load4<T>(pb + k, y);
+            acc += x[0] * y[0] + x[1] * y[1] + x[2] * y[2] + x[3] * y[3];
+        }
+    }
+    g[n * gstride + o] = acc;
+}
+
+// Modifier packs of Prop. 2.  rowp = (1, ubar2, alpha, alpha*ubar1); colp = (vbar2, beta,
+// beta*vbar1, delta) with alpha = exp(u1-u2), beta = exp(v1-v2), delta = exp(v0-v2).
+__global__ void packs_kernel(const float *UV, int Lp, const float *ub2, const float *vb2,
+                             const float *vb1, const float *ub1, long wstride, float4 *rowp,
+                             float4 *colp, long ldp)
+{
+    const int n = blockIdx.y;
+    const int i = blockIdx.x * blockDim.x + threadIdx.x;
+    if (i >= Lp) return;
+    const float *uv = UV + (long)n * 6 * Lp;
+    const float v0 = uv[1 * Lp + i], u1 = uv[2 * Lp + i], v1 = uv[3 * Lp + i];
+    const float u2 = uv[4 * Lp + i], v2 = uv[5 * Lp + i];
+    const float al = __expf(u1 - u2), be = __expf(v1 - v2), de = __expf(v0 - v2);
+    const long w = n * wstride + i;
+    rowp[n * ldp + i] = make_float4(1.f, ub2[w], al, al * ub1[w]);
+    colp[n * ldp + i] = make_float4(vb2[w], be, be * vb1[w], de);
+}
+
+// Dustbin element of a sweep result: the extra row (column) is joined to every
+// index 0..L of the other side by an edge of score sdb.
+//   w == null: out[L] = -log sum_{t<=L} exp(sdb + y_t)
+//   else     : out[L] = pre - exp(x[L]) sum_{t<=L} exp(sdb + y_t) w_t   (pre = 0)
+__global__ __launch_bounds__(1024) void dustbin_kernel(Vec y, Vec w, Vec x, VecOut out, int L, float sdb)
+{
+    __shared__ float sm[32], ss[32];
+    const int n = blockIdx.x, tid = threadIdx.x, lane = tid & 63, wv = tid >> 6;
+    const float *yp = y.p + n * y.stride;
+    float m = -INFINITY;
+    for (int t = tid; t <= L; t += blockDim.x) m = fmaxf(m, yp[t]);
+    for (int s = 32; s >= 1; s >>= 1) m = fmaxf(m, __shfl_xor(m, s));
+    if (lane == 0) sm[wv] = m;
+    __syncthreads();
+    m = sm[0];
+    for (int i = 1; i < (int)(blockDim.x >> 6); ++i) m = fmaxf(m, sm[i]);
+    float acc = 0.f;
+    for (int t = tid; t <= L; t += blockDim.x) {
+        float e = __expf(yp[t] - m);
+        acc += w.p ? e * w.p[n * w.stride + t] : e;
+    }
+    for (int s = 32; s >= 1; s >>= 1) acc += __shfl_xor(acc, s);
+    if (lane == 0) ss[wv] = acc;
+    __syncthreads();
+    if (tid == 0) {
+        float tot = 0.f;
+        for (int i = 0; i < (int)(blockDim.x >> 6); ++i) tot += ss[i];
+        float r;
+        if (!w.p) r = -(sdb + m + __logf(tot));
+        else r = -__expf(x.p[n * x.stride + L] + sdb + m) * tot;
+        out.p[n * out.stride + L] = r;
+    }
+}
+
+// ------------------------------------------------------------------ host side
+struct Problem {
+    int B, H, L, d, W, T, R, dustbin, dtype;
+    float eps, sdb;
+    int N() const { return B * H; }
+    int Lp() const { return L + (dustbin ? 1 : 0); }
+    long ldw() const { return ((long)Lp() + 3) / 4 * 4; }  // stride of workspace vectors
+};
+
+constexpr int WS_VECS = 5;   // gu, vb2, ub2, vb1, ub1
+size_t ws_bytes(const Problem &p)
+{
+    return (size_t)p.N() * p.ldw() * (WS_VECS * sizeof(float) + 2 * sizeof(float4));
+}
+
+int check_common(const Problem &p)
+{
+    if (p.B < 1 || p.H < 1 || p.L < 1 || p.W < 0 || p.T < 0) return SKA_EINVAL;
+    if (!(p.eps > 0.f) || !isfinite(p.eps) || !isfinite(p.sdb)) return SKA_EINVAL;
+    if ((long)p.B * p.H > 65535) return SKA_EINVAL;
+    if (p.R != 2) return SKA_EUNSUPPORTED;
+    if (p.d != 32 && p.d != 64 && p.d != 128) return SKA_EUNSUPPORTED;
+    if (p.dtype != SKA_F32 && p.dtype != SKA_BF16) return SKA_EUNSUPPORTED;
+    return SKA_OK;
+}
+
+template <typename T, int D, int MODE, int FR>
+int launch_sweep(SweepArgs a, int N, hipStream_t st)
+{
+    constexpr int BM = NWAVES * FR * 32;
+    a.nbp = (a.L + BM - 1) / BM;
+    a.nb_total = a.nbp * N;
+    const int chunk = (a.nb_total + 7) / 8;
+    constexpr int LDS = 2 * Stage<T, D, MODE>::BYTES;
+    static bool raised = false;    // static LDS tops out at 64 KB; the CU has 160 KB
+    if (LDS > 48 * 1024 && !raised) {
+        if (hipFuncSetAttribute(reinterpret_cast<const void *>(&sweep_kernel<T, D, MODE, FR>),
+                                hipFuncAttributeMaxDynamicSharedMemorySize, LDS) != hipSuccess)
+            return SKA_EHIP;
+        raised = true;
+    }
+    hipLaunchKernelGGL((sweep_kernel<T, D, MODE, FR>), dim3(chunk * 8), dim3(NTHREADS), LDS, st, a);
+    return hipGetLastError() == hipSuccess ? SKA_OK : SKA_EHIP;
+}
+
+template <typename T, int D> int sweep(int mode, const SweepArgs &a, int N, hipStream_t st)
+{
+    constexpr int FRV = (sizeof(T) == 2) ? 2 : 1;   // vector sweeps: owner rows per wave / 32
+    switch (mode) {
+    case M_LSE_FIRST: return launch_sweep<T, D, M_LSE_FIRST, FRV>(a, N, st);
+    case M_LSE: return launch_sweep<T, D, M_LSE, FRV>(a, N, st);
+    case M_MATVEC: return launch_sweep<T, D, M_MATVEC, FRV>(a, N, st);
+    case M_APPLY: return launch_sweep<T, D, M_APPLY, 1>(a, N, st);
+    default: return launch_sweep<T, D, M_FINAL, 1>(a, N, st);
+    }
+}
+
+#define SKA_TRY(x)                      \
+    do {                                \
+        int rc_ = (x);                  \
+        if (rc_ != SKA_OK) return rc_;  \
+    } while (0)
+
+template <typename T, int D>
+int fwd_impl(const Problem &p, const void *Q, const void *K, const void *V, void *O, float *UV,
+             hipStream_t st)
+{
+    const int N = p.N(), L = p.L, Lp = p.Lp();
+    const long us = 6L * Lp;
+    auto vec = [&](int k) { return Vec{UV + (long)k * Lp, us}; };
+    auto vout = [&](int k) { return VecOut{UV + (long)k * Lp, us}; };
+    SweepArgs base{};
+    base.L = L; base.W = p.W < L ? p.W : L;   // |i-j| <= L-1 always: W >= L is the dense problem
+    base.cs = 1.f / (p.eps * sqrtf((float)p.d));
+    base.c2 = base.cs * LOG2E;
+    base.dustbin = p.dustbin; base.sdb2 = p.sdb * LOG2E;
+
+    // u0 = v0 = 0: the base solve starts from v = 0
+    {
+        long tot = 2L * Lp * N;
+        hipLaunchKernelGGL(fill_kernel, dim3((tot + 255) / 256), dim3(256), 0, st, UV, 2L * Lp, us, N, 0.f);
+        if (hipGetLastError() != hipSuccess) return SKA_EHIP;
+    }
+    bool first = true;
+    // half-step: out slot <- -LSE over the band of (S + yt); prev slot only stabilises
+    auto half = [&](bool row, int yslot, int prevslot, int outslot) -> int {
+        SweepArgs a = base;
+        a.X = row ? Q : K; a.Y = row ? K : Q;
+        a.yt = vec(yslot); a.xs = vec(prevslot); a.out_vec = vout(outslot);
+        SKA_TRY((sweep<T, D>(first ? M_LSE_FIRST : M_LSE, a, N, st)));
+        first = false;
+        if (p.dustbin) {
+            hipLaunchKernelGGL(dustbin_kernel, dim3(N), dim3(1024), 0, st, vec(yslot), Vec{nullptr, 0},
+                               Vec{nullptr, 0}, vout(outslot), L, p.sdb);
+            if (hipGetLastError() != hipSuccess) return SKA_EHIP;
+        }
+        return SKA_OK;
+    };
+    for (int t = 0; t < p.T; ++t) {
+        SKA_TRY(half(true, 1, 0, 0));
+        SKA_TRY(half(false, 0, 1, 1));
+    }
+    SKA_TRY(half(true, 1, 0, 2));    // u1 from v0
+    SKA_TRY(half(false, 2, 1, 3));   // v1 from u1
+    SKA_TRY(half(true, 3, 2, 4));    // u2 from v1
+    SKA_TRY(half(false, 4, 3, 5));   // v2 from u2
+    // output map with the terminal plan
+    SweepArgs a = base;
+    a.X = Q; a.Y = K; a.Pay = V; a.out_mat = O; a.xs = vec(4); a.yt = vec(5);
+    return sweep<T, D>(M_APPLY, a, N, st);
+}
+
+template <typename T, int D>
+int bwd_impl(const Problem &p, const void *Q, const void *K, const void *V, const void *O,
+             const void *G, const float *UV, void *dQ, void *dK, void *dV, float *eta0, void *ws,
+             hipStream_t st)
+{
+    const int N = p.N(), L = p.L, Lp = p.Lp();
+    const long us = 6L * Lp, ldw = p.ldw();
+    auto uv = [&](int k) { return Vec{UV + (long)k * Lp, us}; };
+    float *wf = reinterpret_cast<float *>(ws);
+    float *gu = wf, *vb2 = wf + 1 * N * ldw, *ub2 = wf + 2 * N * ldw, *vb1 = wf + 3 * N * ldw,
+          *ub1 = wf + 4 * N * ldw;
+    float4 *rowp = reinterpret_cast<float4 *>(wf + (long)WS_VECS * N * ldw);
+    float4 *colp = rowp + (long)N * ldw;
+    auto wv = [&](float *q) { return Vec{q, ldw}; };
+    auto wo = [&](float *q) { return VecOut{q, ldw}; };
+
+    SweepArgs base{};
+    base.L = L; base.W = p.W < L ? p.W : L;   // |i-j| <= L-1 always: W >= L is the dense problem
+    base.cs = 1.f / (p.eps * sqrtf((float)p.d));
+    base.c2 = base.cs * LOG2E;
+    base.dustbin = p.dustbin; base.sdb2 = p.sdb * LOG2E;
+    const dim3 vgrid((Lp + 255) / 256, N);
+
+    // g_u = <dO_i, O_i> (= (P22 . Z) 1); dustbin row has dO = 0
+    hipLaunchKernelGGL((rowdot_kernel<T, D>), vgrid, dim3(256), 0, st, reinterpret_cast<const T *>(G),
+                       reinterpret_cast<const T *>(O), gu, ldw, L, Lp);
+    if (hipGetLastError() != hipSuccess) return SKA_EHIP;
+    if (p.dustbin) {   // vbar2 at the dustbin column is 0 because V there is 0
+        hipLaunchKernelGGL(fill_kernel, dim3((N + 255) / 256), dim3(256), 0, st, vb2 + L, 1L, ldw, N, 0.f);
+        if (hipGetLastError() != hipSuccess) return SKA_EHIP;
+    }
+    // dV_j = sum_i P22_ij dO_i ; vbar2_j = <V_j, dV_j>  (column-oriented)
+    {
+        SweepArgs a = base;
+        a.X = K; a.Y = Q; a.Pay = G; a.out_mat = dV; a.xs = uv(5); a.yt = uv(4);
+        a.dot_mat = V; a.dot_out = wo(vb2);
+        SKA_TRY((sweep<T, D>(M_APPLY, a, N, st)));
+    }
+    // reverse recurrences of Prop. 1, each one band mat-vec with a staircase factor
+    // written as P22 times row/column modifiers folded into the exponent (Prop. 2)
+    auto matvec = [&](bool row, Vec xs, Vec yt, float *w, float *pre, VecOut out) -> int {
+        SweepArgs a = base;
+        a.X = row ? Q : K; a.Y = row ? K : Q;
+        a.xs = xs; a.yt = yt; a.w = wv(w); a.pre = Vec{pre, ldw}; a.out_vec = out;
+        SKA_TRY((sweep<T, D>(M_MATVEC, a, N, st)));
+        if (p.dustbin) {
+            hipLaunchKernelGGL(dustbin_kernel, dim3(N), dim3(1024), 0, st, yt, wv(w), xs, out, L, p.sdb);
+            if (hipGetLastError() != hipSuccess) return SKA_EHIP;
+        }
+        return SKA_OK;
+    };
+    SKA_TRY(matvec(true, uv(4), uv(5), vb2, gu, wo(ub2)));        // ubar2 = g_u - P22 vbar2
+    SKA_TRY(matvec(false, uv(3), uv(4), ub2, nullptr, wo(vb1)));  // vbar1 = -(P21)^T ubar2
+    SKA_TRY(matvec(true, uv(2), uv(3), vb1, nullptr, wo(ub1)));   // ubar1 = -P11 vbar1
+    if (eta0) {                                               // vbar0 = -(P10)^T ubar1
+        SKA_TRY(matvec(false, uv(1), uv(2), ub1, nullptr, VecOut{eta0, (long)Lp}));
+    }
+    hipLaunchKernelGGL(packs_kernel, vgrid, dim3(256), 0, st, UV, Lp, ub2, vb2, vb1, ub1, ldw, rowp, colp, ldw);
+    if (hipGetLastError() != hipSuccess) return SKA_EHIP;
+    // one-reference final sweeps
+    {
+        SweepArgs a = base;
+        a.X = Q; a.Y = K; a.A = G; a.Bm = V; a.out_mat = dQ; a.xs = uv(4); a.yt = uv(5);
+        a.po = rowp; a.qt = colp; a.ldp = ldw;
+        SKA_TRY((sweep<T, D>(M_FINAL, a, N, st)));
+    }
+    {
+        SweepArgs a = base;
+        a.X = K; a.Y = Q; a.A = V; a.Bm = G; a.out_mat = dK; a.xs = uv(5); a.yt = uv(4);
+        a.po = colp; a.qt = rowp; a.ldp = ldw;
+        SKA_TRY((sweep<T, D>(M_FINAL, a, N, st)));
+    }
+    return SKA_OK;
+}
+
+}  // namespace
+
+// ====================================================================== C ABI
+extern "C" {
+
+size_t sinkhorn_attn_workspace_bytes(int B, int H, int L, int d, int W, int T, int R, int dustbin, int dtype)
+{
+    Problem p{B, H, L, d, W, T, R, dustbin ? 1 : 0, dtype, 1.f, 0.f};
+    if (check_common(p) != SKA_OK) return 0;
+    return ws_bytes(p);
+}
+
+int sinkhorn_attn_fwd(const void *Q, const void *K, const void *V, void *O, float *UV, int B, int H, int L,
+                      int d, int W, int T, int R, float eps, int dustbin, float dustbin_score, int dtype,
+                      void *workspace, size_t workspace_bytes, void *stream)
+{
+    (void)workspace; (void)workspace_bytes;
+    Problem p{B, H, L, d, W, T, R, dustbin ? 1 : 0, dtype, eps, dustbin_score};
+    if (!Q || !K || !V || !O || !UV) return SKA_EINVAL;
+    int rc = check_common(p);
+    if (rc != SKA_OK) return rc;
+    hipStream_t st = reinterpret_cast<hipStream_t>(stream);
+#define SKA_FWD(TT_, DD_) return fwd_impl<TT_, DD_>(p, Q, K, V, O, UV, st)
+    if (dtype == SKA_F32) {
+        if (d == 32) SKA_FWD(float, 32);
+        if (d == 64) SKA_FWD(float, 64);
+        SKA_FWD(float, 128);
+    } else {
+        if (d == 32) SKA_FWD(__bf16, 32);
+        if (d == 64) SKA_FWD(__bf16, 64);
+        SKA_FWD(__bf16, 128);
+    }
+#undef SKA_FWD
+}
+
+int sinkhorn_attn_bwd(const void *Q, const void *K, const void *V, const void *O, const void *dO,
+                      const float *UV, void *dQ, void *dK, void *dV, float *eta0, int B, int H, int L, int d,
+                      int W, int T, int R, float eps, int dustbin, float dustbin_score, int dtype,
+                      void *workspace, size_t workspace_bytes, void *stream)
+{
+    Problem p{B, H, L, d, W, T, R, dustbin ? 1 : 0, dtype, eps, dustbin_score};
+    if (!Q || !K || !V || !O || !dO || !UV || !dQ || !dK || !dV) return SKA_EINVAL;
+    int rc = check_common(p);
+    if (rc != SKA_OK) return rc;
+    if (!workspace || workspace_bytes < ws_bytes(p)) return SKA_EWORKSPACE;
+    if (reinterpret_cast<uintptr_t>(workspace) & 15) return SKA_EINVAL;
+    hipStream_t st = reinterpret_cast<hipStream_t>(stream);
+#define SKA_BWD(TT_, DD_) return bwd_impl<TT_, DD_>(p, Q, K, V, O, dO, UV, dQ, dK, dV, eta0, workspace, st)
+    if (dtype == SKA_F32) {
+        if (d == 32) SKA_BWD(float, 32);
+        if (d == 64) SKA_BWD(float, 64);
+        SKA_BWD(float, 128);
+    } else {
+        if (d == 32) SKA_BWD(__bf16, 32);
+        if (d == 64) SKA_BWD(__bf16, 64);
+        SKA_BWD(__bf16, 128);
+    }
+#undef SKA_BWD
+}
+
+const char *sinkhorn_attn_strerror(int status)
+{
+    switch (status) {
+    case SKA_OK: return "ok";
+    case SKA_EINVAL: return "invalid argument (null pointer, non-positive size, bad eps, misaligned workspace)";
+    case SKA_EUNSUPPORTED: return "unsupported configuration (need R == 2, d in {32, 64, 128}, dtype f32 or bf16)";
+    case SKA_EWORKSPACE: return "workspace missing or smaller than sinkhorn_attn_workspace_bytes()";
+    case SKA_EHIP: return "a HIP launch failed";
+    default: return "unknown status";
+    }
+}
+
+}  // extern "C"

@@ -1,0 +1,80 @@
+"""Host-side checks of the C-ABI library: it loads, exports every symbol the
+header declares, and rejects bad arguments before anything is launched (so all
+of this runs without a GPU)."""
+import ctypes
+import os
+import re
+
+import pytest
+
+from paper_2605_08123_amd import binding
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+def declared_symbols():
+    text = open(os.path.join(ROOT, "include", "sinkhorn_attn.h")).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(sinkhorn_attn_\w+)\s*\(", text)))
+
+
+def test_library_exports_every_declared_symbol():
+    lib = binding.load()
+    names = declared_symbols()
+    assert names == ["sinkhorn_attn_bwd", "sinkhorn_attn_fwd", "sinkhorn_attn_strerror",
+                     "sinkhorn_attn_workspace_bytes"]
+    for n in names:
+        assert hasattr(lib, n), n
+
+
+def test_workspace_bytes_and_strerror():
+    assert binding.sinkhorn_attn_workspace_bytes(1, 2, 262144, 64, 256, 20) >= 2 * 262144 * 13 * 4
+    assert binding.sinkhorn_attn_workspace_bytes(1, 1, 0, 64, 256, 20) == 0          # L < 1
+    assert binding.sinkhorn_attn_workspace_bytes(1, 1, 16, 48, 256, 20) == 0         # d unsupported
+    assert binding.sinkhorn_attn_workspace_bytes(1, 1, 16, 64, 4, 2, R=3) == 0
+    a = binding.sinkhorn_attn_workspace_bytes(2, 2, 1000, 64, 10, 5, dustbin=False)
+    b = binding.sinkhorn_attn_workspace_bytes(2, 2, 1000, 64, 10, 5, dustbin=True)
+    assert b > a > 0
+    for s in (0, -1, -2, -3, -4, 17):
+        assert isinstance(binding.sinkhorn_attn_strerror(s), str) and binding.sinkhorn_attn_strerror(s)
+
+
+def _fwd(lib, ptr=1 << 20, **kw):
+    a = dict(B=1, H=1, L=64, d=32, W=4, T=2, R=2, eps=1.0, dustbin=0, sdb=0.0, dtype=0)
+    a.update(kw)
+    p = ctypes.c_void_p(ptr)
+    return lib.sinkhorn_attn_fwd(p, p, p, p, p, a["B"], a["H"], a["L"], a["d"], a["W"], a["T"], a["R"],
+                                 a["eps"], a["dustbin"], a["sdb"], a["dtype"], None, 0, None)
+
+
+def _bwd(lib, ws=None, ws_bytes=0, ptr=1 << 20, **kw):
+    a = dict(B=1, H=1, L=64, d=32, W=4, T=2, R=2, eps=1.0, dustbin=0, sdb=0.0, dtype=0)
+    a.update(kw)
+    p = ctypes.c_void_p(ptr)
+    return lib.sinkhorn_attn_bwd(p, p, p, p, p, p, p, p, p, None, a["B"], a["H"], a["L"], a["d"], a["W"],
+                                 a["T"], a["R"], a["eps"], a["dustbin"], a["sdb"], a["dtype"], ws, ws_bytes,
+                                 None)
+
+
+def test_argument_errors_are_reported_before_any_launch():
+    """The pointers below are never dereferenced: every call fails validation."""
+    lib = binding.load()
+    assert _fwd(lib, ptr=0) == binding.SKA_EINVAL
+    for bad in (dict(B=0), dict(H=0), dict(L=0), dict(W=-1), dict(T=-1), dict(eps=0.0), dict(eps=-1.0),
+                dict(eps=float("inf")), dict(eps=float("nan"))):
+        assert _fwd(lib, **bad) == binding.SKA_EINVAL, bad
+        assert _bwd(lib, **bad) == binding.SKA_EINVAL, bad
+    for bad in (dict(R=1), dict(R=3), dict(d=48), dict(d=256), dict(dtype=7)):
+        assert _fwd(lib, **bad) == binding.SKA_EUNSUPPORTED, bad
+        assert _bwd(lib, **bad) == binding.SKA_EUNSUPPORTED, bad
+    assert _bwd(lib, ws=None, ws_bytes=0) == binding.SKA_EWORKSPACE
+    need = binding.sinkhorn_attn_workspace_bytes(1, 1, 64, 32, 4, 2, dtype=0)
+    assert _bwd(lib, ws=ctypes.c_void_p(1 << 20), ws_bytes=need - 1) == binding.SKA_EWORKSPACE
+    assert _bwd(lib, ws=ctypes.c_void_p((1 << 20) + 4), ws_bytes=need) == binding.SKA_EINVAL
+
+
+def test_binding_rejects_cpu_tensors():
+    import torch
+    x = torch.zeros((1, 1, 8, 32))
+    with pytest.raises(ValueError):
+        binding.sinkhorn_attn_fwd(x, x, x, 2, 1)
