@@ -1,0 +1,128 @@
+#!/usr/bin/env python3
+"""Benchmark: fwd + bwd of banded Sinkhorn attention at the paper-scale single-device
+configuration (B=1, H=2, L=262144, d=64, W=256, T=20, R=2, eps=0.5, bf16 storage,
+fp32 accumulation) on one MI355X.  A step is one forward plus one backward over
+one batch of seeded synthetic inputs that already sit in HBM.
+
+Prints ONE JSON line: whole-job tokens/s, plus
+  roofline     - the scaling-sweep kernel (Eq. 1-2; 2T+3 of the 51 launches of a
+                 step are this one kernel) timed in place with HIP events on the
+                 stream it runs on, against the HBM peak;
+  cpu_baseline - the fp64 CPU oracle timed on a bounded slice of the same workload.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBS = 8000.0          # MI355X HBM3E, published
+
+
+def algorithmic_bytes_per_sweep(w) -> float:
+    """One scaling sweep streams the two bf16 operand matrices once and reads one
+    fp32 vector and writes one: (4d + 8) bytes per token and head."""
+    return (2 * w.d * 2 + 8) * w.L * w.N
+
+
+def cpu_baseline(w, budget_tokens: int):
+    """Oracle as it stands on a slice of head 0 (first `budget_tokens` tokens)."""
+    import oracle
+    from paper_2605_08123_amd.workloads import make_inputs
+    ws = w.scaled(B=1, H=1, L=budget_tokens)
+    q, k, v, g = make_inputs(ws)
+    t0 = time.perf_counter()
+    oracle.band(q[0, 0], k[0, 0], v[0, 0], g[0, 0], ws.W, ws.T, ws.R, ws.eps, ws.dustbin, ws.dustbin_score)
+    dt = time.perf_counter() - t0
+    # one token of the metric carries H heads of work
+    return {"value": budget_tokens / (dt * w.H), "unit": "tokens/s", "cores": oracle.threads(),
+            "kind": "oracle",
+            "sample": f"fp64 oracle fwd+bwd on one head, first {budget_tokens} tokens of the workload "
+                      f"({dt:.2f} s); scaled by 1/H to the {w.H}-head token rate"}
+
+
+def main() -> int:
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=10)
+    ap.add_argument("--warmup", type=int, default=2)
+    ap.add_argument("--workload", default="paper")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--cpu-tokens", type=int, default=65536)
+    args = ap.parse_args()
+    if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
+        print("bench.py: this build runs on exactly one GPU (independent (batch, head) problems shard "
+              "with no communication; nothing here launches a second rank). Use --gpus 1.", file=sys.stderr)
+        return 2
+
+    import torch
+
+    import paper_2605_08123_amd as ska
+    from paper_2605_08123_amd.workloads import CONFIGS, make_inputs
+
+    if not torch.cuda.is_available():
+        print("bench.py: no GPU visible", file=sys.stderr)
+        return 3
+    w = CONFIGS[args.workload]
+    dev = torch.device("cuda:0")
+    td = torch.float32 if w.dtype == "f32" else torch.bfloat16
+    Q, K, V, G = (torch.from_numpy(x).to(dev).to(td) for x in make_inputs(w))
+    O = torch.empty_like(Q)
+    UV = torch.empty((w.B, w.H, 6, w.L + int(w.dustbin)), device=dev, dtype=torch.float32)
+    dQ, dK, dV = torch.empty_like(Q), torch.empty_like(Q), torch.empty_like(Q)
+    code = 0 if w.dtype == "f32" else 1
+    wsb = ska.sinkhorn_attn_workspace_bytes(w.B, w.H, w.L, w.d, w.W, w.T, w.R, w.dustbin, code)
+    wsp = torch.empty(wsb, device=dev, dtype=torch.uint8)
+
+    def step():
+        ska.sinkhorn_attn_fwd(Q, K, V, w.W, w.T, w.R, w.eps, w.dustbin, w.dustbin_score, O=O, UV=UV)
+        ska.sinkhorn_attn_bwd(Q, K, V, O, G, UV, w.W, w.T, w.R, w.eps, w.dustbin, w.dustbin_score,
+                              workspace=wsp, dQ=dQ, dK=dK, dV=dV)
+
+    for _ in range(args.warmup):
+        step()
+    torch.cuda.synchronize()
+    ska.sinkhorn_attn_profile_enable(True)
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        step()
+    torch.cuda.synchronize()
+    dt = time.perf_counter() - t0
+    ska.sinkhorn_attn_profile_enable(False)
+    sweep_ms, launches = ska.sinkhorn_attn_profile_read()
+
+    ms_per_step = 1e3 * dt / args.steps
+    tokens_per_s = w.B * w.L * args.steps / dt
+    avg_s = 1e-3 * sweep_ms / max(launches, 1)
+    achieved = algorithmic_bytes_per_sweep(w) / avg_s / 1e9
+    traffic = None
+    tpath = os.path.join(ROOT, "profiles", f"lse_sweep_{w.name}_traffic.json")
+    if os.path.exists(tpath):
+        with open(tpath) as f:
+            traffic = json.load(f).get("hbm_bytes_per_launch")
+    out = {
+        "metric": "fwd+bwd tokens/sec at L=262144 d=64 W=256 T=20 R=2; % MFMA / HBM peak",
+        "value": tokens_per_s, "unit": "tokens/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": ms_per_step, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "bf16" if w.dtype == "bf16" else "f32", "data": "synthetic",
+        "config": {"workload": w.name, "B": w.B, "H": w.H, "L": w.L, "d": w.d, "W": w.W, "T": w.T,
+                   "R": w.R, "eps": w.eps, "dustbin": w.dustbin},
+        "roofline": {"kernel": "scaling sweep (row/column half-step, Eq. 1-2)", "bound": "hbm",
+                     "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                     "frac": achieved / HBM_PEAK_GBS, "traffic": traffic,
+                     "launches_timed": launches, "avg_launch_us": 1e6 * avg_s,
+                     "algorithmic_bytes_per_launch": algorithmic_bytes_per_sweep(w)},
+    }
+    if not args.no_cpu_baseline:
+        out["cpu_baseline"] = cpu_baseline(w, min(args.cpu_tokens, w.L))
+    print(json.dumps(out))
+    return 0
+
+
+if __name__ == "__main__":
+    sys.exit(main())

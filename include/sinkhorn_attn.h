@@ -88,6 +88,21 @@ int sinkhorn_attn_bwd(const void *Q, const void *K, const void *V, const void *O
                       float dustbin_score, int dtype, void *workspace, size_t workspace_bytes,
                       void *stream);
 
+/*
+ * Benchmark hooks (no part of the operator).  While enabled, every forward call
+ * records one HIP event on its stream after its first half-step launch and one
+ * after its last, so that the run of identical half-step kernels in between
+ * (2T + 3 launches of the scaling sweep of Eq. 1-2) can be timed in place,
+ * inside a larger timed region, without a profiler.  At most 256 calls are
+ * remembered between reads.
+ *   sinkhorn_attn_profile_enable(on): 0/1; returns SKA_OK.
+ *   sinkhorn_attn_profile_read(&ms, &launches): waits for the recorded events,
+ *     returns the summed elapsed milliseconds and the number of half-step
+ *     launches they bracket, then forgets them.  Host pointers.
+ */
+int sinkhorn_attn_profile_enable(int on);
+int sinkhorn_attn_profile_read(double *elapsed_ms, long *launches);
+
 /* Static, human-readable text for a ska_status value. Never NULL. */
 const char *sinkhorn_attn_strerror(int status);
 

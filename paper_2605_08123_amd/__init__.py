@@ -4,4 +4,5 @@
 `workloads` holds the seeded synthetic inputs; `build` compiles the library.
 """
 from .binding import (SinkhornAttnError, sinkhorn_attn_bwd, sinkhorn_attn_fwd,  # noqa: F401
+                      sinkhorn_attn_profile_enable, sinkhorn_attn_profile_read,
                       sinkhorn_attn_strerror, sinkhorn_attn_workspace_bytes)

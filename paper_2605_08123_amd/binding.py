@@ -37,6 +37,11 @@ def load():
         lib.sinkhorn_attn_bwd.restype = i
         lib.sinkhorn_attn_bwd.argtypes = [vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, i, i, i, i, i, i, i, f,
                                           i, f, i, vp, sz, vp]
+        lib.sinkhorn_attn_profile_enable.restype = i
+        lib.sinkhorn_attn_profile_enable.argtypes = [i]
+        lib.sinkhorn_attn_profile_read.restype = i
+        lib.sinkhorn_attn_profile_read.argtypes = [ctypes.POINTER(ctypes.c_double),
+                                                   ctypes.POINTER(ctypes.c_long)]
         lib.sinkhorn_attn_strerror.restype = ctypes.c_char_p
         lib.sinkhorn_attn_strerror.argtypes = [i]
         _lib = lib
@@ -51,6 +56,19 @@ class SinkhornAttnError(RuntimeError):
 
 def sinkhorn_attn_strerror(status: int) -> str:
     return load().sinkhorn_attn_strerror(int(status)).decode()
+
+
+def sinkhorn_attn_profile_enable(on: bool) -> None:
+    load().sinkhorn_attn_profile_enable(int(bool(on)))
+
+
+def sinkhorn_attn_profile_read():
+    """(elapsed milliseconds, half-step launches bracketed) since the last read."""
+    ms, n = ctypes.c_double(0.0), ctypes.c_long(0)
+    rc = load().sinkhorn_attn_profile_read(ctypes.byref(ms), ctypes.byref(n))
+    if rc != SKA_OK:
+        raise SinkhornAttnError(rc)
+    return ms.value, n.value
 
 
 def sinkhorn_attn_workspace_bytes(B, H, L, d, W, T, R=2, dustbin=False, dtype=SKA_BF16) -> int:

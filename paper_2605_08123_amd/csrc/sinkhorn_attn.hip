@@ -716,6 +716,12 @@ template <typename T, int D> int sweep(int mode, const SweepArgs &a, int N, hipS
     }
 }
 
+// benchmark hooks: events bracketing the run of identical half-step launches
+struct ProfPair { hipEvent_t a, b; long launches; };
+bool g_prof_on = false;
+ProfPair g_prof[256];
+int g_prof_n = 0;
+
 #define SKA_TRY(x)                      \
     do {                                \
         int rc_ = (x);                  \
@@ -743,12 +749,21 @@ int fwd_impl(const Problem &p, const void *Q, const void *K, const void *V, void
         if (hipGetLastError() != hipSuccess) return SKA_EHIP;
     }
     bool first = true;
+    ProfPair *pp = nullptr;
     // half-step: out slot <- -LSE over the band of (S + yt); prev slot only stabilises
     auto half = [&](bool row, int yslot, int prevslot, int outslot) -> int {
         SweepArgs a = base;
         a.X = row ? Q : K; a.Y = row ? K : Q;
         a.yt = vec(yslot); a.xs = vec(prevslot); a.out_vec = vout(outslot);
         SKA_TRY((sweep<T, D>(first ? M_LSE_FIRST : M_LSE, a, N, st)));
+        if (first && g_prof_on && g_prof_n < 256) {
+            pp = &g_prof[g_prof_n];
+            if (hipEventCreate(&pp->a) != hipSuccess || hipEventCreate(&pp->b) != hipSuccess) return SKA_EHIP;
+            hipEventRecord(pp->a, st);
+            pp->launches = -1;   // the first launch is the other (max-tracking) kernel
+            ++g_prof_n;
+        }
+        if (pp) ++pp->launches;
         first = false;
         if (p.dustbin) {
             hipLaunchKernelGGL(dustbin_kernel, dim3(N), dim3(1024), 0, st, vec(yslot), Vec{nullptr, 0},
@@ -765,6 +780,7 @@ int fwd_impl(const Problem &p, const void *Q, const void *K, const void *V, void
     SKA_TRY(half(false, 2, 1, 3));   // v1 from u1
     SKA_TRY(half(true, 3, 2, 4));    // u2 from v1
     SKA_TRY(half(false, 4, 3, 5));   // v2 from u2
+    if (pp) hipEventRecord(pp->b, st);
     // output map with the terminal plan
     SweepArgs a = base;
     a.X = Q; a.Y = K; a.Pay = V; a.out_mat = O; a.xs = vec(4); a.yt = vec(5);
@@ -904,6 +920,34 @@ int sinkhorn_attn_bwd(const void *Q, const void *K, const void *V, const void *O
         SKA_BWD(__bf16, 128);
     }
 #undef SKA_BWD
+}
+
+int sinkhorn_attn_profile_enable(int on)
+{
+    g_prof_on = on != 0;
+    return SKA_OK;
+}
+
+int sinkhorn_attn_profile_read(double *elapsed_ms, long *launches)
+{
+    if (!elapsed_ms || !launches) return SKA_EINVAL;
+    double ms = 0.0;
+    long n = 0;
+    int rc = SKA_OK;
+    for (int i = 0; i < g_prof_n; ++i) {
+        float t = 0.f;
+        if (hipEventSynchronize(g_prof[i].b) != hipSuccess ||
+            hipEventElapsedTime(&t, g_prof[i].a, g_prof[i].b) != hipSuccess)
+            rc = SKA_EHIP;
+        ms += t;
+        n += g_prof[i].launches;
+        hipEventDestroy(g_prof[i].a);
+        hipEventDestroy(g_prof[i].b);
+    }
+    g_prof_n = 0;
+    *elapsed_ms = ms;
+    *launches = n;
+    return rc;
 }
 
 const char *sinkhorn_attn_strerror(int status)
