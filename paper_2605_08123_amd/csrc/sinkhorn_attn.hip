@@ -23,6 +23,7 @@
 #include <hip/hip_runtime.h>
 #include <math.h>
 #include <stdint.h>
+#include <stdlib.h>
 
 #include "sinkhorn_attn.h"
 
@@ -71,6 +72,7 @@ struct SweepArgs {
     float cs;         // 1 / (eps sqrt d)
     int dustbin;
     float sdb2;       // dustbin score * log2(e)
+    int dbg;          // development knob
     int nbp;          // workgroups per problem
     int nb_total;
 };
@@ -136,6 +138,33 @@ __device__ __forceinline__ void tile_load(TileRegs<T, D> &reg, const T *base, in
             v = *reinterpret_cast<const uint4 *>(base + (long)(t0 + row) * D + ch * (16 / Elem<T>::BYTES));
         reg[c] = v;
     }
+}
+
+// Same, but branch-free: the row index is clamped into [0, L) so the load is always
+// issued (a conditional load makes the compiler wait for every load in flight before
+// it zero-fills the destination); `valid` says whether the data may be used.
+template <typename T, int D>
+__device__ __forceinline__ void tile_load_clamped(TileRegs<T, D> &reg, bool (&valid)[Tile<T, D>::CPT],
+                                                  const T *base, int t0, int L, bool live)
+{
+    using TL = Tile<T, D>;
+#pragma unroll
+    for (int c = 0; c < TL::CPT; ++c) {
+        int idx = threadIdx.x + c * NTHREADS;
+        if (idx >= TL::CHUNKS) idx = TL::CHUNKS - 1;
+        const int row = idx / TL::CPR, ch = idx % TL::CPR;
+        int t = t0 + row;
+        valid[c] = live && t < L;
+        t = t < 0 ? 0 : (t > L - 1 ? L - 1 : t);
+        reg[c] = *reinterpret_cast<const uint4 *>(base + (long)t * D + ch * (16 / Elem<T>::BYTES));
+    }
+}
+template <typename T, int D>
+__device__ __forceinline__ void tile_zero_invalid(TileRegs<T, D> &reg, const bool (&valid)[Tile<T, D>::CPT])
+{
+#pragma unroll
+    for (int c = 0; c < Tile<T, D>::CPT; ++c)
+        if (!valid[c]) reg[c] = make_uint4(0, 0, 0, 0);
 }
 
 // registers -> LDS, row-major (A-operand of the score / Z products)
@@ -237,6 +266,31 @@ __device__ __forceinline__ f32x16 tile_dot(const unsigned char *tile, const Owne
         acc = __builtin_amdgcn_mfma_f32_32x32x2f32(a.w, x.v[4 * q + 3], acc, 0, 0, 0);
     }
     return acc;
+}
+
+// FR score tiles at once from one other-side tile: the tile's fragments are read from
+// LDS once and every product chain is issued before any of them is consumed.
+template <int D, int FR>
+__device__ __forceinline__ void tile_dot_multi(const unsigned char *tile, const OwnerFrag<__bf16, D> (&x)[FR],
+                                               int lane, f32x16 (&acc)[FR])
+{
+    const int t = lane & 31, h = lane >> 5;
+    bf16x8 a[D / 16];
+#pragma unroll
+    for (int s = 0; s < D / 16; ++s)
+        a[s] = *reinterpret_cast<const bf16x8 *>(tile + bf16_chunk_off<D>(t, 2 * s + h));
+#pragma unroll
+    for (int s = 0; s < D / 16; ++s)
+#pragma unroll
+        for (int f = 0; f < FR; ++f)
+            acc[f] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[s], x[f].v[s], acc[f], 0, 0, 0);
+}
+template <int D, int FR>
+__device__ __forceinline__ void tile_dot_multi(const unsigned char *tile, const OwnerFrag<float, D> (&x)[FR],
+                                               int lane, f32x16 (&acc)[FR])
+{
+#pragma unroll
+    for (int f = 0; f < FR; ++f) acc[f] = tile_dot<D>(tile, x[f], lane, acc[f]);
 }
 
 // out[dvt][dv, o] += sum_t pay[t][dv] * e[t, o]   (e in the accumulator layout)
@@ -579,6 +633,206 @@ __global__ __launch_bounds__(NTHREADS) void sweep_kernel(const SweepArgs a)
     }
 }
 
+// ------------------------------------------------------------------ vector sweeps
+// Scaling sweep (M_LSE) and band mat-vec (M_MATVEC): the result is one scalar per
+// owner index, so the only state a wavefront carries is FR owner fragments and FR
+// partial sums.  Wavefront w owns rows [o_blk + 32 FR w, +32 FR) and needs other-side
+// tiles kbase + FR w ... kend + FR w: the same count S for every wavefront, shifted by
+// FR per wavefront.  The tiles therefore go through an LDS ring with that skew: at
+// step s wavefront w works on tile kbase + s + FR w, so all wavefronts are busy in
+// every step, and one new tile enters the ring per step (one barrier per step).
+template <typename T, int D, int MODE, int FR> struct VRing {
+    using TL = Tile<T, D>;
+    static constexpr int LEAD = FR * (NWAVES - 1);          // tiles between first and last wavefront
+    static constexpr int NSLOT = (LEAD + 2 <= 8) ? 8 : 16;  // power of two >= LEAD + 2
+    static constexpr int OFF_VY = TL::RM_BYTES;
+    static constexpr int OFF_VW = OFF_VY + TT * 4;
+    static constexpr int SLOT = OFF_VW + TT * 4;
+    static constexpr int BYTES = NSLOT * SLOT;
+};
+
+template <typename T, int D, int MODE, int FR>
+__global__ __launch_bounds__(NTHREADS) void vsweep_kernel(const SweepArgs a)
+{
+    using TL = Tile<T, D>;
+    using RG = VRing<T, D, MODE, FR>;
+    constexpr int BM = NWAVES * FR * 32;
+    static_assert(MODE == M_LSE || MODE == M_MATVEC, "vector sweeps only");
+
+    extern __shared__ __align__(16) unsigned char smem[];
+    __shared__ float red[NWAVES];
+
+    const int chunk = (a.nb_total + 7) >> 3;
+    const int lb = (blockIdx.x & 7) * chunk + (blockIdx.x >> 3);
+    if (lb >= a.nb_total) return;
+    const int n = lb / a.nbp;
+    const int o_blk = (lb % a.nbp) * BM;
+
+    // the wavefront index is uniform: keep it (and all tile bookkeeping) in scalar registers
+    const int tid = threadIdx.x, lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int c = lane & 31, h = lane >> 5;
+    const int L = a.L, W = a.W;
+    const long moff = (long)n * L * D;
+    const T *Xb = reinterpret_cast<const T *>(a.X) + moff;
+    const T *Yb = reinterpret_cast<const T *>(a.Y) + moff;
+    const float *ytp = a.yt.p + n * a.yt.stride;
+    const float *xsp = a.xs.p + n * a.xs.stride;
+    const float *wp = (MODE == M_MATVEC) ? a.w.p + n * a.w.stride : nullptr;
+
+    float mblk;
+    {
+        float m = -INFINITY;
+        for (int i = tid; i < BM; i += NTHREADS)
+            if (o_blk + i < L) m = fmaxf(m, xsp[o_blk + i]);
+#pragma unroll
+        for (int s = 32; s >= 1; s >>= 1) m = fmaxf(m, __shfl_xor(m, s));
+        if (lane == 0) red[wave] = m;
+        __syncthreads();
+        mblk = fmaxf(fmaxf(red[0], red[1]), fmaxf(red[2], red[3]));
+    }
+    const float m2 = mblk * LOG2E;
+
+    OwnerFrag<T, D> xf[FR];
+    int o_frag[FR];
+    float sum[FR];
+#pragma unroll
+    for (int f = 0; f < FR; ++f) {
+        o_frag[f] = o_blk + (wave * FR + f) * 32;
+        xf[f].load(Xb, o_frag[f] + c, L, h);
+        sum[f] = 0.f;
+    }
+
+    // floor((o_blk - W) / 32) and floor((o_blk + 32 FR - 1 + W) / 32); W <= L so no overflow
+    const int kbase = (o_blk - W) >= 0 ? (o_blk - W) / TT : -((W - o_blk + TT - 1) / TT);
+    const int kend = (o_blk + 32 * FR - 1 + W) / TT;
+    const int S = kend - kbase + 1;
+    const int klast = (L - 1) / TT;
+
+    // One tile in flight between global memory and LDS: loads only, all unconditional
+    // (clamped addresses), so nothing stalls until the values are stored.
+    struct Inflight {
+        uint4 y[TL::CPT];
+        bool ok[TL::CPT];
+        float vy, vw;
+        bool live;
+    };
+    auto g_load = [&](Inflight &g, int k) {   // k may lie outside [0, klast]: then zeros / -inf
+        const int t0 = k * TT;
+        const bool live = (k >= 0 && k <= klast);
+        tile_load_clamped<T, D>(g.y, g.ok, Yb, t0, L, live);
+        int t = t0 + (tid & (TT - 1));
+        g.live = live && t < L;
+        t = t < 0 ? 0 : (t > L - 1 ? L - 1 : t);
+        g.vy = ytp[t];
+        g.vw = (MODE == M_MATVEC) ? wp[t] : 0.f;
+    };
+    auto s_store = [&](Inflight &g, int j) {  // j = tile index relative to kbase
+        unsigned char *sl = smem + (j & (RG::NSLOT - 1)) * RG::SLOT;
+        tile_zero_invalid<T, D>(g.y, g.ok);
+        tile_store_rm<T, D>(g.y, sl);
+        if (tid < TT) {
+            reinterpret_cast<float *>(sl + RG::OFF_VY)[tid] = g.live ? fmaf(g.vy, LOG2E, m2) : -INFINITY;
+            if constexpr (MODE == M_MATVEC) reinterpret_cast<float *>(sl + RG::OFF_VW)[tid] = g.live ? g.vw : 0.f;
+        }
+    };
+
+    // fill the ring with the tiles of step 0: every load is issued before the first store
+    {
+        Inflight fill[RG::LEAD + 1];
+#pragma unroll
+        for (int j = 0; j <= RG::LEAD; ++j) g_load(fill[j], kbase + j);
+#pragma unroll
+        for (int j = 0; j <= RG::LEAD; ++j) s_store(fill[j], j);
+    }
+    __syncthreads();
+    Inflight nxt;
+
+    for (int s = 0; s < S; ++s) {
+        const int jnew = s + 1 + RG::LEAD;
+        const bool more = (s + 1 < S);
+        if (more && !(a.dbg & 2)) g_load(nxt, kbase + jnew);
+
+        const int j = s + wave * FR;
+        const int k = kbase + j;
+        if (k >= 0 && k <= klast && !(a.dbg & 1)) {
+            const unsigned char *sl = smem + (j & (RG::NSLOT - 1)) * RG::SLOT;
+            const int t0 = k * TT;
+            bool use[FR], interior[FR];
+            f32x16 acc[FR];
+#pragma unroll
+            for (int f = 0; f < FR; ++f) {
+                const int of = o_frag[f];
+                use[f] = !(of >= L || t0 + TT - 1 < of - W || t0 > of + 31 + W);
+                interior[f] = (of + 31 - t0 <= W) && (t0 + TT - 1 - of <= W);
+#pragma unroll
+                for (int r = 0; r < 16; ++r) acc[f][r] = 0.f;
+            }
+            tile_dot_multi<D, FR>(sl, xf, lane, acc);   // unconditional: an unused tile costs MFMA only
+
+            float yv[16];
+#pragma unroll
+            for (int q = 0; q < 4; ++q) {
+                float4 v4 = *reinterpret_cast<const float4 *>(sl + RG::OFF_VY + (8 * q + 4 * h) * 4);
+                yv[4 * q + 0] = v4.x; yv[4 * q + 1] = v4.y; yv[4 * q + 2] = v4.z; yv[4 * q + 3] = v4.w;
+            }
+            float wv[MODE == M_MATVEC ? 16 : 1];
+            if constexpr (MODE == M_MATVEC) {
+#pragma unroll
+                for (int q = 0; q < 4; ++q) {
+                    float4 w4 = *reinterpret_cast<const float4 *>(sl + RG::OFF_VW + (8 * q + 4 * h) * 4);
+                    wv[4 * q + 0] = w4.x; wv[4 * q + 1] = w4.y; wv[4 * q + 2] = w4.z; wv[4 * q + 3] = w4.w;
+                }
+            }
+#pragma unroll
+            for (int f = 0; f < FR; ++f) {
+                if (!use[f]) continue;
+                float e[16];
+#pragma unroll
+                for (int r = 0; r < 16; ++r) e[r] = fmaf(acc[f][r], a.c2, yv[r]);
+                if (!interior[f]) {
+                    // keep (o, t) iff -W <= t - o <= W; with t = t0 + 4h + off_r this is
+                    // 0 <= off_r - lo <= 2W for lo = o - W - t0 - 4h: one unsigned compare
+                    const int lo = o_frag[f] + c - W - t0 - 4 * h;
+                    const unsigned span = 2u * (unsigned)W;
+#pragma unroll
+                    for (int r = 0; r < 16; ++r) {
+                        const int off = 8 * (r >> 2) + (r & 3);
+                        if ((unsigned)(off - lo) > span) e[r] = -INFINITY;
+                    }
+                }
+#pragma unroll
+                for (int r = 0; r < 16; ++r) {
+                    const float p = fast_exp2(e[r]);
+                    if constexpr (MODE == M_MATVEC) sum[f] = fmaf(p, wv[r], sum[f]);
+                    else sum[f] += p;
+                }
+            }
+        }
+        if (more) s_store(nxt, jnew);
+        __syncthreads();
+    }
+
+#pragma unroll
+    for (int f = 0; f < FR; ++f) {
+        const int o = o_frag[f] + c;
+        float tot = sum[f] + __shfl_xor(sum[f], 32);
+        if (a.dustbin) {   // spoke edge (o, dustbin element of the other side)
+            float ed = fast_exp2(a.sdb2 + ytp[L] * LOG2E + m2);
+            tot += (MODE == M_MATVEC) ? ed * wp[L] : ed;
+        }
+        if (h == 0 && o < L) {
+            float r;
+            if constexpr (MODE == M_LSE) {
+                r = mblk - LN2 * fast_log2(tot);
+            } else {
+                float pre = a.pre.p ? a.pre.p[n * a.pre.stride + o] : 0.f;
+                r = pre - fast_exp2((xsp[o] - mblk) * LOG2E) * tot;
+            }
+            a.out_vec.p[n * a.out_vec.stride + o] = r;
+        }
+    }
+}
+
 // ------------------------------------------------------------------ small kernels
 __global__ void fill_kernel(float *p, long per, long stride, int nprob, float val)
 {
@@ -704,8 +958,46 @@ int launch_sweep(SweepArgs a, int N, hipStream_t st)
     return hipGetLastError() == hipSuccess ? SKA_OK : SKA_EHIP;
 }
 
+template <typename T, int D, int MODE, int FR>
+int launch_vsweep(SweepArgs a, int N, hipStream_t st)
+{
+    constexpr int BM = NWAVES * FR * 32;
+    a.nbp = (a.L + BM - 1) / BM;
+    a.nb_total = a.nbp * N;
+    const int chunk = (a.nb_total + 7) / 8;
+    constexpr int LDS = VRing<T, D, MODE, FR>::BYTES;
+    static bool raised = false;
+    if (LDS > 48 * 1024 && !raised) {
+        if (hipFuncSetAttribute(reinterpret_cast<const void *>(&vsweep_kernel<T, D, MODE, FR>),
+                                hipFuncAttributeMaxDynamicSharedMemorySize, LDS) != hipSuccess)
+            return SKA_EHIP;
+        raised = true;
+    }
+    hipLaunchKernelGGL((vsweep_kernel<T, D, MODE, FR>), dim3(chunk * 8), dim3(NTHREADS), LDS, st, a);
+    return hipGetLastError() == hipSuccess ? SKA_OK : SKA_EHIP;
+}
+
+int g_variant = -1;   // development switch (SKA_VARIANT): 0 = first kernels, 1.. = ring kernels
+
 template <typename T, int D> int sweep(int mode, const SweepArgs &a, int N, hipStream_t st)
 {
+    if (g_variant < 0) {
+        const char *e = getenv("SKA_VARIANT");
+        g_variant = e ? atoi(e) : 1;
+    }
+    if (const char *e = getenv("SKA_DBG")) const_cast<SweepArgs &>(a).dbg = atoi(e);
+    if (g_variant >= 1 && (mode == M_LSE || mode == M_MATVEC)) {
+        if constexpr (sizeof(T) == 2) {
+            if (g_variant == 2 && D <= 64)
+                return mode == M_LSE ? launch_vsweep<T, D, M_LSE, 4>(a, N, st)
+                                     : launch_vsweep<T, D, M_MATVEC, 4>(a, N, st);
+            return mode == M_LSE ? launch_vsweep<T, D, M_LSE, 2>(a, N, st)
+                                 : launch_vsweep<T, D, M_MATVEC, 2>(a, N, st);
+        } else {
+            return mode == M_LSE ? launch_vsweep<T, D, M_LSE, 1>(a, N, st)
+                                 : launch_vsweep<T, D, M_MATVEC, 1>(a, N, st);
+        }
+    }
     constexpr int FRV = (sizeof(T) == 2) ? 2 : 1;   // vector sweeps: owner rows per wave / 32
     switch (mode) {
     case M_LSE_FIRST: return launch_sweep<T, D, M_LSE_FIRST, FRV>(a, N, st);
@@ -759,7 +1051,7 @@ int fwd_impl(const Problem &p, const void *Q, const void *K, const void *V, void
         if (first && g_prof_on && g_prof_n < 256) {
             pp = &g_prof[g_prof_n];
             if (hipEventCreate(&pp->a) != hipSuccess || hipEventCreate(&pp->b) != hipSuccess) return SKA_EHIP;
-            hipEventRecord(pp->a, st);
+            (void)hipEventRecord(pp->a, st);
             pp->launches = -1;   // the first launch is the other (max-tracking) kernel
             ++g_prof_n;
         }
@@ -780,7 +1072,7 @@ int fwd_impl(const Problem &p, const void *Q, const void *K, const void *V, void
     SKA_TRY(half(false, 2, 1, 3));   // v1 from u1
     SKA_TRY(half(true, 3, 2, 4));    // u2 from v1
     SKA_TRY(half(false, 4, 3, 5));   // v2 from u2
-    if (pp) hipEventRecord(pp->b, st);
+    if (pp) (void)hipEventRecord(pp->b, st);
     // output map with the terminal plan
     SweepArgs a = base;
     a.X = Q; a.Y = K; a.Pay = V; a.out_mat = O; a.xs = vec(4); a.yt = vec(5);
@@ -941,8 +1233,8 @@ int sinkhorn_attn_profile_read(double *elapsed_ms, long *launches)
             rc = SKA_EHIP;
         ms += t;
         n += g_prof[i].launches;
-        hipEventDestroy(g_prof[i].a);
-        hipEventDestroy(g_prof[i].b);
+        (void)hipEventDestroy(g_prof[i].a);
+        (void)hipEventDestroy(g_prof[i].b);
     }
     g_prof_n = 0;
     *elapsed_ms = ms;
