@@ -25,6 +25,8 @@
 #include <stdint.h>
 #include <stdlib.h>
 
+#include <type_traits>
+
 #include "sinkhorn_attn.h"
 
 namespace {
@@ -73,6 +75,7 @@ struct SweepArgs {
     int dustbin;
     float sdb2;       // dustbin score * log2(e)
     int dbg;          // development knob
+    int gpb;          // persistent sweeps: groups of owner rows per workgroup
     int nbp;          // workgroups per problem
     int nb_total;
 };
@@ -833,6 +836,317 @@ __global__ __launch_bounds__(NTHREADS) void vsweep_kernel(const SweepArgs a)
     }
 }
 
+// ------------------------------------------------------------------ persistent vector sweeps
+// Same skewed ring, but a workgroup of NW wavefronts walks several consecutive groups
+// of BM = 32 FR NW owner rows.  Consecutive groups need almost the same other-side
+// tiles (each group brings in exactly TPG = FR NW new ones), so the ring keeps rolling
+// across groups: every other-side tile is fetched once per workgroup, the fetches are
+// spread over the steps (PD tiles in flight in registers) and the next group's owner
+// rows are fetched while the current group computes, so HBM streaming overlaps the
+// exp2/MFMA work instead of alternating with it.
+//
+// Steps are numbered globally, sigma = (g - gA) S + i; in step (g, i) wavefront w
+// consumes tile J(g) + i + FR w, J(g) = g BM/32 + floor(-W/32).  Inside a wavefront the
+// work is software-pipelined by one step: while the VALU part of step sigma runs on one
+// accumulator set, the MFMAs of step sigma+1 fill the other.  The loader therefore stays
+// two steps ahead of the last wavefront: in step sigma it stores the tile that wavefront
+// NW-1 consumes in step sigma+2 (fetched PD steps earlier) and fetches the one for
+// step sigma+PD+2, unless an earlier group already brought that tile in.
+template <int D, int MODE, int NW, int FR> struct PRing {
+    static constexpr int NT = 64 * NW;
+    static constexpr int TPG = NW * FR;
+    static constexpr int LEAD = FR * (NW - 1);
+    static constexpr int NSLOT = 32;
+    static constexpr int PD = 4;                    // tiles in flight
+    static constexpr int AH = PD + 2;               // a tile is fetched AH steps before wavefront NW-1 needs it
+    static constexpr int NFILL = LEAD + AH;         // tiles of the first AH steps, fetched up front
+    static constexpr int TILE_BYTES = 32 * D * 2;
+    static constexpr int BPT = TILE_BYTES / NT;     // bytes each thread moves per tile
+    static constexpr int OFF_VY = TILE_BYTES;
+    static constexpr int OFF_VW = OFF_VY + TT * 4;
+    static constexpr int SLOT = OFF_VW + TT * 4;
+    static constexpr int BYTES = (NSLOT + 1) * SLOT;   // one spare slot for stores nobody reads
+    static constexpr int SMAX = NSLOT + FR - 2;     // largest S the ring can roll across groups
+    static_assert(BPT == 4 || BPT == 8 || BPT == 16, "tile does not split evenly over the threads");
+    static_assert(NFILL <= NSLOT, "initial fill exceeds the ring");
+};
+
+template <int BPT> struct PChunk { unsigned int w[BPT / 4]; };
+
+template <int D, int MODE, int NW, int FR, int DBG = 0>
+__global__ __launch_bounds__(64 * NW) void psweep_kernel(const SweepArgs a)
+{
+    using T = __bf16;
+    using RG = PRing<D, MODE, NW, FR>;
+    constexpr int NT = RG::NT, BM = NW * FR * 32, TPG = RG::TPG, PD = RG::PD, BPT = RG::BPT, AH = RG::AH;
+    static_assert(MODE == M_LSE || MODE == M_MATVEC, "vector sweeps only");
+
+    extern __shared__ __align__(16) unsigned char smem[];
+    __shared__ float red[NW];
+
+    const int chunk = (a.nb_total + 7) >> 3;
+    const int lb = (blockIdx.x & 7) * chunk + (blockIdx.x >> 3);
+    if (lb >= a.nb_total) return;
+    const int L = a.L, W = a.W;
+    const int GP = (L + BM - 1) / BM;               // groups per problem
+    const int n = lb / a.nbp;
+    const int gA = (lb % a.nbp) * a.gpb;
+    const int gB = (gA + a.gpb < GP) ? gA + a.gpb : GP;
+    if (gA >= GP) return;
+
+    const int tid = threadIdx.x, lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int c = lane & 31, h = lane >> 5;
+    const long moff = (long)n * L * D;
+    const T *Xb = reinterpret_cast<const T *>(a.X) + moff;
+    const unsigned char *Yb = reinterpret_cast<const unsigned char *>(reinterpret_cast<const T *>(a.Y) + moff);
+    const float *ytp = a.yt.p + n * a.yt.stride;
+    const float *xsp = a.xs.p + n * a.xs.stride;
+    const float *wp = (MODE == M_MATVEC) ? a.w.p + n * a.w.stride : nullptr;
+
+    // one stabiliser for all rows this workgroup owns (the staged potentials in the ring
+    // carry it, and the ring outlives a group)
+    float mblk;
+    {
+        float m = -INFINITY;
+        const int r1 = (gB * BM < L) ? gB * BM : L;
+        for (int i = gA * BM + tid; i < r1; i += NT) m = fmaxf(m, xsp[i]);
+#pragma unroll
+        for (int s = 32; s >= 1; s >>= 1) m = fmaxf(m, __shfl_xor(m, s));
+        if (lane == 0) red[wave] = m;
+        __syncthreads();
+        mblk = red[0];
+#pragma unroll
+        for (int i = 1; i < NW; ++i) mblk = fmaxf(mblk, red[i]);
+    }
+    const float m2 = mblk * LOG2E;
+
+    // tile bookkeeping (all scalar)
+    const int kb = -((W + TT - 1) / TT);             // floor(-W / 32)
+    const int ke = (32 * FR - 1 + W) / TT;
+    const int S = ke - kb + 1;                       // steps per group; host guarantees TPG <= S <= SMAX
+    const int QUIET = S - TPG;                       // leading steps of a later group that need no new tile
+    const int klast = (L - 1) / TT;
+    const int total = (gB - gA) * S;
+    auto J = [&](int g) { return g * (BM / TT) + kb; };
+
+    // loader: thread -> BPT bytes of the tile, lane -> one element of the vectors
+    const int bo = tid * BPT;
+    const int lrow = bo / (D * 2), lcol = bo % (D * 2);
+    const int lds_off = bf16_chunk_off<D>(lrow, lcol / 16) + (lcol % 16);
+    auto ld_issue = [&](PChunk<BPT> &d, float &vy, float &vw, int k) {
+        int t = k * TT + lrow;
+        t = t < 0 ? 0 : (t > L - 1 ? L - 1 : t);
+        d = *reinterpret_cast<const PChunk<BPT> *>(Yb + (long)t * (D * 2) + lcol);
+        int tv = k * TT + (tid & (TT - 1));
+        tv = tv < 0 ? 0 : (tv > L - 1 ? L - 1 : tv);
+        vy = ytp[tv];
+        vw = (MODE == M_MATVEC) ? wp[tv] : 0.f;
+    };
+    // tiles outside [0, klast] are stored too: their potentials are -inf, so they add nothing
+    auto ld_store = [&](const PChunk<BPT> &d, float vy, float vw, int k, bool wanted = true) {
+        unsigned char *sl = smem + (wanted ? (k & (RG::NSLOT - 1)) : RG::NSLOT) * RG::SLOT;
+        *reinterpret_cast<PChunk<BPT> *>(sl + lds_off) = d;
+        if (tid < TT) {
+            const bool live = k >= 0 && k <= klast && k * TT + tid < L;
+            reinterpret_cast<float *>(sl + RG::OFF_VY)[tid] = live ? fmaf(vy, LOG2E, m2) : -INFINITY;
+            if constexpr (MODE == M_MATVEC) reinterpret_cast<float *>(sl + RG::OFF_VW)[tid] = live ? vw : 0.f;
+        }
+    };
+
+    // owner rows: current group in xf, next group arriving in xn (rows beyond L are clamped:
+    // finite garbage in columns that are never written)
+    OwnerFrag<T, D> xf[FR], xn[FR];
+    auto x_issue = [&](OwnerFrag<T, D> (&x)[FR], int g) {
+#pragma unroll
+        for (int f = 0; f < FR; ++f) {
+            int o = g * BM + (wave * FR + f) * 32 + c;
+            o = o > L - 1 ? L - 1 : o;
+#pragma unroll
+            for (int s = 0; s < D / 16; ++s) {
+                uint4 z = *reinterpret_cast<const uint4 *>(Xb + (long)o * D + (2 * s + h) * 8);
+                x[f].v[s] = *reinterpret_cast<bf16x8 *>(&z);
+            }
+        }
+    };
+    x_issue(xf, gA);
+    if (gA + 1 < gB) x_issue(xn, gA + 1);
+
+    // initial fill: everything the first AH steps consume
+    {
+        PChunk<BPT> fd[RG::NFILL];
+        float fy[RG::NFILL], fw[RG::NFILL];
+#pragma unroll
+        for (int j = 0; j < RG::NFILL; ++j) ld_issue(fd[j], fy[j], fw[j], J(gA) + j);
+#pragma unroll
+        for (int j = 0; j < RG::NFILL; ++j) ld_store(fd[j], fy[j], fw[j], J(gA) + j);
+    }
+
+    // The loader is branch-free: every step publishes one staged tile and fetches one, so
+    // the compiler can count the loads in flight exactly.  The tile fetched in step sigma
+    // is the one wavefront NW-1 consumes in step sigma+AH; when an earlier step already
+    // brought it in, the same bytes are stored again; past the last group the fetch is
+    // clamped and its store goes to a spare slot.
+    auto advance = [&](int &g, int &i, int by) {
+        i += by;
+        if (i >= S) { i -= S; ++g; }
+    };
+    PChunk<BPT> sd[PD];
+    float sy[PD], sw[PD];
+    int sk[PD];            // tile held by each stage
+    bool sok[PD];          // somebody will consume it
+#pragma unroll
+    for (int r = 0; r < PD; ++r) {   // what steps -PD .. -1 would have fetched: tiles of steps 2 .. PD+1
+        int g2 = gA, i2 = 0;
+        advance(g2, i2, r + 2);
+        sok[r] = g2 < gB;
+        sk[r] = J(g2) + RG::LEAD + i2;
+        ld_issue(sd[r], sy[r], sw[r], sk[r]);
+    }
+    __syncthreads();
+
+    f32x16 acc[2][FR];
+    float sum[FR];
+    // One step inside a wavefront: the MFMAs of the NEXT step's tile (k_next, into `nxt`)
+    // interleaved with the exp2 / reduction work on the finished accumulators `cur` of this
+    // step's tile k.  MASKED applies the band mask to every fragment.
+    auto step_body = [&](auto masked_tag, f32x16 (&nxt)[FR], const f32x16 (&cur)[FR], int g, int k, int k_next) {
+        constexpr bool MASKED = decltype(masked_tag)::value;
+        const unsigned char *sl = smem + (k & (RG::NSLOT - 1)) * RG::SLOT;
+        const unsigned char *sn = smem + (k_next & (RG::NSLOT - 1)) * RG::SLOT;
+        const int t0 = k * TT;
+        const int o_w = g * BM + wave * FR * 32;
+        // LDS reads: next tile's fragments, this tile's potentials (and weights)
+        bf16x8 af[D / 16];
+#pragma unroll
+        for (int s = 0; s < D / 16; ++s)
+            af[s] = *reinterpret_cast<const bf16x8 *>(sn + bf16_chunk_off<D>(c, 2 * s + h));
+        float yv[16];
+#pragma unroll
+        for (int q = 0; q < 4; ++q) {
+            float4 v4 = *reinterpret_cast<const float4 *>(sl + RG::OFF_VY + (8 * q + 4 * h) * 4);
+            yv[4 * q + 0] = v4.x; yv[4 * q + 1] = v4.y; yv[4 * q + 2] = v4.z; yv[4 * q + 3] = v4.w;
+        }
+        float wv[MODE == M_MATVEC ? 16 : 1];
+        if constexpr (MODE == M_MATVEC) {
+#pragma unroll
+            for (int q = 0; q < 4; ++q) {
+                float4 w4 = *reinterpret_cast<const float4 *>(sl + RG::OFF_VW + (8 * q + 4 * h) * 4);
+                wv[4 * q + 0] = w4.x; wv[4 * q + 1] = w4.y; wv[4 * q + 2] = w4.z; wv[4 * q + 3] = w4.w;
+            }
+        }
+        const f32x16 zero = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+        for (int s = 0; s < D / 16; ++s)
+#pragma unroll
+            for (int f = 0; f < FR; ++f)
+                if constexpr (DBG & 8) { if (s == 0) nxt[f] = zero; nxt[f][s] += (float)af[s][0] * (float)xf[f].v[s][0]; }
+                else nxt[f] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[s], xf[f].v[s], s == 0 ? zero : nxt[f], 0, 0, 0);
+#pragma unroll
+        for (int f = 0; f < FR; ++f) {
+            // keep (o, t) iff -W <= t - o <= W; with t = t0 + 4h + off_r this is
+            // 0 <= off_r - lo <= 2W for lo = o - W - t0 - 4h: one unsigned compare
+            const int lo = o_w + 32 * f + c - W - t0 - 4 * h;
+            const unsigned span = 2u * (unsigned)W;
+#pragma unroll
+            for (int r = 0; r < 16; ++r) {
+                float e = fmaf(cur[f][r], a.c2, yv[r]);
+                if constexpr (MASKED) {
+                    const int off = 8 * (r >> 2) + (r & 3);
+                    if ((unsigned)(off - lo) > span) e = -INFINITY;
+                }
+                const float p = (DBG & 4) ? e : fast_exp2(e);
+                if constexpr (MODE == M_MATVEC) sum[f] = fmaf(p, wv[r], sum[f]);
+                else sum[f] += p;
+            }
+        }
+        // issue order: all LDS reads, then one MFMA per dozen VALU instructions, so the
+        // matrix pipe runs underneath the exp2 work of the same wavefront
+        __builtin_amdgcn_sched_group_barrier(0x100, D / 16 + (MODE == M_MATVEC ? 8 : 4), 0);
+#pragma unroll
+        for (int q = 0; q < FR * (D / 16); ++q) {
+            __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+            __builtin_amdgcn_sched_group_barrier(0x002, MASKED ? 20 : 12, 0);
+        }
+    };
+    auto epilogue = [&](int g) {
+        const int o_w = g * BM + wave * FR * 32;
+#pragma unroll
+        for (int f = 0; f < FR; ++f) {
+            const int o = o_w + 32 * f + c;
+            float tot = sum[f] + __shfl_xor(sum[f], 32);
+            if (a.dustbin) {
+                float ed = fast_exp2(a.sdb2 + ytp[L] * LOG2E + m2);
+                tot += (MODE == M_MATVEC) ? ed * wp[L] : ed;
+            }
+            if (h == 0 && o < L) {
+                float r;
+                if constexpr (MODE == M_LSE) {
+                    r = mblk - LN2 * fast_log2(tot);
+                } else {
+                    float pre = a.pre.p ? a.pre.p[n * a.pre.stride + o] : 0.f;
+                    r = pre - fast_exp2((xsp[o] - mblk) * LOG2E) * tot;
+                }
+                a.out_vec.p[n * a.out_vec.stride + o] = r;
+            }
+        }
+    };
+
+#pragma unroll
+    for (int f = 0; f < FR; ++f) sum[f] = 0.f;
+    int g = gA, i = 0;
+    {   // accumulators of step 0
+#pragma unroll
+        for (int f = 0; f < FR; ++f)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) acc[0][f][r] = 0.f;
+        tile_dot_multi<D, FR>(smem + ((J(gA) + wave * FR) & (RG::NSLOT - 1)) * RG::SLOT, xf, lane, acc[0]);
+    }
+
+    for (int sg0 = 0; sg0 < total; sg0 += PD) {
+        // PD steps per trip, unconditionally (a conditional step would hide from the compiler
+        // how many fetches are in flight).  If `total` is not a multiple of PD the last trip
+        // runs up to PD-1 steps past the end: g == gB there, so their fetches land in the
+        // spare slot, their sums are never written and no group end is reached (S > PD).
+#pragma unroll
+        for (int r = 0; r < PD; ++r) {
+            {
+                // loader: publish the tile of step sigma+2, fetch the one of step sigma+AH
+                if constexpr (!(DBG & 2)) {
+                    ld_store(sd[r], sy[r], sw[r], sk[r], sok[r]);
+                    int g2 = g, i2 = i;
+                    advance(g2, i2, AH);
+                    sok[r] = g2 < gB;
+                    sk[r] = J(g2) + RG::LEAD + i2;
+                    ld_issue(sd[r], sy[r], sw[r], sk[r]);
+                }
+                const bool last_of_group = (i == S - 1);
+                const int k = J(g) + i + wave * FR;
+                int k_next = k + 1;
+                if (last_of_group) {           // the next step belongs to the next group: its owner rows take over
+#pragma unroll
+                    for (int f = 0; f < FR; ++f) xf[f] = xn[f];
+                    k_next = J(g + 1) + wave * FR;
+                }
+                const int t0 = k * TT, o_w = g * BM + wave * FR * 32;
+                const bool all_in = (o_w + 32 * FR - 1 - t0 <= W) && (t0 + TT - 1 - o_w <= W);
+                if (all_in) step_body(std::false_type{}, acc[(r + 1) & 1], acc[r & 1], g, k, k_next);
+                else step_body(std::true_type{}, acc[(r + 1) & 1], acc[r & 1], g, k, k_next);
+                if constexpr (!(DBG & 16)) __syncthreads();
+                if (last_of_group) {
+                    epilogue(g);
+#pragma unroll
+                    for (int f = 0; f < FR; ++f) sum[f] = 0.f;
+                    i = 0;
+                    ++g;
+                    if (g + 1 < gB) x_issue(xn, g + 1);
+                } else {
+                    ++i;
+                }
+            }
+        }
+    }
+}
+
 // ------------------------------------------------------------------ small kernels
 __global__ void fill_kernel(float *p, long per, long stride, int nprob, float val)
 {
@@ -977,6 +1291,46 @@ int launch_vsweep(SweepArgs a, int N, hipStream_t st)
     return hipGetLastError() == hipSuccess ? SKA_OK : SKA_EHIP;
 }
 
+int g_ncu = 0;
+
+// Persistent sweep when the ring can roll across groups: TPG <= S <= NSLOT + FR - 1.
+template <int D, int MODE, int NW, int FR, int DBG = 0>
+int launch_psweep(SweepArgs a, int N, hipStream_t st, bool *taken)
+{
+    using RG = PRing<D, MODE, NW, FR>;
+    constexpr int BM = NW * FR * 32;
+    const int kb = -((a.W + TT - 1) / TT), ke = (32 * FR - 1 + a.W) / TT, S = ke - kb + 1;
+    *taken = false;
+    if (S < RG::TPG || S > RG::SMAX) return SKA_OK;
+    if (!g_ncu) {
+        if (const char *e = getenv("SKA_NCU")) g_ncu = atoi(e);   // development: pretend a smaller chip
+    }
+    if (!g_ncu) {
+        int dev = 0;
+        if (hipGetDevice(&dev) != hipSuccess ||
+            hipDeviceGetAttribute(&g_ncu, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || g_ncu < 1)
+            return SKA_EHIP;
+    }
+    const int GP = (a.L + BM - 1) / BM;
+    int bpp = (g_ncu + N - 1) / N;
+    if (bpp > GP) bpp = GP;
+    if (bpp < 1) bpp = 1;
+    a.gpb = (GP + bpp - 1) / bpp;
+    a.nbp = (GP + a.gpb - 1) / a.gpb;
+    a.nb_total = a.nbp * N;
+    const int chunk = (a.nb_total + 7) / 8;
+    static bool raised = false;
+    if (!raised) {
+        if (hipFuncSetAttribute(reinterpret_cast<const void *>(&psweep_kernel<D, MODE, NW, FR, DBG>),
+                                hipFuncAttributeMaxDynamicSharedMemorySize, RG::BYTES) != hipSuccess)
+            return SKA_EHIP;
+        raised = true;
+    }
+    hipLaunchKernelGGL((psweep_kernel<D, MODE, NW, FR, DBG>), dim3(chunk * 8), dim3(RG::NT), RG::BYTES, st, a);
+    *taken = true;
+    return hipGetLastError() == hipSuccess ? SKA_OK : SKA_EHIP;
+}
+
 int g_variant = -1;   // development switch (SKA_VARIANT): 0 = first kernels, 1.. = ring kernels
 
 template <typename T, int D> int sweep(int mode, const SweepArgs &a, int N, hipStream_t st)
@@ -987,6 +1341,25 @@ template <typename T, int D> int sweep(int mode, const SweepArgs &a, int N, hipS
     }
     if (const char *e = getenv("SKA_DBG")) const_cast<SweepArgs &>(a).dbg = atoi(e);
     if (g_variant >= 1 && (mode == M_LSE || mode == M_MATVEC)) {
+        if constexpr (sizeof(T) == 2 && D == 64) {
+            if (g_variant == 3) {
+                bool taken = false;
+                int rc;
+                if (mode == M_LSE) {
+                    switch (a.dbg) {
+                    case 2: rc = launch_psweep<D, M_LSE, 8, 2, 2>(a, N, st, &taken); break;
+                    case 4: rc = launch_psweep<D, M_LSE, 8, 2, 4>(a, N, st, &taken); break;
+                    case 8: rc = launch_psweep<D, M_LSE, 8, 2, 8>(a, N, st, &taken); break;
+                    case 12: rc = launch_psweep<D, M_LSE, 8, 2, 12>(a, N, st, &taken); break;
+                    case 16: rc = launch_psweep<D, M_LSE, 8, 2, 16>(a, N, st, &taken); break;
+                    case 18: rc = launch_psweep<D, M_LSE, 8, 2, 18>(a, N, st, &taken); break;
+                    case 30: rc = launch_psweep<D, M_LSE, 8, 2, 30>(a, N, st, &taken); break;
+                    default: rc = launch_psweep<D, M_LSE, 8, 2>(a, N, st, &taken);
+                    }
+                } else rc = launch_psweep<D, M_MATVEC, 8, 2>(a, N, st, &taken);
+                if (rc != SKA_OK || taken) return rc;
+            }
+        }
         if constexpr (sizeof(T) == 2) {
             if (g_variant == 2 && D <= 64)
                 return mode == M_LSE ? launch_vsweep<T, D, M_LSE, 4>(a, N, st)
