@@ -80,7 +80,8 @@ def main() -> int:
     wsp = torch.empty(wsb, device=dev, dtype=torch.uint8)
 
     def step():
-        ska.sinkhorn_attn_fwd(Q, K, V, w.W, w.T, w.R, w.eps, w.dustbin, w.dustbin_score, O=O, UV=UV)
+        ska.sinkhorn_attn_fwd(Q, K, V, w.W, w.T, w.R, w.eps, w.dustbin, w.dustbin_score, O=O, UV=UV,
+                              workspace=wsp)
         ska.sinkhorn_attn_bwd(Q, K, V, O, G, UV, w.W, w.T, w.R, w.eps, w.dustbin, w.dustbin_score,
                               workspace=wsp, dQ=dQ, dK=dK, dV=dV)
 

@@ -53,8 +53,9 @@ typedef enum {
 } ska_status;
 
 /*
- * Bytes of device scratch that sinkhorn_attn_bwd needs for these sizes (the
- * forward needs none).  Host-only, no GPU call.  Returns 0 on invalid sizes.
+ * Bytes of device scratch that sinkhorn_attn_bwd needs for these sizes; the
+ * forward is content with the same buffer (it needs B*H*L*d*2 bytes for bf16
+ * storage, none for fp32).  Host-only, no GPU call.  Returns 0 on invalid sizes.
  */
 size_t sinkhorn_attn_workspace_bytes(int B, int H, int L, int d, int W, int T, int R, int dustbin,
                                      int dtype);
@@ -64,7 +65,9 @@ size_t sinkhorn_attn_workspace_bytes(int B, int H, int L, int d, int W, int T, i
  * (Section 2.1-2.2, Eq. 1-2; Section 2.3 when dustbin != 0).
  *   in : Q, K, V [B,H,L,d]
  *   out: O [B,H,L,d]; UV [B,H,6,Lp] (all six vectors are written)
- * workspace may be NULL (workspace_bytes is ignored by the forward).
+ * workspace: 16-byte aligned scratch; bf16 storage needs at least B*H*L*d*2 bytes
+ * (a copy of Q with the score scale folded in), fp32 storage needs none and accepts
+ * NULL.  A buffer of sinkhorn_attn_workspace_bytes() always suffices.
  */
 int sinkhorn_attn_fwd(const void *Q, const void *K, const void *V, void *O, float *UV, int B, int H,
                       int L, int d, int W, int T, int R, float eps, int dustbin,

@@ -94,7 +94,8 @@ def _stream_ptr() -> int:
     return int(torch.cuda.current_stream().cuda_stream)
 
 
-def sinkhorn_attn_fwd(Q, K, V, W, T, R=2, eps=1.0, dustbin=False, dustbin_score=0.0, O=None, UV=None):
+def sinkhorn_attn_fwd(Q, K, V, W, T, R=2, eps=1.0, dustbin=False, dustbin_score=0.0, O=None, UV=None,
+                      workspace=None):
     """Forward. Q, K, V: [B,H,L,d] CUDA tensors (float32 or bfloat16).
     Returns (O [B,H,L,d], UV [B,H,6,L+dustbin] float32)."""
     B, H, L, d = Q.shape
@@ -107,9 +108,13 @@ def sinkhorn_attn_fwd(Q, K, V, W, T, R=2, eps=1.0, dustbin=False, dustbin_score=
         UV = torch.empty((B, H, 6, Lp), device=Q.device, dtype=torch.float32)
     _check(O, (B, H, L, d), Q.dtype, "O")
     _check(UV, (B, H, 6, Lp), torch.float32, "UV")
+    if workspace is None:
+        need = sinkhorn_attn_workspace_bytes(B, H, L, d, W, T, R, dustbin, _dtype_code(Q))
+        workspace = torch.empty(max(need, 16), device=Q.device, dtype=torch.uint8)
     rc = load().sinkhorn_attn_fwd(Q.data_ptr(), K.data_ptr(), V.data_ptr(), O.data_ptr(), UV.data_ptr(),
                                   B, H, L, d, W, T, R, float(eps), int(bool(dustbin)),
-                                  float(dustbin_score), _dtype_code(Q), None, 0, _stream_ptr())
+                                  float(dustbin_score), _dtype_code(Q), workspace.data_ptr(),
+                                  workspace.numel() * workspace.element_size(), _stream_ptr())
     if rc != SKA_OK:
         raise SinkhornAttnError(rc)
     return O, UV

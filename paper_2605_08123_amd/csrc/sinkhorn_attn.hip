@@ -851,7 +851,12 @@ __global__ __launch_bounds__(NTHREADS) void vsweep_kernel(const SweepArgs a)
 // accumulator set, the MFMAs of step sigma+1 fill the other.  The loader therefore stays
 // two steps ahead of the last wavefront: in step sigma it stores the tile that wavefront
 // NW-1 consumes in step sigma+2 (fetched PD steps earlier) and fetches the one for
-// step sigma+PD+2, unless an earlier group already brought that tile in.
+// step sigma+PD+2.
+//
+// The score operand is expected PRESCALED (log2(e)/(eps sqrt d) already folded into the
+// Q-side matrix) and the staged potential y'_t + m' is the MFMA's initial accumulator,
+// so the exponent comes out of the matrix pipe finished: per edge the VALU does one exp2
+// and one add (or FMA with the weight), nothing else.
 template <int D, int MODE, int NW, int FR> struct PRing {
     static constexpr int NT = 64 * NW;
     static constexpr int TPG = NW * FR;
@@ -860,25 +865,28 @@ template <int D, int MODE, int NW, int FR> struct PRing {
     static constexpr int PD = 4;                    // tiles in flight
     static constexpr int AH = PD + 2;               // a tile is fetched AH steps before wavefront NW-1 needs it
     static constexpr int NFILL = LEAD + AH;         // tiles of the first AH steps, fetched up front
-    static constexpr int TILE_BYTES = 32 * D * 2;
+    static constexpr int ROWB = D * 2 + 16;         // padded row: the 32 fragment rows spread over all banks
+    static constexpr int TILE_BYTES = 32 * D * 2;   // in memory
     static constexpr int BPT = TILE_BYTES / NT;     // bytes each thread moves per tile
-    static constexpr int OFF_VY = TILE_BYTES;
+    static constexpr int OFF_VY = 32 * ROWB;
     static constexpr int OFF_VW = OFF_VY + TT * 4;
     static constexpr int SLOT = OFF_VW + TT * 4;
     static constexpr int BYTES = (NSLOT + 1) * SLOT;   // one spare slot for stores nobody reads
     static constexpr int SMAX = NSLOT + FR - 2;     // largest S the ring can roll across groups
     static_assert(BPT == 4 || BPT == 8 || BPT == 16, "tile does not split evenly over the threads");
     static_assert(NFILL <= NSLOT, "initial fill exceeds the ring");
+    static_assert(BYTES <= 160 * 1024, "ring exceeds the LDS of a CU");
 };
 
 template <int BPT> struct PChunk { unsigned int w[BPT / 4]; };
 
-template <int D, int MODE, int NW, int FR, int DBG = 0>
+template <int D, int MODE, int NW, int FR>
 __global__ __launch_bounds__(64 * NW) void psweep_kernel(const SweepArgs a)
 {
     using T = __bf16;
     using RG = PRing<D, MODE, NW, FR>;
     constexpr int NT = RG::NT, BM = NW * FR * 32, TPG = RG::TPG, PD = RG::PD, BPT = RG::BPT, AH = RG::AH;
+    constexpr int KS = D / 16;
     static_assert(MODE == M_LSE || MODE == M_MATVEC, "vector sweeps only");
 
     extern __shared__ __align__(16) unsigned char smem[];
@@ -924,32 +932,32 @@ __global__ __launch_bounds__(64 * NW) void psweep_kernel(const SweepArgs a)
     const int kb = -((W + TT - 1) / TT);             // floor(-W / 32)
     const int ke = (32 * FR - 1 + W) / TT;
     const int S = ke - kb + 1;                       // steps per group; host guarantees TPG <= S <= SMAX
-    const int QUIET = S - TPG;                       // leading steps of a later group that need no new tile
     const int klast = (L - 1) / TT;
     const int total = (gB - gA) * S;
     auto J = [&](int g) { return g * (BM / TT) + kb; };
+    auto slot_of = [&](int k) { return (k & (RG::NSLOT - 1)) * RG::SLOT; };
 
-    // loader: thread -> BPT bytes of the tile, lane -> one element of the vectors
-    const int bo = tid * BPT;
-    const int lrow = bo / (D * 2), lcol = bo % (D * 2);
-    const int lds_off = bf16_chunk_off<D>(lrow, lcol / 16) + (lcol % 16);
+    // loader: thread -> BPT consecutive bytes of the tile (the tile's rows are contiguous in
+    // memory), lane -> one element of the vectors.  Rows outside [0, L) are clamped (their
+    // potentials are stored as -inf, so whatever is fetched there adds nothing).
+    const int lrow = (tid * BPT) / (D * 2), lcol = (tid * BPT) % (D * 2);
+    const int lds_w = lrow * RG::ROWB + lcol;                 // where this thread's bytes go inside a slot
+    const int lds_v = RG::OFF_VY + (tid & (TT - 1)) * 4;
+    // (32-bit unsigned offsets from uniform base pointers: one VGPR of address per load)
     auto ld_issue = [&](PChunk<BPT> &d, float &vy, float &vw, int k) {
-        int t = k * TT + lrow;
-        t = t < 0 ? 0 : (t > L - 1 ? L - 1 : t);
-        d = *reinterpret_cast<const PChunk<BPT> *>(Yb + (long)t * (D * 2) + lcol);
-        int tv = k * TT + (tid & (TT - 1));
-        tv = tv < 0 ? 0 : (tv > L - 1 ? L - 1 : tv);
+        const unsigned t = (unsigned)min(max(k * TT + lrow, 0), L - 1);
+        d = *reinterpret_cast<const PChunk<BPT> *>(Yb + (t * (unsigned)(D * 2) + (unsigned)lcol));
+        const unsigned tv = (unsigned)min(max(k * TT + (tid & (TT - 1)), 0), L - 1);
         vy = ytp[tv];
-        vw = (MODE == M_MATVEC) ? wp[tv] : 0.f;
+        if constexpr (MODE == M_MATVEC) vw = wp[tv];
     };
-    // tiles outside [0, klast] are stored too: their potentials are -inf, so they add nothing
-    auto ld_store = [&](const PChunk<BPT> &d, float vy, float vw, int k, bool wanted = true) {
-        unsigned char *sl = smem + (wanted ? (k & (RG::NSLOT - 1)) : RG::NSLOT) * RG::SLOT;
-        *reinterpret_cast<PChunk<BPT> *>(sl + lds_off) = d;
+    auto ld_store = [&](const PChunk<BPT> &d, float vy, float vw, int k, bool wanted) {
+        unsigned char *sl = smem + (wanted ? slot_of(k) : RG::NSLOT * RG::SLOT);
+        *reinterpret_cast<PChunk<BPT> *>(sl + lds_w) = d;
         if (tid < TT) {
-            const bool live = k >= 0 && k <= klast && k * TT + tid < L;
-            reinterpret_cast<float *>(sl + RG::OFF_VY)[tid] = live ? fmaf(vy, LOG2E, m2) : -INFINITY;
-            if constexpr (MODE == M_MATVEC) reinterpret_cast<float *>(sl + RG::OFF_VW)[tid] = live ? vw : 0.f;
+            const bool live = k >= 0 && k * TT + tid < L;
+            *reinterpret_cast<float *>(sl + lds_v) = live ? fmaf(vy, LOG2E, m2) : -INFINITY;
+            if constexpr (MODE == M_MATVEC) *reinterpret_cast<float *>(sl + lds_v + TT * 4) = live ? vw : 0.f;
         }
     };
 
@@ -962,7 +970,7 @@ __global__ __launch_bounds__(64 * NW) void psweep_kernel(const SweepArgs a)
             int o = g * BM + (wave * FR + f) * 32 + c;
             o = o > L - 1 ? L - 1 : o;
 #pragma unroll
-            for (int s = 0; s < D / 16; ++s) {
+            for (int s = 0; s < KS; ++s) {
                 uint4 z = *reinterpret_cast<const uint4 *>(Xb + (long)o * D + (2 * s + h) * 8);
                 x[f].v[s] = *reinterpret_cast<bf16x8 *>(&z);
             }
@@ -978,69 +986,65 @@ __global__ __launch_bounds__(64 * NW) void psweep_kernel(const SweepArgs a)
 #pragma unroll
         for (int j = 0; j < RG::NFILL; ++j) ld_issue(fd[j], fy[j], fw[j], J(gA) + j);
 #pragma unroll
-        for (int j = 0; j < RG::NFILL; ++j) ld_store(fd[j], fy[j], fw[j], J(gA) + j);
+        for (int j = 0; j < RG::NFILL; ++j) ld_store(fd[j], fy[j], fw[j], J(gA) + j, true);
     }
 
     // The loader is branch-free: every step publishes one staged tile and fetches one, so
     // the compiler can count the loads in flight exactly.  The tile fetched in step sigma
     // is the one wavefront NW-1 consumes in step sigma+AH; when an earlier step already
     // brought it in, the same bytes are stored again; past the last group the fetch is
-    // clamped and its store goes to a spare slot.
-    auto advance = [&](int &g, int &i, int by) {
-        i += by;
-        if (i >= S) { i -= S; ++g; }
-    };
+    // clamped and its store goes to the spare slot.
     PChunk<BPT> sd[PD];
     float sy[PD], sw[PD];
     int sk[PD];            // tile held by each stage
     bool sok[PD];          // somebody will consume it
+    int gl = gA, il = 0;   // the step the loader is fetching for
+#pragma unroll
+    for (int r = 0; r < 2; ++r) { if (++il == S) { il = 0; ++gl; } }
 #pragma unroll
     for (int r = 0; r < PD; ++r) {   // what steps -PD .. -1 would have fetched: tiles of steps 2 .. PD+1
-        int g2 = gA, i2 = 0;
-        advance(g2, i2, r + 2);
-        sok[r] = g2 < gB;
-        sk[r] = J(g2) + RG::LEAD + i2;
+        sok[r] = gl < gB;
+        sk[r] = J(gl) + RG::LEAD + il;
         ld_issue(sd[r], sy[r], sw[r], sk[r]);
+        if (++il == S) { il = 0; ++gl; }
     }
     __syncthreads();
 
+    // per-lane read offsets inside a slot: fragment row c, 16-byte column h (+32 s per k-step);
+    // potentials / weights of register r live at t = 8 (r>>2) + 4 h + (r&3)
+    const int rd_a = c * RG::ROWB + h * 16;
+    const int rd_v = RG::OFF_VY + h * 16;
+
     f32x16 acc[2][FR];
     float sum[FR];
-    // One step inside a wavefront: the MFMAs of the NEXT step's tile (k_next, into `nxt`)
-    // interleaved with the exp2 / reduction work on the finished accumulators `cur` of this
-    // step's tile k.  MASKED applies the band mask to every fragment.
-    auto step_body = [&](auto masked_tag, f32x16 (&nxt)[FR], const f32x16 (&cur)[FR], int g, int k, int k_next) {
+    // One step inside a wavefront: the MFMAs of the NEXT step's tile (slot sn, into `nxt`,
+    // started from that tile's staged potentials) interleaved with the exp2 / reduction work
+    // on the finished accumulators `cur` of this step's tile.  MASKED applies the band mask.
+    auto step_body = [&](auto masked_tag, f32x16 (&nxt)[FR], const f32x16 (&cur)[FR], int o_w, int t0,
+                         const unsigned char *sl, const unsigned char *sn) {
         constexpr bool MASKED = decltype(masked_tag)::value;
-        const unsigned char *sl = smem + (k & (RG::NSLOT - 1)) * RG::SLOT;
-        const unsigned char *sn = smem + (k_next & (RG::NSLOT - 1)) * RG::SLOT;
-        const int t0 = k * TT;
-        const int o_w = g * BM + wave * FR * 32;
-        // LDS reads: next tile's fragments, this tile's potentials (and weights)
-        bf16x8 af[D / 16];
+        bf16x8 af[KS];
 #pragma unroll
-        for (int s = 0; s < D / 16; ++s)
-            af[s] = *reinterpret_cast<const bf16x8 *>(sn + bf16_chunk_off<D>(c, 2 * s + h));
-        float yv[16];
+        for (int s = 0; s < KS; ++s) af[s] = *reinterpret_cast<const bf16x8 *>(sn + rd_a + 32 * s);
+        f32x16 yn;
 #pragma unroll
         for (int q = 0; q < 4; ++q) {
-            float4 v4 = *reinterpret_cast<const float4 *>(sl + RG::OFF_VY + (8 * q + 4 * h) * 4);
-            yv[4 * q + 0] = v4.x; yv[4 * q + 1] = v4.y; yv[4 * q + 2] = v4.z; yv[4 * q + 3] = v4.w;
+            float4 v4 = *reinterpret_cast<const float4 *>(sn + rd_v + 32 * q);
+            yn[4 * q + 0] = v4.x; yn[4 * q + 1] = v4.y; yn[4 * q + 2] = v4.z; yn[4 * q + 3] = v4.w;
         }
         float wv[MODE == M_MATVEC ? 16 : 1];
         if constexpr (MODE == M_MATVEC) {
 #pragma unroll
             for (int q = 0; q < 4; ++q) {
-                float4 w4 = *reinterpret_cast<const float4 *>(sl + RG::OFF_VW + (8 * q + 4 * h) * 4);
+                float4 w4 = *reinterpret_cast<const float4 *>(sl + rd_v + TT * 4 + 32 * q);
                 wv[4 * q + 0] = w4.x; wv[4 * q + 1] = w4.y; wv[4 * q + 2] = w4.z; wv[4 * q + 3] = w4.w;
             }
         }
-        const f32x16 zero = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
 #pragma unroll
-        for (int s = 0; s < D / 16; ++s)
+        for (int s = 0; s < KS; ++s)
 #pragma unroll
             for (int f = 0; f < FR; ++f)
-                if constexpr (DBG & 8) { if (s == 0) nxt[f] = zero; nxt[f][s] += (float)af[s][0] * (float)xf[f].v[s][0]; }
-                else nxt[f] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[s], xf[f].v[s], s == 0 ? zero : nxt[f], 0, 0, 0);
+                nxt[f] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[s], xf[f].v[s], s == 0 ? yn : nxt[f], 0, 0, 0);
 #pragma unroll
         for (int f = 0; f < FR; ++f) {
             // keep (o, t) iff -W <= t - o <= W; with t = t0 + 4h + off_r this is
@@ -1049,23 +1053,27 @@ __global__ __launch_bounds__(64 * NW) void psweep_kernel(const SweepArgs a)
             const unsigned span = 2u * (unsigned)W;
 #pragma unroll
             for (int r = 0; r < 16; ++r) {
-                float e = fmaf(cur[f][r], a.c2, yv[r]);
+                float e = cur[f][r];
                 if constexpr (MASKED) {
                     const int off = 8 * (r >> 2) + (r & 3);
                     if ((unsigned)(off - lo) > span) e = -INFINITY;
                 }
-                const float p = (DBG & 4) ? e : fast_exp2(e);
+                const float p = fast_exp2(e);
                 if constexpr (MODE == M_MATVEC) sum[f] = fmaf(p, wv[r], sum[f]);
                 else sum[f] += p;
             }
         }
-        // issue order: all LDS reads, then one MFMA per dozen VALU instructions, so the
+        // issue order: all LDS reads, then one MFMA per handful of VALU instructions, so the
         // matrix pipe runs underneath the exp2 work of the same wavefront
-        __builtin_amdgcn_sched_group_barrier(0x100, D / 16 + (MODE == M_MATVEC ? 8 : 4), 0);
+        // (the first MFMA waits for the LDS reads, so a batch of exp2 work goes in between)
+        constexpr int NV = (MASKED ? 5 : 2) * 16 * FR;            // VALU instructions of this step, roughly
+        constexpr int HEAD = NV / 3, EACH = (NV - HEAD) / (FR * KS);
+        __builtin_amdgcn_sched_group_barrier(0x100, KS + (MODE == M_MATVEC ? 8 : 4), 0);
+        __builtin_amdgcn_sched_group_barrier(0x002, HEAD, 0);
 #pragma unroll
-        for (int q = 0; q < FR * (D / 16); ++q) {
+        for (int q = 0; q < FR * KS; ++q) {
             __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
-            __builtin_amdgcn_sched_group_barrier(0x002, MASKED ? 20 : 12, 0);
+            __builtin_amdgcn_sched_group_barrier(0x002, EACH, 0);
         }
     };
     auto epilogue = [&](int g) {
@@ -1094,12 +1102,22 @@ __global__ __launch_bounds__(64 * NW) void psweep_kernel(const SweepArgs a)
 #pragma unroll
     for (int f = 0; f < FR; ++f) sum[f] = 0.f;
     int g = gA, i = 0;
+    int k = J(gA) + wave * FR;                       // this wavefront's tile in step (g, i)
     {   // accumulators of step 0
+        const unsigned char *s0 = smem + slot_of(k);
+        f32x16 y0;
 #pragma unroll
-        for (int f = 0; f < FR; ++f)
+        for (int q = 0; q < 4; ++q) {
+            float4 v4 = *reinterpret_cast<const float4 *>(s0 + rd_v + 32 * q);
+            y0[4 * q + 0] = v4.x; y0[4 * q + 1] = v4.y; y0[4 * q + 2] = v4.z; y0[4 * q + 3] = v4.w;
+        }
 #pragma unroll
-            for (int r = 0; r < 16; ++r) acc[0][f][r] = 0.f;
-        tile_dot_multi<D, FR>(smem + ((J(gA) + wave * FR) & (RG::NSLOT - 1)) * RG::SLOT, xf, lane, acc[0]);
+        for (int s = 0; s < KS; ++s) {
+            bf16x8 af = *reinterpret_cast<const bf16x8 *>(s0 + rd_a + 32 * s);
+#pragma unroll
+            for (int f = 0; f < FR; ++f)
+                acc[0][f] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af, xf[f].v[s], s == 0 ? y0 : acc[0][f], 0, 0, 0);
+        }
     }
 
     for (int sg0 = 0; sg0 < total; sg0 += PD) {
@@ -1109,39 +1127,36 @@ __global__ __launch_bounds__(64 * NW) void psweep_kernel(const SweepArgs a)
         // spare slot, their sums are never written and no group end is reached (S > PD).
 #pragma unroll
         for (int r = 0; r < PD; ++r) {
-            {
-                // loader: publish the tile of step sigma+2, fetch the one of step sigma+AH
-                if constexpr (!(DBG & 2)) {
-                    ld_store(sd[r], sy[r], sw[r], sk[r], sok[r]);
-                    int g2 = g, i2 = i;
-                    advance(g2, i2, AH);
-                    sok[r] = g2 < gB;
-                    sk[r] = J(g2) + RG::LEAD + i2;
-                    ld_issue(sd[r], sy[r], sw[r], sk[r]);
-                }
-                const bool last_of_group = (i == S - 1);
-                const int k = J(g) + i + wave * FR;
-                int k_next = k + 1;
-                if (last_of_group) {           // the next step belongs to the next group: its owner rows take over
+            // loader: publish the tile of step sigma+2, fetch the one of step sigma+AH
+            ld_store(sd[r], sy[r], sw[r], sk[r], sok[r]);
+            sok[r] = gl < gB;
+            sk[r] = J(gl) + RG::LEAD + il;
+            ld_issue(sd[r], sy[r], sw[r], sk[r]);
+            if (++il == S) { il = 0; ++gl; }
+
+            const bool last_of_group = (i == S - 1);
+            int k_next = k + 1;
+            if (last_of_group) {           // the next step belongs to the next group: its owner rows take over
 #pragma unroll
-                    for (int f = 0; f < FR; ++f) xf[f] = xn[f];
-                    k_next = J(g + 1) + wave * FR;
-                }
-                const int t0 = k * TT, o_w = g * BM + wave * FR * 32;
-                const bool all_in = (o_w + 32 * FR - 1 - t0 <= W) && (t0 + TT - 1 - o_w <= W);
-                if (all_in) step_body(std::false_type{}, acc[(r + 1) & 1], acc[r & 1], g, k, k_next);
-                else step_body(std::true_type{}, acc[(r + 1) & 1], acc[r & 1], g, k, k_next);
-                if constexpr (!(DBG & 16)) __syncthreads();
-                if (last_of_group) {
-                    epilogue(g);
+                for (int f = 0; f < FR; ++f) xf[f] = xn[f];
+                k_next = J(g + 1) + wave * FR;
+            }
+            const int t0 = k * TT, o_w = g * BM + wave * FR * 32;
+            const unsigned char *sl = smem + slot_of(k), *sn = smem + slot_of(k_next);
+            const bool all_in = (o_w + 32 * FR - 1 - t0 <= W) && (t0 + TT - 1 - o_w <= W);
+            if (all_in) step_body(std::false_type{}, acc[(r + 1) & 1], acc[r & 1], o_w, t0, sl, sn);
+            else step_body(std::true_type{}, acc[(r + 1) & 1], acc[r & 1], o_w, t0, sl, sn);
+            __syncthreads();
+            k = k_next;
+            if (last_of_group) {
+                epilogue(g);
 #pragma unroll
-                    for (int f = 0; f < FR; ++f) sum[f] = 0.f;
-                    i = 0;
-                    ++g;
-                    if (g + 1 < gB) x_issue(xn, g + 1);
-                } else {
-                    ++i;
-                }
+                for (int f = 0; f < FR; ++f) sum[f] = 0.f;
+                i = 0;
+                ++g;
+                if (g + 1 < gB) x_issue(xn, g + 1);
+            } else {
+                ++i;
             }
         }
     }
@@ -1173,6 +1188,19 @@ __global__ void rowdot_kernel(const T *A, const T *Bm, float *g, long gstride, i
         }
     }
     g[n * gstride + o] = acc;
+}
+
+// Qs = bf16(scale * Q): the score scale log2(e)/(eps sqrt d) folded into one operand once,
+// so that no sweep pays a multiply per edge for it.  8 elements per thread.
+__global__ void prescale_kernel(const __bf16 *src, __bf16 *dst, long n8, float scale)
+{
+    long i = (long)blockIdx.x * blockDim.x + threadIdx.x;
+    if (i >= n8) return;
+    uint4 raw = reinterpret_cast<const uint4 *>(src)[i];
+    bf16x8 v = *reinterpret_cast<bf16x8 *>(&raw);
+#pragma unroll
+    for (int e = 0; e < 8; ++e) v[e] = (__bf16)((float)v[e] * scale);
+    reinterpret_cast<uint4 *>(dst)[i] = *reinterpret_cast<uint4 *>(&v);
 }
 
 // Modifier packs of Prop. 2.  rowp = (1, ubar2, alpha, alpha*ubar1); colp = (vbar2, beta,
@@ -1237,9 +1265,33 @@ struct Problem {
 };
 
 constexpr int WS_VECS = 5;   // gu, vb2, ub2, vb1, ub1
-size_t ws_bytes(const Problem &p)
+// bf16 storage: both directions keep a prescaled copy of Q in the workspace
+size_t ws_qs_bytes(const Problem &p)
+{
+    return p.dtype == SKA_BF16 ? (size_t)p.N() * p.L * p.d * 2 : 0;
+}
+size_t ws_vec_bytes(const Problem &p)
 {
     return (size_t)p.N() * p.ldw() * (WS_VECS * sizeof(float) + 2 * sizeof(float4));
+}
+size_t ws_bytes(const Problem &p) { return ws_vec_bytes(p) + ws_qs_bytes(p); }
+
+template <typename T>
+int make_scores_operand(const Problem &p, const void *Q, void *ws_qs, const void **Qs, float *c2, hipStream_t st)
+{
+    const float cs = 1.f / (p.eps * sqrtf((float)p.d));
+    if constexpr (sizeof(T) == 2) {
+        const long n8 = (long)p.N() * p.L * p.d / 8;
+        hipLaunchKernelGGL(prescale_kernel, dim3((unsigned)((n8 + 255) / 256)), dim3(256), 0, st,
+                           reinterpret_cast<const __bf16 *>(Q), reinterpret_cast<__bf16 *>(ws_qs), n8, cs * LOG2E);
+        if (hipGetLastError() != hipSuccess) return SKA_EHIP;
+        *Qs = ws_qs;
+        *c2 = 1.f;
+    } else {
+        *Qs = Q;
+        *c2 = cs * LOG2E;
+    }
+    return SKA_OK;
 }
 
 int check_common(const Problem &p)
@@ -1294,7 +1346,7 @@ int launch_vsweep(SweepArgs a, int N, hipStream_t st)
 int g_ncu = 0;
 
 // Persistent sweep when the ring can roll across groups: TPG <= S <= NSLOT + FR - 1.
-template <int D, int MODE, int NW, int FR, int DBG = 0>
+template <int D, int MODE, int NW, int FR>
 int launch_psweep(SweepArgs a, int N, hipStream_t st, bool *taken)
 {
     using RG = PRing<D, MODE, NW, FR>;
@@ -1321,12 +1373,12 @@ int launch_psweep(SweepArgs a, int N, hipStream_t st, bool *taken)
     const int chunk = (a.nb_total + 7) / 8;
     static bool raised = false;
     if (!raised) {
-        if (hipFuncSetAttribute(reinterpret_cast<const void *>(&psweep_kernel<D, MODE, NW, FR, DBG>),
+        if (hipFuncSetAttribute(reinterpret_cast<const void *>(&psweep_kernel<D, MODE, NW, FR>),
                                 hipFuncAttributeMaxDynamicSharedMemorySize, RG::BYTES) != hipSuccess)
             return SKA_EHIP;
         raised = true;
     }
-    hipLaunchKernelGGL((psweep_kernel<D, MODE, NW, FR, DBG>), dim3(chunk * 8), dim3(RG::NT), RG::BYTES, st, a);
+    hipLaunchKernelGGL((psweep_kernel<D, MODE, NW, FR>), dim3(chunk * 8), dim3(RG::NT), RG::BYTES, st, a);
     *taken = true;
     return hipGetLastError() == hipSuccess ? SKA_OK : SKA_EHIP;
 }
@@ -1344,19 +1396,8 @@ template <typename T, int D> int sweep(int mode, const SweepArgs &a, int N, hipS
         if constexpr (sizeof(T) == 2 && D == 64) {
             if (g_variant == 3) {
                 bool taken = false;
-                int rc;
-                if (mode == M_LSE) {
-                    switch (a.dbg) {
-                    case 2: rc = launch_psweep<D, M_LSE, 8, 2, 2>(a, N, st, &taken); break;
-                    case 4: rc = launch_psweep<D, M_LSE, 8, 2, 4>(a, N, st, &taken); break;
-                    case 8: rc = launch_psweep<D, M_LSE, 8, 2, 8>(a, N, st, &taken); break;
-                    case 12: rc = launch_psweep<D, M_LSE, 8, 2, 12>(a, N, st, &taken); break;
-                    case 16: rc = launch_psweep<D, M_LSE, 8, 2, 16>(a, N, st, &taken); break;
-                    case 18: rc = launch_psweep<D, M_LSE, 8, 2, 18>(a, N, st, &taken); break;
-                    case 30: rc = launch_psweep<D, M_LSE, 8, 2, 30>(a, N, st, &taken); break;
-                    default: rc = launch_psweep<D, M_LSE, 8, 2>(a, N, st, &taken);
-                    }
-                } else rc = launch_psweep<D, M_MATVEC, 8, 2>(a, N, st, &taken);
+                int rc = mode == M_LSE ? launch_psweep<D, M_LSE, 8, 2>(a, N, st, &taken)
+                                       : launch_psweep<D, M_MATVEC, 8, 2>(a, N, st, &taken);
                 if (rc != SKA_OK || taken) return rc;
             }
         }
@@ -1394,9 +1435,13 @@ int g_prof_n = 0;
     } while (0)
 
 template <typename T, int D>
-int fwd_impl(const Problem &p, const void *Q, const void *K, const void *V, void *O, float *UV,
-             hipStream_t st)
+int fwd_impl(const Problem &p, const void *Qin, const void *K, const void *V, void *O, float *UV,
+             void *ws, hipStream_t st)
 {
+    // Q below is the score operand: for bf16 storage the prescaled copy, with c2 = 1
+    const void *Q = nullptr;
+    float c2 = 0.f;
+    SKA_TRY((make_scores_operand<T>(p, Qin, ws, &Q, &c2, st)));
     const int N = p.N(), L = p.L, Lp = p.Lp();
     const long us = 6L * Lp;
     auto vec = [&](int k) { return Vec{UV + (long)k * Lp, us}; };
@@ -1404,7 +1449,7 @@ int fwd_impl(const Problem &p, const void *Q, const void *K, const void *V, void
     SweepArgs base{};
     base.L = L; base.W = p.W < L ? p.W : L;   // |i-j| <= L-1 always: W >= L is the dense problem
     base.cs = 1.f / (p.eps * sqrtf((float)p.d));
-    base.c2 = base.cs * LOG2E;
+    base.c2 = c2;
     base.dustbin = p.dustbin; base.sdb2 = p.sdb * LOG2E;
 
     // u0 = v0 = 0: the base solve starts from v = 0
@@ -1453,10 +1498,15 @@ int fwd_impl(const Problem &p, const void *Q, const void *K, const void *V, void
 }
 
 template <typename T, int D>
-int bwd_impl(const Problem &p, const void *Q, const void *K, const void *V, const void *O,
+int bwd_impl(const Problem &p, const void *Qin, const void *K, const void *V, const void *O,
              const void *G, const float *UV, void *dQ, void *dK, void *dV, float *eta0, void *ws,
              hipStream_t st)
 {
+    // Q below is the score operand (bf16 storage: prescaled copy at the end of the workspace,
+    // c2 = 1); it also serves as the payload of the dK sweep, whose output scale absorbs it
+    const void *Q = nullptr;
+    float c2 = 0.f;
+    SKA_TRY((make_scores_operand<T>(p, Qin, reinterpret_cast<unsigned char *>(ws) + ws_vec_bytes(p), &Q, &c2, st)));
     const int N = p.N(), L = p.L, Lp = p.Lp();
     const long us = 6L * Lp, ldw = p.ldw();
     auto uv = [&](int k) { return Vec{UV + (long)k * Lp, us}; };
@@ -1471,7 +1521,7 @@ int bwd_impl(const Problem &p, const void *Q, const void *K, const void *V, cons
     SweepArgs base{};
     base.L = L; base.W = p.W < L ? p.W : L;   // |i-j| <= L-1 always: W >= L is the dense problem
     base.cs = 1.f / (p.eps * sqrtf((float)p.d));
-    base.c2 = base.cs * LOG2E;
+    base.c2 = c2;
     base.dustbin = p.dustbin; base.sdb2 = p.sdb * LOG2E;
     const dim3 vgrid((Lp + 255) / 256, N);
 
@@ -1522,6 +1572,8 @@ int bwd_impl(const Problem &p, const void *Q, const void *K, const void *V, cons
         SweepArgs a = base;
         a.X = K; a.Y = Q; a.A = V; a.Bm = G; a.out_mat = dK; a.xs = uv(5); a.yt = uv(4);
         a.po = colp; a.qt = rowp; a.ldp = ldw;
+        // payload rows are Qs = (cs log2 e) Q when prescaled: cs sum Sbar^T Q = ln 2 sum Sbar^T Qs
+        if (sizeof(T) == 2) a.cs = LN2;
         SKA_TRY((sweep<T, D>(M_FINAL, a, N, st)));
     }
     return SKA_OK;
@@ -1543,13 +1595,14 @@ int sinkhorn_attn_fwd(const void *Q, const void *K, const void *V, void *O, floa
                       int d, int W, int T, int R, float eps, int dustbin, float dustbin_score, int dtype,
                       void *workspace, size_t workspace_bytes, void *stream)
 {
-    (void)workspace; (void)workspace_bytes;
     Problem p{B, H, L, d, W, T, R, dustbin ? 1 : 0, dtype, eps, dustbin_score};
     if (!Q || !K || !V || !O || !UV) return SKA_EINVAL;
     int rc = check_common(p);
     if (rc != SKA_OK) return rc;
+    if (ws_qs_bytes(p) && (!workspace || workspace_bytes < ws_qs_bytes(p))) return SKA_EWORKSPACE;
+    if (reinterpret_cast<uintptr_t>(workspace) & 15) return SKA_EINVAL;
     hipStream_t st = reinterpret_cast<hipStream_t>(stream);
-#define SKA_FWD(TT_, DD_) return fwd_impl<TT_, DD_>(p, Q, K, V, O, UV, st)
+#define SKA_FWD(TT_, DD_) return fwd_impl<TT_, DD_>(p, Q, K, V, O, UV, workspace, st)
     if (dtype == SKA_F32) {
         if (d == 32) SKA_FWD(float, 32);
         if (d == 64) SKA_FWD(float, 64);

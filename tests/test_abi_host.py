@@ -69,6 +69,7 @@ def test_argument_errors_are_reported_before_any_launch():
         assert _fwd(lib, **bad) == binding.SKA_EUNSUPPORTED, bad
         assert _bwd(lib, **bad) == binding.SKA_EUNSUPPORTED, bad
     assert _bwd(lib, ws=None, ws_bytes=0) == binding.SKA_EWORKSPACE
+    assert _fwd(lib, dtype=1) == binding.SKA_EWORKSPACE          # bf16 forward needs its scratch
     need = binding.sinkhorn_attn_workspace_bytes(1, 1, 64, 32, 4, 2, dtype=0)
     assert _bwd(lib, ws=ctypes.c_void_p(1 << 20), ws_bytes=need - 1) == binding.SKA_EWORKSPACE
     assert _bwd(lib, ws=ctypes.c_void_p((1 << 20) + 4), ws_bytes=need) == binding.SKA_EINVAL

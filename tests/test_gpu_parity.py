@@ -52,7 +52,9 @@ def check(w: Workload, seed=None, want_eta0=False, uv_atol=None):
     print("   rel-L2:", {k: f"{v:.2e}" for k, v in errs.items()}, flush=True)
     # potentials: both sides iterate the same ungauged map from v = 0, so the raw
     # vectors agree; compared through the gauge-free sums u^(t) + v^(t)
-    uv_atol = uv_atol or (2e-4 if w.dtype == "f32" else 2e-3)
+    # (bf16 storage: the score scale is folded into a bf16 copy of Q, which perturbs every
+    # score by a relative 2^-9; the potentials absorb that as an absolute error ~1e-2)
+    uv_atol = uv_atol or (2e-4 if w.dtype == "f32" else 2e-2)
     for t in ((1, 2) if w.T == 0 else (0, 1, 2)):
         s_got = got["UV"][:, :, 2 * t] + got["UV"][:, :, 2 * t + 1]
         s_ref = ref["UV"][:, :, 2 * t] + ref["UV"][:, :, 2 * t + 1]
