@@ -53,7 +53,10 @@ def main() -> int:
     ap.add_argument("--warmup", type=int, default=2)
     ap.add_argument("--workload", default="paper")
     ap.add_argument("--no-cpu-baseline", action="store_true")
-    ap.add_argument("--cpu-tokens", type=int, default=65536)
+    ap.add_argument("--cpu-tokens", type=int, default=262144)
+    ap.add_argument("--calibrate-copy", action="store_true",
+                    help="also run three 256 MiB device copies (a known-size kernel to scale "
+                         "rocprofv3 FETCH_SIZE / WRITE_SIZE readings by)")
     args = ap.parse_args()
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
         print("bench.py: this build runs on exactly one GPU (independent (batch, head) problems shard "
@@ -85,6 +88,12 @@ def main() -> int:
         ska.sinkhorn_attn_bwd(Q, K, V, O, G, UV, w.W, w.T, w.R, w.eps, w.dustbin, w.dustbin_score,
                               workspace=wsp, dQ=dQ, dK=dK, dV=dV)
 
+    if args.calibrate_copy:
+        src = torch.empty(256 << 20, device=dev, dtype=torch.uint8).random_(0, 255)
+        dst = torch.empty_like(src)
+        for _ in range(3):
+            dst.copy_(src)
+        torch.cuda.synchronize()
     for _ in range(args.warmup):
         step()
     torch.cuda.synchronize()
