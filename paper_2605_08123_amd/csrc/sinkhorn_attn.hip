@@ -74,8 +74,6 @@ struct SweepArgs {
     float cs;         // 1 / (eps sqrt d)
     int dustbin;
     float sdb2;       // dustbin score * log2(e)
-    int dbg;          // development knob
-    int gpb;          // persistent sweeps: groups of owner rows per workgroup
     int nbp;          // workgroups per problem
     int nb_total;
 };
@@ -659,6 +657,7 @@ __global__ __launch_bounds__(NTHREADS) void vsweep_kernel(const SweepArgs a)
 {
     using TL = Tile<T, D>;
     using RG = VRing<T, D, MODE, FR>;
+    constexpr bool PRE = (sizeof(T) == 2);   // bf16 storage: the score operand is prescaled, c2 == 1
     constexpr int BM = NWAVES * FR * 32;
     static_assert(MODE == M_LSE || MODE == M_MATVEC, "vector sweeps only");
 
@@ -682,26 +681,15 @@ __global__ __launch_bounds__(NTHREADS) void vsweep_kernel(const SweepArgs a)
     const float *xsp = a.xs.p + n * a.xs.stride;
     const float *wp = (MODE == M_MATVEC) ? a.w.p + n * a.w.stride : nullptr;
 
-    float mblk;
-    {
-        float m = -INFINITY;
-        for (int i = tid; i < BM; i += NTHREADS)
-            if (o_blk + i < L) m = fmaxf(m, xsp[o_blk + i]);
-#pragma unroll
-        for (int s = 32; s >= 1; s >>= 1) m = fmaxf(m, __shfl_xor(m, s));
-        if (lane == 0) red[wave] = m;
-        __syncthreads();
-        mblk = fmaxf(fmaxf(red[0], red[1]), fmaxf(red[2], red[3]));
-    }
-    const float m2 = mblk * LOG2E;
 
+    float mblk, m2 = 0.f;   // stabiliser: set once the prologue loads are in flight
     OwnerFrag<T, D> xf[FR];
     int o_frag[FR];
     float sum[FR];
 #pragma unroll
     for (int f = 0; f < FR; ++f) {
         o_frag[f] = o_blk + (wave * FR + f) * 32;
-        xf[f].load(Xb, o_frag[f] + c, L, h);
+        xf[f].load(Xb, min(o_frag[f] + c, L - 1), L, h);   // clamped: rows beyond L are never written
         sum[f] = 0.f;
     }
 
@@ -739,45 +727,57 @@ __global__ __launch_bounds__(NTHREADS) void vsweep_kernel(const SweepArgs a)
         }
     };
 
-    // fill the ring with the tiles of step 0: every load is issued before the first store
+    // fill the ring with the tiles of step 0.  Everything the prologue needs from memory is
+    // requested before anything is waited for: owner rows (above), the first tiles, and the
+    // owner-side potentials the stabiliser is taken from.
+    Inflight fill[RG::LEAD + 1];
+#pragma unroll
+    for (int j = 0; j <= RG::LEAD; ++j) g_load(fill[j], kbase + j);
     {
-        Inflight fill[RG::LEAD + 1];
+        float m = -INFINITY;
+        for (int i = tid; i < BM; i += NTHREADS) m = fmaxf(m, xsp[min(o_blk + i, L - 1)]);   // clamped repeats are harmless
 #pragma unroll
-        for (int j = 0; j <= RG::LEAD; ++j) g_load(fill[j], kbase + j);
-#pragma unroll
-        for (int j = 0; j <= RG::LEAD; ++j) s_store(fill[j], j);
+        for (int s = 32; s >= 1; s >>= 1) m = fmaxf(m, __shfl_xor(m, s));
+        if (lane == 0) red[wave] = m;
+        __syncthreads();
+        mblk = fmaxf(fmaxf(red[0], red[1]), fmaxf(red[2], red[3]));
     }
+    m2 = mblk * LOG2E;
+#pragma unroll
+    for (int j = 0; j <= RG::LEAD; ++j) s_store(fill[j], j);
     __syncthreads();
     Inflight nxt;
 
     for (int s = 0; s < S; ++s) {
         const int jnew = s + 1 + RG::LEAD;
         const bool more = (s + 1 < S);
-        if (more && !(a.dbg & 2)) g_load(nxt, kbase + jnew);
+        if (more) g_load(nxt, kbase + jnew);
 
         const int j = s + wave * FR;
         const int k = kbase + j;
-        if (k >= 0 && k <= klast && !(a.dbg & 1)) {
+        if (k >= 0 && k <= klast) {
             const unsigned char *sl = smem + (j & (RG::NSLOT - 1)) * RG::SLOT;
             const int t0 = k * TT;
             bool use[FR], interior[FR];
             f32x16 acc[FR];
-#pragma unroll
-            for (int f = 0; f < FR; ++f) {
-                const int of = o_frag[f];
-                use[f] = !(of >= L || t0 + TT - 1 < of - W || t0 > of + 31 + W);
-                interior[f] = (of + 31 - t0 <= W) && (t0 + TT - 1 - of <= W);
-#pragma unroll
-                for (int r = 0; r < 16; ++r) acc[f][r] = 0.f;
-            }
-            tile_dot_multi<D, FR>(sl, xf, lane, acc);   // unconditional: an unused tile costs MFMA only
-
+            // the staged potentials (c2-scaled away: see `prescaled`) are the MFMA's initial
+            // accumulator when the score operand carries the scale already
             float yv[16];
 #pragma unroll
             for (int q = 0; q < 4; ++q) {
                 float4 v4 = *reinterpret_cast<const float4 *>(sl + RG::OFF_VY + (8 * q + 4 * h) * 4);
                 yv[4 * q + 0] = v4.x; yv[4 * q + 1] = v4.y; yv[4 * q + 2] = v4.z; yv[4 * q + 3] = v4.w;
             }
+#pragma unroll
+            for (int f = 0; f < FR; ++f) {
+                const int of = o_frag[f];
+                use[f] = !(of >= L || t0 + TT - 1 < of - W || t0 > of + 31 + W);
+                interior[f] = (of + 31 - t0 <= W) && (t0 + TT - 1 - of <= W);
+#pragma unroll
+                for (int r = 0; r < 16; ++r) acc[f][r] = PRE ? yv[r] : 0.f;
+            }
+            tile_dot_multi<D, FR>(sl, xf, lane, acc);   // unconditional: an unused tile costs MFMA only
+
             float wv[MODE == M_MATVEC ? 16 : 1];
             if constexpr (MODE == M_MATVEC) {
 #pragma unroll
@@ -791,7 +791,7 @@ __global__ __launch_bounds__(NTHREADS) void vsweep_kernel(const SweepArgs a)
                 if (!use[f]) continue;
                 float e[16];
 #pragma unroll
-                for (int r = 0; r < 16; ++r) e[r] = fmaf(acc[f][r], a.c2, yv[r]);
+                for (int r = 0; r < 16; ++r) e[r] = PRE ? acc[f][r] : fmaf(acc[f][r], a.c2, yv[r]);
                 if (!interior[f]) {
                     // keep (o, t) iff -W <= t - o <= W; with t = t0 + 4h + off_r this is
                     // 0 <= off_r - lo <= 2W for lo = o - W - t0 - 4h: one unsigned compare
@@ -836,327 +836,300 @@ __global__ __launch_bounds__(NTHREADS) void vsweep_kernel(const SweepArgs a)
     }
 }
 
-// ------------------------------------------------------------------ persistent vector sweeps
-// Same skewed ring, but a workgroup of NW wavefronts walks several consecutive groups
-// of BM = 32 FR NW owner rows.  Consecutive groups need almost the same other-side
-// tiles (each group brings in exactly TPG = FR NW new ones), so the ring keeps rolling
-// across groups: every other-side tile is fetched once per workgroup, the fetches are
-// spread over the steps (PD tiles in flight in registers) and the next group's owner
-// rows are fetched while the current group computes, so HBM streaming overlaps the
-// exp2/MFMA work instead of alternating with it.
-//
-// Steps are numbered globally, sigma = (g - gA) S + i; in step (g, i) wavefront w
-// consumes tile J(g) + i + FR w, J(g) = g BM/32 + floor(-W/32).  Inside a wavefront the
-// work is software-pipelined by one step: while the VALU part of step sigma runs on one
-// accumulator set, the MFMAs of step sigma+1 fill the other.  The loader therefore stays
-// two steps ahead of the last wavefront: in step sigma it stores the tile that wavefront
-// NW-1 consumes in step sigma+2 (fetched PD steps earlier) and fetches the one for
-// step sigma+PD+2.
-//
-// The score operand is expected PRESCALED (log2(e)/(eps sqrt d) already folded into the
-// Q-side matrix) and the staged potential y'_t + m' is the MFMA's initial accumulator,
-// so the exponent comes out of the matrix pipe finished: per edge the VALU does one exp2
-// and one add (or FMA with the weight), nothing else.
-template <int D, int MODE, int NW, int FR> struct PRing {
-    static constexpr int NT = 64 * NW;
-    static constexpr int TPG = NW * FR;
-    static constexpr int LEAD = FR * (NW - 1);
-    static constexpr int NSLOT = 32;
-    static constexpr int PD = 4;                    // tiles in flight
-    static constexpr int AH = PD + 2;               // a tile is fetched AH steps before wavefront NW-1 needs it
-    static constexpr int NFILL = LEAD + AH;         // tiles of the first AH steps, fetched up front
-    static constexpr int ROWB = D * 2 + 16;         // padded row: the 32 fragment rows spread over all banks
-    static constexpr int TILE_BYTES = 32 * D * 2;   // in memory
-    static constexpr int BPT = TILE_BYTES / NT;     // bytes each thread moves per tile
-    static constexpr int OFF_VY = 32 * ROWB;
-    static constexpr int OFF_VW = OFF_VY + TT * 4;
-    static constexpr int SLOT = OFF_VW + TT * 4;
-    static constexpr int BYTES = (NSLOT + 1) * SLOT;   // one spare slot for stores nobody reads
-    static constexpr int SMAX = NSLOT + FR - 2;     // largest S the ring can roll across groups
-    static_assert(BPT == 4 || BPT == 8 || BPT == 16, "tile does not split evenly over the threads");
-    static_assert(NFILL <= NSLOT, "initial fill exceeds the ring");
-    static_assert(BYTES <= 160 * 1024, "ring exceeds the LDS of a CU");
+// ------------------------------------------------------------------ matrix sweeps (bf16)
+// Output map / dV (M_APPLY) and the one-reference final sweep (M_FINAL) on the same skewed
+// ring: wavefront w owns 32 rows, four wavefronts per workgroup, the tile of step s for
+// wavefront w is kbase + s + w.  A ring slot holds the other-side score rows, the second
+// streamed matrix (payload for M_APPLY, the other-side factor of Z for M_FINAL), the staged
+// potentials and, for M_FINAL, the other-side modifier pack.  Tiles are row-major in LDS
+// with 16 bytes of padding per row; the second product needs its streamed operand with the
+// band index contiguous, which the transposing LDS read (ds_read_b64_tr_b16) delivers from
+// the row-major tile: within 16 lanes, lane i receives element (i & 3) of the 8-byte pieces
+// addressed by lanes (i >> 2) + 4 e, e = 0..3.
+template <int D, int MODE, int FR> struct MRing {
+    static constexpr int LEAD = FR * (NWAVES - 1);
+    static constexpr int NSLOT = 8;
+    static constexpr int ROWB = D * 2 + 16;
+    static constexpr int TILE = 32 * ROWB;
+    static constexpr int OFF_Y = 0;
+    static constexpr int OFF_B = TILE;                 // payload (M_APPLY) or Z factor (M_FINAL)
+    static constexpr int OFF_VY = 2 * TILE;
+    static constexpr int OFF_VQ = OFF_VY + TT * 4;
+    static constexpr int SLOT = OFF_VQ + (MODE == M_FINAL ? TT * 16 : 0);
+    static constexpr int BYTES = NSLOT * SLOT;
+    static constexpr int CHUNKS = 32 * D * 2 / 16;     // 16-byte pieces of a tile in memory
+    static constexpr int CPT = (CHUNKS + NTHREADS - 1) / NTHREADS;
+    static constexpr int CPR = D * 2 / 16;
+    static_assert(LEAD + 2 <= NSLOT, "ring too small for the skew");
 };
 
-template <int BPT> struct PChunk { unsigned int w[BPT / 4]; };
-
-template <int D, int MODE, int NW, int FR>
-__global__ __launch_bounds__(64 * NW) void psweep_kernel(const SweepArgs a)
+template <int D, int MODE, int FR>
+__global__ __launch_bounds__(NTHREADS) void msweep_kernel(const SweepArgs a)
 {
     using T = __bf16;
-    using RG = PRing<D, MODE, NW, FR>;
-    constexpr int NT = RG::NT, BM = NW * FR * 32, TPG = RG::TPG, PD = RG::PD, BPT = RG::BPT, AH = RG::AH;
-    constexpr int KS = D / 16;
-    static_assert(MODE == M_LSE || MODE == M_MATVEC, "vector sweeps only");
+    using RG = MRing<D, MODE, FR>;
+    constexpr int BM = NWAVES * FR * 32, KS = D / 16;
+    static_assert(MODE == M_APPLY || MODE == M_FINAL, "matrix sweeps only");
 
     extern __shared__ __align__(16) unsigned char smem[];
-    __shared__ float red[NW];
+    __shared__ float red[NWAVES];
 
     const int chunk = (a.nb_total + 7) >> 3;
     const int lb = (blockIdx.x & 7) * chunk + (blockIdx.x >> 3);
     if (lb >= a.nb_total) return;
-    const int L = a.L, W = a.W;
-    const int GP = (L + BM - 1) / BM;               // groups per problem
     const int n = lb / a.nbp;
-    const int gA = (lb % a.nbp) * a.gpb;
-    const int gB = (gA + a.gpb < GP) ? gA + a.gpb : GP;
-    if (gA >= GP) return;
+    const int o_blk = (lb % a.nbp) * BM;
 
     const int tid = threadIdx.x, lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int c = lane & 31, h = lane >> 5;
+    const int L = a.L, W = a.W;
     const long moff = (long)n * L * D;
     const T *Xb = reinterpret_cast<const T *>(a.X) + moff;
     const unsigned char *Yb = reinterpret_cast<const unsigned char *>(reinterpret_cast<const T *>(a.Y) + moff);
+    const unsigned char *Bb = reinterpret_cast<const unsigned char *>(
+        reinterpret_cast<const T *>(MODE == M_FINAL ? a.Bm : a.Pay) + moff);
     const float *ytp = a.yt.p + n * a.yt.stride;
     const float *xsp = a.xs.p + n * a.xs.stride;
-    const float *wp = (MODE == M_MATVEC) ? a.w.p + n * a.w.stride : nullptr;
 
-    // one stabiliser for all rows this workgroup owns (the staged potentials in the ring
-    // carry it, and the ring outlives a group)
-    float mblk;
+    float mblk, m2;
     {
         float m = -INFINITY;
-        const int r1 = (gB * BM < L) ? gB * BM : L;
-        for (int i = gA * BM + tid; i < r1; i += NT) m = fmaxf(m, xsp[i]);
+        for (int i = tid; i < BM; i += NTHREADS) m = fmaxf(m, xsp[min(o_blk + i, L - 1)]);
 #pragma unroll
         for (int s = 32; s >= 1; s >>= 1) m = fmaxf(m, __shfl_xor(m, s));
         if (lane == 0) red[wave] = m;
         __syncthreads();
-        mblk = red[0];
-#pragma unroll
-        for (int i = 1; i < NW; ++i) mblk = fmaxf(mblk, red[i]);
+        mblk = fmaxf(fmaxf(red[0], red[1]), fmaxf(red[2], red[3]));
     }
-    const float m2 = mblk * LOG2E;
+    m2 = mblk * LOG2E;
 
-    // tile bookkeeping (all scalar)
-    const int kb = -((W + TT - 1) / TT);             // floor(-W / 32)
-    const int ke = (32 * FR - 1 + W) / TT;
-    const int S = ke - kb + 1;                       // steps per group; host guarantees TPG <= S <= SMAX
-    const int klast = (L - 1) / TT;
-    const int total = (gB - gA) * S;
-    auto J = [&](int g) { return g * (BM / TT) + kb; };
-    auto slot_of = [&](int k) { return (k & (RG::NSLOT - 1)) * RG::SLOT; };
-
-    // loader: thread -> BPT consecutive bytes of the tile (the tile's rows are contiguous in
-    // memory), lane -> one element of the vectors.  Rows outside [0, L) are clamped (their
-    // potentials are stored as -inf, so whatever is fetched there adds nothing).
-    const int lrow = (tid * BPT) / (D * 2), lcol = (tid * BPT) % (D * 2);
-    const int lds_w = lrow * RG::ROWB + lcol;                 // where this thread's bytes go inside a slot
-    const int lds_v = RG::OFF_VY + (tid & (TT - 1)) * 4;
-    // (32-bit unsigned offsets from uniform base pointers: one VGPR of address per load)
-    auto ld_issue = [&](PChunk<BPT> &d, float &vy, float &vw, int k) {
-        const unsigned t = (unsigned)min(max(k * TT + lrow, 0), L - 1);
-        d = *reinterpret_cast<const PChunk<BPT> *>(Yb + (t * (unsigned)(D * 2) + (unsigned)lcol));
-        const unsigned tv = (unsigned)min(max(k * TT + (tid & (TT - 1)), 0), L - 1);
-        vy = ytp[tv];
-        if constexpr (MODE == M_MATVEC) vw = wp[tv];
-    };
-    auto ld_store = [&](const PChunk<BPT> &d, float vy, float vw, int k, bool wanted) {
-        unsigned char *sl = smem + (wanted ? slot_of(k) : RG::NSLOT * RG::SLOT);
-        *reinterpret_cast<PChunk<BPT> *>(sl + lds_w) = d;
-        if (tid < TT) {
-            const bool live = k >= 0 && k * TT + tid < L;
-            *reinterpret_cast<float *>(sl + lds_v) = live ? fmaf(vy, LOG2E, m2) : -INFINITY;
-            if constexpr (MODE == M_MATVEC) *reinterpret_cast<float *>(sl + lds_v + TT * 4) = live ? vw : 0.f;
-        }
-    };
-
-    // owner rows: current group in xf, next group arriving in xn (rows beyond L are clamped:
-    // finite garbage in columns that are never written)
-    OwnerFrag<T, D> xf[FR], xn[FR];
-    auto x_issue = [&](OwnerFrag<T, D> (&x)[FR], int g) {
+    // owner side: score rows, and for M_FINAL the owner factor of Z and the modifier pack.
+    // Rows beyond L are clamped: they compute garbage that is never stored.
+    const int o_w = o_blk + wave * FR * 32;
+    OwnerFrag<T, D> xf[FR], af[MODE == M_FINAL ? FR : 1];
+    float4 pof[FR];
+    f32x16 outm[FR][D / 32];
 #pragma unroll
-        for (int f = 0; f < FR; ++f) {
-            int o = g * BM + (wave * FR + f) * 32 + c;
-            o = o > L - 1 ? L - 1 : o;
-#pragma unroll
-            for (int s = 0; s < KS; ++s) {
-                uint4 z = *reinterpret_cast<const uint4 *>(Xb + (long)o * D + (2 * s + h) * 8);
-                x[f].v[s] = *reinterpret_cast<bf16x8 *>(&z);
-            }
-        }
-    };
-    x_issue(xf, gA);
-    if (gA + 1 < gB) x_issue(xn, gA + 1);
-
-    // initial fill: everything the first AH steps consume
-    {
-        PChunk<BPT> fd[RG::NFILL];
-        float fy[RG::NFILL], fw[RG::NFILL];
-#pragma unroll
-        for (int j = 0; j < RG::NFILL; ++j) ld_issue(fd[j], fy[j], fw[j], J(gA) + j);
-#pragma unroll
-        for (int j = 0; j < RG::NFILL; ++j) ld_store(fd[j], fy[j], fw[j], J(gA) + j, true);
-    }
-
-    // The loader is branch-free: every step publishes one staged tile and fetches one, so
-    // the compiler can count the loads in flight exactly.  The tile fetched in step sigma
-    // is the one wavefront NW-1 consumes in step sigma+AH; when an earlier step already
-    // brought it in, the same bytes are stored again; past the last group the fetch is
-    // clamped and its store goes to the spare slot.
-    PChunk<BPT> sd[PD];
-    float sy[PD], sw[PD];
-    int sk[PD];            // tile held by each stage
-    bool sok[PD];          // somebody will consume it
-    int gl = gA, il = 0;   // the step the loader is fetching for
-#pragma unroll
-    for (int r = 0; r < 2; ++r) { if (++il == S) { il = 0; ++gl; } }
-#pragma unroll
-    for (int r = 0; r < PD; ++r) {   // what steps -PD .. -1 would have fetched: tiles of steps 2 .. PD+1
-        sok[r] = gl < gB;
-        sk[r] = J(gl) + RG::LEAD + il;
-        ld_issue(sd[r], sy[r], sw[r], sk[r]);
-        if (++il == S) { il = 0; ++gl; }
-    }
-    __syncthreads();
-
-    // per-lane read offsets inside a slot: fragment row c, 16-byte column h (+32 s per k-step);
-    // potentials / weights of register r live at t = 8 (r>>2) + 4 h + (r&3)
-    const int rd_a = c * RG::ROWB + h * 16;
-    const int rd_v = RG::OFF_VY + h * 16;
-
-    f32x16 acc[2][FR];
-    float sum[FR];
-    // One step inside a wavefront: the MFMAs of the NEXT step's tile (slot sn, into `nxt`,
-    // started from that tile's staged potentials) interleaved with the exp2 / reduction work
-    // on the finished accumulators `cur` of this step's tile.  MASKED applies the band mask.
-    auto step_body = [&](auto masked_tag, f32x16 (&nxt)[FR], const f32x16 (&cur)[FR], int o_w, int t0,
-                         const unsigned char *sl, const unsigned char *sn) {
-        constexpr bool MASKED = decltype(masked_tag)::value;
-        bf16x8 af[KS];
-#pragma unroll
-        for (int s = 0; s < KS; ++s) af[s] = *reinterpret_cast<const bf16x8 *>(sn + rd_a + 32 * s);
-        f32x16 yn;
-#pragma unroll
-        for (int q = 0; q < 4; ++q) {
-            float4 v4 = *reinterpret_cast<const float4 *>(sn + rd_v + 32 * q);
-            yn[4 * q + 0] = v4.x; yn[4 * q + 1] = v4.y; yn[4 * q + 2] = v4.z; yn[4 * q + 3] = v4.w;
-        }
-        float wv[MODE == M_MATVEC ? 16 : 1];
-        if constexpr (MODE == M_MATVEC) {
-#pragma unroll
-            for (int q = 0; q < 4; ++q) {
-                float4 w4 = *reinterpret_cast<const float4 *>(sl + rd_v + TT * 4 + 32 * q);
-                wv[4 * q + 0] = w4.x; wv[4 * q + 1] = w4.y; wv[4 * q + 2] = w4.z; wv[4 * q + 3] = w4.w;
-            }
-        }
-#pragma unroll
-        for (int s = 0; s < KS; ++s)
-#pragma unroll
-            for (int f = 0; f < FR; ++f)
-                nxt[f] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[s], xf[f].v[s], s == 0 ? yn : nxt[f], 0, 0, 0);
-#pragma unroll
-        for (int f = 0; f < FR; ++f) {
-            // keep (o, t) iff -W <= t - o <= W; with t = t0 + 4h + off_r this is
-            // 0 <= off_r - lo <= 2W for lo = o - W - t0 - 4h: one unsigned compare
-            const int lo = o_w + 32 * f + c - W - t0 - 4 * h;
-            const unsigned span = 2u * (unsigned)W;
-#pragma unroll
-            for (int r = 0; r < 16; ++r) {
-                float e = cur[f][r];
-                if constexpr (MASKED) {
-                    const int off = 8 * (r >> 2) + (r & 3);
-                    if ((unsigned)(off - lo) > span) e = -INFINITY;
-                }
-                const float p = fast_exp2(e);
-                if constexpr (MODE == M_MATVEC) sum[f] = fmaf(p, wv[r], sum[f]);
-                else sum[f] += p;
-            }
-        }
-        // issue order: all LDS reads, then one MFMA per handful of VALU instructions, so the
-        // matrix pipe runs underneath the exp2 work of the same wavefront
-        // (the first MFMA waits for the LDS reads, so a batch of exp2 work goes in between)
-        constexpr int NV = (MASKED ? 5 : 2) * 16 * FR;            // VALU instructions of this step, roughly
-        constexpr int HEAD = NV / 3, EACH = (NV - HEAD) / (FR * KS);
-        __builtin_amdgcn_sched_group_barrier(0x100, KS + (MODE == M_MATVEC ? 8 : 4), 0);
-        __builtin_amdgcn_sched_group_barrier(0x002, HEAD, 0);
-#pragma unroll
-        for (int q = 0; q < FR * KS; ++q) {
-            __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
-            __builtin_amdgcn_sched_group_barrier(0x002, EACH, 0);
-        }
-    };
-    auto epilogue = [&](int g) {
-        const int o_w = g * BM + wave * FR * 32;
-#pragma unroll
-        for (int f = 0; f < FR; ++f) {
-            const int o = o_w + 32 * f + c;
-            float tot = sum[f] + __shfl_xor(sum[f], 32);
-            if (a.dustbin) {
-                float ed = fast_exp2(a.sdb2 + ytp[L] * LOG2E + m2);
-                tot += (MODE == M_MATVEC) ? ed * wp[L] : ed;
-            }
-            if (h == 0 && o < L) {
-                float r;
-                if constexpr (MODE == M_LSE) {
-                    r = mblk - LN2 * fast_log2(tot);
-                } else {
-                    float pre = a.pre.p ? a.pre.p[n * a.pre.stride + o] : 0.f;
-                    r = pre - fast_exp2((xsp[o] - mblk) * LOG2E) * tot;
-                }
-                a.out_vec.p[n * a.out_vec.stride + o] = r;
-            }
-        }
-    };
-
-#pragma unroll
-    for (int f = 0; f < FR; ++f) sum[f] = 0.f;
-    int g = gA, i = 0;
-    int k = J(gA) + wave * FR;                       // this wavefront's tile in step (g, i)
-    {   // accumulators of step 0
-        const unsigned char *s0 = smem + slot_of(k);
-        f32x16 y0;
-#pragma unroll
-        for (int q = 0; q < 4; ++q) {
-            float4 v4 = *reinterpret_cast<const float4 *>(s0 + rd_v + 32 * q);
-            y0[4 * q + 0] = v4.x; y0[4 * q + 1] = v4.y; y0[4 * q + 2] = v4.z; y0[4 * q + 3] = v4.w;
-        }
+    for (int f = 0; f < FR; ++f) {
+        const int oc = min(o_w + 32 * f + c, L - 1);
 #pragma unroll
         for (int s = 0; s < KS; ++s) {
-            bf16x8 af = *reinterpret_cast<const bf16x8 *>(s0 + rd_a + 32 * s);
-#pragma unroll
-            for (int f = 0; f < FR; ++f)
-                acc[0][f] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af, xf[f].v[s], s == 0 ? y0 : acc[0][f], 0, 0, 0);
+            uint4 z = *reinterpret_cast<const uint4 *>(Xb + (long)oc * D + (2 * s + h) * 8);
+            xf[f].v[s] = *reinterpret_cast<bf16x8 *>(&z);
+            if constexpr (MODE == M_FINAL) {
+                uint4 y = *reinterpret_cast<const uint4 *>(reinterpret_cast<const T *>(a.A) + moff + (long)oc * D +
+                                                           (2 * s + h) * 8);
+                af[f].v[s] = *reinterpret_cast<bf16x8 *>(&y);
+            }
         }
+        pof[f] = make_float4(0, 0, 0, 0);
+        if constexpr (MODE == M_FINAL) pof[f] = a.po[n * a.ldp + oc];
+#pragma unroll
+        for (int j = 0; j < D / 32; ++j)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) outm[f][j][r] = 0.f;
     }
 
-    for (int sg0 = 0; sg0 < total; sg0 += PD) {
-        // PD steps per trip, unconditionally (a conditional step would hide from the compiler
-        // how many fetches are in flight).  If `total` is not a multiple of PD the last trip
-        // runs up to PD-1 steps past the end: g == gB there, so their fetches land in the
-        // spare slot, their sums are never written and no group end is reached (S > PD).
-#pragma unroll
-        for (int r = 0; r < PD; ++r) {
-            // loader: publish the tile of step sigma+2, fetch the one of step sigma+AH
-            ld_store(sd[r], sy[r], sw[r], sk[r], sok[r]);
-            sok[r] = gl < gB;
-            sk[r] = J(gl) + RG::LEAD + il;
-            ld_issue(sd[r], sy[r], sw[r], sk[r]);
-            if (++il == S) { il = 0; ++gl; }
+    const int kbase = (o_blk - W) >= 0 ? (o_blk - W) / TT : -((W - o_blk + TT - 1) / TT);
+    const int kend = (o_blk + 32 * FR - 1 + W) / TT;
+    const int S = kend - kbase + 1;
+    const int klast = (L - 1) / TT;
 
-            const bool last_of_group = (i == S - 1);
-            int k_next = k + 1;
-            if (last_of_group) {           // the next step belongs to the next group: its owner rows take over
+    // one tile pair in flight between global memory and LDS (plain arrays: a struct holding
+    // them ends up in scratch memory)
+    auto g_load = [&](uint4 (&gy)[RG::CPT], uint4 (&gb)[RG::CPT], float &gvy, float4 &gvq, int k) {
 #pragma unroll
-                for (int f = 0; f < FR; ++f) xf[f] = xn[f];
-                k_next = J(g + 1) + wave * FR;
+        for (int q = 0; q < RG::CPT; ++q) {
+            int idx = tid + q * NTHREADS;
+            if (idx >= RG::CHUNKS) idx = RG::CHUNKS - 1;
+            const unsigned row = (unsigned)min(max(k * TT + idx / RG::CPR, 0), L - 1);
+            const unsigned off = row * (unsigned)(D * 2) + (unsigned)(idx % RG::CPR) * 16u;
+            gy[q] = *reinterpret_cast<const uint4 *>(Yb + off);
+            gb[q] = *reinterpret_cast<const uint4 *>(Bb + off);
+        }
+        const unsigned tv = (unsigned)min(max(k * TT + (tid & (TT - 1)), 0), L - 1);
+        gvy = ytp[tv];
+        if constexpr (MODE == M_FINAL) gvq = a.qt[n * a.ldp + tv];
+    };
+    // rows outside [0, L) keep whatever the clamped fetch brought: their potential is -inf,
+    // so their plan entries are exactly zero and finite data times zero adds nothing
+    auto s_store = [&](const uint4 (&gy)[RG::CPT], const uint4 (&gb)[RG::CPT], float gvy, float4 gvq, int j, int k) {
+        unsigned char *sl = smem + (j & (RG::NSLOT - 1)) * RG::SLOT;
+#pragma unroll
+        for (int q = 0; q < RG::CPT; ++q) {
+            const int idx = tid + q * NTHREADS;
+            if (idx < RG::CHUNKS) {
+                const int off = (idx / RG::CPR) * RG::ROWB + (idx % RG::CPR) * 16;
+                *reinterpret_cast<uint4 *>(sl + RG::OFF_Y + off) = gy[q];
+                *reinterpret_cast<uint4 *>(sl + RG::OFF_B + off) = gb[q];
             }
-            const int t0 = k * TT, o_w = g * BM + wave * FR * 32;
-            const unsigned char *sl = smem + slot_of(k), *sn = smem + slot_of(k_next);
-            const bool all_in = (o_w + 32 * FR - 1 - t0 <= W) && (t0 + TT - 1 - o_w <= W);
-            if (all_in) step_body(std::false_type{}, acc[(r + 1) & 1], acc[r & 1], o_w, t0, sl, sn);
-            else step_body(std::true_type{}, acc[(r + 1) & 1], acc[r & 1], o_w, t0, sl, sn);
-            __syncthreads();
-            k = k_next;
-            if (last_of_group) {
-                epilogue(g);
+        }
+        if (tid < TT) {
+            const bool live = k >= 0 && k * TT + tid < L;
+            reinterpret_cast<float *>(sl + RG::OFF_VY)[tid] = live ? fmaf(gvy, LOG2E, m2) : -INFINITY;
+            if constexpr (MODE == M_FINAL)
+                reinterpret_cast<float4 *>(sl + RG::OFF_VQ)[tid] = live ? gvq : make_float4(0, 0, 0, 0);
+        }
+    };
+
+    {
+        uint4 fy[RG::LEAD + 1][RG::CPT], fb[RG::LEAD + 1][RG::CPT];
+        float fvy[RG::LEAD + 1];
+        float4 fvq[RG::LEAD + 1];
 #pragma unroll
-                for (int f = 0; f < FR; ++f) sum[f] = 0.f;
-                i = 0;
-                ++g;
-                if (g + 1 < gB) x_issue(xn, g + 1);
-            } else {
-                ++i;
+        for (int j = 0; j <= RG::LEAD; ++j) g_load(fy[j], fb[j], fvy[j], fvq[j], kbase + j);
+#pragma unroll
+        for (int j = 0; j <= RG::LEAD; ++j) s_store(fy[j], fb[j], fvy[j], fvq[j], j, kbase + j);
+    }
+    __syncthreads();
+    uint4 ny[RG::CPT], nb[RG::CPT];
+    float nvy = 0.f;
+    float4 nvq = make_float4(0, 0, 0, 0);
+
+    // per-lane LDS offsets: fragment rows for the score / Z products, and the 8-byte pieces
+    // this lane addresses in a transposing read (row 4h + (lane & 15) / 4 of a 16-row block,
+    // columns 16 (lane / 16 & 1) + 4 (lane & 3), + 32 per output column tile)
+    const int rd_a = c * RG::ROWB + h * 16;
+    const int rd_t = (4 * h + ((lane & 15) >> 2)) * RG::ROWB + (16 * ((lane >> 4) & 1) + 4 * (lane & 3)) * 2;
+    const float c2 = a.c2;
+    typedef __bf16 bf16x4v __attribute__((ext_vector_type(4)));
+
+    for (int s = 0; s < S; ++s) {
+        const int jnew = s + 1 + RG::LEAD;
+        const bool more = (s + 1 < S);
+        if (more) g_load(ny, nb, nvy, nvq, kbase + jnew);
+
+        const int j = s + wave * FR;
+        const int k = kbase + j;
+        if (k >= 0 && k <= klast) {
+            const unsigned char *sl = smem + (j & (RG::NSLOT - 1)) * RG::SLOT;
+            const int t0 = k * TT;
+            // this tile's fragments (score rows, Z rows) and staged potentials, read once for
+            // all FR owner fragments
+            bf16x8 yfr[KS], bfr[MODE == M_FINAL ? KS : 1];
+#pragma unroll
+            for (int ks = 0; ks < KS; ++ks) {
+                yfr[ks] = *reinterpret_cast<const bf16x8 *>(sl + RG::OFF_Y + rd_a + 32 * ks);
+                if constexpr (MODE == M_FINAL)
+                    bfr[ks] = *reinterpret_cast<const bf16x8 *>(sl + RG::OFF_B + rd_a + 32 * ks);
+            }
+            f32x16 yv;
+#pragma unroll
+            for (int q = 0; q < 4; ++q) {
+                float4 v4 = *reinterpret_cast<const float4 *>(sl + RG::OFF_VY + (8 * q + 4 * h) * 4);
+                yv[4 * q + 0] = v4.x; yv[4 * q + 1] = v4.y; yv[4 * q + 2] = v4.z; yv[4 * q + 3] = v4.w;
+            }
+            bf16x8 pf[FR][2];
+#pragma unroll
+            for (int f = 0; f < FR; ++f) {
+                const int of = o_w + 32 * f;
+                const bool interior = (of + 31 - t0 <= W) && (t0 + TT - 1 - of <= W);
+                // scores start from the staged potentials when the scale is folded into the operand
+                f32x16 acc = yv;
+                if (c2 != 1.f)
+#pragma unroll
+                    for (int r = 0; r < 16; ++r) acc[r] = 0.f;
+#pragma unroll
+                for (int ks = 0; ks < KS; ++ks)
+                    acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(yfr[ks], xf[f].v[ks], acc, 0, 0, 0);
+                float e[16];
+                if (c2 != 1.f)
+#pragma unroll
+                    for (int r = 0; r < 16; ++r) e[r] = fmaf(acc[r], c2, yv[r]);
+                else
+#pragma unroll
+                    for (int r = 0; r < 16; ++r) e[r] = acc[r];
+                if (!interior) {   // also covers a tile that misses this fragment's band entirely
+                    const int lo = of + c - W - t0 - 4 * h;
+                    const unsigned span = 2u * (unsigned)W;
+#pragma unroll
+                    for (int r = 0; r < 16; ++r) {
+                        const int off = 8 * (r >> 2) + (r & 3);
+                        if ((unsigned)(off - lo) > span) e[r] = -INFINITY;
+                    }
+                }
+#pragma unroll
+                for (int r = 0; r < 16; ++r) e[r] = fast_exp2(e[r]);
+
+                if constexpr (MODE == M_FINAL) {
+                    f32x16 z;
+#pragma unroll
+                    for (int r = 0; r < 16; ++r) z[r] = 0.f;
+#pragma unroll
+                    for (int ks = 0; ks < KS; ++ks)
+                        z = __builtin_amdgcn_mfma_f32_32x32x16_bf16(bfr[ks], af[f].v[ks], z, 0, 0, 0);
+#pragma unroll
+                    for (int r = 0; r < 16; ++r) {
+                        const int tl = 8 * (r >> 2) + 4 * h + (r & 3);
+                        float4 q4 = *reinterpret_cast<const float4 *>(sl + RG::OFF_VQ + tl * 16);
+                        float md = z[r];
+                        md = fmaf(-pof[f].x, q4.x, md);
+                        md = fmaf(-pof[f].y, q4.y, md);
+                        md = fmaf(-pof[f].z, q4.z, md);
+                        md = fmaf(-pof[f].w, q4.w, md);
+                        e[r] *= md;
+                    }
+                }
+#pragma unroll
+                for (int m = 0; m < 2; ++m)
+#pragma unroll
+                    for (int r = 0; r < 8; ++r) pf[f][m][r] = (__bf16)e[8 * m + r];
+            }
+
+            // second product: out[dv, o] += sum_t M[t][dv] * e[t, o], M = payload (M_APPLY) or the
+            // other-side score rows themselves (M_FINAL); the transposed fragment of M serves
+            // every owner fragment
+            const unsigned char *pm = sl + (MODE == M_FINAL ? RG::OFF_Y : RG::OFF_B) + rd_t;
+#pragma unroll
+            for (int m = 0; m < 2; ++m)
+#pragma unroll
+                for (int dvt = 0; dvt < D / 32; ++dvt) {
+                    bf16x4v lo4 = __builtin_amdgcn_ds_read_tr16_b64_v4bf16(
+                        (bf16x4v __attribute__((address_space(3))) *)(pm + (16 * m) * RG::ROWB + dvt * 64));
+                    bf16x4v hi4 = __builtin_amdgcn_ds_read_tr16_b64_v4bf16(
+                        (bf16x4v __attribute__((address_space(3))) *)(pm + (16 * m + 8) * RG::ROWB + dvt * 64));
+                    bf16x8 am = {lo4[0], lo4[1], lo4[2], lo4[3], hi4[0], hi4[1], hi4[2], hi4[3]};
+#pragma unroll
+                    for (int f = 0; f < FR; ++f)   // (a fragment the tile misses has e == 0 throughout)
+                        outm[f][dvt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(am, pf[f][m], outm[f][dvt], 0, 0, 0);
+                }
+        }
+        if (more) s_store(ny, nb, nvy, nvq, jnew, kbase + jnew);
+        __syncthreads();
+    }
+
+    // epilogue: owner-side factor, store (and the <dot_mat_o, out_o> reduction for dV)
+#pragma unroll
+    for (int f = 0; f < FR; ++f) {
+        const int o = o_w + 32 * f + c;
+        const int oc = min(o, L - 1);
+        float fac = fast_exp2((xsp[oc] - mblk) * LOG2E);
+        if constexpr (MODE == M_FINAL) fac *= a.cs;
+        T *orow = reinterpret_cast<T *>(a.out_mat) + moff + (long)oc * D;
+        const T *drow = a.dot_mat ? reinterpret_cast<const T *>(a.dot_mat) + moff + (long)oc * D : nullptr;
+        float dot = 0.f;
+#pragma unroll
+        for (int j = 0; j < D / 32; ++j)
+#pragma unroll
+            for (int q = 0; q < 4; ++q) {
+                const int dv = 32 * j + 8 * q + 4 * h;
+                float v0 = outm[f][j][4 * q + 0] * fac, v1 = outm[f][j][4 * q + 1] * fac;
+                float v2 = outm[f][j][4 * q + 2] * fac, v3 = outm[f][j][4 * q + 3] * fac;
+                if (o < L) {
+                    store4<T>(orow + dv, v0, v1, v2, v3);
+                    if constexpr (MODE == M_APPLY) {
+                        if (drow) {
+                            float dd[4];
+                            load4<T>(drow + dv, dd);
+                            dot += dd[0] * v0 + dd[1] * v1 + dd[2] * v2 + dd[3] * v3;
+                        }
+                    }
+                }
+            }
+        if constexpr (MODE == M_APPLY) {
+            if (a.dot_mat) {
+                dot += __shfl_xor(dot, 32);
+                if (h == 0 && o < L) a.dot_out.p[n * a.dot_out.stride + o] = dot;
             }
         }
     }
@@ -1343,82 +1316,43 @@ int launch_vsweep(SweepArgs a, int N, hipStream_t st)
     return hipGetLastError() == hipSuccess ? SKA_OK : SKA_EHIP;
 }
 
-int g_ncu = 0;
-
-// Persistent sweep when the ring can roll across groups: TPG <= S <= NSLOT + FR - 1.
-template <int D, int MODE, int NW, int FR>
-int launch_psweep(SweepArgs a, int N, hipStream_t st, bool *taken)
+template <int D, int MODE, int FR>
+int launch_msweep(SweepArgs a, int N, hipStream_t st)
 {
-    using RG = PRing<D, MODE, NW, FR>;
-    constexpr int BM = NW * FR * 32;
-    const int kb = -((a.W + TT - 1) / TT), ke = (32 * FR - 1 + a.W) / TT, S = ke - kb + 1;
-    *taken = false;
-    if (S < RG::TPG || S > RG::SMAX) return SKA_OK;
-    if (!g_ncu) {
-        if (const char *e = getenv("SKA_NCU")) g_ncu = atoi(e);   // development: pretend a smaller chip
-    }
-    if (!g_ncu) {
-        int dev = 0;
-        if (hipGetDevice(&dev) != hipSuccess ||
-            hipDeviceGetAttribute(&g_ncu, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || g_ncu < 1)
-            return SKA_EHIP;
-    }
-    const int GP = (a.L + BM - 1) / BM;
-    int bpp = (g_ncu + N - 1) / N;
-    if (bpp > GP) bpp = GP;
-    if (bpp < 1) bpp = 1;
-    a.gpb = (GP + bpp - 1) / bpp;
-    a.nbp = (GP + a.gpb - 1) / a.gpb;
+    constexpr int BM = NWAVES * FR * 32;
+    a.nbp = (a.L + BM - 1) / BM;
     a.nb_total = a.nbp * N;
     const int chunk = (a.nb_total + 7) / 8;
+    constexpr int LDS = MRing<D, MODE, FR>::BYTES;
     static bool raised = false;
-    if (!raised) {
-        if (hipFuncSetAttribute(reinterpret_cast<const void *>(&psweep_kernel<D, MODE, NW, FR>),
-                                hipFuncAttributeMaxDynamicSharedMemorySize, RG::BYTES) != hipSuccess)
+    if (LDS > 48 * 1024 && !raised) {
+        if (hipFuncSetAttribute(reinterpret_cast<const void *>(&msweep_kernel<D, MODE, FR>),
+                                hipFuncAttributeMaxDynamicSharedMemorySize, LDS) != hipSuccess)
             return SKA_EHIP;
         raised = true;
     }
-    hipLaunchKernelGGL((psweep_kernel<D, MODE, NW, FR>), dim3(chunk * 8), dim3(RG::NT), RG::BYTES, st, a);
-    *taken = true;
+    hipLaunchKernelGGL((msweep_kernel<D, MODE, FR>), dim3(chunk * 8), dim3(NTHREADS), LDS, st, a);
     return hipGetLastError() == hipSuccess ? SKA_OK : SKA_EHIP;
 }
 
-int g_variant = -1;   // development switch (SKA_VARIANT): 0 = first kernels, 1.. = ring kernels
-
+// Which kernel runs which sweep:
+//   scaling sweeps and band mat-vecs      vsweep_kernel (skewed LDS ring), both storage types
+//   output map / dV, final sweeps         msweep_kernel for bf16 storage with d <= 64,
+//                                         sweep_kernel otherwise
+//   the very first half-step              sweep_kernel<M_LSE_FIRST> (running maximum)
 template <typename T, int D> int sweep(int mode, const SweepArgs &a, int N, hipStream_t st)
 {
-    if (g_variant < 0) {
-        const char *e = getenv("SKA_VARIANT");
-        g_variant = e ? atoi(e) : 1;
-    }
-    if (const char *e = getenv("SKA_DBG")) const_cast<SweepArgs &>(a).dbg = atoi(e);
-    if (g_variant >= 1 && (mode == M_LSE || mode == M_MATVEC)) {
-        if constexpr (sizeof(T) == 2 && D == 64) {
-            if (g_variant == 3) {
-                bool taken = false;
-                int rc = mode == M_LSE ? launch_psweep<D, M_LSE, 8, 2>(a, N, st, &taken)
-                                       : launch_psweep<D, M_MATVEC, 8, 2>(a, N, st, &taken);
-                if (rc != SKA_OK || taken) return rc;
-            }
-        }
-        if constexpr (sizeof(T) == 2) {
-            if (g_variant == 2 && D <= 64)
-                return mode == M_LSE ? launch_vsweep<T, D, M_LSE, 4>(a, N, st)
-                                     : launch_vsweep<T, D, M_MATVEC, 4>(a, N, st);
-            return mode == M_LSE ? launch_vsweep<T, D, M_LSE, 2>(a, N, st)
-                                 : launch_vsweep<T, D, M_MATVEC, 2>(a, N, st);
-        } else {
-            return mode == M_LSE ? launch_vsweep<T, D, M_LSE, 1>(a, N, st)
-                                 : launch_vsweep<T, D, M_MATVEC, 1>(a, N, st);
-        }
-    }
-    constexpr int FRV = (sizeof(T) == 2) ? 2 : 1;   // vector sweeps: owner rows per wave / 32
+    constexpr int FRV = (sizeof(T) == 2) ? 2 : 1;   // vector sweeps: owner rows per wavefront / 32
     switch (mode) {
     case M_LSE_FIRST: return launch_sweep<T, D, M_LSE_FIRST, FRV>(a, N, st);
-    case M_LSE: return launch_sweep<T, D, M_LSE, FRV>(a, N, st);
-    case M_MATVEC: return launch_sweep<T, D, M_MATVEC, FRV>(a, N, st);
-    case M_APPLY: return launch_sweep<T, D, M_APPLY, 1>(a, N, st);
-    default: return launch_sweep<T, D, M_FINAL, 1>(a, N, st);
+    case M_LSE: return launch_vsweep<T, D, M_LSE, FRV>(a, N, st);
+    case M_MATVEC: return launch_vsweep<T, D, M_MATVEC, FRV>(a, N, st);
+    case M_APPLY:
+        if constexpr (sizeof(T) == 2 && D <= 64) return launch_msweep<D, M_APPLY, 2>(a, N, st);
+        else return launch_sweep<T, D, M_APPLY, 1>(a, N, st);
+    default:
+        if constexpr (sizeof(T) == 2 && D <= 64) return launch_msweep<D, M_FINAL, 1>(a, N, st);
+        else return launch_sweep<T, D, M_FINAL, 1>(a, N, st);
     }
 }
 
