@@ -351,7 +351,10 @@ template <> __device__ __forceinline__ void load4<__bf16>(const __bf16 *src, flo
     for (int i = 0; i < 4; ++i) f[i] = (float)v[i];
 }
 
-// ------------------------------------------------------------------ the sweep kernel
+// ------------------------------------------------------------------ the generic sweep kernel
+// Double-buffered LDS staging, one other-side tile per barrier.  It serves the first row
+// half-step (running-maximum LSE, no potentials yet), every fp32-storage matrix sweep
+// and the bf16 matrix sweeps at d = 128; the ring kernels below take the rest.
 template <typename T, int D, int MODE> struct Stage {
     using TL = Tile<T, D>;
     static constexpr bool HAS_B = (MODE == M_FINAL);
@@ -360,8 +363,7 @@ template <typename T, int D, int MODE> struct Stage {
     static constexpr int OFF_B = OFF_Y + TL::RM_BYTES;
     static constexpr int OFF_PAY = OFF_B + (HAS_B ? TL::RM_BYTES : 0);
     static constexpr int OFF_VY = OFF_PAY + (HAS_PAY ? TL::PT_BYTES : 0);
-    static constexpr int OFF_VW = OFF_VY + TT * 4;
-    static constexpr int OFF_VQ = OFF_VW + TT * 4;
+    static constexpr int OFF_VQ = OFF_VY + TT * 4;
     static constexpr int BYTES = ((OFF_VQ + TT * 16) + 15) / 16 * 16;
 };
 
@@ -446,7 +448,7 @@ __global__ __launch_bounds__(NTHREADS) void sweep_kernel(const SweepArgs a)
 
     // staging registers
     uint4 ry[TL::CPT], rb[ST::HAS_B ? TL::CPT : 1], rp[MODE == M_APPLY ? TL::CPT : 1];
-    float rvy = 0.f, rvw = 0.f;
+    float rvy = 0.f;
     float4 rvq = make_float4(0, 0, 0, 0);
 
     auto g_load = [&](int k) {
@@ -457,7 +459,6 @@ __global__ __launch_bounds__(NTHREADS) void sweep_kernel(const SweepArgs a)
         if (tid < TT) {
             const int t = t0 + tid;
             rvy = (t < L) ? ytp[t] * LOG2E + m2 : -INFINITY;
-            if constexpr (MODE == M_MATVEC) rvw = (t < L) ? a.w.p[n * a.w.stride + t] : 0.f;
             if constexpr (MODE == M_FINAL) rvq = (t < L) ? a.qt[n * a.ldp + t] : make_float4(0, 0, 0, 0);
         }
     };
@@ -469,7 +470,6 @@ __global__ __launch_bounds__(NTHREADS) void sweep_kernel(const SweepArgs a)
         if constexpr (MODE == M_FINAL && TL::IS_BF16) tile_store_pay<T, D>(ry, s + ST::OFF_PAY);
         if (tid < TT) {
             reinterpret_cast<float *>(s + ST::OFF_VY)[tid] = rvy;
-            if constexpr (MODE == M_MATVEC) reinterpret_cast<float *>(s + ST::OFF_VW)[tid] = rvw;
             if constexpr (MODE == M_FINAL) reinterpret_cast<float4 *>(s + ST::OFF_VQ)[tid] = rvq;
         }
     };
@@ -529,19 +529,7 @@ __global__ __launch_bounds__(NTHREADS) void sweep_kernel(const SweepArgs a)
             } else {
 #pragma unroll
                 for (int r = 0; r < 16; ++r) e[r] = fast_exp2(e[r]);
-                if constexpr (MODE == M_LSE) {
-#pragma unroll
-                    for (int r = 0; r < 16; ++r) sum[f] += e[r];
-                } else if constexpr (MODE == M_MATVEC) {
-#pragma unroll
-                    for (int q = 0; q < 4; ++q) {
-                        float4 w4 = *reinterpret_cast<const float4 *>(s + ST::OFF_VW + (8 * q + 4 * h) * 4);
-                        sum[f] = fmaf(e[4 * q + 0], w4.x, sum[f]);
-                        sum[f] = fmaf(e[4 * q + 1], w4.y, sum[f]);
-                        sum[f] = fmaf(e[4 * q + 2], w4.z, sum[f]);
-                        sum[f] = fmaf(e[4 * q + 3], w4.w, sum[f]);
-                    }
-                } else if constexpr (MODE == M_APPLY) {
+                if constexpr (MODE == M_APPLY) {
                     tile_accum<T, D>(outm[f], s + ST::OFF_PAY, e, lane);
                 } else {  // M_FINAL
                     f32x16 z;
@@ -583,22 +571,6 @@ __global__ __launch_bounds__(NTHREADS) void sweep_kernel(const SweepArgs a)
                 mn = m3;
             }
             if (h == 0 && o < L) a.out_vec.p[n * a.out_vec.stride + o] = -LN2 * (mn + fast_log2(tot));
-        } else if constexpr (MODE == M_LSE || MODE == M_MATVEC) {
-            float tot = sum[f] + __shfl_xor(sum[f], 32);
-            if (a.dustbin) {
-                float ed = fast_exp2(a.sdb2 + ytp[L] * LOG2E + m2);
-                tot += (MODE == M_MATVEC) ? ed * a.w.p[n * a.w.stride + L] : ed;
-            }
-            if (h == 0 && o < L) {
-                float r;
-                if constexpr (MODE == M_LSE) {
-                    r = mblk - LN2 * fast_log2(tot);
-                } else {
-                    float pre = a.pre.p ? a.pre.p[n * a.pre.stride + o] : 0.f;
-                    r = pre - fast_exp2((xsp[o] - mblk) * LOG2E) * tot;
-                }
-                a.out_vec.p[n * a.out_vec.stride + o] = r;
-            }
         } else {
             float fac = 0.f;
             if (o < L) fac = fast_exp2((xsp[o] - mblk) * LOG2E);
