@@ -654,7 +654,10 @@ __global__ __launch_bounds__(NTHREADS) void vsweep_kernel(const SweepArgs a)
     const float *wp = (MODE == M_MATVEC) ? a.w.p + n * a.w.stride : nullptr;
 
 
-    float mblk, m2 = 0.f;   // stabiliser: set once the prologue loads are in flight
+    // stabiliser input first, so that waiting for it waits for nothing else
+    static_assert(BM <= NTHREADS, "one owner-side potential per thread");
+    float mraw = xsp[min(o_blk + min(tid, BM - 1), L - 1)];   // clamped repeats are harmless
+    float mblk, m2 = 0.f;
     OwnerFrag<T, D> xf[FR];
     int o_frag[FR];
     float sum[FR];
@@ -706,8 +709,7 @@ __global__ __launch_bounds__(NTHREADS) void vsweep_kernel(const SweepArgs a)
 #pragma unroll
     for (int j = 0; j <= RG::LEAD; ++j) g_load(fill[j], kbase + j);
     {
-        float m = -INFINITY;
-        for (int i = tid; i < BM; i += NTHREADS) m = fmaxf(m, xsp[min(o_blk + i, L - 1)]);   // clamped repeats are harmless
+        float m = mraw;
 #pragma unroll
         for (int s = 32; s >= 1; s >>= 1) m = fmaxf(m, __shfl_xor(m, s));
         if (lane == 0) red[wave] = m;
@@ -721,9 +723,11 @@ __global__ __launch_bounds__(NTHREADS) void vsweep_kernel(const SweepArgs a)
     Inflight nxt;
 
     for (int s = 0; s < S; ++s) {
+        // the next tile is requested in every step, also when no later step reads it (its
+        // address is clamped, its ring slot is free): a load under a condition would make
+        // the compiler wait for it at once instead of at the store below
         const int jnew = s + 1 + RG::LEAD;
-        const bool more = (s + 1 < S);
-        if (more) g_load(nxt, kbase + jnew);
+        g_load(nxt, kbase + jnew);
 
         const int j = s + wave * FR;
         const int k = kbase + j;
@@ -783,7 +787,7 @@ __global__ __launch_bounds__(NTHREADS) void vsweep_kernel(const SweepArgs a)
                 }
             }
         }
-        if (more) s_store(nxt, jnew);
+        s_store(nxt, jnew);
         __syncthreads();
     }
 
