@@ -141,33 +141,6 @@ __device__ __forceinline__ void tile_load(TileRegs<T, D> &reg, const T *base, in
     }
 }
 
-// Same, but branch-free: the row index is clamped into [0, L) so the load is always
-// issued (a conditional load makes the compiler wait for every load in flight before
-// it zero-fills the destination); `valid` says whether the data may be used.
-template <typename T, int D>
-__device__ __forceinline__ void tile_load_clamped(TileRegs<T, D> &reg, bool (&valid)[Tile<T, D>::CPT],
-                                                  const T *base, int t0, int L, bool live)
-{
-    using TL = Tile<T, D>;
-#pragma unroll
-    for (int c = 0; c < TL::CPT; ++c) {
-        int idx = threadIdx.x + c * NTHREADS;
-        if (idx >= TL::CHUNKS) idx = TL::CHUNKS - 1;
-        const int row = idx / TL::CPR, ch = idx % TL::CPR;
-        int t = t0 + row;
-        valid[c] = live && t < L;
-        t = t < 0 ? 0 : (t > L - 1 ? L - 1 : t);
-        reg[c] = *reinterpret_cast<const uint4 *>(base + (long)t * D + ch * (16 / Elem<T>::BYTES));
-    }
-}
-template <typename T, int D>
-__device__ __forceinline__ void tile_zero_invalid(TileRegs<T, D> &reg, const bool (&valid)[Tile<T, D>::CPT])
-{
-#pragma unroll
-    for (int c = 0; c < Tile<T, D>::CPT; ++c)
-        if (!valid[c]) reg[c] = make_uint4(0, 0, 0, 0);
-}
-
 // registers -> LDS, row-major (A-operand of the score / Z products)
 template <typename T, int D>
 __device__ __forceinline__ void tile_store_rm(const TileRegs<T, D> &reg, unsigned char *lds)
@@ -269,27 +242,28 @@ __device__ __forceinline__ f32x16 tile_dot(const unsigned char *tile, const Owne
     return acc;
 }
 
-// FR score tiles at once from one other-side tile: the tile's fragments are read from
-// LDS once and every product chain is issued before any of them is consumed.
-template <int D, int FR>
-__device__ __forceinline__ void tile_dot_multi(const unsigned char *tile, const OwnerFrag<__bf16, D> (&x)[FR],
+// FR score tiles at once from one other-side tile of a ring kernel (rows ROWB bytes apart,
+// no swizzle): the tile's fragments are read from LDS once and every product chain is
+// issued before any of them is consumed.
+template <int D, int FR, int ROWB>
+__device__ __forceinline__ void ring_dot_multi(const unsigned char *tile, const OwnerFrag<__bf16, D> (&x)[FR],
                                                int lane, f32x16 (&acc)[FR])
 {
-    const int t = lane & 31, h = lane >> 5;
+    const unsigned char *row = tile + (lane & 31) * ROWB + (lane >> 5) * 16;
     bf16x8 a[D / 16];
 #pragma unroll
-    for (int s = 0; s < D / 16; ++s)
-        a[s] = *reinterpret_cast<const bf16x8 *>(tile + bf16_chunk_off<D>(t, 2 * s + h));
+    for (int s = 0; s < D / 16; ++s) a[s] = *reinterpret_cast<const bf16x8 *>(row + 32 * s);
 #pragma unroll
     for (int s = 0; s < D / 16; ++s)
 #pragma unroll
         for (int f = 0; f < FR; ++f)
             acc[f] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[s], x[f].v[s], acc[f], 0, 0, 0);
 }
-template <int D, int FR>
-__device__ __forceinline__ void tile_dot_multi(const unsigned char *tile, const OwnerFrag<float, D> (&x)[FR],
+template <int D, int FR, int ROWB>
+__device__ __forceinline__ void ring_dot_multi(const unsigned char *tile, const OwnerFrag<float, D> (&x)[FR],
                                                int lane, f32x16 (&acc)[FR])
 {
+    static_assert(ROWB == f32_row_floats<D>() * 4, "fp32 ring tiles use the padded fp32 layout");
 #pragma unroll
     for (int f = 0; f < FR; ++f) acc[f] = tile_dot<D>(tile, x[f], lane, acc[f]);
 }
@@ -618,7 +592,11 @@ template <typename T, int D, int MODE, int FR> struct VRing {
     using TL = Tile<T, D>;
     static constexpr int LEAD = FR * (NWAVES - 1);          // tiles between first and last wavefront
     static constexpr int NSLOT = (LEAD + 2 <= 8) ? 8 : 16;  // power of two >= LEAD + 2
-    static constexpr int OFF_VY = TL::RM_BYTES;
+    // tile rows in LDS: bf16 rows carry 16 bytes of padding (the 32 rows an MFMA operand
+    // read touches then fall on distinct banks, and the chunks of one row sit at fixed
+    // distances: one address register per step); fp32 rows are padded by four floats
+    static constexpr int ROWB = TL::IS_BF16 ? D * 2 + 16 : f32_row_floats<D>() * 4;
+    static constexpr int OFF_VY = 32 * ROWB;
     static constexpr int OFF_VW = OFF_VY + TT * 4;
     static constexpr int SLOT = OFF_VW + TT * 4;
     static constexpr int BYTES = NSLOT * SLOT;
@@ -674,31 +652,57 @@ __global__ __launch_bounds__(NTHREADS) void vsweep_kernel(const SweepArgs a)
     const int S = kend - kbase + 1;
     const int klast = (L - 1) / TT;
 
-    // One tile in flight between global memory and LDS: loads only, all unconditional
-    // (clamped addresses), so nothing stalls until the values are stored.
+    // One tile in flight between global memory and LDS.  A tile is a contiguous block of
+    // memory, so a thread's 16-byte pieces sit at fixed byte offsets from the tile's start:
+    // the start is a scalar, the offset one register, and a load needs no address arithmetic
+    // beyond a clamp that keeps the pieces of a ragged last tile inside the matrix.  Loads
+    // are unconditional (an index outside [0, klast] reads the nearest tile and is zeroed
+    // before it is stored), so nothing stalls until the values are stored.
+    constexpr int ROW_BYTES = D * (int)sizeof(T);
+    constexpr int TILE_BYTES = TT * ROW_BYTES;
+    unsigned goff[TL::CPT], soff[TL::CPT];   // piece offsets: in memory, in the LDS tile
+#pragma unroll
+    for (int q = 0; q < TL::CPT; ++q) {
+        const int idx = min(tid + q * NTHREADS, TL::CHUNKS - 1);
+        goff[q] = idx * 16;
+        soff[q] = (idx / TL::CPR) * RG::ROWB + (idx % TL::CPR) * 16;
+    }
+    const unsigned vrow = tid & (TT - 1);
     struct Inflight {
         uint4 y[TL::CPT];
-        bool ok[TL::CPT];
         float vy, vw;
-        bool live;
+        int rows;          // valid rows of the tile: 32 = whole, 0 = outside the matrix (uniform)
     };
-    auto g_load = [&](Inflight &g, int k) {   // k may lie outside [0, klast]: then zeros / -inf
-        const int t0 = k * TT;
-        const bool live = (k >= 0 && k <= klast);
-        tile_load_clamped<T, D>(g.y, g.ok, Yb, t0, L, live);
-        int t = t0 + (tid & (TT - 1));
-        g.live = live && t < L;
-        t = t < 0 ? 0 : (t > L - 1 ? L - 1 : t);
-        g.vy = ytp[t];
-        g.vw = (MODE == M_MATVEC) ? wp[t] : 0.f;
+    auto g_load = [&](Inflight &g, int k) {
+        const int kc = min(max(k, 0), klast);
+        const int rows = min(TT, L - kc * TT);   // >= 1
+        g.rows = (k == kc) ? rows : 0;
+        const unsigned char *tb = reinterpret_cast<const unsigned char *>(Yb) + (long)kc * TILE_BYTES;
+        const unsigned lim = rows * ROW_BYTES - 16;
+#pragma unroll
+        for (int q = 0; q < TL::CPT; ++q) g.y[q] = *reinterpret_cast<const uint4 *>(tb + min(goff[q], lim));
+        const unsigned vo = min(vrow, (unsigned)(rows - 1)) * 4;
+        g.vy = *reinterpret_cast<const float *>(reinterpret_cast<const unsigned char *>(ytp + kc * TT) + vo);
+        g.vw = 0.f;
+        if constexpr (MODE == M_MATVEC)
+            g.vw = *reinterpret_cast<const float *>(reinterpret_cast<const unsigned char *>(wp + kc * TT) + vo);
     };
     auto s_store = [&](Inflight &g, int j) {  // j = tile index relative to kbase
         unsigned char *sl = smem + (j & (RG::NSLOT - 1)) * RG::SLOT;
-        tile_zero_invalid<T, D>(g.y, g.ok);
-        tile_store_rm<T, D>(g.y, sl);
+        if (g.rows != TT) {   // uniform: ragged or absent tile
+            const unsigned lim = g.rows * ROW_BYTES;
+#pragma unroll
+            for (int q = 0; q < TL::CPT; ++q)
+                if (goff[q] >= lim) g.y[q] = make_uint4(0, 0, 0, 0);
+        }
+#pragma unroll
+        for (int q = 0; q < TL::CPT; ++q)
+            if (TL::CHUNKS % NTHREADS == 0 || tid + q * NTHREADS < TL::CHUNKS)
+                *reinterpret_cast<uint4 *>(sl + soff[q]) = g.y[q];
         if (tid < TT) {
-            reinterpret_cast<float *>(sl + RG::OFF_VY)[tid] = g.live ? fmaf(g.vy, LOG2E, m2) : -INFINITY;
-            if constexpr (MODE == M_MATVEC) reinterpret_cast<float *>(sl + RG::OFF_VW)[tid] = g.live ? g.vw : 0.f;
+            const bool ok = (int)vrow < g.rows;
+            reinterpret_cast<float *>(sl + RG::OFF_VY)[tid] = ok ? fmaf(g.vy, LOG2E, m2) : -INFINITY;
+            if constexpr (MODE == M_MATVEC) reinterpret_cast<float *>(sl + RG::OFF_VW)[tid] = ok ? g.vw : 0.f;
         }
     };
 
@@ -752,7 +756,7 @@ __global__ __launch_bounds__(NTHREADS) void vsweep_kernel(const SweepArgs a)
 #pragma unroll
                 for (int r = 0; r < 16; ++r) acc[f][r] = PRE ? yv[r] : 0.f;
             }
-            tile_dot_multi<D, FR>(sl, xf, lane, acc);   // unconditional: an unused tile costs MFMA only
+            ring_dot_multi<D, FR, RG::ROWB>(sl, xf, lane, acc);   // unconditional: an unused tile costs MFMA only
 
             float wv[MODE == M_MATVEC ? 16 : 1];
             if constexpr (MODE == M_MATVEC) {
@@ -769,14 +773,21 @@ __global__ __launch_bounds__(NTHREADS) void vsweep_kernel(const SweepArgs a)
 #pragma unroll
                 for (int r = 0; r < 16; ++r) e[r] = PRE ? acc[f][r] : fmaf(acc[f][r], a.c2, yv[r]);
                 if (!interior[f]) {
-                    // keep (o, t) iff -W <= t - o <= W; with t = t0 + 4h + off_r this is
-                    // 0 <= off_r - lo <= 2W for lo = o - W - t0 - 4h: one unsigned compare
+                    // keep (o, t) iff -W <= t - o <= W; with t = t0 + 4h + off_r (off_r a
+                    // constant of register r) this is lo <= off_r <= lo + 2W for the lane's
+                    // lo = o - W - t0 - 4h.  A tile crosses the lower edge, the upper edge
+                    // or (narrow bands) both: one compare against a constant per edge.
                     const int lo = o_frag[f] + c - W - t0 - 4 * h;
-                    const unsigned span = 2u * (unsigned)W;
+                    const int hi = lo + 2 * W;
+                    if (o_frag[f] + 31 - t0 > W) {
 #pragma unroll
-                    for (int r = 0; r < 16; ++r) {
-                        const int off = 8 * (r >> 2) + (r & 3);
-                        if ((unsigned)(off - lo) > span) e[r] = -INFINITY;
+                        for (int r = 0; r < 16; ++r)
+                            if (lo > 8 * (r >> 2) + (r & 3)) e[r] = -INFINITY;
+                    }
+                    if (t0 + TT - 1 - o_frag[f] > W) {
+#pragma unroll
+                        for (int r = 0; r < 16; ++r)
+                            if (hi < 8 * (r >> 2) + (r & 3)) e[r] = -INFINITY;
                     }
                 }
 #pragma unroll
