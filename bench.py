@@ -22,12 +22,42 @@ ROOT = os.path.dirname(os.path.abspath(__file__))
 sys.path.insert(0, ROOT)
 
 HBM_PEAK_GBS = 8000.0          # MI355X HBM3E, published
+MFMA_PEAK_TFLOPS = {"bf16": 2500.0, "f32": 157.3}   # dense matrix peak of the storage type's MFMA
+# Plain-ALU ceiling of the scaling sweep: per band edge one exp2 and one add, nothing packed,
+# nothing fused.  256 CUs x 4 SIMDs x 16 lanes x 2.4 GHz = 39.3 T lane-issue-slots/s; an add
+# takes one slot, v_exp_f32 two (it issues at half rate: 8 cycles per 64-wide wavefront,
+# measured), so the pair runs at 2 flop per 3 slots = 26.2 TFLOP/s at best.
+ALU_SLOTS_PER_S = 256 * 4 * 16 * 2.4e9
+ALU_PEAK_TFLOPS = ALU_SLOTS_PER_S * 2.0 / 3.0 / 1e12
+
+
+def edges(w) -> float:
+    """Band edges of the whole batch: |i-j| <= W, per (batch, head) problem L(2W+1) - W(W+1)."""
+    Wc = min(w.W, w.L - 1)
+    return float(w.N) * (w.L * (2 * Wc + 1) - Wc * (Wc + 1))
+
+
+def phase_model(w):
+    """Algorithmic HBM bytes per token-head and MFMA flops per band edge of one launch of each
+    phase's kernel (every operand streamed once, scores recomputed, nothing of size L x W
+    stored).  be = bytes per matrix element."""
+    be, d = (4 if w.dtype == "f32" else 2), w.d
+    return {
+        "prescale": (2 * d * be, 0),
+        "first_half_step": (2 * d * be + 8, 2 * d),
+        "scaling_sweeps": (2 * d * be + 8, 2 * d),
+        "output_map": (4 * d * be + 8, 4 * d),
+        "rowdot": (2 * d * be + 4, 0),
+        "dV": (5 * d * be + 12, 4 * d),
+        "matvec_chain": (2 * d * be + 16, 2 * d),
+        "final_sweeps": (5 * d * be + 40, 6 * d),
+    }
 
 
 def algorithmic_bytes_per_sweep(w) -> float:
-    """One scaling sweep streams the two bf16 operand matrices once and reads one
-    fp32 vector and writes one: (4d + 8) bytes per token and head."""
-    return (2 * w.d * 2 + 8) * w.L * w.N
+    """One scaling sweep streams the two operand matrices once and reads one fp32 vector
+    and writes one: (4d + 8) bytes per token and head for bf16 storage."""
+    return phase_model(w)["scaling_sweeps"][0] * w.L * w.N
 
 
 def cpu_baseline(w, budget_tokens: int):
@@ -97,14 +127,25 @@ def main() -> int:
     for _ in range(args.warmup):
         step()
     torch.cuda.synchronize()
-    ska.sinkhorn_attn_profile_enable(True)
+    ska.sinkhorn_attn_profile_enable(1)
     t0 = time.perf_counter()
     for _ in range(args.steps):
         step()
     torch.cuda.synchronize()
     dt = time.perf_counter() - t0
-    ska.sinkhorn_attn_profile_enable(False)
+    ska.sinkhorn_attn_profile_enable(0)
     sweep_ms, launches = ska.sinkhorn_attn_profile_read()
+    # per-phase times from a short pass of their own (two events per phase are too many to
+    # leave in the timed region)
+    psteps = min(args.steps, 3)
+    ska.sinkhorn_attn_profile_enable(2)
+    tp0 = time.perf_counter()
+    for _ in range(psteps):
+        step()
+    torch.cuda.synchronize()
+    pdt = time.perf_counter() - tp0
+    ska.sinkhorn_attn_profile_enable(0)
+    ph = ska.sinkhorn_attn_profile_read_phases()
 
     ms_per_step = 1e3 * dt / args.steps
     tokens_per_s = w.B * w.L * args.steps / dt
@@ -115,18 +156,37 @@ def main() -> int:
     if os.path.exists(tpath):
         with open(tpath) as f:
             traffic = json.load(f).get("hbm_bytes_per_launch")
+    dt_name = "bf16" if w.dtype == "bf16" else "f32"
+    E = edges(w)
+    model = phase_model(w)
+    phases = {}
+    for name, (ms, n) in ph.items():
+        if n == 0:
+            continue
+        t = 1e-3 * ms / n                      # seconds per launch
+        b, fl = model[name]
+        phases[name] = {"launches": n, "avg_launch_us": 1e6 * t, "share_of_step": 1e-3 * ms / pdt,
+                        "hbm_frac": b * w.L * w.N / t / 1e9 / HBM_PEAK_GBS,
+                        "mfma_frac": fl * E / t / 1e12 / MFMA_PEAK_TFLOPS[dt_name]}
+    alu_tflops = 2.0 * E / avg_s / 1e12
     out = {
         "metric": "fwd+bwd tokens/sec at L=262144 d=64 W=256 T=20 R=2; % MFMA / HBM peak",
         "value": tokens_per_s, "unit": "tokens/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
         "ms_per_step": ms_per_step, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
-        "dtype": "bf16" if w.dtype == "bf16" else "f32", "data": "synthetic",
+        "dtype": dt_name, "data": "synthetic",
         "config": {"workload": w.name, "B": w.B, "H": w.H, "L": w.L, "d": w.d, "W": w.W, "T": w.T,
                    "R": w.R, "eps": w.eps, "dustbin": w.dustbin},
         "roofline": {"kernel": "scaling sweep (row/column half-step, Eq. 1-2)", "bound": "hbm",
                      "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
                      "frac": achieved / HBM_PEAK_GBS, "traffic": traffic,
                      "launches_timed": launches, "avg_launch_us": 1e6 * avg_s,
-                     "algorithmic_bytes_per_launch": algorithmic_bytes_per_sweep(w)},
+                     "algorithmic_bytes_per_launch": algorithmic_bytes_per_sweep(w),
+                     # the same launches against the other two ceilings of this kernel
+                     "alu": {"achieved": alu_tflops, "peak": ALU_PEAK_TFLOPS, "unit": "TFLOP/s",
+                             "frac": alu_tflops / ALU_PEAK_TFLOPS, "flops": "one exp2 + one add per band edge"},
+                     "mfma": {"achieved": 2 * w.d * E / avg_s / 1e12, "peak": MFMA_PEAK_TFLOPS[dt_name],
+                              "unit": "TFLOP/s", "frac": 2 * w.d * E / avg_s / 1e12 / MFMA_PEAK_TFLOPS[dt_name]}},
+        "phases": phases,
     }
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(w, min(args.cpu_tokens, w.L))

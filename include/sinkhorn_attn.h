@@ -92,18 +92,31 @@ int sinkhorn_attn_bwd(const void *Q, const void *K, const void *V, const void *O
                       void *stream);
 
 /*
- * Benchmark hooks (no part of the operator).  While enabled, every forward call
- * records one HIP event on its stream after its first half-step launch and one
- * after its last, so that the run of identical half-step kernels in between
- * (2T + 3 launches of the scaling sweep of Eq. 1-2) can be timed in place,
- * inside a larger timed region, without a profiler.  At most 256 calls are
- * remembered between reads.
- *   sinkhorn_attn_profile_enable(on): 0/1; returns SKA_OK.
- *   sinkhorn_attn_profile_read(&ms, &launches): waits for the recorded events,
- *     returns the summed elapsed milliseconds and the number of half-step
- *     launches they bracket, then forgets them.  Host pointers.
+ * Benchmark hooks (no part of the operator).  While enabled, every forward and backward
+ * call records two HIP events on its stream around each of its phases, so that a phase can
+ * be timed in place, inside a larger timed region, without a profiler.  At most 4096 phase
+ * spans are remembered between reads (further ones are dropped).  Not thread-safe.
+ *   sinkhorn_attn_profile_enable(level): 0 off, 1 only the SKA_PH_SCALING span of every
+ *     forward call (two events per call), 2 every phase; returns SKA_OK.
+ *   sinkhorn_attn_profile_read_phases(ms, launches): host arrays of SKA_PH_COUNT entries;
+ *     waits for the recorded events, returns per phase the summed elapsed milliseconds and
+ *     the number of sweep launches they bracket, then forgets them.
+ *   sinkhorn_attn_profile_read(&ms, &launches): the same, SKA_PH_SCALING only (the run of
+ *     2T + 3 identical launches of the scaling sweep of Eq. 1-2 in every forward call).
  */
+typedef enum {
+    SKA_PH_PRESCALE = 0, /* bf16 storage: copy of Q with the score scale folded in (fwd and bwd) */
+    SKA_PH_FIRST = 1,    /* first row half-step of the base solve (no previous iterate)   */
+    SKA_PH_SCALING = 2,  /* the other 2T + 3 half-steps (Eq. 1-2)                         */
+    SKA_PH_OUTPUT = 3,   /* O = P22 V (Section 2.2)                                      */
+    SKA_PH_ROWDOT = 4,   /* g_u = <dO, O>                                                */
+    SKA_PH_DV = 5,       /* dV = P22^T dO and vbar2 = <V, dV>                            */
+    SKA_PH_MATVEC = 6,   /* reverse recurrences of Prop. 1 (three band mat-vecs, +1 for eta0) */
+    SKA_PH_FINAL = 7,    /* modifier packs and the two one-reference final sweeps (Prop. 2)  */
+    SKA_PH_COUNT = 8
+} ska_phase;
 int sinkhorn_attn_profile_enable(int on);
+int sinkhorn_attn_profile_read_phases(double *elapsed_ms, long *launches);
 int sinkhorn_attn_profile_read(double *elapsed_ms, long *launches);
 
 /* Static, human-readable text for a ska_status value. Never NULL. */

@@ -5,4 +5,5 @@
 """
 from .binding import (SinkhornAttnError, sinkhorn_attn_bwd, sinkhorn_attn_fwd,  # noqa: F401
                       sinkhorn_attn_profile_enable, sinkhorn_attn_profile_read,
+                      sinkhorn_attn_profile_read_phases,
                       sinkhorn_attn_strerror, sinkhorn_attn_workspace_bytes)

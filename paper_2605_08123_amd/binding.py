@@ -42,6 +42,9 @@ def load():
         lib.sinkhorn_attn_profile_read.restype = i
         lib.sinkhorn_attn_profile_read.argtypes = [ctypes.POINTER(ctypes.c_double),
                                                    ctypes.POINTER(ctypes.c_long)]
+        lib.sinkhorn_attn_profile_read_phases.restype = i
+        lib.sinkhorn_attn_profile_read_phases.argtypes = [ctypes.POINTER(ctypes.c_double),
+                                                          ctypes.POINTER(ctypes.c_long)]
         lib.sinkhorn_attn_strerror.restype = ctypes.c_char_p
         lib.sinkhorn_attn_strerror.argtypes = [i]
         _lib = lib
@@ -58,8 +61,9 @@ def sinkhorn_attn_strerror(status: int) -> str:
     return load().sinkhorn_attn_strerror(int(status)).decode()
 
 
-def sinkhorn_attn_profile_enable(on: bool) -> None:
-    load().sinkhorn_attn_profile_enable(int(bool(on)))
+def sinkhorn_attn_profile_enable(level) -> None:
+    """0/False off, 1/True the scaling-sweep run of every forward, 2 every phase."""
+    load().sinkhorn_attn_profile_enable(int(level))
 
 
 def sinkhorn_attn_profile_read():
@@ -69,6 +73,20 @@ def sinkhorn_attn_profile_read():
     if rc != SKA_OK:
         raise SinkhornAttnError(rc)
     return ms.value, n.value
+
+
+SKA_PHASES = ("prescale", "first_half_step", "scaling_sweeps", "output_map", "rowdot", "dV",
+              "matvec_chain", "final_sweeps")   # order of ska_phase in the header
+
+
+def sinkhorn_attn_profile_read_phases():
+    """{phase name: (elapsed milliseconds, sweep launches bracketed)} since the last read."""
+    k = len(SKA_PHASES)
+    ms, n = (ctypes.c_double * k)(), (ctypes.c_long * k)()
+    rc = load().sinkhorn_attn_profile_read_phases(ms, n)
+    if rc != SKA_OK:
+        raise SinkhornAttnError(rc)
+    return {name: (ms[j], n[j]) for j, name in enumerate(SKA_PHASES)}
 
 
 def sinkhorn_attn_workspace_bytes(B, H, L, d, W, T, R=2, dustbin=False, dtype=SKA_BF16) -> int:

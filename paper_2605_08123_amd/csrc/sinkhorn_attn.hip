@@ -25,6 +25,7 @@
 #include <stdint.h>
 #include <stdlib.h>
 
+#include <new>
 #include <type_traits>
 
 #include "sinkhorn_attn.h"
@@ -1343,11 +1344,33 @@ template <typename T, int D> int sweep(int mode, const SweepArgs &a, int N, hipS
     }
 }
 
-// benchmark hooks: events bracketing the run of identical half-step launches
-struct ProfPair { hipEvent_t a, b; long launches; };
-bool g_prof_on = false;
-ProfPair g_prof[256];
+// benchmark hooks: while enabled, every phase of a call is bracketed by two events on the
+// call's stream, so that the phases can be timed in place inside a larger timed region
+struct ProfSpan { hipEvent_t a, b; int phase; long launches; };
+int g_prof_on = 0;   // 0 off, 1 the scaling-sweep run only, 2 every phase
+constexpr int PROF_MAX = 4096;
+ProfSpan g_prof[PROF_MAX];
 int g_prof_n = 0;
+
+struct PhaseTimer {
+    ProfSpan *sp = nullptr;
+    hipStream_t st;
+    PhaseTimer(int phase, hipStream_t st_) : st(st_)
+    {
+        if (g_prof_on < (phase == SKA_PH_SCALING ? 1 : 2) || g_prof_n >= PROF_MAX) return;
+        ProfSpan *c = &g_prof[g_prof_n];
+        if (hipEventCreate(&c->a) != hipSuccess) return;
+        if (hipEventCreate(&c->b) != hipSuccess) { (void)hipEventDestroy(c->a); return; }
+        c->phase = phase;
+        c->launches = 0;
+        (void)hipEventRecord(c->a, st);
+        sp = c;
+        ++g_prof_n;
+    }
+    void launched(long n = 1) { if (sp) sp->launches += n; }
+    void end() { if (sp) { (void)hipEventRecord(sp->b, st); sp = nullptr; } }
+    ~PhaseTimer() { end(); }
+};
 
 #define SKA_TRY(x)                      \
     do {                                \
@@ -1362,7 +1385,11 @@ int fwd_impl(const Problem &p, const void *Qin, const void *K, const void *V, vo
     // Q below is the score operand: for bf16 storage the prescaled copy, with c2 = 1
     const void *Q = nullptr;
     float c2 = 0.f;
-    SKA_TRY((make_scores_operand<T>(p, Qin, ws, &Q, &c2, st)));
+    {
+        PhaseTimer pt(SKA_PH_PRESCALE, st);
+        SKA_TRY((make_scores_operand<T>(p, Qin, ws, &Q, &c2, st)));
+        pt.launched(sizeof(T) == 2 ? 1 : 0);
+    }
     const int N = p.N(), L = p.L, Lp = p.Lp();
     const long us = 6L * Lp;
     auto vec = [&](int k) { return Vec{UV + (long)k * Lp, us}; };
@@ -1380,41 +1407,48 @@ int fwd_impl(const Problem &p, const void *Qin, const void *K, const void *V, vo
         if (hipGetLastError() != hipSuccess) return SKA_EHIP;
     }
     bool first = true;
-    ProfPair *pp = nullptr;
+    PhaseTimer pt_first(SKA_PH_FIRST, st);   // the first launch is the other (max-tracking) kernel
+    PhaseTimer *pt_run = nullptr;
+    alignas(PhaseTimer) unsigned char pt_run_mem[sizeof(PhaseTimer)];
     // half-step: out slot <- -LSE over the band of (S + yt); prev slot only stabilises
     auto half = [&](bool row, int yslot, int prevslot, int outslot) -> int {
         SweepArgs a = base;
         a.X = row ? Q : K; a.Y = row ? K : Q;
         a.yt = vec(yslot); a.xs = vec(prevslot); a.out_vec = vout(outslot);
         SKA_TRY((sweep<T, D>(first ? M_LSE_FIRST : M_LSE, a, N, st)));
-        if (first && g_prof_on && g_prof_n < 256) {
-            pp = &g_prof[g_prof_n];
-            if (hipEventCreate(&pp->a) != hipSuccess || hipEventCreate(&pp->b) != hipSuccess) return SKA_EHIP;
-            (void)hipEventRecord(pp->a, st);
-            pp->launches = -1;   // the first launch is the other (max-tracking) kernel
-            ++g_prof_n;
-        }
-        if (pp) ++pp->launches;
-        first = false;
+        if (first) pt_first.launched();
+        else pt_run->launched();
         if (p.dustbin) {
             hipLaunchKernelGGL(dustbin_kernel, dim3(N), dim3(1024), 0, st, vec(yslot), Vec{nullptr, 0},
                                Vec{nullptr, 0}, vout(outslot), L, p.sdb);
             if (hipGetLastError() != hipSuccess) return SKA_EHIP;
         }
+        if (first) {   // the run of identical scaling sweeps starts after the first launch
+            first = false;
+            pt_first.end();
+            pt_run = new (pt_run_mem) PhaseTimer(SKA_PH_SCALING, st);
+        }
         return SKA_OK;
     };
-    for (int t = 0; t < p.T; ++t) {
-        SKA_TRY(half(true, 1, 0, 0));
-        SKA_TRY(half(false, 0, 1, 1));
-    }
-    SKA_TRY(half(true, 1, 0, 2));    // u1 from v0
-    SKA_TRY(half(false, 2, 1, 3));   // v1 from u1
-    SKA_TRY(half(true, 3, 2, 4));    // u2 from v1
-    SKA_TRY(half(false, 4, 3, 5));   // v2 from u2
-    if (pp) (void)hipEventRecord(pp->b, st);
+    auto halves = [&]() -> int {
+        for (int t = 0; t < p.T; ++t) {
+            SKA_TRY(half(true, 1, 0, 0));
+            SKA_TRY(half(false, 0, 1, 1));
+        }
+        SKA_TRY(half(true, 1, 0, 2));    // u1 from v0
+        SKA_TRY(half(false, 2, 1, 3));   // v1 from u1
+        SKA_TRY(half(true, 3, 2, 4));    // u2 from v1
+        SKA_TRY(half(false, 4, 3, 5));   // v2 from u2
+        return SKA_OK;
+    };
+    const int rc_halves = halves();
+    if (pt_run) pt_run->~PhaseTimer();
+    SKA_TRY(rc_halves);
     // output map with the terminal plan
+    PhaseTimer pt_out(SKA_PH_OUTPUT, st);
     SweepArgs a = base;
     a.X = Q; a.Y = K; a.Pay = V; a.out_mat = O; a.xs = vec(4); a.yt = vec(5);
+    pt_out.launched();
     return sweep<T, D>(M_APPLY, a, N, st);
 }
 
@@ -1427,7 +1461,11 @@ int bwd_impl(const Problem &p, const void *Qin, const void *K, const void *V, co
     // c2 = 1); it also serves as the payload of the dK sweep, whose output scale absorbs it
     const void *Q = nullptr;
     float c2 = 0.f;
-    SKA_TRY((make_scores_operand<T>(p, Qin, reinterpret_cast<unsigned char *>(ws) + ws_vec_bytes(p), &Q, &c2, st)));
+    {
+        PhaseTimer pt(SKA_PH_PRESCALE, st);
+        SKA_TRY((make_scores_operand<T>(p, Qin, reinterpret_cast<unsigned char *>(ws) + ws_vec_bytes(p), &Q, &c2, st)));
+        pt.launched(sizeof(T) == 2 ? 1 : 0);
+    }
     const int N = p.N(), L = p.L, Lp = p.Lp();
     const long us = 6L * Lp, ldw = p.ldw();
     auto uv = [&](int k) { return Vec{UV + (long)k * Lp, us}; };
@@ -1447,6 +1485,8 @@ int bwd_impl(const Problem &p, const void *Qin, const void *K, const void *V, co
     const dim3 vgrid((Lp + 255) / 256, N);
 
     // g_u = <dO_i, O_i> (= (P22 . Z) 1); dustbin row has dO = 0
+    PhaseTimer pt_gu(SKA_PH_ROWDOT, st);
+    pt_gu.launched();
     hipLaunchKernelGGL((rowdot_kernel<T, D>), vgrid, dim3(256), 0, st, reinterpret_cast<const T *>(G),
                        reinterpret_cast<const T *>(O), gu, ldw, L, Lp);
     if (hipGetLastError() != hipSuccess) return SKA_EHIP;
@@ -1454,8 +1494,11 @@ int bwd_impl(const Problem &p, const void *Qin, const void *K, const void *V, co
         hipLaunchKernelGGL(fill_kernel, dim3((N + 255) / 256), dim3(256), 0, st, vb2 + L, 1L, ldw, N, 0.f);
         if (hipGetLastError() != hipSuccess) return SKA_EHIP;
     }
+    pt_gu.end();
     // dV_j = sum_i P22_ij dO_i ; vbar2_j = <V_j, dV_j>  (column-oriented)
     {
+        PhaseTimer pt(SKA_PH_DV, st);
+        pt.launched();
         SweepArgs a = base;
         a.X = K; a.Y = Q; a.Pay = G; a.out_mat = dV; a.xs = uv(5); a.yt = uv(4);
         a.dot_mat = V; a.dot_out = wo(vb2);
@@ -1474,12 +1517,18 @@ int bwd_impl(const Problem &p, const void *Qin, const void *K, const void *V, co
         }
         return SKA_OK;
     };
-    SKA_TRY(matvec(true, uv(4), uv(5), vb2, gu, wo(ub2)));        // ubar2 = g_u - P22 vbar2
-    SKA_TRY(matvec(false, uv(3), uv(4), ub2, nullptr, wo(vb1)));  // vbar1 = -(P21)^T ubar2
-    SKA_TRY(matvec(true, uv(2), uv(3), vb1, nullptr, wo(ub1)));   // ubar1 = -P11 vbar1
-    if (eta0) {                                               // vbar0 = -(P10)^T ubar1
-        SKA_TRY(matvec(false, uv(1), uv(2), ub1, nullptr, VecOut{eta0, (long)Lp}));
+    {
+        PhaseTimer pt(SKA_PH_MATVEC, st);
+        pt.launched(eta0 ? 4 : 3);
+        SKA_TRY(matvec(true, uv(4), uv(5), vb2, gu, wo(ub2)));        // ubar2 = g_u - P22 vbar2
+        SKA_TRY(matvec(false, uv(3), uv(4), ub2, nullptr, wo(vb1)));  // vbar1 = -(P21)^T ubar2
+        SKA_TRY(matvec(true, uv(2), uv(3), vb1, nullptr, wo(ub1)));   // ubar1 = -P11 vbar1
+        if (eta0) {                                               // vbar0 = -(P10)^T ubar1
+            SKA_TRY(matvec(false, uv(1), uv(2), ub1, nullptr, VecOut{eta0, (long)Lp}));
+        }
     }
+    PhaseTimer pt_final(SKA_PH_FINAL, st);   // modifier packs and the two final sweeps
+    pt_final.launched(2);
     hipLaunchKernelGGL(packs_kernel, vgrid, dim3(256), 0, st, UV, Lp, ub2, vb2, vb1, ub1, ldw, rowp, colp, ldw);
     if (hipGetLastError() != hipSuccess) return SKA_EHIP;
     // one-reference final sweeps
@@ -1563,29 +1612,37 @@ int sinkhorn_attn_bwd(const void *Q, const void *K, const void *V, const void *O
 
 int sinkhorn_attn_profile_enable(int on)
 {
-    g_prof_on = on != 0;
+    g_prof_on = on < 0 ? 0 : (on > 2 ? 2 : on);
     return SKA_OK;
 }
 
-int sinkhorn_attn_profile_read(double *elapsed_ms, long *launches)
+int sinkhorn_attn_profile_read_phases(double *elapsed_ms, long *launches)
 {
     if (!elapsed_ms || !launches) return SKA_EINVAL;
-    double ms = 0.0;
-    long n = 0;
+    for (int k = 0; k < SKA_PH_COUNT; ++k) { elapsed_ms[k] = 0.0; launches[k] = 0; }
     int rc = SKA_OK;
     for (int i = 0; i < g_prof_n; ++i) {
         float t = 0.f;
         if (hipEventSynchronize(g_prof[i].b) != hipSuccess ||
             hipEventElapsedTime(&t, g_prof[i].a, g_prof[i].b) != hipSuccess)
             rc = SKA_EHIP;
-        ms += t;
-        n += g_prof[i].launches;
+        elapsed_ms[g_prof[i].phase] += t;
+        launches[g_prof[i].phase] += g_prof[i].launches;
         (void)hipEventDestroy(g_prof[i].a);
         (void)hipEventDestroy(g_prof[i].b);
     }
     g_prof_n = 0;
-    *elapsed_ms = ms;
-    *launches = n;
+    return rc;
+}
+
+int sinkhorn_attn_profile_read(double *elapsed_ms, long *launches)
+{
+    if (!elapsed_ms || !launches) return SKA_EINVAL;
+    double ms[SKA_PH_COUNT];
+    long n[SKA_PH_COUNT];
+    const int rc = sinkhorn_attn_profile_read_phases(ms, n);
+    *elapsed_ms = ms[SKA_PH_SCALING];
+    *launches = n[SKA_PH_SCALING];
     return rc;
 }
 

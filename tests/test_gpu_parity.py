@@ -141,3 +141,33 @@ def test_error_codes_on_device():
     with pytest.raises(ska.SinkhornAttnError) as e:
         ska.sinkhorn_attn_fwd(x, x, x, 4, 2, eps=0.0)
     assert e.value.status == -1
+
+
+def test_profile_hooks_count_launches():
+    """Benchmark hooks: phase spans bracket the documented numbers of sweep launches."""
+    import torch
+
+    import paper_2605_08123_amd as ska
+    w = small("prof", 500, 64, 40, 5, "bf16")
+    arrays = make_inputs(w, 9)
+    ska.sinkhorn_attn_profile_read_phases()          # forget anything recorded earlier
+    ska.sinkhorn_attn_profile_enable(2)
+    try:
+        run_gpu(w, arrays)
+    finally:
+        ska.sinkhorn_attn_profile_enable(0)
+    ph = ska.sinkhorn_attn_profile_read_phases()
+    want = {"prescale": 2, "first_half_step": 1, "scaling_sweeps": 2 * w.T + 3, "output_map": 1,
+            "rowdot": 1, "dV": 1, "matvec_chain": 3, "final_sweeps": 2}
+    assert {k: v[1] for k, v in ph.items()} == want
+    assert all(v[0] >= 0.0 for v in ph.values()) and ph["scaling_sweeps"][0] > 0.0
+    # level 1 keeps the scaling-sweep span only; a read empties the record
+    ska.sinkhorn_attn_profile_enable(1)
+    try:
+        run_gpu(w, arrays)
+    finally:
+        ska.sinkhorn_attn_profile_enable(0)
+    ms, n = ska.sinkhorn_attn_profile_read()
+    assert n == 2 * w.T + 3 and ms > 0.0
+    assert all(v == (0.0, 0) for v in ska.sinkhorn_attn_profile_read_phases().values())
+    torch.cuda.synchronize()
