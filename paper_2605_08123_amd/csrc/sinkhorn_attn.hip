@@ -77,6 +77,7 @@ struct SweepArgs {
     float sdb2;       // dustbin score * log2(e)
     int nbp;          // workgroups per problem
     int nb_total;
+    int rev;          // walk each XCD's share of the blocks backwards (alternates between launches)
 };
 
 // ------------------------------------------------------------------ element traits
@@ -357,7 +358,7 @@ __global__ __launch_bounds__(NTHREADS) void sweep_kernel(const SweepArgs a)
     // give each XCD one contiguous eighth of the (problem, block) sequence; neighbours
     // that share band rows then meet in the same L2.
     const int chunk = (a.nb_total + 7) >> 3;
-    const int lb = (blockIdx.x & 7) * chunk + (blockIdx.x >> 3);
+    const int lb = (blockIdx.x & 7) * chunk + (a.rev ? chunk - 1 - (int)(blockIdx.x >> 3) : (int)(blockIdx.x >> 3));
     if (lb >= a.nb_total) return;
     const int n = lb / a.nbp;
     const int o_blk = (lb % a.nbp) * BM;
@@ -616,7 +617,7 @@ __global__ __launch_bounds__(NTHREADS) void vsweep_kernel(const SweepArgs a)
     __shared__ float red[NWAVES];
 
     const int chunk = (a.nb_total + 7) >> 3;
-    const int lb = (blockIdx.x & 7) * chunk + (blockIdx.x >> 3);
+    const int lb = (blockIdx.x & 7) * chunk + (a.rev ? chunk - 1 - (int)(blockIdx.x >> 3) : (int)(blockIdx.x >> 3));
     if (lb >= a.nb_total) return;
     const int n = lb / a.nbp;
     const int o_blk = (lb % a.nbp) * BM;
@@ -863,7 +864,7 @@ __global__ __launch_bounds__(NTHREADS) void msweep_kernel(const SweepArgs a)
     __shared__ float red[NWAVES];
 
     const int chunk = (a.nb_total + 7) >> 3;
-    const int lb = (blockIdx.x & 7) * chunk + (blockIdx.x >> 3);
+    const int lb = (blockIdx.x & 7) * chunk + (a.rev ? chunk - 1 - (int)(blockIdx.x >> 3) : (int)(blockIdx.x >> 3));
     if (lb >= a.nb_total) return;
     const int n = lb / a.nbp;
     const int o_blk = (lb % a.nbp) * BM;
@@ -1407,6 +1408,7 @@ int fwd_impl(const Problem &p, const void *Qin, const void *K, const void *V, vo
         if (hipGetLastError() != hipSuccess) return SKA_EHIP;
     }
     bool first = true;
+    int nlaunch = 0;
     PhaseTimer pt_first(SKA_PH_FIRST, st);   // the first launch is the other (max-tracking) kernel
     PhaseTimer *pt_run = nullptr;
     alignas(PhaseTimer) unsigned char pt_run_mem[sizeof(PhaseTimer)];
@@ -1415,6 +1417,9 @@ int fwd_impl(const Problem &p, const void *Qin, const void *K, const void *V, vo
         SweepArgs a = base;
         a.X = row ? Q : K; a.Y = row ? K : Q;
         a.yt = vec(yslot); a.xs = vec(prevslot); a.out_vec = vout(outslot);
+        // successive sweeps walk the blocks in opposite directions: a sweep then starts on
+        // the rows its predecessor touched last, which are still in L2
+        a.rev = nlaunch++ & 1;
         SKA_TRY((sweep<T, D>(first ? M_LSE_FIRST : M_LSE, a, N, st)));
         if (first) pt_first.launched();
         else pt_run->launched();
@@ -1448,6 +1453,7 @@ int fwd_impl(const Problem &p, const void *Qin, const void *K, const void *V, vo
     PhaseTimer pt_out(SKA_PH_OUTPUT, st);
     SweepArgs a = base;
     a.X = Q; a.Y = K; a.Pay = V; a.out_mat = O; a.xs = vec(4); a.yt = vec(5);
+    a.rev = nlaunch & 1;
     pt_out.launched();
     return sweep<T, D>(M_APPLY, a, N, st);
 }
@@ -1483,6 +1489,7 @@ int bwd_impl(const Problem &p, const void *Qin, const void *K, const void *V, co
     base.c2 = c2;
     base.dustbin = p.dustbin; base.sdb2 = p.sdb * LOG2E;
     const dim3 vgrid((Lp + 255) / 256, N);
+    int nlaunch = 0;   // successive sweeps walk the blocks in opposite directions (L2 reuse)
 
     // g_u = <dO_i, O_i> (= (P22 . Z) 1); dustbin row has dO = 0
     PhaseTimer pt_gu(SKA_PH_ROWDOT, st);
@@ -1502,6 +1509,7 @@ int bwd_impl(const Problem &p, const void *Qin, const void *K, const void *V, co
         SweepArgs a = base;
         a.X = K; a.Y = Q; a.Pay = G; a.out_mat = dV; a.xs = uv(5); a.yt = uv(4);
         a.dot_mat = V; a.dot_out = wo(vb2);
+        a.rev = nlaunch++ & 1;
         SKA_TRY((sweep<T, D>(M_APPLY, a, N, st)));
     }
     // reverse recurrences of Prop. 1, each one band mat-vec with a staircase factor
@@ -1510,6 +1518,7 @@ int bwd_impl(const Problem &p, const void *Qin, const void *K, const void *V, co
         SweepArgs a = base;
         a.X = row ? Q : K; a.Y = row ? K : Q;
         a.xs = xs; a.yt = yt; a.w = wv(w); a.pre = Vec{pre, ldw}; a.out_vec = out;
+        a.rev = nlaunch++ & 1;
         SKA_TRY((sweep<T, D>(M_MATVEC, a, N, st)));
         if (p.dustbin) {
             hipLaunchKernelGGL(dustbin_kernel, dim3(N), dim3(1024), 0, st, yt, wv(w), xs, out, L, p.sdb);
@@ -1536,6 +1545,7 @@ int bwd_impl(const Problem &p, const void *Qin, const void *K, const void *V, co
         SweepArgs a = base;
         a.X = Q; a.Y = K; a.A = G; a.Bm = V; a.out_mat = dQ; a.xs = uv(4); a.yt = uv(5);
         a.po = rowp; a.qt = colp; a.ldp = ldw;
+        a.rev = nlaunch++ & 1;
         SKA_TRY((sweep<T, D>(M_FINAL, a, N, st)));
     }
     {
@@ -1544,6 +1554,7 @@ int bwd_impl(const Problem &p, const void *Qin, const void *K, const void *V, co
         a.po = colp; a.qt = rowp; a.ldp = ldw;
         // payload rows are Qs = (cs log2 e) Q when prescaled: cs sum Sbar^T Q = ln 2 sum Sbar^T Qs
         if (sizeof(T) == 2) a.cs = LN2;
+        a.rev = nlaunch++ & 1;
         SKA_TRY((sweep<T, D>(M_FINAL, a, N, st)));
     }
     return SKA_OK;
