@@ -67,6 +67,8 @@ struct SweepArgs {
     VecOut out_vec;   // LSE / MATVEC result
     const float4 *po; // FINAL: owner-side modifier pack   [N][ldp]
     const float4 *qt; // FINAL: other-side modifier pack   [N][ldp]
+    const void *poB;  // FINAL on the ring kernel: owner-side pack as 16 bf16 columns  [N][ldp][16]
+    const void *qtA;  // FINAL on the ring kernel: other-side pack as 16 bf16 columns  [N][ldp][16]
     long ldp;
     const void *dot_mat;  // APPLY: if set, dot_out_o = <dot_mat_o, out_o> (fp32 accumulators)
     VecOut dot_out;
@@ -831,7 +833,12 @@ __global__ __launch_bounds__(NTHREADS) void vsweep_kernel(const SweepArgs a)
 // wavefront w is kbase + s + w.  A ring slot holds the other-side score rows, the second
 // streamed matrix (payload for M_APPLY, the other-side factor of Z for M_FINAL), the staged
 // potentials and, for M_FINAL, the other-side modifier pack.  Tiles are row-major in LDS
-// with 16 bytes of padding per row; the second product needs its streamed operand with the
+// with 16 bytes of padding per row.  The four rank-1 modifier terms of Prop. 2 are not VALU
+// work: each side's pack is written as 16 bf16 columns (every fp32 value split into a high
+// and a low bf16 part; per term the three products hi*hi, hi*lo, lo*hi, the owner side
+// negated), which extend the Z product by one K = 16 MFMA step: its result is
+// Z - sum_k po_k qt_k directly.  The other side's 32 bytes per row sit in the padding of the
+// row in the two tiles.  The second product needs its streamed operand with the
 // band index contiguous, which the transposing LDS read (ds_read_b64_tr_b16) delivers from
 // the row-major tile: within 16 lanes, lane i receives element (i & 3) of the 8-byte pieces
 // addressed by lanes (i >> 2) + 4 e, e = 0..3.
@@ -843,8 +850,9 @@ template <int D, int MODE, int FR> struct MRing {
     static constexpr int OFF_Y = 0;
     static constexpr int OFF_B = TILE;                 // payload (M_APPLY) or Z factor (M_FINAL)
     static constexpr int OFF_VY = 2 * TILE;
-    static constexpr int OFF_VQ = OFF_VY + TT * 4;
-    static constexpr int SLOT = OFF_VQ + (MODE == M_FINAL ? TT * 16 : 0);
+    static constexpr int OFF_PK = D * 2;               // M_FINAL: the 16 bytes of padding of a row of either
+                                                       // tile hold half of the row's 16 pack columns
+    static constexpr int SLOT = OFF_VY + TT * 4;
     static constexpr int BYTES = NSLOT * SLOT;
     static constexpr int CHUNKS = 32 * D * 2 / 16;     // 16-byte pieces of a tile in memory
     static constexpr int CPT = (CHUNKS + NTHREADS - 1) / NTHREADS;
@@ -896,7 +904,7 @@ __global__ __launch_bounds__(NTHREADS) void msweep_kernel(const SweepArgs a)
     // Rows beyond L are clamped: they compute garbage that is never stored.
     const int o_w = o_blk + wave * FR * 32;
     OwnerFrag<T, D> xf[FR], af[MODE == M_FINAL ? FR : 1];
-    float4 pof[FR];
+    bf16x8 pob[FR];   // M_FINAL: this lane's half of the owner row's 16 pack columns
     f32x16 outm[FR][D / 32];
 #pragma unroll
     for (int f = 0; f < FR; ++f) {
@@ -911,8 +919,11 @@ __global__ __launch_bounds__(NTHREADS) void msweep_kernel(const SweepArgs a)
                 af[f].v[s] = *reinterpret_cast<bf16x8 *>(&y);
             }
         }
-        pof[f] = make_float4(0, 0, 0, 0);
-        if constexpr (MODE == M_FINAL) pof[f] = a.po[n * a.ldp + oc];
+        if constexpr (MODE == M_FINAL) {
+            uint4 z = *reinterpret_cast<const uint4 *>(reinterpret_cast<const unsigned char *>(a.poB) +
+                                                       ((long)n * a.ldp + oc) * 32 + h * 16);
+            pob[f] = *reinterpret_cast<bf16x8 *>(&z);
+        }
 #pragma unroll
         for (int j = 0; j < D / 32; ++j)
 #pragma unroll
@@ -926,7 +937,7 @@ __global__ __launch_bounds__(NTHREADS) void msweep_kernel(const SweepArgs a)
 
     // one tile pair in flight between global memory and LDS (plain arrays: a struct holding
     // them ends up in scratch memory)
-    auto g_load = [&](uint4 (&gy)[RG::CPT], uint4 (&gb)[RG::CPT], float &gvy, float4 &gvq, int k) {
+    auto g_load = [&](uint4 (&gy)[RG::CPT], uint4 (&gb)[RG::CPT], float &gvy, uint4 &gpk, int k) {
 #pragma unroll
         for (int q = 0; q < RG::CPT; ++q) {
             int idx = tid + q * NTHREADS;
@@ -938,11 +949,17 @@ __global__ __launch_bounds__(NTHREADS) void msweep_kernel(const SweepArgs a)
         }
         const unsigned tv = (unsigned)min(max(k * TT + (tid & (TT - 1)), 0), L - 1);
         gvy = ytp[tv];
-        if constexpr (MODE == M_FINAL) gvq = a.qt[n * a.ldp + tv];
+        if constexpr (MODE == M_FINAL) {
+            // 64 pieces of 16 bytes per tile: every wavefront requests them (same addresses; a
+            // request under a condition would cost a full wait), the first one stores them
+            const unsigned tp = (unsigned)min(max(k * TT + ((tid & 63) >> 1), 0), L - 1);
+            gpk = *reinterpret_cast<const uint4 *>(reinterpret_cast<const unsigned char *>(a.qtA) +
+                                                   ((long)n * a.ldp + tp) * 32 + (tid & 1) * 16);
+        }
     };
     // rows outside [0, L) keep whatever the clamped fetch brought: their potential is -inf,
     // so their plan entries are exactly zero and finite data times zero adds nothing
-    auto s_store = [&](const uint4 (&gy)[RG::CPT], const uint4 (&gb)[RG::CPT], float gvy, float4 gvq, int j, int k) {
+    auto s_store = [&](const uint4 (&gy)[RG::CPT], const uint4 (&gb)[RG::CPT], float gvy, uint4 gpk, int j, int k) {
         unsigned char *sl = smem + (j & (RG::NSLOT - 1)) * RG::SLOT;
 #pragma unroll
         for (int q = 0; q < RG::CPT; ++q) {
@@ -956,15 +973,18 @@ __global__ __launch_bounds__(NTHREADS) void msweep_kernel(const SweepArgs a)
         if (tid < TT) {
             const bool live = k >= 0 && k * TT + tid < L;
             reinterpret_cast<float *>(sl + RG::OFF_VY)[tid] = live ? fmaf(gvy, LOG2E, m2) : -INFINITY;
-            if constexpr (MODE == M_FINAL)
-                reinterpret_cast<float4 *>(sl + RG::OFF_VQ)[tid] = live ? gvq : make_float4(0, 0, 0, 0);
+        }
+        if constexpr (MODE == M_FINAL) {
+            if (tid < 64)   // (rows outside the matrix: clamped data, multiplied by a zero plan entry)
+                *reinterpret_cast<uint4 *>(sl + ((tid & 1) ? RG::OFF_B : RG::OFF_Y) + (tid >> 1) * RG::ROWB +
+                                           RG::OFF_PK) = gpk;
         }
     };
 
     {
         uint4 fy[RG::LEAD + 1][RG::CPT], fb[RG::LEAD + 1][RG::CPT];
         float fvy[RG::LEAD + 1];
-        float4 fvq[RG::LEAD + 1];
+        uint4 fvq[RG::LEAD + 1];
 #pragma unroll
         for (int j = 0; j <= RG::LEAD; ++j) g_load(fy[j], fb[j], fvy[j], fvq[j], kbase + j);
 #pragma unroll
@@ -973,14 +993,13 @@ __global__ __launch_bounds__(NTHREADS) void msweep_kernel(const SweepArgs a)
     __syncthreads();
     uint4 ny[RG::CPT], nb[RG::CPT];
     float nvy = 0.f;
-    float4 nvq = make_float4(0, 0, 0, 0);
+    uint4 nvq = make_uint4(0, 0, 0, 0);
 
     // per-lane LDS offsets: fragment rows for the score / Z products, and the 8-byte pieces
     // this lane addresses in a transposing read (row 4h + (lane & 15) / 4 of a 16-row block,
     // columns 16 (lane / 16 & 1) + 4 (lane & 3), + 32 per output column tile)
     const int rd_a = c * RG::ROWB + h * 16;
     const int rd_t = (4 * h + ((lane & 15) >> 2)) * RG::ROWB + (16 * ((lane >> 4) & 1) + 4 * (lane & 3)) * 2;
-    const float c2 = a.c2;
     typedef __bf16 bf16x4v __attribute__((ext_vector_type(4)));
 
     for (int s = 0; s < S; ++s) {
@@ -1008,6 +1027,9 @@ __global__ __launch_bounds__(NTHREADS) void msweep_kernel(const SweepArgs a)
                 float4 v4 = *reinterpret_cast<const float4 *>(sl + RG::OFF_VY + (8 * q + 4 * h) * 4);
                 yv[4 * q + 0] = v4.x; yv[4 * q + 1] = v4.y; yv[4 * q + 2] = v4.z; yv[4 * q + 3] = v4.w;
             }
+            bf16x8 qpk;   // M_FINAL: row c of the tile, pack columns 8h .. 8h + 7
+            if constexpr (MODE == M_FINAL)
+                qpk = *reinterpret_cast<const bf16x8 *>(sl + (h ? RG::OFF_B : RG::OFF_Y) + c * RG::ROWB + RG::OFF_PK);
             bf16x8 pf[FR][2];
 #pragma unroll
             for (int f = 0; f < FR; ++f) {
@@ -1015,19 +1037,12 @@ __global__ __launch_bounds__(NTHREADS) void msweep_kernel(const SweepArgs a)
                 const bool interior = (of + 31 - t0 <= W) && (t0 + TT - 1 - of <= W);
                 // scores start from the staged potentials when the scale is folded into the operand
                 f32x16 acc = yv;
-                if (c2 != 1.f)
-#pragma unroll
-                    for (int r = 0; r < 16; ++r) acc[r] = 0.f;
 #pragma unroll
                 for (int ks = 0; ks < KS; ++ks)
                     acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(yfr[ks], xf[f].v[ks], acc, 0, 0, 0);
                 float e[16];
-                if (c2 != 1.f)
 #pragma unroll
-                    for (int r = 0; r < 16; ++r) e[r] = fmaf(acc[r], c2, yv[r]);
-                else
-#pragma unroll
-                    for (int r = 0; r < 16; ++r) e[r] = acc[r];
+                for (int r = 0; r < 16; ++r) e[r] = acc[r];
                 if (!interior) {   // also covers a tile that misses this fragment's band entirely
                     const int lo = of + c - W - t0 - 4 * h;
                     const unsigned span = 2u * (unsigned)W;
@@ -1047,17 +1062,9 @@ __global__ __launch_bounds__(NTHREADS) void msweep_kernel(const SweepArgs a)
 #pragma unroll
                     for (int ks = 0; ks < KS; ++ks)
                         z = __builtin_amdgcn_mfma_f32_32x32x16_bf16(bfr[ks], af[f].v[ks], z, 0, 0, 0);
+                    z = __builtin_amdgcn_mfma_f32_32x32x16_bf16(qpk, pob[f], z, 0, 0, 0);   // - sum_k po_k qt_k
 #pragma unroll
-                    for (int r = 0; r < 16; ++r) {
-                        const int tl = 8 * (r >> 2) + 4 * h + (r & 3);
-                        float4 q4 = *reinterpret_cast<const float4 *>(sl + RG::OFF_VQ + tl * 16);
-                        float md = z[r];
-                        md = fmaf(-pof[f].x, q4.x, md);
-                        md = fmaf(-pof[f].y, q4.y, md);
-                        md = fmaf(-pof[f].z, q4.z, md);
-                        md = fmaf(-pof[f].w, q4.w, md);
-                        e[r] *= md;
-                    }
+                    for (int r = 0; r < 16; ++r) e[r] *= z[r];
                 }
 #pragma unroll
                 for (int m = 0; m < 2; ++m)
@@ -1167,9 +1174,26 @@ __global__ void prescale_kernel(const __bf16 *src, __bf16 *dst, long n8, float s
 
 // Modifier packs of Prop. 2.  rowp = (1, ubar2, alpha, alpha*ubar1); colp = (vbar2, beta,
 // beta*vbar1, delta) with alpha = exp(u1-u2), beta = exp(v1-v2), delta = exp(v0-v2).
+// Written either as float4 (generic final sweep) or, for the ring kernel, as 16 bf16 columns per
+// index in two forms: "A" for the side that is streamed ([hi, lo, hi] per value) and "B" for
+// the side that owns the rows ([-hi, -hi, -lo]); an A row times a B row is then
+// -sum_k (hi hi + lo hi + hi lo) = -sum_k p_k q_k to about 2^-16 relative.  aug = rowA, rowB,
+// colA, colB, each [N][ldp][16].
+__device__ __forceinline__ void pack_cols(const float (&x)[4], __bf16 *A, __bf16 *B)
+{
+#pragma unroll
+    for (int k = 0; k < 4; ++k) {
+        const __bf16 hi = (__bf16)x[k];
+        const __bf16 lo = (__bf16)(x[k] - (float)hi);
+        A[3 * k + 0] = hi; A[3 * k + 1] = lo; A[3 * k + 2] = hi;
+        B[3 * k + 0] = (__bf16)(-(float)hi); B[3 * k + 1] = (__bf16)(-(float)hi); B[3 * k + 2] = (__bf16)(-(float)lo);
+    }
+#pragma unroll
+    for (int k = 12; k < 16; ++k) { A[k] = (__bf16)0.f; B[k] = (__bf16)0.f; }
+}
 __global__ void packs_kernel(const float *UV, int Lp, const float *ub2, const float *vb2,
                              const float *vb1, const float *ub1, long wstride, float4 *rowp,
-                             float4 *colp, long ldp)
+                             float4 *colp, __bf16 *aug, long ldp, long nldp)
 {
     const int n = blockIdx.y;
     const int i = blockIdx.x * blockDim.x + threadIdx.x;
@@ -1179,8 +1203,27 @@ __global__ void packs_kernel(const float *UV, int Lp, const float *ub2, const fl
     const float u2 = uv[4 * Lp + i], v2 = uv[5 * Lp + i];
     const float al = __expf(u1 - u2), be = __expf(v1 - v2), de = __expf(v0 - v2);
     const long w = n * wstride + i;
-    rowp[n * ldp + i] = make_float4(1.f, ub2[w], al, al * ub1[w]);
-    colp[n * ldp + i] = make_float4(vb2[w], be, be * vb1[w], de);
+    const float r[4] = {1.f, ub2[w], al, al * ub1[w]};
+    const float c[4] = {vb2[w], be, be * vb1[w], de};
+    if (!aug) {
+        rowp[n * ldp + i] = make_float4(r[0], r[1], r[2], r[3]);
+        colp[n * ldp + i] = make_float4(c[0], c[1], c[2], c[3]);
+    } else {
+        __align__(16) __bf16 A[16], B[16];
+        const long e = (n * ldp + i) * 16;
+        pack_cols(r, A, B);
+#pragma unroll
+        for (int q = 0; q < 2; ++q) {
+            reinterpret_cast<uint4 *>(aug + 0 * nldp * 16 + e)[q] = reinterpret_cast<const uint4 *>(A)[q];
+            reinterpret_cast<uint4 *>(aug + 1 * nldp * 16 + e)[q] = reinterpret_cast<const uint4 *>(B)[q];
+        }
+        pack_cols(c, A, B);
+#pragma unroll
+        for (int q = 0; q < 2; ++q) {
+            reinterpret_cast<uint4 *>(aug + 2 * nldp * 16 + e)[q] = reinterpret_cast<const uint4 *>(A)[q];
+            reinterpret_cast<uint4 *>(aug + 3 * nldp * 16 + e)[q] = reinterpret_cast<const uint4 *>(B)[q];
+        }
+    }
 }
 
 // Dustbin element of a sweep result: the extra row (column) is joined to every
@@ -1234,7 +1277,8 @@ size_t ws_qs_bytes(const Problem &p)
 }
 size_t ws_vec_bytes(const Problem &p)
 {
-    return (size_t)p.N() * p.ldw() * (WS_VECS * sizeof(float) + 2 * sizeof(float4));
+    // five vectors, two float4 packs, four packs of 16 bf16 columns
+    return (size_t)p.N() * p.ldw() * (WS_VECS * sizeof(float) + 2 * sizeof(float4) + 4 * 32);
 }
 size_t ws_bytes(const Problem &p) { return ws_vec_bytes(p) + ws_qs_bytes(p); }
 
@@ -1480,6 +1524,10 @@ int bwd_impl(const Problem &p, const void *Qin, const void *K, const void *V, co
           *ub1 = wf + 4 * N * ldw;
     float4 *rowp = reinterpret_cast<float4 *>(wf + (long)WS_VECS * N * ldw);
     float4 *colp = rowp + (long)N * ldw;
+    // the ring kernel takes the packs as bf16 columns (rowA, rowB, colA, colB)
+    constexpr bool AUG = (sizeof(T) == 2 && D <= 64);
+    const long nldp = (long)N * ldw;
+    __bf16 *aug = reinterpret_cast<__bf16 *>(colp + nldp);
     auto wv = [&](float *q) { return Vec{q, ldw}; };
     auto wo = [&](float *q) { return VecOut{q, ldw}; };
 
@@ -1538,13 +1586,15 @@ int bwd_impl(const Problem &p, const void *Qin, const void *K, const void *V, co
     }
     PhaseTimer pt_final(SKA_PH_FINAL, st);   // modifier packs and the two final sweeps
     pt_final.launched(2);
-    hipLaunchKernelGGL(packs_kernel, vgrid, dim3(256), 0, st, UV, Lp, ub2, vb2, vb1, ub1, ldw, rowp, colp, ldw);
+    hipLaunchKernelGGL(packs_kernel, vgrid, dim3(256), 0, st, UV, Lp, ub2, vb2, vb1, ub1, ldw, rowp, colp,
+                       AUG ? aug : nullptr, ldw, nldp);
     if (hipGetLastError() != hipSuccess) return SKA_EHIP;
     // one-reference final sweeps
     {
         SweepArgs a = base;
         a.X = Q; a.Y = K; a.A = G; a.Bm = V; a.out_mat = dQ; a.xs = uv(4); a.yt = uv(5);
         a.po = rowp; a.qt = colp; a.ldp = ldw;
+        a.poB = aug + 1 * nldp * 16; a.qtA = aug + 2 * nldp * 16;   // rows own, columns stream
         a.rev = nlaunch++ & 1;
         SKA_TRY((sweep<T, D>(M_FINAL, a, N, st)));
     }
@@ -1552,6 +1602,7 @@ int bwd_impl(const Problem &p, const void *Qin, const void *K, const void *V, co
         SweepArgs a = base;
         a.X = K; a.Y = Q; a.A = V; a.Bm = G; a.out_mat = dK; a.xs = uv(5); a.yt = uv(4);
         a.po = colp; a.qt = rowp; a.ldp = ldw;
+        a.poB = aug + 3 * nldp * 16; a.qtA = aug + 0 * nldp * 16;   // columns own, rows stream
         // payload rows are Qs = (cs log2 e) Q when prescaled: cs sum Sbar^T Q = ln 2 sum Sbar^T Qs
         if (sizeof(T) == 2) a.cs = LN2;
         a.rev = nlaunch++ & 1;
