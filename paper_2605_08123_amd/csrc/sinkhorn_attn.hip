@@ -844,7 +844,8 @@ __global__ __launch_bounds__(NTHREADS) void vsweep_kernel(const SweepArgs a)
 // addressed by lanes (i >> 2) + 4 e, e = 0..3.
 template <int D, int MODE, int FR> struct MRing {
     static constexpr int LEAD = FR * (NWAVES - 1);
-    static constexpr int NSLOT = 8;
+    static constexpr int NSLOT = LEAD + 2;             // exactly what the skew needs (5 or 8): LDS decides
+                                                       // how many workgroups share a CU
     static constexpr int ROWB = D * 2 + 16;
     static constexpr int TILE = 32 * ROWB;
     static constexpr int OFF_Y = 0;
@@ -960,7 +961,7 @@ __global__ __launch_bounds__(NTHREADS) void msweep_kernel(const SweepArgs a)
     // rows outside [0, L) keep whatever the clamped fetch brought: their potential is -inf,
     // so their plan entries are exactly zero and finite data times zero adds nothing
     auto s_store = [&](const uint4 (&gy)[RG::CPT], const uint4 (&gb)[RG::CPT], float gvy, uint4 gpk, int j, int k) {
-        unsigned char *sl = smem + (j & (RG::NSLOT - 1)) * RG::SLOT;
+        unsigned char *sl = smem + (j % RG::NSLOT) * RG::SLOT;
 #pragma unroll
         for (int q = 0; q < RG::CPT; ++q) {
             const int idx = tid + q * NTHREADS;
@@ -1010,7 +1011,7 @@ __global__ __launch_bounds__(NTHREADS) void msweep_kernel(const SweepArgs a)
         const int j = s + wave * FR;
         const int k = kbase + j;
         if (k >= 0 && k <= klast) {
-            const unsigned char *sl = smem + (j & (RG::NSLOT - 1)) * RG::SLOT;
+            const unsigned char *sl = smem + (j % RG::NSLOT) * RG::SLOT;
             const int t0 = k * TT;
             // this tile's fragments (score rows, Z rows) and staged potentials, read once for
             // all FR owner fragments
