@@ -170,7 +170,7 @@ def main() -> int:
                         "mfma_frac": fl * E / t / 1e12 / MFMA_PEAK_TFLOPS[dt_name]}
     alu_tflops = 2.0 * E / avg_s / 1e12
     out = {
-        "metric": "fwd+bwd tokens/sec at L=262144 d=64 W=256 T=20 R=2; % MFMA / HBM peak",
+        "metric": f"fwd+bwd tokens/sec at L={w.L} d={w.d} W={w.W} T={w.T} R={w.R}; % MFMA / HBM peak",
         "value": tokens_per_s, "unit": "tokens/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
         "ms_per_step": ms_per_step, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": dt_name, "data": "synthetic",

@@ -54,6 +54,9 @@ CONFIGS = {
                         dustbin_score=0.0, dist="alphabet"),
     "long": Workload("long", 3, 1, 4, 65536, 64, 256, 20, 2, 0.5, "bf16"),
     "paper": Workload("paper", 4, 1, 2, 262144, 64, 256, 20, 2, 0.5, "bf16"),
+    # the shape of the paper's own long-context run (half-band 1024, 15 base steps, one head):
+    # a second benchmark point, four times the band edges per token-head
+    "paper_w1024": Workload("paper_w1024", 5, 1, 1, 262144, 64, 1024, 15, 2, 0.5, "bf16"),
 }
 
 

@@ -39,7 +39,7 @@ def window_check(w, got, arrays, b, h, c0, c1):
         assert e <= TOL[w.dtype], (name, e)
 
 
-@pytest.mark.parametrize("name", ["paper", "long"])
+@pytest.mark.parametrize("name", ["paper", "long", "paper_w1024"])
 def test_full_size_windows(name):
     w = CONFIGS[name]
     print(f"\n[case] {w}", flush=True)
@@ -51,7 +51,8 @@ def test_full_size_windows(name):
     L = w.L
     window_check(w, got, arrays, 0, 0, 0, 2048)                    # true left end
     window_check(w, got, arrays, 0, w.H - 1, L // 2 - 1000, L // 2 + 1048)   # interior, unaligned
-    window_check(w, got, arrays, 0, w.H - 1, L - 2048, L)          # true right end
+    if w.W <= 256:   # (a window at W = 1024 is 86 k rows of 2049 edges: two of them are enough)
+        window_check(w, got, arrays, 0, w.H - 1, L - 2048, L)      # true right end
     # properties that hold at any size: unit column sums of P22 show up as sum_j dK_j = 0
     # (every row of the score cotangent sums to zero) and <dO, O> totals equal <V, dV> totals
     for h in range(w.H):
