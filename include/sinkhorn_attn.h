@@ -7,11 +7,12 @@
  *                                                                      (Eq. 1, Eq. 2)
  *   base        T steps (row half-step, then column half-step) from v = 0; the result
  *               (u0, v0) is a constant for differentiation              (Section 2.2)
- *   tail        R = 2 further steps giving (u1, v1), (u2, v2)            (Section 2.2)
- *   output      O_i = sum_j exp(S_ij + u2_i + v2_j) V_j, no renormalisation
+ *   tail        R further steps giving (u1, v1), ..., (uR, vR); R = 2 is the paper's
+ *               setting                                                 (Section 2.2)
+ *   output      O_i = sum_j exp(S_ij + uR_i + vR_j) V_j, no renormalisation
  *                                                                      (Section 2.2)
  *   backward    exact adjoint of the tail + output (Prop. 1), evaluated from the
- *               single plan P22 = exp(S + u2 + v2) and vector modifiers (Prop. 2)
+ *               single plan P_RR = exp(S + uR + vR) and vector modifiers (Prop. 2)
  *   dustbin     optional: one extra row d_q and column d_k joined to every token
  *               by an edge of constant score `dustbin_score`; all L+1 row and
  *               column targets are one; V at d_k is zero and the d_q output row is
@@ -25,12 +26,12 @@
  *   - Tensors Q, K, V, O, dO, dQ, dK, dV are [B, H, L, d], contiguous, row-major,
  *     of the element type `dtype` (SKA_F32: float; SKA_BF16: bfloat16).  All
  *     scaling vectors and all accumulation are fp32.
- *   - UV is [B, H, 6, Lp] fp32 with Lp = L + (dustbin ? 1 : 0), the six vectors
- *     ordered u0, v0, u1, v1, u2, v2 (natural-log potentials, ungauged; element
- *     L is the dustbin token when present).
+ *   - UV is [B, H, 2(R+1), Lp] fp32 with Lp = L + (dustbin ? 1 : 0), the vectors
+ *     ordered u0, v0, u1, v1, ..., uR, vR (natural-log potentials, ungauged;
+ *     element L is the dustbin token when present).
  *   - Return value: SKA_OK or a negative ska_status.  Arguments are checked
  *     before anything is launched; nothing is written on an argument error.
- *   - Supported: d in {32, 64, 128}; R == 2; any L >= 1, W >= 0 (W >= L-1 is the
+ *   - Supported: d in {32, 64, 128}; R in {1, 2, 3, 4}; any L >= 1, W >= 0 (W >= L-1 is the
  *     dense problem), T >= 0, eps > 0 and finite.
  */
 #ifndef SINKHORN_ATTN_H
@@ -47,7 +48,7 @@ typedef enum { SKA_F32 = 0, SKA_BF16 = 1 } ska_dtype;
 typedef enum {
     SKA_OK = 0,
     SKA_EINVAL = -1,       /* null required pointer, non-positive size, bad eps        */
-    SKA_EUNSUPPORTED = -2, /* R != 2, unsupported d, unknown dtype                      */
+    SKA_EUNSUPPORTED = -2, /* R outside 1..4, unsupported d, unknown dtype              */
     SKA_EWORKSPACE = -3,   /* workspace smaller than sinkhorn_attn_workspace_bytes()    */
     SKA_EHIP = -4          /* a HIP launch failed (hipGetLastError)                     */
 } ska_status;
@@ -61,10 +62,10 @@ size_t sinkhorn_attn_workspace_bytes(int B, int H, int L, int d, int W, int T, i
                                      int dtype);
 
 /*
- * Forward: stopped T-step base solve, R = 2 tail, plan-weighted V
+ * Forward: stopped T-step base solve, R-step tail, plan-weighted V
  * (Section 2.1-2.2, Eq. 1-2; Section 2.3 when dustbin != 0).
  *   in : Q, K, V [B,H,L,d]
- *   out: O [B,H,L,d]; UV [B,H,6,Lp] (all six vectors are written)
+ *   out: O [B,H,L,d]; UV [B,H,2(R+1),Lp] (all vectors are written)
  * workspace: 16-byte aligned scratch; bf16 storage needs at least B*H*L*d*2 bytes
  * (a copy of Q with the score scale folded in), fp32 storage needs none and accepts
  * NULL.  A buffer of sinkhorn_attn_workspace_bytes() always suffices.
@@ -77,7 +78,8 @@ int sinkhorn_attn_fwd(const void *Q, const void *K, const void *V, void *O, floa
 /*
  * Backward: exact VJP of the stopped-base surrogate for an arbitrary output
  * cotangent dO (Prop. 1), scheduled from the one reference plan P22 and the
- * modifiers alpha = exp(u1-u2), beta = exp(v1-v2), delta = exp(v0-v2) (Prop. 2).
+ * modifiers a_t = exp(u_t - u_R), b_t = exp(v_t - v_R) (Prop. 2; for R = 2: alpha = a_1,
+ * beta = b_1, delta = b_0).
  *   in : Q, K, V, O (as returned by the forward), dO [B,H,L,d]; UV from the forward
  *   out: dQ, dK, dV [B,H,L,d], overwritten
  *        eta0 [B,H,Lp] fp32 or NULL: the base cotangent vbar^(0) that the
@@ -102,16 +104,16 @@ int sinkhorn_attn_bwd(const void *Q, const void *K, const void *V, const void *O
  *     waits for the recorded events, returns per phase the summed elapsed milliseconds and
  *     the number of sweep launches they bracket, then forgets them.
  *   sinkhorn_attn_profile_read(&ms, &launches): the same, SKA_PH_SCALING only (the run of
- *     2T + 3 identical launches of the scaling sweep of Eq. 1-2 in every forward call).
+ *     2(T + R) - 1 identical launches of the scaling sweep of Eq. 1-2 in every forward call).
  */
 typedef enum {
     SKA_PH_PRESCALE = 0, /* bf16 storage: copy of Q with the score scale folded in (fwd and bwd) */
     SKA_PH_FIRST = 1,    /* first row half-step of the base solve (no previous iterate)   */
-    SKA_PH_SCALING = 2,  /* the other 2T + 3 half-steps (Eq. 1-2)                         */
+    SKA_PH_SCALING = 2,  /* the other 2(T + R) - 1 half-steps (Eq. 1-2)                   */
     SKA_PH_OUTPUT = 3,   /* O = P22 V (Section 2.2)                                      */
     SKA_PH_ROWDOT = 4,   /* g_u = <dO, O>                                                */
     SKA_PH_DV = 5,       /* dV = P22^T dO and vbar2 = <V, dV>                            */
-    SKA_PH_MATVEC = 6,   /* reverse recurrences of Prop. 1 (three band mat-vecs, +1 for eta0) */
+    SKA_PH_MATVEC = 6,   /* reverse recurrences of Prop. 1 (2R - 1 band mat-vecs, +1 for eta0) */
     SKA_PH_FINAL = 7,    /* modifier packs and the two one-reference final sweeps (Prop. 2)  */
     SKA_PH_COUNT = 8
 } ska_phase;

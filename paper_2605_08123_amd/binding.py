@@ -115,7 +115,7 @@ def _stream_ptr() -> int:
 def sinkhorn_attn_fwd(Q, K, V, W, T, R=2, eps=1.0, dustbin=False, dustbin_score=0.0, O=None, UV=None,
                       workspace=None):
     """Forward. Q, K, V: [B,H,L,d] CUDA tensors (float32 or bfloat16).
-    Returns (O [B,H,L,d], UV [B,H,6,L+dustbin] float32)."""
+    Returns (O [B,H,L,d], UV [B,H,2(R+1),L+dustbin] float32)."""
     B, H, L, d = Q.shape
     for n, x in (("Q", Q), ("K", K), ("V", V)):
         _check(x, (B, H, L, d), Q.dtype, n)
@@ -123,9 +123,9 @@ def sinkhorn_attn_fwd(Q, K, V, W, T, R=2, eps=1.0, dustbin=False, dustbin_score=
     if O is None:
         O = torch.empty_like(Q)
     if UV is None:
-        UV = torch.empty((B, H, 6, Lp), device=Q.device, dtype=torch.float32)
+        UV = torch.empty((B, H, 2 * (R + 1), Lp), device=Q.device, dtype=torch.float32)
     _check(O, (B, H, L, d), Q.dtype, "O")
-    _check(UV, (B, H, 6, Lp), torch.float32, "UV")
+    _check(UV, (B, H, 2 * (R + 1), Lp), torch.float32, "UV")
     if workspace is None:
         need = sinkhorn_attn_workspace_bytes(B, H, L, d, W, T, R, dustbin, _dtype_code(Q))
         workspace = torch.empty(max(need, 16), device=Q.device, dtype=torch.uint8)
@@ -145,7 +145,7 @@ def sinkhorn_attn_bwd(Q, K, V, O, dO, UV, W, T, R=2, eps=1.0, dustbin=False, dus
     for n, x in (("Q", Q), ("K", K), ("V", V), ("O", O), ("dO", dO)):
         _check(x, (B, H, L, d), Q.dtype, n)
     Lp = L + int(bool(dustbin))
-    _check(UV, (B, H, 6, Lp), torch.float32, "UV")
+    _check(UV, (B, H, 2 * (R + 1), Lp), torch.float32, "UV")
     dQ = torch.empty_like(Q) if dQ is None else dQ
     dK = torch.empty_like(Q) if dK is None else dK
     dV = torch.empty_like(Q) if dV is None else dV

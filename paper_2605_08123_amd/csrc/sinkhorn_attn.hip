@@ -42,6 +42,8 @@ constexpr int TT = 32;  // other-side rows per tile
 constexpr float LOG2E = 1.4426950408889634f;
 constexpr float LN2 = 0.6931471805599453f;
 
+constexpr int MAXR = 4;      // deepest differentiable tail
+constexpr int MAXNQ = 2;     // float4 groups of a modifier pack: 2R terms, four per group
 enum Mode { M_LSE_FIRST = 0, M_LSE = 1, M_MATVEC = 2, M_APPLY = 3, M_FINAL = 4 };
 
 struct Vec {          // one fp32 vector per problem
@@ -65,8 +67,9 @@ struct SweepArgs {
     Vec w;            // MATVEC weights on the other side
     Vec pre;          // MATVEC additive term on the owner side (may be null)
     VecOut out_vec;   // LSE / MATVEC result
-    const float4 *po; // FINAL: owner-side modifier pack   [N][ldp]
-    const float4 *qt; // FINAL: other-side modifier pack   [N][ldp]
+    const float4 *po; // FINAL: owner-side modifier pack   [N][ldp][nq]  (2R terms in nq groups of four)
+    const float4 *qt; // FINAL: other-side modifier pack   [N][ldp][nq]
+    int nq;           // 1 (R <= 2) or 2 (R <= 4)
     const void *poB;  // FINAL on the ring kernel: owner-side pack as 16 bf16 columns  [N][ldp][16]
     const void *qtA;  // FINAL on the ring kernel: other-side pack as 16 bf16 columns  [N][ldp][16]
     long ldp;
@@ -342,7 +345,7 @@ template <typename T, int D, int MODE> struct Stage {
     static constexpr int OFF_PAY = OFF_B + (HAS_B ? TL::RM_BYTES : 0);
     static constexpr int OFF_VY = OFF_PAY + (HAS_PAY ? TL::PT_BYTES : 0);
     static constexpr int OFF_VQ = OFF_VY + TT * 4;
-    static constexpr int BYTES = ((OFF_VQ + TT * 16) + 15) / 16 * 16;
+    static constexpr int BYTES = ((OFF_VQ + TT * 16 * MAXNQ) + 15) / 16 * 16;
 };
 
 template <typename T, int D, int MODE, int FR>
@@ -391,7 +394,7 @@ __global__ __launch_bounds__(NTHREADS) void sweep_kernel(const SweepArgs a)
     // owner-side fragments
     OwnerFrag<T, D> xf[FR];
     OwnerFrag<T, D> af[MODE == M_FINAL ? FR : 1];
-    float4 pof[FR];
+    float4 pof[FR][MAXNQ];
     int o_frag[FR];
 #pragma unroll
     for (int f = 0; f < FR; ++f) {
@@ -399,7 +402,10 @@ __global__ __launch_bounds__(NTHREADS) void sweep_kernel(const SweepArgs a)
         xf[f].load(Xb, o_frag[f] + c, L, h);
         if constexpr (MODE == M_FINAL) {
             af[f].load(reinterpret_cast<const T *>(a.A) + moff, o_frag[f] + c, L, h);
-            pof[f] = (o_frag[f] + c < L) ? a.po[n * a.ldp + o_frag[f] + c] : make_float4(0, 0, 0, 0);
+#pragma unroll
+            for (int g = 0; g < MAXNQ; ++g)
+                pof[f][g] = (o_frag[f] + c < L && g < a.nq) ? a.po[(n * a.ldp + o_frag[f] + c) * a.nq + g]
+                                                            : make_float4(0, 0, 0, 0);
         }
     }
 
@@ -427,7 +433,7 @@ __global__ __launch_bounds__(NTHREADS) void sweep_kernel(const SweepArgs a)
     // staging registers
     uint4 ry[TL::CPT], rb[ST::HAS_B ? TL::CPT : 1], rp[MODE == M_APPLY ? TL::CPT : 1];
     float rvy = 0.f;
-    float4 rvq = make_float4(0, 0, 0, 0);
+    float4 rvq[MAXNQ] = {make_float4(0, 0, 0, 0), make_float4(0, 0, 0, 0)};
 
     auto g_load = [&](int k) {
         const int t0 = k * TT;
@@ -437,7 +443,11 @@ __global__ __launch_bounds__(NTHREADS) void sweep_kernel(const SweepArgs a)
         if (tid < TT) {
             const int t = t0 + tid;
             rvy = (t < L) ? ytp[t] * LOG2E + m2 : -INFINITY;
-            if constexpr (MODE == M_FINAL) rvq = (t < L) ? a.qt[n * a.ldp + t] : make_float4(0, 0, 0, 0);
+            if constexpr (MODE == M_FINAL) {
+#pragma unroll
+                for (int g = 0; g < MAXNQ; ++g)
+                    rvq[g] = (t < L && g < a.nq) ? a.qt[(n * a.ldp + t) * a.nq + g] : make_float4(0, 0, 0, 0);
+            }
         }
     };
     auto s_store = [&](int buf) {
@@ -448,7 +458,10 @@ __global__ __launch_bounds__(NTHREADS) void sweep_kernel(const SweepArgs a)
         if constexpr (MODE == M_FINAL && TL::IS_BF16) tile_store_pay<T, D>(ry, s + ST::OFF_PAY);
         if (tid < TT) {
             reinterpret_cast<float *>(s + ST::OFF_VY)[tid] = rvy;
-            if constexpr (MODE == M_FINAL) reinterpret_cast<float4 *>(s + ST::OFF_VQ)[tid] = rvq;
+            if constexpr (MODE == M_FINAL) {
+#pragma unroll
+                for (int g = 0; g < MAXNQ; ++g) reinterpret_cast<float4 *>(s + ST::OFF_VQ)[tid * MAXNQ + g] = rvq[g];
+            }
         }
     };
 
@@ -517,12 +530,15 @@ __global__ __launch_bounds__(NTHREADS) void sweep_kernel(const SweepArgs a)
 #pragma unroll
                     for (int r = 0; r < 16; ++r) {
                         const int tl = 8 * (r >> 2) + 4 * h + (r & 3);
-                        float4 q4 = *reinterpret_cast<const float4 *>(s + ST::OFF_VQ + tl * 16);
                         float md = z[r];
-                        md = fmaf(-pof[f].x, q4.x, md);
-                        md = fmaf(-pof[f].y, q4.y, md);
-                        md = fmaf(-pof[f].z, q4.z, md);
-                        md = fmaf(-pof[f].w, q4.w, md);
+#pragma unroll
+                        for (int g = 0; g < MAXNQ; ++g) {   // (an absent group is all zeros)
+                            float4 q4 = *reinterpret_cast<const float4 *>(s + ST::OFF_VQ + (tl * MAXNQ + g) * 16);
+                            md = fmaf(-pof[f][g].x, q4.x, md);
+                            md = fmaf(-pof[f][g].y, q4.y, md);
+                            md = fmaf(-pof[f][g].z, q4.z, md);
+                            md = fmaf(-pof[f][g].w, q4.w, md);
+                        }
                         e[r] *= md;
                     }
                     tile_accum<T, D>(outm[f], TL::IS_BF16 ? s + ST::OFF_PAY : s + ST::OFF_Y, e, lane);
@@ -1173,14 +1189,19 @@ __global__ void prescale_kernel(const __bf16 *src, __bf16 *dst, long n8, float s
     reinterpret_cast<uint4 *>(dst)[i] = *reinterpret_cast<uint4 *>(&v);
 }
 
-// Modifier packs of Prop. 2.  rowp = (1, ubar2, alpha, alpha*ubar1); colp = (vbar2, beta,
-// beta*vbar1, delta) with alpha = exp(u1-u2), beta = exp(v1-v2), delta = exp(v0-v2).
-// Written either as float4 (generic final sweep) or, for the ring kernel, as 16 bf16 columns per
-// index in two forms: "A" for the side that is streamed ([hi, lo, hi] per value) and "B" for
-// the side that owns the rows ([-hi, -hi, -lo]); an A row times a B row is then
-// -sum_k (hi hi + lo hi + hi lo) = -sum_k p_k q_k to about 2^-16 relative.  aug = rowA, rowB,
-// colA, colB, each [N][ldp][16].
-__device__ __forceinline__ void pack_cols(const float (&x)[4], __bf16 *A, __bf16 *B)
+// Modifier packs of Prop. 2 for a tail of depth R.  With a_t = exp(u_t - u_R), b_t = exp(v_t - v_R)
+// the score cotangent is P_RR . [Z - sum_k row_k(i) col_k(j)] over 2R rank-1 terms, two per
+// tail step t = R ... 1:
+//     row = a_t,           col = b_t vbar_t        (the factor P_tt     . (1 vbar_t^T))
+//     row = a_t ubar_t,    col = b_{t-1}           (the factor P_t,t-1  . (ubar_t 1^T))
+// (R = 2: row = (1, ubar2, alpha, alpha ubar1), col = (vbar2, beta, beta vbar1, delta).)
+// Written as groups of four floats (generic final sweep) or, for the ring kernel (R <= 2), as
+// 16 bf16 columns per index in two forms: "A" for the side that is streamed ([hi, lo, hi] per
+// value) and "B" for the side that owns the rows ([-hi, -hi, -lo]); an A row times a B row is
+// then -sum_k (hi hi + lo hi + hi lo) = -sum_k row_k col_k to about 2^-16 relative.
+// aug = rowA, rowB, colA, colB, each [N][ldp][16].  Workspace vectors: vec 1 + 2(R - t) is
+// vbar_t, vec 2 + 2(R - t) is ubar_t.
+__device__ __forceinline__ void pack_cols(const float (&x)[2 * MAXR], __bf16 *A, __bf16 *B)
 {
 #pragma unroll
     for (int k = 0; k < 4; ++k) {
@@ -1192,23 +1213,36 @@ __device__ __forceinline__ void pack_cols(const float (&x)[4], __bf16 *A, __bf16
 #pragma unroll
     for (int k = 12; k < 16; ++k) { A[k] = (__bf16)0.f; B[k] = (__bf16)0.f; }
 }
-__global__ void packs_kernel(const float *UV, int Lp, const float *ub2, const float *vb2,
-                             const float *vb1, const float *ub1, long wstride, float4 *rowp,
-                             float4 *colp, __bf16 *aug, long ldp, long nldp)
+__global__ void packs_kernel(const float *UV, int Lp, int R, const float *vecs, long nldw, long wstride,
+                             float4 *rowp, float4 *colp, int nq, __bf16 *aug, long ldp, long nldp)
 {
     const int n = blockIdx.y;
     const int i = blockIdx.x * blockDim.x + threadIdx.x;
     if (i >= Lp) return;
-    const float *uv = UV + (long)n * 6 * Lp;
-    const float v0 = uv[1 * Lp + i], u1 = uv[2 * Lp + i], v1 = uv[3 * Lp + i];
-    const float u2 = uv[4 * Lp + i], v2 = uv[5 * Lp + i];
-    const float al = __expf(u1 - u2), be = __expf(v1 - v2), de = __expf(v0 - v2);
+    const float *uv = UV + (long)n * 2 * (R + 1) * Lp;
     const long w = n * wstride + i;
-    const float r[4] = {1.f, ub2[w], al, al * ub1[w]};
-    const float c[4] = {vb2[w], be, be * vb1[w], de};
+    const float uR = uv[(2 * R) * Lp + i], vR = uv[(2 * R + 1) * Lp + i];
+    float r[2 * MAXR], c[2 * MAXR];
+#pragma unroll
+    for (int k = 0; k < 2 * MAXR; ++k) { r[k] = 0.f; c[k] = 0.f; }
+#pragma unroll
+    for (int q = 0; q < MAXR; ++q) {   // q = R - t
+        if (q < R) {
+            const int t = R - q;
+            const float at = __expf(uv[(2 * t) * Lp + i] - uR), bt = __expf(uv[(2 * t + 1) * Lp + i] - vR);
+            const float bp = __expf(uv[(2 * t - 1) * Lp + i] - vR);
+            const float vb = vecs[(1 + 2 * q) * nldw + w], ub = vecs[(2 + 2 * q) * nldw + w];
+            r[2 * q] = at;          c[2 * q] = bt * vb;
+            r[2 * q + 1] = at * ub; c[2 * q + 1] = bp;
+        }
+    }
     if (!aug) {
-        rowp[n * ldp + i] = make_float4(r[0], r[1], r[2], r[3]);
-        colp[n * ldp + i] = make_float4(c[0], c[1], c[2], c[3]);
+#pragma unroll
+        for (int g = 0; g < MAXNQ; ++g)
+            if (g < nq) {
+                rowp[(n * ldp + i) * nq + g] = make_float4(r[4 * g], r[4 * g + 1], r[4 * g + 2], r[4 * g + 3]);
+                colp[(n * ldp + i) * nq + g] = make_float4(c[4 * g], c[4 * g + 1], c[4 * g + 2], c[4 * g + 3]);
+            }
     } else {
         __align__(16) __bf16 A[16], B[16];
         const long e = (n * ldp + i) * 16;
@@ -1270,7 +1304,9 @@ struct Problem {
     long ldw() const { return ((long)Lp() + 3) / 4 * 4; }  // stride of workspace vectors
 };
 
-constexpr int WS_VECS = 5;   // gu, vb2, ub2, vb1, ub1
+// workspace vectors of the backward: g_u, then vbar_R, ubar_R, vbar_{R-1}, ubar_{R-1}, ..., vbar_1, ubar_1
+inline int ws_vecs(int R) { return 1 + 2 * R; }
+inline int pack_groups(int R) { return (2 * R + 3) / 4; }
 // bf16 storage: both directions keep a prescaled copy of Q in the workspace
 size_t ws_qs_bytes(const Problem &p)
 {
@@ -1278,8 +1314,9 @@ size_t ws_qs_bytes(const Problem &p)
 }
 size_t ws_vec_bytes(const Problem &p)
 {
-    // five vectors, two float4 packs, four packs of 16 bf16 columns
-    return (size_t)p.N() * p.ldw() * (WS_VECS * sizeof(float) + 2 * sizeof(float4) + 4 * 32);
+    // 1 + 2R vectors, two packs of float4 groups, four packs of 16 bf16 columns
+    return (size_t)p.N() * p.ldw() *
+           (ws_vecs(p.R) * sizeof(float) + 2 * pack_groups(p.R) * sizeof(float4) + 4 * 32);
 }
 size_t ws_bytes(const Problem &p) { return ws_vec_bytes(p) + ws_qs_bytes(p); }
 
@@ -1306,7 +1343,7 @@ int check_common(const Problem &p)
     if (p.B < 1 || p.H < 1 || p.L < 1 || p.W < 0 || p.T < 0) return SKA_EINVAL;
     if (!(p.eps > 0.f) || !isfinite(p.eps) || !isfinite(p.sdb)) return SKA_EINVAL;
     if ((long)p.B * p.H > 65535) return SKA_EINVAL;
-    if (p.R != 2) return SKA_EUNSUPPORTED;
+    if (p.R < 1 || p.R > MAXR) return SKA_EUNSUPPORTED;
     if (p.d != 32 && p.d != 64 && p.d != 128) return SKA_EUNSUPPORTED;
     if (p.dtype != SKA_F32 && p.dtype != SKA_BF16) return SKA_EUNSUPPORTED;
     return SKA_OK;
@@ -1385,8 +1422,10 @@ template <typename T, int D> int sweep(int mode, const SweepArgs &a, int N, hipS
         if constexpr (sizeof(T) == 2 && D <= 64) return launch_msweep<D, M_APPLY, 2>(a, N, st);
         else return launch_sweep<T, D, M_APPLY, 1>(a, N, st);
     default:
-        if constexpr (sizeof(T) == 2 && D <= 64) return launch_msweep<D, M_FINAL, 1>(a, N, st);
-        else return launch_sweep<T, D, M_FINAL, 1>(a, N, st);
+        if constexpr (sizeof(T) == 2 && D <= 64) {
+            if (a.poB) return launch_msweep<D, M_FINAL, 1>(a, N, st);   // packs as bf16 columns (R <= 2)
+        }
+        return launch_sweep<T, D, M_FINAL, 1>(a, N, st);
     }
 }
 
@@ -1437,8 +1476,9 @@ int fwd_impl(const Problem &p, const void *Qin, const void *K, const void *V, vo
         pt.launched(sizeof(T) == 2 ? 1 : 0);
     }
     const int N = p.N(), L = p.L, Lp = p.Lp();
-    const long us = 6L * Lp;
-    auto vec = [&](int k) { return Vec{UV + (long)k * Lp, us}; };
+    const int R = p.R;
+    const long us = 2L * (R + 1) * Lp;
+    auto vec = [&](int k) { return Vec{UV + (long)k * Lp, us}; };   // slot 2t: u_t, slot 2t + 1: v_t
     auto vout = [&](int k) { return VecOut{UV + (long)k * Lp, us}; };
     SweepArgs base{};
     base.L = L; base.W = p.W < L ? p.W : L;   // |i-j| <= L-1 always: W >= L is the dense problem
@@ -1485,10 +1525,10 @@ int fwd_impl(const Problem &p, const void *Qin, const void *K, const void *V, vo
             SKA_TRY(half(true, 1, 0, 0));
             SKA_TRY(half(false, 0, 1, 1));
         }
-        SKA_TRY(half(true, 1, 0, 2));    // u1 from v0
-        SKA_TRY(half(false, 2, 1, 3));   // v1 from u1
-        SKA_TRY(half(true, 3, 2, 4));    // u2 from v1
-        SKA_TRY(half(false, 4, 3, 5));   // v2 from u2
+        for (int t = 1; t <= R; ++t) {
+            SKA_TRY(half(true, 2 * t - 1, 2 * t - 2, 2 * t));    // u_t from v_{t-1}
+            SKA_TRY(half(false, 2 * t, 2 * t - 1, 2 * t + 1));   // v_t from u_t
+        }
         return SKA_OK;
     };
     const int rc_halves = halves();
@@ -1497,7 +1537,7 @@ int fwd_impl(const Problem &p, const void *Qin, const void *K, const void *V, vo
     // output map with the terminal plan
     PhaseTimer pt_out(SKA_PH_OUTPUT, st);
     SweepArgs a = base;
-    a.X = Q; a.Y = K; a.Pay = V; a.out_mat = O; a.xs = vec(4); a.yt = vec(5);
+    a.X = Q; a.Y = K; a.Pay = V; a.out_mat = O; a.xs = vec(2 * R); a.yt = vec(2 * R + 1);
     a.rev = nlaunch & 1;
     pt_out.launched();
     return sweep<T, D>(M_APPLY, a, N, st);
@@ -1518,17 +1558,19 @@ int bwd_impl(const Problem &p, const void *Qin, const void *K, const void *V, co
         pt.launched(sizeof(T) == 2 ? 1 : 0);
     }
     const int N = p.N(), L = p.L, Lp = p.Lp();
-    const long us = 6L * Lp, ldw = p.ldw();
-    auto uv = [&](int k) { return Vec{UV + (long)k * Lp, us}; };
-    float *wf = reinterpret_cast<float *>(ws);
-    float *gu = wf, *vb2 = wf + 1 * N * ldw, *ub2 = wf + 2 * N * ldw, *vb1 = wf + 3 * N * ldw,
-          *ub1 = wf + 4 * N * ldw;
-    float4 *rowp = reinterpret_cast<float4 *>(wf + (long)WS_VECS * N * ldw);
-    float4 *colp = rowp + (long)N * ldw;
-    // the ring kernel takes the packs as bf16 columns (rowA, rowB, colA, colB)
-    constexpr bool AUG = (sizeof(T) == 2 && D <= 64);
+    const int R = p.R, nq = pack_groups(R);
+    const long us = 2L * (R + 1) * Lp, ldw = p.ldw();
     const long nldp = (long)N * ldw;
-    __bf16 *aug = reinterpret_cast<__bf16 *>(colp + nldp);
+    auto uv = [&](int k) { return Vec{UV + (long)k * Lp, us}; };   // slot 2t: u_t, slot 2t + 1: v_t
+    float *wf = reinterpret_cast<float *>(ws);
+    float *gu = wf;
+    auto vbar = [&](int t) { return wf + (1 + 2 * (R - t)) * nldp; };   // t = 1 ... R
+    auto ubar = [&](int t) { return wf + (2 + 2 * (R - t)) * nldp; };
+    float4 *rowp = reinterpret_cast<float4 *>(wf + (long)ws_vecs(R) * nldp);
+    float4 *colp = rowp + nldp * nq;
+    // the ring kernel (R <= 2) takes the packs as bf16 columns (rowA, rowB, colA, colB)
+    const bool AUG = (sizeof(T) == 2 && D <= 64 && R <= 2);
+    __bf16 *aug = reinterpret_cast<__bf16 *>(colp + nldp * nq);
     auto wv = [&](float *q) { return Vec{q, ldw}; };
     auto wo = [&](float *q) { return VecOut{q, ldw}; };
 
@@ -1546,18 +1588,18 @@ int bwd_impl(const Problem &p, const void *Qin, const void *K, const void *V, co
     hipLaunchKernelGGL((rowdot_kernel<T, D>), vgrid, dim3(256), 0, st, reinterpret_cast<const T *>(G),
                        reinterpret_cast<const T *>(O), gu, ldw, L, Lp);
     if (hipGetLastError() != hipSuccess) return SKA_EHIP;
-    if (p.dustbin) {   // vbar2 at the dustbin column is 0 because V there is 0
-        hipLaunchKernelGGL(fill_kernel, dim3((N + 255) / 256), dim3(256), 0, st, vb2 + L, 1L, ldw, N, 0.f);
+    if (p.dustbin) {   // vbar_R at the dustbin column is 0 because V there is 0
+        hipLaunchKernelGGL(fill_kernel, dim3((N + 255) / 256), dim3(256), 0, st, vbar(R) + L, 1L, ldw, N, 0.f);
         if (hipGetLastError() != hipSuccess) return SKA_EHIP;
     }
     pt_gu.end();
-    // dV_j = sum_i P22_ij dO_i ; vbar2_j = <V_j, dV_j>  (column-oriented)
+    // dV_j = sum_i P_RR,ij dO_i ; vbar_R,j = <V_j, dV_j>  (column-oriented)
     {
         PhaseTimer pt(SKA_PH_DV, st);
         pt.launched();
         SweepArgs a = base;
-        a.X = K; a.Y = Q; a.Pay = G; a.out_mat = dV; a.xs = uv(5); a.yt = uv(4);
-        a.dot_mat = V; a.dot_out = wo(vb2);
+        a.X = K; a.Y = Q; a.Pay = G; a.out_mat = dV; a.xs = uv(2 * R + 1); a.yt = uv(2 * R);
+        a.dot_mat = V; a.dot_out = wo(vbar(R));
         a.rev = nlaunch++ & 1;
         SKA_TRY((sweep<T, D>(M_APPLY, a, N, st)));
     }
@@ -1577,33 +1619,36 @@ int bwd_impl(const Problem &p, const void *Qin, const void *K, const void *V, co
     };
     {
         PhaseTimer pt(SKA_PH_MATVEC, st);
-        pt.launched(eta0 ? 4 : 3);
-        SKA_TRY(matvec(true, uv(4), uv(5), vb2, gu, wo(ub2)));        // ubar2 = g_u - P22 vbar2
-        SKA_TRY(matvec(false, uv(3), uv(4), ub2, nullptr, wo(vb1)));  // vbar1 = -(P21)^T ubar2
-        SKA_TRY(matvec(true, uv(2), uv(3), vb1, nullptr, wo(ub1)));   // ubar1 = -P11 vbar1
-        if (eta0) {                                               // vbar0 = -(P10)^T ubar1
-            SKA_TRY(matvec(false, uv(1), uv(2), ub1, nullptr, VecOut{eta0, (long)Lp}));
+        pt.launched(2 * R - 1 + (eta0 ? 1 : 0));
+        // ubar_R = g_u - P_RR vbar_R
+        SKA_TRY(matvec(true, uv(2 * R), uv(2 * R + 1), vbar(R), gu, wo(ubar(R))));
+        for (int t = R; t >= 1; --t) {
+            // vbar_{t-1} = -(P_t,t-1)^T ubar_t   (t = 1: the base cotangent, only on request)
+            if (t >= 2) SKA_TRY(matvec(false, uv(2 * t - 1), uv(2 * t), ubar(t), nullptr, wo(vbar(t - 1))));
+            else if (eta0) SKA_TRY(matvec(false, uv(1), uv(2), ubar(1), nullptr, VecOut{eta0, (long)Lp}));
+            // ubar_{t-1} = -P_{t-1,t-1} vbar_{t-1}
+            if (t >= 2) SKA_TRY(matvec(true, uv(2 * t - 2), uv(2 * t - 1), vbar(t - 1), nullptr, wo(ubar(t - 1))));
         }
     }
     PhaseTimer pt_final(SKA_PH_FINAL, st);   // modifier packs and the two final sweeps
     pt_final.launched(2);
-    hipLaunchKernelGGL(packs_kernel, vgrid, dim3(256), 0, st, UV, Lp, ub2, vb2, vb1, ub1, ldw, rowp, colp,
+    hipLaunchKernelGGL(packs_kernel, vgrid, dim3(256), 0, st, UV, Lp, R, wf, nldp, ldw, rowp, colp, nq,
                        AUG ? aug : nullptr, ldw, nldp);
     if (hipGetLastError() != hipSuccess) return SKA_EHIP;
     // one-reference final sweeps
     {
         SweepArgs a = base;
-        a.X = Q; a.Y = K; a.A = G; a.Bm = V; a.out_mat = dQ; a.xs = uv(4); a.yt = uv(5);
-        a.po = rowp; a.qt = colp; a.ldp = ldw;
-        a.poB = aug + 1 * nldp * 16; a.qtA = aug + 2 * nldp * 16;   // rows own, columns stream
+        a.X = Q; a.Y = K; a.A = G; a.Bm = V; a.out_mat = dQ; a.xs = uv(2 * R); a.yt = uv(2 * R + 1);
+        a.po = rowp; a.qt = colp; a.ldp = ldw; a.nq = nq;
+        if (AUG) { a.poB = aug + 1 * nldp * 16; a.qtA = aug + 2 * nldp * 16; }   // rows own, columns stream
         a.rev = nlaunch++ & 1;
         SKA_TRY((sweep<T, D>(M_FINAL, a, N, st)));
     }
     {
         SweepArgs a = base;
-        a.X = K; a.Y = Q; a.A = V; a.Bm = G; a.out_mat = dK; a.xs = uv(5); a.yt = uv(4);
-        a.po = colp; a.qt = rowp; a.ldp = ldw;
-        a.poB = aug + 3 * nldp * 16; a.qtA = aug + 0 * nldp * 16;   // columns own, rows stream
+        a.X = K; a.Y = Q; a.A = V; a.Bm = G; a.out_mat = dK; a.xs = uv(2 * R + 1); a.yt = uv(2 * R);
+        a.po = colp; a.qt = rowp; a.ldp = ldw; a.nq = nq;
+        if (AUG) { a.poB = aug + 3 * nldp * 16; a.qtA = aug + 0 * nldp * 16; }   // columns own, rows stream
         // payload rows are Qs = (cs log2 e) Q when prescaled: cs sum Sbar^T Q = ln 2 sum Sbar^T Qs
         if (sizeof(T) == 2) a.cs = LN2;
         a.rev = nlaunch++ & 1;

@@ -55,7 +55,7 @@ def check(w: Workload, seed=None, want_eta0=False, uv_atol=None):
     # (bf16 storage: the score scale is folded into a bf16 copy of Q, which perturbs every
     # score by a relative 2^-9; the potentials absorb that as an absolute error ~1e-2)
     uv_atol = uv_atol or (2e-4 if w.dtype == "f32" else 2e-2)
-    for t in ((1, 2) if w.T == 0 else (0, 1, 2)):
+    for t in range(1 if w.T == 0 else 0, w.R + 1):
         s_got = got["UV"][:, :, 2 * t] + got["UV"][:, :, 2 * t + 1]
         s_ref = ref["UV"][:, :, 2 * t] + ref["UV"][:, :, 2 * t + 1]
         assert np.abs(s_got - s_ref).max() < uv_atol, (t, np.abs(s_got - s_ref).max())
@@ -65,8 +65,8 @@ def check(w: Workload, seed=None, want_eta0=False, uv_atol=None):
     return got, ref
 
 
-def small(name, L, d, W, T, dtype, eps=1.0, B=1, H=1, **kw):
-    return Workload(name, 7, B, H, L, d, W, T, 2, eps, dtype, **kw)
+def small(name, L, d, W, T, dtype, eps=1.0, B=1, H=1, R=2, **kw):
+    return Workload(name, 7, B, H, L, d, W, T, R, eps, dtype, **kw)
 
 
 def test_tiny_config_fp32():
@@ -121,6 +121,27 @@ def test_dustbin_config_slice():
     check(CONFIGS["dustbin"].scaled(B=1, H=1, L=4096))
 
 
+@pytest.mark.parametrize("R", [1, 3, 4])
+@pytest.mark.parametrize("dtype,d", [("f32", 32), ("bf16", 64), ("bf16", 128)])
+def test_tail_depth(R, dtype, d):
+    """Tail depths other than the paper's R = 2 (Prop. 1 holds for any R): 2R rank-1 modifier
+    terms in the final sweeps, 2R - 1 mat-vecs in the reverse chain."""
+    check(small("tail", 520, d, 37, 5, dtype, eps=0.8, B=1, H=2, R=R), seed=40 + R)
+
+
+def test_tail_depth_dustbin():
+    check(small("taildb", 300, 64, 24, 4, "bf16", eps=0.9, R=3, dustbin=True, dustbin_score=-0.2), seed=17)
+    check(small("taildb", 300, 32, 24, 4, "f32", eps=0.9, R=1, dustbin=True, dustbin_score=0.4), seed=18)
+
+
+def test_eta0_general_tail():
+    w = small("eta", 300, 32, 20, 4, "f32", R=3)
+    got = run_gpu(w, make_inputs(w, 6), want_eta0=True)
+    q, k, v, g = make_inputs(w, 6)
+    ref = oracle.band(q[0, 0], k[0, 0], v[0, 0], g[0, 0], w.W, w.T, w.R, w.eps)
+    assert rel(got["eta0"][0, 0], ref["bars"][1]) < 1e-3
+
+
 def test_eta0_is_base_cotangent():
     w = small("eta", 400, 32, 20, 6, "f32")
     got = run_gpu(w, make_inputs(w, 5), want_eta0=True)
@@ -136,7 +157,7 @@ def test_error_codes_on_device():
     import paper_2605_08123_amd as ska
     x = torch.zeros((1, 1, 64, 32), device="cuda")
     with pytest.raises(ska.SinkhornAttnError) as e:
-        ska.sinkhorn_attn_fwd(x, x, x, 4, 2, R=3)
+        ska.sinkhorn_attn_fwd(x, x, x, 4, 2, R=5)
     assert e.value.status == -2
     with pytest.raises(ska.SinkhornAttnError) as e:
         ska.sinkhorn_attn_fwd(x, x, x, 4, 2, eps=0.0)
