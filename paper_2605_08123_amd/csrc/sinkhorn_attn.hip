@@ -1155,25 +1155,30 @@ __global__ void fill_kernel(float *p, long per, long stride, int nprob, float va
     if (i < per * nprob) p[(i / per) * stride + (i % per)] = val;
 }
 
-// g_o = <A_o, B_o> for o < L; g[L..Lp) = 0
+// g_o = <A_o, B_o> for o < L; g[L..Lp) = 0.  A row is read by D * sizeof(T) / 16 neighbouring
+// lanes, 16 bytes each (whole 128-byte lines per group of lanes), and reduced across them.
 template <typename T, int D>
 __global__ void rowdot_kernel(const T *A, const T *Bm, float *g, long gstride, int L, int Lp)
 {
+    constexpr int LPR = D * (int)sizeof(T) / 16;   // lanes per row: 4 ... 32, a power of two
+    constexpr int EPL = 16 / (int)sizeof(T);       // elements per lane
     const int n = blockIdx.y;
-    const int o = blockIdx.x * blockDim.x + threadIdx.x;
-    if (o >= Lp) return;
+    const long p = (long)blockIdx.x * blockDim.x + threadIdx.x;
+    const int o = (int)(p / LPR), sub = (int)(p % LPR);
     float acc = 0.f;
     if (o < L) {
-        const T *pa = A + ((long)n * L + o) * D, *pb = Bm + ((long)n * L + o) * D;
+        const T *pa = A + ((long)n * L + o) * D + sub * EPL, *pb = Bm + ((long)n * L + o) * D + sub * EPL;
 #pragma unroll
-        for (int k = 0; k < D; k += 4) {
+        for (int k = 0; k < EPL; k += 4) {
             float x[4], y[4];
             load4<T>(pa + k, x);
             load4<T>(pb + k, y);
             acc += x[0] * y[0] + x[1] * y[1] + x[2] * y[2] + x[3] * y[3];
         }
     }
-    g[n * gstride + o] = acc;
+#pragma unroll
+    for (int m = LPR / 2; m >= 1; m >>= 1) acc += __shfl_xor(acc, m);
+    if (sub == 0 && o < Lp) g[n * gstride + o] = acc;
 }
 
 // Qs = bf16(scale * Q): the score scale log2(e)/(eps sqrt d) folded into one operand once,
@@ -1585,7 +1590,9 @@ int bwd_impl(const Problem &p, const void *Qin, const void *K, const void *V, co
     // g_u = <dO_i, O_i> (= (P22 . Z) 1); dustbin row has dO = 0
     PhaseTimer pt_gu(SKA_PH_ROWDOT, st);
     pt_gu.launched();
-    hipLaunchKernelGGL((rowdot_kernel<T, D>), vgrid, dim3(256), 0, st, reinterpret_cast<const T *>(G),
+    constexpr int LPR = D * (int)sizeof(T) / 16;
+    hipLaunchKernelGGL((rowdot_kernel<T, D>), dim3(((long)Lp * LPR + 255) / 256, N), dim3(256), 0, st,
+                       reinterpret_cast<const T *>(G),
                        reinterpret_cast<const T *>(O), gu, ldw, L, Lp);
     if (hipGetLastError() != hipSuccess) return SKA_EHIP;
     if (p.dustbin) {   // vbar_R at the dustbin column is 0 because V there is 0
