@@ -31,7 +31,10 @@
  *     element L is the dustbin token when present).
  *   - Return value: SKA_OK or a negative ska_status.  Arguments are checked
  *     before anything is launched; nothing is written on an argument error.
- *   - Supported: d in {32, 64, 128}; R in {1, 2, 3, 4}; any L >= 1, W >= 0 (W >= L-1 is the
+ *   - Supported: d in {32, 64, 128}; R in 1 .. 32 (T = 0 with R = T' + R' stops nothing:
+ *     the backward is then full backpropagation through a T'-step base solve, and its
+ *     difference to the (T', R') backward is the bias of the a-posteriori certificate);
+ *     any L >= 1, W >= 0 (W >= L-1 is the
  *     dense problem), T >= 0, eps > 0 and finite.
  */
 #ifndef SINKHORN_ATTN_H
@@ -48,7 +51,7 @@ typedef enum { SKA_F32 = 0, SKA_BF16 = 1 } ska_dtype;
 typedef enum {
     SKA_OK = 0,
     SKA_EINVAL = -1,       /* null required pointer, non-positive size, bad eps        */
-    SKA_EUNSUPPORTED = -2, /* R outside 1..4, unsupported d, unknown dtype              */
+    SKA_EUNSUPPORTED = -2, /* R outside 1..32, unsupported d, unknown dtype             */
     SKA_EWORKSPACE = -3,   /* workspace smaller than sinkhorn_attn_workspace_bytes()    */
     SKA_EHIP = -4          /* a HIP launch failed (hipGetLastError)                     */
 } ska_status;

@@ -42,8 +42,10 @@ constexpr int TT = 32;  // other-side rows per tile
 constexpr float LOG2E = 1.4426950408889634f;
 constexpr float LN2 = 0.6931471805599453f;
 
-constexpr int MAXR = 4;      // deepest differentiable tail
-constexpr int MAXNQ = 2;     // float4 groups of a modifier pack: 2R terms, four per group
+constexpr int MAXR = 32;     // deepest differentiable tail (T = 0 with R = T' + R' is full
+                             // backpropagation through a T'-step base solve)
+constexpr int MAXNQ = 2;     // float4 groups of modifier terms one final sweep takes (8 terms);
+                             // deeper tails take several sweeps that accumulate
 enum Mode { M_LSE_FIRST = 0, M_LSE = 1, M_MATVEC = 2, M_APPLY = 3, M_FINAL = 4 };
 
 struct Vec {          // one fp32 vector per problem
@@ -67,9 +69,12 @@ struct SweepArgs {
     Vec w;            // MATVEC weights on the other side
     Vec pre;          // MATVEC additive term on the owner side (may be null)
     VecOut out_vec;   // LSE / MATVEC result
-    const float4 *po; // FINAL: owner-side modifier pack   [N][ldp][nq]  (2R terms in nq groups of four)
-    const float4 *qt; // FINAL: other-side modifier pack   [N][ldp][nq]
-    int nq;           // 1 (R <= 2) or 2 (R <= 4)
+    const float4 *po; // FINAL: owner-side modifier pack   [N][ldp][pstride], first group of this sweep
+    const float4 *qt; // FINAL: other-side modifier pack   [N][ldp][pstride]
+    int nq;           // groups of four terms this sweep takes (1 or 2)
+    int pstride;      // groups per index in memory (2R terms in all)
+    int skipz;        // FINAL: leave Z out (second and later sweeps of a deep tail)
+    int accum;        // FINAL: add to the output instead of overwriting it
     const void *poB;  // FINAL on the ring kernel: owner-side pack as 16 bf16 columns  [N][ldp][16]
     const void *qtA;  // FINAL on the ring kernel: other-side pack as 16 bf16 columns  [N][ldp][16]
     long ldp;
@@ -404,7 +409,7 @@ __global__ __launch_bounds__(NTHREADS) void sweep_kernel(const SweepArgs a)
             af[f].load(reinterpret_cast<const T *>(a.A) + moff, o_frag[f] + c, L, h);
 #pragma unroll
             for (int g = 0; g < MAXNQ; ++g)
-                pof[f][g] = (o_frag[f] + c < L && g < a.nq) ? a.po[(n * a.ldp + o_frag[f] + c) * a.nq + g]
+                pof[f][g] = (o_frag[f] + c < L && g < a.nq) ? a.po[(n * a.ldp + o_frag[f] + c) * a.pstride + g]
                                                             : make_float4(0, 0, 0, 0);
         }
     }
@@ -446,7 +451,7 @@ __global__ __launch_bounds__(NTHREADS) void sweep_kernel(const SweepArgs a)
             if constexpr (MODE == M_FINAL) {
 #pragma unroll
                 for (int g = 0; g < MAXNQ; ++g)
-                    rvq[g] = (t < L && g < a.nq) ? a.qt[(n * a.ldp + t) * a.nq + g] : make_float4(0, 0, 0, 0);
+                    rvq[g] = (t < L && g < a.nq) ? a.qt[(n * a.ldp + t) * a.pstride + g] : make_float4(0, 0, 0, 0);
             }
         }
     };
@@ -526,7 +531,7 @@ __global__ __launch_bounds__(NTHREADS) void sweep_kernel(const SweepArgs a)
                     f32x16 z;
 #pragma unroll
                     for (int r = 0; r < 16; ++r) z[r] = 0.f;
-                    z = tile_dot<D>(s + ST::OFF_B, af[f], lane, z);
+                    if (!a.skipz) z = tile_dot<D>(s + ST::OFF_B, af[f], lane, z);
 #pragma unroll
                     for (int r = 0; r < 16; ++r) {
                         const int tl = 8 * (r >> 2) + 4 * h + (r & 3);
@@ -580,6 +585,13 @@ __global__ __launch_bounds__(NTHREADS) void sweep_kernel(const SweepArgs a)
                     float v0 = outm[f][j][4 * q + 0] * fac, v1 = outm[f][j][4 * q + 1] * fac;
                     float v2 = outm[f][j][4 * q + 2] * fac, v3 = outm[f][j][4 * q + 3] * fac;
                     if (o < L) {
+                        if constexpr (MODE == M_FINAL) {
+                            if (a.accum) {
+                                float old[4];
+                                load4<T>(orow + dv, old);
+                                v0 += old[0]; v1 += old[1]; v2 += old[2]; v3 += old[3];
+                            }
+                        }
                         store4<T>(orow + dv, v0, v1, v2, v3);
                         if constexpr (MODE == M_APPLY) {
                             if (drow) {
@@ -1206,7 +1218,7 @@ __global__ void prescale_kernel(const __bf16 *src, __bf16 *dst, long n8, float s
 // then -sum_k (hi hi + lo hi + hi lo) = -sum_k row_k col_k to about 2^-16 relative.
 // aug = rowA, rowB, colA, colB, each [N][ldp][16].  Workspace vectors: vec 1 + 2(R - t) is
 // vbar_t, vec 2 + 2(R - t) is ubar_t.
-__device__ __forceinline__ void pack_cols(const float (&x)[2 * MAXR], __bf16 *A, __bf16 *B)
+__device__ __forceinline__ void pack_cols(const float (&x)[4], __bf16 *A, __bf16 *B)
 {
 #pragma unroll
     for (int k = 0; k < 4; ++k) {
@@ -1219,7 +1231,7 @@ __device__ __forceinline__ void pack_cols(const float (&x)[2 * MAXR], __bf16 *A,
     for (int k = 12; k < 16; ++k) { A[k] = (__bf16)0.f; B[k] = (__bf16)0.f; }
 }
 __global__ void packs_kernel(const float *UV, int Lp, int R, const float *vecs, long nldw, long wstride,
-                             float4 *rowp, float4 *colp, int nq, __bf16 *aug, long ldp, long nldp)
+                             float *rowp, float *colp, int nq, __bf16 *aug, long ldp, long nldp)
 {
     const int n = blockIdx.y;
     const int i = blockIdx.x * blockDim.x + threadIdx.x;
@@ -1227,37 +1239,33 @@ __global__ void packs_kernel(const float *UV, int Lp, int R, const float *vecs, 
     const float *uv = UV + (long)n * 2 * (R + 1) * Lp;
     const long w = n * wstride + i;
     const float uR = uv[(2 * R) * Lp + i], vR = uv[(2 * R + 1) * Lp + i];
-    float r[2 * MAXR], c[2 * MAXR];
-#pragma unroll
-    for (int k = 0; k < 2 * MAXR; ++k) { r[k] = 0.f; c[k] = 0.f; }
-#pragma unroll
-    for (int q = 0; q < MAXR; ++q) {   // q = R - t
-        if (q < R) {
-            const int t = R - q;
-            const float at = __expf(uv[(2 * t) * Lp + i] - uR), bt = __expf(uv[(2 * t + 1) * Lp + i] - vR);
-            const float bp = __expf(uv[(2 * t - 1) * Lp + i] - vR);
-            const float vb = vecs[(1 + 2 * q) * nldw + w], ub = vecs[(2 + 2 * q) * nldw + w];
-            r[2 * q] = at;          c[2 * q] = bt * vb;
-            r[2 * q + 1] = at * ub; c[2 * q + 1] = bp;
+    float r4[4] = {0.f, 0.f, 0.f, 0.f}, c4[4] = {0.f, 0.f, 0.f, 0.f};   // the first four terms (ring kernel)
+    float *rp = rowp + (n * ldp + i) * 4L * nq, *cp = colp + (n * ldp + i) * 4L * nq;
+    for (int q = 0; q < R; ++q) {   // q = R - t
+        const int t = R - q;
+        const float at = __expf(uv[(2 * t) * Lp + i] - uR), bt = __expf(uv[(2 * t + 1) * Lp + i] - vR);
+        const float bp = __expf(uv[(2 * t - 1) * Lp + i] - vR);
+        const float vb = vecs[(1 + 2 * q) * nldw + w], ub = vecs[(2 + 2 * q) * nldw + w];
+        if (!aug) {
+            rp[2 * q] = at;          cp[2 * q] = bt * vb;
+            rp[2 * q + 1] = at * ub; cp[2 * q + 1] = bp;
+        } else if (q < 2) {
+            if (q == 0) { r4[0] = at; c4[0] = bt * vb; r4[1] = at * ub; c4[1] = bp; }
+            else { r4[2] = at; c4[2] = bt * vb; r4[3] = at * ub; c4[3] = bp; }
         }
     }
     if (!aug) {
-#pragma unroll
-        for (int g = 0; g < MAXNQ; ++g)
-            if (g < nq) {
-                rowp[(n * ldp + i) * nq + g] = make_float4(r[4 * g], r[4 * g + 1], r[4 * g + 2], r[4 * g + 3]);
-                colp[(n * ldp + i) * nq + g] = make_float4(c[4 * g], c[4 * g + 1], c[4 * g + 2], c[4 * g + 3]);
-            }
+        for (int k = 2 * R; k < 4 * nq; ++k) { rp[k] = 0.f; cp[k] = 0.f; }   // pad the last group
     } else {
         __align__(16) __bf16 A[16], B[16];
         const long e = (n * ldp + i) * 16;
-        pack_cols(r, A, B);
+        pack_cols(r4, A, B);
 #pragma unroll
         for (int q = 0; q < 2; ++q) {
             reinterpret_cast<uint4 *>(aug + 0 * nldp * 16 + e)[q] = reinterpret_cast<const uint4 *>(A)[q];
             reinterpret_cast<uint4 *>(aug + 1 * nldp * 16 + e)[q] = reinterpret_cast<const uint4 *>(B)[q];
         }
-        pack_cols(c, A, B);
+        pack_cols(c4, A, B);
 #pragma unroll
         for (int q = 0; q < 2; ++q) {
             reinterpret_cast<uint4 *>(aug + 2 * nldp * 16 + e)[q] = reinterpret_cast<const uint4 *>(A)[q];
@@ -1638,28 +1646,35 @@ int bwd_impl(const Problem &p, const void *Qin, const void *K, const void *V, co
         }
     }
     PhaseTimer pt_final(SKA_PH_FINAL, st);   // modifier packs and the two final sweeps
-    pt_final.launched(2);
-    hipLaunchKernelGGL(packs_kernel, vgrid, dim3(256), 0, st, UV, Lp, R, wf, nldp, ldw, rowp, colp, nq,
-                       AUG ? aug : nullptr, ldw, nldp);
+    pt_final.launched(2 * ((nq + MAXNQ - 1) / MAXNQ));
+    hipLaunchKernelGGL(packs_kernel, vgrid, dim3(256), 0, st, UV, Lp, R, wf, nldp, ldw,
+                       reinterpret_cast<float *>(rowp), reinterpret_cast<float *>(colp), nq, AUG ? aug : nullptr,
+                       ldw, nldp);
     if (hipGetLastError() != hipSuccess) return SKA_EHIP;
-    // one-reference final sweeps
-    {
-        SweepArgs a = base;
-        a.X = Q; a.Y = K; a.A = G; a.Bm = V; a.out_mat = dQ; a.xs = uv(2 * R); a.yt = uv(2 * R + 1);
-        a.po = rowp; a.qt = colp; a.ldp = ldw; a.nq = nq;
-        if (AUG) { a.poB = aug + 1 * nldp * 16; a.qtA = aug + 2 * nldp * 16; }   // rows own, columns stream
-        a.rev = nlaunch++ & 1;
-        SKA_TRY((sweep<T, D>(M_FINAL, a, N, st)));
-    }
-    {
-        SweepArgs a = base;
-        a.X = K; a.Y = Q; a.A = V; a.Bm = G; a.out_mat = dK; a.xs = uv(2 * R + 1); a.yt = uv(2 * R);
-        a.po = colp; a.qt = rowp; a.ldp = ldw; a.nq = nq;
-        if (AUG) { a.poB = aug + 3 * nldp * 16; a.qtA = aug + 0 * nldp * 16; }   // columns own, rows stream
-        // payload rows are Qs = (cs log2 e) Q when prescaled: cs sum Sbar^T Q = ln 2 sum Sbar^T Qs
-        if (sizeof(T) == 2) a.cs = LN2;
-        a.rev = nlaunch++ & 1;
-        SKA_TRY((sweep<T, D>(M_FINAL, a, N, st)));
+    // one-reference final sweeps; a sweep takes eight modifier terms, so a tail deeper than
+    // R = 4 takes several that accumulate (Z only in the first)
+    for (int g0 = 0; g0 < nq; g0 += MAXNQ) {
+        const int ng = nq - g0 < MAXNQ ? nq - g0 : MAXNQ;
+        {
+            SweepArgs a = base;
+            a.X = Q; a.Y = K; a.A = G; a.Bm = V; a.out_mat = dQ; a.xs = uv(2 * R); a.yt = uv(2 * R + 1);
+            a.po = rowp + g0; a.qt = colp + g0; a.ldp = ldw; a.nq = ng; a.pstride = nq;
+            a.skipz = a.accum = g0 > 0;
+            if (AUG) { a.poB = aug + 1 * nldp * 16; a.qtA = aug + 2 * nldp * 16; }   // rows own, columns stream
+            a.rev = nlaunch++ & 1;
+            SKA_TRY((sweep<T, D>(M_FINAL, a, N, st)));
+        }
+        {
+            SweepArgs a = base;
+            a.X = K; a.Y = Q; a.A = V; a.Bm = G; a.out_mat = dK; a.xs = uv(2 * R + 1); a.yt = uv(2 * R);
+            a.po = colp + g0; a.qt = rowp + g0; a.ldp = ldw; a.nq = ng; a.pstride = nq;
+            a.skipz = a.accum = g0 > 0;
+            if (AUG) { a.poB = aug + 3 * nldp * 16; a.qtA = aug + 0 * nldp * 16; }   // columns own, rows stream
+            // payload rows are Qs = (cs log2 e) Q when prescaled: cs sum Sbar^T Q = ln 2 sum Sbar^T Qs
+            if (sizeof(T) == 2) a.cs = LN2;
+            a.rev = nlaunch++ & 1;
+            SKA_TRY((sweep<T, D>(M_FINAL, a, N, st)));
+        }
     }
     return SKA_OK;
 }

@@ -33,7 +33,7 @@ def test_workspace_bytes_and_strerror():
     assert binding.sinkhorn_attn_workspace_bytes(1, 2, 262144, 64, 256, 20) >= 2 * 262144 * 13 * 4
     assert binding.sinkhorn_attn_workspace_bytes(1, 1, 0, 64, 256, 20) == 0          # L < 1
     assert binding.sinkhorn_attn_workspace_bytes(1, 1, 16, 48, 256, 20) == 0         # d unsupported
-    assert binding.sinkhorn_attn_workspace_bytes(1, 1, 16, 64, 4, 2, R=5) == 0
+    assert binding.sinkhorn_attn_workspace_bytes(1, 1, 16, 64, 4, 2, R=33) == 0
     assert binding.sinkhorn_attn_workspace_bytes(1, 1, 16, 64, 4, 2, R=0) == 0
     assert (binding.sinkhorn_attn_workspace_bytes(1, 1, 16, 64, 4, 2, R=4)
             > binding.sinkhorn_attn_workspace_bytes(1, 1, 16, 64, 4, 2, R=1) > 0)
@@ -69,7 +69,7 @@ def test_argument_errors_are_reported_before_any_launch():
                 dict(eps=float("inf")), dict(eps=float("nan"))):
         assert _fwd(lib, **bad) == binding.SKA_EINVAL, bad
         assert _bwd(lib, **bad) == binding.SKA_EINVAL, bad
-    for bad in (dict(R=0), dict(R=5), dict(d=48), dict(d=256), dict(dtype=7)):
+    for bad in (dict(R=0), dict(R=33), dict(d=48), dict(d=256), dict(dtype=7)):
         assert _fwd(lib, **bad) == binding.SKA_EUNSUPPORTED, bad
         assert _bwd(lib, **bad) == binding.SKA_EUNSUPPORTED, bad
     assert _bwd(lib, ws=None, ws_bytes=0) == binding.SKA_EWORKSPACE

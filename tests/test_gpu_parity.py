@@ -129,6 +129,31 @@ def test_tail_depth(R, dtype, d):
     check(small("tail", 520, d, 37, 5, dtype, eps=0.8, B=1, H=2, R=R), seed=40 + R)
 
 
+@pytest.mark.parametrize("dtype,d", [("f32", 64), ("bf16", 64)])
+def test_deep_tail_is_full_backprop(dtype, d):
+    """T = 0 with a deep tail: nothing is stopped, the backward is full backpropagation through
+    the whole solve (the final sweeps take the 2R modifier terms eight at a time)."""
+    check(small("deep", 400, d, 30, 0, dtype, eps=0.8, B=1, H=2, R=7), seed=77)
+
+
+def test_bias_certificate_by_difference():
+    """The stopped-base bias D_x z_T^T eta_R (a-posteriori certificate) is the difference of two
+    backward calls: (T = 0, R = T' + R') minus (T', R')."""
+    T, R = 4, 2
+    w_full = small("full", 300, 32, 20, 0, "f32", eps=0.8, R=T + R)
+    w_stop = small("stop", 300, 32, 20, T, "f32", eps=0.8, R=R)
+    arrays = make_inputs(w_full, 5)
+    g_full, g_stop = run_gpu(w_full, arrays), run_gpu(w_stop, arrays)
+    o_full = oracle.band_batched(*arrays, w_full.W, 0, T + R, w_full.eps)
+    o_stop = oracle.band_batched(*arrays, w_stop.W, T, R, w_stop.eps)
+    assert np.abs(g_full["O"] - g_stop["O"]).max() < 1e-5        # the same forward
+    for k in ("dQ", "dK"):
+        gap, ref = g_full[k] - g_stop[k], o_full[k] - o_stop[k]
+        assert np.linalg.norm(ref) > 1e-4 * np.linalg.norm(o_stop[k])      # there is a bias to certify
+        assert rel(gap, ref) < 5e-3, (k, rel(gap, ref))
+    assert np.abs(g_full["dV"] - g_stop["dV"]).max() < 1e-4      # V does not enter the base solve
+
+
 def test_tail_depth_dustbin():
     check(small("taildb", 300, 64, 24, 4, "bf16", eps=0.9, R=3, dustbin=True, dustbin_score=-0.2), seed=17)
     check(small("taildb", 300, 32, 24, 4, "f32", eps=0.9, R=1, dustbin=True, dustbin_score=0.4), seed=18)
@@ -157,7 +182,7 @@ def test_error_codes_on_device():
     import paper_2605_08123_amd as ska
     x = torch.zeros((1, 1, 64, 32), device="cuda")
     with pytest.raises(ska.SinkhornAttnError) as e:
-        ska.sinkhorn_attn_fwd(x, x, x, 4, 2, R=5)
+        ska.sinkhorn_attn_fwd(x, x, x, 4, 2, R=33)
     assert e.value.status == -2
     with pytest.raises(ska.SinkhornAttnError) as e:
         ska.sinkhorn_attn_fwd(x, x, x, 4, 2, eps=0.0)

@@ -73,6 +73,33 @@ def test_fd_through_unfrozen_base_differs():
     assert rel(ref["dQ"], fd) > 1e-3
 
 
+def test_full_backprop_is_the_tail_without_a_base():
+    """With T = 0 nothing is stopped: the surrogate with tail depth T' + R' is the whole
+    (T' + R')-step solve, so its gradient is the full gradient that central differences
+    through the unfrozen solve measure.  The gap to the stopped-base gradient is the bias
+    D_x z_T^T eta_R of the a-posteriori certificate; it shrinks as the tail deepens."""
+    Q, K, V, G = problem()
+    T, W, eps = 6, 5, 0.7
+    h = 1e-6
+    gaps = []
+    for R in (1, 2, 3):
+        kw = dict(W=W, T=T, R=R, eps=eps)
+        full = oracle.band(Q, K, V, G, W=W, T=0, R=T + R, eps=eps)
+        assert np.allclose(full["O"], oracle.band(Q, K, V, None, **kw)["O"], rtol=0, atol=1e-13)
+        if R == 2:
+            fd = np.zeros_like(K)
+            for a in range(K.shape[0]):
+                for b in range(K.shape[1]):
+                    Kp, Km = K.copy(), K.copy()
+                    Kp[a, b] += h
+                    Km[a, b] -= h
+                    fd[a, b] = (_loss(Q, Kp, V, G, None, **kw) - _loss(Q, Km, V, G, None, **kw)) / (2 * h)
+            assert rel(full["dK"], fd) < 2e-7, rel(full["dK"], fd)
+        stopped = oracle.band(Q, K, V, G, **kw)
+        gaps.append(np.abs(full["dQ"] - stopped["dQ"]).max())
+    assert gaps[0] > gaps[1] > gaps[2] > 0.0
+
+
 # ---------------------------------------------------------------- P12: dense brute force
 @pytest.mark.parametrize("L,W", [(24, 5), (17, 0), (9, 8), (9, 20), (33, 1)])
 def test_band_matches_dense_brute_force(L, W):
