@@ -34,7 +34,7 @@
  *   - Supported: d in {32, 64, 128}; R in 1 .. 32 (T = 0 with R = T' + R' stops nothing:
  *     the backward is then full backpropagation through a T'-step base solve, and its
  *     difference to the (T', R') backward is the bias of the a-posteriori certificate);
- *     any L >= 1, W >= 0 (W >= L-1 is the
+ *     1 <= L <= 2^24, B*H <= 65535, W >= 0 (W >= L-1 is the
  *     dense problem), T >= 0, eps > 0 and finite.
  */
 #ifndef SINKHORN_ATTN_H

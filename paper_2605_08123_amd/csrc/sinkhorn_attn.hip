@@ -1356,6 +1356,7 @@ int check_common(const Problem &p)
     if (p.B < 1 || p.H < 1 || p.L < 1 || p.W < 0 || p.T < 0) return SKA_EINVAL;
     if (!(p.eps > 0.f) || !isfinite(p.eps) || !isfinite(p.sdb)) return SKA_EINVAL;
     if ((long)p.B * p.H > 65535) return SKA_EINVAL;
+    if (p.L > (1 << 24)) return SKA_EUNSUPPORTED;   // 32-bit byte offsets inside one [L][d] matrix
     if (p.R < 1 || p.R > MAXR) return SKA_EUNSUPPORTED;
     if (p.d != 32 && p.d != 64 && p.d != 128) return SKA_EUNSUPPORTED;
     if (p.dtype != SKA_F32 && p.dtype != SKA_BF16) return SKA_EUNSUPPORTED;

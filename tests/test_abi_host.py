@@ -35,6 +35,8 @@ def test_workspace_bytes_and_strerror():
     assert binding.sinkhorn_attn_workspace_bytes(1, 1, 16, 48, 256, 20) == 0         # d unsupported
     assert binding.sinkhorn_attn_workspace_bytes(1, 1, 16, 64, 4, 2, R=33) == 0
     assert binding.sinkhorn_attn_workspace_bytes(1, 1, 16, 64, 4, 2, R=0) == 0
+    assert binding.sinkhorn_attn_workspace_bytes(1, 1, (1 << 24) + 1, 64, 4, 2) == 0   # L too long
+    assert binding.sinkhorn_attn_workspace_bytes(1, 1, 1 << 24, 64, 4, 2) > 0
     assert (binding.sinkhorn_attn_workspace_bytes(1, 1, 16, 64, 4, 2, R=4)
             > binding.sinkhorn_attn_workspace_bytes(1, 1, 16, 64, 4, 2, R=1) > 0)
     a = binding.sinkhorn_attn_workspace_bytes(2, 2, 1000, 64, 10, 5, dustbin=False)
