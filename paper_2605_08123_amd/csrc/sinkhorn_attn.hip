@@ -17,6 +17,10 @@
 //   FINAL        out_o = c exp(x_o) sum_t exp(S_ot + y_t) [<A_o, B_t> - sum_k p_k,o q_k,t] Y_t
 //                                                 (Prop. 2: one reference tile + modifiers)
 //
+// Three kernels serve the sweeps: vsweep_kernel (LSE, MATVEC: a skewed ring of tiles in LDS),
+// msweep_kernel (APPLY, FINAL for bf16 storage and d <= 64: the same ring, two products) and
+// sweep_kernel (the first half-step, fp32 storage and d = 128: double-buffered tiles).
+//
 // MFMA tile layout (32x32 accumulators): lane l holds owner o = l & 31; register r
 // holds other index t = 8*(r>>2) + 4*(l>>5) + (r&3).  Sums over t are therefore
 // in-lane register sums plus one exchange between the two lane halves.
@@ -772,8 +776,8 @@ __global__ __launch_bounds__(NTHREADS) void vsweep_kernel(const SweepArgs a)
             const int t0 = k * TT;
             bool use[FR], interior[FR];
             f32x16 acc[FR];
-            // the staged potentials (c2-scaled away: see `prescaled`) are the MFMA's initial
-            // accumulator when the score operand carries the scale already
+            // the staged potentials are the MFMA's initial accumulator when the score operand
+            // carries the scale already (bf16 storage: make_scores_operand)
             float yv[16];
 #pragma unroll
             for (int q = 0; q < 4; ++q) {
