@@ -42,6 +42,14 @@ def _load():
         lib.ska_oracle_band.argtypes = [c_d, c_d, c_d, c_d, i64, i32, i64, i32, i32,
                                         ctypes.c_double, i32, ctypes.c_double, c_d, c_d, c_d, c_d,
                                         c_d, c_d, c_d, c_d]
+        lib.ska_oracle_core_marg.restype = i32
+        lib.ska_oracle_core_marg.argtypes = [i64, i64, i64, ctypes.c_void_p, ctypes.c_void_p, c_d, c_d,
+                                             c_d, i32, i32, i32, c_d, c_d, c_d, c_d, c_d, c_d, c_d, c_d,
+                                             c_d, c_d]
+        lib.ska_oracle_band_marg.restype = i32
+        lib.ska_oracle_band_marg.argtypes = [c_d, c_d, c_d, c_d, i64, i32, i64, i32, i32,
+                                             ctypes.c_double, i32, ctypes.c_double, c_d, c_d, c_d, c_d,
+                                             c_d, c_d, c_d, c_d, c_d, c_d]
         _lib = lib
     return _lib
 
@@ -58,17 +66,18 @@ def _f64(a):
     return None if a is None else np.ascontiguousarray(a, dtype=np.float64)
 
 
-def core(rptr, col, S, V, G, T, R, v0_fixed=None):
+def core(rptr, col, S, V, G, T, R, v0_fixed=None, log_a=None, log_b=None):
     """Support-generic solve on explicit edge scores.
 
     rptr[m+1], col[nnz] describe the active support row by row; S[nnz] are the
     effective scores.  Returns a dict with O, U[(R+1),m], Vp[(R+1),n] and, when
-    G is given, Sbar[nnz], dV, ubar, vbar.
+    G is given, Sbar[nnz], dV, ubar, vbar.  log_a[m], log_b[n]: logarithms of the row and
+    column targets (compatible general marginals); None for unit targets.
     """
     lib = _load()
     rptr = np.ascontiguousarray(rptr, dtype=np.int64)
     col = np.ascontiguousarray(col, dtype=np.int32)
-    S, V, G, v0_fixed = _f64(S), _f64(V), _f64(G), _f64(v0_fixed)
+    S, V, G, v0_fixed, log_a, log_b = _f64(S), _f64(V), _f64(G), _f64(v0_fixed), _f64(log_a), _f64(log_b)
     m, nnz = len(rptr) - 1, len(col)
     n, dv = V.shape
     assert rptr[-1] == nnz and S.shape == (nnz,)
@@ -78,25 +87,28 @@ def core(rptr, col, S, V, G, T, R, v0_fixed=None):
         assert G.shape == (m, dv)
         out.update(Sbar=np.empty(nnz), dV=np.empty((n, dv)), ubar=np.empty((R + 1, m)),
                    vbar=np.empty((R + 1, n)))
-    rc = lib.ska_oracle_core(m, n, nnz, rptr.ctypes.data, col.ctypes.data, _p(S), _p(V), _p(G), dv,
-                             T, R, _p(v0_fixed), _p(out["O"]), _p(out["U"]), _p(out["Vp"]),
-                             _p(out.get("Sbar")), _p(out.get("dV")), _p(out.get("ubar")),
-                             _p(out.get("vbar")))
+    assert (log_a is None or log_a.shape == (m,)) and (log_b is None or log_b.shape == (n,))
+    rc = lib.ska_oracle_core_marg(m, n, nnz, rptr.ctypes.data, col.ctypes.data, _p(S), _p(V), _p(G), dv,
+                                  T, R, _p(v0_fixed), _p(log_a), _p(log_b), _p(out["O"]), _p(out["U"]),
+                                  _p(out["Vp"]), _p(out.get("Sbar")), _p(out.get("dV")),
+                                  _p(out.get("ubar")), _p(out.get("vbar")))
     if rc:
         raise RuntimeError(f"ska_oracle_core failed ({rc})")
     return out
 
 
 def band(Q, K, V, G, W, T, R, eps, dustbin=False, dustbin_score=0.0, v0_fixed=None,
-         want_sbar=False):
+         want_sbar=False, log_a=None, log_b=None):
     """Banded operator for one problem; Q, K, V, G are [L, d] arrays (G may be None).
 
     Returns a dict: O[L,d], UV[2(R+1), Lp] ordered u0,v0,u1,v1,...; with G also
     dQ, dK, dV [L,d], bars[2(R+1), Lp] (same order) and, if want_sbar,
-    Sbar[L, 2W+1] indexed [i, j-i+W].
+    Sbar[L, 2W+1] indexed [i, j-i+W].  log_a, log_b [Lp]: logarithms of the row and
+    column targets, None for unit targets.
     """
     lib = _load()
     Q, K, V, G, v0_fixed = _f64(Q), _f64(K), _f64(V), _f64(G), _f64(v0_fixed)
+    log_a, log_b = _f64(log_a), _f64(log_b)
     L, d = Q.shape
     assert K.shape == (L, d) and V.shape == (L, d) and (G is None or G.shape == (L, d))
     Lp = L + (1 if dustbin else 0)
@@ -107,24 +119,28 @@ def band(Q, K, V, G, W, T, R, eps, dustbin=False, dustbin_score=0.0, v0_fixed=No
                    bars=np.empty((2 * (R + 1), Lp)))
         if want_sbar:
             out["Sbar"] = np.empty((L, 2 * W + 1))
-    rc = lib.ska_oracle_band(_p(Q), _p(K), _p(V), _p(G), L, d, W, T, R, float(eps),
-                             1 if dustbin else 0, float(dustbin_score), _p(v0_fixed), _p(out["O"]),
-                             _p(out["UV"]), _p(out.get("dQ")), _p(out.get("dK")), _p(out.get("dV")),
-                             _p(out.get("bars")), _p(out.get("Sbar")))
+    assert (log_a is None or log_a.shape == (Lp,)) and (log_b is None or log_b.shape == (Lp,))
+    rc = lib.ska_oracle_band_marg(_p(Q), _p(K), _p(V), _p(G), L, d, W, T, R, float(eps),
+                                  1 if dustbin else 0, float(dustbin_score), _p(v0_fixed), _p(log_a),
+                                  _p(log_b), _p(out["O"]), _p(out["UV"]), _p(out.get("dQ")),
+                                  _p(out.get("dK")), _p(out.get("dV")), _p(out.get("bars")),
+                                  _p(out.get("Sbar")))
     if rc:
         raise RuntimeError(f"ska_oracle_band failed ({rc})")
     return out
 
 
-def band_batched(Q, K, V, G, W, T, R, eps, dustbin=False, dustbin_score=0.0):
-    """[B,H,L,d] inputs, one independent problem per (b,h). Returns stacked arrays."""
+def band_batched(Q, K, V, G, W, T, R, eps, dustbin=False, dustbin_score=0.0, log_a=None, log_b=None):
+    """[B,H,L,d] inputs, one independent problem per (b,h) (log_a, log_b: [B,H,Lp] or None).
+    Returns stacked arrays."""
     B, H, L, d = Q.shape
     keys = ("O", "UV") + (("dQ", "dK", "dV") if G is not None else ())
     acc = {k: [] for k in keys}
     for b in range(B):
         for h in range(H):
             r = band(Q[b, h], K[b, h], V[b, h], None if G is None else G[b, h], W, T, R, eps,
-                     dustbin, dustbin_score)
+                     dustbin, dustbin_score, log_a=None if log_a is None else log_a[b, h],
+                     log_b=None if log_b is None else log_b[b, h])
             for k in keys:
                 acc[k].append(r[k])
     return {k: np.stack(v).reshape((B, H) + v[0].shape) for k, v in acc.items()}

@@ -27,6 +27,12 @@
  *                                                        its own exponential
  *                                                        ("direct-four")
  *   sparse-spoke dustbin support                         Section 2.3
+ *   compatible general marginals a, b (optional)         App. "Compatible General
+ *                                                        Marginals": half-steps with
+ *                                                        log a_i / log b_j added, and
+ *                                                        the half-step Jacobians
+ *                                                        -P/a_i, -P/b_j of its lemma in
+ *                                                        the reverse sweep
  *
  * Readings fixed here (the paper is silent): the base solve starts from v = 0
  * and begins with a row half-step; one step = row half-step then column
@@ -90,8 +96,9 @@ static void free_columns(support_t *sp)
     free(sp->erow);
 }
 
-/* Eq. (1): u_i = -log sum_{j in row i} exp(S_ij + v_j). */
-static void row_half_step(const support_t *sp, const double *S, const double *v, double *u)
+/* Eq. (1): u_i = log a_i - log sum_{j in row i} exp(S_ij + v_j)  (loga NULL: a = 1). */
+static void row_half_step(const support_t *sp, const double *S, const double *v, const double *loga,
+                          double *u)
 {
 #pragma omp parallel for schedule(static)
     for (int64_t i = 0; i < sp->m; ++i) {
@@ -103,12 +110,13 @@ static void row_half_step(const support_t *sp, const double *S, const double *v,
         double s = 0.0;
         for (int64_t e = sp->rptr[i]; e < sp->rptr[i + 1]; ++e)
             s += exp(S[e] + v[sp->col[e]] - mx);
-        u[i] = -(mx + log(s));
+        u[i] = (loga ? loga[i] : 0.0) - (mx + log(s));
     }
 }
 
-/* Eq. (2): v_j = -log sum_{i in column j} exp(S_ij + u_i). */
-static void col_half_step(const support_t *sp, const double *S, const double *u, double *v)
+/* Eq. (2): v_j = log b_j - log sum_{i in column j} exp(S_ij + u_i)  (logb NULL: b = 1). */
+static void col_half_step(const support_t *sp, const double *S, const double *u, const double *logb,
+                          double *v)
 {
 #pragma omp parallel for schedule(static)
     for (int64_t j = 0; j < sp->n; ++j) {
@@ -123,7 +131,7 @@ static void col_half_step(const support_t *sp, const double *S, const double *u,
             int64_t e = sp->cedge[c];
             s += exp(S[e] + u[sp->erow[e]] - mx);
         }
-        v[j] = -(mx + log(s));
+        v[j] = (logb ? logb[j] : 0.0) - (mx + log(s));
     }
 }
 
@@ -145,6 +153,7 @@ static void form_plan(const support_t *sp, const double *S, const double *up, co
  *   v0_fixed         NULL: run the T-step base solve from v = 0.
  *                    else: use this vector as the stopped v^(0) and skip the
  *                    base solve (T is ignored, U[0] is filled with zeros).
+ *   loga[m], logb[n] logarithms of the row / column targets, NULL for unit targets
  * Outputs (any may be NULL except U, Vp):
  *   O[m][dv]         transport output with the terminal plan P^(R,R)
  *   U[(R+1)][m], Vp[(R+1)][n]   u^(0..R), v^(0..R)
@@ -153,10 +162,10 @@ static void form_plan(const support_t *sp, const double *S, const double *up, co
  *   ubar[(R+1)][m], vbar[(R+1)][n]  dual cotangents; ubar[0] = 0, vbar[0] is the
  *                    discarded base cotangent
  */
-int ska_oracle_core(int64_t m, int64_t n, int64_t nnz, const int64_t *rptr, const int32_t *col,
-                    const double *S, const double *Vv, const double *G, int dv, int T, int R,
-                    const double *v0_fixed, double *O, double *U, double *Vp, double *Sbar,
-                    double *dV, double *ubar, double *vbar)
+int ska_oracle_core_marg(int64_t m, int64_t n, int64_t nnz, const int64_t *rptr, const int32_t *col,
+                         const double *S, const double *Vv, const double *G, int dv, int T, int R,
+                         const double *v0_fixed, const double *loga, const double *logb, double *O,
+                         double *U, double *Vp, double *Sbar, double *dV, double *ubar, double *vbar)
 {
     if (m < 1 || n < 1 || R < 1 || T < 0 || dv < 1 || !rptr || !col || !S || !U || !Vp) return -1;
     support_t sp = {m, n, nnz, rptr, col, NULL, NULL, NULL};
@@ -170,14 +179,14 @@ int ska_oracle_core(int64_t m, int64_t n, int64_t nnz, const int64_t *rptr, cons
         memset(v0, 0, (size_t)n * sizeof(double));
         memset(u0, 0, (size_t)m * sizeof(double));
         for (int t = 0; t < T; ++t) {
-            row_half_step(&sp, S, v0, u0);
-            col_half_step(&sp, S, u0, v0);
+            row_half_step(&sp, S, v0, loga, u0);
+            col_half_step(&sp, S, u0, logb, v0);
         }
     }
     /* tail: u^(t) from v^(t-1), then v^(t) from u^(t) */
     for (int t = 1; t <= R; ++t) {
-        row_half_step(&sp, S, Vp + (size_t)(t - 1) * n, U + (size_t)t * m);
-        col_half_step(&sp, S, U + (size_t)t * m, Vp + (size_t)t * n);
+        row_half_step(&sp, S, Vp + (size_t)(t - 1) * n, loga, U + (size_t)t * m);
+        col_half_step(&sp, S, U + (size_t)t * m, logb, Vp + (size_t)t * n);
     }
     const double *uR = U + (size_t)R * m, *vR = Vp + (size_t)R * n;
 
@@ -241,31 +250,34 @@ int ska_oracle_core(int64_t m, int64_t n, int64_t nnz, const int64_t *rptr, cons
         double *vbt = vbar + (size_t)t * n;
         double *vbp = vbar + (size_t)(t - 1) * n;
 
-        /* v^(t)_j = -log sum_i exp(S_ij + u^(t)_i): the weight of edge e in it
-           is P^(t,t)_e, with a minus sign. */
+        /* v^(t)_j = log b_j - log sum_i exp(S_ij + u^(t)_i): the weight of edge e in it
+           is P^(t,t)_e / b_j (the column sums of P^(t,t) are b), with a minus sign. */
         form_plan(&sp, S, ut, Vp + (size_t)t * n, P);
 #pragma omp parallel for schedule(static)
         for (int64_t i = 0; i < m; ++i) {
             double acc = 0.0;
             for (int64_t e = rptr[i]; e < rptr[i + 1]; ++e) {
-                double w = P[e] * vbt[col[e]];
+                double w = P[e] * vbt[col[e]] * (logb ? exp(-logb[col[e]]) : 1.0);
                 Sbar[e] -= w;
                 acc += w;
             }
             ubt[i] -= acc;
         }
 
-        /* u^(t)_i = -log sum_j exp(S_ij + v^(t-1)_j): weight P^(t,t-1)_e, minus sign. */
+        /* u^(t)_i = log a_i - log sum_j exp(S_ij + v^(t-1)_j): weight P^(t,t-1)_e / a_i
+           (the row sums of P^(t,t-1) are a), minus sign. */
         form_plan(&sp, S, ut, Vp + (size_t)(t - 1) * n, P);
 #pragma omp parallel for schedule(static)
-        for (int64_t i = 0; i < m; ++i)
-            for (int64_t e = rptr[i]; e < rptr[i + 1]; ++e) Sbar[e] -= P[e] * ubt[i];
+        for (int64_t i = 0; i < m; ++i) {
+            const double ia = loga ? exp(-loga[i]) : 1.0;
+            for (int64_t e = rptr[i]; e < rptr[i + 1]; ++e) Sbar[e] -= P[e] * ubt[i] * ia;
+        }
 #pragma omp parallel for schedule(static)
         for (int64_t j = 0; j < n; ++j) {
             double acc = 0.0;
             for (int64_t c = sp.cptr[j]; c < sp.cptr[j + 1]; ++c) {
                 int64_t e = sp.cedge[c];
-                acc += P[e] * ubt[sp.erow[e]];
+                acc += P[e] * ubt[sp.erow[e]] * (loga ? exp(-loga[sp.erow[e]]) : 1.0);
             }
             vbp[j] -= acc;
         }
@@ -273,6 +285,16 @@ int ska_oracle_core(int64_t m, int64_t n, int64_t nnz, const int64_t *rptr, cons
     free(P);
     free_columns(&sp);
     return 0;
+}
+
+/* Unit targets (the main text's balanced problem). */
+int ska_oracle_core(int64_t m, int64_t n, int64_t nnz, const int64_t *rptr, const int32_t *col,
+                    const double *S, const double *Vv, const double *G, int dv, int T, int R,
+                    const double *v0_fixed, double *O, double *U, double *Vp, double *Sbar,
+                    double *dV, double *ubar, double *vbar)
+{
+    return ska_oracle_core_marg(m, n, nnz, rptr, col, S, Vv, G, dv, T, R, v0_fixed, NULL, NULL, O, U,
+                                Vp, Sbar, dV, ubar, vbar);
 }
 
 /*
@@ -291,12 +313,14 @@ int ska_oracle_core(int64_t m, int64_t n, int64_t nnz, const int64_t *rptr, cons
  *   bars[2(R+1)][Lp] same order for the dual cotangents (may be NULL)
  *   Sbar_band[L][2W+1] (may be NULL): Sbar_band[i][j-i+W] on band edges, 0 elsewhere
  *   v0_fixed[Lp] or NULL, as in the core
+ *   loga[Lp], logb[Lp] or NULL: logarithms of the row / column targets
  * G may be NULL (forward only; the cotangent outputs are then untouched).
  */
-int ska_oracle_band(const double *Q, const double *K, const double *V, const double *G, int64_t L,
-                    int d, int64_t W, int T, int R, double eps, int dustbin, double s_db,
-                    const double *v0_fixed, double *O, double *UV, double *dQ, double *dK,
-                    double *dV, double *bars, double *Sbar_band)
+int ska_oracle_band_marg(const double *Q, const double *K, const double *V, const double *G, int64_t L,
+                         int d, int64_t W, int T, int R, double eps, int dustbin, double s_db,
+                         const double *v0_fixed, const double *loga, const double *logb, double *O,
+                         double *UV, double *dQ, double *dK, double *dV, double *bars,
+                         double *Sbar_band)
 {
     if (L < 1 || d < 1 || W < 0 || R < 1 || T < 0 || !(eps > 0.0) || !Q || !K || !V || !UV)
         return -1;
@@ -344,8 +368,8 @@ int ska_oracle_band(const double *Q, const double *K, const double *V, const dou
     memcpy(Vaug, V, (size_t)L * d * sizeof(double));
     if (G) memcpy(Gaug, G, (size_t)L * d * sizeof(double));
 
-    rc = ska_oracle_core(Lp, Lp, nnz, rptr, col, S, Vaug, G ? Gaug : NULL, d, T, R, v0_fixed, Oaug,
-                         U, Vp, Sbar, dVaug, ub, vb);
+    rc = ska_oracle_core_marg(Lp, Lp, nnz, rptr, col, S, Vaug, G ? Gaug : NULL, d, T, R, v0_fixed, loga,
+                              logb, Oaug, U, Vp, Sbar, dVaug, ub, vb);
     if (rc) goto done;
 
     if (O) memcpy(O, Oaug, (size_t)L * d * sizeof(double));
@@ -396,4 +420,14 @@ done:
     free(rptr); free(col); free(S); free(Sbar); free(Vaug); free(Gaug); free(Oaug); free(dVaug);
     free(U); free(Vp); free(ub); free(vb);
     return rc;
+}
+
+/* Unit targets. */
+int ska_oracle_band(const double *Q, const double *K, const double *V, const double *G, int64_t L,
+                    int d, int64_t W, int T, int R, double eps, int dustbin, double s_db,
+                    const double *v0_fixed, double *O, double *UV, double *dQ, double *dK,
+                    double *dV, double *bars, double *Sbar_band)
+{
+    return ska_oracle_band_marg(Q, K, V, G, L, d, W, T, R, eps, dustbin, s_db, v0_fixed, NULL, NULL, O,
+                                UV, dQ, dK, dV, bars, Sbar_band);
 }

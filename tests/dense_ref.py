@@ -19,21 +19,24 @@ def scores(Q, K, eps):
     return (Q @ K.T) / (eps * np.sqrt(Q.shape[1]))
 
 
-def half_steps(S, mask, T, R, v0_fixed=None):
-    """u^(0..R), v^(0..R) by Eq. (1)-(2); base from v=0 unless v0_fixed is given."""
+def half_steps(S, mask, T, R, v0_fixed=None, a=None, b=None):
+    """u^(0..R), v^(0..R) by Eq. (1)-(2); base from v=0 unless v0_fixed is given.
+    a, b: compatible positive row / column targets (None = ones)."""
     Sm = np.where(mask, S, -np.inf)
     m, n = S.shape
+    la = np.zeros(m) if a is None else np.log(a)
+    lb = np.zeros(n) if b is None else np.log(b)
     if v0_fixed is None:
         u, v = np.zeros(m), np.zeros(n)
         for _ in range(T):
-            u = -logsumexp(Sm + v[None, :], axis=1)
-            v = -logsumexp(Sm + u[:, None], axis=0)
+            u = la - logsumexp(Sm + v[None, :], axis=1)
+            v = lb - logsumexp(Sm + u[:, None], axis=0)
     else:
         u, v = np.zeros(m), np.array(v0_fixed, dtype=np.float64)
     U, Vp = [u], [v]
     for _ in range(R):
-        u = -logsumexp(Sm + Vp[-1][None, :], axis=1)
-        v = -logsumexp(Sm + u[:, None], axis=0)
+        u = la - logsumexp(Sm + Vp[-1][None, :], axis=1)
+        v = lb - logsumexp(Sm + u[:, None], axis=0)
         U.append(u)
         Vp.append(v)
     return np.array(U), np.array(Vp)
@@ -43,9 +46,13 @@ def plan(S, mask, u, v):
     return np.where(mask, np.exp(np.where(mask, S, 0.0) + u[:, None] + v[None, :]), 0.0)
 
 
-def closed_form_adjoint(S, mask, U, Vp, V, G, drop_terminal_pullback=False):
-    """Prop. 1: dual cotangents and the score cotangent, any R >= 1."""
+def closed_form_adjoint(S, mask, U, Vp, V, G, drop_terminal_pullback=False, a=None, b=None):
+    """Prop. 1: dual cotangents and the score cotangent, any R >= 1.  With targets a, b:
+    the general-marginal finite-tail VJP (every ubar is divided by a, every vbar by b where
+    it multiplies a plan)."""
     R = U.shape[0] - 1
+    a = np.ones(S.shape[0]) if a is None else np.asarray(a, dtype=np.float64)
+    b = np.ones(S.shape[1]) if b is None else np.asarray(b, dtype=np.float64)
     P = lambda p, q: plan(S, mask, U[p], Vp[q])
     Z = G @ V.T
     PRR = P(R, R)
@@ -53,16 +60,16 @@ def closed_form_adjoint(S, mask, U, Vp, V, G, drop_terminal_pullback=False):
     ub = np.zeros_like(U)
     vb = np.zeros_like(Vp)
     vb[R] = gv
-    ub[R] = gu if drop_terminal_pullback else gu - PRR @ vb[R]
+    ub[R] = gu if drop_terminal_pullback else gu - PRR @ (vb[R] / b)
     for t in range(R, 0, -1):
-        vb[t - 1] = -P(t, t - 1).T @ ub[t]
+        vb[t - 1] = -P(t, t - 1).T @ (ub[t] / a)
         if t >= 2:
-            ub[t - 1] = -P(t - 1, t - 1) @ vb[t - 1]
+            ub[t - 1] = -P(t - 1, t - 1) @ (vb[t - 1] / b)
     Sbar = PRR * Z
     for t in range(1, R + 1):
         if not (drop_terminal_pullback and t == R):
-            Sbar = Sbar - P(t, t) * vb[t][None, :]
-        Sbar = Sbar - P(t, t - 1) * ub[t][:, None]
+            Sbar = Sbar - P(t, t) * (vb[t] / b)[None, :]
+        Sbar = Sbar - P(t, t - 1) * (ub[t] / a)[:, None]
     return dict(Sbar=Sbar, ubar=ub, vbar=vb, dV=PRR.T @ G, O=PRR @ V, gu=gu, gv=gv)
 
 

@@ -254,6 +254,80 @@ def test_zero_bandwidth_is_identity(T, R):
     assert np.abs(out["dQ"]).max() < 1e-13 and np.abs(out["dK"]).max() < 1e-13
 
 
+# ---------------------------------------------------------------- compatible general marginals
+def _marginals(L, seed):
+    rng = np.random.default_rng(seed)
+    a, b = rng.uniform(0.4, 1.8, L), rng.uniform(0.4, 1.8, L)
+    return a, b * a.sum() / b.sum()
+
+
+@pytest.mark.parametrize("R", [1, 2])
+def test_marginals_fd_gradients_with_frozen_base(R):
+    """Row targets a and column targets b (App. "Compatible General Marginals"): central
+    differences of <G, O> with v^(0) frozen reproduce dQ, dK, dV."""
+    Q, K, V, G = problem(L=20, seed=21)
+    a, b = _marginals(20, 22)
+    kw = dict(W=4, T=5, R=R, eps=0.8, log_a=np.log(a), log_b=np.log(b))
+    ref = oracle.band(Q, K, V, G, **kw)
+    v0 = ref["UV"][1].copy()
+    h = 1e-6
+    for name, idx in (("dQ", 0), ("dK", 1), ("dV", 2)):
+        fd = np.zeros_like(Q)
+        for i in range(Q.shape[0]):
+            for k in range(Q.shape[1]):
+                args = [Q.copy(), K.copy(), V.copy()]
+                args[idx][i, k] += h
+                fp = _loss(*args, G, v0, **kw)
+                args[idx][i, k] -= 2 * h
+                fm = _loss(*args, G, v0, **kw)
+                fd[i, k] = (fp - fm) / (2 * h)
+        assert rel(ref[name], fd) < 2e-7, (name, rel(ref[name], fd))
+
+
+def test_marginals_match_dense_brute_force_and_targets():
+    """Dense library logsumexp with log a / log b added, the closed-form general-marginal
+    adjoint, and the target sums: rows of P^(t,t-1) sum to a, columns of P^(t,t) to b."""
+    L, W, T, R, eps = 22, 6, 5, 2, 0.9
+    Q, K, V, G = problem(L=L, seed=23)
+    a, b = _marginals(L, 24)
+    out = oracle.band(Q, K, V, G, W=W, T=T, R=R, eps=eps, want_sbar=True, log_a=np.log(a), log_b=np.log(b))
+    mask = dr.band_mask(L, W)
+    S = dr.scores(Q, K, eps)
+    U, Vp = dr.half_steps(S, mask, T, R, a=a, b=b)
+    for t in range(R + 1):
+        np.testing.assert_allclose(out["UV"][2 * t][:, None] + out["UV"][2 * t + 1][None, :],
+                                   U[t][:, None] + Vp[t][None, :], atol=1e-12)
+    for t in range(1, R + 1):
+        np.testing.assert_allclose(dr.plan(S, mask, out["UV"][2 * t], out["UV"][2 * t + 1]).sum(0), b, rtol=1e-13)
+        np.testing.assert_allclose(dr.plan(S, mask, out["UV"][2 * t], out["UV"][2 * t - 1]).sum(1), a, rtol=1e-13)
+    cf = dr.closed_form_adjoint(S, mask, U, Vp, V, G, a=a, b=b)
+    cs = 1.0 / (eps * np.sqrt(Q.shape[1]))
+    assert rel(out["O"], cf["O"]) < 1e-13 and rel(out["dV"], cf["dV"]) < 1e-13
+    assert rel(out["dQ"], cs * cf["Sbar"] @ K) < 1e-12 and rel(out["dK"], cs * cf["Sbar"].T @ Q) < 1e-12
+    for t in range(1, R + 1):
+        np.testing.assert_allclose(out["bars"][2 * t], cf["ubar"][t], atol=1e-13)
+        np.testing.assert_allclose(out["bars"][2 * t + 1], cf["vbar"][t], atol=1e-13)
+    # unit targets passed explicitly are the balanced problem
+    one = oracle.band(Q, K, V, G, W=W, T=T, R=R, eps=eps, log_a=np.zeros(L), log_b=np.zeros(L))
+    bal = oracle.band(Q, K, V, G, W=W, T=T, R=R, eps=eps)
+    assert all(np.array_equal(one[k], bal[k]) for k in ("O", "dQ", "dK", "dV"))
+
+
+def test_marginals_dense_support_is_textbook_matrix_scaling():
+    L, T, R, eps = 10, 7, 2, 1.1
+    Q, K, V, _ = problem(L=L, seed=25)
+    a, b = _marginals(L, 26)
+    out = oracle.band(Q, K, V, None, W=L - 1, T=T, R=R, eps=eps, log_a=np.log(a), log_b=np.log(b))
+    M = np.exp(Q @ K.T / (eps * np.sqrt(Q.shape[1])))
+    y = np.ones(L)
+    for _ in range(T + R):
+        x = a / (M @ y)
+        y = b / (M.T @ x)
+    np.testing.assert_allclose(np.exp(out["UV"][2 * R]), x, rtol=1e-12)
+    np.testing.assert_allclose(np.exp(out["UV"][2 * R + 1]), y, rtol=1e-12)
+    np.testing.assert_allclose(out["O"], (x[:, None] * M * y[None, :]) @ V, rtol=1e-12, atol=1e-14)
+
+
 def test_dense_zero_scores_is_uniform_plan():
     L = 11
     _, K, V, G = problem(L=L, seed=10)
