@@ -97,6 +97,27 @@ int sinkhorn_attn_bwd(const void *Q, const void *K, const void *V, const void *O
                       void *stream);
 
 /*
+ * The same two calls with compatible general marginals (appendix "Compatible General
+ * Marginals": half-steps u_i = log a_i - log sum_j exp(S_ij + v_j), v_j = log b_j - log sum_i
+ * exp(S_ij + u_i); in the backward every ubar is divided by a and every vbar by b where it
+ * multiplies a plan, per the general-marginal half-step Jacobians and finite-tail VJP there).
+ *   log_a, log_b: [B,H,L] fp32 device arrays, logarithms of the positive row / column
+ *   targets; the caller makes them compatible (equal totals per problem).  NULL = unit
+ *   targets (both NULL: exactly the calls above).  eta0, when requested, is the raw base
+ *   cotangent vbar^(0) (not divided by b).  Not combined with the dustbin, whose targets are
+ *   all one: SKA_EUNSUPPORTED.
+ */
+int sinkhorn_attn_fwd_marginals(const void *Q, const void *K, const void *V, const float *log_a,
+                                const float *log_b, void *O, float *UV, int B, int H, int L, int d,
+                                int W, int T, int R, float eps, int dustbin, float dustbin_score,
+                                int dtype, void *workspace, size_t workspace_bytes, void *stream);
+int sinkhorn_attn_bwd_marginals(const void *Q, const void *K, const void *V, const float *log_a,
+                                const float *log_b, const void *O, const void *dO, const float *UV,
+                                void *dQ, void *dK, void *dV, float *eta0, int B, int H, int L, int d,
+                                int W, int T, int R, float eps, int dustbin, float dustbin_score,
+                                int dtype, void *workspace, size_t workspace_bytes, void *stream);
+
+/*
  * Benchmark hooks (no part of the operator).  While enabled, every forward and backward
  * call records two HIP events on its stream around each of its phases, so that a phase can
  * be timed in place, inside a larger timed region, without a profiler.  At most 4096 phase

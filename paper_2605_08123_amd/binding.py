@@ -37,6 +37,12 @@ def load():
         lib.sinkhorn_attn_bwd.restype = i
         lib.sinkhorn_attn_bwd.argtypes = [vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, i, i, i, i, i, i, i, f,
                                           i, f, i, vp, sz, vp]
+        lib.sinkhorn_attn_fwd_marginals.restype = i
+        lib.sinkhorn_attn_fwd_marginals.argtypes = [vp, vp, vp, vp, vp, vp, vp, i, i, i, i, i, i, i, f, i, f, i,
+                                                    vp, sz, vp]
+        lib.sinkhorn_attn_bwd_marginals.restype = i
+        lib.sinkhorn_attn_bwd_marginals.argtypes = [vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, i, i, i, i,
+                                                    i, i, i, f, i, f, i, vp, sz, vp]
         lib.sinkhorn_attn_profile_enable.restype = i
         lib.sinkhorn_attn_profile_enable.argtypes = [i]
         lib.sinkhorn_attn_profile_read.restype = i
@@ -112,10 +118,24 @@ def _stream_ptr() -> int:
     return int(torch.cuda.current_stream().cuda_stream)
 
 
+def _marg_ptr(x, shape, name):
+    if x is None:
+        return None
+    _check(x, shape, torch.float32, name)
+    return x.data_ptr()
+
+
 def sinkhorn_attn_fwd(Q, K, V, W, T, R=2, eps=1.0, dustbin=False, dustbin_score=0.0, O=None, UV=None,
                       workspace=None):
     """Forward. Q, K, V: [B,H,L,d] CUDA tensors (float32 or bfloat16).
     Returns (O [B,H,L,d], UV [B,H,2(R+1),L+dustbin] float32)."""
+    return sinkhorn_attn_fwd_marginals(Q, K, V, None, None, W, T, R, eps, dustbin, dustbin_score, O, UV,
+                                       workspace)
+
+
+def sinkhorn_attn_fwd_marginals(Q, K, V, log_a, log_b, W, T, R=2, eps=1.0, dustbin=False, dustbin_score=0.0,
+                                O=None, UV=None, workspace=None):
+    """Forward with marginal targets: log_a, log_b [B,H,L] float32 CUDA tensors or None (unit)."""
     B, H, L, d = Q.shape
     for n, x in (("Q", Q), ("K", K), ("V", V)):
         _check(x, (B, H, L, d), Q.dtype, n)
@@ -129,10 +149,11 @@ def sinkhorn_attn_fwd(Q, K, V, W, T, R=2, eps=1.0, dustbin=False, dustbin_score=
     if workspace is None:
         need = sinkhorn_attn_workspace_bytes(B, H, L, d, W, T, R, dustbin, _dtype_code(Q))
         workspace = torch.empty(max(need, 16), device=Q.device, dtype=torch.uint8)
-    rc = load().sinkhorn_attn_fwd(Q.data_ptr(), K.data_ptr(), V.data_ptr(), O.data_ptr(), UV.data_ptr(),
-                                  B, H, L, d, W, T, R, float(eps), int(bool(dustbin)),
-                                  float(dustbin_score), _dtype_code(Q), workspace.data_ptr(),
-                                  workspace.numel() * workspace.element_size(), _stream_ptr())
+    rc = load().sinkhorn_attn_fwd_marginals(
+        Q.data_ptr(), K.data_ptr(), V.data_ptr(), _marg_ptr(log_a, (B, H, L), "log_a"),
+        _marg_ptr(log_b, (B, H, L), "log_b"), O.data_ptr(), UV.data_ptr(), B, H, L, d, W, T, R, float(eps),
+        int(bool(dustbin)), float(dustbin_score), _dtype_code(Q), workspace.data_ptr(),
+        workspace.numel() * workspace.element_size(), _stream_ptr())
     if rc != SKA_OK:
         raise SinkhornAttnError(rc)
     return O, UV
@@ -141,6 +162,14 @@ def sinkhorn_attn_fwd(Q, K, V, W, T, R=2, eps=1.0, dustbin=False, dustbin_score=
 def sinkhorn_attn_bwd(Q, K, V, O, dO, UV, W, T, R=2, eps=1.0, dustbin=False, dustbin_score=0.0,
                       want_eta0=False, workspace=None, dQ=None, dK=None, dV=None):
     """Backward. Returns (dQ, dK, dV[, eta0])."""
+    return sinkhorn_attn_bwd_marginals(Q, K, V, None, None, O, dO, UV, W, T, R, eps, dustbin, dustbin_score,
+                                       want_eta0, workspace, dQ, dK, dV)
+
+
+def sinkhorn_attn_bwd_marginals(Q, K, V, log_a, log_b, O, dO, UV, W, T, R=2, eps=1.0, dustbin=False,
+                                dustbin_score=0.0, want_eta0=False, workspace=None, dQ=None, dK=None,
+                                dV=None):
+    """Backward with marginal targets (see sinkhorn_attn_fwd_marginals)."""
     B, H, L, d = Q.shape
     for n, x in (("Q", Q), ("K", K), ("V", V), ("O", O), ("dO", dO)):
         _check(x, (B, H, L, d), Q.dtype, n)
@@ -156,11 +185,12 @@ def sinkhorn_attn_bwd(Q, K, V, O, dO, UV, W, T, R=2, eps=1.0, dustbin=False, dus
     if workspace is None:
         workspace = torch.empty(max(need, 16), device=Q.device, dtype=torch.uint8)
     eta0 = torch.empty((B, H, Lp), device=Q.device, dtype=torch.float32) if want_eta0 else None
-    rc = load().sinkhorn_attn_bwd(Q.data_ptr(), K.data_ptr(), V.data_ptr(), O.data_ptr(), dO.data_ptr(),
-                                  UV.data_ptr(), dQ.data_ptr(), dK.data_ptr(), dV.data_ptr(),
-                                  eta0.data_ptr() if want_eta0 else None, B, H, L, d, W, T, R, float(eps),
-                                  int(bool(dustbin)), float(dustbin_score), code, workspace.data_ptr(),
-                                  workspace.numel() * workspace.element_size(), _stream_ptr())
+    rc = load().sinkhorn_attn_bwd_marginals(
+        Q.data_ptr(), K.data_ptr(), V.data_ptr(), _marg_ptr(log_a, (B, H, L), "log_a"),
+        _marg_ptr(log_b, (B, H, L), "log_b"), O.data_ptr(), dO.data_ptr(), UV.data_ptr(), dQ.data_ptr(),
+        dK.data_ptr(), dV.data_ptr(), eta0.data_ptr() if want_eta0 else None, B, H, L, d, W, T, R,
+        float(eps), int(bool(dustbin)), float(dustbin_score), code, workspace.data_ptr(),
+        workspace.numel() * workspace.element_size(), _stream_ptr())
     if rc != SKA_OK:
         raise SinkhornAttnError(rc)
     return (dQ, dK, dV, eta0) if want_eta0 else (dQ, dK, dV)

@@ -73,6 +73,8 @@ struct SweepArgs {
     Vec w;            // MATVEC weights on the other side
     Vec pre;          // MATVEC additive term on the owner side (may be null)
     VecOut out_vec;   // LSE / MATVEC result
+    Vec olog;         // log of the owner side's marginal target (null: unit targets).  LSE adds it
+                      // to the result; MATVEC and the dot of APPLY divide their result by the target
     const float4 *po; // FINAL: owner-side modifier pack   [N][ldp][pstride], first group of this sweep
     const float4 *qt; // FINAL: other-side modifier pack   [N][ldp][pstride]
     int nq;           // groups of four terms this sweep takes (1 or 2)
@@ -573,7 +575,11 @@ __global__ __launch_bounds__(NTHREADS) void sweep_kernel(const SweepArgs a)
                 tot = tot * fast_exp2(mn - m3) + fast_exp2(xd - m3);
                 mn = m3;
             }
-            if (h == 0 && o < L) a.out_vec.p[n * a.out_vec.stride + o] = -LN2 * (mn + fast_log2(tot));
+            if (h == 0 && o < L) {
+                float r = -LN2 * (mn + fast_log2(tot));
+                if (a.olog.p) r += a.olog.p[n * a.olog.stride + o];
+                a.out_vec.p[n * a.out_vec.stride + o] = r;
+            }
         } else {
             float fac = 0.f;
             if (o < L) fac = fast_exp2((xsp[o] - mblk) * LOG2E);
@@ -609,7 +615,10 @@ __global__ __launch_bounds__(NTHREADS) void sweep_kernel(const SweepArgs a)
             if constexpr (MODE == M_APPLY) {
                 if (a.dot_mat) {
                     dot += __shfl_xor(dot, 32);
-                    if (h == 0 && o < L) a.dot_out.p[n * a.dot_out.stride + o] = dot;
+                    if (h == 0 && o < L) {
+                        if (a.olog.p) dot *= __expf(-a.olog.p[n * a.olog.stride + o]);
+                        a.dot_out.p[n * a.dot_out.stride + o] = dot;
+                    }
                 }
             }
         }
@@ -850,9 +859,11 @@ __global__ __launch_bounds__(NTHREADS) void vsweep_kernel(const SweepArgs a)
             float r;
             if constexpr (MODE == M_LSE) {
                 r = mblk - LN2 * fast_log2(tot);
+                if (a.olog.p) r += a.olog.p[n * a.olog.stride + o];
             } else {
                 float pre = a.pre.p ? a.pre.p[n * a.pre.stride + o] : 0.f;
                 r = pre - fast_exp2((xsp[o] - mblk) * LOG2E) * tot;
+                if (a.olog.p) r *= __expf(-a.olog.p[n * a.olog.stride + o]);
             }
             a.out_vec.p[n * a.out_vec.stride + o] = r;
         }
@@ -1158,7 +1169,10 @@ __global__ __launch_bounds__(NTHREADS) void msweep_kernel(const SweepArgs a)
         if constexpr (MODE == M_APPLY) {
             if (a.dot_mat) {
                 dot += __shfl_xor(dot, 32);
-                if (h == 0 && o < L) a.dot_out.p[n * a.dot_out.stride + o] = dot;
+                if (h == 0 && o < L) {
+                    if (a.olog.p) dot *= __expf(-a.olog.p[n * a.olog.stride + o]);
+                    a.dot_out.p[n * a.dot_out.stride + o] = dot;
+                }
             }
         }
     }
@@ -1316,6 +1330,7 @@ __global__ __launch_bounds__(1024) void dustbin_kernel(Vec y, Vec w, Vec x, VecO
 struct Problem {
     int B, H, L, d, W, T, R, dustbin, dtype;
     float eps, sdb;
+    const float *log_a = nullptr, *log_b = nullptr;   // [N][Lp] logs of the marginal targets, or null
     int N() const { return B * H; }
     int Lp() const { return L + (dustbin ? 1 : 0); }
     long ldw() const { return ((long)Lp() + 3) / 4 * 4; }  // stride of workspace vectors
@@ -1361,6 +1376,7 @@ int check_common(const Problem &p)
     if (!(p.eps > 0.f) || !isfinite(p.eps) || !isfinite(p.sdb)) return SKA_EINVAL;
     if ((long)p.B * p.H > 65535) return SKA_EINVAL;
     if (p.L > (1 << 24)) return SKA_EUNSUPPORTED;   // 32-bit byte offsets inside one [L][d] matrix
+    if ((p.log_a || p.log_b) && p.dustbin) return SKA_EUNSUPPORTED;   // the dustbin's targets are all one
     if (p.R < 1 || p.R > MAXR) return SKA_EUNSUPPORTED;
     if (p.d != 32 && p.d != 64 && p.d != 128) return SKA_EUNSUPPORTED;
     if (p.dtype != SKA_F32 && p.dtype != SKA_BF16) return SKA_EUNSUPPORTED;
@@ -1520,6 +1536,7 @@ int fwd_impl(const Problem &p, const void *Qin, const void *K, const void *V, vo
         SweepArgs a = base;
         a.X = row ? Q : K; a.Y = row ? K : Q;
         a.yt = vec(yslot); a.xs = vec(prevslot); a.out_vec = vout(outslot);
+        a.olog = Vec{row ? p.log_a : p.log_b, (long)Lp};
         // successive sweeps walk the blocks in opposite directions: a sweep then starts on
         // the rows its predecessor touched last, which are still in L2
         a.rev = nlaunch++ & 1;
@@ -1620,15 +1637,17 @@ int bwd_impl(const Problem &p, const void *Qin, const void *K, const void *V, co
         SweepArgs a = base;
         a.X = K; a.Y = Q; a.Pay = G; a.out_mat = dV; a.xs = uv(2 * R + 1); a.yt = uv(2 * R);
         a.dot_mat = V; a.dot_out = wo(vbar(R));
+        a.olog = Vec{p.log_b, (long)Lp};   // the workspace holds vbar / b and ubar / a (general marginals)
         a.rev = nlaunch++ & 1;
         SKA_TRY((sweep<T, D>(M_APPLY, a, N, st)));
     }
     // reverse recurrences of Prop. 1, each one band mat-vec with a staircase factor
     // written as P22 times row/column modifiers folded into the exponent (Prop. 2)
-    auto matvec = [&](bool row, Vec xs, Vec yt, float *w, float *pre, VecOut out) -> int {
+    auto matvec = [&](bool row, Vec xs, Vec yt, float *w, float *pre, VecOut out, bool scaled = true) -> int {
         SweepArgs a = base;
         a.X = row ? Q : K; a.Y = row ? K : Q;
         a.xs = xs; a.yt = yt; a.w = wv(w); a.pre = Vec{pre, ldw}; a.out_vec = out;
+        if (scaled) a.olog = Vec{row ? p.log_a : p.log_b, (long)Lp};
         a.rev = nlaunch++ & 1;
         SKA_TRY((sweep<T, D>(M_MATVEC, a, N, st)));
         if (p.dustbin) {
@@ -1645,7 +1664,7 @@ int bwd_impl(const Problem &p, const void *Qin, const void *K, const void *V, co
         for (int t = R; t >= 1; --t) {
             // vbar_{t-1} = -(P_t,t-1)^T ubar_t   (t = 1: the base cotangent, only on request)
             if (t >= 2) SKA_TRY(matvec(false, uv(2 * t - 1), uv(2 * t), ubar(t), nullptr, wo(vbar(t - 1))));
-            else if (eta0) SKA_TRY(matvec(false, uv(1), uv(2), ubar(1), nullptr, VecOut{eta0, (long)Lp}));
+            else if (eta0) SKA_TRY(matvec(false, uv(1), uv(2), ubar(1), nullptr, VecOut{eta0, (long)Lp}, false));
             // ubar_{t-1} = -P_{t-1,t-1} vbar_{t-1}
             if (t >= 2) SKA_TRY(matvec(true, uv(2 * t - 2), uv(2 * t - 1), vbar(t - 1), nullptr, wo(ubar(t - 1))));
         }
@@ -1696,11 +1715,12 @@ size_t sinkhorn_attn_workspace_bytes(int B, int H, int L, int d, int W, int T, i
     return ws_bytes(p);
 }
 
-int sinkhorn_attn_fwd(const void *Q, const void *K, const void *V, void *O, float *UV, int B, int H, int L,
-                      int d, int W, int T, int R, float eps, int dustbin, float dustbin_score, int dtype,
-                      void *workspace, size_t workspace_bytes, void *stream)
+int sinkhorn_attn_fwd_marginals(const void *Q, const void *K, const void *V, const float *log_a,
+                                const float *log_b, void *O, float *UV, int B, int H, int L, int d, int W,
+                                int T, int R, float eps, int dustbin, float dustbin_score, int dtype,
+                                void *workspace, size_t workspace_bytes, void *stream)
 {
-    Problem p{B, H, L, d, W, T, R, dustbin ? 1 : 0, dtype, eps, dustbin_score};
+    Problem p{B, H, L, d, W, T, R, dustbin ? 1 : 0, dtype, eps, dustbin_score, log_a, log_b};
     if (!Q || !K || !V || !O || !UV) return SKA_EINVAL;
     int rc = check_common(p);
     if (rc != SKA_OK) return rc;
@@ -1720,12 +1740,21 @@ int sinkhorn_attn_fwd(const void *Q, const void *K, const void *V, void *O, floa
 #undef SKA_FWD
 }
 
-int sinkhorn_attn_bwd(const void *Q, const void *K, const void *V, const void *O, const void *dO,
-                      const float *UV, void *dQ, void *dK, void *dV, float *eta0, int B, int H, int L, int d,
-                      int W, int T, int R, float eps, int dustbin, float dustbin_score, int dtype,
+int sinkhorn_attn_fwd(const void *Q, const void *K, const void *V, void *O, float *UV, int B, int H, int L,
+                      int d, int W, int T, int R, float eps, int dustbin, float dustbin_score, int dtype,
                       void *workspace, size_t workspace_bytes, void *stream)
 {
-    Problem p{B, H, L, d, W, T, R, dustbin ? 1 : 0, dtype, eps, dustbin_score};
+    return sinkhorn_attn_fwd_marginals(Q, K, V, nullptr, nullptr, O, UV, B, H, L, d, W, T, R, eps, dustbin,
+                                       dustbin_score, dtype, workspace, workspace_bytes, stream);
+}
+
+int sinkhorn_attn_bwd_marginals(const void *Q, const void *K, const void *V, const float *log_a,
+                                const float *log_b, const void *O, const void *dO, const float *UV, void *dQ,
+                                void *dK, void *dV, float *eta0, int B, int H, int L, int d, int W, int T,
+                                int R, float eps, int dustbin, float dustbin_score, int dtype,
+                                void *workspace, size_t workspace_bytes, void *stream)
+{
+    Problem p{B, H, L, d, W, T, R, dustbin ? 1 : 0, dtype, eps, dustbin_score, log_a, log_b};
     if (!Q || !K || !V || !O || !dO || !UV || !dQ || !dK || !dV) return SKA_EINVAL;
     int rc = check_common(p);
     if (rc != SKA_OK) return rc;
@@ -1743,6 +1772,16 @@ int sinkhorn_attn_bwd(const void *Q, const void *K, const void *V, const void *O
         SKA_BWD(__bf16, 128);
     }
 #undef SKA_BWD
+}
+
+int sinkhorn_attn_bwd(const void *Q, const void *K, const void *V, const void *O, const void *dO,
+                      const float *UV, void *dQ, void *dK, void *dV, float *eta0, int B, int H, int L, int d,
+                      int W, int T, int R, float eps, int dustbin, float dustbin_score, int dtype,
+                      void *workspace, size_t workspace_bytes, void *stream)
+{
+    return sinkhorn_attn_bwd_marginals(Q, K, V, nullptr, nullptr, O, dO, UV, dQ, dK, dV, eta0, B, H, L, d, W,
+                                       T, R, eps, dustbin, dustbin_score, dtype, workspace, workspace_bytes,
+                                       stream);
 }
 
 int sinkhorn_attn_profile_enable(int on)

@@ -154,6 +154,62 @@ def test_bias_certificate_by_difference():
     assert np.abs(g_full["dV"] - g_stop["dV"]).max() < 1e-4      # V does not enter the base solve
 
 
+def _targets(w, seed):
+    rng = np.random.default_rng(seed)
+    a = rng.uniform(0.4, 1.8, (w.B, w.H, w.L))
+    b = rng.uniform(0.4, 1.8, (w.B, w.H, w.L))
+    b *= a.sum(-1, keepdims=True) / b.sum(-1, keepdims=True)      # compatible totals
+    return np.log(a).astype(np.float32), np.log(b).astype(np.float32)
+
+
+@pytest.mark.parametrize("dtype,d,R", [("f32", 32, 2), ("bf16", 64, 2), ("bf16", 64, 3), ("f32", 64, 1)])
+def test_general_marginals(dtype, d, R):
+    """Row targets a and column targets b (appendix on compatible general marginals) against
+    the oracle; unit targets passed explicitly reproduce the balanced call bit for bit."""
+    import torch
+
+    import paper_2605_08123_amd as ska
+    w = small("marg", 500, d, 33, 6, dtype, eps=0.8, B=1, H=2, R=R)
+    print(f"\n[case] {w} with marginals", flush=True)
+    arrays = make_inputs(w, 31)
+    la, lb = _targets(w, 32)
+    dev = torch.device("cuda:0")
+    td = torch.float32 if dtype == "f32" else torch.bfloat16
+    Q, K, V, G = (torch.from_numpy(x).to(dev).to(td) for x in arrays)
+    tla, tlb = torch.from_numpy(la).to(dev), torch.from_numpy(lb).to(dev)
+    O, UV = ska.sinkhorn_attn_fwd_marginals(Q, K, V, tla, tlb, w.W, w.T, w.R, w.eps)
+    dQ, dK, dV, eta0 = ska.sinkhorn_attn_bwd_marginals(Q, K, V, tla, tlb, O, G, UV, w.W, w.T, w.R, w.eps,
+                                                       want_eta0=True)
+    torch.cuda.synchronize()
+    ref = oracle.band_batched(*arrays, w.W, w.T, w.R, w.eps, log_a=la.astype(np.float64),
+                              log_b=lb.astype(np.float64))
+    got = {k: v.float().cpu().numpy().astype(np.float64) for k, v in dict(O=O, dQ=dQ, dK=dK, dV=dV).items()}
+    errs = {k: rel(got[k], ref[k]) for k in got}
+    print("   rel-L2:", {k: f"{v:.2e}" for k, v in errs.items()}, flush=True)
+    for k, e in errs.items():
+        assert e <= TOL[dtype], (k, e)
+    # the targets are met: column sums of P_RR are b, so <1, O-weights> ... checked through the
+    # potentials: u_R + v_R agrees with the oracle's
+    s_got = (UV[:, :, 2 * R] + UV[:, :, 2 * R + 1]).cpu().numpy()
+    s_ref = ref["UV"][:, :, 2 * R] + ref["UV"][:, :, 2 * R + 1]
+    assert np.abs(s_got - s_ref).max() < (2e-4 if dtype == "f32" else 2e-2)
+    if dtype == "f32":
+        q, k, v, g = (x[0, 0] for x in arrays)
+        one = oracle.band(q, k, v, g, w.W, w.T, w.R, w.eps, log_a=la[0, 0].astype(np.float64),
+                          log_b=lb[0, 0].astype(np.float64))
+        assert rel(eta0[0, 0].cpu().numpy().astype(np.float64), one["bars"][1]) < 1e-3
+    # unit targets given explicitly == the balanced entry point
+    z = torch.zeros_like(tla)
+    O1, UV1 = ska.sinkhorn_attn_fwd_marginals(Q, K, V, z, z, w.W, w.T, w.R, w.eps)
+    O0, UV0 = ska.sinkhorn_attn_fwd(Q, K, V, w.W, w.T, w.R, w.eps)
+    g1 = ska.sinkhorn_attn_bwd_marginals(Q, K, V, z, z, O1, G, UV1, w.W, w.T, w.R, w.eps)
+    g0 = ska.sinkhorn_attn_bwd(Q, K, V, O0, G, UV0, w.W, w.T, w.R, w.eps)
+    assert torch.equal(O1, O0) and all(torch.equal(x, y) for x, y in zip(g1, g0))
+    with pytest.raises(ska.SinkhornAttnError) as e:      # no marginals on the dustbin's unit-target space
+        ska.sinkhorn_attn_fwd_marginals(Q, K, V, tla, tlb, w.W, w.T, w.R, w.eps, dustbin=True)
+    assert e.value.status == -2
+
+
 def test_tail_depth_dustbin():
     check(small("taildb", 300, 64, 24, 4, "bf16", eps=0.9, R=3, dustbin=True, dustbin_score=-0.2), seed=17)
     check(small("taildb", 300, 32, 24, 4, "f32", eps=0.9, R=1, dustbin=True, dustbin_score=0.4), seed=18)
