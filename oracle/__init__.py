@@ -130,6 +130,35 @@ def band(Q, K, V, G, W, T, R, eps, dustbin=False, dustbin_score=0.0, v0_fixed=No
     return out
 
 
+def band_rect(Q, K, V, G, W, T, R, eps, log_a=None, log_b=None):
+    """Banded operator on a rectangle: Q, G are [Lq, d], K, V are [Lk, d] (token sequences of
+    different lengths, or a padded batch item cut to its valid lengths); the support is
+    {(i, j): |i - j| <= W, i < Lq, j < Lk}.  The support and the edge scores are built here and
+    handed to the support-generic core; the score cotangent is pushed to Q and K by the chain
+    rule of S = Q K^T / (eps sqrt d).  Returns O, dQ [Lq, d], dK, dV [Lk, d], U [(R+1), Lq],
+    Vp [(R+1), Lk] (rows or columns without any active edge have potential 0 and zero results).
+    """
+    Q, K, V, G = _f64(Q), _f64(K), _f64(V), _f64(G)
+    (Lq, d), Lk = Q.shape, K.shape[0]
+    assert K.shape == (Lk, d) and V.shape == (Lk, d) and (G is None or G.shape == (Lq, d))
+    lo = np.maximum(np.arange(Lq) - W, 0)
+    hi = np.minimum(np.arange(Lq) + W, Lk - 1)
+    cnt = np.maximum(hi - lo + 1, 0)
+    rptr = np.concatenate(([0], np.cumsum(cnt))).astype(np.int64)
+    rows = np.repeat(np.arange(Lq), cnt)
+    cols = (np.arange(rptr[-1]) - np.repeat(rptr[:-1], cnt) + np.repeat(lo, cnt)).astype(np.int32)
+    cs = 1.0 / (eps * np.sqrt(d))
+    S = cs * np.einsum("ek,ek->e", Q[rows], K[cols])
+    r = core(rptr, cols, S, V, G, T, R, log_a=log_a, log_b=log_b)
+    out = {"O": r["O"], "U": r["U"], "Vp": r["Vp"]}
+    if G is not None:
+        dQ, dK = np.zeros_like(Q), np.zeros_like(K)
+        np.add.at(dQ, rows, cs * r["Sbar"][:, None] * K[cols])
+        np.add.at(dK, cols, cs * r["Sbar"][:, None] * Q[rows])
+        out.update(dQ=dQ, dK=dK, dV=r["dV"], ubar=r["ubar"], vbar=r["vbar"])
+    return out
+
+
 def band_batched(Q, K, V, G, W, T, R, eps, dustbin=False, dustbin_score=0.0, log_a=None, log_b=None):
     """[B,H,L,d] inputs, one independent problem per (b,h) (log_a, log_b: [B,H,Lp] or None).
     Returns stacked arrays."""

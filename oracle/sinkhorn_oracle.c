@@ -110,7 +110,9 @@ static void row_half_step(const support_t *sp, const double *S, const double *v,
         double s = 0.0;
         for (int64_t e = sp->rptr[i]; e < sp->rptr[i + 1]; ++e)
             s += exp(S[e] + v[sp->col[e]] - mx);
-        u[i] = (loga ? loga[i] : 0.0) - (mx + log(s));
+        /* a row without active edges (possible on rectangular supports) takes no part: its
+           potential is reported as 0 and multiplies nothing */
+        u[i] = sp->rptr[i] == sp->rptr[i + 1] ? 0.0 : (loga ? loga[i] : 0.0) - (mx + log(s));
     }
 }
 
@@ -131,7 +133,7 @@ static void col_half_step(const support_t *sp, const double *S, const double *u,
             int64_t e = sp->cedge[c];
             s += exp(S[e] + u[sp->erow[e]] - mx);
         }
-        v[j] = (logb ? logb[j] : 0.0) - (mx + log(s));
+        v[j] = sp->cptr[j] == sp->cptr[j + 1] ? 0.0 : (logb ? logb[j] : 0.0) - (mx + log(s));
     }
 }
 

@@ -328,6 +328,33 @@ def test_marginals_dense_support_is_textbook_matrix_scaling():
     np.testing.assert_allclose(out["O"], (x[:, None] * M * y[None, :]) @ V, rtol=1e-12, atol=1e-14)
 
 
+# ---------------------------------------------------------------- rectangular band
+@pytest.mark.parametrize("Lq,Lk,W", [(19, 26, 7), (30, 21, 9), (12, 12, 3), (25, 14, 5)])
+def test_rectangular_band_matches_dense_brute_force(Lq, Lk, W):
+    """Sequences of different lengths: |i - j| <= W on an Lq x Lk rectangle.  Dense library
+    logsumexp with a boolean mask and the closed-form adjoint, entry by entry on dQ, dK, dV;
+    the square case is the banded operator.  (25, 14, 5) leaves rows 19..24 without any edge.)"""
+    rng = np.random.default_rng(Lq * 100 + Lk)
+    Q, G = rng.standard_normal((Lq, 4)), rng.standard_normal((Lq, 4))
+    K, V = rng.standard_normal((Lk, 4)), rng.standard_normal((Lk, 4))
+    T, R, eps = 4, 2, 0.9
+    out = oracle.band_rect(Q, K, V, G, W, T, R, eps)
+    mask = np.abs(np.arange(Lq)[:, None] - np.arange(Lk)[None, :]) <= W
+    S = dr.scores(Q, K, eps)
+    live = mask.any(1)
+    with np.errstate(invalid="ignore", divide="ignore"):
+        U, Vp = dr.half_steps(S[live], mask[live], T, R)      # rows without edges take no part
+        cf = dr.closed_form_adjoint(S[live], mask[live], U, Vp, V, G[live])
+    cs = 1.0 / (eps * np.sqrt(4))
+    assert rel(out["O"][live], cf["O"]) < 1e-13 and np.all(out["O"][~live] == 0.0)
+    assert rel(out["dV"], cf["dV"]) < 1e-13
+    assert rel(out["dQ"][live], cs * cf["Sbar"] @ K) < 1e-12 and np.all(out["dQ"][~live] == 0.0)
+    assert rel(out["dK"], cs * cf["Sbar"].T @ Q[live]) < 1e-12
+    if Lq == Lk:
+        sq = oracle.band(Q, K, V, G, W, T, R, eps)
+        assert all(rel(out[k], sq[k]) < 1e-14 for k in ("O", "dQ", "dK", "dV"))
+
+
 def test_dense_zero_scores_is_uniform_plan():
     L = 11
     _, K, V, G = problem(L=L, seed=10)
