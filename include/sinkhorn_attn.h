@@ -118,6 +118,33 @@ int sinkhorn_attn_bwd_marginals(const void *Q, const void *K, const void *V, con
                                 int dtype, void *workspace, size_t workspace_bytes, void *stream);
 
 /*
+ * The same two calls on a padded batch of sequences of different lengths (the remark after
+ * Eq. 1-2: rectangular masked examples run the same unit-target half-steps although their
+ * active row and column counts differ).  Batch item b uses the support
+ * {(i, j): |i - j| <= W, i < len_q[b], j < len_k[b]} in all of its H heads.
+ *   len_q, len_k: int32 device arrays [B]; values are clamped to [0, L]; NULL = L.  Both
+ *   NULL: exactly the calls above.  The arrays are read by the kernels, never by the host.
+ *   Rows of Q, dO beyond len_q[b] and of K, V beyond len_k[b] are never used (they may hold
+ *   anything).  Results there are zeros: rows of O, dQ beyond len_q[b], of dK, dV beyond
+ *   len_k[b], and the potentials (and eta0) of indices beyond the lengths.  A query row whose
+ *   band holds no valid key (i - W >= len_k[b]), and likewise a key column, takes no part
+ *   either: potential 0, zero results.  Strides stay those of the padded [B,H,L,...] arrays.
+ *   log_a, log_b as in the marginals calls (entries beyond the lengths are not read).
+ *   Not combined with the dustbin (its element sits at index L): SKA_EUNSUPPORTED.
+ */
+int sinkhorn_attn_fwd_varlen(const void *Q, const void *K, const void *V, const float *log_a,
+                             const float *log_b, const int *len_q, const int *len_k, void *O,
+                             float *UV, int B, int H, int L, int d, int W, int T, int R, float eps,
+                             int dustbin, float dustbin_score, int dtype, void *workspace,
+                             size_t workspace_bytes, void *stream);
+int sinkhorn_attn_bwd_varlen(const void *Q, const void *K, const void *V, const float *log_a,
+                             const float *log_b, const int *len_q, const int *len_k, const void *O,
+                             const void *dO, const float *UV, void *dQ, void *dK, void *dV,
+                             float *eta0, int B, int H, int L, int d, int W, int T, int R, float eps,
+                             int dustbin, float dustbin_score, int dtype, void *workspace,
+                             size_t workspace_bytes, void *stream);
+
+/*
  * Benchmark hooks (no part of the operator).  While enabled, every forward and backward
  * call records two HIP events on its stream around each of its phases, so that a phase can
  * be timed in place, inside a larger timed region, without a profiler.  At most 4096 phase

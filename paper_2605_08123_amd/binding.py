@@ -43,6 +43,12 @@ def load():
         lib.sinkhorn_attn_bwd_marginals.restype = i
         lib.sinkhorn_attn_bwd_marginals.argtypes = [vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, i, i, i, i,
                                                     i, i, i, f, i, f, i, vp, sz, vp]
+        lib.sinkhorn_attn_fwd_varlen.restype = i
+        lib.sinkhorn_attn_fwd_varlen.argtypes = [vp, vp, vp, vp, vp, vp, vp, vp, vp, i, i, i, i, i, i, i, f, i, f,
+                                                 i, vp, sz, vp]
+        lib.sinkhorn_attn_bwd_varlen.restype = i
+        lib.sinkhorn_attn_bwd_varlen.argtypes = [vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, i, i, i,
+                                                 i, i, i, i, f, i, f, i, vp, sz, vp]
         lib.sinkhorn_attn_profile_enable.restype = i
         lib.sinkhorn_attn_profile_enable.argtypes = [i]
         lib.sinkhorn_attn_profile_read.restype = i
@@ -125,6 +131,13 @@ def _marg_ptr(x, shape, name):
     return x.data_ptr()
 
 
+def _len_ptr(x, B, name):
+    if x is None:
+        return None
+    _check(x, (B,), torch.int32, name)
+    return x.data_ptr()
+
+
 def sinkhorn_attn_fwd(Q, K, V, W, T, R=2, eps=1.0, dustbin=False, dustbin_score=0.0, O=None, UV=None,
                       workspace=None):
     """Forward. Q, K, V: [B,H,L,d] CUDA tensors (float32 or bfloat16).
@@ -136,6 +149,14 @@ def sinkhorn_attn_fwd(Q, K, V, W, T, R=2, eps=1.0, dustbin=False, dustbin_score=
 def sinkhorn_attn_fwd_marginals(Q, K, V, log_a, log_b, W, T, R=2, eps=1.0, dustbin=False, dustbin_score=0.0,
                                 O=None, UV=None, workspace=None):
     """Forward with marginal targets: log_a, log_b [B,H,L] float32 CUDA tensors or None (unit)."""
+    return sinkhorn_attn_fwd_varlen(Q, K, V, log_a, log_b, None, None, W, T, R, eps, dustbin, dustbin_score, O,
+                                    UV, workspace)
+
+
+def sinkhorn_attn_fwd_varlen(Q, K, V, log_a, log_b, len_q, len_k, W, T, R=2, eps=1.0, dustbin=False,
+                             dustbin_score=0.0, O=None, UV=None, workspace=None):
+    """Forward of a padded batch: len_q, len_k are int32 CUDA tensors [B] (or None: L) with the valid
+    lengths of the query and key sequences of each batch item; results beyond them are zeros."""
     B, H, L, d = Q.shape
     for n, x in (("Q", Q), ("K", K), ("V", V)):
         _check(x, (B, H, L, d), Q.dtype, n)
@@ -149,9 +170,10 @@ def sinkhorn_attn_fwd_marginals(Q, K, V, log_a, log_b, W, T, R=2, eps=1.0, dustb
     if workspace is None:
         need = sinkhorn_attn_workspace_bytes(B, H, L, d, W, T, R, dustbin, _dtype_code(Q))
         workspace = torch.empty(max(need, 16), device=Q.device, dtype=torch.uint8)
-    rc = load().sinkhorn_attn_fwd_marginals(
+    rc = load().sinkhorn_attn_fwd_varlen(
         Q.data_ptr(), K.data_ptr(), V.data_ptr(), _marg_ptr(log_a, (B, H, L), "log_a"),
-        _marg_ptr(log_b, (B, H, L), "log_b"), O.data_ptr(), UV.data_ptr(), B, H, L, d, W, T, R, float(eps),
+        _marg_ptr(log_b, (B, H, L), "log_b"), _len_ptr(len_q, B, "len_q"), _len_ptr(len_k, B, "len_k"),
+        O.data_ptr(), UV.data_ptr(), B, H, L, d, W, T, R, float(eps),
         int(bool(dustbin)), float(dustbin_score), _dtype_code(Q), workspace.data_ptr(),
         workspace.numel() * workspace.element_size(), _stream_ptr())
     if rc != SKA_OK:
@@ -170,6 +192,14 @@ def sinkhorn_attn_bwd_marginals(Q, K, V, log_a, log_b, O, dO, UV, W, T, R=2, eps
                                 dustbin_score=0.0, want_eta0=False, workspace=None, dQ=None, dK=None,
                                 dV=None):
     """Backward with marginal targets (see sinkhorn_attn_fwd_marginals)."""
+    return sinkhorn_attn_bwd_varlen(Q, K, V, log_a, log_b, None, None, O, dO, UV, W, T, R, eps, dustbin,
+                                    dustbin_score, want_eta0, workspace, dQ, dK, dV)
+
+
+def sinkhorn_attn_bwd_varlen(Q, K, V, log_a, log_b, len_q, len_k, O, dO, UV, W, T, R=2, eps=1.0,
+                             dustbin=False, dustbin_score=0.0, want_eta0=False, workspace=None, dQ=None,
+                             dK=None, dV=None):
+    """Backward of a padded batch (see sinkhorn_attn_fwd_varlen)."""
     B, H, L, d = Q.shape
     for n, x in (("Q", Q), ("K", K), ("V", V), ("O", O), ("dO", dO)):
         _check(x, (B, H, L, d), Q.dtype, n)
@@ -185,9 +215,10 @@ def sinkhorn_attn_bwd_marginals(Q, K, V, log_a, log_b, O, dO, UV, W, T, R=2, eps
     if workspace is None:
         workspace = torch.empty(max(need, 16), device=Q.device, dtype=torch.uint8)
     eta0 = torch.empty((B, H, Lp), device=Q.device, dtype=torch.float32) if want_eta0 else None
-    rc = load().sinkhorn_attn_bwd_marginals(
+    rc = load().sinkhorn_attn_bwd_varlen(
         Q.data_ptr(), K.data_ptr(), V.data_ptr(), _marg_ptr(log_a, (B, H, L), "log_a"),
-        _marg_ptr(log_b, (B, H, L), "log_b"), O.data_ptr(), dO.data_ptr(), UV.data_ptr(), dQ.data_ptr(),
+        _marg_ptr(log_b, (B, H, L), "log_b"), _len_ptr(len_q, B, "len_q"), _len_ptr(len_k, B, "len_k"),
+        O.data_ptr(), dO.data_ptr(), UV.data_ptr(), dQ.data_ptr(),
         dK.data_ptr(), dV.data_ptr(), eta0.data_ptr() if want_eta0 else None, B, H, L, d, W, T, R,
         float(eps), int(bool(dustbin)), float(dustbin_score), code, workspace.data_ptr(),
         workspace.numel() * workspace.element_size(), _stream_ptr())

@@ -87,6 +87,9 @@ struct SweepArgs {
     const void *dot_mat;  // APPLY: if set, dot_out_o = <dot_mat_o, out_o> (fp32 accumulators)
     VecOut dot_out;
     int L, W;
+    const int *len_own;   // valid owner-side length of each batch item (null: L), device memory [N / nh]
+    const int *len_oth;   // valid other-side length of each batch item (null: L)
+    int nh;               // problems per batch item (heads)
     float c2;         // log2(e) / (eps sqrt d)
     float cs;         // 1 / (eps sqrt d)
     int dustbin;
@@ -107,6 +110,33 @@ template <> struct Elem<__bf16> {
 
 __device__ __forceinline__ float fast_exp2(float x) { return __builtin_amdgcn_exp2f(x); }
 __device__ __forceinline__ float fast_log2(float x) { return __builtin_amdgcn_logf(x); }
+
+// Valid lengths of problem n (padded batches, sequences of different lengths): Lt other-side
+// indices exist, and Le owner indices have at least one band edge (o < Lo and o - W < Lt).
+// Owner rows in [Le, L) take no part and get zeros.  Uniform over the workgroup.
+struct Lens { int Lt, Le; };
+__device__ __forceinline__ Lens problem_lens(const SweepArgs &a, int n)
+{
+    int Lo = a.L, Lt = a.L;
+    if (a.len_own) Lo = min(max(a.len_own[n / a.nh], 0), a.L);
+    if (a.len_oth) Lt = min(max(a.len_oth[n / a.nh], 0), a.L);
+    return Lens{Lt, Lt > 0 ? min(Lo, Lt + a.W) : 0};
+}
+// A workgroup whose owner rows all lie beyond the valid length writes its zeros and leaves.
+template <typename T, int D, int BM>
+__device__ __forceinline__ void zero_block(const SweepArgs &a, int n, int o_blk, bool mat, bool vec)
+{
+    const int rows = min(BM, a.L - o_blk);
+    if (mat && !a.accum) {
+        uint4 *dst = reinterpret_cast<uint4 *>(reinterpret_cast<T *>(a.out_mat) + ((long)n * a.L + o_blk) * D);
+        const int n16 = rows * D * (int)sizeof(T) / 16;
+        for (int i = threadIdx.x; i < n16; i += NTHREADS) dst[i] = make_uint4(0, 0, 0, 0);
+    }
+    for (int i = threadIdx.x; i < rows; i += NTHREADS) {
+        if (vec) a.out_vec.p[n * a.out_vec.stride + o_blk + i] = 0.f;
+        if (mat && a.dot_mat) a.dot_out.p[n * a.dot_out.stride + o_blk + i] = 0.f;
+    }
+}
 
 __device__ __forceinline__ bf16x8 pack8(const float *e)
 {
@@ -382,6 +412,12 @@ __global__ __launch_bounds__(NTHREADS) void sweep_kernel(const SweepArgs a)
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int c = lane & 31, h = lane >> 5;
     const int L = a.L, W = a.W;
+    const Lens ln = problem_lens(a, n);
+    const int Lt = ln.Lt, Le = ln.Le;
+    if (o_blk >= Le) {
+        zero_block<T, D, BM>(a, n, o_blk, MAT_OUT, !MAT_OUT);
+        return;
+    }
     const long moff = (long)n * L * D;
     const T *Xb = reinterpret_cast<const T *>(a.X) + moff;
     const T *Yb = reinterpret_cast<const T *>(a.Y) + moff;
@@ -393,7 +429,7 @@ __global__ __launch_bounds__(NTHREADS) void sweep_kernel(const SweepArgs a)
     if constexpr (MODE != M_LSE_FIRST) {
         float m = -INFINITY;
         for (int i = tid; i < BM; i += NTHREADS)
-            if (o_blk + i < L) m = fmaxf(m, xsp[o_blk + i]);
+            if (o_blk + i < Le) m = fmaxf(m, xsp[o_blk + i]);
 #pragma unroll
         for (int s = 32; s >= 1; s >>= 1) m = fmaxf(m, __shfl_xor(m, s));
         if (lane == 0) red[wave] = m;
@@ -410,12 +446,12 @@ __global__ __launch_bounds__(NTHREADS) void sweep_kernel(const SweepArgs a)
 #pragma unroll
     for (int f = 0; f < FR; ++f) {
         o_frag[f] = o_blk + (wave * FR + f) * 32;
-        xf[f].load(Xb, o_frag[f] + c, L, h);
+        xf[f].load(Xb, o_frag[f] + c, Le, h);
         if constexpr (MODE == M_FINAL) {
-            af[f].load(reinterpret_cast<const T *>(a.A) + moff, o_frag[f] + c, L, h);
+            af[f].load(reinterpret_cast<const T *>(a.A) + moff, o_frag[f] + c, Le, h);
 #pragma unroll
             for (int g = 0; g < MAXNQ; ++g)
-                pof[f][g] = (o_frag[f] + c < L && g < a.nq) ? a.po[(n * a.ldp + o_frag[f] + c) * a.pstride + g]
+                pof[f][g] = (o_frag[f] + c < Le && g < a.nq) ? a.po[(n * a.ldp + o_frag[f] + c) * a.pstride + g]
                                                             : make_float4(0, 0, 0, 0);
         }
     }
@@ -438,7 +474,7 @@ __global__ __launch_bounds__(NTHREADS) void sweep_kernel(const SweepArgs a)
     int lo = o_blk - W;            // the host clamps W to L, so none of this overflows
     if (lo < 0) lo = 0;
     int hi = o_blk + BM - 1 + W;
-    if (hi > L - 1) hi = L - 1;
+    if (hi > Lt - 1) hi = Lt - 1;   // (lo <= hi: the block has a row below Le <= Lt + W)
     const int k_lo = lo / TT, k_hi = hi / TT;
 
     // staging registers
@@ -448,16 +484,16 @@ __global__ __launch_bounds__(NTHREADS) void sweep_kernel(const SweepArgs a)
 
     auto g_load = [&](int k) {
         const int t0 = k * TT;
-        tile_load<T, D>(ry, Yb, t0, L);
-        if constexpr (ST::HAS_B) tile_load<T, D>(rb, reinterpret_cast<const T *>(a.Bm) + moff, t0, L);
-        if constexpr (MODE == M_APPLY) tile_load<T, D>(rp, reinterpret_cast<const T *>(a.Pay) + moff, t0, L);
+        tile_load<T, D>(ry, Yb, t0, Lt);
+        if constexpr (ST::HAS_B) tile_load<T, D>(rb, reinterpret_cast<const T *>(a.Bm) + moff, t0, Lt);
+        if constexpr (MODE == M_APPLY) tile_load<T, D>(rp, reinterpret_cast<const T *>(a.Pay) + moff, t0, Lt);
         if (tid < TT) {
             const int t = t0 + tid;
-            rvy = (t < L) ? ytp[t] * LOG2E + m2 : -INFINITY;
+            rvy = (t < Lt) ? ytp[t] * LOG2E + m2 : -INFINITY;
             if constexpr (MODE == M_FINAL) {
 #pragma unroll
                 for (int g = 0; g < MAXNQ; ++g)
-                    rvq[g] = (t < L && g < a.nq) ? a.qt[(n * a.ldp + t) * a.pstride + g] : make_float4(0, 0, 0, 0);
+                    rvq[g] = (t < Lt && g < a.nq) ? a.qt[(n * a.ldp + t) * a.pstride + g] : make_float4(0, 0, 0, 0);
             }
         }
     };
@@ -490,7 +526,7 @@ __global__ __launch_bounds__(NTHREADS) void sweep_kernel(const SweepArgs a)
         for (int f = 0; f < FR; ++f) {
             const int of = o_frag[f];
             // does this tile meet the band of this fragment at all?
-            if (of >= L || (long)t0 + TT - 1 < (long)of - W || (long)t0 > (long)of + 31 + W) continue;
+            if (of >= Le || (long)t0 + TT - 1 < (long)of - W || (long)t0 > (long)of + 31 + W) continue;
             const bool interior = ((long)of + 31 - t0 <= W) && ((long)t0 + TT - 1 - of <= W);
 
             f32x16 acc;
@@ -576,13 +612,16 @@ __global__ __launch_bounds__(NTHREADS) void sweep_kernel(const SweepArgs a)
                 mn = m3;
             }
             if (h == 0 && o < L) {
-                float r = -LN2 * (mn + fast_log2(tot));
-                if (a.olog.p) r += a.olog.p[n * a.olog.stride + o];
+                float r = 0.f;   // rows beyond the valid length
+                if (o < Le) {
+                    r = -LN2 * (mn + fast_log2(tot));
+                    if (a.olog.p) r += a.olog.p[n * a.olog.stride + o];
+                }
                 a.out_vec.p[n * a.out_vec.stride + o] = r;
             }
         } else {
             float fac = 0.f;
-            if (o < L) fac = fast_exp2((xsp[o] - mblk) * LOG2E);
+            if (o < Le) fac = fast_exp2((xsp[o] - mblk) * LOG2E);
             if constexpr (MODE == M_FINAL) fac *= a.cs;
             T *orow = reinterpret_cast<T *>(a.out_mat) + moff + (long)o * D;
             const T *drow = a.dot_mat ? reinterpret_cast<const T *>(a.dot_mat) + moff + (long)o * D : nullptr;
@@ -594,6 +633,7 @@ __global__ __launch_bounds__(NTHREADS) void sweep_kernel(const SweepArgs a)
                     const int dv = 32 * j + 8 * q + 4 * h;
                     float v0 = outm[f][j][4 * q + 0] * fac, v1 = outm[f][j][4 * q + 1] * fac;
                     float v2 = outm[f][j][4 * q + 2] * fac, v3 = outm[f][j][4 * q + 3] * fac;
+                    if (o >= Le) v0 = v1 = v2 = v3 = 0.f;   // rows beyond the valid length are written as zeros
                     if (o < L) {
                         if constexpr (MODE == M_FINAL) {
                             if (a.accum) {
@@ -604,7 +644,7 @@ __global__ __launch_bounds__(NTHREADS) void sweep_kernel(const SweepArgs a)
                         }
                         store4<T>(orow + dv, v0, v1, v2, v3);
                         if constexpr (MODE == M_APPLY) {
-                            if (drow) {
+                            if (drow && o < Le) {
                                 float dd[4];
                                 load4<T>(drow + dv, dd);
                                 dot += dd[0] * v0 + dd[1] * v1 + dd[2] * v2 + dd[3] * v3;
@@ -616,7 +656,7 @@ __global__ __launch_bounds__(NTHREADS) void sweep_kernel(const SweepArgs a)
                 if (a.dot_mat) {
                     dot += __shfl_xor(dot, 32);
                     if (h == 0 && o < L) {
-                        if (a.olog.p) dot *= __expf(-a.olog.p[n * a.olog.stride + o]);
+                        if (a.olog.p && o < Le) dot *= __expf(-a.olog.p[n * a.olog.stride + o]);
                         a.dot_out.p[n * a.dot_out.stride + o] = dot;
                     }
                 }
@@ -669,6 +709,12 @@ __global__ __launch_bounds__(NTHREADS) void vsweep_kernel(const SweepArgs a)
     const int tid = threadIdx.x, lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int c = lane & 31, h = lane >> 5;
     const int L = a.L, W = a.W;
+    const Lens ln = problem_lens(a, n);
+    const int Lt = ln.Lt, Le = ln.Le;
+    if (o_blk >= Le) {
+        zero_block<T, D, BM>(a, n, o_blk, false, true);
+        return;
+    }
     const long moff = (long)n * L * D;
     const T *Xb = reinterpret_cast<const T *>(a.X) + moff;
     const T *Yb = reinterpret_cast<const T *>(a.Y) + moff;
@@ -679,7 +725,7 @@ __global__ __launch_bounds__(NTHREADS) void vsweep_kernel(const SweepArgs a)
 
     // stabiliser input first, so that waiting for it waits for nothing else
     static_assert(BM <= NTHREADS, "one owner-side potential per thread");
-    float mraw = xsp[min(o_blk + min(tid, BM - 1), L - 1)];   // clamped repeats are harmless
+    float mraw = xsp[min(o_blk + min(tid, BM - 1), Le - 1)];   // clamped repeats are harmless
     float mblk, m2 = 0.f;
     OwnerFrag<T, D> xf[FR];
     int o_frag[FR];
@@ -687,7 +733,7 @@ __global__ __launch_bounds__(NTHREADS) void vsweep_kernel(const SweepArgs a)
 #pragma unroll
     for (int f = 0; f < FR; ++f) {
         o_frag[f] = o_blk + (wave * FR + f) * 32;
-        xf[f].load(Xb, min(o_frag[f] + c, L - 1), L, h);   // clamped: rows beyond L are never written
+        xf[f].load(Xb, min(o_frag[f] + c, Le - 1), Le, h);   // clamped: rows beyond Le are written as zeros
         sum[f] = 0.f;
     }
 
@@ -695,7 +741,7 @@ __global__ __launch_bounds__(NTHREADS) void vsweep_kernel(const SweepArgs a)
     const int kbase = (o_blk - W) >= 0 ? (o_blk - W) / TT : -((W - o_blk + TT - 1) / TT);
     const int kend = (o_blk + 32 * FR - 1 + W) / TT;
     const int S = kend - kbase + 1;
-    const int klast = (L - 1) / TT;
+    const int klast = (Lt - 1) / TT;
 
     // One tile in flight between global memory and LDS.  A tile is a contiguous block of
     // memory, so a thread's 16-byte pieces sit at fixed byte offsets from the tile's start:
@@ -720,7 +766,7 @@ __global__ __launch_bounds__(NTHREADS) void vsweep_kernel(const SweepArgs a)
     };
     auto g_load = [&](Inflight &g, int k) {
         const int kc = min(max(k, 0), klast);
-        const int rows = min(TT, L - kc * TT);   // >= 1
+        const int rows = min(TT, Lt - kc * TT);   // >= 1
         g.rows = (k == kc) ? rows : 0;
         const unsigned char *tb = reinterpret_cast<const unsigned char *>(Yb) + (long)kc * TILE_BYTES;
         const unsigned lim = rows * ROW_BYTES - 16;
@@ -796,7 +842,7 @@ __global__ __launch_bounds__(NTHREADS) void vsweep_kernel(const SweepArgs a)
 #pragma unroll
             for (int f = 0; f < FR; ++f) {
                 const int of = o_frag[f];
-                use[f] = !(of >= L || t0 + TT - 1 < of - W || t0 > of + 31 + W);
+                use[f] = !(of >= Le || t0 + TT - 1 < of - W || t0 > of + 31 + W);
                 interior[f] = (of + 31 - t0 <= W) && (t0 + TT - 1 - of <= W);
 #pragma unroll
                 for (int r = 0; r < 16; ++r) acc[f][r] = PRE ? yv[r] : 0.f;
@@ -857,7 +903,9 @@ __global__ __launch_bounds__(NTHREADS) void vsweep_kernel(const SweepArgs a)
         }
         if (h == 0 && o < L) {
             float r;
-            if constexpr (MODE == M_LSE) {
+            if (o >= Le) {
+                r = 0.f;   // rows beyond the valid length
+            } else if constexpr (MODE == M_LSE) {
                 r = mblk - LN2 * fast_log2(tot);
                 if (a.olog.p) r += a.olog.p[n * a.olog.stride + o];
             } else {
@@ -924,6 +972,12 @@ __global__ __launch_bounds__(NTHREADS) void msweep_kernel(const SweepArgs a)
     const int tid = threadIdx.x, lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int c = lane & 31, h = lane >> 5;
     const int L = a.L, W = a.W;
+    const Lens ln = problem_lens(a, n);
+    const int Lt = ln.Lt, Le = ln.Le;
+    if (o_blk >= Le) {
+        zero_block<T, D, BM>(a, n, o_blk, true, false);
+        return;
+    }
     const long moff = (long)n * L * D;
     const T *Xb = reinterpret_cast<const T *>(a.X) + moff;
     const unsigned char *Yb = reinterpret_cast<const unsigned char *>(reinterpret_cast<const T *>(a.Y) + moff);
@@ -935,7 +989,7 @@ __global__ __launch_bounds__(NTHREADS) void msweep_kernel(const SweepArgs a)
     float mblk, m2;
     {
         float m = -INFINITY;
-        for (int i = tid; i < BM; i += NTHREADS) m = fmaxf(m, xsp[min(o_blk + i, L - 1)]);
+        for (int i = tid; i < BM; i += NTHREADS) m = fmaxf(m, xsp[min(o_blk + i, Le - 1)]);
 #pragma unroll
         for (int s = 32; s >= 1; s >>= 1) m = fmaxf(m, __shfl_xor(m, s));
         if (lane == 0) red[wave] = m;
@@ -945,14 +999,14 @@ __global__ __launch_bounds__(NTHREADS) void msweep_kernel(const SweepArgs a)
     m2 = mblk * LOG2E;
 
     // owner side: score rows, and for M_FINAL the owner factor of Z and the modifier pack.
-    // Rows beyond L are clamped: they compute garbage that is never stored.
+    // Rows beyond Le are clamped: they compute garbage that is never stored.
     const int o_w = o_blk + wave * FR * 32;
     OwnerFrag<T, D> xf[FR], af[MODE == M_FINAL ? FR : 1];
     bf16x8 pob[FR];   // M_FINAL: this lane's half of the owner row's 16 pack columns
     f32x16 outm[FR][D / 32];
 #pragma unroll
     for (int f = 0; f < FR; ++f) {
-        const int oc = min(o_w + 32 * f + c, L - 1);
+        const int oc = min(o_w + 32 * f + c, Le - 1);
 #pragma unroll
         for (int s = 0; s < KS; ++s) {
             uint4 z = *reinterpret_cast<const uint4 *>(Xb + (long)oc * D + (2 * s + h) * 8);
@@ -977,7 +1031,7 @@ __global__ __launch_bounds__(NTHREADS) void msweep_kernel(const SweepArgs a)
     const int kbase = (o_blk - W) >= 0 ? (o_blk - W) / TT : -((W - o_blk + TT - 1) / TT);
     const int kend = (o_blk + 32 * FR - 1 + W) / TT;
     const int S = kend - kbase + 1;
-    const int klast = (L - 1) / TT;
+    const int klast = (Lt - 1) / TT;
 
     // one tile pair in flight between global memory and LDS (plain arrays: a struct holding
     // them ends up in scratch memory)
@@ -986,22 +1040,22 @@ __global__ __launch_bounds__(NTHREADS) void msweep_kernel(const SweepArgs a)
         for (int q = 0; q < RG::CPT; ++q) {
             int idx = tid + q * NTHREADS;
             if (idx >= RG::CHUNKS) idx = RG::CHUNKS - 1;
-            const unsigned row = (unsigned)min(max(k * TT + idx / RG::CPR, 0), L - 1);
+            const unsigned row = (unsigned)min(max(k * TT + idx / RG::CPR, 0), Lt - 1);
             const unsigned off = row * (unsigned)(D * 2) + (unsigned)(idx % RG::CPR) * 16u;
             gy[q] = *reinterpret_cast<const uint4 *>(Yb + off);
             gb[q] = *reinterpret_cast<const uint4 *>(Bb + off);
         }
-        const unsigned tv = (unsigned)min(max(k * TT + (tid & (TT - 1)), 0), L - 1);
+        const unsigned tv = (unsigned)min(max(k * TT + (tid & (TT - 1)), 0), Lt - 1);
         gvy = ytp[tv];
         if constexpr (MODE == M_FINAL) {
             // 64 pieces of 16 bytes per tile: every wavefront requests them (same addresses; a
             // request under a condition would cost a full wait), the first one stores them
-            const unsigned tp = (unsigned)min(max(k * TT + ((tid & 63) >> 1), 0), L - 1);
+            const unsigned tp = (unsigned)min(max(k * TT + ((tid & 63) >> 1), 0), Lt - 1);
             gpk = *reinterpret_cast<const uint4 *>(reinterpret_cast<const unsigned char *>(a.qtA) +
                                                    ((long)n * a.ldp + tp) * 32 + (tid & 1) * 16);
         }
     };
-    // rows outside [0, L) keep whatever the clamped fetch brought: their potential is -inf,
+    // rows outside [0, Lt) keep whatever the clamped fetch brought: their potential is -inf,
     // so their plan entries are exactly zero and finite data times zero adds nothing
     auto s_store = [&](const uint4 (&gy)[RG::CPT], const uint4 (&gb)[RG::CPT], float gvy, uint4 gpk, int j, int k) {
         unsigned char *sl = smem + (j % RG::NSLOT) * RG::SLOT;
@@ -1015,7 +1069,7 @@ __global__ __launch_bounds__(NTHREADS) void msweep_kernel(const SweepArgs a)
             }
         }
         if (tid < TT) {
-            const bool live = k >= 0 && k * TT + tid < L;
+            const bool live = k >= 0 && k * TT + tid < Lt;
             reinterpret_cast<float *>(sl + RG::OFF_VY)[tid] = live ? fmaf(gvy, LOG2E, m2) : -INFINITY;
         }
         if constexpr (MODE == M_FINAL) {
@@ -1143,7 +1197,7 @@ __global__ __launch_bounds__(NTHREADS) void msweep_kernel(const SweepArgs a)
     for (int f = 0; f < FR; ++f) {
         const int o = o_w + 32 * f + c;
         const int oc = min(o, L - 1);
-        float fac = fast_exp2((xsp[oc] - mblk) * LOG2E);
+        float fac = fast_exp2((xsp[min(o, Le - 1)] - mblk) * LOG2E);
         if constexpr (MODE == M_FINAL) fac *= a.cs;
         T *orow = reinterpret_cast<T *>(a.out_mat) + moff + (long)oc * D;
         const T *drow = a.dot_mat ? reinterpret_cast<const T *>(a.dot_mat) + moff + (long)oc * D : nullptr;
@@ -1155,10 +1209,11 @@ __global__ __launch_bounds__(NTHREADS) void msweep_kernel(const SweepArgs a)
                 const int dv = 32 * j + 8 * q + 4 * h;
                 float v0 = outm[f][j][4 * q + 0] * fac, v1 = outm[f][j][4 * q + 1] * fac;
                 float v2 = outm[f][j][4 * q + 2] * fac, v3 = outm[f][j][4 * q + 3] * fac;
+                if (o >= Le) v0 = v1 = v2 = v3 = 0.f;   // rows beyond the valid length are written as zeros
                 if (o < L) {
                     store4<T>(orow + dv, v0, v1, v2, v3);
                     if constexpr (MODE == M_APPLY) {
-                        if (drow) {
+                        if (drow && o < Le) {
                             float dd[4];
                             load4<T>(drow + dv, dd);
                             dot += dd[0] * v0 + dd[1] * v1 + dd[2] * v2 + dd[3] * v3;
@@ -1170,7 +1225,7 @@ __global__ __launch_bounds__(NTHREADS) void msweep_kernel(const SweepArgs a)
             if (a.dot_mat) {
                 dot += __shfl_xor(dot, 32);
                 if (h == 0 && o < L) {
-                    if (a.olog.p) dot *= __expf(-a.olog.p[n * a.olog.stride + o]);
+                    if (a.olog.p && o < Le) dot *= __expf(-a.olog.p[n * a.olog.stride + o]);
                     a.dot_out.p[n * a.dot_out.stride + o] = dot;
                 }
             }
@@ -1185,10 +1240,11 @@ __global__ void fill_kernel(float *p, long per, long stride, int nprob, float va
     if (i < per * nprob) p[(i / per) * stride + (i % per)] = val;
 }
 
-// g_o = <A_o, B_o> for o < L; g[L..Lp) = 0.  A row is read by D * sizeof(T) / 16 neighbouring
+// g_o = <A_o, B_o> for o below the problem's valid length (len[n / nh], or L if len is null);
+// g = 0 from there to Lp.  A row is read by D * sizeof(T) / 16 neighbouring
 // lanes, 16 bytes each (whole 128-byte lines per group of lanes), and reduced across them.
 template <typename T, int D>
-__global__ void rowdot_kernel(const T *A, const T *Bm, float *g, long gstride, int L, int Lp)
+__global__ void rowdot_kernel(const T *A, const T *Bm, float *g, long gstride, int L, int Lp, const int *len, int nh)
 {
     constexpr int LPR = D * (int)sizeof(T) / 16;   // lanes per row: 4 ... 32, a power of two
     constexpr int EPL = 16 / (int)sizeof(T);       // elements per lane
@@ -1196,7 +1252,8 @@ __global__ void rowdot_kernel(const T *A, const T *Bm, float *g, long gstride, i
     const long p = (long)blockIdx.x * blockDim.x + threadIdx.x;
     const int o = (int)(p / LPR), sub = (int)(p % LPR);
     float acc = 0.f;
-    if (o < L) {
+    const int Lv = len ? min(max(len[n / nh], 0), L) : L;
+    if (o < Lv) {
         const T *pa = A + ((long)n * L + o) * D + sub * EPL, *pb = Bm + ((long)n * L + o) * D + sub * EPL;
 #pragma unroll
         for (int k = 0; k < EPL; k += 4) {
@@ -1331,6 +1388,7 @@ struct Problem {
     int B, H, L, d, W, T, R, dustbin, dtype;
     float eps, sdb;
     const float *log_a = nullptr, *log_b = nullptr;   // [N][Lp] logs of the marginal targets, or null
+    const int *len_q = nullptr, *len_k = nullptr;     // [B] valid lengths of the two sequences, or null
     int N() const { return B * H; }
     int Lp() const { return L + (dustbin ? 1 : 0); }
     long ldw() const { return ((long)Lp() + 3) / 4 * 4; }  // stride of workspace vectors
@@ -1377,6 +1435,7 @@ int check_common(const Problem &p)
     if ((long)p.B * p.H > 65535) return SKA_EINVAL;
     if (p.L > (1 << 24)) return SKA_EUNSUPPORTED;   // 32-bit byte offsets inside one [L][d] matrix
     if ((p.log_a || p.log_b) && p.dustbin) return SKA_EUNSUPPORTED;   // the dustbin's targets are all one
+    if ((p.len_q || p.len_k) && p.dustbin) return SKA_EUNSUPPORTED;   // the dustbin sits at index L
     if (p.R < 1 || p.R > MAXR) return SKA_EUNSUPPORTED;
     if (p.d != 32 && p.d != 64 && p.d != 128) return SKA_EUNSUPPORTED;
     if (p.dtype != SKA_F32 && p.dtype != SKA_BF16) return SKA_EUNSUPPORTED;
@@ -1519,6 +1578,7 @@ int fwd_impl(const Problem &p, const void *Qin, const void *K, const void *V, vo
     base.cs = 1.f / (p.eps * sqrtf((float)p.d));
     base.c2 = c2;
     base.dustbin = p.dustbin; base.sdb2 = p.sdb * LOG2E;
+    base.nh = p.H;
 
     // u0 = v0 = 0: the base solve starts from v = 0
     {
@@ -1537,6 +1597,7 @@ int fwd_impl(const Problem &p, const void *Qin, const void *K, const void *V, vo
         a.X = row ? Q : K; a.Y = row ? K : Q;
         a.yt = vec(yslot); a.xs = vec(prevslot); a.out_vec = vout(outslot);
         a.olog = Vec{row ? p.log_a : p.log_b, (long)Lp};
+        a.len_own = row ? p.len_q : p.len_k; a.len_oth = row ? p.len_k : p.len_q;
         // successive sweeps walk the blocks in opposite directions: a sweep then starts on
         // the rows its predecessor touched last, which are still in L2
         a.rev = nlaunch++ & 1;
@@ -1573,6 +1634,7 @@ int fwd_impl(const Problem &p, const void *Qin, const void *K, const void *V, vo
     PhaseTimer pt_out(SKA_PH_OUTPUT, st);
     SweepArgs a = base;
     a.X = Q; a.Y = K; a.Pay = V; a.out_mat = O; a.xs = vec(2 * R); a.yt = vec(2 * R + 1);
+    a.len_own = p.len_q; a.len_oth = p.len_k;
     a.rev = nlaunch & 1;
     pt_out.launched();
     return sweep<T, D>(M_APPLY, a, N, st);
@@ -1614,6 +1676,7 @@ int bwd_impl(const Problem &p, const void *Qin, const void *K, const void *V, co
     base.cs = 1.f / (p.eps * sqrtf((float)p.d));
     base.c2 = c2;
     base.dustbin = p.dustbin; base.sdb2 = p.sdb * LOG2E;
+    base.nh = p.H;
     const dim3 vgrid((Lp + 255) / 256, N);
     int nlaunch = 0;   // successive sweeps walk the blocks in opposite directions (L2 reuse)
 
@@ -1623,7 +1686,7 @@ int bwd_impl(const Problem &p, const void *Qin, const void *K, const void *V, co
     constexpr int LPR = D * (int)sizeof(T) / 16;
     hipLaunchKernelGGL((rowdot_kernel<T, D>), dim3(((long)Lp * LPR + 255) / 256, N), dim3(256), 0, st,
                        reinterpret_cast<const T *>(G),
-                       reinterpret_cast<const T *>(O), gu, ldw, L, Lp);
+                       reinterpret_cast<const T *>(O), gu, ldw, L, Lp, p.len_q, p.H);
     if (hipGetLastError() != hipSuccess) return SKA_EHIP;
     if (p.dustbin) {   // vbar_R at the dustbin column is 0 because V there is 0
         hipLaunchKernelGGL(fill_kernel, dim3((N + 255) / 256), dim3(256), 0, st, vbar(R) + L, 1L, ldw, N, 0.f);
@@ -1637,6 +1700,7 @@ int bwd_impl(const Problem &p, const void *Qin, const void *K, const void *V, co
         SweepArgs a = base;
         a.X = K; a.Y = Q; a.Pay = G; a.out_mat = dV; a.xs = uv(2 * R + 1); a.yt = uv(2 * R);
         a.dot_mat = V; a.dot_out = wo(vbar(R));
+        a.len_own = p.len_k; a.len_oth = p.len_q;
         a.olog = Vec{p.log_b, (long)Lp};   // the workspace holds vbar / b and ubar / a (general marginals)
         a.rev = nlaunch++ & 1;
         SKA_TRY((sweep<T, D>(M_APPLY, a, N, st)));
@@ -1648,6 +1712,7 @@ int bwd_impl(const Problem &p, const void *Qin, const void *K, const void *V, co
         a.X = row ? Q : K; a.Y = row ? K : Q;
         a.xs = xs; a.yt = yt; a.w = wv(w); a.pre = Vec{pre, ldw}; a.out_vec = out;
         if (scaled) a.olog = Vec{row ? p.log_a : p.log_b, (long)Lp};
+        a.len_own = row ? p.len_q : p.len_k; a.len_oth = row ? p.len_k : p.len_q;
         a.rev = nlaunch++ & 1;
         SKA_TRY((sweep<T, D>(M_MATVEC, a, N, st)));
         if (p.dustbin) {
@@ -1683,6 +1748,7 @@ int bwd_impl(const Problem &p, const void *Qin, const void *K, const void *V, co
             SweepArgs a = base;
             a.X = Q; a.Y = K; a.A = G; a.Bm = V; a.out_mat = dQ; a.xs = uv(2 * R); a.yt = uv(2 * R + 1);
             a.po = rowp + g0; a.qt = colp + g0; a.ldp = ldw; a.nq = ng; a.pstride = nq;
+            a.len_own = p.len_q; a.len_oth = p.len_k;
             a.skipz = a.accum = g0 > 0;
             if (AUG) { a.poB = aug + 1 * nldp * 16; a.qtA = aug + 2 * nldp * 16; }   // rows own, columns stream
             a.rev = nlaunch++ & 1;
@@ -1692,6 +1758,7 @@ int bwd_impl(const Problem &p, const void *Qin, const void *K, const void *V, co
             SweepArgs a = base;
             a.X = K; a.Y = Q; a.A = V; a.Bm = G; a.out_mat = dK; a.xs = uv(2 * R + 1); a.yt = uv(2 * R);
             a.po = colp + g0; a.qt = rowp + g0; a.ldp = ldw; a.nq = ng; a.pstride = nq;
+            a.len_own = p.len_k; a.len_oth = p.len_q;
             a.skipz = a.accum = g0 > 0;
             if (AUG) { a.poB = aug + 3 * nldp * 16; a.qtA = aug + 0 * nldp * 16; }   // columns own, rows stream
             // payload rows are Qs = (cs log2 e) Q when prescaled: cs sum Sbar^T Q = ln 2 sum Sbar^T Qs
@@ -1715,12 +1782,13 @@ size_t sinkhorn_attn_workspace_bytes(int B, int H, int L, int d, int W, int T, i
     return ws_bytes(p);
 }
 
-int sinkhorn_attn_fwd_marginals(const void *Q, const void *K, const void *V, const float *log_a,
-                                const float *log_b, void *O, float *UV, int B, int H, int L, int d, int W,
-                                int T, int R, float eps, int dustbin, float dustbin_score, int dtype,
-                                void *workspace, size_t workspace_bytes, void *stream)
+int sinkhorn_attn_fwd_varlen(const void *Q, const void *K, const void *V, const float *log_a,
+                             const float *log_b, const int *len_q, const int *len_k, void *O, float *UV, int B,
+                             int H, int L, int d, int W, int T, int R, float eps, int dustbin,
+                             float dustbin_score, int dtype, void *workspace, size_t workspace_bytes,
+                             void *stream)
 {
-    Problem p{B, H, L, d, W, T, R, dustbin ? 1 : 0, dtype, eps, dustbin_score, log_a, log_b};
+    Problem p{B, H, L, d, W, T, R, dustbin ? 1 : 0, dtype, eps, dustbin_score, log_a, log_b, len_q, len_k};
     if (!Q || !K || !V || !O || !UV) return SKA_EINVAL;
     int rc = check_common(p);
     if (rc != SKA_OK) return rc;
@@ -1740,6 +1808,15 @@ int sinkhorn_attn_fwd_marginals(const void *Q, const void *K, const void *V, con
 #undef SKA_FWD
 }
 
+int sinkhorn_attn_fwd_marginals(const void *Q, const void *K, const void *V, const float *log_a,
+                                const float *log_b, void *O, float *UV, int B, int H, int L, int d, int W,
+                                int T, int R, float eps, int dustbin, float dustbin_score, int dtype,
+                                void *workspace, size_t workspace_bytes, void *stream)
+{
+    return sinkhorn_attn_fwd_varlen(Q, K, V, log_a, log_b, nullptr, nullptr, O, UV, B, H, L, d, W, T, R, eps,
+                                    dustbin, dustbin_score, dtype, workspace, workspace_bytes, stream);
+}
+
 int sinkhorn_attn_fwd(const void *Q, const void *K, const void *V, void *O, float *UV, int B, int H, int L,
                       int d, int W, int T, int R, float eps, int dustbin, float dustbin_score, int dtype,
                       void *workspace, size_t workspace_bytes, void *stream)
@@ -1748,13 +1825,14 @@ int sinkhorn_attn_fwd(const void *Q, const void *K, const void *V, void *O, floa
                                        dustbin_score, dtype, workspace, workspace_bytes, stream);
 }
 
-int sinkhorn_attn_bwd_marginals(const void *Q, const void *K, const void *V, const float *log_a,
-                                const float *log_b, const void *O, const void *dO, const float *UV, void *dQ,
-                                void *dK, void *dV, float *eta0, int B, int H, int L, int d, int W, int T,
-                                int R, float eps, int dustbin, float dustbin_score, int dtype,
-                                void *workspace, size_t workspace_bytes, void *stream)
+int sinkhorn_attn_bwd_varlen(const void *Q, const void *K, const void *V, const float *log_a,
+                             const float *log_b, const int *len_q, const int *len_k, const void *O,
+                             const void *dO, const float *UV, void *dQ, void *dK, void *dV, float *eta0, int B,
+                             int H, int L, int d, int W, int T, int R, float eps, int dustbin,
+                             float dustbin_score, int dtype, void *workspace, size_t workspace_bytes,
+                             void *stream)
 {
-    Problem p{B, H, L, d, W, T, R, dustbin ? 1 : 0, dtype, eps, dustbin_score, log_a, log_b};
+    Problem p{B, H, L, d, W, T, R, dustbin ? 1 : 0, dtype, eps, dustbin_score, log_a, log_b, len_q, len_k};
     if (!Q || !K || !V || !O || !dO || !UV || !dQ || !dK || !dV) return SKA_EINVAL;
     int rc = check_common(p);
     if (rc != SKA_OK) return rc;
@@ -1772,6 +1850,17 @@ int sinkhorn_attn_bwd_marginals(const void *Q, const void *K, const void *V, con
         SKA_BWD(__bf16, 128);
     }
 #undef SKA_BWD
+}
+
+int sinkhorn_attn_bwd_marginals(const void *Q, const void *K, const void *V, const float *log_a,
+                                const float *log_b, const void *O, const void *dO, const float *UV, void *dQ,
+                                void *dK, void *dV, float *eta0, int B, int H, int L, int d, int W, int T,
+                                int R, float eps, int dustbin, float dustbin_score, int dtype,
+                                void *workspace, size_t workspace_bytes, void *stream)
+{
+    return sinkhorn_attn_bwd_varlen(Q, K, V, log_a, log_b, nullptr, nullptr, O, dO, UV, dQ, dK, dV, eta0, B, H,
+                                    L, d, W, T, R, eps, dustbin, dustbin_score, dtype, workspace,
+                                    workspace_bytes, stream);
 }
 
 int sinkhorn_attn_bwd(const void *Q, const void *K, const void *V, const void *O, const void *dO,
@@ -1825,7 +1914,7 @@ const char *sinkhorn_attn_strerror(int status)
     switch (status) {
     case SKA_OK: return "ok";
     case SKA_EINVAL: return "invalid argument (null pointer, non-positive size, bad eps, misaligned workspace)";
-    case SKA_EUNSUPPORTED: return "unsupported configuration (need R == 2, d in {32, 64, 128}, dtype f32 or bf16)";
+    case SKA_EUNSUPPORTED: return "unsupported configuration (need R in 1..32, L <= 2^24, d in {32, 64, 128}, dtype f32 or bf16; no dustbin with marginal targets or lengths)";
     case SKA_EWORKSPACE: return "workspace missing or smaller than sinkhorn_attn_workspace_bytes()";
     case SKA_EHIP: return "a HIP launch failed";
     default: return "unknown status";

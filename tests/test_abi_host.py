@@ -21,8 +21,9 @@ def declared_symbols():
 def test_library_exports_every_declared_symbol():
     lib = binding.load()
     names = declared_symbols()
-    assert names == ["sinkhorn_attn_bwd", "sinkhorn_attn_bwd_marginals", "sinkhorn_attn_fwd",
-                     "sinkhorn_attn_fwd_marginals", "sinkhorn_attn_profile_enable",
+    assert names == ["sinkhorn_attn_bwd", "sinkhorn_attn_bwd_marginals", "sinkhorn_attn_bwd_varlen",
+                     "sinkhorn_attn_fwd", "sinkhorn_attn_fwd_marginals", "sinkhorn_attn_fwd_varlen",
+                     "sinkhorn_attn_profile_enable",
                      "sinkhorn_attn_profile_read", "sinkhorn_attn_profile_read_phases",
                      "sinkhorn_attn_strerror",
                      "sinkhorn_attn_workspace_bytes"]
@@ -75,6 +76,11 @@ def test_argument_errors_are_reported_before_any_launch():
     for bad in (dict(R=0), dict(R=33), dict(d=48), dict(d=256), dict(dtype=7)):
         assert _fwd(lib, **bad) == binding.SKA_EUNSUPPORTED, bad
         assert _bwd(lib, **bad) == binding.SKA_EUNSUPPORTED, bad
+    # lengths and marginal targets do not combine with the dustbin
+    pp, nul = ctypes.c_void_p(1 << 20), None
+    for la, lq in ((pp, nul), (nul, pp)):
+        assert lib.sinkhorn_attn_fwd_varlen(pp, pp, pp, la, nul, lq, nul, pp, pp, 1, 1, 64, 32, 4, 2, 2, 1.0, 1,
+                                            0.0, 0, None, 0, None) == binding.SKA_EUNSUPPORTED
     assert _bwd(lib, ws=None, ws_bytes=0) == binding.SKA_EWORKSPACE
     assert _fwd(lib, dtype=1) == binding.SKA_EWORKSPACE          # bf16 forward needs its scratch
     need = binding.sinkhorn_attn_workspace_bytes(1, 1, 64, 32, 4, 2, dtype=0)

@@ -210,6 +210,84 @@ def test_general_marginals(dtype, d, R):
     assert e.value.status == -2
 
 
+@pytest.mark.parametrize("dtype,d,R,marg", [("f32", 32, 2, False), ("bf16", 64, 2, False), ("bf16", 128, 2, False),
+                                            ("bf16", 64, 3, False), ("f32", 64, 1, True)])
+def test_padded_batch_of_different_lengths(dtype, d, R, marg):
+    """Per-item query and key lengths (rectangular supports, the remark after Eq. 1-2): every
+    (item, head) against the oracle's rectangular operator on the unpadded slices.  The padding
+    of every input holds NaN, so any use of it shows; results in the padding are exact zeros.
+    Item 1 has query rows whose band holds no key (len_q > len_k + W), item 3 is shorter than
+    one tile, item 4 is full length."""
+    import torch
+
+    import paper_2605_08123_amd as ska
+    lq = np.array([700, 610, 333, 20, 700, 97], dtype=np.int32)
+    lk = np.array([655, 140, 400, 9, 700, 260], dtype=np.int32)
+    w = small("varlen", 700, d, 33, 5, dtype, eps=0.8, B=len(lq), H=2, R=R)
+    print(f"\n[case] {w} lengths q={lq.tolist()} k={lk.tolist()} marginals={marg}", flush=True)
+    q, k, v, g = make_inputs(w, 41)
+    la = lb = None
+    if marg:
+        la, lb = _targets(w, 42)
+    for b in range(w.B):
+        q[b, :, lq[b]:] = np.nan
+        g[b, :, lq[b]:] = np.nan
+        k[b, :, lk[b]:] = np.nan
+        v[b, :, lk[b]:] = np.nan
+        if marg:
+            la[b, :, lq[b]:] = np.nan
+            lb[b, :, lk[b]:] = np.nan
+    dev = torch.device("cuda:0")
+    td = torch.float32 if dtype == "f32" else torch.bfloat16
+    Q, K, V, G = (torch.from_numpy(x).to(dev).to(td) for x in (q, k, v, g))
+    tla = torch.from_numpy(la).to(dev) if marg else None
+    tlb = torch.from_numpy(lb).to(dev) if marg else None
+    tq, tk = torch.from_numpy(lq).to(dev), torch.from_numpy(lk).to(dev)
+    O, UV = ska.sinkhorn_attn_fwd_varlen(Q, K, V, tla, tlb, tq, tk, w.W, w.T, w.R, w.eps)
+    dQ, dK, dV, eta0 = ska.sinkhorn_attn_bwd_varlen(Q, K, V, tla, tlb, tq, tk, O, G, UV, w.W, w.T, w.R, w.eps,
+                                                    want_eta0=True)
+    torch.cuda.synchronize()
+    got = {n: x.float().cpu().numpy().astype(np.float64)
+           for n, x in dict(O=O, dQ=dQ, dK=dK, dV=dV, UV=UV, eta0=eta0).items()}
+    for n in got:
+        assert np.isfinite(got[n]).all(), n
+    # the GPU rounds its inputs to the storage type; the oracle gets the same rounded values
+    qr, kr, vr, gr = (x.float().cpu().numpy().astype(np.float64) for x in (Q, K, V, G))
+    worst = dict(O=0.0, dQ=0.0, dK=0.0, dV=0.0)
+    for b in range(w.B):
+        for h in range(w.H):
+            a, c = int(lq[b]), int(lk[b])
+            ref = oracle.band_rect(qr[b, h, :a], kr[b, h, :c], vr[b, h, :c], gr[b, h, :a], w.W, w.T, w.R, w.eps,
+                                   log_a=la[b, h, :a].astype(np.float64) if marg else None,
+                                   log_b=lb[b, h, :c].astype(np.float64) if marg else None)
+            for n, cut in (("O", a), ("dQ", a), ("dK", c), ("dV", c)):
+                worst[n] = max(worst[n], rel(got[n][b, h, :cut], ref[n]))
+                assert np.all(got[n][b, h, cut:] == 0.0), (n, b, h)
+            for t in range(R + 1):
+                assert np.all(got["UV"][b, h, 2 * t, a:] == 0.0) and np.all(got["UV"][b, h, 2 * t + 1, c:] == 0.0)
+            # potentials of the rows that have edges, through the terminal plan's row sums being
+            # unit (or a): u_R + logsumexp_j(S + v_R) = log a -- covered by the O comparison; here
+            # the raw terminal potentials themselves
+            tol_uv = 2e-4 if dtype == "f32" else 3e-2
+            assert np.abs(got["UV"][b, h, 2 * R, :a] - ref["U"][R]).max() < tol_uv
+            assert np.abs(got["UV"][b, h, 2 * R + 1, :c] - ref["Vp"][R]).max() < tol_uv
+            assert np.all(got["eta0"][b, h, c:] == 0.0)
+    print("   worst rel-L2 over items:", {n: f"{e:.2e}" for n, e in worst.items()}, flush=True)
+    for n, e in worst.items():
+        assert e <= TOL[dtype], (n, e)
+    # lengths equal to L reproduce the plain call bit for bit (finite inputs for this one)
+    Qf, Kf, Vf, Gf = (torch.nan_to_num(x) for x in (Q, K, V, G))
+    full = torch.full((w.B,), w.L, dtype=torch.int32, device=dev)
+    O1, UV1 = ska.sinkhorn_attn_fwd_varlen(Qf, Kf, Vf, None, None, full, full, w.W, w.T, w.R, w.eps)
+    O0, UV0 = ska.sinkhorn_attn_fwd(Qf, Kf, Vf, w.W, w.T, w.R, w.eps)
+    g1 = ska.sinkhorn_attn_bwd_varlen(Qf, Kf, Vf, None, None, full, full, O1, Gf, UV1, w.W, w.T, w.R, w.eps)
+    g0 = ska.sinkhorn_attn_bwd(Qf, Kf, Vf, O0, Gf, UV0, w.W, w.T, w.R, w.eps)
+    assert torch.equal(O1, O0) and torch.equal(UV1, UV0) and all(torch.equal(x, y) for x, y in zip(g1, g0))
+    with pytest.raises(ska.SinkhornAttnError) as e:      # the dustbin sits at index L
+        ska.sinkhorn_attn_fwd_varlen(Qf, Kf, Vf, None, None, tq, tk, w.W, w.T, w.R, w.eps, dustbin=True)
+    assert e.value.status == -2
+
+
 def test_tail_depth_dustbin():
     check(small("taildb", 300, 64, 24, 4, "bf16", eps=0.9, R=3, dustbin=True, dustbin_score=-0.2), seed=17)
     check(small("taildb", 300, 32, 24, 4, "f32", eps=0.9, R=1, dustbin=True, dustbin_score=0.4), seed=18)
