@@ -91,3 +91,51 @@ def test_mid_config_full_size():
         for n in ("O", "dQ", "dK", "dV"):
             e = float(np.linalg.norm(got[n][b, h] - ref[n]) / np.linalg.norm(ref[n]))
             assert e <= TOL[w.dtype], (b, h, n, e)
+
+
+def test_full_size_padded_lengths():
+    """The benchmark shape as a padded item: 200003 valid queries, 187654 valid keys of 262144.
+    The oracle's rectangular operator runs on a window that ends at the true (ragged) end of
+    the valid region; queries between len_k + W and len_q have no key in their band and are
+    zeros like the padding, whose inputs are NaN here."""
+    import torch
+
+    import paper_2605_08123_amd as ska
+    w = CONFIGS["paper"]
+    lq, lk = 200003, 187654
+    print(f"\n[case] {w} len_q={lq} len_k={lk}", flush=True)
+    q, k, v, g = make_inputs(w)
+    q[:, :, lq:] = np.nan
+    g[:, :, lq:] = np.nan
+    k[:, :, lk:] = np.nan
+    v[:, :, lk:] = np.nan
+    dev = torch.device("cuda:0")
+    Q, K, V, G = (torch.from_numpy(x).to(dev).to(torch.bfloat16) for x in (q, k, v, g))
+    tq = torch.tensor([lq], dtype=torch.int32, device=dev)
+    tk = torch.tensor([lk], dtype=torch.int32, device=dev)
+    O, UV = ska.sinkhorn_attn_fwd_varlen(Q, K, V, None, None, tq, tk, w.W, w.T, w.R, w.eps)
+    dQ, dK, dV = ska.sinkhorn_attn_bwd_varlen(Q, K, V, None, None, tq, tk, O, G, UV, w.W, w.T, w.R, w.eps)
+    torch.cuda.synchronize()
+    got = {n: x.float().cpu().numpy().astype(np.float64) for n, x in dict(O=O, dQ=dQ, dK=dK, dV=dV).items()}
+    for n in got:
+        assert np.isfinite(got[n]).all(), n
+    le = lk + w.W                                   # first query row without any valid key
+    for h in range(w.H):
+        assert np.all(got["O"][0, h, le:] == 0.0) and np.all(got["dQ"][0, h, le:] == 0.0)
+        assert np.all(got["dK"][0, h, lk:] == 0.0) and np.all(got["dV"][0, h, lk:] == 0.0)
+        assert np.all(UV[0, h, 0::2, le:].cpu().numpy() == 0.0) and np.all(UV[0, h, 1::2, lk:].cpu().numpy() == 0.0)
+    margin = (2 * (w.T + w.R) + 7) * w.W
+    a0 = lk - 1500 - margin
+    qr, kr, vr, gr = (x.float().cpu().numpy().astype(np.float64) for x in (Q, K, V, G))
+    for h in (0, w.H - 1):
+        ref = oracle.band_rect(qr[0, h, a0:lq], kr[0, h, a0:lk], vr[0, h, a0:lk], gr[0, h, a0:lq],
+                               w.W, w.T, w.R, w.eps)
+        errs = {}
+        for n, end in (("O", le), ("dQ", le), ("dK", lk), ("dV", lk)):
+            r = ref[n][lk - 1500 - a0:end - a0]
+            errs[n] = float(np.linalg.norm(got[n][0, h, lk - 1500:end] - r) / np.linalg.norm(r))
+        print(f"   (0,{h}) rows [{lk - 1500}, end):", {n: f"{e:.2e}" for n, e in errs.items()}, flush=True)
+        for n, e in errs.items():
+            assert e <= TOL[w.dtype], (n, e)
+    # the left part is far from the ragged end: identical to an ordinary window of the full problem
+    window_check(w, {n: got[n] for n in got}, (qr, kr, vr, gr), 0, 0, 0, 2048)
