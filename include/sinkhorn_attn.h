@@ -145,6 +145,26 @@ int sinkhorn_attn_bwd_varlen(const void *Q, const void *K, const void *V, const 
                              size_t workspace_bytes, void *stream);
 
 /*
+ * Vector-Jacobian product through the base solve: dQ, dK = (D_x z_T)^T eta for the base state
+ * z_T = v^(T) reached by T full steps from v = 0 (the a-posteriori bias certificate,
+ * Prop. "A Posteriori Bias Certificate": with eta = eta_R, the base cotangent that the
+ * backward call returns as eta0, this is exactly the part of the full gradient that stopping
+ * the base leaves out; V does not enter the base solve, so there is no dV).  Evaluated with
+ * the same reverse recurrences and one-reference final sweeps as the backward call (Prop. 1,
+ * Prop. 2 for a chain of depth T with no output map behind it).
+ *   UV : [B,H,2(T+1),Lp] all iterates of the base solve, as sinkhorn_attn_fwd(T = 0, R = T)
+ *        returns them (same kernels, so v^(T) there equals the base state of the (T, R) call).
+ *   eta: [B,H,Lp] fp32, cotangent of v^(T) (raw, as eta0 is returned).
+ *   dQ, dK: [B,H,L,d] out.  1 <= T <= 32.  log_a, log_b, len_q, len_k: as above, may be NULL.
+ *   workspace: at least sinkhorn_attn_workspace_bytes(B, H, L, d, W, 0, T, dustbin, dtype).
+ */
+int sinkhorn_attn_base_vjp(const void *Q, const void *K, const float *log_a, const float *log_b,
+                           const int *len_q, const int *len_k, const float *UV, const float *eta,
+                           void *dQ, void *dK, int B, int H, int L, int d, int W, int T, float eps,
+                           int dustbin, float dustbin_score, int dtype, void *workspace,
+                           size_t workspace_bytes, void *stream);
+
+/*
  * Benchmark hooks (no part of the operator).  While enabled, every forward and backward
  * call records two HIP events on its stream around each of its phases, so that a phase can
  * be timed in place, inside a larger timed region, without a profiler.  At most 4096 phase

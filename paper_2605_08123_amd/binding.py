@@ -49,6 +49,9 @@ def load():
         lib.sinkhorn_attn_bwd_varlen.restype = i
         lib.sinkhorn_attn_bwd_varlen.argtypes = [vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, i, i, i,
                                                  i, i, i, i, f, i, f, i, vp, sz, vp]
+        lib.sinkhorn_attn_base_vjp.restype = i
+        lib.sinkhorn_attn_base_vjp.argtypes = [vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, i, i, i, i, i, i, f, i, f, i,
+                                               vp, sz, vp]
         lib.sinkhorn_attn_profile_enable.restype = i
         lib.sinkhorn_attn_profile_enable.argtypes = [i]
         lib.sinkhorn_attn_profile_read.restype = i
@@ -179,6 +182,33 @@ def sinkhorn_attn_fwd_varlen(Q, K, V, log_a, log_b, len_q, len_k, W, T, R=2, eps
     if rc != SKA_OK:
         raise SinkhornAttnError(rc)
     return O, UV
+
+
+def sinkhorn_attn_base_vjp(Q, K, UV, eta, W, T, eps=1.0, dustbin=False, dustbin_score=0.0, log_a=None,
+                           log_b=None, len_q=None, len_k=None, workspace=None, dQ=None, dK=None):
+    """(D_x z_T)^T eta through the T-step base solve: UV [B,H,2(T+1),Lp] from
+    sinkhorn_attn_fwd(T=0, R=T), eta [B,H,Lp] (the eta0 of a backward call).  Returns (dQ, dK)."""
+    B, H, L, d = Q.shape
+    _check(K, (B, H, L, d), Q.dtype, "K")
+    Lp = L + int(bool(dustbin))
+    _check(UV, (B, H, 2 * (T + 1), Lp), torch.float32, "UV")
+    _check(eta, (B, H, Lp), torch.float32, "eta")
+    dQ = torch.empty_like(Q) if dQ is None else dQ
+    dK = torch.empty_like(Q) if dK is None else dK
+    for n, x in (("dQ", dQ), ("dK", dK)):
+        _check(x, (B, H, L, d), Q.dtype, n)
+    code = _dtype_code(Q)
+    if workspace is None:
+        need = sinkhorn_attn_workspace_bytes(B, H, L, d, W, 0, T, dustbin, code)
+        workspace = torch.empty(max(need, 16), device=Q.device, dtype=torch.uint8)
+    rc = load().sinkhorn_attn_base_vjp(
+        Q.data_ptr(), K.data_ptr(), _marg_ptr(log_a, (B, H, L), "log_a"), _marg_ptr(log_b, (B, H, L), "log_b"),
+        _len_ptr(len_q, B, "len_q"), _len_ptr(len_k, B, "len_k"), UV.data_ptr(), eta.data_ptr(), dQ.data_ptr(),
+        dK.data_ptr(), B, H, L, d, W, T, float(eps), int(bool(dustbin)), float(dustbin_score), code,
+        workspace.data_ptr(), workspace.numel() * workspace.element_size(), _stream_ptr())
+    if rc != SKA_OK:
+        raise SinkhornAttnError(rc)
+    return dQ, dK
 
 
 def sinkhorn_attn_bwd(Q, K, V, O, dO, UV, W, T, R=2, eps=1.0, dustbin=False, dustbin_score=0.0,

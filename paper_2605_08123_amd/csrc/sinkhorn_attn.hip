@@ -1268,6 +1268,18 @@ __global__ void rowdot_kernel(const T *A, const T *Bm, float *g, long gstride, i
     if (sub == 0 && o < Lp) g[n * gstride + o] = acc;
 }
 
+// out[n][j] = seed[n][j] / b_j for j < Lp: a cotangent handed in from outside enters the reverse
+// recurrences in the form the workspace keeps (divided by the marginal target).
+__global__ void seed_kernel(const float *seed, const float *olog, float *out, long ostride, int Lp)
+{
+    const int n = blockIdx.y;
+    const int j = blockIdx.x * blockDim.x + threadIdx.x;
+    if (j >= Lp) return;
+    float r = seed[(long)n * Lp + j];
+    if (olog) r *= __expf(-olog[(long)n * Lp + j]);
+    out[n * ostride + j] = r;
+}
+
 // Qs = bf16(scale * Q): the score scale log2(e)/(eps sqrt d) folded into one operand once,
 // so that no sweep pays a multiply per edge for it.  8 elements per thread.
 __global__ void prescale_kernel(const __bf16 *src, __bf16 *dst, long n8, float scale)
@@ -1643,8 +1655,11 @@ int fwd_impl(const Problem &p, const void *Qin, const void *K, const void *V, vo
 template <typename T, int D>
 int bwd_impl(const Problem &p, const void *Qin, const void *K, const void *V, const void *O,
              const void *G, const float *UV, void *dQ, void *dK, void *dV, float *eta0, void *ws,
-             hipStream_t st)
+             hipStream_t st, const float *seed = nullptr)
 {
+    // seed != null: no output map at the end of the chain.  The reverse recurrences start from
+    // vbar_R = seed (a cotangent of v^(R) given by the caller), Z = 0, and only dQ, dK are
+    // produced: the vector-Jacobian product through R full steps started at v = 0.
     // Q below is the score operand (bf16 storage: prescaled copy at the end of the workspace,
     // c2 = 1); it also serves as the payload of the dK sweep, whose output scale absorbs it
     const void *Q = nullptr;
@@ -1666,7 +1681,7 @@ int bwd_impl(const Problem &p, const void *Qin, const void *K, const void *V, co
     float4 *rowp = reinterpret_cast<float4 *>(wf + (long)ws_vecs(R) * nldp);
     float4 *colp = rowp + nldp * nq;
     // the ring kernel (R <= 2) takes the packs as bf16 columns (rowA, rowB, colA, colB)
-    const bool AUG = (sizeof(T) == 2 && D <= 64 && R <= 2);
+    const bool AUG = (sizeof(T) == 2 && D <= 64 && R <= 2 && !seed);   // (that kernel always adds Z)
     __bf16 *aug = reinterpret_cast<__bf16 *>(colp + nldp * nq);
     auto wv = [&](float *q) { return Vec{q, ldw}; };
     auto wo = [&](float *q) { return VecOut{q, ldw}; };
@@ -1684,17 +1699,22 @@ int bwd_impl(const Problem &p, const void *Qin, const void *K, const void *V, co
     PhaseTimer pt_gu(SKA_PH_ROWDOT, st);
     pt_gu.launched();
     constexpr int LPR = D * (int)sizeof(T) / 16;
-    hipLaunchKernelGGL((rowdot_kernel<T, D>), dim3(((long)Lp * LPR + 255) / 256, N), dim3(256), 0, st,
-                       reinterpret_cast<const T *>(G),
-                       reinterpret_cast<const T *>(O), gu, ldw, L, Lp, p.len_q, p.H);
-    if (hipGetLastError() != hipSuccess) return SKA_EHIP;
-    if (p.dustbin) {   // vbar_R at the dustbin column is 0 because V there is 0
-        hipLaunchKernelGGL(fill_kernel, dim3((N + 255) / 256), dim3(256), 0, st, vbar(R) + L, 1L, ldw, N, 0.f);
+    if (seed) {
+        hipLaunchKernelGGL(seed_kernel, vgrid, dim3(256), 0, st, seed, p.log_b, vbar(R), ldw, Lp);
         if (hipGetLastError() != hipSuccess) return SKA_EHIP;
+    } else {
+        hipLaunchKernelGGL((rowdot_kernel<T, D>), dim3(((long)Lp * LPR + 255) / 256, N), dim3(256), 0, st,
+                           reinterpret_cast<const T *>(G),
+                           reinterpret_cast<const T *>(O), gu, ldw, L, Lp, p.len_q, p.H);
+        if (hipGetLastError() != hipSuccess) return SKA_EHIP;
+        if (p.dustbin) {   // vbar_R at the dustbin column is 0 because V there is 0
+            hipLaunchKernelGGL(fill_kernel, dim3((N + 255) / 256), dim3(256), 0, st, vbar(R) + L, 1L, ldw, N, 0.f);
+            if (hipGetLastError() != hipSuccess) return SKA_EHIP;
+        }
     }
     pt_gu.end();
     // dV_j = sum_i P_RR,ij dO_i ; vbar_R,j = <V_j, dV_j>  (column-oriented)
-    {
+    if (!seed) {
         PhaseTimer pt(SKA_PH_DV, st);
         pt.launched();
         SweepArgs a = base;
@@ -1725,7 +1745,7 @@ int bwd_impl(const Problem &p, const void *Qin, const void *K, const void *V, co
         PhaseTimer pt(SKA_PH_MATVEC, st);
         pt.launched(2 * R - 1 + (eta0 ? 1 : 0));
         // ubar_R = g_u - P_RR vbar_R
-        SKA_TRY(matvec(true, uv(2 * R), uv(2 * R + 1), vbar(R), gu, wo(ubar(R))));
+        SKA_TRY(matvec(true, uv(2 * R), uv(2 * R + 1), vbar(R), seed ? nullptr : gu, wo(ubar(R))));
         for (int t = R; t >= 1; --t) {
             // vbar_{t-1} = -(P_t,t-1)^T ubar_t   (t = 1: the base cotangent, only on request)
             if (t >= 2) SKA_TRY(matvec(false, uv(2 * t - 1), uv(2 * t), ubar(t), nullptr, wo(vbar(t - 1))));
@@ -1750,6 +1770,7 @@ int bwd_impl(const Problem &p, const void *Qin, const void *K, const void *V, co
             a.po = rowp + g0; a.qt = colp + g0; a.ldp = ldw; a.nq = ng; a.pstride = nq;
             a.len_own = p.len_q; a.len_oth = p.len_k;
             a.skipz = a.accum = g0 > 0;
+            if (seed) { a.A = Q; a.Bm = K; a.skipz = 1; }   // Z = 0; the factors are fetched but unused
             if (AUG) { a.poB = aug + 1 * nldp * 16; a.qtA = aug + 2 * nldp * 16; }   // rows own, columns stream
             a.rev = nlaunch++ & 1;
             SKA_TRY((sweep<T, D>(M_FINAL, a, N, st)));
@@ -1760,6 +1781,7 @@ int bwd_impl(const Problem &p, const void *Qin, const void *K, const void *V, co
             a.po = colp + g0; a.qt = rowp + g0; a.ldp = ldw; a.nq = ng; a.pstride = nq;
             a.len_own = p.len_k; a.len_oth = p.len_q;
             a.skipz = a.accum = g0 > 0;
+            if (seed) { a.A = K; a.Bm = Q; a.skipz = 1; }
             if (AUG) { a.poB = aug + 3 * nldp * 16; a.qtA = aug + 0 * nldp * 16; }   // columns own, rows stream
             // payload rows are Qs = (cs log2 e) Q when prescaled: cs sum Sbar^T Q = ln 2 sum Sbar^T Qs
             if (sizeof(T) == 2) a.cs = LN2;
@@ -1850,6 +1872,34 @@ int sinkhorn_attn_bwd_varlen(const void *Q, const void *K, const void *V, const 
         SKA_BWD(__bf16, 128);
     }
 #undef SKA_BWD
+}
+
+int sinkhorn_attn_base_vjp(const void *Q, const void *K, const float *log_a, const float *log_b,
+                           const int *len_q, const int *len_k, const float *UV, const float *eta, void *dQ,
+                           void *dK, int B, int H, int L, int d, int W, int T, float eps, int dustbin,
+                           float dustbin_score, int dtype, void *workspace, size_t workspace_bytes,
+                           void *stream)
+{
+    // T full steps from v = 0 are a tail of depth T without a stopped base in front of it
+    Problem p{B, H, L, d, W, 0, T, dustbin ? 1 : 0, dtype, eps, dustbin_score, log_a, log_b, len_q, len_k};
+    if (!Q || !K || !UV || !eta || !dQ || !dK) return SKA_EINVAL;
+    int rc = check_common(p);
+    if (rc != SKA_OK) return rc;
+    if (!workspace || workspace_bytes < ws_bytes(p)) return SKA_EWORKSPACE;
+    if (reinterpret_cast<uintptr_t>(workspace) & 15) return SKA_EINVAL;
+    hipStream_t st = reinterpret_cast<hipStream_t>(stream);
+#define SKA_VJP(TT_, DD_) \
+    return bwd_impl<TT_, DD_>(p, Q, K, nullptr, nullptr, nullptr, UV, dQ, dK, nullptr, nullptr, workspace, st, eta)
+    if (dtype == SKA_F32) {
+        if (d == 32) SKA_VJP(float, 32);
+        if (d == 64) SKA_VJP(float, 64);
+        SKA_VJP(float, 128);
+    } else {
+        if (d == 32) SKA_VJP(__bf16, 32);
+        if (d == 64) SKA_VJP(__bf16, 64);
+        SKA_VJP(__bf16, 128);
+    }
+#undef SKA_VJP
 }
 
 int sinkhorn_attn_bwd_marginals(const void *Q, const void *K, const void *V, const float *log_a,

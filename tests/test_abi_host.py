@@ -21,7 +21,7 @@ def declared_symbols():
 def test_library_exports_every_declared_symbol():
     lib = binding.load()
     names = declared_symbols()
-    assert names == ["sinkhorn_attn_bwd", "sinkhorn_attn_bwd_marginals", "sinkhorn_attn_bwd_varlen",
+    assert names == ["sinkhorn_attn_base_vjp", "sinkhorn_attn_bwd", "sinkhorn_attn_bwd_marginals", "sinkhorn_attn_bwd_varlen",
                      "sinkhorn_attn_fwd", "sinkhorn_attn_fwd_marginals", "sinkhorn_attn_fwd_varlen",
                      "sinkhorn_attn_profile_enable",
                      "sinkhorn_attn_profile_read", "sinkhorn_attn_profile_read_phases",
@@ -81,6 +81,9 @@ def test_argument_errors_are_reported_before_any_launch():
     for la, lq in ((pp, nul), (nul, pp)):
         assert lib.sinkhorn_attn_fwd_varlen(pp, pp, pp, la, nul, lq, nul, pp, pp, 1, 1, 64, 32, 4, 2, 2, 1.0, 1,
                                             0.0, 0, None, 0, None) == binding.SKA_EUNSUPPORTED
+    for T, want in ((0, binding.SKA_EUNSUPPORTED), (33, binding.SKA_EUNSUPPORTED), (4, binding.SKA_EWORKSPACE)):
+        assert lib.sinkhorn_attn_base_vjp(pp, pp, nul, nul, nul, nul, pp, pp, pp, pp, 1, 1, 64, 32, 4, T, 1.0, 0,
+                                          0.0, 0, None, 0, None) == want
     assert _bwd(lib, ws=None, ws_bytes=0) == binding.SKA_EWORKSPACE
     assert _fwd(lib, dtype=1) == binding.SKA_EWORKSPACE          # bf16 forward needs its scratch
     need = binding.sinkhorn_attn_workspace_bytes(1, 1, 64, 32, 4, 2, dtype=0)

@@ -154,6 +154,48 @@ def test_bias_certificate_by_difference():
     assert np.abs(g_full["dV"] - g_stop["dV"]).max() < 1e-4      # V does not enter the base solve
 
 
+@pytest.mark.parametrize("dtype,d,kind", [("f32", 32, "plain"), ("bf16", 64, "plain"), ("f32", 64, "marginals"),
+                                          ("f32", 32, "dustbin"), ("bf16", 128, "plain")])
+def test_base_vjp_is_the_stopped_bias(dtype, d, kind):
+    """One call gives the certificate's D_x z_T^T eta_R: eta_R is the backward's eta0, the base
+    iterates come from a (T = 0, R = T) forward.  Reference: the oracle's full backpropagation
+    (T = 0, R = T + R) minus its stopped-base backward, in fp64."""
+    import torch
+
+    import paper_2605_08123_amd as ska
+    T, R = 5, 2
+    db = kind == "dustbin"
+    w = small("cert", 400, d, 24, T, dtype, eps=0.8, B=1, H=2, R=R, dustbin=db, dustbin_score=-0.3)
+    print(f"\n[case] {w} base VJP ({kind})", flush=True)
+    arrays = make_inputs(w, 9)
+    la = lb = None
+    if kind == "marginals":
+        la, lb = _targets(w, 10)
+    dev = torch.device("cuda:0")
+    td = torch.float32 if dtype == "f32" else torch.bfloat16
+    Q, K, V, G = (torch.from_numpy(x).to(dev).to(td) for x in arrays)
+    tla = torch.from_numpy(la).to(dev) if la is not None else None
+    tlb = torch.from_numpy(lb).to(dev) if lb is not None else None
+    O, UV = ska.sinkhorn_attn_fwd_marginals(Q, K, V, tla, tlb, w.W, T, R, w.eps, db, w.dustbin_score)
+    _, _, _, eta = ska.sinkhorn_attn_bwd_marginals(Q, K, V, tla, tlb, O, G, UV, w.W, T, R, w.eps, db,
+                                                   w.dustbin_score, want_eta0=True)
+    _, UVb = ska.sinkhorn_attn_fwd_marginals(Q, K, V, tla, tlb, w.W, 0, T, w.eps, db, w.dustbin_score)
+    assert torch.equal(UVb[:, :, 2 * T + 1], UV[:, :, 1])          # the same base state, bit for bit
+    eQ, eK = ska.sinkhorn_attn_base_vjp(Q, K, UVb, eta, w.W, T, w.eps, db, w.dustbin_score, tla, tlb)
+    torch.cuda.synchronize()
+    kw = dict(log_a=None if la is None else la.astype(np.float64), log_b=None if lb is None else lb.astype(np.float64))
+    o_full = oracle.band_batched(*arrays, w.W, 0, T + R, w.eps, db, w.dustbin_score, **kw)
+    o_stop = oracle.band_batched(*arrays, w.W, T, R, w.eps, db, w.dustbin_score, **kw)
+    tol = TOL[dtype]
+    for name, got in (("dQ", eQ), ("dK", eK)):
+        ref = o_full[name] - o_stop[name]
+        e = rel(got.float().cpu().numpy().astype(np.float64), ref)
+        print(f"   bias {name}: |ref| {np.linalg.norm(ref):.3e} of |grad| {np.linalg.norm(o_stop[name]):.3e}, "
+              f"rel-L2 {e:.2e}", flush=True)
+        assert np.linalg.norm(ref) > 1e-5 * np.linalg.norm(o_stop[name])
+        assert e < tol, (name, e)
+
+
 def _targets(w, seed):
     rng = np.random.default_rng(seed)
     a = rng.uniform(0.4, 1.8, (w.B, w.H, w.L))
