@@ -165,6 +165,35 @@ int sinkhorn_attn_base_vjp(const void *Q, const void *K, const float *log_a, con
                            size_t workspace_bytes, void *stream);
 
 /*
+ * Certified tail-depth selection (Cor. "Certified Tail-Depth Selection"): for R = 1, 2, ...,
+ * R_max run the forward and the stopped-base backward of depth R, take eta_R from it, evaluate
+ * the certificate e_R = (D_x z_T)^T eta_R with sinkhorn_attn_base_vjp, and stop at the first R
+ * whose largest absolute entry over (dQ, dK) parts of e_R is <= tau.  Then the gradient left in
+ * dQ, dK, dV differs from full backpropagation through the same T-step base solve by at most
+ * tau in every entry (the dV part of the gap is zero: V does not enter the base solve).
+ *   Q, K, V, dO in; O, dQ, dK, dV out: results of the selected depth (of R_max if none passes).
+ *   UV out: room for [B,H,2(R_max+1),Lp] floats; on return it holds the selected depth's
+ *        [B,H,2(R+1),Lp] array, densely packed at the start.
+ *   R_selected (host int): the depth chosen, 0 if no depth up to R_max passes.
+ *   e_absmax (host, R_max floats): max |e_R| for every depth tried, -1 for depths not tried;
+ *   eta_absmax (host, R_max floats, may be NULL): max |eta_R| likewise.
+ *   1 <= T <= 32 (the 2(T+1) base iterates are kept), 1 <= R_max <= 32, tau >= 0.
+ *   workspace: sinkhorn_attn_select_workspace_bytes(...) bytes, 256-byte aligned.
+ * The call synchronises the stream once per depth tried (the decision is taken on the host);
+ * it cannot be captured in a graph.  Depth 0 (no differentiable tail) is not a candidate:
+ * the operator needs R >= 1.
+ */
+size_t sinkhorn_attn_select_workspace_bytes(int B, int H, int L, int d, int W, int T, int R_max,
+                                            int dustbin, int dtype);
+int sinkhorn_attn_select_tail_depth(const void *Q, const void *K, const void *V, const void *dO,
+                                    const float *log_a, const float *log_b, const int *len_q,
+                                    const int *len_k, void *O, float *UV, void *dQ, void *dK,
+                                    void *dV, int B, int H, int L, int d, int W, int T, int R_max,
+                                    float eps, int dustbin, float dustbin_score, int dtype,
+                                    float tau, int *R_selected, float *e_absmax, float *eta_absmax,
+                                    void *workspace, size_t workspace_bytes, void *stream);
+
+/*
  * Benchmark hooks (no part of the operator).  While enabled, every forward and backward
  * call records two HIP events on its stream around each of its phases, so that a phase can
  * be timed in place, inside a larger timed region, without a profiler.  At most 4096 phase

@@ -52,6 +52,10 @@ def load():
         lib.sinkhorn_attn_base_vjp.restype = i
         lib.sinkhorn_attn_base_vjp.argtypes = [vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, i, i, i, i, i, i, f, i, f, i,
                                                vp, sz, vp]
+        lib.sinkhorn_attn_select_workspace_bytes.restype = sz
+        lib.sinkhorn_attn_select_workspace_bytes.argtypes = [i] * 9
+        lib.sinkhorn_attn_select_tail_depth.restype = i
+        lib.sinkhorn_attn_select_tail_depth.argtypes = [vp] * 13 + [i] * 7 + [f, i, f, i, f, vp, vp, vp, vp, sz, vp]
         lib.sinkhorn_attn_profile_enable.restype = i
         lib.sinkhorn_attn_profile_enable.argtypes = [i]
         lib.sinkhorn_attn_profile_read.restype = i
@@ -209,6 +213,42 @@ def sinkhorn_attn_base_vjp(Q, K, UV, eta, W, T, eps=1.0, dustbin=False, dustbin_
     if rc != SKA_OK:
         raise SinkhornAttnError(rc)
     return dQ, dK
+
+
+def sinkhorn_attn_select_workspace_bytes(B, H, L, d, W, T, R_max, dustbin=False, dtype=SKA_BF16) -> int:
+    return int(load().sinkhorn_attn_select_workspace_bytes(B, H, L, d, W, T, R_max, int(bool(dustbin)), dtype))
+
+
+def sinkhorn_attn_select_tail_depth(Q, K, V, dO, W, T, R_max, tau, eps=1.0, dustbin=False, dustbin_score=0.0,
+                                    log_a=None, log_b=None, len_q=None, len_k=None):
+    """First tail depth R <= R_max whose certificate max|(D_x z_T)^T eta_R| is <= tau.
+    Returns a dict: R (0 if none passes), e_absmax and eta_absmax (lists over the depths tried),
+    and O, UV, dQ, dK, dV of the selected depth (of R_max if none passes)."""
+    B, H, L, d = Q.shape
+    for n, x in (("Q", Q), ("K", K), ("V", V), ("dO", dO)):
+        _check(x, (B, H, L, d), Q.dtype, n)
+    Lp = L + int(bool(dustbin))
+    code = _dtype_code(Q)
+    O, dQ, dK, dV = (torch.empty_like(Q) for _ in range(4))
+    UV = torch.empty(B * H * 2 * (R_max + 1) * Lp, device=Q.device, dtype=torch.float32)
+    need = sinkhorn_attn_select_workspace_bytes(B, H, L, d, W, T, R_max, dustbin, code)
+    if need == 0:
+        raise SinkhornAttnError(SKA_EUNSUPPORTED)
+    ws = torch.empty(need, device=Q.device, dtype=torch.uint8)
+    sel = ctypes.c_int(0)
+    e, eta = (ctypes.c_float * R_max)(), (ctypes.c_float * R_max)()
+    rc = load().sinkhorn_attn_select_tail_depth(
+        Q.data_ptr(), K.data_ptr(), V.data_ptr(), dO.data_ptr(), _marg_ptr(log_a, (B, H, L), "log_a"),
+        _marg_ptr(log_b, (B, H, L), "log_b"), _len_ptr(len_q, B, "len_q"), _len_ptr(len_k, B, "len_k"),
+        O.data_ptr(), UV.data_ptr(), dQ.data_ptr(), dK.data_ptr(), dV.data_ptr(), B, H, L, d, W, T, R_max,
+        float(eps), int(bool(dustbin)), float(dustbin_score), code, float(tau), ctypes.addressof(sel),
+        ctypes.addressof(e), ctypes.addressof(eta), ws.data_ptr(), need, _stream_ptr())
+    if rc != SKA_OK:
+        raise SinkhornAttnError(rc)
+    R = sel.value or R_max
+    tried = [k for k in range(R_max) if e[k] >= 0.0]
+    return dict(R=sel.value, e_absmax=[e[k] for k in tried], eta_absmax=[eta[k] for k in tried], O=O,
+                UV=UV[:B * H * 2 * (R + 1) * Lp].view(B, H, 2 * (R + 1), Lp), dQ=dQ, dK=dK, dV=dV)
 
 
 def sinkhorn_attn_bwd(Q, K, V, O, dO, UV, W, T, R=2, eps=1.0, dustbin=False, dustbin_score=0.0,

@@ -1268,6 +1268,27 @@ __global__ void rowdot_kernel(const T *A, const T *Bm, float *g, long gstride, i
     if (sub == 0 && o < Lp) g[n * gstride + o] = acc;
 }
 
+// *out = max(*out, max_i |x_i|) over n elements (a NaN counts as +inf).  Non-negative floats
+// order like their bit patterns, so the maximum is taken on unsigned integers.
+template <typename T>
+__global__ __launch_bounds__(256) void absmax_kernel(const T *x, long n, float *out)
+{
+    float m = 0.f;
+    for (long i = (long)blockIdx.x * blockDim.x + threadIdx.x; i < n; i += (long)gridDim.x * blockDim.x) {
+        const float v = fabsf((float)x[i]);
+        m = (v == v) ? fmaxf(m, v) : INFINITY;
+    }
+#pragma unroll
+    for (int s = 32; s >= 1; s >>= 1) m = fmaxf(m, __shfl_xor(m, s));
+    __shared__ float red[4];
+    if ((threadIdx.x & 63) == 0) red[threadIdx.x >> 6] = m;
+    __syncthreads();
+    if (threadIdx.x == 0) {
+        m = fmaxf(fmaxf(red[0], red[1]), fmaxf(red[2], red[3]));
+        atomicMax(reinterpret_cast<unsigned int *>(out), __float_as_uint(m));
+    }
+}
+
 // out[n][j] = seed[n][j] / b_j for j < Lp: a cotangent handed in from outside enters the reverse
 // recurrences in the form the workspace keeps (divided by the marginal target).
 __global__ void seed_kernel(const float *seed, const float *olog, float *out, long ostride, int Lp)
@@ -1792,6 +1813,34 @@ int bwd_impl(const Problem &p, const void *Qin, const void *K, const void *V, co
     return SKA_OK;
 }
 
+// the tail-depth selector's scratch, carved out of one workspace
+size_t up256(size_t x) { return (x + 255) / 256 * 256; }
+struct SelectLayout {
+    size_t core, eq, ek, uvb, eta, norm, total;
+};
+SelectLayout select_layout(const Problem &p, int T, int R_max)
+{
+    Problem q = p;
+    q.R = R_max > T ? R_max : T;   // workspace of the deepest call (it grows with the depth)
+    SelectLayout l{};
+    const size_t mat = (size_t)p.N() * p.L * p.d * (p.dtype == SKA_BF16 ? 2 : 4);
+    l.core = 0;
+    l.eq = up256(ws_bytes(q));
+    l.ek = l.eq + up256(mat);
+    l.uvb = l.ek + up256(mat);
+    l.eta = l.uvb + up256((size_t)p.N() * 2 * (T + 1) * p.Lp() * sizeof(float));
+    l.norm = l.eta + up256((size_t)p.N() * p.Lp() * sizeof(float));
+    l.total = l.norm + 256;
+    return l;
+}
+template <typename T> int absmax_launch(const void *x, long n, float *out, hipStream_t st)
+{
+    long blocks = (n + 255) / 256;
+    if (blocks > 2048) blocks = 2048;
+    hipLaunchKernelGGL((absmax_kernel<T>), dim3((unsigned)blocks), dim3(256), 0, st, reinterpret_cast<const T *>(x), n, out);
+    return hipGetLastError() == hipSuccess ? SKA_OK : SKA_EHIP;
+}
+
 }  // namespace
 
 // ====================================================================== C ABI
@@ -1921,6 +1970,74 @@ int sinkhorn_attn_bwd(const void *Q, const void *K, const void *V, const void *O
     return sinkhorn_attn_bwd_marginals(Q, K, V, nullptr, nullptr, O, dO, UV, dQ, dK, dV, eta0, B, H, L, d, W,
                                        T, R, eps, dustbin, dustbin_score, dtype, workspace, workspace_bytes,
                                        stream);
+}
+
+size_t sinkhorn_attn_select_workspace_bytes(int B, int H, int L, int d, int W, int T, int R_max, int dustbin,
+                                            int dtype)
+{
+    Problem p{B, H, L, d, W, T, R_max, dustbin ? 1 : 0, dtype, 1.f, 0.f};
+    if (check_common(p) != SKA_OK || T < 1 || T > MAXR) return 0;
+    return select_layout(p, T, R_max).total;
+}
+
+int sinkhorn_attn_select_tail_depth(const void *Q, const void *K, const void *V, const void *dO,
+                                    const float *log_a, const float *log_b, const int *len_q, const int *len_k,
+                                    void *O, float *UV, void *dQ, void *dK, void *dV, int B, int H, int L, int d,
+                                    int W, int T, int R_max, float eps, int dustbin, float dustbin_score,
+                                    int dtype, float tau, int *R_selected, float *e_absmax, float *eta_absmax,
+                                    void *workspace, size_t workspace_bytes, void *stream)
+{
+    Problem p{B, H, L, d, W, T, R_max, dustbin ? 1 : 0, dtype, eps, dustbin_score, log_a, log_b, len_q, len_k};
+    if (!Q || !K || !V || !dO || !O || !UV || !dQ || !dK || !dV || !R_selected || !e_absmax) return SKA_EINVAL;
+    if (!(tau >= 0.f)) return SKA_EINVAL;
+    int rc = check_common(p);
+    if (rc != SKA_OK) return rc;
+    if (T < 1 || T > MAXR) return SKA_EUNSUPPORTED;   // the base iterates are kept: 2(T + 1) vectors
+    const SelectLayout l = select_layout(p, T, R_max);
+    if (!workspace || workspace_bytes < l.total) return SKA_EWORKSPACE;
+    if (reinterpret_cast<uintptr_t>(workspace) & 255) return SKA_EINVAL;
+    hipStream_t st = reinterpret_cast<hipStream_t>(stream);
+    unsigned char *w = reinterpret_cast<unsigned char *>(workspace);
+    void *eQ = w + l.eq, *eK = w + l.ek;
+    float *UVb = reinterpret_cast<float *>(w + l.uvb), *eta = reinterpret_cast<float *>(w + l.eta);
+    float *norm = reinterpret_cast<float *>(w + l.norm);   // [0] certificate, [1] eta
+    const long nmat = (long)p.N() * L * d, nvec = (long)p.N() * p.Lp();
+    for (int r = 0; r < R_max; ++r) {
+        e_absmax[r] = -1.f;
+        if (eta_absmax) eta_absmax[r] = -1.f;
+    }
+    *R_selected = 0;
+    // all iterates of the base solve, once (O is scratch here)
+    SKA_TRY(sinkhorn_attn_fwd_varlen(Q, K, V, log_a, log_b, len_q, len_k, O, UVb, B, H, L, d, W, 0, T, eps, dustbin,
+                                     dustbin_score, dtype, w, l.eq, stream));
+    for (int R = 1; R <= R_max; ++R) {
+        SKA_TRY(sinkhorn_attn_fwd_varlen(Q, K, V, log_a, log_b, len_q, len_k, O, UV, B, H, L, d, W, T, R, eps,
+                                         dustbin, dustbin_score, dtype, w, l.eq, stream));
+        SKA_TRY(sinkhorn_attn_bwd_varlen(Q, K, V, log_a, log_b, len_q, len_k, O, dO, UV, dQ, dK, dV, eta, B, H, L,
+                                         d, W, T, R, eps, dustbin, dustbin_score, dtype, w, l.eq, stream));
+        SKA_TRY(sinkhorn_attn_base_vjp(Q, K, log_a, log_b, len_q, len_k, UVb, eta, eQ, eK, B, H, L, d, W, T, eps,
+                                       dustbin, dustbin_score, dtype, w, l.eq, stream));
+        hipLaunchKernelGGL(fill_kernel, dim3(1), dim3(64), 0, st, norm, 2L, 2L, 1, 0.f);
+        if (hipGetLastError() != hipSuccess) return SKA_EHIP;
+        if (dtype == SKA_F32) {
+            SKA_TRY(absmax_launch<float>(eQ, nmat, norm, st));
+            SKA_TRY(absmax_launch<float>(eK, nmat, norm, st));
+        } else {
+            SKA_TRY(absmax_launch<__bf16>(eQ, nmat, norm, st));
+            SKA_TRY(absmax_launch<__bf16>(eK, nmat, norm, st));
+        }
+        SKA_TRY(absmax_launch<float>(eta, nvec, norm + 1, st));
+        float host[2] = {0.f, 0.f};
+        if (hipMemcpyAsync(host, norm, sizeof(host), hipMemcpyDeviceToHost, st) != hipSuccess) return SKA_EHIP;
+        if (hipStreamSynchronize(st) != hipSuccess) return SKA_EHIP;
+        e_absmax[R - 1] = host[0];
+        if (eta_absmax) eta_absmax[R - 1] = host[1];
+        if (host[0] <= tau) {
+            *R_selected = R;
+            return SKA_OK;
+        }
+    }
+    return SKA_OK;
 }
 
 int sinkhorn_attn_profile_enable(int on)

@@ -25,6 +25,7 @@ def test_library_exports_every_declared_symbol():
                      "sinkhorn_attn_fwd", "sinkhorn_attn_fwd_marginals", "sinkhorn_attn_fwd_varlen",
                      "sinkhorn_attn_profile_enable",
                      "sinkhorn_attn_profile_read", "sinkhorn_attn_profile_read_phases",
+                     "sinkhorn_attn_select_tail_depth", "sinkhorn_attn_select_workspace_bytes",
                      "sinkhorn_attn_strerror",
                      "sinkhorn_attn_workspace_bytes"]
     for n in names:
@@ -84,6 +85,9 @@ def test_argument_errors_are_reported_before_any_launch():
     for T, want in ((0, binding.SKA_EUNSUPPORTED), (33, binding.SKA_EUNSUPPORTED), (4, binding.SKA_EWORKSPACE)):
         assert lib.sinkhorn_attn_base_vjp(pp, pp, nul, nul, nul, nul, pp, pp, pp, pp, 1, 1, 64, 32, 4, T, 1.0, 0,
                                           0.0, 0, None, 0, None) == want
+    assert binding.sinkhorn_attn_select_workspace_bytes(1, 1, 64, 32, 4, 0, 4) == 0       # T >= 1
+    assert (binding.sinkhorn_attn_select_workspace_bytes(1, 1, 64, 32, 4, 5, 4, dtype=0)
+            > binding.sinkhorn_attn_workspace_bytes(1, 1, 64, 32, 4, 0, 5, dtype=0) + 2 * 64 * 32 * 4)
     assert _bwd(lib, ws=None, ws_bytes=0) == binding.SKA_EWORKSPACE
     assert _fwd(lib, dtype=1) == binding.SKA_EWORKSPACE          # bf16 forward needs its scratch
     need = binding.sinkhorn_attn_workspace_bytes(1, 1, 64, 32, 4, 2, dtype=0)

@@ -196,6 +196,46 @@ def test_base_vjp_is_the_stopped_bias(dtype, d, kind):
         assert e < tol, (name, e)
 
 
+@pytest.mark.parametrize("seed", [0, 1, 2])
+def test_certified_tail_depth_selection(seed):
+    """Cor. 'Certified Tail-Depth Selection' on a setting shaped like the paper's certificate table
+    (L = 128, T = 15, band covering the whole problem, eps = 1): the certificate max|e_R| of every
+    depth against the oracle's full-minus-stopped gap, its decay with R, the depth chosen for a
+    tolerance placed between two depths, and the guarantee itself -- the returned gradient is
+    within tau (plus fp32 noise) of the oracle's full backpropagation."""
+    import torch
+
+    import paper_2605_08123_amd as ska
+    T, Rmax = 15, 4
+    w = small("table2", 128, 32, 128, T, "f32", eps=1.0, B=1, H=1, R=Rmax)
+    print(f"\n[case] {w} seed {seed}: certified selector", flush=True)
+    arrays = make_inputs(w, seed)
+    dev = torch.device("cuda:0")
+    Q, K, V, G = (torch.from_numpy(x).to(dev) for x in arrays)
+    full = {R: oracle.band_batched(*arrays, w.W, 0, T + R, w.eps) for R in range(1, Rmax + 1)}
+    stop = {R: oracle.band_batched(*arrays, w.W, T, R, w.eps) for R in range(1, Rmax + 1)}
+    gap = [max(np.abs(full[R][k] - stop[R][k]).max() for k in ("dQ", "dK")) for R in range(1, Rmax + 1)]
+    allr = ska.sinkhorn_attn_select_tail_depth(Q, K, V, G, w.W, T, Rmax, 0.0, w.eps)     # tau = 0: try every depth
+    print("   max|e_R|  gpu:", [f"{x:.3e}" for x in allr["e_absmax"]], flush=True)
+    print("   max|e_R|  ref:", [f"{x:.3e}" for x in gap], flush=True)
+    print("   max|eta_R| gpu:", [f"{x:.3e}" for x in allr["eta_absmax"]], flush=True)
+    assert allr["R"] == 0 and len(allr["e_absmax"]) == Rmax
+    scale = max(np.abs(stop[1][k]).max() for k in ("dQ", "dK"))
+    for R in range(1, Rmax + 1):
+        assert abs(allr["e_absmax"][R - 1] - gap[R - 1]) <= 0.02 * gap[R - 1] + 2e-6 * scale, R
+    assert all(gap[k + 1] < 0.5 * gap[k] for k in range(2))          # the bias falls with the depth
+    assert all(allr["eta_absmax"][k + 1] < 0.5 * allr["eta_absmax"][k] for k in range(2))
+    tau = float(np.sqrt(gap[0] * gap[1]))                            # between depth 1 and depth 2
+    sel = ska.sinkhorn_attn_select_tail_depth(Q, K, V, G, w.W, T, Rmax, tau, w.eps)
+    assert sel["R"] == 2 and len(sel["e_absmax"]) == 2 and sel["e_absmax"][1] <= tau < sel["e_absmax"][0]
+    for k in ("dQ", "dK", "dV"):
+        got = sel[k].cpu().numpy().astype(np.float64)
+        assert rel(got, stop[2][k]) < TOL["f32"], k                  # the stopped gradient of depth 2
+        assert np.abs(got - full[2][k]).max() <= tau + 1e-5 * scale, k   # ... certified against full BPTT
+    O2, UV2 = ska.sinkhorn_attn_fwd(Q, K, V, w.W, T, 2, w.eps)
+    assert torch.equal(sel["O"], O2) and torch.equal(sel["UV"], UV2)
+
+
 def _targets(w, seed):
     rng = np.random.default_rng(seed)
     a = rng.uniform(0.4, 1.8, (w.B, w.H, w.L))
