@@ -84,6 +84,10 @@ def main() -> int:
     ap.add_argument("--steps", type=int, default=10)
     ap.add_argument("--warmup", type=int, default=2)
     ap.add_argument("--workload", default="paper")
+    ap.add_argument("--backward", default="one_reference",
+                    choices=["one_reference", "direct", "one_reference_generic"],
+                    help="how the final sweeps of the backward obtain the plan factors (the last two are "
+                         "comparators: every factor by its own exponential / Prop. 2 on the generic kernel)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-tokens", type=int, default=262144)
     ap.add_argument("--calibrate-copy", action="store_true",
@@ -114,11 +118,13 @@ def main() -> int:
     wsb = ska.sinkhorn_attn_workspace_bytes(w.B, w.H, w.L, w.d, w.W, w.T, w.R, w.dustbin, code)
     wsp = torch.empty(wsb, device=dev, dtype=torch.uint8)
 
+    variant = {"one_reference": 0, "direct": 1, "one_reference_generic": 2}[args.backward]
+
     def step():
         ska.sinkhorn_attn_fwd(Q, K, V, w.W, w.T, w.R, w.eps, w.dustbin, w.dustbin_score, O=O, UV=UV,
                               workspace=wsp)
-        ska.sinkhorn_attn_bwd(Q, K, V, O, G, UV, w.W, w.T, w.R, w.eps, w.dustbin, w.dustbin_score,
-                              workspace=wsp, dQ=dQ, dK=dK, dV=dV)
+        ska.sinkhorn_attn_bwd_variant(variant, Q, K, V, None, None, None, None, O, G, UV, w.W, w.T, w.R, w.eps,
+                                      w.dustbin, w.dustbin_score, workspace=wsp, dQ=dQ, dK=dK, dV=dV)
 
     if args.calibrate_copy:
         src = torch.empty(256 << 20, device=dev, dtype=torch.uint8).random_(0, 255)
@@ -177,7 +183,7 @@ def main() -> int:
         "ms_per_step": ms_per_step, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": dt_name, "data": "synthetic",
         "config": {"workload": w.name, "B": w.B, "H": w.H, "L": w.L, "d": w.d, "W": w.W, "T": w.T,
-                   "R": w.R, "eps": w.eps, "dustbin": w.dustbin},
+                   "R": w.R, "eps": w.eps, "dustbin": w.dustbin, "backward": args.backward},
         # the scaling sweep against its three ceilings; the one that binds (the largest lower bound on
         # a launch's time: 20.5 us ALU, 17.3 us HBM, 13.8 us MFMA at this workload) is the plain-ALU
         # issue rate of one exp2 and one add per band edge

@@ -194,6 +194,31 @@ int sinkhorn_attn_select_tail_depth(const void *Q, const void *K, const void *V,
                                     void *workspace, size_t workspace_bytes, void *stream);
 
 /*
+ * Comparators for the final sweeps of the backward (same arguments and results as
+ * sinkhorn_attn_bwd_varlen; they exist to be measured against it):
+ *   SKA_BWD_ONE_REFERENCE          the production path (Prop. 2: one reference plan tile per
+ *                                  edge, the other staircase factors by row/column modifiers);
+ *   SKA_BWD_DIRECT                 the plain evaluation of Prop. 1: every staircase factor
+ *                                  P^(t,t) and P^(t,t-1), t = R..1, is formed by an exponential
+ *                                  of its own from the scores and its pair of potentials (four
+ *                                  plans for R = 2; the paper's "direct four-plan" form);
+ *   SKA_BWD_ONE_REFERENCE_GENERIC  Prop. 2 on the same generic kernel the direct form runs on
+ *                                  (for bf16 storage with d <= 64 the production path uses a
+ *                                  different, faster kernel), so that the two differ in nothing
+ *                                  but how the plan factors are obtained.
+ * Any other variant: SKA_EINVAL.
+ */
+#define SKA_BWD_ONE_REFERENCE 0
+#define SKA_BWD_DIRECT 1
+#define SKA_BWD_ONE_REFERENCE_GENERIC 2
+int sinkhorn_attn_bwd_variant(int variant, const void *Q, const void *K, const void *V,
+                              const float *log_a, const float *log_b, const int *len_q,
+                              const int *len_k, const void *O, const void *dO, const float *UV,
+                              void *dQ, void *dK, void *dV, float *eta0, int B, int H, int L, int d,
+                              int W, int T, int R, float eps, int dustbin, float dustbin_score,
+                              int dtype, void *workspace, size_t workspace_bytes, void *stream);
+
+/*
  * Benchmark hooks (no part of the operator).  While enabled, every forward and backward
  * call records two HIP events on its stream around each of its phases, so that a phase can
  * be timed in place, inside a larger timed region, without a profiler.  At most 4096 phase

@@ -4,7 +4,7 @@
 `workloads` holds the seeded synthetic inputs; `build` compiles the library.
 """
 from .binding import (SinkhornAttnError, sinkhorn_attn_base_vjp, sinkhorn_attn_bwd, sinkhorn_attn_bwd_marginals,  # noqa: F401
-                      sinkhorn_attn_bwd_varlen, sinkhorn_attn_fwd, sinkhorn_attn_fwd_marginals,
+                      sinkhorn_attn_bwd_variant, sinkhorn_attn_bwd_varlen, sinkhorn_attn_fwd, sinkhorn_attn_fwd_marginals,
                       sinkhorn_attn_fwd_varlen,
                       sinkhorn_attn_profile_enable, sinkhorn_attn_profile_read,
                       sinkhorn_attn_profile_read_phases,

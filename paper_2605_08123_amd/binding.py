@@ -15,6 +15,7 @@ _PKG = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.path.join(_PKG, "libsinkhorn_attn.so")
 
 SKA_F32, SKA_BF16 = 0, 1
+SKA_BWD_ONE_REFERENCE, SKA_BWD_DIRECT, SKA_BWD_ONE_REFERENCE_GENERIC = 0, 1, 2
 SKA_OK, SKA_EINVAL, SKA_EUNSUPPORTED, SKA_EWORKSPACE, SKA_EHIP = 0, -1, -2, -3, -4
 
 _lib = None
@@ -56,6 +57,8 @@ def load():
         lib.sinkhorn_attn_select_workspace_bytes.argtypes = [i] * 9
         lib.sinkhorn_attn_select_tail_depth.restype = i
         lib.sinkhorn_attn_select_tail_depth.argtypes = [vp] * 13 + [i] * 7 + [f, i, f, i, f, vp, vp, vp, vp, sz, vp]
+        lib.sinkhorn_attn_bwd_variant.restype = i
+        lib.sinkhorn_attn_bwd_variant.argtypes = [i] + lib.sinkhorn_attn_bwd_varlen.argtypes
         lib.sinkhorn_attn_profile_enable.restype = i
         lib.sinkhorn_attn_profile_enable.argtypes = [i]
         lib.sinkhorn_attn_profile_read.restype = i
@@ -270,6 +273,15 @@ def sinkhorn_attn_bwd_varlen(Q, K, V, log_a, log_b, len_q, len_k, O, dO, UV, W, 
                              dustbin=False, dustbin_score=0.0, want_eta0=False, workspace=None, dQ=None,
                              dK=None, dV=None):
     """Backward of a padded batch (see sinkhorn_attn_fwd_varlen)."""
+    return sinkhorn_attn_bwd_variant(SKA_BWD_ONE_REFERENCE, Q, K, V, log_a, log_b, len_q, len_k, O, dO, UV, W,
+                                     T, R, eps, dustbin, dustbin_score, want_eta0, workspace, dQ, dK, dV)
+
+
+def sinkhorn_attn_bwd_variant(variant, Q, K, V, log_a, log_b, len_q, len_k, O, dO, UV, W, T, R=2, eps=1.0,
+                              dustbin=False, dustbin_score=0.0, want_eta0=False, workspace=None, dQ=None,
+                              dK=None, dV=None):
+    """The backward with its final sweeps evaluated as SKA_BWD_ONE_REFERENCE (production),
+    SKA_BWD_DIRECT (every plan factor by its own exponential) or SKA_BWD_ONE_REFERENCE_GENERIC."""
     B, H, L, d = Q.shape
     for n, x in (("Q", Q), ("K", K), ("V", V), ("O", O), ("dO", dO)):
         _check(x, (B, H, L, d), Q.dtype, n)
@@ -285,8 +297,8 @@ def sinkhorn_attn_bwd_varlen(Q, K, V, log_a, log_b, len_q, len_k, O, dO, UV, W, 
     if workspace is None:
         workspace = torch.empty(max(need, 16), device=Q.device, dtype=torch.uint8)
     eta0 = torch.empty((B, H, Lp), device=Q.device, dtype=torch.float32) if want_eta0 else None
-    rc = load().sinkhorn_attn_bwd_varlen(
-        Q.data_ptr(), K.data_ptr(), V.data_ptr(), _marg_ptr(log_a, (B, H, L), "log_a"),
+    rc = load().sinkhorn_attn_bwd_variant(
+        int(variant), Q.data_ptr(), K.data_ptr(), V.data_ptr(), _marg_ptr(log_a, (B, H, L), "log_a"),
         _marg_ptr(log_b, (B, H, L), "log_b"), _len_ptr(len_q, B, "len_q"), _len_ptr(len_k, B, "len_k"),
         O.data_ptr(), dO.data_ptr(), UV.data_ptr(), dQ.data_ptr(),
         dK.data_ptr(), dV.data_ptr(), eta0.data_ptr() if want_eta0 else None, B, H, L, d, W, T, R,

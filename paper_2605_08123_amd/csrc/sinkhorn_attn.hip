@@ -50,7 +50,8 @@ constexpr int MAXR = 32;     // deepest differentiable tail (T = 0 with R = T' +
                              // backpropagation through a T'-step base solve)
 constexpr int MAXNQ = 2;     // float4 groups of modifier terms one final sweep takes (8 terms);
                              // deeper tails take several sweeps that accumulate
-enum Mode { M_LSE_FIRST = 0, M_LSE = 1, M_MATVEC = 2, M_APPLY = 3, M_FINAL = 4 };
+enum Mode { M_LSE_FIRST = 0, M_LSE = 1, M_MATVEC = 2, M_APPLY = 3, M_FINAL = 4,
+            M_FINAL_DIRECT = 5 /* dispatch only: M_FINAL of the generic kernel with DIRECT = true */ };
 
 struct Vec {          // one fp32 vector per problem
     const float *p;
@@ -80,6 +81,7 @@ struct SweepArgs {
     int nq;           // groups of four terms this sweep takes (1 or 2)
     int pstride;      // groups per index in memory (2R terms in all)
     int skipz;        // FINAL: leave Z out (second and later sweeps of a deep tail)
+    int refterm;      // direct FINAL: the first term of this sweep multiplies the reference plan itself
     int accum;        // FINAL: add to the output instead of overwriting it
     const void *poB;  // FINAL on the ring kernel: owner-side pack as 16 bf16 columns  [N][ldp][16]
     const void *qtA;  // FINAL on the ring kernel: other-side pack as 16 bf16 columns  [N][ldp][16]
@@ -389,7 +391,11 @@ template <typename T, int D, int MODE> struct Stage {
     static constexpr int BYTES = ((OFF_VQ + TT * 16 * MAXNQ) + 15) / 16 * 16;
 };
 
-template <typename T, int D, int MODE, int FR>
+// DIRECT (M_FINAL only): the comparator that forms every staircase plan factor by an
+// exponential of its own, exp(S + u_t + v_t'), instead of scaling the one reference tile
+// (Prop. 2 versus the plain evaluation of Prop. 1).  A pack group then holds two terms as
+// (log2 modifier, weight) pairs: the term is exp2(score + l_row + l_col) w_row w_col.
+template <typename T, int D, int MODE, int FR, bool DIRECT = false>
 __global__ __launch_bounds__(NTHREADS) void sweep_kernel(const SweepArgs a)
 {
     using TL = Tile<T, D>;
@@ -565,6 +571,10 @@ __global__ __launch_bounds__(NTHREADS) void sweep_kernel(const SweepArgs a)
                 sum[f] = sacc;
                 mx[f] = mn;
             } else {
+                float el[DIRECT ? 16 : 1];
+                if constexpr (DIRECT)
+#pragma unroll
+                    for (int r = 0; r < 16; ++r) el[r] = e[r];
 #pragma unroll
                 for (int r = 0; r < 16; ++r) e[r] = fast_exp2(e[r]);
                 if constexpr (MODE == M_APPLY) {
@@ -578,15 +588,29 @@ __global__ __launch_bounds__(NTHREADS) void sweep_kernel(const SweepArgs a)
                     for (int r = 0; r < 16; ++r) {
                         const int tl = 8 * (r >> 2) + 4 * h + (r & 3);
                         float md = z[r];
+                        if constexpr (DIRECT) {
+                            float sb = e[r] * md;
 #pragma unroll
-                        for (int g = 0; g < MAXNQ; ++g) {   // (an absent group is all zeros)
-                            float4 q4 = *reinterpret_cast<const float4 *>(s + ST::OFF_VQ + (tl * MAXNQ + g) * 16);
-                            md = fmaf(-pof[f][g].x, q4.x, md);
-                            md = fmaf(-pof[f][g].y, q4.y, md);
-                            md = fmaf(-pof[f][g].z, q4.z, md);
-                            md = fmaf(-pof[f][g].w, q4.w, md);
+                            for (int g = 0; g < MAXNQ; ++g) {   // (an absent group has zero weights)
+                                float4 q4 = *reinterpret_cast<const float4 *>(s + ST::OFF_VQ + (tl * MAXNQ + g) * 16);
+                                const float p0 = (g == 0 && a.refterm) ? e[r]
+                                                                       : fast_exp2(el[r] + pof[f][g].x + q4.x);
+                                const float p1 = fast_exp2(el[r] + pof[f][g].z + q4.z);
+                                sb = fmaf(-p0 * pof[f][g].y, q4.y, sb);
+                                sb = fmaf(-p1 * pof[f][g].w, q4.w, sb);
+                            }
+                            e[r] = sb;
+                        } else {
+#pragma unroll
+                            for (int g = 0; g < MAXNQ; ++g) {   // (an absent group is all zeros)
+                                float4 q4 = *reinterpret_cast<const float4 *>(s + ST::OFF_VQ + (tl * MAXNQ + g) * 16);
+                                md = fmaf(-pof[f][g].x, q4.x, md);
+                                md = fmaf(-pof[f][g].y, q4.y, md);
+                                md = fmaf(-pof[f][g].z, q4.z, md);
+                                md = fmaf(-pof[f][g].w, q4.w, md);
+                            }
+                            e[r] *= md;
                         }
-                        e[r] *= md;
                     }
                     tile_accum<T, D>(outm[f], TL::IS_BF16 ? s + ST::OFF_PAY : s + ST::OFF_Y, e, lane);
                 }
@@ -1338,8 +1362,11 @@ __device__ __forceinline__ void pack_cols(const float (&x)[4], __bf16 *A, __bf16
 #pragma unroll
     for (int k = 12; k < 16; ++k) { A[k] = (__bf16)0.f; B[k] = (__bf16)0.f; }
 }
+// direct != 0 (comparator): a group holds the two terms of one tail step as (log2 modifier, weight)
+// pairs, row side (l_t, 1, l_t, ubar_t), column side (m_t, vbar_t, m_{t-1}, 1) with
+// l_t = (u_t - u_R) log2 e, m_t = (v_t - v_R) log2 e; nq = R groups.
 __global__ void packs_kernel(const float *UV, int Lp, int R, const float *vecs, long nldw, long wstride,
-                             float *rowp, float *colp, int nq, __bf16 *aug, long ldp, long nldp)
+                             float *rowp, float *colp, int nq, __bf16 *aug, long ldp, long nldp, int direct)
 {
     const int n = blockIdx.y;
     const int i = blockIdx.x * blockDim.x + threadIdx.x;
@@ -1354,7 +1381,12 @@ __global__ void packs_kernel(const float *UV, int Lp, int R, const float *vecs, 
         const float at = __expf(uv[(2 * t) * Lp + i] - uR), bt = __expf(uv[(2 * t + 1) * Lp + i] - vR);
         const float bp = __expf(uv[(2 * t - 1) * Lp + i] - vR);
         const float vb = vecs[(1 + 2 * q) * nldw + w], ub = vecs[(2 + 2 * q) * nldw + w];
-        if (!aug) {
+        if (direct) {
+            const float lt = (uv[(2 * t) * Lp + i] - uR) * LOG2E, mt = (uv[(2 * t + 1) * Lp + i] - vR) * LOG2E;
+            const float mp = (uv[(2 * t - 1) * Lp + i] - vR) * LOG2E;
+            rp[4 * q] = lt; rp[4 * q + 1] = 1.f; rp[4 * q + 2] = lt; rp[4 * q + 3] = ub;
+            cp[4 * q] = mt; cp[4 * q + 1] = vb;  cp[4 * q + 2] = mp; cp[4 * q + 3] = 1.f;
+        } else if (!aug) {
             rp[2 * q] = at;          cp[2 * q] = bt * vb;
             rp[2 * q + 1] = at * ub; cp[2 * q + 1] = bp;
         } else if (q < 2) {
@@ -1362,7 +1394,9 @@ __global__ void packs_kernel(const float *UV, int Lp, int R, const float *vecs, 
             else { r4[2] = at; c4[2] = bt * vb; r4[3] = at * ub; c4[3] = bp; }
         }
     }
-    if (!aug) {
+    if (direct) {
+        // (R groups, all written)
+    } else if (!aug) {
         for (int k = 2 * R; k < 4 * nq; ++k) { rp[k] = 0.f; cp[k] = 0.f; }   // pad the last group
     } else {
         __align__(16) __bf16 A[16], B[16];
@@ -1422,6 +1456,8 @@ struct Problem {
     float eps, sdb;
     const float *log_a = nullptr, *log_b = nullptr;   // [N][Lp] logs of the marginal targets, or null
     const int *len_q = nullptr, *len_k = nullptr;     // [B] valid lengths of the two sequences, or null
+    int variant = 0;                                  // backward: SKA_BWD_* (comparators of the final sweeps)
+    bool direct() const { return variant == SKA_BWD_DIRECT; }
     int N() const { return B * H; }
     int Lp() const { return L + (dustbin ? 1 : 0); }
     long ldw() const { return ((long)Lp() + 3) / 4 * 4; }  // stride of workspace vectors
@@ -1437,9 +1473,9 @@ size_t ws_qs_bytes(const Problem &p)
 }
 size_t ws_vec_bytes(const Problem &p)
 {
-    // 1 + 2R vectors, two packs of float4 groups, four packs of 16 bf16 columns
-    return (size_t)p.N() * p.ldw() *
-           (ws_vecs(p.R) * sizeof(float) + 2 * pack_groups(p.R) * sizeof(float4) + 4 * 32);
+    // 1 + 2R vectors, two packs of R float4 groups (the one-reference sweeps use the first
+    // (2R + 3) / 4 of them, the direct comparator all), four packs of 16 bf16 columns
+    return (size_t)p.N() * p.ldw() * (ws_vecs(p.R) * sizeof(float) + 2 * p.R * sizeof(float4) + 4 * 32);
 }
 size_t ws_bytes(const Problem &p) { return ws_vec_bytes(p) + ws_qs_bytes(p); }
 
@@ -1475,7 +1511,7 @@ int check_common(const Problem &p)
     return SKA_OK;
 }
 
-template <typename T, int D, int MODE, int FR>
+template <typename T, int D, int MODE, int FR, bool DIRECT = false>
 int launch_sweep(SweepArgs a, int N, hipStream_t st)
 {
     constexpr int BM = NWAVES * FR * 32;
@@ -1485,12 +1521,12 @@ int launch_sweep(SweepArgs a, int N, hipStream_t st)
     constexpr int LDS = 2 * Stage<T, D, MODE>::BYTES;
     static bool raised = false;    // static LDS tops out at 64 KB; the CU has 160 KB
     if (LDS > 48 * 1024 && !raised) {
-        if (hipFuncSetAttribute(reinterpret_cast<const void *>(&sweep_kernel<T, D, MODE, FR>),
+        if (hipFuncSetAttribute(reinterpret_cast<const void *>(&sweep_kernel<T, D, MODE, FR, DIRECT>),
                                 hipFuncAttributeMaxDynamicSharedMemorySize, LDS) != hipSuccess)
             return SKA_EHIP;
         raised = true;
     }
-    hipLaunchKernelGGL((sweep_kernel<T, D, MODE, FR>), dim3(chunk * 8), dim3(NTHREADS), LDS, st, a);
+    hipLaunchKernelGGL((sweep_kernel<T, D, MODE, FR, DIRECT>), dim3(chunk * 8), dim3(NTHREADS), LDS, st, a);
     return hipGetLastError() == hipSuccess ? SKA_OK : SKA_EHIP;
 }
 
@@ -1547,6 +1583,7 @@ template <typename T, int D> int sweep(int mode, const SweepArgs &a, int N, hipS
     case M_APPLY:
         if constexpr (sizeof(T) == 2 && D <= 64) return launch_msweep<D, M_APPLY, 2>(a, N, st);
         else return launch_sweep<T, D, M_APPLY, 1>(a, N, st);
+    case M_FINAL_DIRECT: return launch_sweep<T, D, M_FINAL, 1, true>(a, N, st);
     default:
         if constexpr (sizeof(T) == 2 && D <= 64) {
             if (a.poB) return launch_msweep<D, M_FINAL, 1>(a, N, st);   // packs as bf16 columns (R <= 2)
@@ -1691,7 +1728,7 @@ int bwd_impl(const Problem &p, const void *Qin, const void *K, const void *V, co
         pt.launched(sizeof(T) == 2 ? 1 : 0);
     }
     const int N = p.N(), L = p.L, Lp = p.Lp();
-    const int R = p.R, nq = pack_groups(R);
+    const int R = p.R, nq = p.direct() ? R : pack_groups(R);
     const long us = 2L * (R + 1) * Lp, ldw = p.ldw();
     const long nldp = (long)N * ldw;
     auto uv = [&](int k) { return Vec{UV + (long)k * Lp, us}; };   // slot 2t: u_t, slot 2t + 1: v_t
@@ -1700,10 +1737,11 @@ int bwd_impl(const Problem &p, const void *Qin, const void *K, const void *V, co
     auto vbar = [&](int t) { return wf + (1 + 2 * (R - t)) * nldp; };   // t = 1 ... R
     auto ubar = [&](int t) { return wf + (2 + 2 * (R - t)) * nldp; };
     float4 *rowp = reinterpret_cast<float4 *>(wf + (long)ws_vecs(R) * nldp);
-    float4 *colp = rowp + nldp * nq;
+    float4 *colp = rowp + nldp * R;   // (room for R groups per side)
     // the ring kernel (R <= 2) takes the packs as bf16 columns (rowA, rowB, colA, colB)
-    const bool AUG = (sizeof(T) == 2 && D <= 64 && R <= 2 && !seed);   // (that kernel always adds Z)
-    __bf16 *aug = reinterpret_cast<__bf16 *>(colp + nldp * nq);
+    const bool AUG = (sizeof(T) == 2 && D <= 64 && R <= 2 && !seed && p.variant == SKA_BWD_ONE_REFERENCE);   // (that kernel always adds Z)
+    __bf16 *aug = reinterpret_cast<__bf16 *>(colp + nldp * R);
+    const int final_mode = p.direct() ? M_FINAL_DIRECT : M_FINAL;
     auto wv = [&](float *q) { return Vec{q, ldw}; };
     auto wo = [&](float *q) { return VecOut{q, ldw}; };
 
@@ -1779,7 +1817,7 @@ int bwd_impl(const Problem &p, const void *Qin, const void *K, const void *V, co
     pt_final.launched(2 * ((nq + MAXNQ - 1) / MAXNQ));
     hipLaunchKernelGGL(packs_kernel, vgrid, dim3(256), 0, st, UV, Lp, R, wf, nldp, ldw,
                        reinterpret_cast<float *>(rowp), reinterpret_cast<float *>(colp), nq, AUG ? aug : nullptr,
-                       ldw, nldp);
+                       ldw, nldp, p.direct() ? 1 : 0);
     if (hipGetLastError() != hipSuccess) return SKA_EHIP;
     // one-reference final sweeps; a sweep takes eight modifier terms, so a tail deeper than
     // R = 4 takes several that accumulate (Z only in the first)
@@ -1791,10 +1829,11 @@ int bwd_impl(const Problem &p, const void *Qin, const void *K, const void *V, co
             a.po = rowp + g0; a.qt = colp + g0; a.ldp = ldw; a.nq = ng; a.pstride = nq;
             a.len_own = p.len_q; a.len_oth = p.len_k;
             a.skipz = a.accum = g0 > 0;
+            a.refterm = g0 == 0;   // (direct: the first term of all is P_RR vbar_R itself)
             if (seed) { a.A = Q; a.Bm = K; a.skipz = 1; }   // Z = 0; the factors are fetched but unused
             if (AUG) { a.poB = aug + 1 * nldp * 16; a.qtA = aug + 2 * nldp * 16; }   // rows own, columns stream
             a.rev = nlaunch++ & 1;
-            SKA_TRY((sweep<T, D>(M_FINAL, a, N, st)));
+            SKA_TRY((sweep<T, D>(final_mode, a, N, st)));
         }
         {
             SweepArgs a = base;
@@ -1802,12 +1841,13 @@ int bwd_impl(const Problem &p, const void *Qin, const void *K, const void *V, co
             a.po = colp + g0; a.qt = rowp + g0; a.ldp = ldw; a.nq = ng; a.pstride = nq;
             a.len_own = p.len_k; a.len_oth = p.len_q;
             a.skipz = a.accum = g0 > 0;
+            a.refterm = g0 == 0;
             if (seed) { a.A = K; a.Bm = Q; a.skipz = 1; }
             if (AUG) { a.poB = aug + 3 * nldp * 16; a.qtA = aug + 0 * nldp * 16; }   // columns own, rows stream
             // payload rows are Qs = (cs log2 e) Q when prescaled: cs sum Sbar^T Q = ln 2 sum Sbar^T Qs
             if (sizeof(T) == 2) a.cs = LN2;
             a.rev = nlaunch++ & 1;
-            SKA_TRY((sweep<T, D>(M_FINAL, a, N, st)));
+            SKA_TRY((sweep<T, D>(final_mode, a, N, st)));
         }
     }
     return SKA_OK;
@@ -1896,14 +1936,13 @@ int sinkhorn_attn_fwd(const void *Q, const void *K, const void *V, void *O, floa
                                        dustbin_score, dtype, workspace, workspace_bytes, stream);
 }
 
-int sinkhorn_attn_bwd_varlen(const void *Q, const void *K, const void *V, const float *log_a,
-                             const float *log_b, const int *len_q, const int *len_k, const void *O,
-                             const void *dO, const float *UV, void *dQ, void *dK, void *dV, float *eta0, int B,
-                             int H, int L, int d, int W, int T, int R, float eps, int dustbin,
-                             float dustbin_score, int dtype, void *workspace, size_t workspace_bytes,
-                             void *stream)
+static int bwd_call(int variant, const void *Q, const void *K, const void *V, const float *log_a,
+                    const float *log_b, const int *len_q, const int *len_k, const void *O, const void *dO,
+                    const float *UV, void *dQ, void *dK, void *dV, float *eta0, int B, int H, int L, int d, int W,
+                    int T, int R, float eps, int dustbin, float dustbin_score, int dtype, void *workspace,
+                    size_t workspace_bytes, void *stream)
 {
-    Problem p{B, H, L, d, W, T, R, dustbin ? 1 : 0, dtype, eps, dustbin_score, log_a, log_b, len_q, len_k};
+    Problem p{B, H, L, d, W, T, R, dustbin ? 1 : 0, dtype, eps, dustbin_score, log_a, log_b, len_q, len_k, variant};
     if (!Q || !K || !V || !O || !dO || !UV || !dQ || !dK || !dV) return SKA_EINVAL;
     int rc = check_common(p);
     if (rc != SKA_OK) return rc;
@@ -1949,6 +1988,30 @@ int sinkhorn_attn_base_vjp(const void *Q, const void *K, const float *log_a, con
         SKA_VJP(__bf16, 128);
     }
 #undef SKA_VJP
+}
+
+int sinkhorn_attn_bwd_varlen(const void *Q, const void *K, const void *V, const float *log_a,
+                             const float *log_b, const int *len_q, const int *len_k, const void *O,
+                             const void *dO, const float *UV, void *dQ, void *dK, void *dV, float *eta0, int B,
+                             int H, int L, int d, int W, int T, int R, float eps, int dustbin,
+                             float dustbin_score, int dtype, void *workspace, size_t workspace_bytes,
+                             void *stream)
+{
+    return bwd_call(0, Q, K, V, log_a, log_b, len_q, len_k, O, dO, UV, dQ, dK, dV, eta0, B, H, L, d, W, T, R, eps,
+                    dustbin, dustbin_score, dtype, workspace, workspace_bytes, stream);
+}
+
+int sinkhorn_attn_bwd_variant(int variant, const void *Q, const void *K, const void *V, const float *log_a,
+                              const float *log_b, const int *len_q, const int *len_k, const void *O,
+                              const void *dO, const float *UV, void *dQ, void *dK, void *dV, float *eta0, int B,
+                              int H, int L, int d, int W, int T, int R, float eps, int dustbin,
+                              float dustbin_score, int dtype, void *workspace, size_t workspace_bytes,
+                              void *stream)
+{
+    if (variant != SKA_BWD_ONE_REFERENCE && variant != SKA_BWD_DIRECT && variant != SKA_BWD_ONE_REFERENCE_GENERIC)
+        return SKA_EINVAL;
+    return bwd_call(variant, Q, K, V, log_a, log_b, len_q, len_k, O, dO, UV, dQ, dK, dV, eta0, B, H, L, d, W, T, R, eps,
+                    dustbin, dustbin_score, dtype, workspace, workspace_bytes, stream);
 }
 
 int sinkhorn_attn_bwd_marginals(const void *Q, const void *K, const void *V, const float *log_a,

@@ -21,7 +21,7 @@ def declared_symbols():
 def test_library_exports_every_declared_symbol():
     lib = binding.load()
     names = declared_symbols()
-    assert names == ["sinkhorn_attn_base_vjp", "sinkhorn_attn_bwd", "sinkhorn_attn_bwd_marginals", "sinkhorn_attn_bwd_varlen",
+    assert names == ["sinkhorn_attn_base_vjp", "sinkhorn_attn_bwd", "sinkhorn_attn_bwd_marginals", "sinkhorn_attn_bwd_variant", "sinkhorn_attn_bwd_varlen",
                      "sinkhorn_attn_fwd", "sinkhorn_attn_fwd_marginals", "sinkhorn_attn_fwd_varlen",
                      "sinkhorn_attn_profile_enable",
                      "sinkhorn_attn_profile_read", "sinkhorn_attn_profile_read_phases",

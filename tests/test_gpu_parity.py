@@ -236,6 +236,49 @@ def test_certified_tail_depth_selection(seed):
     assert torch.equal(sel["O"], O2) and torch.equal(sel["UV"], UV2)
 
 
+@pytest.mark.parametrize("dtype,d,R,kind", [("f32", 32, 2, "plain"), ("bf16", 64, 2, "plain"), ("bf16", 128, 3, "plain"),
+                                            ("f32", 64, 1, "marginals"), ("bf16", 32, 5, "plain"),
+                                            ("f32", 32, 2, "dustbin")])
+def test_backward_variants(dtype, d, R, kind):
+    """The comparators of the final sweeps -- every staircase factor by its own exponential
+    (direct; Prop. 1 as it stands) and Prop. 2 on the generic kernel -- against the oracle to
+    the same tolerance as the production path; their dV and eta0 are the production path's."""
+    import torch
+
+    import paper_2605_08123_amd as ska
+    from paper_2605_08123_amd.binding import SKA_BWD_DIRECT, SKA_BWD_ONE_REFERENCE_GENERIC
+    db = kind == "dustbin"
+    w = small("variants", 450, d, 29, 4, dtype, eps=0.8, B=1, H=2, R=R, dustbin=db, dustbin_score=0.2)
+    print(f"\n[case] {w} backward variants ({kind})", flush=True)
+    arrays = make_inputs(w, 13)
+    la = lb = None
+    if kind == "marginals":
+        la, lb = _targets(w, 14)
+    dev = torch.device("cuda:0")
+    td = torch.float32 if dtype == "f32" else torch.bfloat16
+    Q, K, V, G = (torch.from_numpy(x).to(dev).to(td) for x in arrays)
+    tla = torch.from_numpy(la).to(dev) if la is not None else None
+    tlb = torch.from_numpy(lb).to(dev) if lb is not None else None
+    O, UV = ska.sinkhorn_attn_fwd_marginals(Q, K, V, tla, tlb, w.W, w.T, R, w.eps, db, w.dustbin_score)
+    prod = ska.sinkhorn_attn_bwd_marginals(Q, K, V, tla, tlb, O, G, UV, w.W, w.T, R, w.eps, db, w.dustbin_score,
+                                           want_eta0=True)
+    kw = dict(log_a=None if la is None else la.astype(np.float64), log_b=None if lb is None else lb.astype(np.float64))
+    ref = oracle.band_batched(*arrays, w.W, w.T, R, w.eps, db, w.dustbin_score, **kw)
+    for variant in (SKA_BWD_DIRECT, SKA_BWD_ONE_REFERENCE_GENERIC):
+        got = ska.sinkhorn_attn_bwd_variant(variant, Q, K, V, tla, tlb, None, None, O, G, UV, w.W, w.T, R, w.eps,
+                                            db, w.dustbin_score, want_eta0=True)
+        torch.cuda.synchronize()
+        errs = {n: rel(x.float().cpu().numpy().astype(np.float64), ref[n]) for n, x in zip(("dQ", "dK", "dV"), got)}
+        print(f"   variant {variant} rel-L2:", {n: f"{e:.2e}" for n, e in errs.items()}, flush=True)
+        for n, e in errs.items():
+            assert e <= TOL[dtype], (variant, n, e)
+        assert torch.equal(got[2], prod[2]) and torch.equal(got[3], prod[3])
+    with pytest.raises(ska.SinkhornAttnError) as e:
+        ska.sinkhorn_attn_bwd_variant(7, Q, K, V, tla, tlb, None, None, O, G, UV, w.W, w.T, R, w.eps, db,
+                                      w.dustbin_score)
+    assert e.value.status == -1
+
+
 def _targets(w, seed):
     rng = np.random.default_rng(seed)
     a = rng.uniform(0.4, 1.8, (w.B, w.H, w.L))
