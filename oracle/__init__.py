@@ -130,6 +130,31 @@ def band(Q, K, V, G, W, T, R, eps, dustbin=False, dustbin_score=0.0, v0_fixed=No
     return out
 
 
+def band_eps_schedule(Q, K, V, G, W, eps_stages, T_stages, R, eps, dustbin=False, dustbin_score=0.0,
+                      log_a=None, log_b=None):
+    """Stopped base solve with a continuation schedule eps_1 >= ... >= eps_N = eps (remark
+    "Fixed-Budget eps-Scaling"): stage s runs T_s full steps on the scores A / eps_s.  Between
+    stages the column log-scaling is carried as a potential in cost units, eps_s v -> v' =
+    v eps_s / eps_{s+1} (the paper does not say how; this is the usual continuation rule).  The
+    tail and its backward are the ordinary ones at eps, started from the final base state, which
+    is a constant for differentiation.  dustbin_score is the spoke score at eps and scales like
+    every other score.  Built from `band` calls: a stage is T_s tail steps from a fixed v."""
+    Q = _f64(Q)
+    L = Q.shape[0]
+    assert len(eps_stages) == len(T_stages) >= 1 and abs(eps_stages[-1] - eps) <= 1e-12 * eps
+    v = np.zeros(L + (1 if dustbin else 0))
+    for s, (es, Ts) in enumerate(zip(eps_stages, T_stages)):
+        if Ts > 0:
+            r = band(Q, K, V, None, W, 0, Ts, es, dustbin, dustbin_score * eps / es, v0_fixed=v,
+                     log_a=log_a, log_b=log_b)
+            v = r["UV"][2 * Ts + 1].copy()
+        if s + 1 < len(eps_stages):
+            v = v * (es / eps_stages[s + 1])
+    out = band(Q, K, V, G, W, 0, R, eps, dustbin, dustbin_score, v0_fixed=v, log_a=log_a, log_b=log_b)
+    out["v_base"] = v
+    return out
+
+
 def band_rect(Q, K, V, G, W, T, R, eps, log_a=None, log_b=None):
     """Banded operator on a rectangle: Q, G are [Lq, d], K, V are [Lk, d] (token sequences of
     different lengths, or a padded batch item cut to its valid lengths); the support is

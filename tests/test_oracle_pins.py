@@ -355,6 +355,59 @@ def test_rectangular_band_matches_dense_brute_force(Lq, Lk, W):
         assert all(rel(out[k], sq[k]) < 1e-14 for k in ("O", "dQ", "dK", "dV"))
 
 
+# ---------------------------------------------------------------- eps-scaling of the stopped base
+def test_eps_schedule_matches_dense_stage_loop():
+    """Continuation schedule in the base solve: an explicit dense stage loop with the library
+    logsumexp (scores A / eps_s, v carried as eps v) gives the same base state, output and --
+    through the closed-form adjoint with that base state frozen -- the same gradients."""
+    rng = np.random.default_rng(77)
+    L, d, W, R, eps = 40, 4, 6, 2, 0.25
+    Q, K, V, G = (rng.standard_normal((L, d)) for _ in range(4))
+    stages, steps = [1.0, 0.5, 0.25], [3, 2, 4]
+    out = oracle.band_eps_schedule(Q, K, V, G, W, stages, steps, R, eps)
+    mask = dr.band_mask(L, W)
+    A = (Q @ K.T) / np.sqrt(d)
+    v = np.zeros(L)
+    for s, (es, Ts) in enumerate(zip(stages, steps)):
+        Sm = np.where(mask, A / es, -np.inf)
+        for _ in range(Ts):
+            u = -dr.logsumexp(Sm + v[None, :], axis=1)
+            v = -dr.logsumexp(Sm + u[:, None], axis=0)
+        if s + 1 < len(stages):
+            v = v * es / stages[s + 1]
+    assert np.abs(out["v_base"] - v).max() < 1e-12
+    S = A / eps
+    U, Vp = dr.half_steps(S, mask, 0, R, v0_fixed=v)
+    cf = dr.closed_form_adjoint(S, mask, U, Vp, V, G)
+    cs = 1.0 / (eps * np.sqrt(d))
+    assert rel(out["O"], cf["O"]) < 1e-12 and rel(out["dV"], cf["dV"]) < 1e-12
+    assert rel(out["dQ"], cs * cf["Sbar"] @ K) < 1e-11 and rel(out["dK"], cs * cf["Sbar"].T @ Q) < 1e-11
+    # one stage at eps is the plain operator
+    plain = oracle.band(Q, K, V, G, W, 9, R, eps)
+    one = oracle.band_eps_schedule(Q, K, V, G, W, [eps], [9], R, eps)
+    assert all(rel(one[k], plain[k]) < 1e-14 for k in ("O", "dQ", "dK", "dV"))
+    # equal temperatures in every stage: the split into stages changes nothing
+    split = oracle.band_eps_schedule(Q, K, V, G, W, [eps, eps, eps], [3, 2, 4], R, eps)
+    assert all(rel(split[k], plain[k]) < 1e-13 for k in ("O", "dQ", "dK", "dV"))
+
+
+def test_eps_schedule_helps_at_sharp_temperature():
+    """What the continuation is for: at a sharp eps and a fixed budget of T steps, the terminal
+    plan of the scheduled solve is closer to unit row sums than the plain one."""
+    rng = np.random.default_rng(78)
+    L, d, W, R, eps, T = 96, 8, 12, 1, 0.05, 8
+    Q, K, V = (rng.standard_normal((L, d)) for _ in range(3))
+    mask = dr.band_mask(L, W)
+    S = dr.scores(Q, K, eps)
+
+    def row_error(o):
+        P = dr.plan(S, mask, o["UV"][2 * R], o["UV"][2 * R + 1])
+        return np.abs(P.sum(1) - 1.0).max()
+    plain = oracle.band(Q, K, V, None, W, T, R, eps)
+    sched = oracle.band_eps_schedule(Q, K, V, None, W, [0.4, 0.2, 0.1, 0.05], [2, 2, 2, 2], R, eps)
+    assert row_error(sched) < row_error(plain)
+
+
 def test_dense_zero_scores_is_uniform_plan():
     L = 11
     _, K, V, G = problem(L=L, seed=10)
