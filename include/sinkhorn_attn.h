@@ -145,6 +145,25 @@ int sinkhorn_attn_bwd_varlen(const void *Q, const void *K, const void *V, const 
                              size_t workspace_bytes, void *stream);
 
 /*
+ * Forward with a continuation schedule in the stopped base solve (remark "Fixed-Budget
+ * eps-Scaling"): stage s = 1..n_stages runs T_stage[s] full steps on the scores A / eps_stage[s],
+ * eps_stage[1] >= ... >= eps_stage[n_stages] = eps; T = sum of T_stage.  Between stages the
+ * log-scalings are carried as potentials in cost units (multiplied by eps_s / eps_{s+1}; the paper
+ * leaves this open).  The tail, the output and UV are those of the plain call at eps, and the
+ * backward calls apply unchanged (the base is stopped; pass T = sum of T_stage, which they only
+ * check).  eps_stage, T_stage: HOST arrays of n_stages entries (1 <= n_stages <= 64), read
+ * before the call returns.  A schedule that increases, a last entry different from eps, a
+ * negative count: SKA_EINVAL.  dustbin_score is the spoke score at eps and is rescaled like all
+ * scores.  Other arguments as in sinkhorn_attn_fwd_varlen.
+ */
+int sinkhorn_attn_fwd_eps_schedule(const void *Q, const void *K, const void *V, const float *log_a,
+                                   const float *log_b, const int *len_q, const int *len_k, void *O,
+                                   float *UV, int B, int H, int L, int d, int W, int n_stages,
+                                   const float *eps_stage, const int *T_stage, int R, float eps,
+                                   int dustbin, float dustbin_score, int dtype, void *workspace,
+                                   size_t workspace_bytes, void *stream);
+
+/*
  * Vector-Jacobian product through the base solve: dQ, dK = (D_x z_T)^T eta for the base state
  * z_T = v^(T) reached by T full steps from v = 0 (the a-posteriori bias certificate,
  * Prop. "A Posteriori Bias Certificate": with eta = eta_R, the base cotangent that the

@@ -59,6 +59,8 @@ def load():
         lib.sinkhorn_attn_select_tail_depth.argtypes = [vp] * 13 + [i] * 7 + [f, i, f, i, f, vp, vp, vp, vp, sz, vp]
         lib.sinkhorn_attn_bwd_variant.restype = i
         lib.sinkhorn_attn_bwd_variant.argtypes = [i] + lib.sinkhorn_attn_bwd_varlen.argtypes
+        lib.sinkhorn_attn_fwd_eps_schedule.restype = i
+        lib.sinkhorn_attn_fwd_eps_schedule.argtypes = [vp] * 9 + [i] * 6 + [vp, vp, i, f, i, f, i, vp, sz, vp]
         lib.sinkhorn_attn_profile_enable.restype = i
         lib.sinkhorn_attn_profile_enable.argtypes = [i]
         lib.sinkhorn_attn_profile_read.restype = i
@@ -163,8 +165,20 @@ def sinkhorn_attn_fwd_marginals(Q, K, V, log_a, log_b, W, T, R=2, eps=1.0, dustb
                                     UV, workspace)
 
 
+def sinkhorn_attn_fwd_eps_schedule(Q, K, V, W, eps_stage, T_stage, R=2, eps=1.0, dustbin=False,
+                                   dustbin_score=0.0, log_a=None, log_b=None, len_q=None, len_k=None, O=None,
+                                   UV=None, workspace=None):
+    """Forward whose stopped base solve follows a continuation schedule: T_stage[s] steps at
+    eps_stage[s] (non-increasing, ending at eps).  Returns (O, UV) as sinkhorn_attn_fwd."""
+    n = len(eps_stage)
+    sched = ((ctypes.c_float * max(n, 1))(*[float(x) for x in eps_stage]),
+             (ctypes.c_int * max(n, 1))(*[int(x) for x in T_stage]))
+    return sinkhorn_attn_fwd_varlen(Q, K, V, log_a, log_b, len_q, len_k, W, sum(int(x) for x in T_stage), R, eps,
+                                    dustbin, dustbin_score, O, UV, workspace, _sched=(n,) + sched)
+
+
 def sinkhorn_attn_fwd_varlen(Q, K, V, log_a, log_b, len_q, len_k, W, T, R=2, eps=1.0, dustbin=False,
-                             dustbin_score=0.0, O=None, UV=None, workspace=None):
+                             dustbin_score=0.0, O=None, UV=None, workspace=None, _sched=None):
     """Forward of a padded batch: len_q, len_k are int32 CUDA tensors [B] (or None: L) with the valid
     lengths of the query and key sequences of each batch item; results beyond them are zeros."""
     B, H, L, d = Q.shape
@@ -180,6 +194,17 @@ def sinkhorn_attn_fwd_varlen(Q, K, V, log_a, log_b, len_q, len_k, W, T, R=2, eps
     if workspace is None:
         need = sinkhorn_attn_workspace_bytes(B, H, L, d, W, T, R, dustbin, _dtype_code(Q))
         workspace = torch.empty(max(need, 16), device=Q.device, dtype=torch.uint8)
+    head = (Q.data_ptr(), K.data_ptr(), V.data_ptr(), _marg_ptr(log_a, (B, H, L), "log_a"),
+            _marg_ptr(log_b, (B, H, L), "log_b"), _len_ptr(len_q, B, "len_q"), _len_ptr(len_k, B, "len_k"),
+            O.data_ptr(), UV.data_ptr(), B, H, L, d, W)
+    tail = (R, float(eps), int(bool(dustbin)), float(dustbin_score), _dtype_code(Q), workspace.data_ptr(),
+            workspace.numel() * workspace.element_size(), _stream_ptr())
+    if _sched is not None:
+        rc = load().sinkhorn_attn_fwd_eps_schedule(*head, _sched[0], ctypes.addressof(_sched[1]),
+                                                   ctypes.addressof(_sched[2]), *tail)
+        if rc != SKA_OK:
+            raise SinkhornAttnError(rc)
+        return O, UV
     rc = load().sinkhorn_attn_fwd_varlen(
         Q.data_ptr(), K.data_ptr(), V.data_ptr(), _marg_ptr(log_a, (B, H, L), "log_a"),
         _marg_ptr(log_b, (B, H, L), "log_b"), _len_ptr(len_q, B, "len_q"), _len_ptr(len_k, B, "len_k"),

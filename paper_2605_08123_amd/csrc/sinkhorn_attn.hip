@@ -1292,6 +1292,13 @@ __global__ void rowdot_kernel(const T *A, const T *Bm, float *g, long gstride, i
     if (sub == 0 && o < Lp) g[n * gstride + o] = acc;
 }
 
+// p[n][j] *= f for j < per (the base potentials between two stages of a continuation schedule)
+__global__ void scale_kernel(float *p, long per, long stride, int nprob, float f)
+{
+    long i = (long)blockIdx.x * blockDim.x + threadIdx.x;
+    if (i < per * nprob) p[(i / per) * stride + (i % per)] *= f;
+}
+
 // *out = max(*out, max_i |x_i|) over n elements (a NaN counts as +inf).  Non-negative floats
 // order like their bit patterns, so the maximum is taken on unsigned integers.
 template <typename T>
@@ -1457,6 +1464,9 @@ struct Problem {
     const float *log_a = nullptr, *log_b = nullptr;   // [N][Lp] logs of the marginal targets, or null
     const int *len_q = nullptr, *len_k = nullptr;     // [B] valid lengths of the two sequences, or null
     int variant = 0;                                  // backward: SKA_BWD_* (comparators of the final sweeps)
+    int n_stages = 0;                                 // forward: continuation schedule of the base solve
+    const float *eps_stage = nullptr;                 //   (host arrays; 0 stages: T steps at eps)
+    const int *T_stage = nullptr;
     bool direct() const { return variant == SKA_BWD_DIRECT; }
     int N() const { return B * H; }
     int Lp() const { return L + (dustbin ? 1 : 0); }
@@ -1480,9 +1490,10 @@ size_t ws_vec_bytes(const Problem &p)
 size_t ws_bytes(const Problem &p) { return ws_vec_bytes(p) + ws_qs_bytes(p); }
 
 template <typename T>
-int make_scores_operand(const Problem &p, const void *Q, void *ws_qs, const void **Qs, float *c2, hipStream_t st)
+int make_scores_operand(const Problem &p, float eps, const void *Q, void *ws_qs, const void **Qs, float *c2,
+                        hipStream_t st)
 {
-    const float cs = 1.f / (p.eps * sqrtf((float)p.d));
+    const float cs = 1.f / (eps * sqrtf((float)p.d));
     if constexpr (sizeof(T) == 2) {
         const long n8 = (long)p.N() * p.L * p.d / 8;
         hipLaunchKernelGGL(prescale_kernel, dim3((unsigned)((n8 + 255) / 256)), dim3(256), 0, st,
@@ -1635,7 +1646,7 @@ int fwd_impl(const Problem &p, const void *Qin, const void *K, const void *V, vo
     float c2 = 0.f;
     {
         PhaseTimer pt(SKA_PH_PRESCALE, st);
-        SKA_TRY((make_scores_operand<T>(p, Qin, ws, &Q, &c2, st)));
+        SKA_TRY((make_scores_operand<T>(p, p.n_stages ? p.eps_stage[0] : p.eps, Qin, ws, &Q, &c2, st)));
         pt.launched(sizeof(T) == 2 ? 1 : 0);
     }
     const int N = p.N(), L = p.L, Lp = p.Lp();
@@ -1662,8 +1673,10 @@ int fwd_impl(const Problem &p, const void *Qin, const void *K, const void *V, vo
     PhaseTimer *pt_run = nullptr;
     alignas(PhaseTimer) unsigned char pt_run_mem[sizeof(PhaseTimer)];
     // half-step: out slot <- -LSE over the band of (S + yt); prev slot only stabilises
+    float stage_c2 = c2, stage_sdb2 = base.sdb2;   // (a continuation stage has its own score scale)
     auto half = [&](bool row, int yslot, int prevslot, int outslot) -> int {
         SweepArgs a = base;
+        a.c2 = stage_c2; a.sdb2 = stage_sdb2;
         a.X = row ? Q : K; a.Y = row ? K : Q;
         a.yt = vec(yslot); a.xs = vec(prevslot); a.out_vec = vout(outslot);
         a.olog = Vec{row ? p.log_a : p.log_b, (long)Lp};
@@ -1676,7 +1689,7 @@ int fwd_impl(const Problem &p, const void *Qin, const void *K, const void *V, vo
         else pt_run->launched();
         if (p.dustbin) {
             hipLaunchKernelGGL(dustbin_kernel, dim3(N), dim3(1024), 0, st, vec(yslot), Vec{nullptr, 0},
-                               Vec{nullptr, 0}, vout(outslot), L, p.sdb);
+                               Vec{nullptr, 0}, vout(outslot), L, stage_sdb2 * LN2);
             if (hipGetLastError() != hipSuccess) return SKA_EHIP;
         }
         if (first) {   // the run of identical scaling sweeps starts after the first launch
@@ -1687,10 +1700,28 @@ int fwd_impl(const Problem &p, const void *Qin, const void *K, const void *V, vo
         return SKA_OK;
     };
     auto halves = [&]() -> int {
-        for (int t = 0; t < p.T; ++t) {
-            SKA_TRY(half(true, 1, 0, 0));
-            SKA_TRY(half(false, 0, 1, 1));
+        // base solve: T steps at eps, or the stages of the continuation schedule (remark
+        // "Fixed-Budget eps-Scaling"): stage s runs on the scores A / eps_s; between stages both
+        // potentials are carried in cost units, x -> x eps_s / eps_{s+1} (u only stabilises)
+        const int nst = p.n_stages ? p.n_stages : 1;
+        for (int sidx = 0; sidx < nst; ++sidx) {
+            const float es = p.n_stages ? p.eps_stage[sidx] : p.eps;
+            const int Ts = p.n_stages ? p.T_stage[sidx] : p.T;
+            if (sidx > 0) {
+                const float ratio = p.eps_stage[sidx - 1] / es;
+                long tot = 2L * Lp * N;
+                hipLaunchKernelGGL(scale_kernel, dim3((tot + 255) / 256), dim3(256), 0, st, UV, 2L * Lp, us, N, ratio);
+                if (hipGetLastError() != hipSuccess) return SKA_EHIP;
+                SKA_TRY((make_scores_operand<T>(p, es, Qin, ws, &Q, &stage_c2, st)));
+            }
+            stage_sdb2 = p.sdb * (p.eps / es) * LOG2E;
+            for (int t = 0; t < Ts; ++t) {
+                SKA_TRY(half(true, 1, 0, 0));
+                SKA_TRY(half(false, 0, 1, 1));
+            }
         }
+        stage_c2 = base.c2 = (sizeof(T) == 2) ? 1.f : base.cs * LOG2E;   // the tail runs at eps (= the last stage's)
+        stage_sdb2 = base.sdb2;
         for (int t = 1; t <= R; ++t) {
             SKA_TRY(half(true, 2 * t - 1, 2 * t - 2, 2 * t));    // u_t from v_{t-1}
             SKA_TRY(half(false, 2 * t, 2 * t - 1, 2 * t + 1));   // v_t from u_t
@@ -1724,7 +1755,7 @@ int bwd_impl(const Problem &p, const void *Qin, const void *K, const void *V, co
     float c2 = 0.f;
     {
         PhaseTimer pt(SKA_PH_PRESCALE, st);
-        SKA_TRY((make_scores_operand<T>(p, Qin, reinterpret_cast<unsigned char *>(ws) + ws_vec_bytes(p), &Q, &c2, st)));
+        SKA_TRY((make_scores_operand<T>(p, p.eps, Qin, reinterpret_cast<unsigned char *>(ws) + ws_vec_bytes(p), &Q, &c2, st)));
         pt.launched(sizeof(T) == 2 ? 1 : 0);
     }
     const int N = p.N(), L = p.L, Lp = p.Lp();
@@ -1893,13 +1924,10 @@ size_t sinkhorn_attn_workspace_bytes(int B, int H, int L, int d, int W, int T, i
     return ws_bytes(p);
 }
 
-int sinkhorn_attn_fwd_varlen(const void *Q, const void *K, const void *V, const float *log_a,
-                             const float *log_b, const int *len_q, const int *len_k, void *O, float *UV, int B,
-                             int H, int L, int d, int W, int T, int R, float eps, int dustbin,
-                             float dustbin_score, int dtype, void *workspace, size_t workspace_bytes,
-                             void *stream)
+static int fwd_call(const Problem &p, const void *Q, const void *K, const void *V, void *O, float *UV,
+                    void *workspace, size_t workspace_bytes, void *stream)
 {
-    Problem p{B, H, L, d, W, T, R, dustbin ? 1 : 0, dtype, eps, dustbin_score, log_a, log_b, len_q, len_k};
+    const int d = p.d, dtype = p.dtype;
     if (!Q || !K || !V || !O || !UV) return SKA_EINVAL;
     int rc = check_common(p);
     if (rc != SKA_OK) return rc;
@@ -1917,6 +1945,35 @@ int sinkhorn_attn_fwd_varlen(const void *Q, const void *K, const void *V, const 
         SKA_FWD(__bf16, 128);
     }
 #undef SKA_FWD
+}
+
+int sinkhorn_attn_fwd_varlen(const void *Q, const void *K, const void *V, const float *log_a,
+                             const float *log_b, const int *len_q, const int *len_k, void *O, float *UV, int B,
+                             int H, int L, int d, int W, int T, int R, float eps, int dustbin,
+                             float dustbin_score, int dtype, void *workspace, size_t workspace_bytes,
+                             void *stream)
+{
+    Problem p{B, H, L, d, W, T, R, dustbin ? 1 : 0, dtype, eps, dustbin_score, log_a, log_b, len_q, len_k};
+    return fwd_call(p, Q, K, V, O, UV, workspace, workspace_bytes, stream);
+}
+
+int sinkhorn_attn_fwd_eps_schedule(const void *Q, const void *K, const void *V, const float *log_a,
+                                   const float *log_b, const int *len_q, const int *len_k, void *O, float *UV,
+                                   int B, int H, int L, int d, int W, int n_stages, const float *eps_stage,
+                                   const int *T_stage, int R, float eps, int dustbin, float dustbin_score,
+                                   int dtype, void *workspace, size_t workspace_bytes, void *stream)
+{
+    if (n_stages < 1 || n_stages > 64 || !eps_stage || !T_stage) return SKA_EINVAL;
+    int T = 0;
+    for (int s = 0; s < n_stages; ++s) {
+        if (!(eps_stage[s] > 0.f) || !isfinite(eps_stage[s]) || T_stage[s] < 0) return SKA_EINVAL;
+        if (s > 0 && eps_stage[s] > eps_stage[s - 1]) return SKA_EINVAL;   // eps_1 >= ... >= eps_N
+        T += T_stage[s];
+    }
+    if (fabsf(eps_stage[n_stages - 1] - eps) > 1e-6f * eps) return SKA_EINVAL;   // eps_N = eps
+    Problem p{B, H, L, d, W, T, R, dustbin ? 1 : 0, dtype, eps, dustbin_score, log_a, log_b, len_q, len_k};
+    p.n_stages = n_stages; p.eps_stage = eps_stage; p.T_stage = T_stage;
+    return fwd_call(p, Q, K, V, O, UV, workspace, workspace_bytes, stream);
 }
 
 int sinkhorn_attn_fwd_marginals(const void *Q, const void *K, const void *V, const float *log_a,

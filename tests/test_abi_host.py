@@ -22,7 +22,8 @@ def test_library_exports_every_declared_symbol():
     lib = binding.load()
     names = declared_symbols()
     assert names == ["sinkhorn_attn_base_vjp", "sinkhorn_attn_bwd", "sinkhorn_attn_bwd_marginals", "sinkhorn_attn_bwd_variant", "sinkhorn_attn_bwd_varlen",
-                     "sinkhorn_attn_fwd", "sinkhorn_attn_fwd_marginals", "sinkhorn_attn_fwd_varlen",
+                     "sinkhorn_attn_fwd", "sinkhorn_attn_fwd_eps_schedule", "sinkhorn_attn_fwd_marginals",
+                     "sinkhorn_attn_fwd_varlen",
                      "sinkhorn_attn_profile_enable",
                      "sinkhorn_attn_profile_read", "sinkhorn_attn_profile_read_phases",
                      "sinkhorn_attn_select_tail_depth", "sinkhorn_attn_select_workspace_bytes",
@@ -88,6 +89,16 @@ def test_argument_errors_are_reported_before_any_launch():
     assert binding.sinkhorn_attn_select_workspace_bytes(1, 1, 64, 32, 4, 0, 4) == 0       # T >= 1
     assert (binding.sinkhorn_attn_select_workspace_bytes(1, 1, 64, 32, 4, 5, 4, dtype=0)
             > binding.sinkhorn_attn_workspace_bytes(1, 1, 64, 32, 4, 0, 5, dtype=0) + 2 * 64 * 32 * 4)
+    def sched(eps_s, T_s, eps=0.5):
+        n = len(eps_s)
+        return lib.sinkhorn_attn_fwd_eps_schedule(pp, pp, pp, nul, nul, nul, nul, pp, pp, 1, 1, 64, 32, 4, n,
+                                                  (ctypes.c_float * max(n, 1))(*eps_s), (ctypes.c_int * max(n, 1))(*T_s),
+                                                  2, eps, 0, 0.0, 1, None, 0, None)
+    assert sched([2.0, 1.0, 0.5], [1, 1, 1]) == binding.SKA_EWORKSPACE     # valid schedule: gets as far as the workspace
+    assert sched([1.0, 2.0, 0.5], [1, 1, 1]) == binding.SKA_EINVAL         # increasing
+    assert sched([2.0, 1.0], [1, 1]) == binding.SKA_EINVAL                 # does not end at eps
+    assert sched([2.0, 0.5], [1, -1]) == binding.SKA_EINVAL
+    assert sched([], []) == binding.SKA_EINVAL
     assert _bwd(lib, ws=None, ws_bytes=0) == binding.SKA_EWORKSPACE
     assert _fwd(lib, dtype=1) == binding.SKA_EWORKSPACE          # bf16 forward needs its scratch
     need = binding.sinkhorn_attn_workspace_bytes(1, 1, 64, 32, 4, 2, dtype=0)

@@ -279,6 +279,55 @@ def test_backward_variants(dtype, d, R, kind):
     assert e.value.status == -1
 
 
+@pytest.mark.parametrize("dtype,d,kind", [("f32", 32, "plain"), ("bf16", 64, "plain"), ("f32", 64, "dustbin"),
+                                          ("bf16", 128, "marginals")])
+def test_eps_schedule_in_the_base_solve(dtype, d, kind):
+    """Continuation schedule (remark 'Fixed-Budget eps-Scaling'): forward with three stages, the
+    ordinary backward on its UV, against the oracle's scheduled solve; a single stage at eps is
+    the plain forward bit for bit."""
+    import torch
+
+    import paper_2605_08123_amd as ska
+    stages, steps, eps, R = [1.6, 0.8, 0.4], [3, 2, 4], 0.4, 2
+    db = kind == "dustbin"
+    w = small("sched", 500, d, 27, sum(steps), dtype, eps=eps, B=1, H=2, R=R, dustbin=db, dustbin_score=0.3)
+    print(f"\n[case] {w} eps schedule {stages} x {steps} ({kind})", flush=True)
+    arrays = make_inputs(w, 17)
+    la = lb = None
+    if kind == "marginals":
+        la, lb = _targets(w, 18)
+    dev = torch.device("cuda:0")
+    td = torch.float32 if dtype == "f32" else torch.bfloat16
+    Q, K, V, G = (torch.from_numpy(x).to(dev).to(td) for x in arrays)
+    tla = torch.from_numpy(la).to(dev) if la is not None else None
+    tlb = torch.from_numpy(lb).to(dev) if lb is not None else None
+    O, UV = ska.sinkhorn_attn_fwd_eps_schedule(Q, K, V, w.W, stages, steps, R, eps, db, w.dustbin_score, tla, tlb)
+    dQ, dK, dV = ska.sinkhorn_attn_bwd_marginals(Q, K, V, tla, tlb, O, G, UV, w.W, w.T, R, eps, db, w.dustbin_score)
+    torch.cuda.synchronize()
+    got = {n: x.float().cpu().numpy().astype(np.float64) for n, x in dict(O=O, dQ=dQ, dK=dK, dV=dV).items()}
+    worst = dict.fromkeys(got, 0.0)
+    for h in range(w.H):
+        q, k, v, g = (x[0, h] for x in arrays)
+        ref = oracle.band_eps_schedule(q, k, v, g, w.W, stages, steps, R, eps, db, w.dustbin_score,
+                                       log_a=None if la is None else la[0, h].astype(np.float64),
+                                       log_b=None if lb is None else lb[0, h].astype(np.float64))
+        plain = oracle.band(q, k, v, g, w.W, w.T, R, eps, db, w.dustbin_score,
+                            log_a=None if la is None else la[0, h].astype(np.float64),
+                            log_b=None if lb is None else lb[0, h].astype(np.float64))
+        if dtype == "f32":      # the schedule matters on this input: far outside the tolerance of the plain solve
+            assert rel(plain["O"], ref["O"]) > 10 * TOL[dtype]
+        for n in got:
+            worst[n] = max(worst[n], rel(got[n][0, h], ref[n]))
+        vb = UV[0, h, 1].cpu().numpy().astype(np.float64)
+        assert np.abs(vb - ref["v_base"]).max() < (5e-4 if dtype == "f32" else 5e-2)
+    print("   rel-L2:", {n: f"{e:.2e}" for n, e in worst.items()}, flush=True)
+    for n, e in worst.items():
+        assert e <= TOL[dtype], (n, e)
+    O1, UV1 = ska.sinkhorn_attn_fwd_eps_schedule(Q, K, V, w.W, [eps], [w.T], R, eps, db, w.dustbin_score, tla, tlb)
+    O0, UV0 = ska.sinkhorn_attn_fwd_marginals(Q, K, V, tla, tlb, w.W, w.T, R, eps, db, w.dustbin_score)
+    assert torch.equal(O1, O0) and torch.equal(UV1, UV0)
+
+
 def _targets(w, seed):
     rng = np.random.default_rng(seed)
     a = rng.uniform(0.4, 1.8, (w.B, w.H, w.L))
