@@ -130,6 +130,44 @@ def band(Q, K, V, G, W, T, R, eps, dustbin=False, dustbin_score=0.0, v0_fixed=No
     return out
 
 
+def band_dustbin_token(Q, K, V, G, q_db, k_db, v_db, W, T, R, eps):
+    """Single-active-dustbin bridge with a learned dustbin token per side (Sec. 'Single-Active-
+    Dustbin Bridge'): the tensors are augmented by one row, Q~ = [Q; q_db], K~ = [K; k_db],
+    V~ = [V; v_db], and the unit-target operator runs on the sparse-spoke support
+    band + {(i, d_k)} + {(d_q, j)} + {(d_q, d_k)} with every score q~_i . k~_j / (eps sqrt d).
+    The dustbin query row has no output cotangent (its output is dropped).  Returns O [L,d],
+    dQ, dK, dV [L,d], dq_db, dk_db, dv_db [d], UV [2(R+1), L+1].  Support and scores are built
+    here; the solve is the support-generic core."""
+    Q, K, V, G = _f64(Q), _f64(K), _f64(V), _f64(G)
+    L, d = Q.shape
+    Qa, Ka, Va = (np.vstack([x, _f64(t)[None, :]]) for x, t in ((Q, q_db), (K, k_db), (V, v_db)))
+    i = np.arange(L)
+    lo, hi = np.maximum(i - W, 0), np.minimum(i + W, L - 1)
+    cnt = hi - lo + 1
+    rows_b = np.repeat(i, cnt)
+    start = np.concatenate(([0], np.cumsum(cnt)))[:-1]
+    cols_b = np.arange(cnt.sum()) - np.repeat(start, cnt) + np.repeat(lo, cnt)
+    # row i: its band columns then the dustbin column; dustbin row: every column
+    order_rows = np.concatenate([rows_b, i, np.full(L + 1, L)])
+    order_cols = np.concatenate([cols_b, np.full(L, L), np.arange(L + 1)])
+    key = np.lexsort((order_cols, order_rows))
+    rows, cols = order_rows[key], order_cols[key].astype(np.int32)
+    rptr = np.concatenate(([0], np.cumsum(np.bincount(rows, minlength=L + 1)))).astype(np.int64)
+    cs = 1.0 / (eps * np.sqrt(d))
+    S = cs * np.einsum("ek,ek->e", Qa[rows], Ka[cols])
+    Ga = None if G is None else np.vstack([G, np.zeros((1, d))])
+    r = core(rptr, cols, S, Va, Ga, T, R)
+    UV = np.empty((2 * (R + 1), L + 1))
+    UV[0::2], UV[1::2] = r["U"], r["Vp"]
+    out = {"O": r["O"][:L], "UV": UV}
+    if G is not None:
+        dQa, dKa = np.zeros_like(Qa), np.zeros_like(Ka)
+        np.add.at(dQa, rows, cs * r["Sbar"][:, None] * Ka[cols])
+        np.add.at(dKa, cols, cs * r["Sbar"][:, None] * Qa[rows])
+        out.update(dQ=dQa[:L], dK=dKa[:L], dV=r["dV"][:L], dq_db=dQa[L], dk_db=dKa[L], dv_db=r["dV"][L])
+    return out
+
+
 def band_eps_schedule(Q, K, V, G, W, eps_stages, T_stages, R, eps, dustbin=False, dustbin_score=0.0,
                       log_a=None, log_b=None):
     """Stopped base solve with a continuation schedule eps_1 >= ... >= eps_N = eps (remark

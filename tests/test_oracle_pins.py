@@ -355,6 +355,47 @@ def test_rectangular_band_matches_dense_brute_force(Lq, Lk, W):
         assert all(rel(out[k], sq[k]) < 1e-14 for k in ("O", "dQ", "dK", "dV"))
 
 
+# ---------------------------------------------------------------- learned dustbin tokens
+def test_dustbin_token_matches_dense_augmented_problem():
+    """Learned dustbin tokens: the augmented (L+1) x (L+1) problem, dense, with a boolean mask
+    for band + spokes, library logsumexp half-steps and the closed-form adjoint, against the
+    oracle's sparse construction -- on the gradients of the tokens as well."""
+    rng = np.random.default_rng(91)
+    L, d, W, T, R, eps = 33, 4, 5, 5, 2, 0.7
+    Q, K, V, G = (rng.standard_normal((L, d)) for _ in range(4))
+    qd, kd, vd = (rng.standard_normal(d) for _ in range(3))
+    out = oracle.band_dustbin_token(Q, K, V, G, qd, kd, vd, W, T, R, eps)
+    Qa, Ka, Va = np.vstack([Q, qd]), np.vstack([K, kd]), np.vstack([V, vd])
+    Ga = np.vstack([G, np.zeros(d)])
+    mask = np.zeros((L + 1, L + 1), dtype=bool)
+    mask[:L, :L] = dr.band_mask(L, W)
+    mask[L, :] = True
+    mask[:, L] = True
+    S = dr.scores(Qa, Ka, eps)
+    U, Vp = dr.half_steps(S, mask, T, R)
+    cf = dr.closed_form_adjoint(S, mask, U, Vp, Va, Ga)
+    cs = 1.0 / (eps * np.sqrt(d))
+    dQa, dKa = cs * cf["Sbar"] @ Ka, cs * cf["Sbar"].T @ Qa
+    assert rel(out["O"], cf["O"][:L]) < 1e-12
+    for name, ref in (("dQ", dQa[:L]), ("dK", dKa[:L]), ("dV", cf["dV"][:L]), ("dq_db", dQa[L]),
+                      ("dk_db", dKa[L]), ("dv_db", cf["dV"][L])):
+        assert rel(out[name], ref) < 1e-11, name
+    assert np.abs(out["UV"][2 * R] + 0 - U[R]).max() < 1e-12
+
+
+def test_dustbin_token_with_zero_tokens_is_the_scalar_dustbin():
+    """q_db = k_db = 0 makes every spoke score 0 and v_db = 0 removes the dustbin's value: the
+    scalar-score dustbin operator with score 0."""
+    rng = np.random.default_rng(92)
+    L, d, W, T, R, eps = 40, 4, 6, 4, 2, 0.9
+    Q, K, V, G = (rng.standard_normal((L, d)) for _ in range(4))
+    z = np.zeros(d)
+    tok = oracle.band_dustbin_token(Q, K, V, G, z, z, z, W, T, R, eps)
+    sc = oracle.band(Q, K, V, G, W, T, R, eps, True, 0.0)
+    assert all(rel(tok[k], sc[k]) < 1e-13 for k in ("O", "dQ", "dK", "dV"))
+    assert np.abs(tok["UV"] - sc["UV"]).max() < 1e-12
+
+
 # ---------------------------------------------------------------- eps-scaling of the stopped base
 def test_eps_schedule_matches_dense_stage_loop():
     """Continuation schedule in the base solve: an explicit dense stage loop with the library
