@@ -145,6 +145,31 @@ int sinkhorn_attn_bwd_varlen(const void *Q, const void *K, const void *V, const 
                              size_t workspace_bytes, void *stream);
 
 /*
+ * The dustbin as a learned token per side (Sec. "Single-Active-Dustbin Bridge": Q, K, V are
+ * augmented by one active token, Q~ = [Q; q_db], K~ = [K; k_db], V~ = [V; v_db], and the same
+ * unit-target operator runs on the augmented problem), on the sparse-spoke support
+ * band + {(i, d_k)} + {(d_q, j)} + {(d_q, d_k)}: spoke scores q_i.k_db, q_db.k_j, q_db.k_db (all
+ * divided by eps sqrt d) instead of one scalar, the dustbin key carries the value v_db, and the
+ * backward also returns the gradients of the three tokens.  The dustbin query's output row is
+ * dropped (no cotangent).  O(L d) extra work; the band sweeps are the same kernels.
+ *   q_db, k_db, v_db : [B,H,d] fp32 device arrays, 16-byte aligned (in)
+ *   dq_db, dk_db, dv_db : [B,H,d] fp32 (out)
+ *   UV : [B,H,2(R+1),L+1] as with dustbin = 1; eta0 [B,H,L+1] or NULL.
+ *   workspace: sinkhorn_attn_workspace_bytes(..., dustbin = 1, ...) bytes for BOTH calls.
+ * Other arguments as in sinkhorn_attn_fwd / sinkhorn_attn_bwd.
+ */
+int sinkhorn_attn_fwd_dustbin_token(const void *Q, const void *K, const void *V, const float *q_db,
+                                    const float *k_db, const float *v_db, void *O, float *UV, int B,
+                                    int H, int L, int d, int W, int T, int R, float eps, int dtype,
+                                    void *workspace, size_t workspace_bytes, void *stream);
+int sinkhorn_attn_bwd_dustbin_token(const void *Q, const void *K, const void *V, const float *q_db,
+                                    const float *k_db, const float *v_db, const void *O,
+                                    const void *dO, const float *UV, void *dQ, void *dK, void *dV,
+                                    float *dq_db, float *dk_db, float *dv_db, float *eta0, int B,
+                                    int H, int L, int d, int W, int T, int R, float eps, int dtype,
+                                    void *workspace, size_t workspace_bytes, void *stream);
+
+/*
  * Forward with a continuation schedule in the stopped base solve (remark "Fixed-Budget
  * eps-Scaling"): stage s = 1..n_stages runs T_stage[s] full steps on the scores A / eps_stage[s],
  * eps_stage[1] >= ... >= eps_stage[n_stages] = eps; T = sum of T_stage.  Between stages the

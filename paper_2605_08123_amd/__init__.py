@@ -3,7 +3,8 @@
 `binding` is the thin ctypes layer over the C ABI of include/sinkhorn_attn.h;
 `workloads` holds the seeded synthetic inputs; `build` compiles the library.
 """
-from .binding import (SinkhornAttnError, sinkhorn_attn_base_vjp, sinkhorn_attn_bwd, sinkhorn_attn_bwd_marginals,  # noqa: F401
+from .binding import (SinkhornAttnError, sinkhorn_attn_base_vjp, sinkhorn_attn_bwd,
+                      sinkhorn_attn_bwd_dustbin_token, sinkhorn_attn_fwd_dustbin_token, sinkhorn_attn_bwd_marginals,  # noqa: F401
                       sinkhorn_attn_bwd_variant, sinkhorn_attn_bwd_varlen, sinkhorn_attn_fwd, sinkhorn_attn_fwd_marginals,
                       sinkhorn_attn_fwd_eps_schedule, sinkhorn_attn_fwd_varlen,
                       sinkhorn_attn_profile_enable, sinkhorn_attn_profile_read,

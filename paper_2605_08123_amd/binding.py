@@ -61,6 +61,10 @@ def load():
         lib.sinkhorn_attn_bwd_variant.argtypes = [i] + lib.sinkhorn_attn_bwd_varlen.argtypes
         lib.sinkhorn_attn_fwd_eps_schedule.restype = i
         lib.sinkhorn_attn_fwd_eps_schedule.argtypes = [vp] * 9 + [i] * 6 + [vp, vp, i, f, i, f, i, vp, sz, vp]
+        lib.sinkhorn_attn_fwd_dustbin_token.restype = i
+        lib.sinkhorn_attn_fwd_dustbin_token.argtypes = [vp] * 8 + [i] * 7 + [f, i, vp, sz, vp]
+        lib.sinkhorn_attn_bwd_dustbin_token.restype = i
+        lib.sinkhorn_attn_bwd_dustbin_token.argtypes = [vp] * 16 + [i] * 7 + [f, i, vp, sz, vp]
         lib.sinkhorn_attn_profile_enable.restype = i
         lib.sinkhorn_attn_profile_enable.argtypes = [i]
         lib.sinkhorn_attn_profile_read.restype = i
@@ -241,6 +245,59 @@ def sinkhorn_attn_base_vjp(Q, K, UV, eta, W, T, eps=1.0, dustbin=False, dustbin_
     if rc != SKA_OK:
         raise SinkhornAttnError(rc)
     return dQ, dK
+
+
+def sinkhorn_attn_fwd_dustbin_token(Q, K, V, q_db, k_db, v_db, W, T, R=2, eps=1.0, O=None, UV=None,
+                                    workspace=None):
+    """Forward with a learned dustbin token per side: q_db, k_db, v_db [B,H,d] float32.
+    Returns (O [B,H,L,d], UV [B,H,2(R+1),L+1])."""
+    B, H, L, d = Q.shape
+    for n, x in (("Q", Q), ("K", K), ("V", V)):
+        _check(x, (B, H, L, d), Q.dtype, n)
+    for n, x in (("q_db", q_db), ("k_db", k_db), ("v_db", v_db)):
+        _check(x, (B, H, d), torch.float32, n)
+    O = torch.empty_like(Q) if O is None else O
+    if UV is None:
+        UV = torch.empty((B, H, 2 * (R + 1), L + 1), device=Q.device, dtype=torch.float32)
+    _check(O, (B, H, L, d), Q.dtype, "O")
+    _check(UV, (B, H, 2 * (R + 1), L + 1), torch.float32, "UV")
+    code = _dtype_code(Q)
+    if workspace is None:
+        workspace = torch.empty(sinkhorn_attn_workspace_bytes(B, H, L, d, W, T, R, True, code), device=Q.device,
+                                dtype=torch.uint8)
+    rc = load().sinkhorn_attn_fwd_dustbin_token(
+        Q.data_ptr(), K.data_ptr(), V.data_ptr(), q_db.data_ptr(), k_db.data_ptr(), v_db.data_ptr(), O.data_ptr(),
+        UV.data_ptr(), B, H, L, d, W, T, R, float(eps), code, workspace.data_ptr(),
+        workspace.numel() * workspace.element_size(), _stream_ptr())
+    if rc != SKA_OK:
+        raise SinkhornAttnError(rc)
+    return O, UV
+
+
+def sinkhorn_attn_bwd_dustbin_token(Q, K, V, q_db, k_db, v_db, O, dO, UV, W, T, R=2, eps=1.0, want_eta0=False,
+                                    workspace=None):
+    """Backward with learned dustbin tokens. Returns (dQ, dK, dV, dq_db, dk_db, dv_db[, eta0])."""
+    B, H, L, d = Q.shape
+    for n, x in (("Q", Q), ("K", K), ("V", V), ("O", O), ("dO", dO)):
+        _check(x, (B, H, L, d), Q.dtype, n)
+    for n, x in (("q_db", q_db), ("k_db", k_db), ("v_db", v_db)):
+        _check(x, (B, H, d), torch.float32, n)
+    _check(UV, (B, H, 2 * (R + 1), L + 1), torch.float32, "UV")
+    dQ, dK, dV = (torch.empty_like(Q) for _ in range(3))
+    dq, dk, dv = (torch.empty_like(q_db) for _ in range(3))
+    code = _dtype_code(Q)
+    if workspace is None:
+        workspace = torch.empty(sinkhorn_attn_workspace_bytes(B, H, L, d, W, T, R, True, code), device=Q.device,
+                                dtype=torch.uint8)
+    eta0 = torch.empty((B, H, L + 1), device=Q.device, dtype=torch.float32) if want_eta0 else None
+    rc = load().sinkhorn_attn_bwd_dustbin_token(
+        Q.data_ptr(), K.data_ptr(), V.data_ptr(), q_db.data_ptr(), k_db.data_ptr(), v_db.data_ptr(), O.data_ptr(),
+        dO.data_ptr(), UV.data_ptr(), dQ.data_ptr(), dK.data_ptr(), dV.data_ptr(), dq.data_ptr(), dk.data_ptr(),
+        dv.data_ptr(), eta0.data_ptr() if want_eta0 else None, B, H, L, d, W, T, R, float(eps), code,
+        workspace.data_ptr(), workspace.numel() * workspace.element_size(), _stream_ptr())
+    if rc != SKA_OK:
+        raise SinkhornAttnError(rc)
+    return (dQ, dK, dV, dq, dk, dv, eta0) if want_eta0 else (dQ, dK, dV, dq, dk, dv)
 
 
 def sinkhorn_attn_select_workspace_bytes(B, H, L, d, W, T, R_max, dustbin=False, dtype=SKA_BF16) -> int:

@@ -96,6 +96,9 @@ struct SweepArgs {
     float cs;         // 1 / (eps sqrt d)
     int dustbin;
     float sdb2;       // dustbin score * log2(e)
+    Vec spoke_own;    // learned dustbin token: score of the spoke (o, dustbin of the other side) per
+                      // owner index, natural units (null: the scalar score above)
+    const float *pay_db;  // APPLY with a learned token: payload row of the other side's dustbin [N][D]
     int nbp;          // workgroups per problem
     int nb_total;
     int rev;          // walk each XCD's share of the blocks backwards (alternates between launches)
@@ -630,7 +633,8 @@ __global__ __launch_bounds__(NTHREADS) void sweep_kernel(const SweepArgs a)
             float mn = fmaxf(mx[f], mo);
             float tot = sum[f] * fast_exp2(mx[f] - mn) + so * fast_exp2(mo - mn);
             if (a.dustbin) {   // spoke edge (o, dustbin): score sdb, other-side potential yt[L]
-                float xd = a.sdb2 + ytp[L] * LOG2E;
+                const float sp2 = a.spoke_own.p ? a.spoke_own.p[n * a.spoke_own.stride + min(o, L - 1)] * LOG2E : a.sdb2;
+                float xd = sp2 + ytp[L] * LOG2E;
                 float m3 = fmaxf(mn, xd);
                 tot = tot * fast_exp2(mn - m3) + fast_exp2(xd - m3);
                 mn = m3;
@@ -647,6 +651,9 @@ __global__ __launch_bounds__(NTHREADS) void sweep_kernel(const SweepArgs a)
             float fac = 0.f;
             if (o < Le) fac = fast_exp2((xsp[o] - mblk) * LOG2E);
             if constexpr (MODE == M_FINAL) fac *= a.cs;
+            float pdb = 0.f;   // plan entry of the spoke (o, dustbin) when the dustbin carries a payload
+            if constexpr (MODE == M_APPLY)
+                if (a.pay_db && o < L) pdb = __expf(a.spoke_own.p[n * a.spoke_own.stride + o] + xsp[o] + ytp[L]);
             T *orow = reinterpret_cast<T *>(a.out_mat) + moff + (long)o * D;
             const T *drow = a.dot_mat ? reinterpret_cast<const T *>(a.dot_mat) + moff + (long)o * D : nullptr;
             float dot = 0.f;
@@ -657,6 +664,13 @@ __global__ __launch_bounds__(NTHREADS) void sweep_kernel(const SweepArgs a)
                     const int dv = 32 * j + 8 * q + 4 * h;
                     float v0 = outm[f][j][4 * q + 0] * fac, v1 = outm[f][j][4 * q + 1] * fac;
                     float v2 = outm[f][j][4 * q + 2] * fac, v3 = outm[f][j][4 * q + 3] * fac;
+                    if constexpr (MODE == M_APPLY) {
+                        if (a.pay_db) {
+                            const float4 pv = *reinterpret_cast<const float4 *>(a.pay_db + (long)n * D + dv);
+                            v0 = fmaf(pdb, pv.x, v0); v1 = fmaf(pdb, pv.y, v1);
+                            v2 = fmaf(pdb, pv.z, v2); v3 = fmaf(pdb, pv.w, v3);
+                        }
+                    }
                     if (o >= Le) v0 = v1 = v2 = v3 = 0.f;   // rows beyond the valid length are written as zeros
                     if (o < L) {
                         if constexpr (MODE == M_FINAL) {
@@ -922,7 +936,8 @@ __global__ __launch_bounds__(NTHREADS) void vsweep_kernel(const SweepArgs a)
         const int o = o_frag[f] + c;
         float tot = sum[f] + __shfl_xor(sum[f], 32);
         if (a.dustbin) {   // spoke edge (o, dustbin element of the other side)
-            float ed = fast_exp2(a.sdb2 + ytp[L] * LOG2E + m2);
+            const float sp2 = a.spoke_own.p ? a.spoke_own.p[n * a.spoke_own.stride + min(o, L - 1)] * LOG2E : a.sdb2;
+            float ed = fast_exp2(sp2 + ytp[L] * LOG2E + m2);
             tot += (MODE == M_MATVEC) ? ed * wp[L] : ed;
         }
         if (h == 0 && o < L) {
@@ -1223,6 +1238,9 @@ __global__ __launch_bounds__(NTHREADS) void msweep_kernel(const SweepArgs a)
         const int oc = min(o, L - 1);
         float fac = fast_exp2((xsp[min(o, Le - 1)] - mblk) * LOG2E);
         if constexpr (MODE == M_FINAL) fac *= a.cs;
+        float pdb = 0.f;   // plan entry of the spoke (o, dustbin) when the dustbin carries a payload
+        if constexpr (MODE == M_APPLY)
+            if (a.pay_db) pdb = __expf(a.spoke_own.p[n * a.spoke_own.stride + oc] + xsp[oc] + ytp[L]);
         T *orow = reinterpret_cast<T *>(a.out_mat) + moff + (long)oc * D;
         const T *drow = a.dot_mat ? reinterpret_cast<const T *>(a.dot_mat) + moff + (long)oc * D : nullptr;
         float dot = 0.f;
@@ -1233,6 +1251,13 @@ __global__ __launch_bounds__(NTHREADS) void msweep_kernel(const SweepArgs a)
                 const int dv = 32 * j + 8 * q + 4 * h;
                 float v0 = outm[f][j][4 * q + 0] * fac, v1 = outm[f][j][4 * q + 1] * fac;
                 float v2 = outm[f][j][4 * q + 2] * fac, v3 = outm[f][j][4 * q + 3] * fac;
+                if constexpr (MODE == M_APPLY) {
+                    if (a.pay_db) {
+                        const float4 pv = *reinterpret_cast<const float4 *>(a.pay_db + (long)n * D + dv);
+                        v0 = fmaf(pdb, pv.x, v0); v1 = fmaf(pdb, pv.y, v1);
+                        v2 = fmaf(pdb, pv.z, v2); v3 = fmaf(pdb, pv.w, v3);
+                    }
+                }
                 if (o >= Le) v0 = v1 = v2 = v3 = 0.f;   // rows beyond the valid length are written as zeros
                 if (o < L) {
                     store4<T>(orow + dv, v0, v1, v2, v3);
@@ -1290,6 +1315,157 @@ __global__ void rowdot_kernel(const T *A, const T *Bm, float *g, long gstride, i
 #pragma unroll
     for (int m = LPR / 2; m >= 1; m >>= 1) acc += __shfl_xor(acc, m);
     if (sub == 0 && o < Lp) g[n * gstride + o] = acc;
+}
+
+// ---- learned dustbin token (Sec. "Single-Active-Dustbin Bridge"): the O(L d) work on the spokes
+// out[n][o] = scale <M[n][o], x[n]> for o < L, out[n][L] = scale <x[n], xc[n]> (the corner).
+// LPR lanes per row, 16 bytes each, like rowdot_kernel.
+template <typename T, int D>
+__global__ void spoke_scores_kernel(const T *M, const float *x, const float *xc, float *out, long ostride, int L,
+                                    float scale)
+{
+    constexpr int LPR = D * (int)sizeof(T) / 16, EPL = 16 / (int)sizeof(T);
+    const int n = blockIdx.y;
+    const long p = (long)blockIdx.x * blockDim.x + threadIdx.x;
+    const int o = (int)(p / LPR), sub = (int)(p % LPR);
+    float acc = 0.f;
+    if (o <= L) {
+        const float *xv = x + (long)n * D + sub * EPL;
+#pragma unroll
+        for (int k = 0; k < EPL; k += 4) {
+            float a4[4];
+            if (o < L) load4<T>(M + ((long)n * L + o) * D + sub * EPL + k, a4);
+            else { const float *c4 = xc + (long)n * D + sub * EPL + k; a4[0] = c4[0]; a4[1] = c4[1]; a4[2] = c4[2]; a4[3] = c4[3]; }
+            acc += a4[0] * xv[k] + a4[1] * xv[k + 1] + a4[2] * xv[k + 2] + a4[3] * xv[k + 3];
+        }
+    }
+#pragma unroll
+    for (int m = LPR / 2; m >= 1; m >>= 1) acc += __shfl_xor(acc, m);
+    if (sub == 0 && o <= L) out[n * ostride + o] = scale * acc;
+}
+
+// Weights of a weighted row sum, two kinds:
+//   plan : w_o = exp(spoke[o] + x[o] + yL)   (plan entries of the spokes (o, dustbin); yL = y[L])
+//   given: w_o = wv[o]
+// partial[n][chunk][dv] = sum over the chunk's rows o of w_o M[n][o][dv]; rows in chunks of WS_ROWS.
+constexpr int WS_ROWS = 1024;
+template <typename T, int D>
+__global__ __launch_bounds__(256) void wsum_kernel(const T *M, Vec wv, Vec spoke, Vec x, Vec y, float *partial, int L)
+{
+    constexpr int TPR = D / 4;            // threads per row, four columns each
+    constexpr int RPI = 256 / TPR;        // rows per iteration
+    __shared__ float red[256][4];
+    const int n = blockIdx.y, chunk = blockIdx.x, tid = threadIdx.x;
+    const int col = (tid % TPR) * 4, r0 = tid / TPR;
+    const int o_end = min(L, (chunk + 1) * WS_ROWS);
+    float yL = 0.f;
+    if (!wv.p) yL = y.p[n * y.stride + L];
+    float acc[4] = {0.f, 0.f, 0.f, 0.f};
+    for (int o = chunk * WS_ROWS + r0; o < o_end; o += RPI) {
+        const float w = wv.p ? wv.p[n * wv.stride + o]
+                             : __expf(spoke.p[n * spoke.stride + o] + x.p[n * x.stride + o] + yL);
+        float m4[4];
+        load4<T>(M + ((long)n * L + o) * D + col, m4);
+        acc[0] = fmaf(w, m4[0], acc[0]); acc[1] = fmaf(w, m4[1], acc[1]);
+        acc[2] = fmaf(w, m4[2], acc[2]); acc[3] = fmaf(w, m4[3], acc[3]);
+    }
+#pragma unroll
+    for (int k = 0; k < 4; ++k) red[tid][k] = acc[k];
+    __syncthreads();
+    if (tid < TPR) {
+        float t4[4] = {0.f, 0.f, 0.f, 0.f};
+        for (int r = 0; r < RPI; ++r)
+#pragma unroll
+            for (int k = 0; k < 4; ++k) t4[k] += red[r * TPR + tid][k];
+        float *dst = partial + ((long)n * gridDim.x + chunk) * D + col;
+        dst[0] = t4[0]; dst[1] = t4[1]; dst[2] = t4[2]; dst[3] = t4[3];
+    }
+}
+// out[n][dv] = scale (sum_chunk partial[n][chunk][dv] + wc[n] xc[n][dv]); if dotv is given also
+// dot_out[n] = <dotv[n], out[n]>.  wc_at: index of the corner weight in wc (null: no corner).
+template <int D>
+__global__ void wsum_final_kernel(const float *partial, int nchunk, Vec wc, int wc_at, const float *xc, float scale,
+                                  float *out, const float *dotv, VecOut dot_out, int dot_at)
+{
+    const int n = blockIdx.x, dv = threadIdx.x;   // D threads
+    float acc = 0.f;
+    for (int c = 0; c < nchunk; ++c) acc += partial[((long)n * nchunk + c) * D + dv];
+    if (wc.p) acc = fmaf(wc.p[n * wc.stride + wc_at], xc[(long)n * D + dv], acc);
+    acc *= scale;
+    out[(long)n * D + dv] = acc;
+    if (dotv) {
+        __shared__ float red[D];
+        red[dv] = acc * dotv[(long)n * D + dv];
+        __syncthreads();
+        if (dv == 0) {
+            float t = 0.f;
+            for (int k = 0; k < D; ++k) t += red[k];
+            dot_out.p[n * dot_out.stride + dot_at] = t;
+        }
+    }
+}
+
+// Score cotangent on the spokes (Prop. 2 on the augmented support), one-reference form:
+//   sbr[i] = P_RR(i, d_k) (<dO_i, v_db> - sum_k rowp_k[i] colp_k[L])        i < L
+//   sbc[j] = P_RR(d_q, j) (            - sum_k rowp_k[L] colp_k[j])          j < L
+//   sbr[L] = sbc[L] = P_RR(d_q, d_k) (- sum_k rowp_k[L] colp_k[L])
+// with P_RR(i, d_k) = exp(SQ[i] + u_R[i] + v_R[L]), P_RR(d_q, j) = exp(SK[j] + u_R[L] + v_R[j]).
+template <typename T, int D>
+__global__ void spoke_sbar_kernel(const T *G, const float *vdb, Vec uR, Vec vR, Vec SQ, Vec SK, const float4 *rowp,
+                                  const float4 *colp, int nq, long ldp, float *sbr, float *sbc, long ostride, int L)
+{
+    constexpr int LPR = D * (int)sizeof(T) / 16, EPL = 16 / (int)sizeof(T);
+    const int n = blockIdx.y;
+    const long p = (long)blockIdx.x * blockDim.x + threadIdx.x;
+    const int o = (int)(p / LPR), sub = (int)(p % LPR);
+    float z = 0.f;
+    if (o < L) {
+        const float *xv = vdb + (long)n * D + sub * EPL;
+#pragma unroll
+        for (int k = 0; k < EPL; k += 4) {
+            float a4[4];
+            load4<T>(G + ((long)n * L + o) * D + sub * EPL + k, a4);
+            z += a4[0] * xv[k] + a4[1] * xv[k + 1] + a4[2] * xv[k + 2] + a4[3] * xv[k + 3];
+        }
+    }
+#pragma unroll
+    for (int m = LPR / 2; m >= 1; m >>= 1) z += __shfl_xor(z, m);
+    if (sub != 0 || o > L) return;
+    const float4 *ro = rowp + ((long)n * ldp + o) * nq, *co = colp + ((long)n * ldp + o) * nq;
+    const float4 *rL = rowp + ((long)n * ldp + L) * nq, *cL = colp + ((long)n * ldp + L) * nq;
+    float mr = 0.f, mc = 0.f;   // sum_k rowp_k[o] colp_k[L], sum_k rowp_k[L] colp_k[o]
+    for (int g = 0; g < nq; ++g) {
+        const float4 a = ro[g], b = cL[g], c = rL[g], d = co[g];
+        mr += a.x * b.x + a.y * b.y + a.z * b.z + a.w * b.w;
+        mc += c.x * d.x + c.y * d.y + c.z * d.z + c.w * d.w;
+    }
+    const float uRo = uR.p[n * uR.stride + o], vRo = vR.p[n * vR.stride + o];
+    const float uRL = uR.p[n * uR.stride + L], vRL = vR.p[n * vR.stride + L];
+    if (o < L) {
+        sbr[n * ostride + o] = __expf(SQ.p[n * SQ.stride + o] + uRo + vRL) * (z - mr);
+        sbc[n * ostride + o] = -__expf(SK.p[n * SK.stride + o] + uRL + vRo) * mc;
+    } else {
+        const float c = -__expf(SQ.p[n * SQ.stride + L] + uRL + vRL) * mr;
+        sbr[n * ostride + L] = c;
+        sbc[n * ostride + L] = c;
+    }
+}
+
+// M[n][o][:] += scale w[n][o] x[n][:] for o < L (the spoke part of dQ / dK), storage type T
+template <typename T, int D>
+__global__ void spoke_axpy_kernel(T *M, Vec w, const float *x, float scale, int L)
+{
+    constexpr int TPR = D / 4;
+    const int n = blockIdx.y;
+    const long p = (long)blockIdx.x * blockDim.x + threadIdx.x;
+    const int o = (int)(p / TPR), col = (int)(p % TPR) * 4;
+    if (o >= L) return;
+    const float f = scale * w.p[n * w.stride + o];
+    const float *xv = x + (long)n * D + col;
+    T *dst = M + ((long)n * L + o) * D + col;
+    float m4[4];
+    load4<T>(dst, m4);
+    store4<T>(dst, fmaf(f, xv[0], m4[0]), fmaf(f, xv[1], m4[1]), fmaf(f, xv[2], m4[2]), fmaf(f, xv[3], m4[3]));
 }
 
 // p[n][j] *= f for j < per (the base potentials between two stages of a continuation schedule)
@@ -1373,8 +1549,11 @@ __device__ __forceinline__ void pack_cols(const float (&x)[4], __bf16 *A, __bf16
 // pairs, row side (l_t, 1, l_t, ubar_t), column side (m_t, vbar_t, m_{t-1}, 1) with
 // l_t = (u_t - u_R) log2 e, m_t = (v_t - v_R) log2 e; nq = R groups.
 __global__ void packs_kernel(const float *UV, int Lp, int R, const float *vecs, long nldw, long wstride,
-                             float *rowp, float *colp, int nq, __bf16 *aug, long ldp, long nldp, int direct)
+                             float *rowp, float *colp, int nq, __bf16 *aug, long ldp, long nldp, int direct,
+                             int both)
 {
+    // both != 0: the float groups are written next to the bf16 columns (the spokes of a learned
+    // dustbin token read them)
     const int n = blockIdx.y;
     const int i = blockIdx.x * blockDim.x + threadIdx.x;
     if (i >= Lp) return;
@@ -1393,19 +1572,21 @@ __global__ void packs_kernel(const float *UV, int Lp, int R, const float *vecs, 
             const float mp = (uv[(2 * t - 1) * Lp + i] - vR) * LOG2E;
             rp[4 * q] = lt; rp[4 * q + 1] = 1.f; rp[4 * q + 2] = lt; rp[4 * q + 3] = ub;
             cp[4 * q] = mt; cp[4 * q + 1] = vb;  cp[4 * q + 2] = mp; cp[4 * q + 3] = 1.f;
-        } else if (!aug) {
+            continue;
+        }
+        if (!aug || both) {
             rp[2 * q] = at;          cp[2 * q] = bt * vb;
             rp[2 * q + 1] = at * ub; cp[2 * q + 1] = bp;
-        } else if (q < 2) {
+        }
+        if (aug && q < 2) {
             if (q == 0) { r4[0] = at; c4[0] = bt * vb; r4[1] = at * ub; c4[1] = bp; }
             else { r4[2] = at; c4[2] = bt * vb; r4[3] = at * ub; c4[3] = bp; }
         }
     }
-    if (direct) {
-        // (R groups, all written)
-    } else if (!aug) {
+    if (direct) return;   // (R groups, all written)
+    if (!aug || both)
         for (int k = 2 * R; k < 4 * nq; ++k) { rp[k] = 0.f; cp[k] = 0.f; }   // pad the last group
-    } else {
+    if (aug) {
         __align__(16) __bf16 A[16], B[16];
         const long e = (n * ldp + i) * 16;
         pack_cols(r4, A, B);
@@ -1424,16 +1605,19 @@ __global__ void packs_kernel(const float *UV, int Lp, int R, const float *vecs, 
 }
 
 // Dustbin element of a sweep result: the extra row (column) is joined to every
-// index 0..L of the other side by an edge of score sdb.
-//   w == null: out[L] = -log sum_{t<=L} exp(sdb + y_t)
-//   else     : out[L] = pre - exp(x[L]) sum_{t<=L} exp(sdb + y_t) w_t   (pre = 0)
-__global__ __launch_bounds__(1024) void dustbin_kernel(Vec y, Vec w, Vec x, VecOut out, int L, float sdb)
+// index 0..L of the other side by an edge of score s_t (the scalar sdb, or spoke[t] when
+// the dustbin is a learned token).
+//   w == null: out[L] = -log sum_{t<=L} exp(s_t + y_t)
+//   else     : out[L] = pre - exp(x[L]) sum_{t<=L} exp(s_t + y_t) w_t   (pre = 0)
+__global__ __launch_bounds__(1024) void dustbin_kernel(Vec y, Vec w, Vec x, VecOut out, int L, float sdb, Vec spoke)
 {
     __shared__ float sm[32], ss[32];
     const int n = blockIdx.x, tid = threadIdx.x, lane = tid & 63, wv = tid >> 6;
     const float *yp = y.p + n * y.stride;
+    const float *sp = spoke.p ? spoke.p + n * spoke.stride : nullptr;
+    if (sp) sdb = 0.f;
     float m = -INFINITY;
-    for (int t = tid; t <= L; t += blockDim.x) m = fmaxf(m, yp[t]);
+    for (int t = tid; t <= L; t += blockDim.x) m = fmaxf(m, yp[t] + (sp ? sp[t] : 0.f));
     for (int s = 32; s >= 1; s >>= 1) m = fmaxf(m, __shfl_xor(m, s));
     if (lane == 0) sm[wv] = m;
     __syncthreads();
@@ -1441,7 +1625,7 @@ __global__ __launch_bounds__(1024) void dustbin_kernel(Vec y, Vec w, Vec x, VecO
     for (int i = 1; i < (int)(blockDim.x >> 6); ++i) m = fmaxf(m, sm[i]);
     float acc = 0.f;
     for (int t = tid; t <= L; t += blockDim.x) {
-        float e = __expf(yp[t] - m);
+        float e = __expf(yp[t] + (sp ? sp[t] : 0.f) - m);
         acc += w.p ? e * w.p[n * w.stride + t] : e;
     }
     for (int s = 32; s >= 1; s >>= 1) acc += __shfl_xor(acc, s);
@@ -1464,6 +1648,9 @@ struct Problem {
     const float *log_a = nullptr, *log_b = nullptr;   // [N][Lp] logs of the marginal targets, or null
     const int *len_q = nullptr, *len_k = nullptr;     // [B] valid lengths of the two sequences, or null
     int variant = 0;                                  // backward: SKA_BWD_* (comparators of the final sweeps)
+    const float *q_db = nullptr, *k_db = nullptr, *v_db = nullptr;   // learned dustbin tokens [N][d] fp32, or null
+    float *dq_db = nullptr, *dk_db = nullptr, *dv_db = nullptr;      //   and their gradients (backward)
+    bool token() const { return q_db != nullptr; }
     int n_stages = 0;                                 // forward: continuation schedule of the base solve
     const float *eps_stage = nullptr;                 //   (host arrays; 0 stages: T steps at eps)
     const int *T_stage = nullptr;
@@ -1487,7 +1674,31 @@ size_t ws_vec_bytes(const Problem &p)
     // (2R + 3) / 4 of them, the direct comparator all), four packs of 16 bf16 columns
     return (size_t)p.N() * p.ldw() * (ws_vecs(p.R) * sizeof(float) + 2 * p.R * sizeof(float4) + 4 * 32);
 }
-size_t ws_bytes(const Problem &p) { return ws_vec_bytes(p) + ws_qs_bytes(p); }
+// dustbin: spoke score vectors SQ, SK and spoke cotangents sbr, sbc (stride ldw), and the partial
+// sums of the weighted row sums (learned tokens only, but sized by the flag alone)
+inline int ws_chunks(const Problem &p) { return (p.L + WS_ROWS - 1) / WS_ROWS; }
+size_t ws_tok_bytes(const Problem &p)
+{
+    return p.dustbin ? ((size_t)4 * p.N() * p.ldw() + (size_t)p.N() * ws_chunks(p) * p.d) * sizeof(float) : 0;
+}
+size_t ws_bytes(const Problem &p) { return ws_vec_bytes(p) + ws_qs_bytes(p) + ws_tok_bytes(p); }
+inline float *ws_tok(const Problem &p, void *ws)
+{
+    return reinterpret_cast<float *>(reinterpret_cast<unsigned char *>(ws) + ws_vec_bytes(p) + ws_qs_bytes(p));
+}
+// spoke scores of the learned tokens: SQ[i] = c q_i.k_db, SK[j] = c q_db.k_j, SQ[L] = SK[L] = c q_db.k_db
+template <typename T, int D>
+int spoke_scores(const Problem &p, const void *Qin, const void *K, float *SQ, float *SK, hipStream_t st)
+{
+    constexpr int LPR = D * (int)sizeof(T) / 16;
+    const float cs = 1.f / (p.eps * sqrtf((float)p.d));
+    const dim3 grid((unsigned)(((long)(p.L + 1) * LPR + 255) / 256), p.N());
+    hipLaunchKernelGGL((spoke_scores_kernel<T, D>), grid, dim3(256), 0, st, reinterpret_cast<const T *>(Qin), p.k_db,
+                       p.q_db, SQ, p.ldw(), p.L, cs);
+    hipLaunchKernelGGL((spoke_scores_kernel<T, D>), grid, dim3(256), 0, st, reinterpret_cast<const T *>(K), p.q_db,
+                       p.k_db, SK, p.ldw(), p.L, cs);
+    return hipGetLastError() == hipSuccess ? SKA_OK : SKA_EHIP;
+}
 
 template <typename T>
 int make_scores_operand(const Problem &p, float eps, const void *Q, void *ws_qs, const void **Qs, float *c2,
@@ -1516,6 +1727,7 @@ int check_common(const Problem &p)
     if (p.L > (1 << 24)) return SKA_EUNSUPPORTED;   // 32-bit byte offsets inside one [L][d] matrix
     if ((p.log_a || p.log_b) && p.dustbin) return SKA_EUNSUPPORTED;   // the dustbin's targets are all one
     if ((p.len_q || p.len_k) && p.dustbin) return SKA_EUNSUPPORTED;   // the dustbin sits at index L
+    if (p.token() && (!p.dustbin || p.n_stages || p.variant != SKA_BWD_ONE_REFERENCE)) return SKA_EUNSUPPORTED;
     if (p.R < 1 || p.R > MAXR) return SKA_EUNSUPPORTED;
     if (p.d != 32 && p.d != 64 && p.d != 128) return SKA_EUNSUPPORTED;
     if (p.dtype != SKA_F32 && p.dtype != SKA_BF16) return SKA_EUNSUPPORTED;
@@ -1673,10 +1885,19 @@ int fwd_impl(const Problem &p, const void *Qin, const void *K, const void *V, vo
     PhaseTimer *pt_run = nullptr;
     alignas(PhaseTimer) unsigned char pt_run_mem[sizeof(PhaseTimer)];
     // half-step: out slot <- -LSE over the band of (S + yt); prev slot only stabilises
+    // learned dustbin tokens: spoke score vectors instead of the scalar score
+    Vec SQ{nullptr, 0}, SK{nullptr, 0};
+    if (p.token()) {
+        float *tok = ws_tok(p, ws);
+        SQ = Vec{tok, p.ldw()};
+        SK = Vec{tok + (long)N * p.ldw(), p.ldw()};
+        SKA_TRY((spoke_scores<T, D>(p, Qin, K, tok, tok + (long)N * p.ldw(), st)));
+    }
     float stage_c2 = c2, stage_sdb2 = base.sdb2;   // (a continuation stage has its own score scale)
     auto half = [&](bool row, int yslot, int prevslot, int outslot) -> int {
         SweepArgs a = base;
         a.c2 = stage_c2; a.sdb2 = stage_sdb2;
+        a.spoke_own = row ? SQ : SK;
         a.X = row ? Q : K; a.Y = row ? K : Q;
         a.yt = vec(yslot); a.xs = vec(prevslot); a.out_vec = vout(outslot);
         a.olog = Vec{row ? p.log_a : p.log_b, (long)Lp};
@@ -1689,7 +1910,7 @@ int fwd_impl(const Problem &p, const void *Qin, const void *K, const void *V, vo
         else pt_run->launched();
         if (p.dustbin) {
             hipLaunchKernelGGL(dustbin_kernel, dim3(N), dim3(1024), 0, st, vec(yslot), Vec{nullptr, 0},
-                               Vec{nullptr, 0}, vout(outslot), L, stage_sdb2 * LN2);
+                               Vec{nullptr, 0}, vout(outslot), L, stage_sdb2 * LN2, row ? SK : SQ);
             if (hipGetLastError() != hipSuccess) return SKA_EHIP;
         }
         if (first) {   // the run of identical scaling sweeps starts after the first launch
@@ -1736,6 +1957,7 @@ int fwd_impl(const Problem &p, const void *Qin, const void *K, const void *V, vo
     SweepArgs a = base;
     a.X = Q; a.Y = K; a.Pay = V; a.out_mat = O; a.xs = vec(2 * R); a.yt = vec(2 * R + 1);
     a.len_own = p.len_q; a.len_oth = p.len_k;
+    if (p.token()) { a.spoke_own = SQ; a.pay_db = p.v_db; }   // O_i += P(i, d_k) v_db
     a.rev = nlaunch & 1;
     pt_out.launched();
     return sweep<T, D>(M_APPLY, a, N, st);
@@ -1784,6 +2006,17 @@ int bwd_impl(const Problem &p, const void *Qin, const void *K, const void *V, co
     base.nh = p.H;
     const dim3 vgrid((Lp + 255) / 256, N);
     int nlaunch = 0;   // successive sweeps walk the blocks in opposite directions (L2 reuse)
+    // learned dustbin tokens: spoke scores, spoke cotangents, partial sums
+    Vec SQ{nullptr, 0}, SK{nullptr, 0};
+    float *tok = p.token() ? ws_tok(p, ws) : nullptr;
+    float *sbr = tok ? tok + 2 * nldp : nullptr, *sbc = tok ? tok + 3 * nldp : nullptr;
+    float *partial = tok ? tok + 4 * nldp : nullptr;
+    const int nchunk = ws_chunks(p);
+    if (p.token()) {
+        SQ = Vec{tok, ldw};
+        SK = Vec{tok + nldp, ldw};
+        SKA_TRY((spoke_scores<T, D>(p, Qin, K, tok, tok + nldp, st)));
+    }
 
     // g_u = <dO_i, O_i> (= (P22 . Z) 1); dustbin row has dO = 0
     PhaseTimer pt_gu(SKA_PH_ROWDOT, st);
@@ -1797,7 +2030,14 @@ int bwd_impl(const Problem &p, const void *Qin, const void *K, const void *V, co
                            reinterpret_cast<const T *>(G),
                            reinterpret_cast<const T *>(O), gu, ldw, L, Lp, p.len_q, p.H);
         if (hipGetLastError() != hipSuccess) return SKA_EHIP;
-        if (p.dustbin) {   // vbar_R at the dustbin column is 0 because V there is 0
+        if (p.token()) {
+            // dv_db = sum_i P_RR(i, d_k) dO_i and vbar_R at the dustbin column = <v_db, dv_db>
+            hipLaunchKernelGGL((wsum_kernel<T, D>), dim3(nchunk, N), dim3(256), 0, st, reinterpret_cast<const T *>(G),
+                               Vec{nullptr, 0}, SQ, uv(2 * R), uv(2 * R + 1), partial, L);
+            hipLaunchKernelGGL((wsum_final_kernel<D>), dim3(N), dim3(D), 0, st, partial, nchunk, Vec{nullptr, 0}, 0,
+                               nullptr, 1.f, p.dv_db, p.v_db, wo(vbar(R)), L);
+            if (hipGetLastError() != hipSuccess) return SKA_EHIP;
+        } else if (p.dustbin) {   // vbar_R at the dustbin column is 0 because V there is 0
             hipLaunchKernelGGL(fill_kernel, dim3((N + 255) / 256), dim3(256), 0, st, vbar(R) + L, 1L, ldw, N, 0.f);
             if (hipGetLastError() != hipSuccess) return SKA_EHIP;
         }
@@ -1823,10 +2063,12 @@ int bwd_impl(const Problem &p, const void *Qin, const void *K, const void *V, co
         a.xs = xs; a.yt = yt; a.w = wv(w); a.pre = Vec{pre, ldw}; a.out_vec = out;
         if (scaled) a.olog = Vec{row ? p.log_a : p.log_b, (long)Lp};
         a.len_own = row ? p.len_q : p.len_k; a.len_oth = row ? p.len_k : p.len_q;
+        a.spoke_own = row ? SQ : SK;
         a.rev = nlaunch++ & 1;
         SKA_TRY((sweep<T, D>(M_MATVEC, a, N, st)));
         if (p.dustbin) {
-            hipLaunchKernelGGL(dustbin_kernel, dim3(N), dim3(1024), 0, st, yt, wv(w), xs, out, L, p.sdb);
+            hipLaunchKernelGGL(dustbin_kernel, dim3(N), dim3(1024), 0, st, yt, wv(w), xs, out, L, p.sdb,
+                               row ? SK : SQ);
             if (hipGetLastError() != hipSuccess) return SKA_EHIP;
         }
         return SKA_OK;
@@ -1848,7 +2090,7 @@ int bwd_impl(const Problem &p, const void *Qin, const void *K, const void *V, co
     pt_final.launched(2 * ((nq + MAXNQ - 1) / MAXNQ));
     hipLaunchKernelGGL(packs_kernel, vgrid, dim3(256), 0, st, UV, Lp, R, wf, nldp, ldw,
                        reinterpret_cast<float *>(rowp), reinterpret_cast<float *>(colp), nq, AUG ? aug : nullptr,
-                       ldw, nldp, p.direct() ? 1 : 0);
+                       ldw, nldp, p.direct() ? 1 : 0, p.token() ? 1 : 0);
     if (hipGetLastError() != hipSuccess) return SKA_EHIP;
     // one-reference final sweeps; a sweep takes eight modifier terms, so a tail deeper than
     // R = 4 takes several that accumulate (Z only in the first)
@@ -1880,6 +2122,30 @@ int bwd_impl(const Problem &p, const void *Qin, const void *K, const void *V, co
             a.rev = nlaunch++ & 1;
             SKA_TRY((sweep<T, D>(final_mode, a, N, st)));
         }
+    }
+    if (p.token()) {
+        // the spokes' share (Prop. 2 on the augmented support): cotangents of the 2L + 1 spoke
+        // scores, then their chain rule to Q, K (rank-1 updates) and to the tokens (weighted sums)
+        constexpr int LPR2 = D * (int)sizeof(T) / 16;
+        const float cs = base.cs;
+        hipLaunchKernelGGL((spoke_sbar_kernel<T, D>), dim3((unsigned)(((long)Lp * LPR2 + 255) / 256), N), dim3(256), 0,
+                           st, reinterpret_cast<const T *>(G), p.v_db, uv(2 * R), uv(2 * R + 1), SQ, SK, rowp, colp, nq,
+                           ldw, sbr, sbc, ldw, L);
+        const dim3 agrid((unsigned)(((long)L * (D / 4) + 255) / 256), N);
+        hipLaunchKernelGGL((spoke_axpy_kernel<T, D>), agrid, dim3(256), 0, st, reinterpret_cast<T *>(dQ), wv(sbr),
+                           p.k_db, cs, L);
+        hipLaunchKernelGGL((spoke_axpy_kernel<T, D>), agrid, dim3(256), 0, st, reinterpret_cast<T *>(dK), wv(sbc),
+                           p.q_db, cs, L);
+        // dk_db = c (sum_i sbr_i q_i + sbr_L q_db), dq_db = c (sum_j sbc_j k_j + sbc_L k_db)
+        hipLaunchKernelGGL((wsum_kernel<T, D>), dim3(nchunk, N), dim3(256), 0, st, reinterpret_cast<const T *>(Qin),
+                           wv(sbr), Vec{nullptr, 0}, Vec{nullptr, 0}, Vec{nullptr, 0}, partial, L);
+        hipLaunchKernelGGL((wsum_final_kernel<D>), dim3(N), dim3(D), 0, st, partial, nchunk, wv(sbr), L, p.q_db, cs,
+                           p.dk_db, nullptr, VecOut{nullptr, 0}, 0);
+        hipLaunchKernelGGL((wsum_kernel<T, D>), dim3(nchunk, N), dim3(256), 0, st, reinterpret_cast<const T *>(K),
+                           wv(sbc), Vec{nullptr, 0}, Vec{nullptr, 0}, Vec{nullptr, 0}, partial, L);
+        hipLaunchKernelGGL((wsum_final_kernel<D>), dim3(N), dim3(D), 0, st, partial, nchunk, wv(sbc), L, p.k_db, cs,
+                           p.dq_db, nullptr, VecOut{nullptr, 0}, 0);
+        if (hipGetLastError() != hipSuccess) return SKA_EHIP;
     }
     return SKA_OK;
 }
@@ -1932,6 +2198,7 @@ static int fwd_call(const Problem &p, const void *Q, const void *K, const void *
     int rc = check_common(p);
     if (rc != SKA_OK) return rc;
     if (ws_qs_bytes(p) && (!workspace || workspace_bytes < ws_qs_bytes(p))) return SKA_EWORKSPACE;
+    if (p.token() && (!workspace || workspace_bytes < ws_bytes(p))) return SKA_EWORKSPACE;
     if (reinterpret_cast<uintptr_t>(workspace) & 15) return SKA_EINVAL;
     hipStream_t st = reinterpret_cast<hipStream_t>(stream);
 #define SKA_FWD(TT_, DD_) return fwd_impl<TT_, DD_>(p, Q, K, V, O, UV, workspace, st)
@@ -1993,6 +2260,10 @@ int sinkhorn_attn_fwd(const void *Q, const void *K, const void *V, void *O, floa
                                        dustbin_score, dtype, workspace, workspace_bytes, stream);
 }
 
+static int bwd_problem(const Problem &p, const void *Q, const void *K, const void *V, const void *O, const void *dO,
+                       const float *UV, void *dQ, void *dK, void *dV, float *eta0, void *workspace,
+                       size_t workspace_bytes, void *stream);
+
 static int bwd_call(int variant, const void *Q, const void *K, const void *V, const float *log_a,
                     const float *log_b, const int *len_q, const int *len_k, const void *O, const void *dO,
                     const float *UV, void *dQ, void *dK, void *dV, float *eta0, int B, int H, int L, int d, int W,
@@ -2000,6 +2271,41 @@ static int bwd_call(int variant, const void *Q, const void *K, const void *V, co
                     size_t workspace_bytes, void *stream)
 {
     Problem p{B, H, L, d, W, T, R, dustbin ? 1 : 0, dtype, eps, dustbin_score, log_a, log_b, len_q, len_k, variant};
+    return bwd_problem(p, Q, K, V, O, dO, UV, dQ, dK, dV, eta0, workspace, workspace_bytes, stream);
+}
+
+static bool aligned16(const void *x) { return (reinterpret_cast<uintptr_t>(x) & 15) == 0; }
+
+int sinkhorn_attn_fwd_dustbin_token(const void *Q, const void *K, const void *V, const float *q_db,
+                                    const float *k_db, const float *v_db, void *O, float *UV, int B, int H, int L,
+                                    int d, int W, int T, int R, float eps, int dtype, void *workspace,
+                                    size_t workspace_bytes, void *stream)
+{
+    if (!q_db || !k_db || !v_db || !aligned16(q_db) || !aligned16(k_db) || !aligned16(v_db)) return SKA_EINVAL;
+    Problem p{B, H, L, d, W, T, R, 1, dtype, eps, 0.f};
+    p.q_db = q_db; p.k_db = k_db; p.v_db = v_db;
+    return fwd_call(p, Q, K, V, O, UV, workspace, workspace_bytes, stream);
+}
+
+int sinkhorn_attn_bwd_dustbin_token(const void *Q, const void *K, const void *V, const float *q_db,
+                                    const float *k_db, const float *v_db, const void *O, const void *dO,
+                                    const float *UV, void *dQ, void *dK, void *dV, float *dq_db, float *dk_db,
+                                    float *dv_db, float *eta0, int B, int H, int L, int d, int W, int T, int R,
+                                    float eps, int dtype, void *workspace, size_t workspace_bytes, void *stream)
+{
+    if (!q_db || !k_db || !v_db || !dq_db || !dk_db || !dv_db) return SKA_EINVAL;
+    if (!aligned16(q_db) || !aligned16(k_db) || !aligned16(v_db)) return SKA_EINVAL;
+    Problem p{B, H, L, d, W, T, R, 1, dtype, eps, 0.f};
+    p.q_db = q_db; p.k_db = k_db; p.v_db = v_db;
+    p.dq_db = dq_db; p.dk_db = dk_db; p.dv_db = dv_db;
+    return bwd_problem(p, Q, K, V, O, dO, UV, dQ, dK, dV, eta0, workspace, workspace_bytes, stream);
+}
+
+static int bwd_problem(const Problem &p, const void *Q, const void *K, const void *V, const void *O, const void *dO,
+                       const float *UV, void *dQ, void *dK, void *dV, float *eta0, void *workspace,
+                       size_t workspace_bytes, void *stream)
+{
+    const int d = p.d, dtype = p.dtype;
     if (!Q || !K || !V || !O || !dO || !UV || !dQ || !dK || !dV) return SKA_EINVAL;
     int rc = check_common(p);
     if (rc != SKA_OK) return rc;

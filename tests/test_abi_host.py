@@ -21,8 +21,9 @@ def declared_symbols():
 def test_library_exports_every_declared_symbol():
     lib = binding.load()
     names = declared_symbols()
-    assert names == ["sinkhorn_attn_base_vjp", "sinkhorn_attn_bwd", "sinkhorn_attn_bwd_marginals", "sinkhorn_attn_bwd_variant", "sinkhorn_attn_bwd_varlen",
-                     "sinkhorn_attn_fwd", "sinkhorn_attn_fwd_eps_schedule", "sinkhorn_attn_fwd_marginals",
+    assert names == ["sinkhorn_attn_base_vjp", "sinkhorn_attn_bwd", "sinkhorn_attn_bwd_dustbin_token",
+                     "sinkhorn_attn_bwd_marginals", "sinkhorn_attn_bwd_variant", "sinkhorn_attn_bwd_varlen",
+                     "sinkhorn_attn_fwd", "sinkhorn_attn_fwd_dustbin_token", "sinkhorn_attn_fwd_eps_schedule", "sinkhorn_attn_fwd_marginals",
                      "sinkhorn_attn_fwd_varlen",
                      "sinkhorn_attn_profile_enable",
                      "sinkhorn_attn_profile_read", "sinkhorn_attn_profile_read_phases",
@@ -99,6 +100,11 @@ def test_argument_errors_are_reported_before_any_launch():
     assert sched([2.0, 1.0], [1, 1]) == binding.SKA_EINVAL                 # does not end at eps
     assert sched([2.0, 0.5], [1, -1]) == binding.SKA_EINVAL
     assert sched([], []) == binding.SKA_EINVAL
+    # learned dustbin tokens: missing or misaligned tokens, and the forward needs the full workspace
+    tok = lambda q: lib.sinkhorn_attn_fwd_dustbin_token(pp, pp, pp, q, pp, pp, pp, pp, 1, 1, 64, 32, 4, 2, 2, 1.0, 0,
+                                                        None, 0, None)
+    assert tok(nul) == binding.SKA_EINVAL and tok(ctypes.c_void_p((1 << 20) + 4)) == binding.SKA_EINVAL
+    assert tok(pp) == binding.SKA_EWORKSPACE
     assert _bwd(lib, ws=None, ws_bytes=0) == binding.SKA_EWORKSPACE
     assert _fwd(lib, dtype=1) == binding.SKA_EWORKSPACE          # bf16 forward needs its scratch
     need = binding.sinkhorn_attn_workspace_bytes(1, 1, 64, 32, 4, 2, dtype=0)

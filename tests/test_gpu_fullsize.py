@@ -139,3 +139,32 @@ def test_full_size_padded_lengths():
             assert e <= TOL[w.dtype], (n, e)
     # the left part is far from the ragged end: identical to an ordinary window of the full problem
     window_check(w, {n: got[n] for n in got}, (qr, kr, vr, gr), 0, 0, 0, 2048)
+
+
+def test_dustbin_config_with_learned_tokens():
+    """The dustbin configuration at its full size with a learned token per side instead of the
+    scalar score; the oracle checks one of the eight problems (tokens' gradients included)."""
+    import torch
+
+    import paper_2605_08123_amd as ska
+    w = CONFIGS["dustbin"]
+    print(f"\n[case] {w} with learned dustbin tokens", flush=True)
+    arrays = make_inputs(w)
+    rng = np.random.default_rng(5)
+    toks = [rng.standard_normal((w.B, w.H, w.d)).astype(np.float32) for _ in range(3)]
+    dev = torch.device("cuda:0")
+    Q, K, V, G = (torch.from_numpy(x).to(dev).to(torch.bfloat16) for x in arrays)
+    tq, tk, tv = (torch.from_numpy(x).to(dev) for x in toks)
+    O, UV = ska.sinkhorn_attn_fwd_dustbin_token(Q, K, V, tq, tk, tv, w.W, w.T, w.R, w.eps)
+    res = ska.sinkhorn_attn_bwd_dustbin_token(Q, K, V, tq, tk, tv, O, G, UV, w.W, w.T, w.R, w.eps)
+    torch.cuda.synchronize()
+    names = ("dQ", "dK", "dV", "dq_db", "dk_db", "dv_db")
+    got = dict(zip(names, (x.float().cpu().numpy().astype(np.float64) for x in res)))
+    got["O"] = O.float().cpu().numpy().astype(np.float64)
+    b, h = 1, 2
+    q, k, v, g = (x[b, h] for x in arrays)
+    ref = oracle.band_dustbin_token(q, k, v, g, toks[0][b, h], toks[1][b, h], toks[2][b, h], w.W, w.T, w.R, w.eps)
+    errs = {n: float(np.linalg.norm(got[n][b, h] - ref[n]) / np.linalg.norm(ref[n])) for n in got}
+    print(f"   ({b},{h}):", {n: f"{e:.2e}" for n, e in errs.items()}, flush=True)
+    for n, e in errs.items():
+        assert np.isfinite(got[n]).all() and e <= TOL[w.dtype], (n, e)

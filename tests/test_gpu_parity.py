@@ -328,6 +328,51 @@ def test_eps_schedule_in_the_base_solve(dtype, d, kind):
     assert torch.equal(O1, O0) and torch.equal(UV1, UV0)
 
 
+@pytest.mark.parametrize("dtype,d,R,L", [("f32", 32, 2, 300), ("bf16", 64, 2, 1500), ("bf16", 128, 2, 700),
+                                         ("f32", 64, 3, 2100), ("bf16", 32, 1, 333)])
+def test_learned_dustbin_tokens(dtype, d, R, L):
+    """Learned dustbin token per side (Sec. 'Single-Active-Dustbin Bridge') on the sparse-spoke
+    support: O, dQ, dK, dV and the gradients of the three tokens against the oracle's augmented
+    problem; zero tokens reproduce the scalar-score dustbin with score 0."""
+    import torch
+
+    import paper_2605_08123_amd as ska
+    w = small("token", L, d, 31, 5, dtype, eps=0.8, B=1, H=2, R=R, dustbin=True)
+    print(f"\n[case] {w} learned dustbin tokens", flush=True)
+    arrays = make_inputs(w, 23)
+    rng = np.random.default_rng(24)
+    toks = [rng.standard_normal((1, w.H, d)).astype(np.float32) for _ in range(3)]
+    dev = torch.device("cuda:0")
+    td = torch.float32 if dtype == "f32" else torch.bfloat16
+    Q, K, V, G = (torch.from_numpy(x).to(dev).to(td) for x in arrays)
+    tq, tk, tv = (torch.from_numpy(x).to(dev) for x in toks)
+    O, UV = ska.sinkhorn_attn_fwd_dustbin_token(Q, K, V, tq, tk, tv, w.W, w.T, R, w.eps)
+    res = ska.sinkhorn_attn_bwd_dustbin_token(Q, K, V, tq, tk, tv, O, G, UV, w.W, w.T, R, w.eps)
+    torch.cuda.synchronize()
+    names = ("dQ", "dK", "dV", "dq_db", "dk_db", "dv_db")
+    got = dict(zip(names, (x.float().cpu().numpy().astype(np.float64) for x in res)))
+    got["O"] = O.float().cpu().numpy().astype(np.float64)
+    worst = dict.fromkeys(got, 0.0)
+    for h in range(w.H):
+        q, k, v, g = (x[0, h] for x in arrays)
+        ref = oracle.band_dustbin_token(q, k, v, g, toks[0][0, h], toks[1][0, h], toks[2][0, h], w.W, w.T, R, w.eps)
+        for n in got:
+            worst[n] = max(worst[n], rel(got[n][0, h], ref[n]))
+        s_got = (UV[0, h, 2 * R] + UV[0, h, 2 * R + 1]).cpu().numpy().astype(np.float64)
+        assert np.abs(s_got - (ref["UV"][2 * R] + ref["UV"][2 * R + 1])).max() < (2e-4 if dtype == "f32" else 3e-2)
+    print("   rel-L2:", {n: f"{e:.2e}" for n, e in worst.items()}, flush=True)
+    for n, e in worst.items():
+        assert np.isfinite(got[n]).all() and e <= TOL[dtype], (n, e)
+    z = torch.zeros_like(tq)
+    Oz, UVz = ska.sinkhorn_attn_fwd_dustbin_token(Q, K, V, z, z, z, w.W, w.T, R, w.eps)
+    Os, UVs = ska.sinkhorn_attn_fwd(Q, K, V, w.W, w.T, R, w.eps, True, 0.0)
+    assert torch.equal(Oz, Os) and (UVz - UVs).abs().max().item() < 1e-5
+    gz = ska.sinkhorn_attn_bwd_dustbin_token(Q, K, V, z, z, z, Oz, G, UVz, w.W, w.T, R, w.eps)
+    gs = ska.sinkhorn_attn_bwd(Q, K, V, Os, G, UVs, w.W, w.T, R, w.eps, True, 0.0)
+    for a, b in zip(gz[:3], gs):
+        assert rel(a.float().cpu().numpy().astype(np.float64), b.float().cpu().numpy().astype(np.float64)) < 1e-5
+
+
 def _targets(w, seed):
     rng = np.random.default_rng(seed)
     a = rng.uniform(0.4, 1.8, (w.B, w.H, w.L))
