@@ -373,6 +373,38 @@ def test_learned_dustbin_tokens(dtype, d, R, L):
         assert rel(a.float().cpu().numpy().astype(np.float64), b.float().cpu().numpy().astype(np.float64)) < 1e-5
 
 
+def test_dense_widened_band_dustbin():
+    """The paper's own dustbin path: one learned token appended per side and a band wide enough
+    to cover everything (W~ = max(W, L)).  That is the plain operator on the augmented tensors;
+    the oracle is its support-generic core on the dense (L+1) x (L+1) support."""
+    import torch
+
+    import paper_2605_08123_amd as ska
+    L, d, T, R, eps = 200, 32, 6, 2, 0.9
+    w = small("widened", L + 1, d, L + 1, T, "f32", eps=eps, R=R)
+    print(f"\n[case] {w}: dense widened-band dustbin", flush=True)
+    arrays = make_inputs(w, 27)              # the last row of Q, K, V plays the learned token
+    arrays[3][:, :, L] = 0.0                 # the dustbin query's output is dropped
+    got, ref = None, None
+    dev = torch.device("cuda:0")
+    Q, K, V, G = (torch.from_numpy(x).to(dev) for x in arrays)
+    O, UV = ska.sinkhorn_attn_fwd(Q, K, V, w.W, T, R, eps)
+    dQ, dK, dV = ska.sinkhorn_attn_bwd(Q, K, V, O, G, UV, w.W, T, R, eps)
+    torch.cuda.synchronize()
+    q, k, v, g = (x[0, 0].astype(np.float64) for x in arrays)
+    n = L + 1
+    rptr = np.arange(n + 1, dtype=np.int64) * n
+    cols = np.tile(np.arange(n, dtype=np.int32), n)
+    S = ((q @ k.T) / (eps * np.sqrt(d))).reshape(-1)
+    r = oracle.core(rptr, cols, S, v, g, T, R)
+    cs = 1.0 / (eps * np.sqrt(d))
+    Sb = r["Sbar"].reshape(n, n)
+    for name, x, y in (("O", O, r["O"]), ("dQ", dQ, cs * Sb @ k), ("dK", dK, cs * Sb.T @ q), ("dV", dV, r["dV"])):
+        e = rel(x[0, 0].cpu().numpy().astype(np.float64), y)
+        print(f"   {name}: rel-L2 {e:.2e}", flush=True)
+        assert e <= TOL["f32"], (name, e)
+
+
 def _targets(w, seed):
     rng = np.random.default_rng(seed)
     a = rng.uniform(0.4, 1.8, (w.B, w.H, w.L))
