@@ -130,6 +130,38 @@ def band(Q, K, V, G, W, T, R, eps, dustbin=False, dustbin_score=0.0, v0_fixed=No
     return out
 
 
+def band_masked(Q, K, V, G, mask_q, mask_k, W, T, R, eps, log_a=None, log_b=None):
+    """Banded operator with inactive tokens (the masked half-steps of Eq. 1-2: the support is
+    {(i, j): |i - j| <= W, mask_q[i], mask_k[j]}).  Inactive tokens, and active ones left without
+    any partner, take no part: potential -inf (reported as such), zero output and gradients.
+    Q, K, V, G are [L, d]; returns O, dQ, dK, dV [L, d], U [(R+1), L], Vp [(R+1), L].  Support and
+    scores are built here for the support-generic core, which runs on the active tokens only."""
+    Q, K, V, G = _f64(Q), _f64(K), _f64(V), _f64(G)
+    L, d = Q.shape
+    mq, mk = np.asarray(mask_q, dtype=bool), np.asarray(mask_k, dtype=bool)
+    ii, jj = np.nonzero((np.abs(np.arange(L)[:, None] - np.arange(L)[None, :]) <= W) & mq[:, None] & mk[None, :])
+    rows_act, cols_act = np.unique(ii), np.unique(jj)         # tokens with at least one edge
+    rmap, cmap = np.full(L, -1), np.full(L, -1)
+    rmap[rows_act], cmap[cols_act] = np.arange(len(rows_act)), np.arange(len(cols_act))
+    r_, c_ = rmap[ii], cmap[jj].astype(np.int32)              # nonzero() is row-major: rows sorted
+    rptr = np.concatenate(([0], np.cumsum(np.bincount(r_, minlength=len(rows_act))))).astype(np.int64)
+    cs = 1.0 / (eps * np.sqrt(d))
+    S = cs * np.einsum("ek,ek->e", Q[ii], K[jj])
+    r = core(rptr, c_, S, V[cols_act], None if G is None else G[rows_act], T, R,
+             log_a=None if log_a is None else _f64(log_a)[rows_act],
+             log_b=None if log_b is None else _f64(log_b)[cols_act])
+    out = {"O": np.zeros((L, d)), "U": np.full((R + 1, L), -np.inf), "Vp": np.full((R + 1, L), -np.inf)}
+    out["O"][rows_act] = r["O"]
+    out["U"][:, rows_act], out["Vp"][:, cols_act] = r["U"], r["Vp"]
+    if G is not None:
+        dQ, dK, dV = np.zeros((L, d)), np.zeros((L, d)), np.zeros((L, d))
+        np.add.at(dQ, ii, cs * r["Sbar"][:, None] * K[jj])
+        np.add.at(dK, jj, cs * r["Sbar"][:, None] * Q[ii])
+        dV[cols_act] = r["dV"]
+        out.update(dQ=dQ, dK=dK, dV=dV)
+    return out
+
+
 def band_dustbin_token(Q, K, V, G, q_db, k_db, v_db, W, T, R, eps):
     """Single-active-dustbin bridge with a learned dustbin token per side (Sec. 'Single-Active-
     Dustbin Bridge'): the tensors are augmented by one row, Q~ = [Q; q_db], K~ = [K; k_db],

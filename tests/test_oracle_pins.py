@@ -355,6 +355,41 @@ def test_rectangular_band_matches_dense_brute_force(Lq, Lk, W):
         assert all(rel(out[k], sq[k]) < 1e-14 for k in ("O", "dQ", "dK", "dV"))
 
 
+# ---------------------------------------------------------------- inactive tokens
+def test_masked_tokens_match_dense_brute_force():
+    """Inactive tokens on either side: dense masked library logsumexp on the active rows and
+    columns + closed-form adjoint; a prefix mask is the rectangular operator; an all-true mask is
+    the plain one.  Row 7 is active but every key in its band is masked: it drops out too."""
+    rng = np.random.default_rng(55)
+    L, d, W, T, R, eps = 48, 4, 5, 4, 2, 0.8
+    Q, K, V, G = (rng.standard_normal((L, d)) for _ in range(4))
+    mq, mk = rng.random(L) > 0.25, rng.random(L) > 0.25
+    mk[2:13] = False
+    mq[7] = True
+    out = oracle.band_masked(Q, K, V, G, mq, mk, W, T, R, eps)
+    mask = dr.band_mask(L, W) & mq[:, None] & mk[None, :]
+    ra, ca = mask.any(1), mask.any(0)
+    assert not ra[7] and np.all(out["O"][7] == 0.0) and np.all(np.isneginf(out["U"][:, 7]))
+    S = dr.scores(Q, K, eps)
+    sub = np.ix_(ra, ca)
+    U, Vp = dr.half_steps(S[sub], mask[sub], T, R)
+    cf = dr.closed_form_adjoint(S[sub], mask[sub], U, Vp, V[ca], G[ra])
+    cs = 1.0 / (eps * np.sqrt(d))
+    assert rel(out["O"][ra], cf["O"]) < 1e-12 and np.all(out["O"][~ra] == 0.0)
+    assert rel(out["dV"][ca], cf["dV"]) < 1e-12 and np.all(out["dV"][~ca] == 0.0)
+    assert rel(out["dQ"][ra], cs * cf["Sbar"] @ K[ca]) < 1e-11 and np.all(out["dQ"][~ra] == 0.0)
+    assert rel(out["dK"][ca], cs * cf["Sbar"].T @ Q[ra]) < 1e-11 and np.all(out["dK"][~ca] == 0.0)
+    assert np.abs(out["U"][:, ra] - U).max() < 1e-12 and np.all(np.isneginf(out["Vp"][:, ~ca]))
+    # prefix masks = rectangle; no mask = the plain operator
+    pq, pk = np.arange(L) < 37, np.arange(L) < 29
+    pm = oracle.band_masked(Q, K, V, G, pq, pk, W, T, R, eps)
+    rc = oracle.band_rect(Q[:37], K[:29], V[:29], G[:37], W, T, R, eps)
+    assert rel(pm["O"][:37], rc["O"]) < 1e-13 and rel(pm["dK"][:29], rc["dK"]) < 1e-13
+    full = oracle.band_masked(Q, K, V, G, np.ones(L, bool), np.ones(L, bool), W, T, R, eps)
+    plain = oracle.band(Q, K, V, G, W, T, R, eps)
+    assert all(rel(full[k], plain[k]) < 1e-13 for k in ("O", "dQ", "dK", "dV"))
+
+
 # ---------------------------------------------------------------- learned dustbin tokens
 def test_dustbin_token_matches_dense_augmented_problem():
     """Learned dustbin tokens: the augmented (L+1) x (L+1) problem, dense, with a boolean mask
