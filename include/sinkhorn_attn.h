@@ -145,6 +145,24 @@ int sinkhorn_attn_bwd_varlen(const void *Q, const void *K, const void *V, const 
                              size_t workspace_bytes, void *stream);
 
 /*
+ * Forward with inactive tokens (the masked half-steps of Eq. 1-2 with a boolean activity per
+ * token on either side): the support is {(i, j): |i - j| <= W, mask_q[b][i], mask_k[b][j]}.
+ *   mask_q, mask_k: uint8 device arrays [B,L] (shared by the heads), nonzero = active; NULL = all
+ *   active.  An inactive token, and an active one whose band holds no active partner, takes no
+ *   part: its potentials in UV are -inf in every iterate, its rows of O, dQ, dK, dV are zeros.
+ *   The rows of Q, K, V, dO at inactive tokens must still hold finite numbers (they are
+ *   multiplied by zero plan entries), unlike the padding of the _varlen calls.
+ * There is no masked backward call: the -inf potentials in UV carry the masks, and every backward
+ * entry point (sinkhorn_attn_bwd, _bwd_marginals, sinkhorn_attn_base_vjp, ...) applied to this UV
+ * gives the masked operator's gradients.  Not combined with the dustbin: SKA_EUNSUPPORTED.
+ */
+int sinkhorn_attn_fwd_masked(const void *Q, const void *K, const void *V, const float *log_a,
+                             const float *log_b, const unsigned char *mask_q,
+                             const unsigned char *mask_k, void *O, float *UV, int B, int H, int L,
+                             int d, int W, int T, int R, float eps, int dtype, void *workspace,
+                             size_t workspace_bytes, void *stream);
+
+/*
  * The dustbin as a learned token per side (Sec. "Single-Active-Dustbin Bridge": Q, K, V are
  * augmented by one active token, Q~ = [Q; q_db], K~ = [K; k_db], V~ = [V; v_db], and the same
  * unit-target operator runs on the augmented problem), on the sparse-spoke support

@@ -65,6 +65,8 @@ def load():
         lib.sinkhorn_attn_fwd_dustbin_token.argtypes = [vp] * 8 + [i] * 7 + [f, i, vp, sz, vp]
         lib.sinkhorn_attn_bwd_dustbin_token.restype = i
         lib.sinkhorn_attn_bwd_dustbin_token.argtypes = [vp] * 16 + [i] * 7 + [f, i, vp, sz, vp]
+        lib.sinkhorn_attn_fwd_masked.restype = i
+        lib.sinkhorn_attn_fwd_masked.argtypes = [vp] * 9 + [i] * 7 + [f, i, vp, sz, vp]
         lib.sinkhorn_attn_profile_enable.restype = i
         lib.sinkhorn_attn_profile_enable.argtypes = [i]
         lib.sinkhorn_attn_profile_read.restype = i
@@ -167,6 +169,35 @@ def sinkhorn_attn_fwd_marginals(Q, K, V, log_a, log_b, W, T, R=2, eps=1.0, dustb
     """Forward with marginal targets: log_a, log_b [B,H,L] float32 CUDA tensors or None (unit)."""
     return sinkhorn_attn_fwd_varlen(Q, K, V, log_a, log_b, None, None, W, T, R, eps, dustbin, dustbin_score, O,
                                     UV, workspace)
+
+
+def sinkhorn_attn_fwd_masked(Q, K, V, mask_q, mask_k, W, T, R=2, eps=1.0, log_a=None, log_b=None, O=None, UV=None,
+                             workspace=None):
+    """Forward with inactive tokens: mask_q, mask_k uint8 CUDA tensors [B,L] (nonzero = active) or
+    None.  The backward calls take the returned UV as it is (inactive potentials are -inf)."""
+    B, H, L, d = Q.shape
+    for n, x in (("Q", Q), ("K", K), ("V", V)):
+        _check(x, (B, H, L, d), Q.dtype, n)
+    for n, x in (("mask_q", mask_q), ("mask_k", mask_k)):
+        if x is not None:
+            _check(x, (B, L), torch.uint8, n)
+    O = torch.empty_like(Q) if O is None else O
+    if UV is None:
+        UV = torch.empty((B, H, 2 * (R + 1), L), device=Q.device, dtype=torch.float32)
+    _check(O, (B, H, L, d), Q.dtype, "O")
+    _check(UV, (B, H, 2 * (R + 1), L), torch.float32, "UV")
+    code = _dtype_code(Q)
+    if workspace is None:
+        workspace = torch.empty(max(sinkhorn_attn_workspace_bytes(B, H, L, d, W, T, R, False, code), 16),
+                                device=Q.device, dtype=torch.uint8)
+    rc = load().sinkhorn_attn_fwd_masked(
+        Q.data_ptr(), K.data_ptr(), V.data_ptr(), _marg_ptr(log_a, (B, H, L), "log_a"),
+        _marg_ptr(log_b, (B, H, L), "log_b"), None if mask_q is None else mask_q.data_ptr(),
+        None if mask_k is None else mask_k.data_ptr(), O.data_ptr(), UV.data_ptr(), B, H, L, d, W, T, R, float(eps),
+        code, workspace.data_ptr(), workspace.numel() * workspace.element_size(), _stream_ptr())
+    if rc != SKA_OK:
+        raise SinkhornAttnError(rc)
+    return O, UV
 
 
 def sinkhorn_attn_fwd_eps_schedule(Q, K, V, W, eps_stage, T_stage, R=2, eps=1.0, dustbin=False,

@@ -431,7 +431,10 @@ __global__ __launch_bounds__(NTHREADS) void sweep_kernel(const SweepArgs a)
     const T *Xb = reinterpret_cast<const T *>(a.X) + moff;
     const T *Yb = reinterpret_cast<const T *>(a.Y) + moff;
     const float *ytp = a.yt.p + n * a.yt.stride;
-    const float *xsp = (MODE == M_LSE_FIRST) ? nullptr : a.xs.p + n * a.xs.stride;
+    // owner-side potential: stabiliser and factor of the plan; -inf marks an inactive token (a
+    // masked one, or one without any active partner), which stays inactive in every later
+    // iterate.  The first half-step has no previous iterate: there xs only carries the marks.
+    const float *xsp = a.xs.p ? a.xs.p + n * a.xs.stride : nullptr;
 
     // workgroup stabiliser: largest owner-side potential in this block
     float mblk = 0.f;
@@ -444,6 +447,7 @@ __global__ __launch_bounds__(NTHREADS) void sweep_kernel(const SweepArgs a)
         if (lane == 0) red[wave] = m;
         __syncthreads();
         mblk = fmaxf(fmaxf(red[0], red[1]), fmaxf(red[2], red[3]));
+        if (mblk == -INFINITY) mblk = 0.f;   // a block of inactive tokens only
     }
     const float m2 = mblk * LOG2E;
 
@@ -642,14 +646,22 @@ __global__ __launch_bounds__(NTHREADS) void sweep_kernel(const SweepArgs a)
             if (h == 0 && o < L) {
                 float r = 0.f;   // rows beyond the valid length
                 if (o < Le) {
-                    r = -LN2 * (mn + fast_log2(tot));
-                    if (a.olog.p) r += a.olog.p[n * a.olog.stride + o];
+                    if ((xsp && xsp[o] == -INFINITY) || !(mn > -INFINITY)) {
+                        r = -INFINITY;   // inactive token
+                    } else {
+                        r = -LN2 * (mn + fast_log2(tot));
+                        if (a.olog.p) r += a.olog.p[n * a.olog.stride + o];
+                    }
                 }
                 a.out_vec.p[n * a.out_vec.stride + o] = r;
             }
         } else {
             float fac = 0.f;
-            if (o < Le) fac = fast_exp2((xsp[o] - mblk) * LOG2E);
+            bool dead = true;   // beyond the valid length, or an inactive token: zeros
+            if (o < Le) {
+                fac = fast_exp2((xsp[o] - mblk) * LOG2E);
+                dead = xsp[o] == -INFINITY;
+            }
             if constexpr (MODE == M_FINAL) fac *= a.cs;
             float pdb = 0.f;   // plan entry of the spoke (o, dustbin) when the dustbin carries a payload
             if constexpr (MODE == M_APPLY)
@@ -671,7 +683,7 @@ __global__ __launch_bounds__(NTHREADS) void sweep_kernel(const SweepArgs a)
                             v2 = fmaf(pdb, pv.z, v2); v3 = fmaf(pdb, pv.w, v3);
                         }
                     }
-                    if (o >= Le) v0 = v1 = v2 = v3 = 0.f;   // rows beyond the valid length are written as zeros
+                    if (dead) v0 = v1 = v2 = v3 = 0.f;
                     if (o < L) {
                         if constexpr (MODE == M_FINAL) {
                             if (a.accum) {
@@ -682,7 +694,7 @@ __global__ __launch_bounds__(NTHREADS) void sweep_kernel(const SweepArgs a)
                         }
                         store4<T>(orow + dv, v0, v1, v2, v3);
                         if constexpr (MODE == M_APPLY) {
-                            if (drow && o < Le) {
+                            if (drow && !dead) {
                                 float dd[4];
                                 load4<T>(drow + dv, dd);
                                 dot += dd[0] * v0 + dd[1] * v1 + dd[2] * v2 + dd[3] * v3;
@@ -694,7 +706,7 @@ __global__ __launch_bounds__(NTHREADS) void sweep_kernel(const SweepArgs a)
                 if (a.dot_mat) {
                     dot += __shfl_xor(dot, 32);
                     if (h == 0 && o < L) {
-                        if (a.olog.p && o < Le) dot *= __expf(-a.olog.p[n * a.olog.stride + o]);
+                        if (a.olog.p && !dead) dot *= __expf(-a.olog.p[n * a.olog.stride + o]);
                         a.dot_out.p[n * a.dot_out.stride + o] = dot;
                     }
                 }
@@ -848,6 +860,7 @@ __global__ __launch_bounds__(NTHREADS) void vsweep_kernel(const SweepArgs a)
         if (lane == 0) red[wave] = m;
         __syncthreads();
         mblk = fmaxf(fmaxf(red[0], red[1]), fmaxf(red[2], red[3]));
+        if (mblk == -INFINITY) mblk = 0.f;   // a block of inactive tokens only
     }
     m2 = mblk * LOG2E;
 #pragma unroll
@@ -944,6 +957,8 @@ __global__ __launch_bounds__(NTHREADS) void vsweep_kernel(const SweepArgs a)
             float r;
             if (o >= Le) {
                 r = 0.f;   // rows beyond the valid length
+            } else if (xsp[o] == -INFINITY || (MODE == M_LSE && !(tot > 0.f))) {
+                r = (MODE == M_LSE) ? -INFINITY : 0.f;   // inactive token (stays so), or none of its partners is active
             } else if constexpr (MODE == M_LSE) {
                 r = mblk - LN2 * fast_log2(tot);
                 if (a.olog.p) r += a.olog.p[n * a.olog.stride + o];
@@ -1034,6 +1049,7 @@ __global__ __launch_bounds__(NTHREADS) void msweep_kernel(const SweepArgs a)
         if (lane == 0) red[wave] = m;
         __syncthreads();
         mblk = fmaxf(fmaxf(red[0], red[1]), fmaxf(red[2], red[3]));
+        if (mblk == -INFINITY) mblk = 0.f;   // a block of inactive tokens only
     }
     m2 = mblk * LOG2E;
 
@@ -1236,7 +1252,9 @@ __global__ __launch_bounds__(NTHREADS) void msweep_kernel(const SweepArgs a)
     for (int f = 0; f < FR; ++f) {
         const int o = o_w + 32 * f + c;
         const int oc = min(o, L - 1);
-        float fac = fast_exp2((xsp[min(o, Le - 1)] - mblk) * LOG2E);
+        const float xso = xsp[min(o, Le - 1)];
+        const bool dead = o >= Le || xso == -INFINITY;   // beyond the valid length, or an inactive token: zeros
+        float fac = fast_exp2((xso - mblk) * LOG2E);
         if constexpr (MODE == M_FINAL) fac *= a.cs;
         float pdb = 0.f;   // plan entry of the spoke (o, dustbin) when the dustbin carries a payload
         if constexpr (MODE == M_APPLY)
@@ -1258,11 +1276,11 @@ __global__ __launch_bounds__(NTHREADS) void msweep_kernel(const SweepArgs a)
                         v2 = fmaf(pdb, pv.z, v2); v3 = fmaf(pdb, pv.w, v3);
                     }
                 }
-                if (o >= Le) v0 = v1 = v2 = v3 = 0.f;   // rows beyond the valid length are written as zeros
+                if (dead) v0 = v1 = v2 = v3 = 0.f;
                 if (o < L) {
                     store4<T>(orow + dv, v0, v1, v2, v3);
                     if constexpr (MODE == M_APPLY) {
-                        if (drow && o < Le) {
+                        if (drow && !dead) {
                             float dd[4];
                             load4<T>(drow + dv, dd);
                             dot += dd[0] * v0 + dd[1] * v1 + dd[2] * v2 + dd[3] * v3;
@@ -1274,7 +1292,7 @@ __global__ __launch_bounds__(NTHREADS) void msweep_kernel(const SweepArgs a)
             if (a.dot_mat) {
                 dot += __shfl_xor(dot, 32);
                 if (h == 0 && o < L) {
-                    if (a.olog.p && o < Le) dot *= __expf(-a.olog.p[n * a.olog.stride + o]);
+                    if (a.olog.p && !dead) dot *= __expf(-a.olog.p[n * a.olog.stride + o]);
                     a.dot_out.p[n * a.dot_out.stride + o] = dot;
                 }
             }
@@ -1468,6 +1486,19 @@ __global__ void spoke_axpy_kernel(T *M, Vec w, const float *x, float scale, int 
     store4<T>(dst, fmaf(f, xv[0], m4[0]), fmaf(f, xv[1], m4[1]), fmaf(f, xv[2], m4[2]), fmaf(f, xv[3], m4[3]));
 }
 
+// Start of the base solve with inactive tokens: u0[i] = -inf where mask_q[b][i] == 0,
+// v0[j] = -inf where mask_k[b][j] == 0 (elsewhere they keep their zeros).  UV slots 0 and 1.
+__global__ void mask_fill_kernel(float *UV, long us, int Lp, int L, const unsigned char *mq, const unsigned char *mk,
+                                 int nh)
+{
+    const int n = blockIdx.y;
+    const int i = blockIdx.x * blockDim.x + threadIdx.x;
+    if (i >= L) return;
+    const long m = (long)(n / nh) * L + i;
+    if (mq && !mq[m]) UV[n * us + i] = -INFINITY;
+    if (mk && !mk[m]) UV[n * us + Lp + i] = -INFINITY;
+}
+
 // p[n][j] *= f for j < per (the base potentials between two stages of a continuation schedule)
 __global__ void scale_kernel(float *p, long per, long stride, int nprob, float f)
 {
@@ -1564,14 +1595,18 @@ __global__ void packs_kernel(const float *UV, int Lp, int R, const float *vecs, 
     float *rp = rowp + (n * ldp + i) * 4L * nq, *cp = colp + (n * ldp + i) * 4L * nq;
     for (int q = 0; q < R; ++q) {   // q = R - t
         const int t = R - q;
-        const float at = __expf(uv[(2 * t) * Lp + i] - uR), bt = __expf(uv[(2 * t + 1) * Lp + i] - vR);
-        const float bp = __expf(uv[(2 * t - 1) * Lp + i] - vR);
+        // an inactive token (potential -inf on its side) has all-zero modifiers
+        const bool rdead = uR == -INFINITY, cdead = vR == -INFINITY;
+        const float at = rdead ? 0.f : __expf(uv[(2 * t) * Lp + i] - uR);
+        const float bt = cdead ? 0.f : __expf(uv[(2 * t + 1) * Lp + i] - vR);
+        const float bp = cdead ? 0.f : __expf(uv[(2 * t - 1) * Lp + i] - vR);
         const float vb = vecs[(1 + 2 * q) * nldw + w], ub = vecs[(2 + 2 * q) * nldw + w];
         if (direct) {
-            const float lt = (uv[(2 * t) * Lp + i] - uR) * LOG2E, mt = (uv[(2 * t + 1) * Lp + i] - vR) * LOG2E;
-            const float mp = (uv[(2 * t - 1) * Lp + i] - vR) * LOG2E;
-            rp[4 * q] = lt; rp[4 * q + 1] = 1.f; rp[4 * q + 2] = lt; rp[4 * q + 3] = ub;
-            cp[4 * q] = mt; cp[4 * q + 1] = vb;  cp[4 * q + 2] = mp; cp[4 * q + 3] = 1.f;
+            const float lt = rdead ? 0.f : (uv[(2 * t) * Lp + i] - uR) * LOG2E;
+            const float mt = cdead ? 0.f : (uv[(2 * t + 1) * Lp + i] - vR) * LOG2E;
+            const float mp = cdead ? 0.f : (uv[(2 * t - 1) * Lp + i] - vR) * LOG2E;
+            rp[4 * q] = lt; rp[4 * q + 1] = rdead ? 0.f : 1.f; rp[4 * q + 2] = lt; rp[4 * q + 3] = ub;
+            cp[4 * q] = mt; cp[4 * q + 1] = vb;  cp[4 * q + 2] = mp; cp[4 * q + 3] = cdead ? 0.f : 1.f;
             continue;
         }
         if (!aug || both) {
@@ -1648,6 +1683,7 @@ struct Problem {
     const float *log_a = nullptr, *log_b = nullptr;   // [N][Lp] logs of the marginal targets, or null
     const int *len_q = nullptr, *len_k = nullptr;     // [B] valid lengths of the two sequences, or null
     int variant = 0;                                  // backward: SKA_BWD_* (comparators of the final sweeps)
+    const unsigned char *mask_q = nullptr, *mask_k = nullptr;        // [B][L] token activity (forward), or null
     const float *q_db = nullptr, *k_db = nullptr, *v_db = nullptr;   // learned dustbin tokens [N][d] fp32, or null
     float *dq_db = nullptr, *dk_db = nullptr, *dv_db = nullptr;      //   and their gradients (backward)
     bool token() const { return q_db != nullptr; }
@@ -1727,6 +1763,7 @@ int check_common(const Problem &p)
     if (p.L > (1 << 24)) return SKA_EUNSUPPORTED;   // 32-bit byte offsets inside one [L][d] matrix
     if ((p.log_a || p.log_b) && p.dustbin) return SKA_EUNSUPPORTED;   // the dustbin's targets are all one
     if ((p.len_q || p.len_k) && p.dustbin) return SKA_EUNSUPPORTED;   // the dustbin sits at index L
+    if ((p.mask_q || p.mask_k) && p.dustbin) return SKA_EUNSUPPORTED;
     if (p.token() && (!p.dustbin || p.n_stages || p.variant != SKA_BWD_ONE_REFERENCE)) return SKA_EUNSUPPORTED;
     if (p.R < 1 || p.R > MAXR) return SKA_EUNSUPPORTED;
     if (p.d != 32 && p.d != 64 && p.d != 128) return SKA_EUNSUPPORTED;
@@ -1877,6 +1914,11 @@ int fwd_impl(const Problem &p, const void *Qin, const void *K, const void *V, vo
     {
         long tot = 2L * Lp * N;
         hipLaunchKernelGGL(fill_kernel, dim3((tot + 255) / 256), dim3(256), 0, st, UV, 2L * Lp, us, N, 0.f);
+        if (hipGetLastError() != hipSuccess) return SKA_EHIP;
+    }
+    if (p.mask_q || p.mask_k) {   // inactive tokens start, and stay, at -inf
+        hipLaunchKernelGGL(mask_fill_kernel, dim3((L + 255) / 256, N), dim3(256), 0, st, UV, us, Lp, L, p.mask_q,
+                           p.mask_k, p.H);
         if (hipGetLastError() != hipSuccess) return SKA_EHIP;
     }
     bool first = true;
@@ -2221,6 +2263,16 @@ int sinkhorn_attn_fwd_varlen(const void *Q, const void *K, const void *V, const 
                              void *stream)
 {
     Problem p{B, H, L, d, W, T, R, dustbin ? 1 : 0, dtype, eps, dustbin_score, log_a, log_b, len_q, len_k};
+    return fwd_call(p, Q, K, V, O, UV, workspace, workspace_bytes, stream);
+}
+
+int sinkhorn_attn_fwd_masked(const void *Q, const void *K, const void *V, const float *log_a,
+                             const float *log_b, const unsigned char *mask_q, const unsigned char *mask_k,
+                             void *O, float *UV, int B, int H, int L, int d, int W, int T, int R, float eps,
+                             int dtype, void *workspace, size_t workspace_bytes, void *stream)
+{
+    Problem p{B, H, L, d, W, T, R, 0, dtype, eps, 0.f, log_a, log_b};
+    p.mask_q = mask_q; p.mask_k = mask_k;
     return fwd_call(p, Q, K, V, O, UV, workspace, workspace_bytes, stream);
 }
 

@@ -373,6 +373,64 @@ def test_learned_dustbin_tokens(dtype, d, R, L):
         assert rel(a.float().cpu().numpy().astype(np.float64), b.float().cpu().numpy().astype(np.float64)) < 1e-5
 
 
+@pytest.mark.parametrize("dtype,d,R,variant", [("f32", 32, 2, 0), ("bf16", 64, 2, 0), ("bf16", 128, 2, 0),
+                                               ("f32", 64, 3, 0), ("bf16", 64, 2, 1), ("bf16", 32, 1, 0)])
+def test_inactive_tokens(dtype, d, R, variant):
+    """Boolean activity per token on both sides (the masked half-steps of Eq. 1-2): random masks,
+    a run of masked keys wider than the band (so some active queries lose every partner), a
+    whole masked block, per batch item.  The ordinary backward runs on the forward's UV."""
+    import torch
+
+    import paper_2605_08123_amd as ska
+    w = small("masks", 900, d, 21, 5, dtype, eps=0.8, B=2, H=2, R=R)
+    print(f"\n[case] {w} inactive tokens (backward variant {variant})", flush=True)
+    arrays = make_inputs(w, 51)
+    rng = np.random.default_rng(52)
+    mq = (rng.random((w.B, w.L)) > 0.2)
+    mk = (rng.random((w.B, w.L)) > 0.2)
+    mk[0, 100:160] = False           # wider than 2W + 1: queries 121..138 lose every key
+    mq[0, 125] = True
+    mq[1, 256:540] = False           # more than a whole workgroup of inactive queries
+    mk[1, 300:500] = False
+    dev = torch.device("cuda:0")
+    td = torch.float32 if dtype == "f32" else torch.bfloat16
+    Q, K, V, G = (torch.from_numpy(x).to(dev).to(td) for x in arrays)
+    tmq, tmk = (torch.from_numpy(x.astype(np.uint8)).to(dev) for x in (mq, mk))
+    O, UV = ska.sinkhorn_attn_fwd_masked(Q, K, V, tmq, tmk, w.W, w.T, R, w.eps)
+    dQ, dK, dV, eta0 = ska.sinkhorn_attn_bwd_variant(variant, Q, K, V, None, None, None, None, O, G, UV, w.W, w.T, R,
+                                                     w.eps, want_eta0=True)
+    torch.cuda.synchronize()
+    got = {n: x.float().cpu().numpy().astype(np.float64) for n, x in dict(O=O, dQ=dQ, dK=dK, dV=dV).items()}
+    uv = UV.cpu().numpy().astype(np.float64)
+    assert np.isfinite(eta0.cpu().numpy()).all()
+    worst = dict.fromkeys(got, 0.0)
+    for b in range(w.B):
+        for h in range(w.H):
+            q, k, v, g = (x[b, h] for x in arrays)
+            ref = oracle.band_masked(q, k, v, g, mq[b], mk[b], w.W, w.T, R, w.eps)
+            dead_q, dead_k = np.isneginf(ref["U"][R]), np.isneginf(ref["Vp"][R])
+            assert dead_q[125] if b == 0 else dead_q[300]
+            for n in got:
+                assert np.isfinite(got[n][b, h]).all(), n
+                worst[n] = max(worst[n], rel(got[n][b, h], ref[n]))
+            assert np.all(got["O"][b, h][dead_q] == 0.0) and np.all(got["dQ"][b, h][dead_q] == 0.0)
+            assert np.all(got["dK"][b, h][dead_k] == 0.0) and np.all(got["dV"][b, h][dead_k] == 0.0)
+            for t in range(R + 1):
+                assert np.array_equal(np.isneginf(uv[b, h, 2 * t]), dead_q)
+                assert np.array_equal(np.isneginf(uv[b, h, 2 * t + 1]), dead_k)
+            tol_uv = 2e-4 if dtype == "f32" else 3e-2
+            assert np.abs(uv[b, h, 2 * R][~dead_q] - ref["U"][R][~dead_q]).max() < tol_uv
+            assert np.abs(uv[b, h, 2 * R + 1][~dead_k] - ref["Vp"][R][~dead_k]).max() < tol_uv
+    print("   worst rel-L2:", {n: f"{e:.2e}" for n, e in worst.items()}, flush=True)
+    for n, e in worst.items():
+        assert e <= TOL[dtype], (n, e)
+    if variant == 0 and dtype == "f32":   # all-active masks are the plain call, bit for bit
+        one = torch.ones_like(tmq)
+        O1, UV1 = ska.sinkhorn_attn_fwd_masked(Q, K, V, one, one, w.W, w.T, R, w.eps)
+        O0, UV0 = ska.sinkhorn_attn_fwd(Q, K, V, w.W, w.T, R, w.eps)
+        assert torch.equal(O1, O0) and torch.equal(UV1, UV0)
+
+
 def test_dense_widened_band_dustbin():
     """The paper's own dustbin path: one learned token appended per side and a band wide enough
     to cover everything (W~ = max(W, L)).  That is the plain operator on the augmented tensors;
