@@ -431,6 +431,47 @@ def test_inactive_tokens(dtype, d, R, variant):
         assert torch.equal(O1, O0) and torch.equal(UV1, UV0)
 
 
+def test_forward_backward_replay_from_a_hip_graph():
+    """The calls only launch kernels on the caller's stream (no allocation, no memset, no host
+    synchronisation), so a forward + backward pair can be captured into a HIP graph.  Three
+    replays, with eager work and synchronisations between them, each against the eager result."""
+    import torch
+
+    import paper_2605_08123_amd as ska
+    w = small("graph", 3000, 64, 40, 6, "bf16", eps=0.7, B=2, H=2)
+    print(f"\n[case] {w} graph replay", flush=True)
+    dev = torch.device("cuda:0")
+    Q, K, V, G = (torch.from_numpy(x).to(dev).to(torch.bfloat16) for x in make_inputs(w, 61))
+    O, dQ, dK, dV = (torch.empty_like(Q) for _ in range(4))
+    UV = torch.empty((w.B, w.H, 6, w.L), device=dev, dtype=torch.float32)
+    ws = torch.empty(ska.sinkhorn_attn_workspace_bytes(w.B, w.H, w.L, w.d, w.W, w.T, w.R, False, 1), device=dev,
+                     dtype=torch.uint8)
+
+    def run():
+        ska.sinkhorn_attn_fwd(Q, K, V, w.W, w.T, w.R, w.eps, O=O, UV=UV, workspace=ws)
+        ska.sinkhorn_attn_bwd(Q, K, V, O, G, UV, w.W, w.T, w.R, w.eps, workspace=ws, dQ=dQ, dK=dK, dV=dV)
+
+    run()
+    torch.cuda.synchronize()
+    want = [x.clone() for x in (O, UV, dQ, dK, dV)]
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(side):
+        run()                                   # warm-up on the capture stream
+    torch.cuda.current_stream().wait_stream(side)
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph, stream=side):
+        run()
+    for rep in range(3):
+        for x in (O, UV, dQ, dK, dV):
+            x.zero_()                           # eager work between replays
+        torch.cuda.synchronize()
+        graph.replay()
+        torch.cuda.synchronize()
+        for got, ref in zip((O, UV, dQ, dK, dV), want):
+            assert torch.equal(got, ref), rep
+
+
 def test_dense_widened_band_dustbin():
     """The paper's own dustbin path: one learned token appended per side and a band wide enough
     to cover everything (W~ = max(W, L)).  That is the plain operator on the augmented tensors;
