@@ -33,1648 +33,12 @@
 #include <type_traits>
 
 #include "sinkhorn_attn.h"
+#include "ska_common.h"
+#include "ska_small_kernels.h"
+#include "ska_sweep_generic.h"
+#include "ska_sweep_ring.h"
 
 namespace {
-
-typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8;
-typedef __attribute__((ext_vector_type(4))) __bf16 bf16x4;
-typedef __attribute__((ext_vector_type(16))) float f32x16;
-
-constexpr int NTHREADS = 256;
-constexpr int NWAVES = 4;
-constexpr int TT = 32;  // other-side rows per tile
-constexpr float LOG2E = 1.4426950408889634f;
-constexpr float LN2 = 0.6931471805599453f;
-
-constexpr int MAXR = 32;     // deepest differentiable tail (T = 0 with R = T' + R' is full
-                             // backpropagation through a T'-step base solve)
-constexpr int MAXNQ = 2;     // float4 groups of modifier terms one final sweep takes (8 terms);
-                             // deeper tails take several sweeps that accumulate
-enum Mode { M_LSE_FIRST = 0, M_LSE = 1, M_MATVEC = 2, M_APPLY = 3, M_FINAL = 4,
-            M_FINAL_DIRECT = 5 /* dispatch only: M_FINAL of the generic kernel with DIRECT = true */ };
-
-struct Vec {          // one fp32 vector per problem
-    const float *p;
-    long stride;      // elements between consecutive problems
-};
-struct VecOut {
-    float *p;
-    long stride;
-};
-
-struct SweepArgs {
-    const void *X;    // owner-side matrix      [N][L][D]
-    const void *Y;    // other-side matrix      [N][L][D]
-    const void *A;    // FINAL: owner-side factor of Z (dO for rows, V for columns)
-    const void *Bm;   // FINAL: other-side factor of Z
-    const void *Pay;  // APPLY: other-side payload (V for the output, dO for dV)
-    void *out_mat;    // APPLY / FINAL result   [N][L][D]
-    Vec yt;           // other-side potential (natural log units), length Lp
-    Vec xs;           // owner-side potential / previous iterate (stabiliser), length Lp
-    Vec w;            // MATVEC weights on the other side
-    Vec pre;          // MATVEC additive term on the owner side (may be null)
-    VecOut out_vec;   // LSE / MATVEC result
-    Vec olog;         // log of the owner side's marginal target (null: unit targets).  LSE adds it
-                      // to the result; MATVEC and the dot of APPLY divide their result by the target
-    const float4 *po; // FINAL: owner-side modifier pack   [N][ldp][pstride], first group of this sweep
-    const float4 *qt; // FINAL: other-side modifier pack   [N][ldp][pstride]
-    int nq;           // groups of four terms this sweep takes (1 or 2)
-    int pstride;      // groups per index in memory (2R terms in all)
-    int skipz;        // FINAL: leave Z out (second and later sweeps of a deep tail)
-    int refterm;      // direct FINAL: the first term of this sweep multiplies the reference plan itself
-    int accum;        // FINAL: add to the output instead of overwriting it
-    const void *poB;  // FINAL on the ring kernel: owner-side pack as 16 bf16 columns  [N][ldp][16]
-    const void *qtA;  // FINAL on the ring kernel: other-side pack as 16 bf16 columns  [N][ldp][16]
-    long ldp;
-    const void *dot_mat;  // APPLY: if set, dot_out_o = <dot_mat_o, out_o> (fp32 accumulators)
-    VecOut dot_out;
-    int L, W;
-    const int *len_own;   // valid owner-side length of each batch item (null: L), device memory [N / nh]
-    const int *len_oth;   // valid other-side length of each batch item (null: L)
-    int nh;               // problems per batch item (heads)
-    float c2;         // log2(e) / (eps sqrt d)
-    float cs;         // 1 / (eps sqrt d)
-    int dustbin;
-    float sdb2;       // dustbin score * log2(e)
-    Vec spoke_own;    // learned dustbin token: score of the spoke (o, dustbin of the other side) per
-                      // owner index, natural units (null: the scalar score above)
-    const float *pay_db;  // APPLY with a learned token: payload row of the other side's dustbin [N][D]
-    int nbp;          // workgroups per problem
-    int nb_total;
-    int rev;          // walk each XCD's share of the blocks backwards (alternates between launches)
-};
-
-// ------------------------------------------------------------------ element traits
-template <typename T> struct Elem;
-template <> struct Elem<float> {
-    static constexpr int BYTES = 4;
-};
-template <> struct Elem<__bf16> {
-    static constexpr int BYTES = 2;
-};
-
-__device__ __forceinline__ float fast_exp2(float x) { return __builtin_amdgcn_exp2f(x); }
-__device__ __forceinline__ float fast_log2(float x) { return __builtin_amdgcn_logf(x); }
-
-// Valid lengths of problem n (padded batches, sequences of different lengths): Lt other-side
-// indices exist, and Le owner indices have at least one band edge (o < Lo and o - W < Lt).
-// Owner rows in [Le, L) take no part and get zeros.  Uniform over the workgroup.
-struct Lens { int Lt, Le; };
-__device__ __forceinline__ Lens problem_lens(const SweepArgs &a, int n)
-{
-    int Lo = a.L, Lt = a.L;
-    if (a.len_own) Lo = min(max(a.len_own[n / a.nh], 0), a.L);
-    if (a.len_oth) Lt = min(max(a.len_oth[n / a.nh], 0), a.L);
-    return Lens{Lt, Lt > 0 ? min(Lo, Lt + a.W) : 0};
-}
-// A workgroup whose owner rows all lie beyond the valid length writes its zeros and leaves.
-template <typename T, int D, int BM>
-__device__ __forceinline__ void zero_block(const SweepArgs &a, int n, int o_blk, bool mat, bool vec)
-{
-    const int rows = min(BM, a.L - o_blk);
-    if (mat && !a.accum) {
-        uint4 *dst = reinterpret_cast<uint4 *>(reinterpret_cast<T *>(a.out_mat) + ((long)n * a.L + o_blk) * D);
-        const int n16 = rows * D * (int)sizeof(T) / 16;
-        for (int i = threadIdx.x; i < n16; i += NTHREADS) dst[i] = make_uint4(0, 0, 0, 0);
-    }
-    for (int i = threadIdx.x; i < rows; i += NTHREADS) {
-        if (vec) a.out_vec.p[n * a.out_vec.stride + o_blk + i] = 0.f;
-        if (mat && a.dot_mat) a.dot_out.p[n * a.dot_out.stride + o_blk + i] = 0.f;
-    }
-}
-
-__device__ __forceinline__ bf16x8 pack8(const float *e)
-{
-    bf16x8 r;
-#pragma unroll
-    for (int i = 0; i < 8; ++i) r[i] = (__bf16)e[i];
-    return r;
-}
-
-// LDS layouts -------------------------------------------------------------------
-// bf16 row-major tile [32][D]: 16-byte chunks XOR-swizzled so that the 32 lanes of
-// an A-fragment read (one chunk per lane, consecutive rows) spread over all banks.
-template <int D> __device__ __forceinline__ int bf16_chunk_off(int row, int chunk)
-{
-    constexpr int CH = D / 8;                       // chunks per row
-    constexpr int RPB = (CH >= 8) ? 1 : 8 / CH;     // rows per 128-byte line
-    constexpr int MASK = (CH >= 8) ? 7 : CH - 1;
-    return (row * CH + (chunk ^ ((row / RPB) & MASK))) * 16;
-}
-// bf16 transposed payload tile [D][32 + 4] (t contiguous, 72-byte rows)
-constexpr int PT_STRIDE = 72;
-// fp32 row-major tile [32][D + 4]
-template <int D> constexpr int f32_row_floats() { return D + 4; }
-
-template <typename T, int D> struct Tile {
-    static constexpr bool IS_BF16 = (Elem<T>::BYTES == 2);
-    static constexpr int RM_BYTES = IS_BF16 ? 32 * D * 2 : 32 * f32_row_floats<D>() * 4;
-    static constexpr int PT_BYTES = IS_BF16 ? D * PT_STRIDE : RM_BYTES;
-    static constexpr int CHUNKS = 32 * D * Elem<T>::BYTES / 16;       // 16-byte pieces per tile
-    static constexpr int CPT = (CHUNKS + NTHREADS - 1) / NTHREADS;    // per thread
-    static constexpr int CPR = D * Elem<T>::BYTES / 16;               // per row
-};
-
-template <typename T, int D> using TileRegs = uint4[Tile<T, D>::CPT];
-
-// ------------------------------------------------------------------ staging
-// Global -> registers for one 32-row tile of a [L][D] matrix (rows beyond L read as 0).
-template <typename T, int D>
-__device__ __forceinline__ void tile_load(TileRegs<T, D> &reg, const T *base, int t0, int L)
-{
-    using TL = Tile<T, D>;
-#pragma unroll
-    for (int c = 0; c < TL::CPT; ++c) {
-        int idx = threadIdx.x + c * NTHREADS;
-        int row = idx / TL::CPR, ch = idx % TL::CPR;
-        uint4 v = make_uint4(0, 0, 0, 0);
-        if (idx < TL::CHUNKS && t0 + row < L)
-            v = *reinterpret_cast<const uint4 *>(base + (long)(t0 + row) * D + ch * (16 / Elem<T>::BYTES));
-        reg[c] = v;
-    }
-}
-
-// registers -> LDS, row-major (A-operand of the score / Z products)
-template <typename T, int D>
-__device__ __forceinline__ void tile_store_rm(const TileRegs<T, D> &reg, unsigned char *lds)
-{
-    using TL = Tile<T, D>;
-#pragma unroll
-    for (int c = 0; c < TL::CPT; ++c) {
-        int idx = threadIdx.x + c * NTHREADS;
-        if (idx < TL::CHUNKS) {
-            int row = idx / TL::CPR, ch = idx % TL::CPR;
-            if constexpr (TL::IS_BF16)
-                *reinterpret_cast<uint4 *>(lds + bf16_chunk_off<D>(row, ch)) = reg[c];
-            else
-                *reinterpret_cast<uint4 *>(lds + (row * f32_row_floats<D>() + ch * 4) * 4) = reg[c];
-        }
-    }
-}
-
-// registers -> LDS in the layout the second product wants: bf16 transposed [dv][t],
-// fp32 row-major.
-template <typename T, int D>
-__device__ __forceinline__ void tile_store_pay(const TileRegs<T, D> &reg, unsigned char *lds)
-{
-    using TL = Tile<T, D>;
-    if constexpr (!TL::IS_BF16) {
-        tile_store_rm<T, D>(reg, lds);
-    } else {
-#pragma unroll
-        for (int c = 0; c < TL::CPT; ++c) {
-            int idx = threadIdx.x + c * NTHREADS;
-            if (idx < TL::CHUNKS) {
-                int row = idx / TL::CPR, ch = idx % TL::CPR;
-                const unsigned int wds[4] = {reg[c].x, reg[c].y, reg[c].z, reg[c].w};
-#pragma unroll
-                for (int e = 0; e < 8; ++e) {
-                    unsigned short v = (unsigned short)(wds[e >> 1] >> ((e & 1) * 16));
-                    *reinterpret_cast<unsigned short *>(lds + (ch * 8 + e) * PT_STRIDE + row * 2) = v;
-                }
-            }
-        }
-    }
-}
-
-// ------------------------------------------------------------------ fragments
-// Owner-side fragment kept in registers for the whole sweep (B operand, columns o).
-template <typename T, int D> struct OwnerFrag;
-template <int D> struct OwnerFrag<__bf16, D> {
-    bf16x8 v[D / 16];
-    __device__ __forceinline__ void load(const __bf16 *base, int o, int L, int h)
-    {
-#pragma unroll
-        for (int s = 0; s < D / 16; ++s) {
-            uint4 z = make_uint4(0, 0, 0, 0);
-            if (o < L) z = *reinterpret_cast<const uint4 *>(base + (long)o * D + (2 * s + h) * 8);
-            v[s] = *reinterpret_cast<bf16x8 *>(&z);
-        }
-    }
-};
-template <int D> struct OwnerFrag<float, D> {
-    float v[D / 2];   // feature k = h*D/2 + s
-    __device__ __forceinline__ void load(const float *base, int o, int L, int h)
-    {
-#pragma unroll
-        for (int q = 0; q < D / 8; ++q) {
-            float4 z = make_float4(0.f, 0.f, 0.f, 0.f);
-            if (o < L) z = *reinterpret_cast<const float4 *>(base + (long)o * D + h * (D / 2) + 4 * q);
-            v[4 * q + 0] = z.x; v[4 * q + 1] = z.y; v[4 * q + 2] = z.z; v[4 * q + 3] = z.w;
-        }
-    }
-};
-
-// acc[t, o] += sum_k tile[t][k] * frag[o][k]
-template <int D>
-__device__ __forceinline__ f32x16 tile_dot(const unsigned char *tile, const OwnerFrag<__bf16, D> &x,
-                                           int lane, f32x16 acc)
-{
-    const int t = lane & 31, h = lane >> 5;
-#pragma unroll
-    for (int s = 0; s < D / 16; ++s) {
-        bf16x8 a = *reinterpret_cast<const bf16x8 *>(tile + bf16_chunk_off<D>(t, 2 * s + h));
-        acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, x.v[s], acc, 0, 0, 0);
-    }
-    return acc;
-}
-template <int D>
-__device__ __forceinline__ f32x16 tile_dot(const unsigned char *tile, const OwnerFrag<float, D> &x,
-                                           int lane, f32x16 acc)
-{
-    const int t = lane & 31, h = lane >> 5;
-    const float *row = reinterpret_cast<const float *>(tile) + t * f32_row_floats<D>() + h * (D / 2);
-#pragma unroll
-    for (int q = 0; q < D / 8; ++q) {
-        float4 a = *reinterpret_cast<const float4 *>(row + 4 * q);
-        acc = __builtin_amdgcn_mfma_f32_32x32x2f32(a.x, x.v[4 * q + 0], acc, 0, 0, 0);
-        acc = __builtin_amdgcn_mfma_f32_32x32x2f32(a.y, x.v[4 * q + 1], acc, 0, 0, 0);
-        acc = __builtin_amdgcn_mfma_f32_32x32x2f32(a.z, x.v[4 * q + 2], acc, 0, 0, 0);
-        acc = __builtin_amdgcn_mfma_f32_32x32x2f32(a.w, x.v[4 * q + 3], acc, 0, 0, 0);
-    }
-    return acc;
-}
-
-// FR score tiles at once from one other-side tile of a ring kernel (rows ROWB bytes apart,
-// no swizzle): the tile's fragments are read from LDS once and every product chain is
-// issued before any of them is consumed.
-template <int D, int FR, int ROWB>
-__device__ __forceinline__ void ring_dot_multi(const unsigned char *tile, const OwnerFrag<__bf16, D> (&x)[FR],
-                                               int lane, f32x16 (&acc)[FR])
-{
-    const unsigned char *row = tile + (lane & 31) * ROWB + (lane >> 5) * 16;
-    bf16x8 a[D / 16];
-#pragma unroll
-    for (int s = 0; s < D / 16; ++s) a[s] = *reinterpret_cast<const bf16x8 *>(row + 32 * s);
-#pragma unroll
-    for (int s = 0; s < D / 16; ++s)
-#pragma unroll
-        for (int f = 0; f < FR; ++f)
-            acc[f] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[s], x[f].v[s], acc[f], 0, 0, 0);
-}
-template <int D, int FR, int ROWB>
-__device__ __forceinline__ void ring_dot_multi(const unsigned char *tile, const OwnerFrag<float, D> (&x)[FR],
-                                               int lane, f32x16 (&acc)[FR])
-{
-    static_assert(ROWB == f32_row_floats<D>() * 4, "fp32 ring tiles use the padded fp32 layout");
-#pragma unroll
-    for (int f = 0; f < FR; ++f) acc[f] = tile_dot<D>(tile, x[f], lane, acc[f]);
-}
-
-// out[dvt][dv, o] += sum_t pay[t][dv] * e[t, o]   (e in the accumulator layout)
-template <typename T, int D>
-__device__ __forceinline__ void tile_accum(f32x16 (&out)[D / 32], const unsigned char *pay,
-                                           const float (&e)[16], int lane)
-{
-    const int c = lane & 31, h = lane >> 5;
-    if constexpr (Elem<T>::BYTES == 2) {
-#pragma unroll
-        for (int m = 0; m < 2; ++m) {
-            bf16x8 pf = pack8(&e[8 * m]);
-#pragma unroll
-            for (int dvt = 0; dvt < D / 32; ++dvt) {
-                const unsigned char *rowp = pay + (32 * dvt + c) * PT_STRIDE;
-                uint2 lo = *reinterpret_cast<const uint2 *>(rowp + (16 * m + 4 * h) * 2);
-                uint2 hi = *reinterpret_cast<const uint2 *>(rowp + (16 * m + 8 + 4 * h) * 2);
-                uint4 both = make_uint4(lo.x, lo.y, hi.x, hi.y);
-                bf16x8 af = *reinterpret_cast<bf16x8 *>(&both);
-                out[dvt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af, pf, out[dvt], 0, 0, 0);
-            }
-        }
-    } else {
-        const float *p = reinterpret_cast<const float *>(pay);
-#pragma unroll
-        for (int r = 0; r < 16; ++r) {
-            const int t = 8 * (r >> 2) + 4 * h + (r & 3);
-#pragma unroll
-            for (int dvt = 0; dvt < D / 32; ++dvt) {
-                float a = p[t * f32_row_floats<D>() + 32 * dvt + c];
-                out[dvt] = __builtin_amdgcn_mfma_f32_32x32x2f32(a, e[r], out[dvt], 0, 0, 0);
-            }
-        }
-    }
-}
-
-template <typename T> __device__ __forceinline__ void store4(T *dst, float a, float b, float c, float d);
-template <> __device__ __forceinline__ void store4<float>(float *dst, float a, float b, float c, float d)
-{
-    *reinterpret_cast<float4 *>(dst) = make_float4(a, b, c, d);
-}
-template <> __device__ __forceinline__ void store4<__bf16>(__bf16 *dst, float a, float b, float c, float d)
-{
-    bf16x4 v = {(__bf16)a, (__bf16)b, (__bf16)c, (__bf16)d};
-    *reinterpret_cast<bf16x4 *>(dst) = v;
-}
-template <typename T> __device__ __forceinline__ void load4(const T *src, float (&f)[4]);
-template <> __device__ __forceinline__ void load4<float>(const float *src, float (&f)[4])
-{
-    float4 v = *reinterpret_cast<const float4 *>(src);
-    f[0] = v.x; f[1] = v.y; f[2] = v.z; f[3] = v.w;
-}
-template <> __device__ __forceinline__ void load4<__bf16>(const __bf16 *src, float (&f)[4])
-{
-    bf16x4 v = *reinterpret_cast<const bf16x4 *>(src);
-#pragma unroll
-    for (int i = 0; i < 4; ++i) f[i] = (float)v[i];
-}
-
-// ------------------------------------------------------------------ the generic sweep kernel
-// Double-buffered LDS staging, one other-side tile per barrier.  It serves the first row
-// half-step (running-maximum LSE, no potentials yet), every fp32-storage matrix sweep
-// and the bf16 matrix sweeps at d = 128; the ring kernels below take the rest.
-template <typename T, int D, int MODE> struct Stage {
-    using TL = Tile<T, D>;
-    static constexpr bool HAS_B = (MODE == M_FINAL);
-    static constexpr bool HAS_PAY = (MODE == M_APPLY) || (MODE == M_FINAL && TL::IS_BF16);
-    static constexpr int OFF_Y = 0;
-    static constexpr int OFF_B = OFF_Y + TL::RM_BYTES;
-    static constexpr int OFF_PAY = OFF_B + (HAS_B ? TL::RM_BYTES : 0);
-    static constexpr int OFF_VY = OFF_PAY + (HAS_PAY ? TL::PT_BYTES : 0);
-    static constexpr int OFF_VQ = OFF_VY + TT * 4;
-    static constexpr int BYTES = ((OFF_VQ + TT * 16 * MAXNQ) + 15) / 16 * 16;
-};
-
-// DIRECT (M_FINAL only): the comparator that forms every staircase plan factor by an
-// exponential of its own, exp(S + u_t + v_t'), instead of scaling the one reference tile
-// (Prop. 2 versus the plain evaluation of Prop. 1).  A pack group then holds two terms as
-// (log2 modifier, weight) pairs: the term is exp2(score + l_row + l_col) w_row w_col.
-template <typename T, int D, int MODE, int FR, bool DIRECT = false>
-__global__ __launch_bounds__(NTHREADS) void sweep_kernel(const SweepArgs a)
-{
-    using TL = Tile<T, D>;
-    using ST = Stage<T, D, MODE>;
-    constexpr int BM = NWAVES * FR * 32;
-    constexpr bool MAT_OUT = (MODE == M_APPLY || MODE == M_FINAL);
-
-    extern __shared__ __align__(16) unsigned char smem[];   // two stages of ST::BYTES
-    __shared__ float red[NWAVES];
-
-    // XCD-aware placement: hardware deals workgroups round-robin over the 8 XCDs, so
-    // give each XCD one contiguous eighth of the (problem, block) sequence; neighbours
-    // that share band rows then meet in the same L2.
-    const int chunk = (a.nb_total + 7) >> 3;
-    const int lb = (blockIdx.x & 7) * chunk + (a.rev ? chunk - 1 - (int)(blockIdx.x >> 3) : (int)(blockIdx.x >> 3));
-    if (lb >= a.nb_total) return;
-    const int n = lb / a.nbp;
-    const int o_blk = (lb % a.nbp) * BM;
-
-    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-    const int c = lane & 31, h = lane >> 5;
-    const int L = a.L, W = a.W;
-    const Lens ln = problem_lens(a, n);
-    const int Lt = ln.Lt, Le = ln.Le;
-    if (o_blk >= Le) {
-        zero_block<T, D, BM>(a, n, o_blk, MAT_OUT, !MAT_OUT);
-        return;
-    }
-    const long moff = (long)n * L * D;
-    const T *Xb = reinterpret_cast<const T *>(a.X) + moff;
-    const T *Yb = reinterpret_cast<const T *>(a.Y) + moff;
-    const float *ytp = a.yt.p + n * a.yt.stride;
-    // owner-side potential: stabiliser and factor of the plan; -inf marks an inactive token (a
-    // masked one, or one without any active partner), which stays inactive in every later
-    // iterate.  The first half-step has no previous iterate: there xs only carries the marks.
-    const float *xsp = a.xs.p ? a.xs.p + n * a.xs.stride : nullptr;
-
-    // workgroup stabiliser: largest owner-side potential in this block
-    float mblk = 0.f;
-    if constexpr (MODE != M_LSE_FIRST) {
-        float m = -INFINITY;
-        for (int i = tid; i < BM; i += NTHREADS)
-            if (o_blk + i < Le) m = fmaxf(m, xsp[o_blk + i]);
-#pragma unroll
-        for (int s = 32; s >= 1; s >>= 1) m = fmaxf(m, __shfl_xor(m, s));
-        if (lane == 0) red[wave] = m;
-        __syncthreads();
-        mblk = fmaxf(fmaxf(red[0], red[1]), fmaxf(red[2], red[3]));
-        if (mblk == -INFINITY) mblk = 0.f;   // a block of inactive tokens only
-    }
-    const float m2 = mblk * LOG2E;
-
-    // owner-side fragments
-    OwnerFrag<T, D> xf[FR];
-    OwnerFrag<T, D> af[MODE == M_FINAL ? FR : 1];
-    float4 pof[FR][MAXNQ];
-    int o_frag[FR];
-#pragma unroll
-    for (int f = 0; f < FR; ++f) {
-        o_frag[f] = o_blk + (wave * FR + f) * 32;
-        xf[f].load(Xb, o_frag[f] + c, Le, h);
-        if constexpr (MODE == M_FINAL) {
-            af[f].load(reinterpret_cast<const T *>(a.A) + moff, o_frag[f] + c, Le, h);
-#pragma unroll
-            for (int g = 0; g < MAXNQ; ++g)
-                pof[f][g] = (o_frag[f] + c < Le && g < a.nq) ? a.po[(n * a.ldp + o_frag[f] + c) * a.pstride + g]
-                                                            : make_float4(0, 0, 0, 0);
-        }
-    }
-
-    // accumulators
-    float sum[FR], mx[FR];
-    f32x16 outm[MAT_OUT ? FR : 1][D / 32];
-#pragma unroll
-    for (int f = 0; f < FR; ++f) {
-        sum[f] = 0.f;
-        mx[f] = -INFINITY;
-        if constexpr (MAT_OUT)
-#pragma unroll
-            for (int j = 0; j < D / 32; ++j)
-#pragma unroll
-                for (int r = 0; r < 16; ++r) outm[f][j][r] = 0.f;
-    }
-
-    // other-side tile range of the whole block (tiles aligned to multiples of 32)
-    int lo = o_blk - W;            // the host clamps W to L, so none of this overflows
-    if (lo < 0) lo = 0;
-    int hi = o_blk + BM - 1 + W;
-    if (hi > Lt - 1) hi = Lt - 1;   // (lo <= hi: the block has a row below Le <= Lt + W)
-    const int k_lo = lo / TT, k_hi = hi / TT;
-
-    // staging registers
-    uint4 ry[TL::CPT], rb[ST::HAS_B ? TL::CPT : 1], rp[MODE == M_APPLY ? TL::CPT : 1];
-    float rvy = 0.f;
-    float4 rvq[MAXNQ] = {make_float4(0, 0, 0, 0), make_float4(0, 0, 0, 0)};
-
-    auto g_load = [&](int k) {
-        const int t0 = k * TT;
-        tile_load<T, D>(ry, Yb, t0, Lt);
-        if constexpr (ST::HAS_B) tile_load<T, D>(rb, reinterpret_cast<const T *>(a.Bm) + moff, t0, Lt);
-        if constexpr (MODE == M_APPLY) tile_load<T, D>(rp, reinterpret_cast<const T *>(a.Pay) + moff, t0, Lt);
-        if (tid < TT) {
-            const int t = t0 + tid;
-            rvy = (t < Lt) ? ytp[t] * LOG2E + m2 : -INFINITY;
-            if constexpr (MODE == M_FINAL) {
-#pragma unroll
-                for (int g = 0; g < MAXNQ; ++g)
-                    rvq[g] = (t < Lt && g < a.nq) ? a.qt[(n * a.ldp + t) * a.pstride + g] : make_float4(0, 0, 0, 0);
-            }
-        }
-    };
-    auto s_store = [&](int buf) {
-        unsigned char *s = smem + buf * ST::BYTES;
-        tile_store_rm<T, D>(ry, s + ST::OFF_Y);
-        if constexpr (ST::HAS_B) tile_store_rm<T, D>(rb, s + ST::OFF_B);
-        if constexpr (MODE == M_APPLY) tile_store_pay<T, D>(rp, s + ST::OFF_PAY);
-        if constexpr (MODE == M_FINAL && TL::IS_BF16) tile_store_pay<T, D>(ry, s + ST::OFF_PAY);
-        if (tid < TT) {
-            reinterpret_cast<float *>(s + ST::OFF_VY)[tid] = rvy;
-            if constexpr (MODE == M_FINAL) {
-#pragma unroll
-                for (int g = 0; g < MAXNQ; ++g) reinterpret_cast<float4 *>(s + ST::OFF_VQ)[tid * MAXNQ + g] = rvq[g];
-            }
-        }
-    };
-
-    g_load(k_lo);
-    s_store(0);
-    __syncthreads();
-
-    for (int k = k_lo; k <= k_hi; ++k) {
-        const int buf = (k - k_lo) & 1;
-        if (k < k_hi) g_load(k + 1);
-        const unsigned char *s = smem + buf * ST::BYTES;
-        const int t0 = k * TT;
-
-#pragma unroll
-        for (int f = 0; f < FR; ++f) {
-            const int of = o_frag[f];
-            // does this tile meet the band of this fragment at all?
-            if (of >= Le || (long)t0 + TT - 1 < (long)of - W || (long)t0 > (long)of + 31 + W) continue;
-            const bool interior = ((long)of + 31 - t0 <= W) && ((long)t0 + TT - 1 - of <= W);
-
-            f32x16 acc;
-#pragma unroll
-            for (int r = 0; r < 16; ++r) acc[r] = 0.f;
-            acc = tile_dot<D>(s + ST::OFF_Y, xf[f], lane, acc);
-
-            float yv[16];
-#pragma unroll
-            for (int q = 0; q < 4; ++q) {
-                float4 v4 = *reinterpret_cast<const float4 *>(s + ST::OFF_VY + (8 * q + 4 * h) * 4);
-                yv[4 * q + 0] = v4.x; yv[4 * q + 1] = v4.y; yv[4 * q + 2] = v4.z; yv[4 * q + 3] = v4.w;
-            }
-            float e[16];
-#pragma unroll
-            for (int r = 0; r < 16; ++r) e[r] = fmaf(acc[r], a.c2, yv[r]);
-            if (!interior) {
-                const int o = of + c;
-#pragma unroll
-                for (int r = 0; r < 16; ++r) {
-                    const int t = t0 + 8 * (r >> 2) + 4 * h + (r & 3);
-                    const int dlt = o > t ? o - t : t - o;
-                    if (dlt > W) e[r] = -INFINITY;
-                }
-            }
-
-            if constexpr (MODE == M_LSE_FIRST) {
-                float tm = e[0];
-#pragma unroll
-                for (int r = 1; r < 16; ++r) tm = fmaxf(tm, e[r]);
-                const float mn = fmaxf(mx[f], tm);
-                const float ms = (mn == -INFINITY) ? 0.f : mn;
-                float sacc = sum[f] * fast_exp2(mx[f] - ms);
-#pragma unroll
-                for (int r = 0; r < 16; ++r) sacc += fast_exp2(e[r] - ms);
-                sum[f] = sacc;
-                mx[f] = mn;
-            } else {
-                float el[DIRECT ? 16 : 1];
-                if constexpr (DIRECT)
-#pragma unroll
-                    for (int r = 0; r < 16; ++r) el[r] = e[r];
-#pragma unroll
-                for (int r = 0; r < 16; ++r) e[r] = fast_exp2(e[r]);
-                if constexpr (MODE == M_APPLY) {
-                    tile_accum<T, D>(outm[f], s + ST::OFF_PAY, e, lane);
-                } else {  // M_FINAL
-                    f32x16 z;
-#pragma unroll
-                    for (int r = 0; r < 16; ++r) z[r] = 0.f;
-                    if (!a.skipz) z = tile_dot<D>(s + ST::OFF_B, af[f], lane, z);
-#pragma unroll
-                    for (int r = 0; r < 16; ++r) {
-                        const int tl = 8 * (r >> 2) + 4 * h + (r & 3);
-                        float md = z[r];
-                        if constexpr (DIRECT) {
-                            float sb = e[r] * md;
-#pragma unroll
-                            for (int g = 0; g < MAXNQ; ++g) {   // (an absent group has zero weights)
-                                float4 q4 = *reinterpret_cast<const float4 *>(s + ST::OFF_VQ + (tl * MAXNQ + g) * 16);
-                                const float p0 = (g == 0 && a.refterm) ? e[r]
-                                                                       : fast_exp2(el[r] + pof[f][g].x + q4.x);
-                                const float p1 = fast_exp2(el[r] + pof[f][g].z + q4.z);
-                                sb = fmaf(-p0 * pof[f][g].y, q4.y, sb);
-                                sb = fmaf(-p1 * pof[f][g].w, q4.w, sb);
-                            }
-                            e[r] = sb;
-                        } else {
-#pragma unroll
-                            for (int g = 0; g < MAXNQ; ++g) {   // (an absent group is all zeros)
-                                float4 q4 = *reinterpret_cast<const float4 *>(s + ST::OFF_VQ + (tl * MAXNQ + g) * 16);
-                                md = fmaf(-pof[f][g].x, q4.x, md);
-                                md = fmaf(-pof[f][g].y, q4.y, md);
-                                md = fmaf(-pof[f][g].z, q4.z, md);
-                                md = fmaf(-pof[f][g].w, q4.w, md);
-                            }
-                            e[r] *= md;
-                        }
-                    }
-                    tile_accum<T, D>(outm[f], TL::IS_BF16 ? s + ST::OFF_PAY : s + ST::OFF_Y, e, lane);
-                }
-            }
-        }
-
-        if (k < k_hi) s_store(buf ^ 1);
-        __syncthreads();
-    }
-
-    // ---------------------------------------------------------------- epilogue
-#pragma unroll
-    for (int f = 0; f < FR; ++f) {
-        const int o = o_frag[f] + c;
-        if constexpr (MODE == M_LSE_FIRST) {
-            float mo = __shfl_xor(mx[f], 32), so = __shfl_xor(sum[f], 32);
-            float mn = fmaxf(mx[f], mo);
-            float tot = sum[f] * fast_exp2(mx[f] - mn) + so * fast_exp2(mo - mn);
-            if (a.dustbin) {   // spoke edge (o, dustbin): score sdb, other-side potential yt[L]
-                const float sp2 = a.spoke_own.p ? a.spoke_own.p[n * a.spoke_own.stride + min(o, L - 1)] * LOG2E : a.sdb2;
-                float xd = sp2 + ytp[L] * LOG2E;
-                float m3 = fmaxf(mn, xd);
-                tot = tot * fast_exp2(mn - m3) + fast_exp2(xd - m3);
-                mn = m3;
-            }
-            if (h == 0 && o < L) {
-                float r = 0.f;   // rows beyond the valid length
-                if (o < Le) {
-                    if ((xsp && xsp[o] == -INFINITY) || !(mn > -INFINITY)) {
-                        r = -INFINITY;   // inactive token
-                    } else {
-                        r = -LN2 * (mn + fast_log2(tot));
-                        if (a.olog.p) r += a.olog.p[n * a.olog.stride + o];
-                    }
-                }
-                a.out_vec.p[n * a.out_vec.stride + o] = r;
-            }
-        } else {
-            float fac = 0.f;
-            bool dead = true;   // beyond the valid length, or an inactive token: zeros
-            if (o < Le) {
-                fac = fast_exp2((xsp[o] - mblk) * LOG2E);
-                dead = xsp[o] == -INFINITY;
-            }
-            if constexpr (MODE == M_FINAL) fac *= a.cs;
-            float pdb = 0.f;   // plan entry of the spoke (o, dustbin) when the dustbin carries a payload
-            if constexpr (MODE == M_APPLY)
-                if (a.pay_db && o < L) pdb = __expf(a.spoke_own.p[n * a.spoke_own.stride + o] + xsp[o] + ytp[L]);
-            T *orow = reinterpret_cast<T *>(a.out_mat) + moff + (long)o * D;
-            const T *drow = a.dot_mat ? reinterpret_cast<const T *>(a.dot_mat) + moff + (long)o * D : nullptr;
-            float dot = 0.f;
-#pragma unroll
-            for (int j = 0; j < D / 32; ++j)
-#pragma unroll
-                for (int q = 0; q < 4; ++q) {
-                    const int dv = 32 * j + 8 * q + 4 * h;
-                    float v0 = outm[f][j][4 * q + 0] * fac, v1 = outm[f][j][4 * q + 1] * fac;
-                    float v2 = outm[f][j][4 * q + 2] * fac, v3 = outm[f][j][4 * q + 3] * fac;
-                    if constexpr (MODE == M_APPLY) {
-                        if (a.pay_db) {
-                            const float4 pv = *reinterpret_cast<const float4 *>(a.pay_db + (long)n * D + dv);
-                            v0 = fmaf(pdb, pv.x, v0); v1 = fmaf(pdb, pv.y, v1);
-                            v2 = fmaf(pdb, pv.z, v2); v3 = fmaf(pdb, pv.w, v3);
-                        }
-                    }
-                    if (dead) v0 = v1 = v2 = v3 = 0.f;
-                    if (o < L) {
-                        if constexpr (MODE == M_FINAL) {
-                            if (a.accum) {
-                                float old[4];
-                                load4<T>(orow + dv, old);
-                                v0 += old[0]; v1 += old[1]; v2 += old[2]; v3 += old[3];
-                            }
-                        }
-                        store4<T>(orow + dv, v0, v1, v2, v3);
-                        if constexpr (MODE == M_APPLY) {
-                            if (drow && !dead) {
-                                float dd[4];
-                                load4<T>(drow + dv, dd);
-                                dot += dd[0] * v0 + dd[1] * v1 + dd[2] * v2 + dd[3] * v3;
-                            }
-                        }
-                    }
-                }
-            if constexpr (MODE == M_APPLY) {
-                if (a.dot_mat) {
-                    dot += __shfl_xor(dot, 32);
-                    if (h == 0 && o < L) {
-                        if (a.olog.p && !dead) dot *= __expf(-a.olog.p[n * a.olog.stride + o]);
-                        a.dot_out.p[n * a.dot_out.stride + o] = dot;
-                    }
-                }
-            }
-        }
-    }
-}
-
-// ------------------------------------------------------------------ vector sweeps
-// Scaling sweep (M_LSE) and band mat-vec (M_MATVEC): the result is one scalar per
-// owner index, so the only state a wavefront carries is FR owner fragments and FR
-// partial sums.  Wavefront w owns rows [o_blk + 32 FR w, +32 FR) and needs other-side
-// tiles kbase + FR w ... kend + FR w: the same count S for every wavefront, shifted by
-// FR per wavefront.  The tiles therefore go through an LDS ring with that skew: at
-// step s wavefront w works on tile kbase + s + FR w, so all wavefronts are busy in
-// every step, and one new tile enters the ring per step (one barrier per step).
-template <typename T, int D, int MODE, int FR> struct VRing {
-    using TL = Tile<T, D>;
-    static constexpr int LEAD = FR * (NWAVES - 1);          // tiles between first and last wavefront
-    static constexpr int NSLOT = (LEAD + 2 <= 8) ? 8 : 16;  // power of two >= LEAD + 2
-    // tile rows in LDS: bf16 rows carry 16 bytes of padding (the 32 rows an MFMA operand
-    // read touches then fall on distinct banks, and the chunks of one row sit at fixed
-    // distances: one address register per step); fp32 rows are padded by four floats
-    static constexpr int ROWB = TL::IS_BF16 ? D * 2 + 16 : f32_row_floats<D>() * 4;
-    static constexpr int OFF_VY = 32 * ROWB;
-    static constexpr int OFF_VW = OFF_VY + TT * 4;
-    static constexpr int SLOT = OFF_VW + TT * 4;
-    static constexpr int BYTES = NSLOT * SLOT;
-};
-
-template <typename T, int D, int MODE, int FR>
-__global__ __launch_bounds__(NTHREADS) void vsweep_kernel(const SweepArgs a)
-{
-    using TL = Tile<T, D>;
-    using RG = VRing<T, D, MODE, FR>;
-    constexpr bool PRE = (sizeof(T) == 2);   // bf16 storage: the score operand is prescaled, c2 == 1
-    constexpr int BM = NWAVES * FR * 32;
-    static_assert(MODE == M_LSE || MODE == M_MATVEC, "vector sweeps only");
-
-    extern __shared__ __align__(16) unsigned char smem[];
-    __shared__ float red[NWAVES];
-
-    const int chunk = (a.nb_total + 7) >> 3;
-    const int lb = (blockIdx.x & 7) * chunk + (a.rev ? chunk - 1 - (int)(blockIdx.x >> 3) : (int)(blockIdx.x >> 3));
-    if (lb >= a.nb_total) return;
-    const int n = lb / a.nbp;
-    const int o_blk = (lb % a.nbp) * BM;
-
-    // the wavefront index is uniform: keep it (and all tile bookkeeping) in scalar registers
-    const int tid = threadIdx.x, lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6);
-    const int c = lane & 31, h = lane >> 5;
-    const int L = a.L, W = a.W;
-    const Lens ln = problem_lens(a, n);
-    const int Lt = ln.Lt, Le = ln.Le;
-    if (o_blk >= Le) {
-        zero_block<T, D, BM>(a, n, o_blk, false, true);
-        return;
-    }
-    const long moff = (long)n * L * D;
-    const T *Xb = reinterpret_cast<const T *>(a.X) + moff;
-    const T *Yb = reinterpret_cast<const T *>(a.Y) + moff;
-    const float *ytp = a.yt.p + n * a.yt.stride;
-    const float *xsp = a.xs.p + n * a.xs.stride;
-    const float *wp = (MODE == M_MATVEC) ? a.w.p + n * a.w.stride : nullptr;
-
-
-    // stabiliser input first, so that waiting for it waits for nothing else
-    static_assert(BM <= NTHREADS, "one owner-side potential per thread");
-    float mraw = xsp[min(o_blk + min(tid, BM - 1), Le - 1)];   // clamped repeats are harmless
-    float mblk, m2 = 0.f;
-    OwnerFrag<T, D> xf[FR];
-    int o_frag[FR];
-    float sum[FR];
-#pragma unroll
-    for (int f = 0; f < FR; ++f) {
-        o_frag[f] = o_blk + (wave * FR + f) * 32;
-        xf[f].load(Xb, min(o_frag[f] + c, Le - 1), Le, h);   // clamped: rows beyond Le are written as zeros
-        sum[f] = 0.f;
-    }
-
-    // floor((o_blk - W) / 32) and floor((o_blk + 32 FR - 1 + W) / 32); W <= L so no overflow
-    const int kbase = (o_blk - W) >= 0 ? (o_blk - W) / TT : -((W - o_blk + TT - 1) / TT);
-    const int kend = (o_blk + 32 * FR - 1 + W) / TT;
-    const int S = kend - kbase + 1;
-    const int klast = (Lt - 1) / TT;
-
-    // One tile in flight between global memory and LDS.  A tile is a contiguous block of
-    // memory, so a thread's 16-byte pieces sit at fixed byte offsets from the tile's start:
-    // the start is a scalar, the offset one register, and a load needs no address arithmetic
-    // beyond a clamp that keeps the pieces of a ragged last tile inside the matrix.  Loads
-    // are unconditional (an index outside [0, klast] reads the nearest tile and is zeroed
-    // before it is stored), so nothing stalls until the values are stored.
-    constexpr int ROW_BYTES = D * (int)sizeof(T);
-    constexpr int TILE_BYTES = TT * ROW_BYTES;
-    unsigned goff[TL::CPT], soff[TL::CPT];   // piece offsets: in memory, in the LDS tile
-#pragma unroll
-    for (int q = 0; q < TL::CPT; ++q) {
-        const int idx = min(tid + q * NTHREADS, TL::CHUNKS - 1);
-        goff[q] = idx * 16;
-        soff[q] = (idx / TL::CPR) * RG::ROWB + (idx % TL::CPR) * 16;
-    }
-    const unsigned vrow = tid & (TT - 1);
-    struct Inflight {
-        uint4 y[TL::CPT];
-        float vy, vw;
-        int rows;          // valid rows of the tile: 32 = whole, 0 = outside the matrix (uniform)
-    };
-    auto g_load = [&](Inflight &g, int k) {
-        const int kc = min(max(k, 0), klast);
-        const int rows = min(TT, Lt - kc * TT);   // >= 1
-        g.rows = (k == kc) ? rows : 0;
-        const unsigned char *tb = reinterpret_cast<const unsigned char *>(Yb) + (long)kc * TILE_BYTES;
-        const unsigned lim = rows * ROW_BYTES - 16;
-#pragma unroll
-        for (int q = 0; q < TL::CPT; ++q) g.y[q] = *reinterpret_cast<const uint4 *>(tb + min(goff[q], lim));
-        const unsigned vo = min(vrow, (unsigned)(rows - 1)) * 4;
-        g.vy = *reinterpret_cast<const float *>(reinterpret_cast<const unsigned char *>(ytp + kc * TT) + vo);
-        g.vw = 0.f;
-        if constexpr (MODE == M_MATVEC)
-            g.vw = *reinterpret_cast<const float *>(reinterpret_cast<const unsigned char *>(wp + kc * TT) + vo);
-    };
-    auto s_store = [&](Inflight &g, int j) {  // j = tile index relative to kbase
-        unsigned char *sl = smem + (j & (RG::NSLOT - 1)) * RG::SLOT;
-        if (g.rows != TT) {   // uniform: ragged or absent tile
-            const unsigned lim = g.rows * ROW_BYTES;
-#pragma unroll
-            for (int q = 0; q < TL::CPT; ++q)
-                if (goff[q] >= lim) g.y[q] = make_uint4(0, 0, 0, 0);
-        }
-#pragma unroll
-        for (int q = 0; q < TL::CPT; ++q)
-            if (TL::CHUNKS % NTHREADS == 0 || tid + q * NTHREADS < TL::CHUNKS)
-                *reinterpret_cast<uint4 *>(sl + soff[q]) = g.y[q];
-        if (tid < TT) {
-            const bool ok = (int)vrow < g.rows;
-            reinterpret_cast<float *>(sl + RG::OFF_VY)[tid] = ok ? fmaf(g.vy, LOG2E, m2) : -INFINITY;
-            if constexpr (MODE == M_MATVEC) reinterpret_cast<float *>(sl + RG::OFF_VW)[tid] = ok ? g.vw : 0.f;
-        }
-    };
-
-    // fill the ring with the tiles of step 0.  Everything the prologue needs from memory is
-    // requested before anything is waited for: owner rows (above), the first tiles, and the
-    // owner-side potentials the stabiliser is taken from.
-    Inflight fill[RG::LEAD + 1];
-#pragma unroll
-    for (int j = 0; j <= RG::LEAD; ++j) g_load(fill[j], kbase + j);
-    {
-        float m = mraw;
-#pragma unroll
-        for (int s = 32; s >= 1; s >>= 1) m = fmaxf(m, __shfl_xor(m, s));
-        if (lane == 0) red[wave] = m;
-        __syncthreads();
-        mblk = fmaxf(fmaxf(red[0], red[1]), fmaxf(red[2], red[3]));
-        if (mblk == -INFINITY) mblk = 0.f;   // a block of inactive tokens only
-    }
-    m2 = mblk * LOG2E;
-#pragma unroll
-    for (int j = 0; j <= RG::LEAD; ++j) s_store(fill[j], j);
-    __syncthreads();
-    Inflight nxt;
-
-    for (int s = 0; s < S; ++s) {
-        // the next tile is requested in every step, also when no later step reads it (its
-        // address is clamped, its ring slot is free): a load under a condition would make
-        // the compiler wait for it at once instead of at the store below
-        const int jnew = s + 1 + RG::LEAD;
-        g_load(nxt, kbase + jnew);
-
-        const int j = s + wave * FR;
-        const int k = kbase + j;
-        if (k >= 0 && k <= klast) {
-            const unsigned char *sl = smem + (j & (RG::NSLOT - 1)) * RG::SLOT;
-            const int t0 = k * TT;
-            bool use[FR], interior[FR];
-            f32x16 acc[FR];
-            // the staged potentials are the MFMA's initial accumulator when the score operand
-            // carries the scale already (bf16 storage: make_scores_operand)
-            float yv[16];
-#pragma unroll
-            for (int q = 0; q < 4; ++q) {
-                float4 v4 = *reinterpret_cast<const float4 *>(sl + RG::OFF_VY + (8 * q + 4 * h) * 4);
-                yv[4 * q + 0] = v4.x; yv[4 * q + 1] = v4.y; yv[4 * q + 2] = v4.z; yv[4 * q + 3] = v4.w;
-            }
-#pragma unroll
-            for (int f = 0; f < FR; ++f) {
-                const int of = o_frag[f];
-                use[f] = !(of >= Le || t0 + TT - 1 < of - W || t0 > of + 31 + W);
-                interior[f] = (of + 31 - t0 <= W) && (t0 + TT - 1 - of <= W);
-#pragma unroll
-                for (int r = 0; r < 16; ++r) acc[f][r] = PRE ? yv[r] : 0.f;
-            }
-            ring_dot_multi<D, FR, RG::ROWB>(sl, xf, lane, acc);   // unconditional: an unused tile costs MFMA only
-
-            float wv[MODE == M_MATVEC ? 16 : 1];
-            if constexpr (MODE == M_MATVEC) {
-#pragma unroll
-                for (int q = 0; q < 4; ++q) {
-                    float4 w4 = *reinterpret_cast<const float4 *>(sl + RG::OFF_VW + (8 * q + 4 * h) * 4);
-                    wv[4 * q + 0] = w4.x; wv[4 * q + 1] = w4.y; wv[4 * q + 2] = w4.z; wv[4 * q + 3] = w4.w;
-                }
-            }
-#pragma unroll
-            for (int f = 0; f < FR; ++f) {
-                if (!use[f]) continue;
-                float e[16];
-#pragma unroll
-                for (int r = 0; r < 16; ++r) e[r] = PRE ? acc[f][r] : fmaf(acc[f][r], a.c2, yv[r]);
-                if (!interior[f]) {
-                    // keep (o, t) iff -W <= t - o <= W; with t = t0 + 4h + off_r (off_r a
-                    // constant of register r) this is lo <= off_r <= lo + 2W for the lane's
-                    // lo = o - W - t0 - 4h.  A tile crosses the lower edge, the upper edge
-                    // or (narrow bands) both: one compare against a constant per edge.
-                    const int lo = o_frag[f] + c - W - t0 - 4 * h;
-                    const int hi = lo + 2 * W;
-                    if (o_frag[f] + 31 - t0 > W) {
-#pragma unroll
-                        for (int r = 0; r < 16; ++r)
-                            if (lo > 8 * (r >> 2) + (r & 3)) e[r] = -INFINITY;
-                    }
-                    if (t0 + TT - 1 - o_frag[f] > W) {
-#pragma unroll
-                        for (int r = 0; r < 16; ++r)
-                            if (hi < 8 * (r >> 2) + (r & 3)) e[r] = -INFINITY;
-                    }
-                }
-#pragma unroll
-                for (int r = 0; r < 16; ++r) {
-                    const float p = fast_exp2(e[r]);
-                    if constexpr (MODE == M_MATVEC) sum[f] = fmaf(p, wv[r], sum[f]);
-                    else sum[f] += p;
-                }
-            }
-        }
-        s_store(nxt, jnew);
-        __syncthreads();
-    }
-
-#pragma unroll
-    for (int f = 0; f < FR; ++f) {
-        const int o = o_frag[f] + c;
-        float tot = sum[f] + __shfl_xor(sum[f], 32);
-        if (a.dustbin) {   // spoke edge (o, dustbin element of the other side)
-            const float sp2 = a.spoke_own.p ? a.spoke_own.p[n * a.spoke_own.stride + min(o, L - 1)] * LOG2E : a.sdb2;
-            float ed = fast_exp2(sp2 + ytp[L] * LOG2E + m2);
-            tot += (MODE == M_MATVEC) ? ed * wp[L] : ed;
-        }
-        if (h == 0 && o < L) {
-            float r;
-            if (o >= Le) {
-                r = 0.f;   // rows beyond the valid length
-            } else if (xsp[o] == -INFINITY || (MODE == M_LSE && !(tot > 0.f))) {
-                r = (MODE == M_LSE) ? -INFINITY : 0.f;   // inactive token (stays so), or none of its partners is active
-            } else if constexpr (MODE == M_LSE) {
-                r = mblk - LN2 * fast_log2(tot);
-                if (a.olog.p) r += a.olog.p[n * a.olog.stride + o];
-            } else {
-                float pre = a.pre.p ? a.pre.p[n * a.pre.stride + o] : 0.f;
-                r = pre - fast_exp2((xsp[o] - mblk) * LOG2E) * tot;
-                if (a.olog.p) r *= __expf(-a.olog.p[n * a.olog.stride + o]);
-            }
-            a.out_vec.p[n * a.out_vec.stride + o] = r;
-        }
-    }
-}
-
-// ------------------------------------------------------------------ matrix sweeps (bf16)
-// Output map / dV (M_APPLY) and the one-reference final sweep (M_FINAL) on the same skewed
-// ring: wavefront w owns 32 rows, four wavefronts per workgroup, the tile of step s for
-// wavefront w is kbase + s + w.  A ring slot holds the other-side score rows, the second
-// streamed matrix (payload for M_APPLY, the other-side factor of Z for M_FINAL), the staged
-// potentials and, for M_FINAL, the other-side modifier pack.  Tiles are row-major in LDS
-// with 16 bytes of padding per row.  The four rank-1 modifier terms of Prop. 2 are not VALU
-// work: each side's pack is written as 16 bf16 columns (every fp32 value split into a high
-// and a low bf16 part; per term the three products hi*hi, hi*lo, lo*hi, the owner side
-// negated), which extend the Z product by one K = 16 MFMA step: its result is
-// Z - sum_k po_k qt_k directly.  The other side's 32 bytes per row sit in the padding of the
-// row in the two tiles.  The second product needs its streamed operand with the
-// band index contiguous, which the transposing LDS read (ds_read_b64_tr_b16) delivers from
-// the row-major tile: within 16 lanes, lane i receives element (i & 3) of the 8-byte pieces
-// addressed by lanes (i >> 2) + 4 e, e = 0..3.
-template <int D, int MODE, int FR> struct MRing {
-    static constexpr int LEAD = FR * (NWAVES - 1);
-    static constexpr int NSLOT = LEAD + 2;             // exactly what the skew needs (5 or 8): LDS decides
-                                                       // how many workgroups share a CU
-    static constexpr int ROWB = D * 2 + 16;
-    static constexpr int TILE = 32 * ROWB;
-    static constexpr int OFF_Y = 0;
-    static constexpr int OFF_B = TILE;                 // payload (M_APPLY) or Z factor (M_FINAL)
-    static constexpr int OFF_VY = 2 * TILE;
-    static constexpr int OFF_PK = D * 2;               // M_FINAL: the 16 bytes of padding of a row of either
-                                                       // tile hold half of the row's 16 pack columns
-    static constexpr int SLOT = OFF_VY + TT * 4;
-    static constexpr int BYTES = NSLOT * SLOT;
-    static constexpr int CHUNKS = 32 * D * 2 / 16;     // 16-byte pieces of a tile in memory
-    static constexpr int CPT = (CHUNKS + NTHREADS - 1) / NTHREADS;
-    static constexpr int CPR = D * 2 / 16;
-    static_assert(LEAD + 2 <= NSLOT, "ring too small for the skew");
-};
-
-template <int D, int MODE, int FR>
-__global__ __launch_bounds__(NTHREADS) void msweep_kernel(const SweepArgs a)
-{
-    using T = __bf16;
-    using RG = MRing<D, MODE, FR>;
-    constexpr int BM = NWAVES * FR * 32, KS = D / 16;
-    static_assert(MODE == M_APPLY || MODE == M_FINAL, "matrix sweeps only");
-
-    extern __shared__ __align__(16) unsigned char smem[];
-    __shared__ float red[NWAVES];
-
-    const int chunk = (a.nb_total + 7) >> 3;
-    const int lb = (blockIdx.x & 7) * chunk + (a.rev ? chunk - 1 - (int)(blockIdx.x >> 3) : (int)(blockIdx.x >> 3));
-    if (lb >= a.nb_total) return;
-    const int n = lb / a.nbp;
-    const int o_blk = (lb % a.nbp) * BM;
-
-    const int tid = threadIdx.x, lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6);
-    const int c = lane & 31, h = lane >> 5;
-    const int L = a.L, W = a.W;
-    const Lens ln = problem_lens(a, n);
-    const int Lt = ln.Lt, Le = ln.Le;
-    if (o_blk >= Le) {
-        zero_block<T, D, BM>(a, n, o_blk, true, false);
-        return;
-    }
-    const long moff = (long)n * L * D;
-    const T *Xb = reinterpret_cast<const T *>(a.X) + moff;
-    const unsigned char *Yb = reinterpret_cast<const unsigned char *>(reinterpret_cast<const T *>(a.Y) + moff);
-    const unsigned char *Bb = reinterpret_cast<const unsigned char *>(
-        reinterpret_cast<const T *>(MODE == M_FINAL ? a.Bm : a.Pay) + moff);
-    const float *ytp = a.yt.p + n * a.yt.stride;
-    const float *xsp = a.xs.p + n * a.xs.stride;
-
-    float mblk, m2;
-    {
-        float m = -INFINITY;
-        for (int i = tid; i < BM; i += NTHREADS) m = fmaxf(m, xsp[min(o_blk + i, Le - 1)]);
-#pragma unroll
-        for (int s = 32; s >= 1; s >>= 1) m = fmaxf(m, __shfl_xor(m, s));
-        if (lane == 0) red[wave] = m;
-        __syncthreads();
-        mblk = fmaxf(fmaxf(red[0], red[1]), fmaxf(red[2], red[3]));
-        if (mblk == -INFINITY) mblk = 0.f;   // a block of inactive tokens only
-    }
-    m2 = mblk * LOG2E;
-
-    // owner side: score rows, and for M_FINAL the owner factor of Z and the modifier pack.
-    // Rows beyond Le are clamped: they compute garbage that is never stored.
-    const int o_w = o_blk + wave * FR * 32;
-    OwnerFrag<T, D> xf[FR], af[MODE == M_FINAL ? FR : 1];
-    bf16x8 pob[FR];   // M_FINAL: this lane's half of the owner row's 16 pack columns
-    f32x16 outm[FR][D / 32];
-#pragma unroll
-    for (int f = 0; f < FR; ++f) {
-        const int oc = min(o_w + 32 * f + c, Le - 1);
-#pragma unroll
-        for (int s = 0; s < KS; ++s) {
-            uint4 z = *reinterpret_cast<const uint4 *>(Xb + (long)oc * D + (2 * s + h) * 8);
-            xf[f].v[s] = *reinterpret_cast<bf16x8 *>(&z);
-            if constexpr (MODE == M_FINAL) {
-                uint4 y = *reinterpret_cast<const uint4 *>(reinterpret_cast<const T *>(a.A) + moff + (long)oc * D +
-                                                           (2 * s + h) * 8);
-                af[f].v[s] = *reinterpret_cast<bf16x8 *>(&y);
-            }
-        }
-        if constexpr (MODE == M_FINAL) {
-            uint4 z = *reinterpret_cast<const uint4 *>(reinterpret_cast<const unsigned char *>(a.poB) +
-                                                       ((long)n * a.ldp + oc) * 32 + h * 16);
-            pob[f] = *reinterpret_cast<bf16x8 *>(&z);
-        }
-#pragma unroll
-        for (int j = 0; j < D / 32; ++j)
-#pragma unroll
-            for (int r = 0; r < 16; ++r) outm[f][j][r] = 0.f;
-    }
-
-    const int kbase = (o_blk - W) >= 0 ? (o_blk - W) / TT : -((W - o_blk + TT - 1) / TT);
-    const int kend = (o_blk + 32 * FR - 1 + W) / TT;
-    const int S = kend - kbase + 1;
-    const int klast = (Lt - 1) / TT;
-
-    // one tile pair in flight between global memory and LDS (plain arrays: a struct holding
-    // them ends up in scratch memory)
-    auto g_load = [&](uint4 (&gy)[RG::CPT], uint4 (&gb)[RG::CPT], float &gvy, uint4 &gpk, int k) {
-#pragma unroll
-        for (int q = 0; q < RG::CPT; ++q) {
-            int idx = tid + q * NTHREADS;
-            if (idx >= RG::CHUNKS) idx = RG::CHUNKS - 1;
-            const unsigned row = (unsigned)min(max(k * TT + idx / RG::CPR, 0), Lt - 1);
-            const unsigned off = row * (unsigned)(D * 2) + (unsigned)(idx % RG::CPR) * 16u;
-            gy[q] = *reinterpret_cast<const uint4 *>(Yb + off);
-            gb[q] = *reinterpret_cast<const uint4 *>(Bb + off);
-        }
-        const unsigned tv = (unsigned)min(max(k * TT + (tid & (TT - 1)), 0), Lt - 1);
-        gvy = ytp[tv];
-        if constexpr (MODE == M_FINAL) {
-            // 64 pieces of 16 bytes per tile: every wavefront requests them (same addresses; a
-            // request under a condition would cost a full wait), the first one stores them
-            const unsigned tp = (unsigned)min(max(k * TT + ((tid & 63) >> 1), 0), Lt - 1);
-            gpk = *reinterpret_cast<const uint4 *>(reinterpret_cast<const unsigned char *>(a.qtA) +
-                                                   ((long)n * a.ldp + tp) * 32 + (tid & 1) * 16);
-        }
-    };
-    // rows outside [0, Lt) keep whatever the clamped fetch brought: their potential is -inf,
-    // so their plan entries are exactly zero and finite data times zero adds nothing
-    auto s_store = [&](const uint4 (&gy)[RG::CPT], const uint4 (&gb)[RG::CPT], float gvy, uint4 gpk, int j, int k) {
-        unsigned char *sl = smem + (j % RG::NSLOT) * RG::SLOT;
-#pragma unroll
-        for (int q = 0; q < RG::CPT; ++q) {
-            const int idx = tid + q * NTHREADS;
-            if (idx < RG::CHUNKS) {
-                const int off = (idx / RG::CPR) * RG::ROWB + (idx % RG::CPR) * 16;
-                *reinterpret_cast<uint4 *>(sl + RG::OFF_Y + off) = gy[q];
-                *reinterpret_cast<uint4 *>(sl + RG::OFF_B + off) = gb[q];
-            }
-        }
-        if (tid < TT) {
-            const bool live = k >= 0 && k * TT + tid < Lt;
-            reinterpret_cast<float *>(sl + RG::OFF_VY)[tid] = live ? fmaf(gvy, LOG2E, m2) : -INFINITY;
-        }
-        if constexpr (MODE == M_FINAL) {
-            if (tid < 64)   // (rows outside the matrix: clamped data, multiplied by a zero plan entry)
-                *reinterpret_cast<uint4 *>(sl + ((tid & 1) ? RG::OFF_B : RG::OFF_Y) + (tid >> 1) * RG::ROWB +
-                                           RG::OFF_PK) = gpk;
-        }
-    };
-
-    {
-        uint4 fy[RG::LEAD + 1][RG::CPT], fb[RG::LEAD + 1][RG::CPT];
-        float fvy[RG::LEAD + 1];
-        uint4 fvq[RG::LEAD + 1];
-#pragma unroll
-        for (int j = 0; j <= RG::LEAD; ++j) g_load(fy[j], fb[j], fvy[j], fvq[j], kbase + j);
-#pragma unroll
-        for (int j = 0; j <= RG::LEAD; ++j) s_store(fy[j], fb[j], fvy[j], fvq[j], j, kbase + j);
-    }
-    __syncthreads();
-    uint4 ny[RG::CPT], nb[RG::CPT];
-    float nvy = 0.f;
-    uint4 nvq = make_uint4(0, 0, 0, 0);
-
-    // per-lane LDS offsets: fragment rows for the score / Z products, and the 8-byte pieces
-    // this lane addresses in a transposing read (row 4h + (lane & 15) / 4 of a 16-row block,
-    // columns 16 (lane / 16 & 1) + 4 (lane & 3), + 32 per output column tile)
-    const int rd_a = c * RG::ROWB + h * 16;
-    const int rd_t = (4 * h + ((lane & 15) >> 2)) * RG::ROWB + (16 * ((lane >> 4) & 1) + 4 * (lane & 3)) * 2;
-    typedef __bf16 bf16x4v __attribute__((ext_vector_type(4)));
-
-    for (int s = 0; s < S; ++s) {
-        const int jnew = s + 1 + RG::LEAD;
-        const bool more = (s + 1 < S);
-        if (more) g_load(ny, nb, nvy, nvq, kbase + jnew);
-
-        const int j = s + wave * FR;
-        const int k = kbase + j;
-        if (k >= 0 && k <= klast) {
-            const unsigned char *sl = smem + (j % RG::NSLOT) * RG::SLOT;
-            const int t0 = k * TT;
-            // this tile's fragments (score rows, Z rows) and staged potentials, read once for
-            // all FR owner fragments
-            bf16x8 yfr[KS], bfr[MODE == M_FINAL ? KS : 1];
-#pragma unroll
-            for (int ks = 0; ks < KS; ++ks) {
-                yfr[ks] = *reinterpret_cast<const bf16x8 *>(sl + RG::OFF_Y + rd_a + 32 * ks);
-                if constexpr (MODE == M_FINAL)
-                    bfr[ks] = *reinterpret_cast<const bf16x8 *>(sl + RG::OFF_B + rd_a + 32 * ks);
-            }
-            f32x16 yv;
-#pragma unroll
-            for (int q = 0; q < 4; ++q) {
-                float4 v4 = *reinterpret_cast<const float4 *>(sl + RG::OFF_VY + (8 * q + 4 * h) * 4);
-                yv[4 * q + 0] = v4.x; yv[4 * q + 1] = v4.y; yv[4 * q + 2] = v4.z; yv[4 * q + 3] = v4.w;
-            }
-            bf16x8 qpk;   // M_FINAL: row c of the tile, pack columns 8h .. 8h + 7
-            if constexpr (MODE == M_FINAL)
-                qpk = *reinterpret_cast<const bf16x8 *>(sl + (h ? RG::OFF_B : RG::OFF_Y) + c * RG::ROWB + RG::OFF_PK);
-            bf16x8 pf[FR][2];
-#pragma unroll
-            for (int f = 0; f < FR; ++f) {
-                const int of = o_w + 32 * f;
-                const bool interior = (of + 31 - t0 <= W) && (t0 + TT - 1 - of <= W);
-                // scores start from the staged potentials when the scale is folded into the operand
-                f32x16 acc = yv;
-#pragma unroll
-                for (int ks = 0; ks < KS; ++ks)
-                    acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(yfr[ks], xf[f].v[ks], acc, 0, 0, 0);
-                float e[16];
-#pragma unroll
-                for (int r = 0; r < 16; ++r) e[r] = acc[r];
-                if (!interior) {   // also covers a tile that misses this fragment's band entirely
-                    const int lo = of + c - W - t0 - 4 * h;
-                    const unsigned span = 2u * (unsigned)W;
-#pragma unroll
-                    for (int r = 0; r < 16; ++r) {
-                        const int off = 8 * (r >> 2) + (r & 3);
-                        if ((unsigned)(off - lo) > span) e[r] = -INFINITY;
-                    }
-                }
-#pragma unroll
-                for (int r = 0; r < 16; ++r) e[r] = fast_exp2(e[r]);
-
-                if constexpr (MODE == M_FINAL) {
-                    f32x16 z;
-#pragma unroll
-                    for (int r = 0; r < 16; ++r) z[r] = 0.f;
-#pragma unroll
-                    for (int ks = 0; ks < KS; ++ks)
-                        z = __builtin_amdgcn_mfma_f32_32x32x16_bf16(bfr[ks], af[f].v[ks], z, 0, 0, 0);
-                    z = __builtin_amdgcn_mfma_f32_32x32x16_bf16(qpk, pob[f], z, 0, 0, 0);   // - sum_k po_k qt_k
-#pragma unroll
-                    for (int r = 0; r < 16; ++r) e[r] *= z[r];
-                }
-#pragma unroll
-                for (int m = 0; m < 2; ++m)
-#pragma unroll
-                    for (int r = 0; r < 8; ++r) pf[f][m][r] = (__bf16)e[8 * m + r];
-            }
-
-            // second product: out[dv, o] += sum_t M[t][dv] * e[t, o], M = payload (M_APPLY) or the
-            // other-side score rows themselves (M_FINAL); the transposed fragment of M serves
-            // every owner fragment
-            const unsigned char *pm = sl + (MODE == M_FINAL ? RG::OFF_Y : RG::OFF_B) + rd_t;
-#pragma unroll
-            for (int m = 0; m < 2; ++m)
-#pragma unroll
-                for (int dvt = 0; dvt < D / 32; ++dvt) {
-                    bf16x4v lo4 = __builtin_amdgcn_ds_read_tr16_b64_v4bf16(
-                        (bf16x4v __attribute__((address_space(3))) *)(pm + (16 * m) * RG::ROWB + dvt * 64));
-                    bf16x4v hi4 = __builtin_amdgcn_ds_read_tr16_b64_v4bf16(
-                        (bf16x4v __attribute__((address_space(3))) *)(pm + (16 * m + 8) * RG::ROWB + dvt * 64));
-                    bf16x8 am = {lo4[0], lo4[1], lo4[2], lo4[3], hi4[0], hi4[1], hi4[2], hi4[3]};
-#pragma unroll
-                    for (int f = 0; f < FR; ++f)   // (a fragment the tile misses has e == 0 throughout)
-                        outm[f][dvt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(am, pf[f][m], outm[f][dvt], 0, 0, 0);
-                }
-        }
-        if (more) s_store(ny, nb, nvy, nvq, jnew, kbase + jnew);
-        __syncthreads();
-    }
-
-    // epilogue: owner-side factor, store (and the <dot_mat_o, out_o> reduction for dV)
-#pragma unroll
-    for (int f = 0; f < FR; ++f) {
-        const int o = o_w + 32 * f + c;
-        const int oc = min(o, L - 1);
-        const float xso = xsp[min(o, Le - 1)];
-        const bool dead = o >= Le || xso == -INFINITY;   // beyond the valid length, or an inactive token: zeros
-        float fac = fast_exp2((xso - mblk) * LOG2E);
-        if constexpr (MODE == M_FINAL) fac *= a.cs;
-        float pdb = 0.f;   // plan entry of the spoke (o, dustbin) when the dustbin carries a payload
-        if constexpr (MODE == M_APPLY)
-            if (a.pay_db) pdb = __expf(a.spoke_own.p[n * a.spoke_own.stride + oc] + xsp[oc] + ytp[L]);
-        T *orow = reinterpret_cast<T *>(a.out_mat) + moff + (long)oc * D;
-        const T *drow = a.dot_mat ? reinterpret_cast<const T *>(a.dot_mat) + moff + (long)oc * D : nullptr;
-        float dot = 0.f;
-#pragma unroll
-        for (int j = 0; j < D / 32; ++j)
-#pragma unroll
-            for (int q = 0; q < 4; ++q) {
-                const int dv = 32 * j + 8 * q + 4 * h;
-                float v0 = outm[f][j][4 * q + 0] * fac, v1 = outm[f][j][4 * q + 1] * fac;
-                float v2 = outm[f][j][4 * q + 2] * fac, v3 = outm[f][j][4 * q + 3] * fac;
-                if constexpr (MODE == M_APPLY) {
-                    if (a.pay_db) {
-                        const float4 pv = *reinterpret_cast<const float4 *>(a.pay_db + (long)n * D + dv);
-                        v0 = fmaf(pdb, pv.x, v0); v1 = fmaf(pdb, pv.y, v1);
-                        v2 = fmaf(pdb, pv.z, v2); v3 = fmaf(pdb, pv.w, v3);
-                    }
-                }
-                if (dead) v0 = v1 = v2 = v3 = 0.f;
-                if (o < L) {
-                    store4<T>(orow + dv, v0, v1, v2, v3);
-                    if constexpr (MODE == M_APPLY) {
-                        if (drow && !dead) {
-                            float dd[4];
-                            load4<T>(drow + dv, dd);
-                            dot += dd[0] * v0 + dd[1] * v1 + dd[2] * v2 + dd[3] * v3;
-                        }
-                    }
-                }
-            }
-        if constexpr (MODE == M_APPLY) {
-            if (a.dot_mat) {
-                dot += __shfl_xor(dot, 32);
-                if (h == 0 && o < L) {
-                    if (a.olog.p && !dead) dot *= __expf(-a.olog.p[n * a.olog.stride + o]);
-                    a.dot_out.p[n * a.dot_out.stride + o] = dot;
-                }
-            }
-        }
-    }
-}
-
-// ------------------------------------------------------------------ small kernels
-__global__ void fill_kernel(float *p, long per, long stride, int nprob, float val)
-{
-    long i = (long)blockIdx.x * blockDim.x + threadIdx.x;
-    if (i < per * nprob) p[(i / per) * stride + (i % per)] = val;
-}
-
-// g_o = <A_o, B_o> for o below the problem's valid length (len[n / nh], or L if len is null);
-// g = 0 from there to Lp.  A row is read by D * sizeof(T) / 16 neighbouring
-// lanes, 16 bytes each (whole 128-byte lines per group of lanes), and reduced across them.
-template <typename T, int D>
-__global__ void rowdot_kernel(const T *A, const T *Bm, float *g, long gstride, int L, int Lp, const int *len, int nh)
-{
-    constexpr int LPR = D * (int)sizeof(T) / 16;   // lanes per row: 4 ... 32, a power of two
-    constexpr int EPL = 16 / (int)sizeof(T);       // elements per lane
-    const int n = blockIdx.y;
-    const long p = (long)blockIdx.x * blockDim.x + threadIdx.x;
-    const int o = (int)(p / LPR), sub = (int)(p % LPR);
-    float acc = 0.f;
-    const int Lv = len ? min(max(len[n / nh], 0), L) : L;
-    if (o < Lv) {
-        const T *pa = A + ((long)n * L + o) * D + sub * EPL, *pb = Bm + ((long)n * L + o) * D + sub * EPL;
-#pragma unroll
-        for (int k = 0; k < EPL; k += 4) {
-            float x[4], y[4];
-            load4<T>(pa + k, x);
-            load4<T>(pb + k, y);
-            acc += x[0] * y[0] + x[1] * y[1] + x[2] * y[2] + x[3] * y[3];
-        }
-    }
-#pragma unroll
-    for (int m = LPR / 2; m >= 1; m >>= 1) acc += __shfl_xor(acc, m);
-    if (sub == 0 && o < Lp) g[n * gstride + o] = acc;
-}
-
-// ---- learned dustbin token (Sec. "Single-Active-Dustbin Bridge"): the O(L d) work on the spokes
-// out[n][o] = scale <M[n][o], x[n]> for o < L, out[n][L] = scale <x[n], xc[n]> (the corner).
-// LPR lanes per row, 16 bytes each, like rowdot_kernel.
-template <typename T, int D>
-__global__ void spoke_scores_kernel(const T *M, const float *x, const float *xc, float *out, long ostride, int L,
-                                    float scale)
-{
-    constexpr int LPR = D * (int)sizeof(T) / 16, EPL = 16 / (int)sizeof(T);
-    const int n = blockIdx.y;
-    const long p = (long)blockIdx.x * blockDim.x + threadIdx.x;
-    const int o = (int)(p / LPR), sub = (int)(p % LPR);
-    float acc = 0.f;
-    if (o <= L) {
-        const float *xv = x + (long)n * D + sub * EPL;
-#pragma unroll
-        for (int k = 0; k < EPL; k += 4) {
-            float a4[4];
-            if (o < L) load4<T>(M + ((long)n * L + o) * D + sub * EPL + k, a4);
-            else { const float *c4 = xc + (long)n * D + sub * EPL + k; a4[0] = c4[0]; a4[1] = c4[1]; a4[2] = c4[2]; a4[3] = c4[3]; }
-            acc += a4[0] * xv[k] + a4[1] * xv[k + 1] + a4[2] * xv[k + 2] + a4[3] * xv[k + 3];
-        }
-    }
-#pragma unroll
-    for (int m = LPR / 2; m >= 1; m >>= 1) acc += __shfl_xor(acc, m);
-    if (sub == 0 && o <= L) out[n * ostride + o] = scale * acc;
-}
-
-// Weights of a weighted row sum, two kinds:
-//   plan : w_o = exp(spoke[o] + x[o] + yL)   (plan entries of the spokes (o, dustbin); yL = y[L])
-//   given: w_o = wv[o]
-// partial[n][chunk][dv] = sum over the chunk's rows o of w_o M[n][o][dv]; rows in chunks of WS_ROWS.
-constexpr int WS_ROWS = 1024;
-template <typename T, int D>
-__global__ __launch_bounds__(256) void wsum_kernel(const T *M, Vec wv, Vec spoke, Vec x, Vec y, float *partial, int L)
-{
-    constexpr int TPR = D / 4;            // threads per row, four columns each
-    constexpr int RPI = 256 / TPR;        // rows per iteration
-    __shared__ float red[256][4];
-    const int n = blockIdx.y, chunk = blockIdx.x, tid = threadIdx.x;
-    const int col = (tid % TPR) * 4, r0 = tid / TPR;
-    const int o_end = min(L, (chunk + 1) * WS_ROWS);
-    float yL = 0.f;
-    if (!wv.p) yL = y.p[n * y.stride + L];
-    float acc[4] = {0.f, 0.f, 0.f, 0.f};
-    for (int o = chunk * WS_ROWS + r0; o < o_end; o += RPI) {
-        const float w = wv.p ? wv.p[n * wv.stride + o]
-                             : __expf(spoke.p[n * spoke.stride + o] + x.p[n * x.stride + o] + yL);
-        float m4[4];
-        load4<T>(M + ((long)n * L + o) * D + col, m4);
-        acc[0] = fmaf(w, m4[0], acc[0]); acc[1] = fmaf(w, m4[1], acc[1]);
-        acc[2] = fmaf(w, m4[2], acc[2]); acc[3] = fmaf(w, m4[3], acc[3]);
-    }
-#pragma unroll
-    for (int k = 0; k < 4; ++k) red[tid][k] = acc[k];
-    __syncthreads();
-    if (tid < TPR) {
-        float t4[4] = {0.f, 0.f, 0.f, 0.f};
-        for (int r = 0; r < RPI; ++r)
-#pragma unroll
-            for (int k = 0; k < 4; ++k) t4[k] += red[r * TPR + tid][k];
-        float *dst = partial + ((long)n * gridDim.x + chunk) * D + col;
-        dst[0] = t4[0]; dst[1] = t4[1]; dst[2] = t4[2]; dst[3] = t4[3];
-    }
-}
-// out[n][dv] = scale (sum_chunk partial[n][chunk][dv] + wc[n] xc[n][dv]); if dotv is given also
-// dot_out[n] = <dotv[n], out[n]>.  wc_at: index of the corner weight in wc (null: no corner).
-template <int D>
-__global__ void wsum_final_kernel(const float *partial, int nchunk, Vec wc, int wc_at, const float *xc, float scale,
-                                  float *out, const float *dotv, VecOut dot_out, int dot_at)
-{
-    const int n = blockIdx.x, dv = threadIdx.x;   // D threads
-    float acc = 0.f;
-    for (int c = 0; c < nchunk; ++c) acc += partial[((long)n * nchunk + c) * D + dv];
-    if (wc.p) acc = fmaf(wc.p[n * wc.stride + wc_at], xc[(long)n * D + dv], acc);
-    acc *= scale;
-    out[(long)n * D + dv] = acc;
-    if (dotv) {
-        __shared__ float red[D];
-        red[dv] = acc * dotv[(long)n * D + dv];
-        __syncthreads();
-        if (dv == 0) {
-            float t = 0.f;
-            for (int k = 0; k < D; ++k) t += red[k];
-            dot_out.p[n * dot_out.stride + dot_at] = t;
-        }
-    }
-}
-
-// Score cotangent on the spokes (Prop. 2 on the augmented support), one-reference form:
-//   sbr[i] = P_RR(i, d_k) (<dO_i, v_db> - sum_k rowp_k[i] colp_k[L])        i < L
-//   sbc[j] = P_RR(d_q, j) (            - sum_k rowp_k[L] colp_k[j])          j < L
-//   sbr[L] = sbc[L] = P_RR(d_q, d_k) (- sum_k rowp_k[L] colp_k[L])
-// with P_RR(i, d_k) = exp(SQ[i] + u_R[i] + v_R[L]), P_RR(d_q, j) = exp(SK[j] + u_R[L] + v_R[j]).
-template <typename T, int D>
-__global__ void spoke_sbar_kernel(const T *G, const float *vdb, Vec uR, Vec vR, Vec SQ, Vec SK, const float4 *rowp,
-                                  const float4 *colp, int nq, long ldp, float *sbr, float *sbc, long ostride, int L)
-{
-    constexpr int LPR = D * (int)sizeof(T) / 16, EPL = 16 / (int)sizeof(T);
-    const int n = blockIdx.y;
-    const long p = (long)blockIdx.x * blockDim.x + threadIdx.x;
-    const int o = (int)(p / LPR), sub = (int)(p % LPR);
-    float z = 0.f;
-    if (o < L) {
-        const float *xv = vdb + (long)n * D + sub * EPL;
-#pragma unroll
-        for (int k = 0; k < EPL; k += 4) {
-            float a4[4];
-            load4<T>(G + ((long)n * L + o) * D + sub * EPL + k, a4);
-            z += a4[0] * xv[k] + a4[1] * xv[k + 1] + a4[2] * xv[k + 2] + a4[3] * xv[k + 3];
-        }
-    }
-#pragma unroll
-    for (int m = LPR / 2; m >= 1; m >>= 1) z += __shfl_xor(z, m);
-    if (sub != 0 || o > L) return;
-    const float4 *ro = rowp + ((long)n * ldp + o) * nq, *co = colp + ((long)n * ldp + o) * nq;
-    const float4 *rL = rowp + ((long)n * ldp + L) * nq, *cL = colp + ((long)n * ldp + L) * nq;
-    float mr = 0.f, mc = 0.f;   // sum_k rowp_k[o] colp_k[L], sum_k rowp_k[L] colp_k[o]
-    for (int g = 0; g < nq; ++g) {
-        const float4 a = ro[g], b = cL[g], c = rL[g], d = co[g];
-        mr += a.x * b.x + a.y * b.y + a.z * b.z + a.w * b.w;
-        mc += c.x * d.x + c.y * d.y + c.z * d.z + c.w * d.w;
-    }
-    const float uRo = uR.p[n * uR.stride + o], vRo = vR.p[n * vR.stride + o];
-    const float uRL = uR.p[n * uR.stride + L], vRL = vR.p[n * vR.stride + L];
-    if (o < L) {
-        sbr[n * ostride + o] = __expf(SQ.p[n * SQ.stride + o] + uRo + vRL) * (z - mr);
-        sbc[n * ostride + o] = -__expf(SK.p[n * SK.stride + o] + uRL + vRo) * mc;
-    } else {
-        const float c = -__expf(SQ.p[n * SQ.stride + L] + uRL + vRL) * mr;
-        sbr[n * ostride + L] = c;
-        sbc[n * ostride + L] = c;
-    }
-}
-
-// M[n][o][:] += scale w[n][o] x[n][:] for o < L (the spoke part of dQ / dK), storage type T
-template <typename T, int D>
-__global__ void spoke_axpy_kernel(T *M, Vec w, const float *x, float scale, int L)
-{
-    constexpr int TPR = D / 4;
-    const int n = blockIdx.y;
-    const long p = (long)blockIdx.x * blockDim.x + threadIdx.x;
-    const int o = (int)(p / TPR), col = (int)(p % TPR) * 4;
-    if (o >= L) return;
-    const float f = scale * w.p[n * w.stride + o];
-    const float *xv = x + (long)n * D + col;
-    T *dst = M + ((long)n * L + o) * D + col;
-    float m4[4];
-    load4<T>(dst, m4);
-    store4<T>(dst, fmaf(f, xv[0], m4[0]), fmaf(f, xv[1], m4[1]), fmaf(f, xv[2], m4[2]), fmaf(f, xv[3], m4[3]));
-}
-
-// Start of the base solve with inactive tokens: u0[i] = -inf where mask_q[b][i] == 0,
-// v0[j] = -inf where mask_k[b][j] == 0 (elsewhere they keep their zeros).  UV slots 0 and 1.
-__global__ void mask_fill_kernel(float *UV, long us, int Lp, int L, const unsigned char *mq, const unsigned char *mk,
-                                 int nh)
-{
-    const int n = blockIdx.y;
-    const int i = blockIdx.x * blockDim.x + threadIdx.x;
-    if (i >= L) return;
-    const long m = (long)(n / nh) * L + i;
-    if (mq && !mq[m]) UV[n * us + i] = -INFINITY;
-    if (mk && !mk[m]) UV[n * us + Lp + i] = -INFINITY;
-}
-
-// p[n][j] *= f for j < per (the base potentials between two stages of a continuation schedule)
-__global__ void scale_kernel(float *p, long per, long stride, int nprob, float f)
-{
-    long i = (long)blockIdx.x * blockDim.x + threadIdx.x;
-    if (i < per * nprob) p[(i / per) * stride + (i % per)] *= f;
-}
-
-// *out = max(*out, max_i |x_i|) over n elements (a NaN counts as +inf).  Non-negative floats
-// order like their bit patterns, so the maximum is taken on unsigned integers.
-template <typename T>
-__global__ __launch_bounds__(256) void absmax_kernel(const T *x, long n, float *out)
-{
-    float m = 0.f;
-    for (long i = (long)blockIdx.x * blockDim.x + threadIdx.x; i < n; i += (long)gridDim.x * blockDim.x) {
-        const float v = fabsf((float)x[i]);
-        m = (v == v) ? fmaxf(m, v) : INFINITY;
-    }
-#pragma unroll
-    for (int s = 32; s >= 1; s >>= 1) m = fmaxf(m, __shfl_xor(m, s));
-    __shared__ float red[4];
-    if ((threadIdx.x & 63) == 0) red[threadIdx.x >> 6] = m;
-    __syncthreads();
-    if (threadIdx.x == 0) {
-        m = fmaxf(fmaxf(red[0], red[1]), fmaxf(red[2], red[3]));
-        atomicMax(reinterpret_cast<unsigned int *>(out), __float_as_uint(m));
-    }
-}
-
-// out[n][j] = seed[n][j] / b_j for j < Lp: a cotangent handed in from outside enters the reverse
-// recurrences in the form the workspace keeps (divided by the marginal target).
-__global__ void seed_kernel(const float *seed, const float *olog, float *out, long ostride, int Lp)
-{
-    const int n = blockIdx.y;
-    const int j = blockIdx.x * blockDim.x + threadIdx.x;
-    if (j >= Lp) return;
-    float r = seed[(long)n * Lp + j];
-    if (olog) r *= __expf(-olog[(long)n * Lp + j]);
-    out[n * ostride + j] = r;
-}
-
-// Qs = bf16(scale * Q): the score scale log2(e)/(eps sqrt d) folded into one operand once,
-// so that no sweep pays a multiply per edge for it.  8 elements per thread.
-__global__ void prescale_kernel(const __bf16 *src, __bf16 *dst, long n8, float scale)
-{
-    long i = (long)blockIdx.x * blockDim.x + threadIdx.x;
-    if (i >= n8) return;
-    uint4 raw = reinterpret_cast<const uint4 *>(src)[i];
-    bf16x8 v = *reinterpret_cast<bf16x8 *>(&raw);
-#pragma unroll
-    for (int e = 0; e < 8; ++e) v[e] = (__bf16)((float)v[e] * scale);
-    reinterpret_cast<uint4 *>(dst)[i] = *reinterpret_cast<uint4 *>(&v);
-}
-
-// Modifier packs of Prop. 2 for a tail of depth R.  With a_t = exp(u_t - u_R), b_t = exp(v_t - v_R)
-// the score cotangent is P_RR . [Z - sum_k row_k(i) col_k(j)] over 2R rank-1 terms, two per
-// tail step t = R ... 1:
-//     row = a_t,           col = b_t vbar_t        (the factor P_tt     . (1 vbar_t^T))
-//     row = a_t ubar_t,    col = b_{t-1}           (the factor P_t,t-1  . (ubar_t 1^T))
-// (R = 2: row = (1, ubar2, alpha, alpha ubar1), col = (vbar2, beta, beta vbar1, delta).)
-// Written as groups of four floats (generic final sweep) or, for the ring kernel (R <= 2), as
-// 16 bf16 columns per index in two forms: "A" for the side that is streamed ([hi, lo, hi] per
-// value) and "B" for the side that owns the rows ([-hi, -hi, -lo]); an A row times a B row is
-// then -sum_k (hi hi + lo hi + hi lo) = -sum_k row_k col_k to about 2^-16 relative.
-// aug = rowA, rowB, colA, colB, each [N][ldp][16].  Workspace vectors: vec 1 + 2(R - t) is
-// vbar_t, vec 2 + 2(R - t) is ubar_t.
-__device__ __forceinline__ void pack_cols(const float (&x)[4], __bf16 *A, __bf16 *B)
-{
-#pragma unroll
-    for (int k = 0; k < 4; ++k) {
-        const __bf16 hi = (__bf16)x[k];
-        const __bf16 lo = (__bf16)(x[k] - (float)hi);
-        A[3 * k + 0] = hi; A[3 * k + 1] = lo; A[3 * k + 2] = hi;
-        B[3 * k + 0] = (__bf16)(-(float)hi); B[3 * k + 1] = (__bf16)(-(float)hi); B[3 * k + 2] = (__bf16)(-(float)lo);
-    }
-#pragma unroll
-    for (int k = 12; k < 16; ++k) { A[k] = (__bf16)0.f; B[k] = (__bf16)0.f; }
-}
-// direct != 0 (comparator): a group holds the two terms of one tail step as (log2 modifier, weight)
-// pairs, row side (l_t, 1, l_t, ubar_t), column side (m_t, vbar_t, m_{t-1}, 1) with
-// l_t = (u_t - u_R) log2 e, m_t = (v_t - v_R) log2 e; nq = R groups.
-__global__ void packs_kernel(const float *UV, int Lp, int R, const float *vecs, long nldw, long wstride,
-                             float *rowp, float *colp, int nq, __bf16 *aug, long ldp, long nldp, int direct,
-                             int both)
-{
-    // both != 0: the float groups are written next to the bf16 columns (the spokes of a learned
-    // dustbin token read them)
-    const int n = blockIdx.y;
-    const int i = blockIdx.x * blockDim.x + threadIdx.x;
-    if (i >= Lp) return;
-    const float *uv = UV + (long)n * 2 * (R + 1) * Lp;
-    const long w = n * wstride + i;
-    const float uR = uv[(2 * R) * Lp + i], vR = uv[(2 * R + 1) * Lp + i];
-    float r4[4] = {0.f, 0.f, 0.f, 0.f}, c4[4] = {0.f, 0.f, 0.f, 0.f};   // the first four terms (ring kernel)
-    float *rp = rowp + (n * ldp + i) * 4L * nq, *cp = colp + (n * ldp + i) * 4L * nq;
-    for (int q = 0; q < R; ++q) {   // q = R - t
-        const int t = R - q;
-        // an inactive token (potential -inf on its side) has all-zero modifiers
-        const bool rdead = uR == -INFINITY, cdead = vR == -INFINITY;
-        const float at = rdead ? 0.f : __expf(uv[(2 * t) * Lp + i] - uR);
-        const float bt = cdead ? 0.f : __expf(uv[(2 * t + 1) * Lp + i] - vR);
-        const float bp = cdead ? 0.f : __expf(uv[(2 * t - 1) * Lp + i] - vR);
-        const float vb = vecs[(1 + 2 * q) * nldw + w], ub = vecs[(2 + 2 * q) * nldw + w];
-        if (direct) {
-            const float lt = rdead ? 0.f : (uv[(2 * t) * Lp + i] - uR) * LOG2E;
-            const float mt = cdead ? 0.f : (uv[(2 * t + 1) * Lp + i] - vR) * LOG2E;
-            const float mp = cdead ? 0.f : (uv[(2 * t - 1) * Lp + i] - vR) * LOG2E;
-            rp[4 * q] = lt; rp[4 * q + 1] = rdead ? 0.f : 1.f; rp[4 * q + 2] = lt; rp[4 * q + 3] = ub;
-            cp[4 * q] = mt; cp[4 * q + 1] = vb;  cp[4 * q + 2] = mp; cp[4 * q + 3] = cdead ? 0.f : 1.f;
-            continue;
-        }
-        if (!aug || both) {
-            rp[2 * q] = at;          cp[2 * q] = bt * vb;
-            rp[2 * q + 1] = at * ub; cp[2 * q + 1] = bp;
-        }
-        if (aug && q < 2) {
-            if (q == 0) { r4[0] = at; c4[0] = bt * vb; r4[1] = at * ub; c4[1] = bp; }
-            else { r4[2] = at; c4[2] = bt * vb; r4[3] = at * ub; c4[3] = bp; }
-        }
-    }
-    if (direct) return;   // (R groups, all written)
-    if (!aug || both)
-        for (int k = 2 * R; k < 4 * nq; ++k) { rp[k] = 0.f; cp[k] = 0.f; }   // pad the last group
-    if (aug) {
-        __align__(16) __bf16 A[16], B[16];
-        const long e = (n * ldp + i) * 16;
-        pack_cols(r4, A, B);
-#pragma unroll
-        for (int q = 0; q < 2; ++q) {
-            reinterpret_cast<uint4 *>(aug + 0 * nldp * 16 + e)[q] = reinterpret_cast<const uint4 *>(A)[q];
-            reinterpret_cast<uint4 *>(aug + 1 * nldp * 16 + e)[q] = reinterpret_cast<const uint4 *>(B)[q];
-        }
-        pack_cols(c4, A, B);
-#pragma unroll
-        for (int q = 0; q < 2; ++q) {
-            reinterpret_cast<uint4 *>(aug + 2 * nldp * 16 + e)[q] = reinterpret_cast<const uint4 *>(A)[q];
-            reinterpret_cast<uint4 *>(aug + 3 * nldp * 16 + e)[q] = reinterpret_cast<const uint4 *>(B)[q];
-        }
-    }
-}
-
-// Dustbin element of a sweep result: the extra row (column) is joined to every
-// index 0..L of the other side by an edge of score s_t (the scalar sdb, or spoke[t] when
-// the dustbin is a learned token).
-//   w == null: out[L] = -log sum_{t<=L} exp(s_t + y_t)
-//   else     : out[L] = pre - exp(x[L]) sum_{t<=L} exp(s_t + y_t) w_t   (pre = 0)
-__global__ __launch_bounds__(1024) void dustbin_kernel(Vec y, Vec w, Vec x, VecOut out, int L, float sdb, Vec spoke)
-{
-    __shared__ float sm[32], ss[32];
-    const int n = blockIdx.x, tid = threadIdx.x, lane = tid & 63, wv = tid >> 6;
-    const float *yp = y.p + n * y.stride;
-    const float *sp = spoke.p ? spoke.p + n * spoke.stride : nullptr;
-    if (sp) sdb = 0.f;
-    float m = -INFINITY;
-    for (int t = tid; t <= L; t += blockDim.x) m = fmaxf(m, yp[t] + (sp ? sp[t] : 0.f));
-    for (int s = 32; s >= 1; s >>= 1) m = fmaxf(m, __shfl_xor(m, s));
-    if (lane == 0) sm[wv] = m;
-    __syncthreads();
-    m = sm[0];
-    for (int i = 1; i < (int)(blockDim.x >> 6); ++i) m = fmaxf(m, sm[i]);
-    float acc = 0.f;
-    for (int t = tid; t <= L; t += blockDim.x) {
-        float e = __expf(yp[t] + (sp ? sp[t] : 0.f) - m);
-        acc += w.p ? e * w.p[n * w.stride + t] : e;
-    }
-    for (int s = 32; s >= 1; s >>= 1) acc += __shfl_xor(acc, s);
-    if (lane == 0) ss[wv] = acc;
-    __syncthreads();
-    if (tid == 0) {
-        float tot = 0.f;
-        for (int i = 0; i < (int)(blockDim.x >> 6); ++i) tot += ss[i];
-        float r;
-        if (!w.p) r = -(sdb + m + __logf(tot));
-        else r = -__expf(x.p[n * x.stride + L] + sdb + m) * tot;
-        out.p[n * out.stride + L] = r;
-    }
-}
 
 // ------------------------------------------------------------------ host side
 struct Problem {

@@ -1,0 +1,593 @@
+// The ring kernels: vector sweeps (scaling sweep, band mat-vec) and bf16 matrix sweeps (output map / dV, final
+// sweeps) on a skewed ring of tiles in LDS.
+#pragma once
+#include "ska_common.h"
+
+namespace {
+
+// ------------------------------------------------------------------ vector sweeps
+// Scaling sweep (M_LSE) and band mat-vec (M_MATVEC): the result is one scalar per
+// owner index, so the only state a wavefront carries is FR owner fragments and FR
+// partial sums.  Wavefront w owns rows [o_blk + 32 FR w, +32 FR) and needs other-side
+// tiles kbase + FR w ... kend + FR w: the same count S for every wavefront, shifted by
+// FR per wavefront.  The tiles therefore go through an LDS ring with that skew: at
+// step s wavefront w works on tile kbase + s + FR w, so all wavefronts are busy in
+// every step, and one new tile enters the ring per step (one barrier per step).
+template <typename T, int D, int MODE, int FR> struct VRing {
+    using TL = Tile<T, D>;
+    static constexpr int LEAD = FR * (NWAVES - 1);          // tiles between first and last wavefront
+    static constexpr int NSLOT = (LEAD + 2 <= 8) ? 8 : 16;  // power of two >= LEAD + 2
+    // tile rows in LDS: bf16 rows carry 16 bytes of padding (the 32 rows an MFMA operand
+    // read touches then fall on distinct banks, and the chunks of one row sit at fixed
+    // distances: one address register per step); fp32 rows are padded by four floats
+    static constexpr int ROWB = TL::IS_BF16 ? D * 2 + 16 : f32_row_floats<D>() * 4;
+    static constexpr int OFF_VY = 32 * ROWB;
+    static constexpr int OFF_VW = OFF_VY + TT * 4;
+    static constexpr int SLOT = OFF_VW + TT * 4;
+    static constexpr int BYTES = NSLOT * SLOT;
+};
+
+template <typename T, int D, int MODE, int FR>
+__global__ __launch_bounds__(NTHREADS) void vsweep_kernel(const SweepArgs a)
+{
+    using TL = Tile<T, D>;
+    using RG = VRing<T, D, MODE, FR>;
+    constexpr bool PRE = (sizeof(T) == 2);   // bf16 storage: the score operand is prescaled, c2 == 1
+    constexpr int BM = NWAVES * FR * 32;
+    static_assert(MODE == M_LSE || MODE == M_MATVEC, "vector sweeps only");
+
+    extern __shared__ __align__(16) unsigned char smem[];
+    __shared__ float red[NWAVES];
+
+    const int chunk = (a.nb_total + 7) >> 3;
+    const int lb = (blockIdx.x & 7) * chunk + (a.rev ? chunk - 1 - (int)(blockIdx.x >> 3) : (int)(blockIdx.x >> 3));
+    if (lb >= a.nb_total) return;
+    const int n = lb / a.nbp;
+    const int o_blk = (lb % a.nbp) * BM;
+
+    // the wavefront index is uniform: keep it (and all tile bookkeeping) in scalar registers
+    const int tid = threadIdx.x, lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int c = lane & 31, h = lane >> 5;
+    const int L = a.L, W = a.W;
+    const Lens ln = problem_lens(a, n);
+    const int Lt = ln.Lt, Le = ln.Le;
+    if (o_blk >= Le) {
+        zero_block<T, D, BM>(a, n, o_blk, false, true);
+        return;
+    }
+    const long moff = (long)n * L * D;
+    const T *Xb = reinterpret_cast<const T *>(a.X) + moff;
+    const T *Yb = reinterpret_cast<const T *>(a.Y) + moff;
+    const float *ytp = a.yt.p + n * a.yt.stride;
+    const float *xsp = a.xs.p + n * a.xs.stride;
+    const float *wp = (MODE == M_MATVEC) ? a.w.p + n * a.w.stride : nullptr;
+
+
+    // stabiliser input first, so that waiting for it waits for nothing else
+    static_assert(BM <= NTHREADS, "one owner-side potential per thread");
+    float mraw = xsp[min(o_blk + min(tid, BM - 1), Le - 1)];   // clamped repeats are harmless
+    float mblk, m2 = 0.f;
+    OwnerFrag<T, D> xf[FR];
+    int o_frag[FR];
+    float sum[FR];
+#pragma unroll
+    for (int f = 0; f < FR; ++f) {
+        o_frag[f] = o_blk + (wave * FR + f) * 32;
+        xf[f].load(Xb, min(o_frag[f] + c, Le - 1), Le, h);   // clamped: rows beyond Le are written as zeros
+        sum[f] = 0.f;
+    }
+
+    // floor((o_blk - W) / 32) and floor((o_blk + 32 FR - 1 + W) / 32); W <= L so no overflow
+    const int kbase = (o_blk - W) >= 0 ? (o_blk - W) / TT : -((W - o_blk + TT - 1) / TT);
+    const int kend = (o_blk + 32 * FR - 1 + W) / TT;
+    const int S = kend - kbase + 1;
+    const int klast = (Lt - 1) / TT;
+
+    // One tile in flight between global memory and LDS.  A tile is a contiguous block of
+    // memory, so a thread's 16-byte pieces sit at fixed byte offsets from the tile's start:
+    // the start is a scalar, the offset one register, and a load needs no address arithmetic
+    // beyond a clamp that keeps the pieces of a ragged last tile inside the matrix.  Loads
+    // are unconditional (an index outside [0, klast] reads the nearest tile and is zeroed
+    // before it is stored), so nothing stalls until the values are stored.
+    constexpr int ROW_BYTES = D * (int)sizeof(T);
+    constexpr int TILE_BYTES = TT * ROW_BYTES;
+    unsigned goff[TL::CPT], soff[TL::CPT];   // piece offsets: in memory, in the LDS tile
+#pragma unroll
+    for (int q = 0; q < TL::CPT; ++q) {
+        const int idx = min(tid + q * NTHREADS, TL::CHUNKS - 1);
+        goff[q] = idx * 16;
+        soff[q] = (idx / TL::CPR) * RG::ROWB + (idx % TL::CPR) * 16;
+    }
+    const unsigned vrow = tid & (TT - 1);
+    struct Inflight {
+        uint4 y[TL::CPT];
+        float vy, vw;
+        int rows;          // valid rows of the tile: 32 = whole, 0 = outside the matrix (uniform)
+    };
+    auto g_load = [&](Inflight &g, int k) {
+        const int kc = min(max(k, 0), klast);
+        const int rows = min(TT, Lt - kc * TT);   // >= 1
+        g.rows = (k == kc) ? rows : 0;
+        const unsigned char *tb = reinterpret_cast<const unsigned char *>(Yb) + (long)kc * TILE_BYTES;
+        const unsigned lim = rows * ROW_BYTES - 16;
+#pragma unroll
+        for (int q = 0; q < TL::CPT; ++q) g.y[q] = *reinterpret_cast<const uint4 *>(tb + min(goff[q], lim));
+        const unsigned vo = min(vrow, (unsigned)(rows - 1)) * 4;
+        g.vy = *reinterpret_cast<const float *>(reinterpret_cast<const unsigned char *>(ytp + kc * TT) + vo);
+        g.vw = 0.f;
+        if constexpr (MODE == M_MATVEC)
+            g.vw = *reinterpret_cast<const float *>(reinterpret_cast<const unsigned char *>(wp + kc * TT) + vo);
+    };
+    auto s_store = [&](Inflight &g, int j) {  // j = tile index relative to kbase
+        unsigned char *sl = smem + (j & (RG::NSLOT - 1)) * RG::SLOT;
+        if (g.rows != TT) {   // uniform: ragged or absent tile
+            const unsigned lim = g.rows * ROW_BYTES;
+#pragma unroll
+            for (int q = 0; q < TL::CPT; ++q)
+                if (goff[q] >= lim) g.y[q] = make_uint4(0, 0, 0, 0);
+        }
+#pragma unroll
+        for (int q = 0; q < TL::CPT; ++q)
+            if (TL::CHUNKS % NTHREADS == 0 || tid + q * NTHREADS < TL::CHUNKS)
+                *reinterpret_cast<uint4 *>(sl + soff[q]) = g.y[q];
+        if (tid < TT) {
+            const bool ok = (int)vrow < g.rows;
+            reinterpret_cast<float *>(sl + RG::OFF_VY)[tid] = ok ? fmaf(g.vy, LOG2E, m2) : -INFINITY;
+            if constexpr (MODE == M_MATVEC) reinterpret_cast<float *>(sl + RG::OFF_VW)[tid] = ok ? g.vw : 0.f;
+        }
+    };
+
+    // fill the ring with the tiles of step 0.  Everything the prologue needs from memory is
+    // requested before anything is waited for: owner rows (above), the first tiles, and the
+    // owner-side potentials the stabiliser is taken from.
+    Inflight fill[RG::LEAD + 1];
+#pragma unroll
+    for (int j = 0; j <= RG::LEAD; ++j) g_load(fill[j], kbase + j);
+    {
+        float m = mraw;
+#pragma unroll
+        for (int s = 32; s >= 1; s >>= 1) m = fmaxf(m, __shfl_xor(m, s));
+        if (lane == 0) red[wave] = m;
+        __syncthreads();
+        mblk = fmaxf(fmaxf(red[0], red[1]), fmaxf(red[2], red[3]));
+        if (mblk == -INFINITY) mblk = 0.f;   // a block of inactive tokens only
+    }
+    m2 = mblk * LOG2E;
+#pragma unroll
+    for (int j = 0; j <= RG::LEAD; ++j) s_store(fill[j], j);
+    __syncthreads();
+    Inflight nxt;
+
+    for (int s = 0; s < S; ++s) {
+        // the next tile is requested in every step, also when no later step reads it (its
+        // address is clamped, its ring slot is free): a load under a condition would make
+        // the compiler wait for it at once instead of at the store below
+        const int jnew = s + 1 + RG::LEAD;
+        g_load(nxt, kbase + jnew);
+
+        const int j = s + wave * FR;
+        const int k = kbase + j;
+        if (k >= 0 && k <= klast) {
+            const unsigned char *sl = smem + (j & (RG::NSLOT - 1)) * RG::SLOT;
+            const int t0 = k * TT;
+            bool use[FR], interior[FR];
+            f32x16 acc[FR];
+            // the staged potentials are the MFMA's initial accumulator when the score operand
+            // carries the scale already (bf16 storage: make_scores_operand)
+            float yv[16];
+#pragma unroll
+            for (int q = 0; q < 4; ++q) {
+                float4 v4 = *reinterpret_cast<const float4 *>(sl + RG::OFF_VY + (8 * q + 4 * h) * 4);
+                yv[4 * q + 0] = v4.x; yv[4 * q + 1] = v4.y; yv[4 * q + 2] = v4.z; yv[4 * q + 3] = v4.w;
+            }
+#pragma unroll
+            for (int f = 0; f < FR; ++f) {
+                const int of = o_frag[f];
+                use[f] = !(of >= Le || t0 + TT - 1 < of - W || t0 > of + 31 + W);
+                interior[f] = (of + 31 - t0 <= W) && (t0 + TT - 1 - of <= W);
+#pragma unroll
+                for (int r = 0; r < 16; ++r) acc[f][r] = PRE ? yv[r] : 0.f;
+            }
+            ring_dot_multi<D, FR, RG::ROWB>(sl, xf, lane, acc);   // unconditional: an unused tile costs MFMA only
+
+            float wv[MODE == M_MATVEC ? 16 : 1];
+            if constexpr (MODE == M_MATVEC) {
+#pragma unroll
+                for (int q = 0; q < 4; ++q) {
+                    float4 w4 = *reinterpret_cast<const float4 *>(sl + RG::OFF_VW + (8 * q + 4 * h) * 4);
+                    wv[4 * q + 0] = w4.x; wv[4 * q + 1] = w4.y; wv[4 * q + 2] = w4.z; wv[4 * q + 3] = w4.w;
+                }
+            }
+#pragma unroll
+            for (int f = 0; f < FR; ++f) {
+                if (!use[f]) continue;
+                float e[16];
+#pragma unroll
+                for (int r = 0; r < 16; ++r) e[r] = PRE ? acc[f][r] : fmaf(acc[f][r], a.c2, yv[r]);
+                if (!interior[f]) {
+                    // keep (o, t) iff -W <= t - o <= W; with t = t0 + 4h + off_r (off_r a
+                    // constant of register r) this is lo <= off_r <= lo + 2W for the lane's
+                    // lo = o - W - t0 - 4h.  A tile crosses the lower edge, the upper edge
+                    // or (narrow bands) both: one compare against a constant per edge.
+                    const int lo = o_frag[f] + c - W - t0 - 4 * h;
+                    const int hi = lo + 2 * W;
+                    if (o_frag[f] + 31 - t0 > W) {
+#pragma unroll
+                        for (int r = 0; r < 16; ++r)
+                            if (lo > 8 * (r >> 2) + (r & 3)) e[r] = -INFINITY;
+                    }
+                    if (t0 + TT - 1 - o_frag[f] > W) {
+#pragma unroll
+                        for (int r = 0; r < 16; ++r)
+                            if (hi < 8 * (r >> 2) + (r & 3)) e[r] = -INFINITY;
+                    }
+                }
+#pragma unroll
+                for (int r = 0; r < 16; ++r) {
+                    const float p = fast_exp2(e[r]);
+                    if constexpr (MODE == M_MATVEC) sum[f] = fmaf(p, wv[r], sum[f]);
+                    else sum[f] += p;
+                }
+            }
+        }
+        s_store(nxt, jnew);
+        __syncthreads();
+    }
+
+#pragma unroll
+    for (int f = 0; f < FR; ++f) {
+        const int o = o_frag[f] + c;
+        float tot = sum[f] + __shfl_xor(sum[f], 32);
+        if (a.dustbin) {   // spoke edge (o, dustbin element of the other side)
+            const float sp2 = a.spoke_own.p ? a.spoke_own.p[n * a.spoke_own.stride + min(o, L - 1)] * LOG2E : a.sdb2;
+            float ed = fast_exp2(sp2 + ytp[L] * LOG2E + m2);
+            tot += (MODE == M_MATVEC) ? ed * wp[L] : ed;
+        }
+        if (h == 0 && o < L) {
+            float r;
+            if (o >= Le) {
+                r = 0.f;   // rows beyond the valid length
+            } else if (xsp[o] == -INFINITY || (MODE == M_LSE && !(tot > 0.f))) {
+                r = (MODE == M_LSE) ? -INFINITY : 0.f;   // inactive token (stays so), or none of its partners is active
+            } else if constexpr (MODE == M_LSE) {
+                r = mblk - LN2 * fast_log2(tot);
+                if (a.olog.p) r += a.olog.p[n * a.olog.stride + o];
+            } else {
+                float pre = a.pre.p ? a.pre.p[n * a.pre.stride + o] : 0.f;
+                r = pre - fast_exp2((xsp[o] - mblk) * LOG2E) * tot;
+                if (a.olog.p) r *= __expf(-a.olog.p[n * a.olog.stride + o]);
+            }
+            a.out_vec.p[n * a.out_vec.stride + o] = r;
+        }
+    }
+}
+
+// ------------------------------------------------------------------ matrix sweeps (bf16)
+// Output map / dV (M_APPLY) and the one-reference final sweep (M_FINAL) on the same skewed
+// ring: wavefront w owns 32 rows, four wavefronts per workgroup, the tile of step s for
+// wavefront w is kbase + s + w.  A ring slot holds the other-side score rows, the second
+// streamed matrix (payload for M_APPLY, the other-side factor of Z for M_FINAL), the staged
+// potentials and, for M_FINAL, the other-side modifier pack.  Tiles are row-major in LDS
+// with 16 bytes of padding per row.  The four rank-1 modifier terms of Prop. 2 are not VALU
+// work: each side's pack is written as 16 bf16 columns (every fp32 value split into a high
+// and a low bf16 part; per term the three products hi*hi, hi*lo, lo*hi, the owner side
+// negated), which extend the Z product by one K = 16 MFMA step: its result is
+// Z - sum_k po_k qt_k directly.  The other side's 32 bytes per row sit in the padding of the
+// row in the two tiles.  The second product needs its streamed operand with the
+// band index contiguous, which the transposing LDS read (ds_read_b64_tr_b16) delivers from
+// the row-major tile: within 16 lanes, lane i receives element (i & 3) of the 8-byte pieces
+// addressed by lanes (i >> 2) + 4 e, e = 0..3.
+template <int D, int MODE, int FR> struct MRing {
+    static constexpr int LEAD = FR * (NWAVES - 1);
+    static constexpr int NSLOT = LEAD + 2;             // exactly what the skew needs (5 or 8): LDS decides
+                                                       // how many workgroups share a CU
+    static constexpr int ROWB = D * 2 + 16;
+    static constexpr int TILE = 32 * ROWB;
+    static constexpr int OFF_Y = 0;
+    static constexpr int OFF_B = TILE;                 // payload (M_APPLY) or Z factor (M_FINAL)
+    static constexpr int OFF_VY = 2 * TILE;
+    static constexpr int OFF_PK = D * 2;               // M_FINAL: the 16 bytes of padding of a row of either
+                                                       // tile hold half of the row's 16 pack columns
+    static constexpr int SLOT = OFF_VY + TT * 4;
+    static constexpr int BYTES = NSLOT * SLOT;
+    static constexpr int CHUNKS = 32 * D * 2 / 16;     // 16-byte pieces of a tile in memory
+    static constexpr int CPT = (CHUNKS + NTHREADS - 1) / NTHREADS;
+    static constexpr int CPR = D * 2 / 16;
+    static_assert(LEAD + 2 <= NSLOT, "ring too small for the skew");
+};
+
+template <int D, int MODE, int FR>
+__global__ __launch_bounds__(NTHREADS) void msweep_kernel(const SweepArgs a)
+{
+    using T = __bf16;
+    using RG = MRing<D, MODE, FR>;
+    constexpr int BM = NWAVES * FR * 32, KS = D / 16;
+    static_assert(MODE == M_APPLY || MODE == M_FINAL, "matrix sweeps only");
+
+    extern __shared__ __align__(16) unsigned char smem[];
+    __shared__ float red[NWAVES];
+
+    const int chunk = (a.nb_total + 7) >> 3;
+    const int lb = (blockIdx.x & 7) * chunk + (a.rev ? chunk - 1 - (int)(blockIdx.x >> 3) : (int)(blockIdx.x >> 3));
+    if (lb >= a.nb_total) return;
+    const int n = lb / a.nbp;
+    const int o_blk = (lb % a.nbp) * BM;
+
+    const int tid = threadIdx.x, lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int c = lane & 31, h = lane >> 5;
+    const int L = a.L, W = a.W;
+    const Lens ln = problem_lens(a, n);
+    const int Lt = ln.Lt, Le = ln.Le;
+    if (o_blk >= Le) {
+        zero_block<T, D, BM>(a, n, o_blk, true, false);
+        return;
+    }
+    const long moff = (long)n * L * D;
+    const T *Xb = reinterpret_cast<const T *>(a.X) + moff;
+    const unsigned char *Yb = reinterpret_cast<const unsigned char *>(reinterpret_cast<const T *>(a.Y) + moff);
+    const unsigned char *Bb = reinterpret_cast<const unsigned char *>(
+        reinterpret_cast<const T *>(MODE == M_FINAL ? a.Bm : a.Pay) + moff);
+    const float *ytp = a.yt.p + n * a.yt.stride;
+    const float *xsp = a.xs.p + n * a.xs.stride;
+
+    float mblk, m2;
+    {
+        float m = -INFINITY;
+        for (int i = tid; i < BM; i += NTHREADS) m = fmaxf(m, xsp[min(o_blk + i, Le - 1)]);
+#pragma unroll
+        for (int s = 32; s >= 1; s >>= 1) m = fmaxf(m, __shfl_xor(m, s));
+        if (lane == 0) red[wave] = m;
+        __syncthreads();
+        mblk = fmaxf(fmaxf(red[0], red[1]), fmaxf(red[2], red[3]));
+        if (mblk == -INFINITY) mblk = 0.f;   // a block of inactive tokens only
+    }
+    m2 = mblk * LOG2E;
+
+    // owner side: score rows, and for M_FINAL the owner factor of Z and the modifier pack.
+    // Rows beyond Le are clamped: they compute garbage that is never stored.
+    const int o_w = o_blk + wave * FR * 32;
+    OwnerFrag<T, D> xf[FR], af[MODE == M_FINAL ? FR : 1];
+    bf16x8 pob[FR];   // M_FINAL: this lane's half of the owner row's 16 pack columns
+    f32x16 outm[FR][D / 32];
+#pragma unroll
+    for (int f = 0; f < FR; ++f) {
+        const int oc = min(o_w + 32 * f + c, Le - 1);
+#pragma unroll
+        for (int s = 0; s < KS; ++s) {
+            uint4 z = *reinterpret_cast<const uint4 *>(Xb + (long)oc * D + (2 * s + h) * 8);
+            xf[f].v[s] = *reinterpret_cast<bf16x8 *>(&z);
+            if constexpr (MODE == M_FINAL) {
+                uint4 y = *reinterpret_cast<const uint4 *>(reinterpret_cast<const T *>(a.A) + moff + (long)oc * D +
+                                                           (2 * s + h) * 8);
+                af[f].v[s] = *reinterpret_cast<bf16x8 *>(&y);
+            }
+        }
+        if constexpr (MODE == M_FINAL) {
+            uint4 z = *reinterpret_cast<const uint4 *>(reinterpret_cast<const unsigned char *>(a.poB) +
+                                                       ((long)n * a.ldp + oc) * 32 + h * 16);
+            pob[f] = *reinterpret_cast<bf16x8 *>(&z);
+        }
+#pragma unroll
+        for (int j = 0; j < D / 32; ++j)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) outm[f][j][r] = 0.f;
+    }
+
+    const int kbase = (o_blk - W) >= 0 ? (o_blk - W) / TT : -((W - o_blk + TT - 1) / TT);
+    const int kend = (o_blk + 32 * FR - 1 + W) / TT;
+    const int S = kend - kbase + 1;
+    const int klast = (Lt - 1) / TT;
+
+    // one tile pair in flight between global memory and LDS (plain arrays: a struct holding
+    // them ends up in scratch memory)
+    auto g_load = [&](uint4 (&gy)[RG::CPT], uint4 (&gb)[RG::CPT], float &gvy, uint4 &gpk, int k) {
+#pragma unroll
+        for (int q = 0; q < RG::CPT; ++q) {
+            int idx = tid + q * NTHREADS;
+            if (idx >= RG::CHUNKS) idx = RG::CHUNKS - 1;
+            const unsigned row = (unsigned)min(max(k * TT + idx / RG::CPR, 0), Lt - 1);
+            const unsigned off = row * (unsigned)(D * 2) + (unsigned)(idx % RG::CPR) * 16u;
+            gy[q] = *reinterpret_cast<const uint4 *>(Yb + off);
+            gb[q] = *reinterpret_cast<const uint4 *>(Bb + off);
+        }
+        const unsigned tv = (unsigned)min(max(k * TT + (tid & (TT - 1)), 0), Lt - 1);
+        gvy = ytp[tv];
+        if constexpr (MODE == M_FINAL) {
+            // 64 pieces of 16 bytes per tile: every wavefront requests them (same addresses; a
+            // request under a condition would cost a full wait), the first one stores them
+            const unsigned tp = (unsigned)min(max(k * TT + ((tid & 63) >> 1), 0), Lt - 1);
+            gpk = *reinterpret_cast<const uint4 *>(reinterpret_cast<const unsigned char *>(a.qtA) +
+                                                   ((long)n * a.ldp + tp) * 32 + (tid & 1) * 16);
+        }
+    };
+    // rows outside [0, Lt) keep whatever the clamped fetch brought: their potential is -inf,
+    // so their plan entries are exactly zero and finite data times zero adds nothing
+    auto s_store = [&](const uint4 (&gy)[RG::CPT], const uint4 (&gb)[RG::CPT], float gvy, uint4 gpk, int j, int k) {
+        unsigned char *sl = smem + (j % RG::NSLOT) * RG::SLOT;
+#pragma unroll
+        for (int q = 0; q < RG::CPT; ++q) {
+            const int idx = tid + q * NTHREADS;
+            if (idx < RG::CHUNKS) {
+                const int off = (idx / RG::CPR) * RG::ROWB + (idx % RG::CPR) * 16;
+                *reinterpret_cast<uint4 *>(sl + RG::OFF_Y + off) = gy[q];
+                *reinterpret_cast<uint4 *>(sl + RG::OFF_B + off) = gb[q];
+            }
+        }
+        if (tid < TT) {
+            const bool live = k >= 0 && k * TT + tid < Lt;
+            reinterpret_cast<float *>(sl + RG::OFF_VY)[tid] = live ? fmaf(gvy, LOG2E, m2) : -INFINITY;
+        }
+        if constexpr (MODE == M_FINAL) {
+            if (tid < 64)   // (rows outside the matrix: clamped data, multiplied by a zero plan entry)
+                *reinterpret_cast<uint4 *>(sl + ((tid & 1) ? RG::OFF_B : RG::OFF_Y) + (tid >> 1) * RG::ROWB +
+                                           RG::OFF_PK) = gpk;
+        }
+    };
+
+    {
+        uint4 fy[RG::LEAD + 1][RG::CPT], fb[RG::LEAD + 1][RG::CPT];
+        float fvy[RG::LEAD + 1];
+        uint4 fvq[RG::LEAD + 1];
+#pragma unroll
+        for (int j = 0; j <= RG::LEAD; ++j) g_load(fy[j], fb[j], fvy[j], fvq[j], kbase + j);
+#pragma unroll
+        for (int j = 0; j <= RG::LEAD; ++j) s_store(fy[j], fb[j], fvy[j], fvq[j], j, kbase + j);
+    }
+    __syncthreads();
+    uint4 ny[RG::CPT], nb[RG::CPT];
+    float nvy = 0.f;
+    uint4 nvq = make_uint4(0, 0, 0, 0);
+
+    // per-lane LDS offsets: fragment rows for the score / Z products, and the 8-byte pieces
+    // this lane addresses in a transposing read (row 4h + (lane & 15) / 4 of a 16-row block,
+    // columns 16 (lane / 16 & 1) + 4 (lane & 3), + 32 per output column tile)
+    const int rd_a = c * RG::ROWB + h * 16;
+    const int rd_t = (4 * h + ((lane & 15) >> 2)) * RG::ROWB + (16 * ((lane >> 4) & 1) + 4 * (lane & 3)) * 2;
+    typedef __bf16 bf16x4v __attribute__((ext_vector_type(4)));
+
+    for (int s = 0; s < S; ++s) {
+        const int jnew = s + 1 + RG::LEAD;
+        const bool more = (s + 1 < S);
+        if (more) g_load(ny, nb, nvy, nvq, kbase + jnew);
+
+        const int j = s + wave * FR;
+        const int k = kbase + j;
+        if (k >= 0 && k <= klast) {
+            const unsigned char *sl = smem + (j % RG::NSLOT) * RG::SLOT;
+            const int t0 = k * TT;
+            // this tile's fragments (score rows, Z rows) and staged potentials, read once for
+            // all FR owner fragments
+            bf16x8 yfr[KS], bfr[MODE == M_FINAL ? KS : 1];
+#pragma unroll
+            for (int ks = 0; ks < KS; ++ks) {
+                yfr[ks] = *reinterpret_cast<const bf16x8 *>(sl + RG::OFF_Y + rd_a + 32 * ks);
+                if constexpr (MODE == M_FINAL)
+                    bfr[ks] = *reinterpret_cast<const bf16x8 *>(sl + RG::OFF_B + rd_a + 32 * ks);
+            }
+            f32x16 yv;
+#pragma unroll
+            for (int q = 0; q < 4; ++q) {
+                float4 v4 = *reinterpret_cast<const float4 *>(sl + RG::OFF_VY + (8 * q + 4 * h) * 4);
+                yv[4 * q + 0] = v4.x; yv[4 * q + 1] = v4.y; yv[4 * q + 2] = v4.z; yv[4 * q + 3] = v4.w;
+            }
+            bf16x8 qpk;   // M_FINAL: row c of the tile, pack columns 8h .. 8h + 7
+            if constexpr (MODE == M_FINAL)
+                qpk = *reinterpret_cast<const bf16x8 *>(sl + (h ? RG::OFF_B : RG::OFF_Y) + c * RG::ROWB + RG::OFF_PK);
+            bf16x8 pf[FR][2];
+#pragma unroll
+            for (int f = 0; f < FR; ++f) {
+                const int of = o_w + 32 * f;
+                const bool interior = (of + 31 - t0 <= W) && (t0 + TT - 1 - of <= W);
+                // scores start from the staged potentials when the scale is folded into the operand
+                f32x16 acc = yv;
+#pragma unroll
+                for (int ks = 0; ks < KS; ++ks)
+                    acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(yfr[ks], xf[f].v[ks], acc, 0, 0, 0);
+                float e[16];
+#pragma unroll
+                for (int r = 0; r < 16; ++r) e[r] = acc[r];
+                if (!interior) {   // also covers a tile that misses this fragment's band entirely
+                    const int lo = of + c - W - t0 - 4 * h;
+                    const unsigned span = 2u * (unsigned)W;
+#pragma unroll
+                    for (int r = 0; r < 16; ++r) {
+                        const int off = 8 * (r >> 2) + (r & 3);
+                        if ((unsigned)(off - lo) > span) e[r] = -INFINITY;
+                    }
+                }
+#pragma unroll
+                for (int r = 0; r < 16; ++r) e[r] = fast_exp2(e[r]);
+
+                if constexpr (MODE == M_FINAL) {
+                    f32x16 z;
+#pragma unroll
+                    for (int r = 0; r < 16; ++r) z[r] = 0.f;
+#pragma unroll
+                    for (int ks = 0; ks < KS; ++ks)
+                        z = __builtin_amdgcn_mfma_f32_32x32x16_bf16(bfr[ks], af[f].v[ks], z, 0, 0, 0);
+                    z = __builtin_amdgcn_mfma_f32_32x32x16_bf16(qpk, pob[f], z, 0, 0, 0);   // - sum_k po_k qt_k
+#pragma unroll
+                    for (int r = 0; r < 16; ++r) e[r] *= z[r];
+                }
+#pragma unroll
+                for (int m = 0; m < 2; ++m)
+#pragma unroll
+                    for (int r = 0; r < 8; ++r) pf[f][m][r] = (__bf16)e[8 * m + r];
+            }
+
+            // second product: out[dv, o] += sum_t M[t][dv] * e[t, o], M = payload (M_APPLY) or the
+            // other-side score rows themselves (M_FINAL); the transposed fragment of M serves
+            // every owner fragment
+            const unsigned char *pm = sl + (MODE == M_FINAL ? RG::OFF_Y : RG::OFF_B) + rd_t;
+#pragma unroll
+            for (int m = 0; m < 2; ++m)
+#pragma unroll
+                for (int dvt = 0; dvt < D / 32; ++dvt) {
+                    bf16x4v lo4 = __builtin_amdgcn_ds_read_tr16_b64_v4bf16(
+                        (bf16x4v __attribute__((address_space(3))) *)(pm + (16 * m) * RG::ROWB + dvt * 64));
+                    bf16x4v hi4 = __builtin_amdgcn_ds_read_tr16_b64_v4bf16(
+                        (bf16x4v __attribute__((address_space(3))) *)(pm + (16 * m + 8) * RG::ROWB + dvt * 64));
+                    bf16x8 am = {lo4[0], lo4[1], lo4[2], lo4[3], hi4[0], hi4[1], hi4[2], hi4[3]};
+#pragma unroll
+                    for (int f = 0; f < FR; ++f)   // (a fragment the tile misses has e == 0 throughout)
+                        outm[f][dvt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(am, pf[f][m], outm[f][dvt], 0, 0, 0);
+                }
+        }
+        if (more) s_store(ny, nb, nvy, nvq, jnew, kbase + jnew);
+        __syncthreads();
+    }
+
+    // epilogue: owner-side factor, store (and the <dot_mat_o, out_o> reduction for dV)
+#pragma unroll
+    for (int f = 0; f < FR; ++f) {
+        const int o = o_w + 32 * f + c;
+        const int oc = min(o, L - 1);
+        const float xso = xsp[min(o, Le - 1)];
+        const bool dead = o >= Le || xso == -INFINITY;   // beyond the valid length, or an inactive token: zeros
+        float fac = fast_exp2((xso - mblk) * LOG2E);
+        if constexpr (MODE == M_FINAL) fac *= a.cs;
+        float pdb = 0.f;   // plan entry of the spoke (o, dustbin) when the dustbin carries a payload
+        if constexpr (MODE == M_APPLY)
+            if (a.pay_db) pdb = __expf(a.spoke_own.p[n * a.spoke_own.stride + oc] + xsp[oc] + ytp[L]);
+        T *orow = reinterpret_cast<T *>(a.out_mat) + moff + (long)oc * D;
+        const T *drow = a.dot_mat ? reinterpret_cast<const T *>(a.dot_mat) + moff + (long)oc * D : nullptr;
+        float dot = 0.f;
+#pragma unroll
+        for (int j = 0; j < D / 32; ++j)
+#pragma unroll
+            for (int q = 0; q < 4; ++q) {
+                const int dv = 32 * j + 8 * q + 4 * h;
+                float v0 = outm[f][j][4 * q + 0] * fac, v1 = outm[f][j][4 * q + 1] * fac;
+                float v2 = outm[f][j][4 * q + 2] * fac, v3 = outm[f][j][4 * q + 3] * fac;
+                if constexpr (MODE == M_APPLY) {
+                    if (a.pay_db) {
+                        const float4 pv = *reinterpret_cast<const float4 *>(a.pay_db + (long)n * D + dv);
+                        v0 = fmaf(pdb, pv.x, v0); v1 = fmaf(pdb, pv.y, v1);
+                        v2 = fmaf(pdb, pv.z, v2); v3 = fmaf(pdb, pv.w, v3);
+                    }
+                }
+                if (dead) v0 = v1 = v2 = v3 = 0.f;
+                if (o < L) {
+                    store4<T>(orow + dv, v0, v1, v2, v3);
+                    if constexpr (MODE == M_APPLY) {
+                        if (drow && !dead) {
+                            float dd[4];
+                            load4<T>(drow + dv, dd);
+                            dot += dd[0] * v0 + dd[1] * v1 + dd[2] * v2 + dd[3] * v3;
+                        }
+                    }
+                }
+            }
+        if constexpr (MODE == M_APPLY) {
+            if (a.dot_mat) {
+                dot += __shfl_xor(dot, 32);
+                if (h == 0 && o < L) {
+                    if (a.olog.p && !dead) dot *= __expf(-a.olog.p[n * a.olog.stride + o]);
+                    a.dot_out.p[n * a.dot_out.stride + o] = dot;
+                }
+            }
+        }
+    }
+}
+
+}  // namespace
