@@ -155,6 +155,20 @@ def main() -> int:
     ska.sinkhorn_attn_profile_enable(0)
     ph = ska.sinkhorn_attn_profile_read_phases()
 
+    # forward and backward apart (a few untimed-region steps each)
+    def timed(fn, n=3):
+        torch.cuda.synchronize()
+        t = time.perf_counter()
+        for _ in range(n):
+            fn()
+        torch.cuda.synchronize()
+        return 1e3 * (time.perf_counter() - t) / n
+    fwd_ms = timed(lambda: ska.sinkhorn_attn_fwd(Q, K, V, w.W, w.T, w.R, w.eps, w.dustbin, w.dustbin_score, O=O, UV=UV,
+                                                 workspace=wsp))
+    bwd_ms = timed(lambda: ska.sinkhorn_attn_bwd_variant(variant, Q, K, V, None, None, None, None, O, G, UV, w.W, w.T,
+                                                         w.R, w.eps, w.dustbin, w.dustbin_score, workspace=wsp, dQ=dQ,
+                                                         dK=dK, dV=dV))
+
     ms_per_step = 1e3 * dt / args.steps
     tokens_per_s = w.B * w.L * args.steps / dt
     avg_s = 1e-3 * sweep_ms / max(launches, 1)
@@ -198,6 +212,10 @@ def main() -> int:
                      "mfma": {"achieved": 2 * w.d * E / avg_s / 1e12, "peak": MFMA_PEAK_TFLOPS[dt_name],
                               "unit": "TFLOP/s", "frac": 2 * w.d * E / avg_s / 1e12 / MFMA_PEAK_TFLOPS[dt_name]}},
         "phases": phases,
+        # the same run in other units: per (token, head), per band edge and sweep (2(T+R) half-steps,
+        # the output map and six backward sweeps), and the two directions apart
+        "extra": {"head_tokens_per_s": tokens_per_s * w.H, "edge_sweeps_per_s": E * (2 * (w.T + w.R) + 7) / (dt / args.steps),
+                  "fwd_ms": fwd_ms, "bwd_ms": bwd_ms},
     }
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(w, min(args.cpu_tokens, w.L))

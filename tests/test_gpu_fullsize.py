@@ -174,3 +174,22 @@ def test_dustbin_config_with_learned_tokens():
     num = np.sqrt(sum(np.linalg.norm(got[n][b, h] - ref[n]) ** 2 for n in tok))
     den = np.sqrt(sum(np.linalg.norm(ref[n]) ** 2 for n in tok))
     assert all(np.isfinite(got[n]).all() for n in tok) and num / den <= TOL[w.dtype], num / den
+
+
+def test_paper_scale_one_full_head():
+    """One whole head of the benchmark workload (262144 tokens) against the oracle run on the
+    whole head: rel-L2 over the full tensors, no windows (about half a minute of CPU)."""
+    w = CONFIGS["paper"]
+    print(f"\n[case] {w}: full head 0 against the oracle", flush=True)
+    arrays = make_inputs(w)
+    got = run_gpu(w, arrays)
+    q, k, v, g = (x[0, 0] for x in arrays)
+    ref = oracle.band(q, k, v, g, w.W, w.T, w.R, w.eps)
+    errs = {n: float(np.linalg.norm(got[n][0, 0] - ref[n]) / np.linalg.norm(ref[n])) for n in ("O", "dQ", "dK", "dV")}
+    print("   rel-L2 over the whole head:", {n: f"{e:.2e}" for n, e in errs.items()}, flush=True)
+    for n, e in errs.items():
+        assert e <= TOL[w.dtype], (n, e)
+    for t in range(w.R + 1):
+        s_got = got["UV"][0, 0, 2 * t] + got["UV"][0, 0, 2 * t + 1]
+        s_ref = ref["UV"][2 * t] + ref["UV"][2 * t + 1]
+        assert np.abs(s_got - s_ref).max() < 2e-2, t
