@@ -202,8 +202,18 @@ template <typename T, int D> int sweep(int mode, const SweepArgs &a, int N, hipS
     constexpr int FRV = (sizeof(T) == 2) ? 2 : 1;   // vector sweeps: owner rows per wavefront / 32
     switch (mode) {
     case M_LSE_FIRST: return launch_sweep<T, D, M_LSE_FIRST, FRV>(a, N, st);
-    case M_LSE: return launch_vsweep<T, D, M_LSE, FRV>(a, N, st);
-    case M_MATVEC: return launch_vsweep<T, D, M_MATVEC, FRV>(a, N, st);
+    case M_LSE:
+    case M_MATVEC: {
+        // 64 rows per wavefront reuse every tile fragment twice, but a launch then has N L / 256
+        // workgroups.  The 256 CUs hold four of them each; up to three per CU (measured: two per CU
+        // gains 4-7 %, four per CU loses 3 %) halve the block instead: twice the workgroups
+        constexpr long SMALL_ROWS = 3L * 256 * 256;
+        if constexpr (sizeof(T) == 2) {
+            if ((long)N * a.L <= SMALL_ROWS)
+                return mode == M_LSE ? launch_vsweep<T, D, M_LSE, 1>(a, N, st) : launch_vsweep<T, D, M_MATVEC, 1>(a, N, st);
+        }
+        return mode == M_LSE ? launch_vsweep<T, D, M_LSE, FRV>(a, N, st) : launch_vsweep<T, D, M_MATVEC, FRV>(a, N, st);
+    }
     case M_APPLY:
         if constexpr (sizeof(T) == 2 && D <= 64) return launch_msweep<D, M_APPLY, 2>(a, N, st);
         else return launch_sweep<T, D, M_APPLY, 1>(a, N, st);
