@@ -150,7 +150,9 @@ int launch_sweep(SweepArgs a, int N, hipStream_t st)
             return SKA_EHIP;
         raised = true;
     }
-    hipLaunchKernelGGL((sweep_kernel<T, D, MODE, FR, DIRECT>), dim3(chunk * 8), dim3(NTHREADS), LDS, st, a);
+    // (the first half-step starts with one workgroup per problem for the dustbin element)
+    a.lead = (MODE == M_LSE_FIRST && a.dustbin) ? (N + 7) / 8 * 8 : 0;
+    hipLaunchKernelGGL((sweep_kernel<T, D, MODE, FR, DIRECT>), dim3(chunk * 8 + a.lead), dim3(NTHREADS), LDS, st, a);
     return hipGetLastError() == hipSuccess ? SKA_OK : SKA_EHIP;
 }
 
@@ -169,7 +171,8 @@ int launch_vsweep(SweepArgs a, int N, hipStream_t st)
             return SKA_EHIP;
         raised = true;
     }
-    hipLaunchKernelGGL((vsweep_kernel<T, D, MODE, FR>), dim3(chunk * 8), dim3(NTHREADS), LDS, st, a);
+    a.lead = a.dustbin ? (N + 7) / 8 * 8 : 0;   // one workgroup per problem in front: the dustbin element
+    hipLaunchKernelGGL((vsweep_kernel<T, D, MODE, FR>), dim3(chunk * 8 + a.lead), dim3(NTHREADS), LDS, st, a);
     return hipGetLastError() == hipSuccess ? SKA_OK : SKA_EHIP;
 }
 
@@ -313,7 +316,7 @@ int fwd_impl(const Problem &p, const void *Qin, const void *K, const void *V, vo
     auto half = [&](bool row, int yslot, int prevslot, int outslot) -> int {
         SweepArgs a = base;
         a.c2 = stage_c2; a.sdb2 = stage_sdb2;
-        a.spoke_own = row ? SQ : SK;
+        a.spoke_own = row ? SQ : SK; a.spoke_oth = row ? SK : SQ;
         a.X = row ? Q : K; a.Y = row ? K : Q;
         a.yt = vec(yslot); a.xs = vec(prevslot); a.out_vec = vout(outslot);
         a.olog = Vec{row ? p.log_a : p.log_b, (long)Lp};
@@ -324,11 +327,6 @@ int fwd_impl(const Problem &p, const void *Qin, const void *K, const void *V, vo
         SKA_TRY((sweep<T, D>(first ? M_LSE_FIRST : M_LSE, a, N, st)));
         if (first) pt_first.launched();
         else pt_run->launched();
-        if (p.dustbin) {
-            hipLaunchKernelGGL(dustbin_kernel, dim3(N), dim3(1024), 0, st, vec(yslot), Vec{nullptr, 0},
-                               Vec{nullptr, 0}, vout(outslot), L, stage_sdb2 * LN2, row ? SK : SQ);
-            if (hipGetLastError() != hipSuccess) return SKA_EHIP;
-        }
         if (first) {   // the run of identical scaling sweeps starts after the first launch
             first = false;
             pt_first.end();
@@ -479,14 +477,9 @@ int bwd_impl(const Problem &p, const void *Qin, const void *K, const void *V, co
         a.xs = xs; a.yt = yt; a.w = wv(w); a.pre = Vec{pre, ldw}; a.out_vec = out;
         if (scaled) a.olog = Vec{row ? p.log_a : p.log_b, (long)Lp};
         a.len_own = row ? p.len_q : p.len_k; a.len_oth = row ? p.len_k : p.len_q;
-        a.spoke_own = row ? SQ : SK;
+        a.spoke_own = row ? SQ : SK; a.spoke_oth = row ? SK : SQ;
         a.rev = nlaunch++ & 1;
         SKA_TRY((sweep<T, D>(M_MATVEC, a, N, st)));
-        if (p.dustbin) {
-            hipLaunchKernelGGL(dustbin_kernel, dim3(N), dim3(1024), 0, st, yt, wv(w), xs, out, L, p.sdb,
-                               row ? SK : SQ);
-            if (hipGetLastError() != hipSuccess) return SKA_EHIP;
-        }
         return SKA_OK;
     };
     {

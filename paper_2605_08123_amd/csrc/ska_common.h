@@ -72,9 +72,11 @@ struct SweepArgs {
     float sdb2;       // dustbin score * log2(e)
     Vec spoke_own;    // learned dustbin token: score of the spoke (o, dustbin of the other side) per
                       // owner index, natural units (null: the scalar score above)
+    Vec spoke_oth;    // ... and the scores of the spokes from this side's dustbin element to the other side's indices
     const float *pay_db;  // APPLY with a learned token: payload row of the other side's dustbin [N][D]
     int nbp;          // workgroups per problem
     int nb_total;
+    int lead;         // workgroups in front of the sweep's own (dustbin elements; a multiple of 8)
     int rev;          // walk each XCD's share of the blocks backwards (alternates between launches)
 };
 
@@ -350,6 +352,45 @@ template <> __device__ __forceinline__ void load4<__bf16>(const __bf16 *src, flo
     bf16x4 v = *reinterpret_cast<const bf16x4 *>(src);
 #pragma unroll
     for (int i = 0; i < 4; ++i) f[i] = (float)v[i];
+}
+
+// Dustbin element of a sweep result (one workgroup per problem, appended to the sweep's own
+// launch: it reads only the sweep's inputs): the extra row (column) is joined to every index
+// 0..L of the other side by an edge of score s_t (the scalar, or spoke_oth[t] when the dustbin
+// is a learned token).
+//   half-steps: out[L] = -log sum_{t<=L} exp(s_t + y_t)
+//   mat-vec   : out[L] = -exp(x[L]) sum_{t<=L} exp(s_t + y_t) w_t    (its additive term is 0)
+__device__ __forceinline__ void dustbin_element(const SweepArgs &a, int n, bool matvec)
+{
+    __shared__ float sm[NWAVES], ss[NWAVES];
+    const int L = a.L, tid = threadIdx.x, lane = tid & 63, wv = tid >> 6;
+    const float *yp = a.yt.p + n * a.yt.stride;
+    const float *sp = a.spoke_oth.p ? a.spoke_oth.p + n * a.spoke_oth.stride : nullptr;
+    const float *wp = matvec ? a.w.p + n * a.w.stride : nullptr;
+    const float sdb = sp ? 0.f : a.sdb2 * LN2;
+    // one pass: running maximum m and sum of exp(. - m) (times the weight), merged pairwise
+    float m = -INFINITY, acc = 0.f;
+    for (int t = tid; t <= L; t += NTHREADS) {
+        const float v = yp[t] + (sp ? sp[t] : 0.f);
+        const float wt = wp ? wp[t] : 1.f;
+        const float mn = fmaxf(m, v);
+        if (mn > -INFINITY) acc = acc * __expf(m - mn) + wt * __expf(v - mn);
+        m = mn;
+    }
+    auto merge = [](float &m0, float &s0, float m1, float s1) {
+        const float mn = fmaxf(m0, m1);
+        s0 = (mn > -INFINITY) ? s0 * __expf(m0 - mn) + s1 * __expf(m1 - mn) : 0.f;
+        m0 = mn;
+    };
+    for (int s = 32; s >= 1; s >>= 1) merge(m, acc, __shfl_xor(m, s), __shfl_xor(acc, s));
+    if (lane == 0) { sm[wv] = m; ss[wv] = acc; }
+    __syncthreads();
+    if (tid == 0) {
+        m = sm[0]; acc = ss[0];
+        for (int i = 1; i < NWAVES; ++i) merge(m, acc, sm[i], ss[i]);
+        a.out_vec.p[n * a.out_vec.stride + L] =
+            matvec ? -__expf(a.xs.p[n * a.xs.stride + L] + sdb + m) * acc : -(sdb + m + __logf(acc));
+    }
 }
 
 }  // namespace

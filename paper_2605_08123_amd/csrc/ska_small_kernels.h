@@ -344,41 +344,4 @@ __global__ void packs_kernel(const float *UV, int Lp, int R, const float *vecs, 
     }
 }
 
-// Dustbin element of a sweep result: the extra row (column) is joined to every
-// index 0..L of the other side by an edge of score s_t (the scalar sdb, or spoke[t] when
-// the dustbin is a learned token).
-//   w == null: out[L] = -log sum_{t<=L} exp(s_t + y_t)
-//   else     : out[L] = pre - exp(x[L]) sum_{t<=L} exp(s_t + y_t) w_t   (pre = 0)
-__global__ __launch_bounds__(1024) void dustbin_kernel(Vec y, Vec w, Vec x, VecOut out, int L, float sdb, Vec spoke)
-{
-    __shared__ float sm[32], ss[32];
-    const int n = blockIdx.x, tid = threadIdx.x, lane = tid & 63, wv = tid >> 6;
-    const float *yp = y.p + n * y.stride;
-    const float *sp = spoke.p ? spoke.p + n * spoke.stride : nullptr;
-    if (sp) sdb = 0.f;
-    float m = -INFINITY;
-    for (int t = tid; t <= L; t += blockDim.x) m = fmaxf(m, yp[t] + (sp ? sp[t] : 0.f));
-    for (int s = 32; s >= 1; s >>= 1) m = fmaxf(m, __shfl_xor(m, s));
-    if (lane == 0) sm[wv] = m;
-    __syncthreads();
-    m = sm[0];
-    for (int i = 1; i < (int)(blockDim.x >> 6); ++i) m = fmaxf(m, sm[i]);
-    float acc = 0.f;
-    for (int t = tid; t <= L; t += blockDim.x) {
-        float e = __expf(yp[t] + (sp ? sp[t] : 0.f) - m);
-        acc += w.p ? e * w.p[n * w.stride + t] : e;
-    }
-    for (int s = 32; s >= 1; s >>= 1) acc += __shfl_xor(acc, s);
-    if (lane == 0) ss[wv] = acc;
-    __syncthreads();
-    if (tid == 0) {
-        float tot = 0.f;
-        for (int i = 0; i < (int)(blockDim.x >> 6); ++i) tot += ss[i];
-        float r;
-        if (!w.p) r = -(sdb + m + __logf(tot));
-        else r = -__expf(x.p[n * x.stride + L] + sdb + m) * tot;
-        out.p[n * out.stride + L] = r;
-    }
-}
-
 }  // namespace

@@ -40,7 +40,14 @@ __global__ __launch_bounds__(NTHREADS) void vsweep_kernel(const SweepArgs a)
     __shared__ float red[NWAVES];
 
     const int chunk = (a.nb_total + 7) >> 3;
-    const int lb = (blockIdx.x & 7) * chunk + (a.rev ? chunk - 1 - (int)(blockIdx.x >> 3) : (int)(blockIdx.x >> 3));
+    // a.lead workgroups come first (a multiple of 8, so the XCD of a sweep block is unchanged): one
+    // per problem for the dustbin element, started first so that it ends under the sweep
+    if ((int)blockIdx.x < a.lead) {
+        if ((int)blockIdx.x < a.nb_total / a.nbp) dustbin_element(a, blockIdx.x, MODE == M_MATVEC);
+        return;
+    }
+    const int bx = (int)blockIdx.x - a.lead;
+    const int lb = (bx & 7) * chunk + (a.rev ? chunk - 1 - (bx >> 3) : (bx >> 3));
     if (lb >= a.nb_total) return;
     const int n = lb / a.nbp;
     const int o_blk = (lb % a.nbp) * BM;
