@@ -472,6 +472,54 @@ def test_forward_backward_replay_from_a_hip_graph():
             assert torch.equal(got, ref), rep
 
 
+@pytest.mark.parametrize("dtype,d", [("f32", 32), ("bf16", 64)])
+def test_degenerate_lengths_and_masks(dtype, d):
+    """Items with no query, no key, lengths beyond L (clamped), a fully masked item and a
+    single active pair: everything outside the problem is zero, nothing is NaN, and the
+    ordinary item next to them is unaffected."""
+    import torch
+
+    import paper_2605_08123_amd as ska
+    w = small("degenerate", 300, d, 17, 4, dtype, eps=0.9, B=4, H=1)
+    print(f"\n[case] {w} degenerate lengths and masks", flush=True)
+    arrays = make_inputs(w, 71)
+    dev = torch.device("cuda:0")
+    td = torch.float32 if dtype == "f32" else torch.bfloat16
+    Q, K, V, G = (torch.from_numpy(x).to(dev).to(td) for x in arrays)
+    lq = torch.tensor([0, 300, 5000, 123], dtype=torch.int32, device=dev)      # item 2: clamped to L
+    lk = torch.tensor([300, 0, 300, -7], dtype=torch.int32, device=dev)        # item 3: negative -> 0
+    O, UV = ska.sinkhorn_attn_fwd_varlen(Q, K, V, None, None, lq, lk, w.W, w.T, w.R, w.eps)
+    dQ, dK, dV = ska.sinkhorn_attn_bwd_varlen(Q, K, V, None, None, lq, lk, O, G, UV, w.W, w.T, w.R, w.eps)
+    O0, UV0 = ska.sinkhorn_attn_fwd(Q[2:3], K[2:3], V[2:3], w.W, w.T, w.R, w.eps)
+    g0 = ska.sinkhorn_attn_bwd(Q[2:3], K[2:3], V[2:3], O0, G[2:3], UV0, w.W, w.T, w.R, w.eps)
+    torch.cuda.synchronize()
+    for x in (O, UV, dQ, dK, dV):
+        assert torch.isfinite(x).all()
+    for b in (0, 1, 3):
+        assert all(float(x[b].abs().max()) == 0.0 for x in (O, UV, dQ, dK, dV)), b
+    assert torch.equal(O[2:3], O0) and all(torch.equal(x[2:3], y) for x, y in zip((dQ, dK, dV), g0))
+    # masks: item 0 fully inactive, item 1 one active pair inside the band, item 2 one pair outside it
+    mq = torch.zeros((4, 300), dtype=torch.uint8, device=dev)
+    mk = torch.zeros((4, 300), dtype=torch.uint8, device=dev)
+    mq[1, 40] = mk[1, 50] = 1
+    mq[2, 40] = mk[2, 90] = 1
+    mq[3], mk[3] = 1, 1
+    O, UV = ska.sinkhorn_attn_fwd_masked(Q, K, V, mq, mk, w.W, w.T, w.R, w.eps)
+    dQ, dK, dV = ska.sinkhorn_attn_bwd(Q, K, V, O, G, UV, w.W, w.T, w.R, w.eps)
+    torch.cuda.synchronize()
+    for x in (O, dQ, dK, dV):
+        assert torch.isfinite(x).all()
+    for b in (0, 2):
+        assert all(float(x[b].abs().max()) == 0.0 for x in (O, dQ, dK, dV)) and bool(torch.isneginf(UV[b]).all())
+    # a single edge: the plan is the 1 x 1 matrix [1], so O_40 = V_50, dV_50 = dO_40, dQ = dK = 0
+    assert torch.allclose(O[1, 0, 40].float(), V[1, 0, 50].float(), rtol=1e-2, atol=1e-5)
+    assert torch.allclose(dV[1, 0, 50].float(), G[1, 0, 40].float(), rtol=1e-2, atol=1e-5)
+    assert float(dQ[1].abs().max()) < 1e-4 * float(G.float().abs().max()) + 1e-6
+    assert float(O[1, 0, :40].abs().max()) == 0.0 and float(O[1, 0, 41:].abs().max()) == 0.0
+    O3, UV3 = ska.sinkhorn_attn_fwd(Q[3:4], K[3:4], V[3:4], w.W, w.T, w.R, w.eps)
+    assert torch.equal(O[3:4], O3)
+
+
 def test_dense_widened_band_dustbin():
     """The paper's own dustbin path: one learned token appended per side and a band wide enough
     to cover everything (W~ = max(W, L)).  That is the plain operator on the augmented tensors;
