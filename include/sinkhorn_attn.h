@@ -291,11 +291,13 @@ int sinkhorn_attn_bwd_variant(int variant, const void *Q, const void *K, const v
  *     waits for the recorded events, returns per phase the summed elapsed milliseconds and
  *     the number of sweep launches they bracket, then forgets them.
  *   sinkhorn_attn_profile_read(&ms, &launches): the same, SKA_PH_SCALING only (the run of
- *     2(T + R) - 1 identical launches of the scaling sweep of Eq. 1-2 in every forward call).
+ *     2(T + R) - 1 identical launches of the scaling sweep of Eq. 1-2 in every forward call;
+ *     one fewer in sinkhorn_attn_fwd_masked, whose first column half-step counts as SKA_PH_FIRST).
  */
 typedef enum {
     SKA_PH_PRESCALE = 0, /* bf16 storage: copy of Q with the score scale folded in (fwd and bwd) */
-    SKA_PH_FIRST = 1,    /* first row half-step of the base solve (no previous iterate)   */
+    SKA_PH_FIRST = 1,    /* first row half-step of the base solve (no previous iterate:   */
+                         /* running-maximum kernel); with masks also the first column one */
     SKA_PH_SCALING = 2,  /* the other 2(T + R) - 1 half-steps (Eq. 1-2)                   */
     SKA_PH_OUTPUT = 3,   /* O = P22 V (Section 2.2)                                      */
     SKA_PH_ROWDOT = 4,   /* g_u = <dO, O>                                                */

@@ -298,9 +298,13 @@ int fwd_impl(const Problem &p, const void *Qin, const void *K, const void *V, vo
                            p.mask_k, p.H);
         if (hipGetLastError() != hipSuccess) return SKA_EHIP;
     }
-    bool first = true;
+    // The first row half-step has no previous iterate to stabilise with: it runs on the kernel
+    // that tracks a running maximum, which is exact whatever the scores are and tells an empty sum
+    // (no active partner) from a small one.  With token masks the first column half-step does so
+    // too: after these two every token's activity is settled, and an empty sum later is an error.
+    int cold = (p.mask_q || p.mask_k) ? 2 : 1;
     int nlaunch = 0;
-    PhaseTimer pt_first(SKA_PH_FIRST, st);   // the first launch is the other (max-tracking) kernel
+    PhaseTimer pt_first(SKA_PH_FIRST, st);   // the two cold launches are the other (max-tracking) kernel
     PhaseTimer *pt_run = nullptr;
     alignas(PhaseTimer) unsigned char pt_run_mem[sizeof(PhaseTimer)];
     // half-step: out slot <- -LSE over the band of (S + yt); prev slot only stabilises
@@ -324,11 +328,10 @@ int fwd_impl(const Problem &p, const void *Qin, const void *K, const void *V, vo
         // successive sweeps walk the blocks in opposite directions: a sweep then starts on
         // the rows its predecessor touched last, which are still in L2
         a.rev = nlaunch++ & 1;
-        SKA_TRY((sweep<T, D>(first ? M_LSE_FIRST : M_LSE, a, N, st)));
-        if (first) pt_first.launched();
+        SKA_TRY((sweep<T, D>(cold > 0 ? M_LSE_FIRST : M_LSE, a, N, st)));
+        if (cold > 0) pt_first.launched();
         else pt_run->launched();
-        if (first) {   // the run of identical scaling sweeps starts after the first launch
-            first = false;
+        if (cold > 0 && --cold == 0) {   // the run of identical scaling sweeps starts after the cold launches
             pt_first.end();
             pt_run = new (pt_run_mem) PhaseTimer(SKA_PH_SCALING, st);
         }

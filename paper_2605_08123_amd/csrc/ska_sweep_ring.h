@@ -254,8 +254,14 @@ __global__ __launch_bounds__(NTHREADS) void vsweep_kernel(const SweepArgs a)
             float r;
             if (o >= Le) {
                 r = 0.f;   // rows beyond the valid length
-            } else if (xsp[o] == -INFINITY || (MODE == M_LSE && !(tot > 0.f))) {
-                r = (MODE == M_LSE) ? -INFINITY : 0.f;   // inactive token (stays so), or none of its partners is active
+            } else if (xsp[o] == -INFINITY) {
+                r = (MODE == M_LSE) ? -INFINITY : 0.f;   // inactive token: stays so
+            } else if (MODE == M_LSE && !(tot > 0.f && tot < INFINITY)) {
+                // An active token has active partners (activity is settled by the two cold
+                // half-steps), so an empty or infinite sum here is underflow or overflow: the
+                // potentials inside this workgroup's 128 or 256 rows are spread further than the
+                // fp32 exponent reaches under one stabiliser per workgroup.  Say so.
+                r = __builtin_nanf("");
             } else if constexpr (MODE == M_LSE) {
                 r = mblk - LN2 * fast_log2(tot);
                 if (a.olog.p) r += a.olog.p[n * a.olog.stride + o];
