@@ -193,3 +193,20 @@ def test_paper_scale_one_full_head():
         s_got = got["UV"][0, 0, 2 * t] + got["UV"][0, 0, 2 * t + 1]
         s_ref = ref["UV"][2 * t] + ref["UV"][2 * t + 1]
         assert np.abs(s_got - s_ref).max() < 2e-2, t
+
+
+def test_four_million_tokens():
+    """A sequence sixteen times the benchmark's (L = 2^22, a quarter of the largest L the 32-bit
+    offsets inside one matrix allow), fewer base steps to keep the oracle windows small: both
+    true ends and the middle against the oracle."""
+    from paper_2605_08123_amd.workloads import Workload
+    w = Workload("huge", 9, 1, 1, 1 << 22, 64, 256, 6, 2, 0.5, "bf16")
+    print(f"\n[case] {w}", flush=True)
+    arrays = make_inputs(w)
+    got = run_gpu(w, arrays)
+    for key in ("O", "dQ", "dK", "dV"):
+        assert np.isfinite(got[key]).all(), key
+    L = w.L
+    window_check(w, got, arrays, 0, 0, 0, 1024)
+    window_check(w, got, arrays, 0, 0, L // 2 - 500, L // 2 + 524)
+    window_check(w, got, arrays, 0, 0, L - 1024, L)
