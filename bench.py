@@ -88,6 +88,9 @@ def main() -> int:
                     choices=["one_reference", "direct", "one_reference_generic"],
                     help="how the final sweeps of the backward obtain the plan factors (the last two are "
                          "comparators: every factor by its own exponential / Prop. 2 on the generic kernel)")
+    ap.add_argument("--probe-issue", action="store_true",
+                    help="also run the library's register-only issue-rate probe (exp2+add only, MFMA only, "
+                         "both) and report cycles per tile and SIMD at the nominal clock")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-tokens", type=int, default=262144)
     ap.add_argument("--calibrate-copy", action="store_true",
@@ -217,6 +220,27 @@ def main() -> int:
         "extra": {"head_tokens_per_s": tokens_per_s * w.H, "edge_sweeps_per_s": E * (2 * (w.T + w.R) + 7) / (dt / args.steps),
                   "fwd_ms": fwd_ms, "bwd_ms": bwd_ms},
     }
+    # What a SIMD sustains of the sweep's own instruction mix (register-only probe kernels in the
+    # library: 16 exp2 + 16 adds and four 32x32x16 bf16 MFMAs per 32 x 32 tile, four wavefronts per
+    # SIMD as in the sweep): MFMA and VALU work of different wavefronts overlap only in part, so this
+    # measured rate, not either unit's peak, is what the sweep's inner loop can reach.
+    tiles = 4000
+    ms3, simds = ska.sinkhorn_attn_probe_issue(tiles, 4)
+    tile_s = {k: 1e-3 * t / (tiles * 4) for k, t in zip(("valu_only", "mfma_only", "both"), ms3)}
+    issue_peak = simds * 1024.0 * 1.0 / tile_s["both"] if w.d == 64 and dt_name == "bf16" else None
+    out["roofline"]["issue"] = {
+        "probe_ns_per_tile_and_simd": {k: 1e9 * v for k, v in tile_s.items()},
+        "achieved": E / avg_s / 1e12, "peak": None if issue_peak is None else issue_peak / 1e12,
+        "unit": "T band edges/s", "frac": None if issue_peak is None else E / avg_s / issue_peak,
+        "note": "peak = SIMDs x 1024 edges per tile / measured time of one probe tile (d = 64 bf16 mix)"}
+    if args.probe_issue:
+        probe = {}
+        for wps in (1, 2, 4, 8):
+            ms, _ = ska.sinkhorn_attn_probe_issue(tiles, wps)
+            # cycles one SIMD spends per tile of one wavefront, at the nominal 2.4 GHz
+            probe[f"waves_per_simd_{wps}"] = {k: 1e-3 * t * 2.4e9 / (tiles * wps)
+                                              for k, t in zip(("valu_only", "mfma_only", "both"), ms)}
+        out["issue_probe_cycles_per_tile"] = probe
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(w, min(args.cpu_tokens, w.L))
     print(json.dumps(out))

@@ -294,6 +294,18 @@ int sinkhorn_attn_bwd_variant(int variant, const void *Q, const void *K, const v
  *     2(T + R) - 1 identical launches of the scaling sweep of Eq. 1-2 in every forward call;
  *     one fewer in sinkhorn_attn_fwd_masked, whose first column half-step counts as SKA_PH_FIRST).
  */
+/*
+ * Issue-rate probe (benchmark hook, no part of the operator): runs three register-only kernels
+ * with the instruction mix of one scaling-sweep tile per loop iteration -- 0: 16 exp2 + 16 adds,
+ * 1: four dependent 32x32x16 bf16 MFMAs, 2: both, the exponentials consuming the MFMA result --
+ * with waves_per_simd (1..8) wavefronts resident on every SIMD of the current device, `tiles`
+ * iterations each, and returns their elapsed milliseconds in ms3[0..2] (host array).  It shows
+ * how far MFMA and VALU work of different wavefronts overlap on one SIMD.  scratch: device
+ * buffer of at least CUs * waves_per_simd * 256 floats.  Synchronises the stream.
+ */
+int sinkhorn_attn_probe_issue(float *scratch, size_t scratch_bytes, int tiles, int waves_per_simd,
+                              double *ms3, void *stream);
+
 typedef enum {
     SKA_PH_PRESCALE = 0, /* bf16 storage: copy of Q with the score scale folded in (fwd and bwd) */
     SKA_PH_FIRST = 1,    /* first row half-step of the base solve (no previous iterate:   */

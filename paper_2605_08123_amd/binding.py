@@ -67,6 +67,8 @@ def load():
         lib.sinkhorn_attn_bwd_dustbin_token.argtypes = [vp] * 16 + [i] * 7 + [f, i, vp, sz, vp]
         lib.sinkhorn_attn_fwd_masked.restype = i
         lib.sinkhorn_attn_fwd_masked.argtypes = [vp] * 9 + [i] * 7 + [f, i, vp, sz, vp]
+        lib.sinkhorn_attn_probe_issue.restype = i
+        lib.sinkhorn_attn_probe_issue.argtypes = [vp, sz, i, i, ctypes.POINTER(ctypes.c_double), vp]
         lib.sinkhorn_attn_profile_enable.restype = i
         lib.sinkhorn_attn_profile_enable.argtypes = [i]
         lib.sinkhorn_attn_profile_read.restype = i
@@ -89,6 +91,19 @@ class SinkhornAttnError(RuntimeError):
 
 def sinkhorn_attn_strerror(status: int) -> str:
     return load().sinkhorn_attn_strerror(int(status)).decode()
+
+
+def sinkhorn_attn_probe_issue(tiles=4000, waves_per_simd=4):
+    """Milliseconds of the three issue-rate probe kernels (exp2 + add only, MFMA only, both) and
+    the number of SIMDs they ran on."""
+    cus = torch.cuda.get_device_properties(0).multi_processor_count
+    scratch = torch.empty(cus * waves_per_simd * 256, device="cuda", dtype=torch.float32)
+    ms = (ctypes.c_double * 3)()
+    rc = load().sinkhorn_attn_probe_issue(scratch.data_ptr(), scratch.numel() * 4, int(tiles), int(waves_per_simd), ms,
+                                          _stream_ptr())
+    if rc != SKA_OK:
+        raise SinkhornAttnError(rc)
+    return [ms[0], ms[1], ms[2]], 4 * cus
 
 
 def sinkhorn_attn_profile_enable(level) -> None:

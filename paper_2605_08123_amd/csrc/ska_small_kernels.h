@@ -40,6 +40,41 @@ __global__ void rowdot_kernel(const T *A, const T *Bm, float *g, long gstride, i
     if (sub == 0 && o < Lp) g[n * gstride + o] = acc;
 }
 
+// ---- issue-rate probe (benchmark hook): what one SIMD sustains of the scaling sweep's instruction
+// mix, with no memory traffic.  WHAT 0: 16 exp2 + 16 adds per "tile"; 1: four dependent
+// 32x32x16 bf16 MFMAs per tile; 2: both, the exponentials consuming the MFMA result (the sweep's
+// pattern; other wavefronts of the SIMD are free to fill the gaps).  One float per thread is written.
+template <int WHAT>
+__global__ __launch_bounds__(256) void issue_probe_kernel(float *out, int tiles)
+{
+    bf16x8 a, b;
+#pragma unroll
+    for (int i = 0; i < 8; ++i) { a[i] = (__bf16)(threadIdx.x * 0.01f); b[i] = (__bf16)(i * 0.1f); }
+    f32x16 c0, c;
+#pragma unroll
+    for (int i = 0; i < 16; ++i) { c0[i] = -30.f - 0.01f * i; c[i] = -1.f - 0.01f * i; }
+    float sum = 0.f;
+    for (int it = 0; it < tiles; ++it) {
+        if (WHAT >= 1) {   // the first MFMA starts from a loop-invariant accumulator, as the sweep's does
+            c = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, b, c0, 0, 0, 0);
+#pragma unroll
+            for (int k = 1; k < 4; ++k) c = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, b, c, 0, 0, 0);
+        }
+        if (WHAT == 0) {   // iterated exp2 keeps every exponential dependent on the previous tile
+#pragma unroll
+            for (int r = 0; r < 16; ++r) { c[r] = fast_exp2(c[r]); sum += c[r]; }
+        } else if (WHAT == 2) {
+#pragma unroll
+            for (int r = 0; r < 16; ++r) sum += fast_exp2(c[r]);
+        }
+        if (WHAT >= 1) a[0] = (__bf16)(WHAT == 1 ? c[0] : sum);   // the next tile depends on this one
+    }
+    float s = sum;
+#pragma unroll
+    for (int r = 0; r < 16; ++r) s += c[r];
+    out[blockIdx.x * blockDim.x + threadIdx.x] = s;
+}
+
 // ---- learned dustbin token (Sec. "Single-Active-Dustbin Bridge"): the O(L d) work on the spokes
 // out[n][o] = scale <M[n][o], x[n]> for o < L, out[n][L] = scale <x[n], xc[n]> (the corner).
 // LPR lanes per row, 16 bytes each, like rowdot_kernel.

@@ -721,6 +721,18 @@ def test_error_codes_on_device():
     assert e.value.status == -1
 
 
+def test_issue_probe_hook():
+    """The register-only probe returns three positive times; both units together cost at least as
+    much as either alone and at most their sum (with some slack for clocks and launch overhead)."""
+    import paper_2605_08123_amd as ska
+    ms, simds = ska.sinkhorn_attn_probe_issue(tiles=2000, waves_per_simd=4)
+    print(f"\n[case] issue probe: {ms} ms on {simds} SIMDs", flush=True)
+    assert simds >= 4 and all(t > 0.0 for t in ms)
+    assert max(ms[0], ms[1]) * 0.9 <= ms[2] <= (ms[0] + ms[1]) * 1.25
+    with pytest.raises(ska.SinkhornAttnError):
+        ska.sinkhorn_attn_probe_issue(tiles=0)
+
+
 def test_profile_hooks_count_launches():
     """Benchmark hooks: phase spans bracket the documented numbers of sweep launches."""
     import torch
