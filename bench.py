@@ -91,6 +91,8 @@ def main() -> int:
     ap.add_argument("--probe-issue", action="store_true",
                     help="also run the library's register-only issue-rate probe (exp2+add only, MFMA only, "
                          "both) and report cycles per tile and SIMD at the nominal clock")
+    ap.add_argument("--streams", type=int, default=2, choices=[1, 2],
+                    help="2 (the library's default): half of the problems' sweeps run on its helper stream")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-tokens", type=int, default=262144)
     ap.add_argument("--calibrate-copy", action="store_true",
@@ -121,6 +123,7 @@ def main() -> int:
     wsb = ska.sinkhorn_attn_workspace_bytes(w.B, w.H, w.L, w.d, w.W, w.T, w.R, w.dustbin, code)
     wsp = torch.empty(wsb, device=dev, dtype=torch.uint8)
 
+    ska.sinkhorn_attn_set_streams(args.streams)
     variant = {"one_reference": 0, "direct": 1, "one_reference_generic": 2}[args.backward]
 
     def step():
@@ -200,7 +203,8 @@ def main() -> int:
         "ms_per_step": ms_per_step, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": dt_name, "data": "synthetic",
         "config": {"workload": w.name, "B": w.B, "H": w.H, "L": w.L, "d": w.d, "W": w.W, "T": w.T,
-                   "R": w.R, "eps": w.eps, "dustbin": w.dustbin, "backward": args.backward},
+                   "R": w.R, "eps": w.eps, "dustbin": w.dustbin, "backward": args.backward,
+                   "streams": args.streams},
         # the scaling sweep against its three ceilings; the one that binds (the largest lower bound on
         # a launch's time: 20.5 us ALU, 17.3 us HBM, 13.8 us MFMA at this workload) is the plain-ALU
         # issue rate of one exp2 and one add per band edge

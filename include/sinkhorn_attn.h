@@ -20,9 +20,16 @@
  *
  * Conventions common to every entry point
  *   - Every pointer is a DEVICE pointer owned by the caller unless stated.  The
- *     library allocates nothing, frees nothing and keeps no pointer after return.
+ *     library allocates no device memory, frees nothing and keeps no pointer after return.
  *   - Work is enqueued on `stream` (a hipStream_t passed as void*, NULL = the
- *     null stream) and is asynchronous with respect to the host.
+ *     null stream) and is asynchronous with respect to the host.  A call on two or more
+ *     problems (B*H >= 2) runs the band sweeps of the second half of its problems on a helper
+ *     stream that the library creates once per device (non-blocking, default priority, never
+ *     destroyed): it is forked from `stream` by an event after the call's first kernels and
+ *     joined to it again before the call returns, so everything the call does is ordered on
+ *     `stream` as seen by the caller, also under stream capture.  sinkhorn_attn_set_streams(1)
+ *     keeps all work on `stream` itself.  Calls from several host threads at once are not
+ *     supported.
  *   - Tensors Q, K, V, O, dO, dQ, dK, dV are [B, H, L, d], contiguous, row-major,
  *     of the element type `dtype` (SKA_F32: float; SKA_BF16: bfloat16).  All
  *     scaling vectors and all accumulation are fp32.
@@ -294,6 +301,12 @@ int sinkhorn_attn_bwd_variant(int variant, const void *Q, const void *K, const v
  *     2(T + R) - 1 identical launches of the scaling sweep of Eq. 1-2 in every forward call;
  *     one fewer in sinkhorn_attn_fwd_masked, whose first column half-step counts as SKA_PH_FIRST).
  */
+/*
+ * Number of streams a call spreads its band sweeps over: 2 (default; see the conventions at the
+ * top) or 1.  Process-wide.  Returns SKA_OK, or SKA_EINVAL for any other number.
+ */
+int sinkhorn_attn_set_streams(int n);
+
 /*
  * Issue-rate probe (benchmark hook, no part of the operator): runs three register-only kernels
  * with the instruction mix of one scaling-sweep tile per loop iteration -- 0: 16 exp2 + 16 adds,

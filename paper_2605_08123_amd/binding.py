@@ -69,6 +69,8 @@ def load():
         lib.sinkhorn_attn_fwd_masked.argtypes = [vp] * 9 + [i] * 7 + [f, i, vp, sz, vp]
         lib.sinkhorn_attn_probe_issue.restype = i
         lib.sinkhorn_attn_probe_issue.argtypes = [vp, sz, i, i, ctypes.POINTER(ctypes.c_double), vp]
+        lib.sinkhorn_attn_set_streams.restype = i
+        lib.sinkhorn_attn_set_streams.argtypes = [i]
         lib.sinkhorn_attn_profile_enable.restype = i
         lib.sinkhorn_attn_profile_enable.argtypes = [i]
         lib.sinkhorn_attn_profile_read.restype = i
@@ -104,6 +106,14 @@ def sinkhorn_attn_probe_issue(tiles=4000, waves_per_simd=4):
     if rc != SKA_OK:
         raise SinkhornAttnError(rc)
     return [ms[0], ms[1], ms[2]], 4 * cus
+
+
+def sinkhorn_attn_set_streams(n: int) -> None:
+    """2 (default): a call on several problems runs half of its sweeps on the library's helper
+    stream; 1: everything on the caller's stream."""
+    rc = load().sinkhorn_attn_set_streams(int(n))
+    if rc != SKA_OK:
+        raise SinkhornAttnError(rc)
 
 
 def sinkhorn_attn_profile_enable(level) -> None:

@@ -66,6 +66,7 @@ struct SweepArgs {
     const int *len_own;   // valid owner-side length of each batch item (null: L), device memory [N / nh]
     const int *len_oth;   // valid other-side length of each batch item (null: L)
     int nh;               // problems per batch item (heads)
+    int n0;               // index of this launch's first problem within the call (launches may take a part)
     float c2;         // log2(e) / (eps sqrt d)
     float cs;         // 1 / (eps sqrt d)
     int dustbin;
@@ -99,8 +100,8 @@ struct Lens { int Lt, Le; };
 __device__ __forceinline__ Lens problem_lens(const SweepArgs &a, int n)
 {
     int Lo = a.L, Lt = a.L;
-    if (a.len_own) Lo = min(max(a.len_own[n / a.nh], 0), a.L);
-    if (a.len_oth) Lt = min(max(a.len_oth[n / a.nh], 0), a.L);
+    if (a.len_own) Lo = min(max(a.len_own[(n + a.n0) / a.nh], 0), a.L);
+    if (a.len_oth) Lt = min(max(a.len_oth[(n + a.n0) / a.nh], 0), a.L);
     return Lens{Lt, Lt > 0 ? min(Lo, Lt + a.W) : 0};
 }
 // A workgroup whose owner rows all lie beyond the valid length writes its zeros and leaves.

@@ -28,6 +28,7 @@ def test_library_exports_every_declared_symbol():
                      "sinkhorn_attn_probe_issue", "sinkhorn_attn_profile_enable",
                      "sinkhorn_attn_profile_read", "sinkhorn_attn_profile_read_phases",
                      "sinkhorn_attn_select_tail_depth", "sinkhorn_attn_select_workspace_bytes",
+                     "sinkhorn_attn_set_streams",
                      "sinkhorn_attn_strerror",
                      "sinkhorn_attn_workspace_bytes"]
     for n in names:
@@ -105,6 +106,7 @@ def test_argument_errors_are_reported_before_any_launch():
                                                         None, 0, None)
     assert tok(nul) == binding.SKA_EINVAL and tok(ctypes.c_void_p((1 << 20) + 4)) == binding.SKA_EINVAL
     assert tok(pp) == binding.SKA_EWORKSPACE
+    assert lib.sinkhorn_attn_set_streams(3) == binding.SKA_EINVAL and lib.sinkhorn_attn_set_streams(2) == binding.SKA_OK
     assert _bwd(lib, ws=None, ws_bytes=0) == binding.SKA_EWORKSPACE
     assert _fwd(lib, dtype=1) == binding.SKA_EWORKSPACE          # bf16 forward needs its scratch
     need = binding.sinkhorn_attn_workspace_bytes(1, 1, 64, 32, 4, 2, dtype=0)
