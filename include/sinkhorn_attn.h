@@ -23,7 +23,8 @@
  *     library allocates no device memory, frees nothing and keeps no pointer after return.
  *   - Work is enqueued on `stream` (a hipStream_t passed as void*, NULL = the
  *     null stream) and is asynchronous with respect to the host.  A call on two or more
- *     problems (B*H >= 2) runs the band sweeps of the second half of its problems on a helper
+ *     problems (B*H >= 2) whose sweeps are long enough to be worth two dispatches (at least
+ *     50 M band edges per half) runs the band sweeps of the second half of its problems on a helper
  *     stream that the library creates once per device (non-blocking, default priority, never
  *     destroyed): it is forked from `stream` by an event after the call's first kernels and
  *     joined to it again before the call returns, so everything the call does is ordered on
@@ -306,6 +307,12 @@ int sinkhorn_attn_bwd_variant(int variant, const void *Q, const void *K, const v
  * top) or 1.  Process-wide.  Returns SKA_OK, or SKA_EINVAL for any other number.
  */
 int sinkhorn_attn_set_streams(int n);
+/*
+ * The least number of band edges per dispatch (half of a call's problems times L times 2W + 1)
+ * from which a call uses the helper stream; default 5e7.  0 makes every call on two or more
+ * problems split (used by the tests to run small cases through both streams).  Process-wide.
+ */
+int sinkhorn_attn_set_split_min_edges(double edges);
 
 /*
  * Issue-rate probe (benchmark hook, no part of the operator): runs three register-only kernels

@@ -71,6 +71,8 @@ def load():
         lib.sinkhorn_attn_probe_issue.argtypes = [vp, sz, i, i, ctypes.POINTER(ctypes.c_double), vp]
         lib.sinkhorn_attn_set_streams.restype = i
         lib.sinkhorn_attn_set_streams.argtypes = [i]
+        lib.sinkhorn_attn_set_split_min_edges.restype = i
+        lib.sinkhorn_attn_set_split_min_edges.argtypes = [ctypes.c_double]
         lib.sinkhorn_attn_profile_enable.restype = i
         lib.sinkhorn_attn_profile_enable.argtypes = [i]
         lib.sinkhorn_attn_profile_read.restype = i
@@ -112,6 +114,13 @@ def sinkhorn_attn_set_streams(n: int) -> None:
     """2 (default): a call on several problems runs half of its sweeps on the library's helper
     stream; 1: everything on the caller's stream."""
     rc = load().sinkhorn_attn_set_streams(int(n))
+    if rc != SKA_OK:
+        raise SinkhornAttnError(rc)
+
+
+def sinkhorn_attn_set_split_min_edges(edges: float) -> None:
+    """Band edges per dispatch from which a call uses the helper stream (default 5e7; 0: always)."""
+    rc = load().sinkhorn_attn_set_split_min_edges(float(edges))
     if rc != SKA_OK:
         raise SinkhornAttnError(rc)
 

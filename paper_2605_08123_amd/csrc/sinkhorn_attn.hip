@@ -250,6 +250,7 @@ struct Side {
 };
 Side g_side[16];
 int g_streams = 2;            // sinkhorn_attn_set_streams: 1 = everything on the caller's stream
+double g_split_min_edges = 50e6;   // sinkhorn_attn_set_split_min_edges
 Side *g_cur_side = nullptr;   // set while a call splits its sweeps (one host thread at a time)
 bool g_side_busy = false;     // the helper stream holds work that the caller's stream has not joined
 
@@ -288,9 +289,13 @@ int side_join(hipStream_t st)
 }
 
 struct SideScope {   // a call that may split its sweeps
-    explicit SideScope(int nproblems)
+    // Splitting doubles the dispatches of a call, which pays only while a dispatch is long against
+    // the host's cost of enqueueing it: at least 50 M band edges per dispatch (about 10 us).  Below
+    // that (measured: 17 M and 34 M edges per dispatch) two streams are no faster or slower.
+    SideScope(int nproblems, int L, int W)
     {
-        g_cur_side = (g_streams >= 2 && nproblems >= 2) ? side_for_current_device() : nullptr;
+        const double edges = (double)(nproblems / 2) * L * (2.0 * (W < L ? W : L) + 1.0);
+        g_cur_side = (g_streams >= 2 && nproblems >= 2 && edges >= g_split_min_edges) ? side_for_current_device() : nullptr;
         g_side_busy = false;
     }
     ~SideScope() { g_cur_side = nullptr; }
@@ -723,7 +728,7 @@ static int fwd_call(const Problem &p, const void *Q, const void *K, const void *
     if (p.token() && (!workspace || workspace_bytes < ws_bytes(p))) return SKA_EWORKSPACE;
     if (reinterpret_cast<uintptr_t>(workspace) & 15) return SKA_EINVAL;
     hipStream_t st = reinterpret_cast<hipStream_t>(stream);
-    SideScope split(p.N());
+    SideScope split(p.N(), p.L, p.W);
 #define SKA_FWD(TT_, DD_) return fwd_impl<TT_, DD_>(p, Q, K, V, O, UV, workspace, st)
     if (dtype == SKA_F32) {
         if (d == 32) SKA_FWD(float, 32);
@@ -845,7 +850,7 @@ static int bwd_problem(const Problem &p, const void *Q, const void *K, const voi
     if (!workspace || workspace_bytes < ws_bytes(p)) return SKA_EWORKSPACE;
     if (reinterpret_cast<uintptr_t>(workspace) & 15) return SKA_EINVAL;
     hipStream_t st = reinterpret_cast<hipStream_t>(stream);
-    SideScope split(p.N());
+    SideScope split(p.N(), p.L, p.W);
 #define SKA_BWD(TT_, DD_) return bwd_impl<TT_, DD_>(p, Q, K, V, O, dO, UV, dQ, dK, dV, eta0, workspace, st)
     if (dtype == SKA_F32) {
         if (d == 32) SKA_BWD(float, 32);
@@ -873,7 +878,7 @@ int sinkhorn_attn_base_vjp(const void *Q, const void *K, const float *log_a, con
     if (!workspace || workspace_bytes < ws_bytes(p)) return SKA_EWORKSPACE;
     if (reinterpret_cast<uintptr_t>(workspace) & 15) return SKA_EINVAL;
     hipStream_t st = reinterpret_cast<hipStream_t>(stream);
-    SideScope split(p.N());
+    SideScope split(p.N(), p.L, p.W);
 #define SKA_VJP(TT_, DD_) \
     return bwd_impl<TT_, DD_>(p, Q, K, nullptr, nullptr, nullptr, UV, dQ, dK, nullptr, nullptr, workspace, st, eta)
     if (dtype == SKA_F32) {
@@ -1037,6 +1042,13 @@ int sinkhorn_attn_set_streams(int n)
 {
     if (n != 1 && n != 2) return SKA_EINVAL;
     g_streams = n;
+    return SKA_OK;
+}
+
+int sinkhorn_attn_set_split_min_edges(double edges)
+{
+    if (!(edges >= 0.0)) return SKA_EINVAL;
+    g_split_min_edges = edges;
     return SKA_OK;
 }
 

@@ -12,6 +12,17 @@ from paper_2605_08123_amd.workloads import CONFIGS, Workload, make_inputs
 
 pytestmark = pytest.mark.gpu
 
+
+@pytest.fixture(autouse=True, scope="module", params=["default", "two_streams"])
+def stream_split(request):
+    """Every case of this module runs twice: with the library's own choice (cases this small stay
+    on one stream) and with the split onto the helper stream forced for every call on two or more
+    problems."""
+    import paper_2605_08123_amd as ska
+    ska.sinkhorn_attn_set_split_min_edges(0.0 if request.param == "two_streams" else 5e7)
+    yield request.param
+    ska.sinkhorn_attn_set_split_min_edges(5e7)
+
 TOL = {"f32": 1e-4, "bf16": 2e-2}
 
 
