@@ -93,6 +93,9 @@ def main() -> int:
                          "both) and report cycles per tile and SIMD at the nominal clock")
     ap.add_argument("--streams", type=int, default=2, choices=[1, 2],
                     help="2 (the library's default): half of the problems' sweeps run on its helper stream")
+    ap.add_argument("--separate-calls", action="store_true",
+                    help="a step as two library calls (sinkhorn_attn_fwd, then the backward) instead of the "
+                         "one-call step")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-tokens", type=int, default=262144)
     ap.add_argument("--calibrate-copy", action="store_true",
@@ -127,6 +130,10 @@ def main() -> int:
     variant = {"one_reference": 0, "direct": 1, "one_reference_generic": 2}[args.backward]
 
     def step():
+        if not args.separate_calls and variant == 0:
+            ska.sinkhorn_attn_step(Q, K, V, G, w.W, w.T, w.R, w.eps, w.dustbin, w.dustbin_score, workspace=wsp, O=O,
+                                   UV=UV, dQ=dQ, dK=dK, dV=dV)
+            return
         ska.sinkhorn_attn_fwd(Q, K, V, w.W, w.T, w.R, w.eps, w.dustbin, w.dustbin_score, O=O, UV=UV,
                               workspace=wsp)
         ska.sinkhorn_attn_bwd_variant(variant, Q, K, V, None, None, None, None, O, G, UV, w.W, w.T, w.R, w.eps,
@@ -204,7 +211,7 @@ def main() -> int:
         "dtype": dt_name, "data": "synthetic",
         "config": {"workload": w.name, "B": w.B, "H": w.H, "L": w.L, "d": w.d, "W": w.W, "T": w.T,
                    "R": w.R, "eps": w.eps, "dustbin": w.dustbin, "backward": args.backward,
-                   "streams": args.streams},
+                   "streams": args.streams, "calls_per_step": 2 if (args.separate_calls or variant) else 1},
         # the scaling sweep against its three ceilings; the one that binds (the largest lower bound on
         # a launch's time: 20.5 us ALU, 17.3 us HBM, 13.8 us MFMA at this workload) is the plain-ALU
         # issue rate of one exp2 and one add per band edge

@@ -105,6 +105,23 @@ int sinkhorn_attn_bwd(const void *Q, const void *K, const void *V, const void *O
                       void *stream);
 
 /*
+ * Forward and backward in one call, for a cotangent dO that is known beforehand (the paper's
+ * "complete-step executable": output plus the Q/K/V VJP for a given output cotangent, which is
+ * what its throughput is quoted on).  Results are those of sinkhorn_attn_fwd_varlen followed by
+ * sinkhorn_attn_bwd_varlen, bit for bit; what the single call saves is the second prescale of Q
+ * and the joining of the two streams between the two directions: each half of the problems runs
+ * its forward and its backward as one uninterrupted chain.
+ *   in : Q, K, V, dO; log_a, log_b, len_q, len_k as in those calls (may be NULL)
+ *   out: O, UV, dQ, dK, dV, eta0 (may be NULL)
+ *   workspace: sinkhorn_attn_workspace_bytes(...) bytes, 16-byte aligned.
+ */
+int sinkhorn_attn_step(const void *Q, const void *K, const void *V, const void *dO,
+                       const float *log_a, const float *log_b, const int *len_q, const int *len_k,
+                       void *O, float *UV, void *dQ, void *dK, void *dV, float *eta0, int B, int H,
+                       int L, int d, int W, int T, int R, float eps, int dustbin, float dustbin_score,
+                       int dtype, void *workspace, size_t workspace_bytes, void *stream);
+
+/*
  * The same two calls with compatible general marginals (appendix "Compatible General
  * Marginals": half-steps u_i = log a_i - log sum_j exp(S_ij + v_j), v_j = log b_j - log sum_i
  * exp(S_ij + u_i); in the backward every ubar is divided by a and every vbar by b where it

@@ -73,6 +73,8 @@ def load():
         lib.sinkhorn_attn_set_streams.argtypes = [i]
         lib.sinkhorn_attn_set_split_min_edges.restype = i
         lib.sinkhorn_attn_set_split_min_edges.argtypes = [ctypes.c_double]
+        lib.sinkhorn_attn_step.restype = i
+        lib.sinkhorn_attn_step.argtypes = [vp] * 14 + [i] * 7 + [f, i, f, i, vp, sz, vp]
         lib.sinkhorn_attn_profile_enable.restype = i
         lib.sinkhorn_attn_profile_enable.argtypes = [i]
         lib.sinkhorn_attn_profile_read.restype = i
@@ -363,6 +365,40 @@ def sinkhorn_attn_bwd_dustbin_token(Q, K, V, q_db, k_db, v_db, O, dO, UV, W, T, 
     if rc != SKA_OK:
         raise SinkhornAttnError(rc)
     return (dQ, dK, dV, dq, dk, dv, eta0) if want_eta0 else (dQ, dK, dV, dq, dk, dv)
+
+
+def sinkhorn_attn_step(Q, K, V, dO, W, T, R=2, eps=1.0, dustbin=False, dustbin_score=0.0, log_a=None, log_b=None,
+                       len_q=None, len_k=None, want_eta0=False, workspace=None, O=None, UV=None, dQ=None, dK=None,
+                       dV=None):
+    """Forward and backward in one call for a cotangent known beforehand.
+    Returns (O, UV, dQ, dK, dV[, eta0])."""
+    B, H, L, d = Q.shape
+    for n, x in (("Q", Q), ("K", K), ("V", V), ("dO", dO)):
+        _check(x, (B, H, L, d), Q.dtype, n)
+    Lp = L + int(bool(dustbin))
+    O = torch.empty_like(Q) if O is None else O
+    dQ = torch.empty_like(Q) if dQ is None else dQ
+    dK = torch.empty_like(Q) if dK is None else dK
+    dV = torch.empty_like(Q) if dV is None else dV
+    if UV is None:
+        UV = torch.empty((B, H, 2 * (R + 1), Lp), device=Q.device, dtype=torch.float32)
+    for n, x in (("O", O), ("dQ", dQ), ("dK", dK), ("dV", dV)):
+        _check(x, (B, H, L, d), Q.dtype, n)
+    _check(UV, (B, H, 2 * (R + 1), Lp), torch.float32, "UV")
+    code = _dtype_code(Q)
+    if workspace is None:
+        workspace = torch.empty(max(sinkhorn_attn_workspace_bytes(B, H, L, d, W, T, R, dustbin, code), 16),
+                                device=Q.device, dtype=torch.uint8)
+    eta0 = torch.empty((B, H, Lp), device=Q.device, dtype=torch.float32) if want_eta0 else None
+    rc = load().sinkhorn_attn_step(
+        Q.data_ptr(), K.data_ptr(), V.data_ptr(), dO.data_ptr(), _marg_ptr(log_a, (B, H, L), "log_a"),
+        _marg_ptr(log_b, (B, H, L), "log_b"), _len_ptr(len_q, B, "len_q"), _len_ptr(len_k, B, "len_k"), O.data_ptr(),
+        UV.data_ptr(), dQ.data_ptr(), dK.data_ptr(), dV.data_ptr(), eta0.data_ptr() if want_eta0 else None, B, H, L, d,
+        W, T, R, float(eps), int(bool(dustbin)), float(dustbin_score), code, workspace.data_ptr(),
+        workspace.numel() * workspace.element_size(), _stream_ptr())
+    if rc != SKA_OK:
+        raise SinkhornAttnError(rc)
+    return (O, UV, dQ, dK, dV, eta0) if want_eta0 else (O, UV, dQ, dK, dV)
 
 
 def sinkhorn_attn_select_workspace_bytes(B, H, L, d, W, T, R_max, dustbin=False, dtype=SKA_BF16) -> int:

@@ -363,14 +363,18 @@ struct PhaseTimer {
 
 template <typename T, int D>
 int fwd_impl(const Problem &p, const void *Qin, const void *K, const void *V, void *O, float *UV,
-             void *ws, hipStream_t st)
+             void *ws, hipStream_t st, bool fused = false)
 {
+    // fused: the backward of the same call follows (sinkhorn_attn_step).  The prescaled operand
+    // then goes where the backward expects it, and the helper stream is not joined at the end:
+    // each half of the problems runs its forward and backward as one uninterrupted chain.
     // Q below is the score operand: for bf16 storage the prescaled copy, with c2 = 1
     const void *Q = nullptr;
     float c2 = 0.f;
     {
         PhaseTimer pt(SKA_PH_PRESCALE, st);
-        SKA_TRY((make_scores_operand<T>(p, p.n_stages ? p.eps_stage[0] : p.eps, Qin, ws, &Q, &c2, st)));
+        void *ws_q = fused ? reinterpret_cast<unsigned char *>(ws) + ws_vec_bytes(p) : ws;
+        SKA_TRY((make_scores_operand<T>(p, p.n_stages ? p.eps_stage[0] : p.eps, Qin, ws_q, &Q, &c2, st)));
         pt.launched(sizeof(T) == 2 ? 1 : 0);
     }
     const int N = p.N(), L = p.L, Lp = p.Lp();
@@ -480,14 +484,16 @@ int fwd_impl(const Problem &p, const void *Qin, const void *K, const void *V, vo
     pt_out.launched();
     SKA_TRY((sweep<T, D>(M_APPLY, a, N, st)));
     pt_out.end();
-    return side_join(st);
+    return fused ? SKA_OK : side_join(st);
 }
 
 template <typename T, int D>
 int bwd_impl(const Problem &p, const void *Qin, const void *K, const void *V, const void *O,
              const void *G, const float *UV, void *dQ, void *dK, void *dV, float *eta0, void *ws,
-             hipStream_t st, const float *seed = nullptr)
+             hipStream_t st, const float *seed = nullptr, bool fused = false)
 {
+    // fused: the forward of the same call has just run (sinkhorn_attn_step): its prescaled operand
+    // is in place, and the helper stream is still running its half of the problems.
     // seed != null: no output map at the end of the chain.  The reverse recurrences start from
     // vbar_R = seed (a cotangent of v^(R) given by the caller), Z = 0, and only dQ, dK are
     // produced: the vector-Jacobian product through R full steps started at v = 0.
@@ -495,7 +501,10 @@ int bwd_impl(const Problem &p, const void *Qin, const void *K, const void *V, co
     // c2 = 1); it also serves as the payload of the dK sweep, whose output scale absorbs it
     const void *Q = nullptr;
     float c2 = 0.f;
-    {
+    if (fused) {
+        Q = (sizeof(T) == 2) ? reinterpret_cast<unsigned char *>(ws) + ws_vec_bytes(p) : Qin;
+        c2 = (sizeof(T) == 2) ? 1.f : LOG2E / (p.eps * sqrtf((float)p.d));
+    } else {
         PhaseTimer pt(SKA_PH_PRESCALE, st);
         SKA_TRY((make_scores_operand<T>(p, p.eps, Qin, reinterpret_cast<unsigned char *>(ws) + ws_vec_bytes(p), &Q, &c2, st)));
         pt.launched(sizeof(T) == 2 ? 1 : 0);
@@ -532,6 +541,10 @@ int bwd_impl(const Problem &p, const void *Qin, const void *K, const void *V, co
     float *sbr = tok ? tok + 2 * nldp : nullptr, *sbc = tok ? tok + 3 * nldp : nullptr;
     float *partial = tok ? tok + 4 * nldp : nullptr;
     const int nchunk = ws_chunks(p);
+    // the kernels before the sweeps take all problems on st -- except the plain row dot of a fused
+    // step, which each stream does for its own half so that the two chains stay apart
+    const bool own_halves = fused && g_cur_side && !seed && !p.dustbin;
+    if (fused && !own_halves) SKA_TRY(side_join(st));
     if (p.token()) {
         SQ = Vec{tok, ldw};
         SK = Vec{tok + nldp, ldw};
@@ -546,9 +559,15 @@ int bwd_impl(const Problem &p, const void *Qin, const void *K, const void *V, co
         hipLaunchKernelGGL(seed_kernel, vgrid, dim3(256), 0, st, seed, p.log_b, vbar(R), ldw, Lp);
         if (hipGetLastError() != hipSuccess) return SKA_EHIP;
     } else {
-        hipLaunchKernelGGL((rowdot_kernel<T, D>), dim3(((long)Lp * LPR + 255) / 256, N), dim3(256), 0, st,
+        const int n1 = own_halves ? N / 2 : N;
+        hipLaunchKernelGGL((rowdot_kernel<T, D>), dim3(((long)Lp * LPR + 255) / 256, n1), dim3(256), 0, st,
                            reinterpret_cast<const T *>(G),
-                           reinterpret_cast<const T *>(O), gu, ldw, L, Lp, p.len_q, p.H);
+                           reinterpret_cast<const T *>(O), gu, ldw, L, Lp, p.len_q, p.H, 0);
+        if (N > n1)
+            hipLaunchKernelGGL((rowdot_kernel<T, D>), dim3(((long)Lp * LPR + 255) / 256, N - n1), dim3(256), 0,
+                               g_cur_side->s, reinterpret_cast<const T *>(G) + (long)n1 * L * D,
+                               reinterpret_cast<const T *>(O) + (long)n1 * L * D, gu + n1 * ldw, ldw, L, Lp, p.len_q,
+                               p.H, n1);
         if (hipGetLastError() != hipSuccess) return SKA_EHIP;
         if (p.token()) {
             // dv_db = sum_i P_RR(i, d_k) dO_i and vbar_R at the dustbin column = <v_db, dv_db>
@@ -563,7 +582,7 @@ int bwd_impl(const Problem &p, const void *Qin, const void *K, const void *V, co
         }
     }
     pt_gu.end();
-    SKA_TRY(side_fork(st));   // everything above ran for all problems on st
+    if (!own_halves) SKA_TRY(side_fork(st));   // everything above ran for all problems on st
     // dV_j = sum_i P_RR,ij dO_i ; vbar_R,j = <V_j, dV_j>  (column-oriented)
     if (!seed) {
         PhaseTimer pt(SKA_PH_DV, st);
@@ -915,6 +934,40 @@ int sinkhorn_attn_bwd_variant(int variant, const void *Q, const void *K, const v
         return SKA_EINVAL;
     return bwd_call(variant, Q, K, V, log_a, log_b, len_q, len_k, O, dO, UV, dQ, dK, dV, eta0, B, H, L, d, W, T, R, eps,
                     dustbin, dustbin_score, dtype, workspace, workspace_bytes, stream);
+}
+
+int sinkhorn_attn_step(const void *Q, const void *K, const void *V, const void *dO, const float *log_a,
+                       const float *log_b, const int *len_q, const int *len_k, void *O, float *UV, void *dQ,
+                       void *dK, void *dV, float *eta0, int B, int H, int L, int d, int W, int T, int R, float eps,
+                       int dustbin, float dustbin_score, int dtype, void *workspace, size_t workspace_bytes,
+                       void *stream)
+{
+    Problem p{B, H, L, d, W, T, R, dustbin ? 1 : 0, dtype, eps, dustbin_score, log_a, log_b, len_q, len_k};
+    if (!Q || !K || !V || !dO || !O || !UV || !dQ || !dK || !dV) return SKA_EINVAL;
+    int rc = check_common(p);
+    if (rc != SKA_OK) return rc;
+    if (!workspace || workspace_bytes < ws_bytes(p)) return SKA_EWORKSPACE;
+    if (reinterpret_cast<uintptr_t>(workspace) & 15) return SKA_EINVAL;
+    hipStream_t st = reinterpret_cast<hipStream_t>(stream);
+    SideScope split(p.N(), p.L, p.W);
+#define SKA_STEP(TT_, DD_)                                                                              \
+    do {                                                                                                \
+        rc = fwd_impl<TT_, DD_>(p, Q, K, V, O, UV, workspace, st, true);                                \
+        if (rc == SKA_OK)                                                                               \
+            rc = bwd_impl<TT_, DD_>(p, Q, K, V, O, dO, UV, dQ, dK, dV, eta0, workspace, st, nullptr, true); \
+        if (rc != SKA_OK) (void)side_join(st);                                                          \
+        return rc;                                                                                      \
+    } while (0)
+    if (dtype == SKA_F32) {
+        if (d == 32) SKA_STEP(float, 32);
+        if (d == 64) SKA_STEP(float, 64);
+        SKA_STEP(float, 128);
+    } else {
+        if (d == 32) SKA_STEP(__bf16, 32);
+        if (d == 64) SKA_STEP(__bf16, 64);
+        SKA_STEP(__bf16, 128);
+    }
+#undef SKA_STEP
 }
 
 int sinkhorn_attn_bwd_marginals(const void *Q, const void *K, const void *V, const float *log_a,

@@ -16,15 +16,16 @@ __global__ void fill_kernel(float *p, long per, long stride, int nprob, float va
 // g = 0 from there to Lp.  A row is read by D * sizeof(T) / 16 neighbouring
 // lanes, 16 bytes each (whole 128-byte lines per group of lanes), and reduced across them.
 template <typename T, int D>
-__global__ void rowdot_kernel(const T *A, const T *Bm, float *g, long gstride, int L, int Lp, const int *len, int nh)
-{
+__global__ void rowdot_kernel(const T *A, const T *Bm, float *g, long gstride, int L, int Lp, const int *len, int nh,
+                              int n0)
+{   // (n0: index of this launch's first problem within the call, for the length lookup)
     constexpr int LPR = D * (int)sizeof(T) / 16;   // lanes per row: 4 ... 32, a power of two
     constexpr int EPL = 16 / (int)sizeof(T);       // elements per lane
     const int n = blockIdx.y;
     const long p = (long)blockIdx.x * blockDim.x + threadIdx.x;
     const int o = (int)(p / LPR), sub = (int)(p % LPR);
     float acc = 0.f;
-    const int Lv = len ? min(max(len[n / nh], 0), L) : L;
+    const int Lv = len ? min(max(len[(n + n0) / nh], 0), L) : L;
     if (o < Lv) {
         const T *pa = A + ((long)n * L + o) * D + sub * EPL, *pb = Bm + ((long)n * L + o) * D + sub * EPL;
 #pragma unroll

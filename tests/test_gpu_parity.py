@@ -531,6 +531,38 @@ def test_degenerate_lengths_and_masks(dtype, d):
     assert torch.allclose(O[3:4].float(), O3.float(), rtol=2e-2 if dtype == "bf16" else 1e-4, atol=1e-2 if dtype == "bf16" else 1e-5)
 
 
+@pytest.mark.parametrize("dtype,d,kind", [("f32", 32, "plain"), ("bf16", 64, "plain"), ("bf16", 64, "dustbin"),
+                                          ("f32", 64, "marginals"), ("bf16", 128, "varlen")])
+def test_step_is_forward_then_backward(dtype, d, kind):
+    """The one-call step (forward + backward for a given cotangent) gives the results of the two
+    separate calls bit for bit."""
+    import torch
+
+    import paper_2605_08123_amd as ska
+    db = kind == "dustbin"
+    w = small("step", 700, d, 33, 5, dtype, eps=0.8, B=2, H=2, dustbin=db, dustbin_score=0.1)
+    print(f"\n[case] {w} one-call step ({kind})", flush=True)
+    arrays = make_inputs(w, 81)
+    dev = torch.device("cuda:0")
+    td = torch.float32 if dtype == "f32" else torch.bfloat16
+    Q, K, V, G = (torch.from_numpy(x).to(dev).to(td) for x in arrays)
+    la = lb = lq = lk = None
+    if kind == "marginals":
+        la, lb = (torch.from_numpy(x).to(dev) for x in _targets(w, 82))
+    if kind == "varlen":
+        lq = torch.tensor([700, 333], dtype=torch.int32, device=dev)
+        lk = torch.tensor([512, 700], dtype=torch.int32, device=dev)
+    O, UV, dQ, dK, dV, eta = ska.sinkhorn_attn_step(Q, K, V, G, w.W, w.T, w.R, w.eps, db, w.dustbin_score, la, lb, lq,
+                                                    lk, want_eta0=True)
+    O0, UV0 = ska.sinkhorn_attn_fwd_varlen(Q, K, V, la, lb, lq, lk, w.W, w.T, w.R, w.eps, db, w.dustbin_score)
+    g0 = ska.sinkhorn_attn_bwd_varlen(Q, K, V, la, lb, lq, lk, O0, G, UV0, w.W, w.T, w.R, w.eps, db, w.dustbin_score,
+                                      want_eta0=True)
+    torch.cuda.synchronize()
+    assert torch.equal(O, O0) and torch.equal(UV, UV0)
+    for name, x, y in zip(("dQ", "dK", "dV", "eta0"), (dQ, dK, dV, eta), g0):
+        assert torch.equal(x, y), name
+
+
 def test_dense_widened_band_dustbin():
     """The paper's own dustbin path: one learned token appended per side and a band wide enough
     to cover everything (W~ = max(W, L)).  That is the plain operator on the augmented tensors;
