@@ -563,6 +563,36 @@ def test_step_is_forward_then_backward(dtype, d, kind):
         assert torch.equal(x, y), name
 
 
+def test_caller_streams_and_ordering():
+    """Work is ordered on the caller's stream whichever it is: results on a side stream of the
+    caller equal those on the default stream, and a consumer enqueued on that stream right after
+    the call (no host synchronisation) sees the finished output -- also when the library spreads
+    the sweeps over its helper stream."""
+    import torch
+
+    import paper_2605_08123_amd as ska
+    w = small("streams", 2000, 64, 30, 5, "bf16", eps=0.7, B=2, H=2)
+    print(f"\n[case] {w} caller streams", flush=True)
+    dev = torch.device("cuda:0")
+    Q, K, V, G = (torch.from_numpy(x).to(dev).to(torch.bfloat16) for x in make_inputs(w, 91))
+    O0, UV0, dQ0, dK0, dV0 = ska.sinkhorn_attn_step(Q, K, V, G, w.W, w.T, w.R, w.eps)
+    torch.cuda.synchronize()
+    s = torch.cuda.Stream()
+    for rep in range(3):
+        with torch.cuda.stream(s):
+            O1, UV1, dQ1, dK1, dV1 = ska.sinkhorn_attn_step(Q, K, V, G, w.W, w.T, w.R, w.eps)
+            checks = [(a.float() - b.float()).abs().max() for a, b in ((O1, O0), (dQ1, dQ0), (dK1, dK0), (dV1, dV0))]
+        s.synchronize()
+        assert all(float(c) == 0.0 for c in checks), rep
+    ska.sinkhorn_attn_set_streams(1)
+    try:
+        O2, UV2, dQ2, dK2, dV2 = ska.sinkhorn_attn_step(Q, K, V, G, w.W, w.T, w.R, w.eps)
+        torch.cuda.synchronize()
+    finally:
+        ska.sinkhorn_attn_set_streams(2)
+    assert torch.equal(O2, O0) and torch.equal(dQ2, dQ0) and torch.equal(dK2, dK0) and torch.equal(dV2, dV0)
+
+
 def test_dense_widened_band_dustbin():
     """The paper's own dustbin path: one learned token appended per side and a band wide enough
     to cover everything (W~ = max(W, L)).  That is the plain operator on the augmented tensors;
