@@ -150,9 +150,8 @@ int launch_sweep(SweepArgs a, int N, hipStream_t st)
             return SKA_EHIP;
         raised = true;
     }
-    // (the first half-step starts with one workgroup per problem for the dustbin element)
-    a.lead = (MODE == M_LSE_FIRST && a.dustbin) ? (N + 7) / 8 * 8 : 0;
-    hipLaunchKernelGGL((sweep_kernel<T, D, MODE, FR, DIRECT>), dim3(chunk * 8 + a.lead), dim3(NTHREADS), LDS, st, a);
+    a.lead = 0;
+    hipLaunchKernelGGL((sweep_kernel<T, D, MODE, FR, DIRECT>), dim3(chunk * 8), dim3(NTHREADS), LDS, st, a);
     return hipGetLastError() == hipSuccess ? SKA_OK : SKA_EHIP;
 }
 
@@ -196,15 +195,15 @@ int launch_msweep(SweepArgs a, int N, hipStream_t st)
 }
 
 // Which kernel runs which sweep:
-//   scaling sweeps and band mat-vecs      vsweep_kernel (skewed LDS ring), both storage types
+//   scaling sweeps and band mat-vecs      vsweep_kernel (skewed LDS ring), both storage types; the very
+//                                         first half-step is its running-maximum variant
 //   output map / dV, final sweeps         msweep_kernel for bf16 storage with d <= 64,
 //                                         sweep_kernel otherwise
-//   the very first half-step              sweep_kernel<M_LSE_FIRST> (running maximum)
 template <typename T, int D> int sweep_one(int mode, const SweepArgs &a, int N, hipStream_t st)
 {
     constexpr int FRV = (sizeof(T) == 2) ? 2 : 1;   // vector sweeps: owner rows per wavefront / 32
     switch (mode) {
-    case M_LSE_FIRST: return launch_sweep<T, D, M_LSE_FIRST, FRV>(a, N, st);
+    case M_LSE_FIRST:
     case M_LSE:
     case M_MATVEC: {
         // 64 rows per wavefront reuse every tile fragment twice, but a launch then has N L / 256
@@ -213,9 +212,13 @@ template <typename T, int D> int sweep_one(int mode, const SweepArgs &a, int N, 
         constexpr long SMALL_ROWS = 3L * 256 * 256;
         if constexpr (sizeof(T) == 2) {
             if ((long)N * a.L <= SMALL_ROWS)
-                return mode == M_LSE ? launch_vsweep<T, D, M_LSE, 1>(a, N, st) : launch_vsweep<T, D, M_MATVEC, 1>(a, N, st);
+                return mode == M_LSE         ? launch_vsweep<T, D, M_LSE, 1>(a, N, st)
+                       : mode == M_MATVEC    ? launch_vsweep<T, D, M_MATVEC, 1>(a, N, st)
+                                             : launch_vsweep<T, D, M_LSE_FIRST, 1>(a, N, st);
         }
-        return mode == M_LSE ? launch_vsweep<T, D, M_LSE, FRV>(a, N, st) : launch_vsweep<T, D, M_MATVEC, FRV>(a, N, st);
+        return mode == M_LSE      ? launch_vsweep<T, D, M_LSE, FRV>(a, N, st)
+               : mode == M_MATVEC ? launch_vsweep<T, D, M_MATVEC, FRV>(a, N, st)
+                                  : launch_vsweep<T, D, M_LSE_FIRST, FRV>(a, N, st);
     }
     case M_APPLY:
         if constexpr (sizeof(T) == 2 && D <= 64) return launch_msweep<D, M_APPLY, 2>(a, N, st);

@@ -1,14 +1,13 @@
-// The generic sweep kernel (double-buffered LDS tiles): first half-step, fp32 storage, d = 128, deep tails,
-// and the direct plan-by-plan comparator.
+// The generic sweep kernel (double-buffered LDS tiles): matrix sweeps in fp32 storage and at d = 128, deep
+// tails, and the direct plan-by-plan comparator.
 #pragma once
 #include "ska_common.h"
 
 namespace {
 
 // ------------------------------------------------------------------ the generic sweep kernel
-// Double-buffered LDS staging, one other-side tile per barrier.  It serves the first row
-// half-step (running-maximum LSE, no potentials yet), every fp32-storage matrix sweep
-// and the bf16 matrix sweeps at d = 128; the ring kernels below take the rest.
+// Double-buffered LDS staging, one other-side tile per barrier.  It serves every fp32-storage
+// matrix sweep and the bf16 matrix sweeps at d = 128; the ring kernels take the rest.
 template <typename T, int D, int MODE> struct Stage {
     using TL = Tile<T, D>;
     static constexpr bool HAS_B = (MODE == M_FINAL);
@@ -31,7 +30,7 @@ __global__ __launch_bounds__(NTHREADS) void sweep_kernel(const SweepArgs a)
     using TL = Tile<T, D>;
     using ST = Stage<T, D, MODE>;
     constexpr int BM = NWAVES * FR * 32;
-    constexpr bool MAT_OUT = (MODE == M_APPLY || MODE == M_FINAL);
+    static_assert(MODE == M_APPLY || MODE == M_FINAL, "matrix sweeps only");
 
     extern __shared__ __align__(16) unsigned char smem[];   // two stages of ST::BYTES
     __shared__ float red[NWAVES];
@@ -40,15 +39,7 @@ __global__ __launch_bounds__(NTHREADS) void sweep_kernel(const SweepArgs a)
     // give each XCD one contiguous eighth of the (problem, block) sequence; neighbours
     // that share band rows then meet in the same L2.
     const int chunk = (a.nb_total + 7) >> 3;
-    // a.lead workgroups come first (a multiple of 8, so the XCD of a sweep block is unchanged): one
-    // per problem for the dustbin element, started first so that it ends under the sweep
-    if constexpr (MODE == M_LSE_FIRST) {
-        if ((int)blockIdx.x < a.lead) {
-            if ((int)blockIdx.x < a.nb_total / a.nbp) dustbin_element(a, blockIdx.x, false);
-            return;
-        }
-    }
-    const int bx = (MODE == M_LSE_FIRST) ? (int)blockIdx.x - a.lead : (int)blockIdx.x;
+    const int bx = (int)blockIdx.x;
     const int lb = (bx & 7) * chunk + (a.rev ? chunk - 1 - (bx >> 3) : (bx >> 3));
     if (lb >= a.nb_total) return;
     const int n = lb / a.nbp;
@@ -60,7 +51,7 @@ __global__ __launch_bounds__(NTHREADS) void sweep_kernel(const SweepArgs a)
     const Lens ln = problem_lens(a, n);
     const int Lt = ln.Lt, Le = ln.Le;
     if (o_blk >= Le) {
-        zero_block<T, D, BM>(a, n, o_blk, MAT_OUT, !MAT_OUT);
+        zero_block<T, D, BM>(a, n, o_blk, true, false);
         return;
     }
     const long moff = (long)n * L * D;
@@ -69,12 +60,12 @@ __global__ __launch_bounds__(NTHREADS) void sweep_kernel(const SweepArgs a)
     const float *ytp = a.yt.p + n * a.yt.stride;
     // owner-side potential: stabiliser and factor of the plan; -inf marks an inactive token (a
     // masked one, or one without any active partner), which stays inactive in every later
-    // iterate.  The first half-step has no previous iterate: there xs only carries the marks.
-    const float *xsp = a.xs.p ? a.xs.p + n * a.xs.stride : nullptr;
+    // iterate.
+    const float *xsp = a.xs.p + n * a.xs.stride;
 
     // workgroup stabiliser: largest owner-side potential in this block
     float mblk = 0.f;
-    if constexpr (MODE != M_LSE_FIRST) {
+    {
         float m = -INFINITY;
         for (int i = tid; i < BM; i += NTHREADS)
             if (o_blk + i < Le) m = fmaxf(m, xsp[o_blk + i]);
@@ -106,18 +97,13 @@ __global__ __launch_bounds__(NTHREADS) void sweep_kernel(const SweepArgs a)
     }
 
     // accumulators
-    float sum[FR], mx[FR];
-    f32x16 outm[MAT_OUT ? FR : 1][D / 32];
+    f32x16 outm[FR][D / 32];
 #pragma unroll
-    for (int f = 0; f < FR; ++f) {
-        sum[f] = 0.f;
-        mx[f] = -INFINITY;
-        if constexpr (MAT_OUT)
+    for (int f = 0; f < FR; ++f)
 #pragma unroll
-            for (int j = 0; j < D / 32; ++j)
+        for (int j = 0; j < D / 32; ++j)
 #pragma unroll
-                for (int r = 0; r < 16; ++r) outm[f][j][r] = 0.f;
-    }
+            for (int r = 0; r < 16; ++r) outm[f][j][r] = 0.f;
 
     // other-side tile range of the whole block (tiles aligned to multiples of 32)
     int lo = o_blk - W;            // the host clamps W to L, so none of this overflows
@@ -202,18 +188,7 @@ __global__ __launch_bounds__(NTHREADS) void sweep_kernel(const SweepArgs a)
                 }
             }
 
-            if constexpr (MODE == M_LSE_FIRST) {
-                float tm = e[0];
-#pragma unroll
-                for (int r = 1; r < 16; ++r) tm = fmaxf(tm, e[r]);
-                const float mn = fmaxf(mx[f], tm);
-                const float ms = (mn == -INFINITY) ? 0.f : mn;
-                float sacc = sum[f] * fast_exp2(mx[f] - ms);
-#pragma unroll
-                for (int r = 0; r < 16; ++r) sacc += fast_exp2(e[r] - ms);
-                sum[f] = sacc;
-                mx[f] = mn;
-            } else {
+            {
                 float el[DIRECT ? 16 : 1];
                 if constexpr (DIRECT)
 #pragma unroll
@@ -268,30 +243,7 @@ __global__ __launch_bounds__(NTHREADS) void sweep_kernel(const SweepArgs a)
 #pragma unroll
     for (int f = 0; f < FR; ++f) {
         const int o = o_frag[f] + c;
-        if constexpr (MODE == M_LSE_FIRST) {
-            float mo = __shfl_xor(mx[f], 32), so = __shfl_xor(sum[f], 32);
-            float mn = fmaxf(mx[f], mo);
-            float tot = sum[f] * fast_exp2(mx[f] - mn) + so * fast_exp2(mo - mn);
-            if (a.dustbin) {   // spoke edge (o, dustbin): score sdb, other-side potential yt[L]
-                const float sp2 = a.spoke_own.p ? a.spoke_own.p[n * a.spoke_own.stride + min(o, L - 1)] * LOG2E : a.sdb2;
-                float xd = sp2 + ytp[L] * LOG2E;
-                float m3 = fmaxf(mn, xd);
-                tot = tot * fast_exp2(mn - m3) + fast_exp2(xd - m3);
-                mn = m3;
-            }
-            if (h == 0 && o < L) {
-                float r = 0.f;   // rows beyond the valid length
-                if (o < Le) {
-                    if ((xsp && xsp[o] == -INFINITY) || !(mn > -INFINITY)) {
-                        r = -INFINITY;   // inactive token
-                    } else {
-                        r = -LN2 * (mn + fast_log2(tot));
-                        if (a.olog.p) r += a.olog.p[n * a.olog.stride + o];
-                    }
-                }
-                a.out_vec.p[n * a.out_vec.stride + o] = r;
-            }
-        } else {
+        {
             float fac = 0.f;
             bool dead = true;   // beyond the valid length, or an inactive token: zeros
             if (o < Le) {

@@ -6,7 +6,7 @@
 namespace {
 
 // ------------------------------------------------------------------ vector sweeps
-// Scaling sweep (M_LSE) and band mat-vec (M_MATVEC): the result is one scalar per
+// Scaling sweep (M_LSE, M_LSE_FIRST) and band mat-vec (M_MATVEC): the result is one scalar per
 // owner index, so the only state a wavefront carries is FR owner fragments and FR
 // partial sums.  Wavefront w owns rows [o_blk + 32 FR w, +32 FR) and needs other-side
 // tiles kbase + FR w ... kend + FR w: the same count S for every wavefront, shifted by
@@ -34,7 +34,11 @@ __global__ __launch_bounds__(NTHREADS) void vsweep_kernel(const SweepArgs a)
     using RG = VRing<T, D, MODE, FR>;
     constexpr bool PRE = (sizeof(T) == 2);   // bf16 storage: the score operand is prescaled, c2 == 1
     constexpr int BM = NWAVES * FR * 32;
-    static_assert(MODE == M_LSE || MODE == M_MATVEC, "vector sweeps only");
+    static_assert(MODE == M_LSE || MODE == M_MATVEC || MODE == M_LSE_FIRST, "vector sweeps only");
+    // The very first half-step has no previous iterate to take a stabiliser from: it keeps a
+    // running maximum per lane and fragment instead (exact for any scores), and the owner-side
+    // vector xs, when given, only carries the marks of inactive tokens.
+    constexpr bool FIRST = (MODE == M_LSE_FIRST);
 
     extern __shared__ __align__(16) unsigned char smem[];
     __shared__ float red[NWAVES];
@@ -66,22 +70,23 @@ __global__ __launch_bounds__(NTHREADS) void vsweep_kernel(const SweepArgs a)
     const T *Xb = reinterpret_cast<const T *>(a.X) + moff;
     const T *Yb = reinterpret_cast<const T *>(a.Y) + moff;
     const float *ytp = a.yt.p + n * a.yt.stride;
-    const float *xsp = a.xs.p + n * a.xs.stride;
+    const float *xsp = (FIRST && !a.xs.p) ? nullptr : a.xs.p + n * a.xs.stride;
     const float *wp = (MODE == M_MATVEC) ? a.w.p + n * a.w.stride : nullptr;
 
 
     // stabiliser input first, so that waiting for it waits for nothing else
     static_assert(BM <= NTHREADS, "one owner-side potential per thread");
-    float mraw = xsp[min(o_blk + min(tid, BM - 1), Le - 1)];   // clamped repeats are harmless
-    float mblk, m2 = 0.f;
+    float mraw = FIRST ? 0.f : xsp[min(o_blk + min(tid, BM - 1), Le - 1)];   // clamped repeats are harmless
+    float mblk = 0.f, m2 = 0.f;
     OwnerFrag<T, D> xf[FR];
     int o_frag[FR];
-    float sum[FR];
+    float sum[FR], mx[FR];
 #pragma unroll
     for (int f = 0; f < FR; ++f) {
         o_frag[f] = o_blk + (wave * FR + f) * 32;
         xf[f].load(Xb, min(o_frag[f] + c, Le - 1), Le, h);   // clamped: rows beyond Le are written as zeros
         sum[f] = 0.f;
+        mx[f] = -INFINITY;
     }
 
     // floor((o_blk - W) / 32) and floor((o_blk + 32 FR - 1 + W) / 32); W <= L so no overflow
@@ -150,7 +155,7 @@ __global__ __launch_bounds__(NTHREADS) void vsweep_kernel(const SweepArgs a)
     Inflight fill[RG::LEAD + 1];
 #pragma unroll
     for (int j = 0; j <= RG::LEAD; ++j) g_load(fill[j], kbase + j);
-    {
+    if constexpr (!FIRST) {
         float m = mraw;
 #pragma unroll
         for (int s = 32; s >= 1; s >>= 1) m = fmaxf(m, __shfl_xor(m, s));
@@ -229,11 +234,24 @@ __global__ __launch_bounds__(NTHREADS) void vsweep_kernel(const SweepArgs a)
                             if (hi < 8 * (r >> 2) + (r & 3)) e[r] = -INFINITY;
                     }
                 }
+                if constexpr (FIRST) {
+                    float tm = e[0];
 #pragma unroll
-                for (int r = 0; r < 16; ++r) {
-                    const float p = fast_exp2(e[r]);
-                    if constexpr (MODE == M_MATVEC) sum[f] = fmaf(p, wv[r], sum[f]);
-                    else sum[f] += p;
+                    for (int r = 1; r < 16; ++r) tm = fmaxf(tm, e[r]);
+                    const float mn = fmaxf(mx[f], tm);
+                    const float ms = (mn == -INFINITY) ? 0.f : mn;
+                    float sacc = sum[f] * fast_exp2(mx[f] - ms);
+#pragma unroll
+                    for (int r = 0; r < 16; ++r) sacc += fast_exp2(e[r] - ms);
+                    sum[f] = sacc;
+                    mx[f] = mn;
+                } else {
+#pragma unroll
+                    for (int r = 0; r < 16; ++r) {
+                        const float p = fast_exp2(e[r]);
+                        if constexpr (MODE == M_MATVEC) sum[f] = fmaf(p, wv[r], sum[f]);
+                        else sum[f] += p;
+                    }
                 }
             }
         }
@@ -244,6 +262,32 @@ __global__ __launch_bounds__(NTHREADS) void vsweep_kernel(const SweepArgs a)
 #pragma unroll
     for (int f = 0; f < FR; ++f) {
         const int o = o_frag[f] + c;
+        if constexpr (FIRST) {
+            // the two lanes of a row merge their (maximum, sum) pairs; then the spoke edge
+            const float mo = __shfl_xor(mx[f], 32), so = __shfl_xor(sum[f], 32);
+            float mn = fmaxf(mx[f], mo);
+            float tot = sum[f] * fast_exp2(mx[f] - mn) + so * fast_exp2(mo - mn);
+            if (a.dustbin) {   // spoke edge (o, dustbin): its score, other-side potential yt[L]
+                const float sp2 = a.spoke_own.p ? a.spoke_own.p[n * a.spoke_own.stride + min(o, L - 1)] * LOG2E : a.sdb2;
+                const float xd = sp2 + ytp[L] * LOG2E;
+                const float m3 = fmaxf(mn, xd);
+                tot = tot * fast_exp2(mn - m3) + fast_exp2(xd - m3);
+                mn = m3;
+            }
+            if (h == 0 && o < L) {
+                float r = 0.f;   // rows beyond the valid length
+                if (o < Le) {
+                    if ((xsp && xsp[o] == -INFINITY) || !(mn > -INFINITY)) {
+                        r = -INFINITY;   // inactive token, or one without an active partner
+                    } else {
+                        r = -LN2 * (mn + fast_log2(tot));
+                        if (a.olog.p) r += a.olog.p[n * a.olog.stride + o];
+                    }
+                }
+                a.out_vec.p[n * a.out_vec.stride + o] = r;
+            }
+            continue;
+        }
         float tot = sum[f] + __shfl_xor(sum[f], 32);
         if (a.dustbin) {   // spoke edge (o, dustbin element of the other side)
             const float sp2 = a.spoke_own.p ? a.spoke_own.p[n * a.spoke_own.stride + min(o, L - 1)] * LOG2E : a.sdb2;

@@ -764,6 +764,46 @@ def test_tail_depth_dustbin():
     check(small("taildb", 300, 32, 24, 4, "f32", eps=0.9, R=1, dustbin=True, dustbin_score=0.4), seed=18)
 
 
+@pytest.mark.parametrize("d,W,L", [(32, 300, 900), (64, 250, 800)])
+def test_first_half_step_wide_dynamic_range(d, W, L):
+    """Scores that rise by about 0.2 nats per column: inside one row's band they span about
+    100 nats, more than one fixed stabiliser covers in fp32, so the very first half-step (no
+    previous iterate to take one from) has to follow the running maximum while it sweeps the
+    band.  fp32 storage (bf16 scores of this size carry an absolute error of a third of a nat
+    from the rounding of the scaled operand alone).  Potentials and all four results against
+    the oracle at the usual fp32 tolerance."""
+    import torch
+
+    import paper_2605_08123_amd as ska
+    w = small("ramp", L, d, W, 3, "f32", eps=1.0, B=1, H=2, R=2)
+    print(f"\n[case] {w} score ramp", flush=True)
+    q, k, v, g = make_inputs(w, 77)
+    c = 1.0 / (w.eps * np.sqrt(d))
+    q[..., 0] = 1.0
+    k[..., 0] = (0.2 / c) * np.arange(L, dtype=np.float32)
+    q[..., 1:] *= 0.5
+    dev = torch.device("cuda:0")
+    Q, K, V, G = (torch.from_numpy(x).to(dev) for x in (q, k, v, g))
+    O, UV = ska.sinkhorn_attn_fwd(Q, K, V, w.W, w.T, w.R, w.eps)
+    dQ, dK, dV = ska.sinkhorn_attn_bwd(Q, K, V, O, G, UV, w.W, w.T, w.R, w.eps)[:3]
+    torch.cuda.synchronize()
+    got = {n: x.cpu().numpy().astype(np.float64) for n, x in dict(O=O, dQ=dQ, dK=dK, dV=dV, UV=UV).items()}
+    ref = oracle.band_batched(q, k, v, g, w.W, w.T, w.R, w.eps)
+    band_rise = 0.2 * (2 * W)
+    assert band_rise > 88.0                           # exp() of the spread overflows fp32
+    assert np.abs(ref["UV"][:, :, 0]).max() > 100.0   # potentials of that size
+    for n in got:
+        assert np.isfinite(got[n]).all(), n
+    errs = {n: rel(got[n], ref[n]) for n in ("O", "dQ", "dK", "dV")}
+    print("   rel-L2:", {n: f"{e:.2e}" for n, e in errs.items()}, flush=True)
+    for t in range(w.R + 1):
+        s_got = got["UV"][:, :, 2 * t] + got["UV"][:, :, 2 * t + 1]
+        s_ref = ref["UV"][:, :, 2 * t] + ref["UV"][:, :, 2 * t + 1]
+        assert np.abs(s_got - s_ref).max() < 1e-3, (t, np.abs(s_got - s_ref).max())
+    for n, e in errs.items():
+        assert e <= TOL["f32"], (n, e)
+
+
 def test_eta0_general_tail():
     w = small("eta", 300, 32, 20, 4, "f32", R=3)
     got = run_gpu(w, make_inputs(w, 6), want_eta0=True)
