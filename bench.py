@@ -26,11 +26,13 @@ sys.path.insert(0, ROOT)
 HBM_PEAK_GBS = 8000.0          # MI355X HBM3E, published
 MFMA_PEAK_TFLOPS = {"bf16": 2500.0, "f32": 157.3}   # dense matrix peak of the storage type's MFMA
 # Plain-ALU ceiling of the scaling sweep: per band edge one exp2 and one add, nothing packed,
-# nothing fused.  256 CUs x 4 SIMDs x 16 lanes x 2.4 GHz = 39.3 T lane-issue-slots/s; an add
-# takes one slot, v_exp_f32 two (it issues at half rate: 8 cycles per 64-wide wavefront,
-# measured), so the pair runs at 2 flop per 3 slots = 26.2 TFLOP/s at best.
-ALU_SLOTS_PER_S = 256 * 4 * 16 * 2.4e9
-ALU_PEAK_TFLOPS = ALU_SLOTS_PER_S * 2.0 / 3.0 / 1e12
+# nothing fused.  256 CUs x 4 SIMDs x 32 lanes x 2.4 GHz = 78.6 T lane-issue-slots/s (the
+# published 157.3 TFLOP/s fp32 vector peak is this times two for an FMA); an add takes one slot,
+# v_exp_f32 four (quarter rate: 8 cycles per 64-wide wavefront against 2 for an add, both
+# measured with two or more wavefronts on a SIMD), so the pair runs at 2 flop per 5 slots =
+# 31.5 TFLOP/s at best.
+ALU_SLOTS_PER_S = 256 * 4 * 32 * 2.4e9
+ALU_PEAK_TFLOPS = ALU_SLOTS_PER_S * 2.0 / 5.0 / 1e12
 
 
 def edges(w) -> float:
@@ -218,7 +220,7 @@ def main() -> int:
         "roofline": {"kernel": "scaling sweep (row/column half-step, Eq. 1-2)", "bound": "alu",
                      "achieved": alu_tflops, "peak": ALU_PEAK_TFLOPS, "unit": "TFLOP/s",
                      "frac": alu_tflops / ALU_PEAK_TFLOPS, "traffic": traffic,
-                     "flops": "one exp2 + one add per band edge; v_exp_f32 issues at half rate",
+                     "flops": "one exp2 + one add per band edge; v_exp_f32 issues at quarter rate",
                      "launches_timed": launches, "avg_launch_us": 1e6 * avg_s,
                      "hbm": {"achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
                              "frac": achieved / HBM_PEAK_GBS,
