@@ -1062,10 +1062,10 @@ int sinkhorn_attn_select_tail_depth(const void *Q, const void *K, const void *V,
     return SKA_OK;
 }
 
-int sinkhorn_attn_probe_issue(float *scratch, size_t scratch_bytes, int tiles, int waves_per_simd, double *ms3,
+int sinkhorn_attn_probe_issue(float *scratch, size_t scratch_bytes, int tiles, int waves_per_simd, double *ms6,
                               void *stream)
 {
-    if (!scratch || !ms3 || tiles < 1 || tiles > (1 << 20) || waves_per_simd < 1 || waves_per_simd > 8) return SKA_EINVAL;
+    if (!scratch || !ms6 || tiles < 1 || tiles > (1 << 20) || waves_per_simd < 1 || waves_per_simd > 8) return SKA_EINVAL;
     int dev = 0, cus = 0;
     if (hipGetDevice(&dev) != hipSuccess || hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess)
         return SKA_EHIP;
@@ -1076,18 +1076,21 @@ int sinkhorn_attn_probe_issue(float *scratch, size_t scratch_bytes, int tiles, i
     if (hipEventCreate(&e0) != hipSuccess) return SKA_EHIP;
     if (hipEventCreate(&e1) != hipSuccess) { (void)hipEventDestroy(e0); return SKA_EHIP; }
     int rc = SKA_OK;
-    for (int what = 0; what < 3 && rc == SKA_OK; ++what) {
+    for (int what = 0; what < 6 && rc == SKA_OK; ++what) {
         for (int rep = 0; rep < 2; ++rep) {   // the second launch is the timed one
             if (rep == 1) (void)hipEventRecord(e0, st);
             if (what == 0) hipLaunchKernelGGL(issue_probe_kernel<0>, dim3(nblk), dim3(256), 0, st, scratch, tiles);
             if (what == 1) hipLaunchKernelGGL(issue_probe_kernel<1>, dim3(nblk), dim3(256), 0, st, scratch, tiles);
             if (what == 2) hipLaunchKernelGGL(issue_probe_kernel<2>, dim3(nblk), dim3(256), 0, st, scratch, tiles);
+            if (what == 3) hipLaunchKernelGGL(issue_probe_kernel<3>, dim3(nblk), dim3(256), 0, st, scratch, tiles);
+            if (what == 4) hipLaunchKernelGGL(issue_probe_kernel<4>, dim3(nblk), dim3(256), 0, st, scratch, tiles);
+            if (what == 5) hipLaunchKernelGGL(issue_probe_kernel<5>, dim3(nblk), dim3(256), 0, st, scratch, tiles);
         }
         float ms = 0.f;
         if (hipEventRecord(e1, st) != hipSuccess || hipEventSynchronize(e1) != hipSuccess ||
             hipEventElapsedTime(&ms, e0, e1) != hipSuccess || hipGetLastError() != hipSuccess)
             rc = SKA_EHIP;
-        ms3[what] = ms;
+        ms6[what] = ms;
     }
     (void)hipEventDestroy(e0);
     (void)hipEventDestroy(e1);

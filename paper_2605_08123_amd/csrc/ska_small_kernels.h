@@ -42,12 +42,16 @@ __global__ void rowdot_kernel(const T *A, const T *Bm, float *g, long gstride, i
 }
 
 // ---- issue-rate probe (benchmark hook): what one SIMD sustains of the scaling sweep's instruction
-// mix, with no memory traffic.  WHAT 0: 16 exp2 + 16 adds per "tile"; 1: four dependent
-// 32x32x16 bf16 MFMAs per tile; 2: both, the exponentials consuming the MFMA result (the sweep's
-// pattern; other wavefronts of the SIMD are free to fill the gaps).  One float per thread is written.
+// mix, with no memory traffic.  Per loop iteration ("tile") a wavefront runs, depending on WHAT,
+// four dependent 32x32x16 bf16 MFMAs (M), 16 exp2 (E) and 16 adds (A), the VALU work consuming the
+// MFMA result as in the sweep (other wavefronts of the SIMD are free to fill the gaps):
+//   0: E + A   1: M   2: M + E + A (the sweep's pattern)   3: M + A   4: M + E   5: A
+// Without adds the 16 values are folded by eight max3 instead.  One float per thread is written.
 template <int WHAT>
 __global__ __launch_bounds__(256) void issue_probe_kernel(float *out, int tiles)
 {
+    constexpr bool M = (WHAT >= 1 && WHAT <= 4), E = (WHAT == 0 || WHAT == 2 || WHAT == 4);
+    constexpr bool A = (WHAT == 0 || WHAT == 2 || WHAT == 3 || WHAT == 5);
     bf16x8 a, b;
 #pragma unroll
     for (int i = 0; i < 8; ++i) { a[i] = (__bf16)(threadIdx.x * 0.01f); b[i] = (__bf16)(i * 0.1f); }
@@ -55,20 +59,38 @@ __global__ __launch_bounds__(256) void issue_probe_kernel(float *out, int tiles)
 #pragma unroll
     for (int i = 0; i < 16; ++i) { c0[i] = -30.f - 0.01f * i; c[i] = -1.f - 0.01f * i; }
     float sum = 0.f;
+    const float step = 1e-3f * (float)(threadIdx.x & 7);
     for (int it = 0; it < tiles; ++it) {
-        if (WHAT >= 1) {   // the first MFMA starts from a loop-invariant accumulator, as the sweep's does
+        if constexpr (M) {   // the first MFMA starts from a loop-invariant accumulator, as the sweep's does
             c = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, b, c0, 0, 0, 0);
 #pragma unroll
             for (int k = 1; k < 4; ++k) c = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, b, c, 0, 0, 0);
         }
-        if (WHAT == 0) {   // iterated exp2 keeps every exponential dependent on the previous tile
+        if constexpr (!M) {   // no MFMA: iterate on the values themselves so that every tile depends on the last
+            if constexpr (E) {
 #pragma unroll
-            for (int r = 0; r < 16; ++r) { c[r] = fast_exp2(c[r]); sum += c[r]; }
-        } else if (WHAT == 2) {
+                for (int r = 0; r < 16; ++r) { c[r] = fast_exp2(c[r]); sum += c[r]; }
+            } else {
 #pragma unroll
-            for (int r = 0; r < 16; ++r) sum += fast_exp2(c[r]);
+                for (int r = 0; r < 16; ++r) c[r] += step;
+            }
+        } else {
+            float e[16];
+#pragma unroll
+            for (int r = 0; r < 16; ++r) e[r] = E ? fast_exp2(c[r]) : c[r];
+            if constexpr (A) {
+#pragma unroll
+                for (int r = 0; r < 16; ++r) sum += e[r];
+            } else if constexpr (E) {
+                float m = e[0];
+#pragma unroll
+                for (int r = 1; r < 16; ++r) m = fmaxf(m, e[r]);
+                sum += m;
+            } else {
+                sum = e[0];
+            }
+            a[0] = (__bf16)sum;   // the next tile depends on this one
         }
-        if (WHAT >= 1) a[0] = (__bf16)(WHAT == 1 ? c[0] : sum);   // the next tile depends on this one
     }
     float s = sum;
 #pragma unroll
