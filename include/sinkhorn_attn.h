@@ -28,9 +28,11 @@
  *     stream that the library creates once per device (non-blocking, default priority, never
  *     destroyed): it is forked from `stream` by an event after the call's first kernels and
  *     joined to it again before the call returns, so everything the call does is ordered on
- *     `stream` as seen by the caller, also under stream capture.  sinkhorn_attn_set_streams(1)
- *     keeps all work on `stream` itself.  Calls from several host threads at once are not
- *     supported.
+ *     `stream` as seen by the caller, also under stream capture, and also when a launch fails
+ *     half-way through a call.  sinkhorn_attn_set_streams(1) keeps all work on `stream` itself.
+ *   - Entry points may be called from several host threads at once (each on a stream of its
+ *     own): a call holds a process-wide lock while it enqueues its kernels, so calls are
+ *     serialised at the enqueue while their GPU work overlaps as the streams allow.
  *   - Tensors Q, K, V, O, dO, dQ, dK, dV are [B, H, L, d], contiguous, row-major,
  *     of the element type `dtype` (SKA_F32: float; SKA_BF16: bfloat16).  All
  *     scaling vectors and all accumulation are fp32.
@@ -309,7 +311,9 @@ int sinkhorn_attn_bwd_variant(int variant, const void *Q, const void *K, const v
  * Benchmark hooks (no part of the operator).  While enabled, every forward and backward
  * call records two HIP events on its stream around each of its phases, so that a phase can
  * be timed in place, inside a larger timed region, without a profiler.  At most 4096 phase
- * spans are remembered between reads (further ones are dropped).  Not thread-safe.
+ * spans are remembered between reads (further ones are dropped).  Level 1 leaves the schedule of
+ * a call as it is (a span on two streams ends with an event on each, the later one counts);
+ * level 2 joins the helper stream at the end of every phase so that phases do not overlap.
  *   sinkhorn_attn_profile_enable(level): 0 off, 1 only the SKA_PH_SCALING span of every
  *     forward call (two events per call), 2 every phase; returns SKA_OK.
  *   sinkhorn_attn_profile_read_phases(ms, launches): host arrays of SKA_PH_COUNT entries;

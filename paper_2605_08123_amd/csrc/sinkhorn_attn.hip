@@ -17,9 +17,10 @@
 //   FINAL        out_o = c exp(x_o) sum_t exp(S_ot + y_t) [<A_o, B_t> - sum_k p_k,o q_k,t] Y_t
 //                                                 (Prop. 2: one reference tile + modifiers)
 //
-// Three kernels serve the sweeps: vsweep_kernel (LSE, MATVEC: a skewed ring of tiles in LDS),
-// msweep_kernel (APPLY, FINAL for bf16 storage and d <= 64: the same ring, two products) and
-// sweep_kernel (the first half-step, fp32 storage and d = 128: double-buffered tiles).
+// Three kernels serve the sweeps: vsweep_kernel (every half-step, the first one in its
+// running-maximum form, and the band mat-vecs: a skewed ring of tiles in LDS), msweep_kernel
+// (APPLY, FINAL for bf16 storage and d <= 64: the same ring, two products) and sweep_kernel
+// (APPLY, FINAL for fp32 storage and d = 128, deep tails: double-buffered tiles).
 //
 // MFMA tile layout (32x32 accumulators): lane l holds owner o = l & 31; register r
 // holds other index t = 8*(r>>2) + 4*(l>>5) + (r&3).  Sums over t are therefore
@@ -29,6 +30,7 @@
 #include <stdint.h>
 #include <stdlib.h>
 
+#include <mutex>
 #include <new>
 #include <type_traits>
 
@@ -41,6 +43,8 @@
 namespace {
 
 // ------------------------------------------------------------------ host side
+constexpr int MAX_DEVICES = 16;   // per-device state of the library (helper stream, raised LDS limits)
+
 struct Problem {
     int B, H, L, d, W, T, R, dustbin, dtype;
     float eps, sdb;
@@ -136,19 +140,19 @@ int check_common(const Problem &p)
 }
 
 template <typename T, int D, int MODE, int FR, bool DIRECT = false>
-int launch_sweep(SweepArgs a, int N, hipStream_t st)
+int launch_sweep(SweepArgs a, int N, hipStream_t st, int dev)
 {
     constexpr int BM = NWAVES * FR * 32;
     a.nbp = (a.L + BM - 1) / BM;
     a.nb_total = a.nbp * N;
     const int chunk = (a.nb_total + 7) / 8;
     constexpr int LDS = 2 * Stage<T, D, MODE>::BYTES;
-    static bool raised = false;    // static LDS tops out at 64 KB; the CU has 160 KB
-    if (LDS > 48 * 1024 && !raised) {
+    static bool raised[MAX_DEVICES];    // static LDS tops out at 64 KB; the CU has 160 KB (an attribute per device)
+    if (LDS > 48 * 1024 && !raised[dev]) {
         if (hipFuncSetAttribute(reinterpret_cast<const void *>(&sweep_kernel<T, D, MODE, FR, DIRECT>),
                                 hipFuncAttributeMaxDynamicSharedMemorySize, LDS) != hipSuccess)
             return SKA_EHIP;
-        raised = true;
+        raised[dev] = true;
     }
     a.lead = 0;
     hipLaunchKernelGGL((sweep_kernel<T, D, MODE, FR, DIRECT>), dim3(chunk * 8), dim3(NTHREADS), LDS, st, a);
@@ -156,19 +160,19 @@ int launch_sweep(SweepArgs a, int N, hipStream_t st)
 }
 
 template <typename T, int D, int MODE, int FR>
-int launch_vsweep(SweepArgs a, int N, hipStream_t st)
+int launch_vsweep(SweepArgs a, int N, hipStream_t st, int dev)
 {
     constexpr int BM = NWAVES * FR * 32;
     a.nbp = (a.L + BM - 1) / BM;
     a.nb_total = a.nbp * N;
     const int chunk = (a.nb_total + 7) / 8;
     constexpr int LDS = VRing<T, D, MODE, FR>::BYTES;
-    static bool raised = false;
-    if (LDS > 48 * 1024 && !raised) {
+    static bool raised[MAX_DEVICES];
+    if (LDS > 48 * 1024 && !raised[dev]) {
         if (hipFuncSetAttribute(reinterpret_cast<const void *>(&vsweep_kernel<T, D, MODE, FR>),
                                 hipFuncAttributeMaxDynamicSharedMemorySize, LDS) != hipSuccess)
             return SKA_EHIP;
-        raised = true;
+        raised[dev] = true;
     }
     a.lead = a.dustbin ? (N + 7) / 8 * 8 : 0;   // one workgroup per problem in front: the dustbin element
     hipLaunchKernelGGL((vsweep_kernel<T, D, MODE, FR>), dim3(chunk * 8 + a.lead), dim3(NTHREADS), LDS, st, a);
@@ -176,19 +180,19 @@ int launch_vsweep(SweepArgs a, int N, hipStream_t st)
 }
 
 template <int D, int MODE, int FR>
-int launch_msweep(SweepArgs a, int N, hipStream_t st)
+int launch_msweep(SweepArgs a, int N, hipStream_t st, int dev)
 {
     constexpr int BM = NWAVES * FR * 32;
     a.nbp = (a.L + BM - 1) / BM;
     a.nb_total = a.nbp * N;
     const int chunk = (a.nb_total + 7) / 8;
     constexpr int LDS = MRing<D, MODE, FR>::BYTES;
-    static bool raised = false;
-    if (LDS > 48 * 1024 && !raised) {
+    static bool raised[MAX_DEVICES];
+    if (LDS > 48 * 1024 && !raised[dev]) {
         if (hipFuncSetAttribute(reinterpret_cast<const void *>(&msweep_kernel<D, MODE, FR>),
                                 hipFuncAttributeMaxDynamicSharedMemorySize, LDS) != hipSuccess)
             return SKA_EHIP;
-        raised = true;
+        raised[dev] = true;
     }
     hipLaunchKernelGGL((msweep_kernel<D, MODE, FR>), dim3(chunk * 8), dim3(NTHREADS), LDS, st, a);
     return hipGetLastError() == hipSuccess ? SKA_OK : SKA_EHIP;
@@ -199,7 +203,7 @@ int launch_msweep(SweepArgs a, int N, hipStream_t st)
 //                                         first half-step is its running-maximum variant
 //   output map / dV, final sweeps         msweep_kernel for bf16 storage with d <= 64,
 //                                         sweep_kernel otherwise
-template <typename T, int D> int sweep_one(int mode, const SweepArgs &a, int N, hipStream_t st)
+template <typename T, int D> int sweep_one(int mode, const SweepArgs &a, int N, hipStream_t st, int dev)
 {
     constexpr int FRV = (sizeof(T) == 2) ? 2 : 1;   // vector sweeps: owner rows per wavefront / 32
     switch (mode) {
@@ -212,23 +216,23 @@ template <typename T, int D> int sweep_one(int mode, const SweepArgs &a, int N, 
         constexpr long SMALL_ROWS = 3L * 256 * 256;
         if constexpr (sizeof(T) == 2) {
             if ((long)N * a.L <= SMALL_ROWS)
-                return mode == M_LSE         ? launch_vsweep<T, D, M_LSE, 1>(a, N, st)
-                       : mode == M_MATVEC    ? launch_vsweep<T, D, M_MATVEC, 1>(a, N, st)
-                                             : launch_vsweep<T, D, M_LSE_FIRST, 1>(a, N, st);
+                return mode == M_LSE         ? launch_vsweep<T, D, M_LSE, 1>(a, N, st, dev)
+                       : mode == M_MATVEC    ? launch_vsweep<T, D, M_MATVEC, 1>(a, N, st, dev)
+                                             : launch_vsweep<T, D, M_LSE_FIRST, 1>(a, N, st, dev);
         }
-        return mode == M_LSE      ? launch_vsweep<T, D, M_LSE, FRV>(a, N, st)
-               : mode == M_MATVEC ? launch_vsweep<T, D, M_MATVEC, FRV>(a, N, st)
-                                  : launch_vsweep<T, D, M_LSE_FIRST, FRV>(a, N, st);
+        return mode == M_LSE      ? launch_vsweep<T, D, M_LSE, FRV>(a, N, st, dev)
+               : mode == M_MATVEC ? launch_vsweep<T, D, M_MATVEC, FRV>(a, N, st, dev)
+                                  : launch_vsweep<T, D, M_LSE_FIRST, FRV>(a, N, st, dev);
     }
     case M_APPLY:
-        if constexpr (sizeof(T) == 2 && D <= 64) return launch_msweep<D, M_APPLY, 2>(a, N, st);
-        else return launch_sweep<T, D, M_APPLY, 1>(a, N, st);
-    case M_FINAL_DIRECT: return launch_sweep<T, D, M_FINAL, 1, true>(a, N, st);
+        if constexpr (sizeof(T) == 2 && D <= 64) return launch_msweep<D, M_APPLY, 2>(a, N, st, dev);
+        else return launch_sweep<T, D, M_APPLY, 1>(a, N, st, dev);
+    case M_FINAL_DIRECT: return launch_sweep<T, D, M_FINAL, 1, true>(a, N, st, dev);
     default:
         if constexpr (sizeof(T) == 2 && D <= 64) {
-            if (a.poB) return launch_msweep<D, M_FINAL, 1>(a, N, st);   // packs as bf16 columns (R <= 2)
+            if (a.poB) return launch_msweep<D, M_FINAL, 1>(a, N, st, dev);   // packs as bf16 columns (R <= 2)
         }
-        return launch_sweep<T, D, M_FINAL, 1>(a, N, st);
+        return launch_sweep<T, D, M_FINAL, 1>(a, N, st, dev);
     }
 }
 
@@ -251,16 +255,16 @@ struct Side {
     hipEvent_t fork_ev = nullptr, join_ev = nullptr;
     bool tried = false;
 };
-Side g_side[16];
+// State shared by all calls of the process; g_mutex guards all of it.  A call holds the mutex
+// while it enqueues (host work only, the GPU runs on), so calls from several host threads are
+// serialised at the enqueue and each sees consistent helper streams, events and flags.
+std::mutex g_mutex;
+Side g_side[MAX_DEVICES];
 int g_streams = 2;            // sinkhorn_attn_set_streams: 1 = everything on the caller's stream
 double g_split_min_edges = 50e6;   // sinkhorn_attn_set_split_min_edges
-Side *g_cur_side = nullptr;   // set while a call splits its sweeps (one host thread at a time)
-bool g_side_busy = false;     // the helper stream holds work that the caller's stream has not joined
 
-Side *side_for_current_device()
+Side *side_for_device(int dev)   // (g_mutex held)
 {
-    int dev = 0;
-    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= 16) return nullptr;
     Side &sd = g_side[dev];
     if (!sd.tried) {
         sd.tried = true;
@@ -271,42 +275,53 @@ Side *side_for_current_device()
     }
     return sd.s ? &sd : nullptr;
 }
-// the helper stream waits for everything enqueued on st so far
-int side_fork(hipStream_t st)
-{
-    if (!g_cur_side) return SKA_OK;
-    if (hipEventRecord(g_cur_side->fork_ev, st) != hipSuccess ||
-        hipStreamWaitEvent(g_cur_side->s, g_cur_side->fork_ev, 0) != hipSuccess)
-        return SKA_EHIP;
-    return SKA_OK;
-}
-// st waits for everything enqueued on the helper stream so far
-int side_join(hipStream_t st)
-{
-    if (!g_cur_side || !g_side_busy) return SKA_OK;
-    if (hipEventRecord(g_cur_side->join_ev, g_cur_side->s) != hipSuccess ||
-        hipStreamWaitEvent(st, g_cur_side->join_ev, 0) != hipSuccess)
-        return SKA_EHIP;
-    g_side_busy = false;
-    return SKA_OK;
-}
 
-struct SideScope {   // a call that may split its sweeps
-    // Splitting doubles the dispatches of a call, which pays only while a dispatch is long against
-    // the host's cost of enqueueing it: at least 50 M band edges per dispatch (about 10 us).  Below
-    // that (measured: 17 M and 34 M edges per dispatch) two streams are no faster or slower.
-    SideScope(int nproblems, int L, int W)
+// One library call: the stream it enqueues on, the device, and whether its sweeps are split
+// over the helper stream.  Splitting doubles the dispatches of a call, which pays only while a
+// dispatch is long against the host's cost of enqueueing it: at least 50 M band edges per
+// dispatch (about 10 us).  Below that (measured: 17 M and 34 M edges per dispatch) two streams
+// are no faster or slower.  The destructor joins the helper stream, so every way out of a call,
+// a failed launch included, leaves all of its work ordered on the caller's stream (a capture
+// in progress stays a valid graph).
+struct Call {
+    hipStream_t st;
+    int dev = 0;
+    int rc = SKA_OK;
+    Side *side = nullptr;    // the helper stream while this call splits its sweeps
+    bool busy = false;       // the helper stream holds work that st has not joined
+    std::unique_lock<std::mutex> lk;
+    Call(void *stream, int nproblems, int L, int W, bool may_split = true)
+        : st(reinterpret_cast<hipStream_t>(stream)), lk(g_mutex)
     {
+        if (hipGetDevice(&dev) != hipSuccess) { rc = SKA_EHIP; dev = 0; return; }
+        if (dev < 0 || dev >= MAX_DEVICES) { rc = SKA_EUNSUPPORTED; dev = 0; return; }
         const double edges = (double)(nproblems / 2) * L * (2.0 * (W < L ? W : L) + 1.0);
-        g_cur_side = (g_streams >= 2 && nproblems >= 2 && edges >= g_split_min_edges) ? side_for_current_device() : nullptr;
-        g_side_busy = false;
+        if (may_split && g_streams >= 2 && nproblems >= 2 && edges >= g_split_min_edges) side = side_for_device(dev);
     }
-    ~SideScope() { g_cur_side = nullptr; }
+    Call(const Call &) = delete;
+    ~Call() { (void)join(); }
+    // the helper stream waits for everything enqueued on st so far
+    int fork()
+    {
+        if (!side) return SKA_OK;
+        if (hipEventRecord(side->fork_ev, st) != hipSuccess || hipStreamWaitEvent(side->s, side->fork_ev, 0) != hipSuccess)
+            return SKA_EHIP;
+        return SKA_OK;
+    }
+    // st waits for everything enqueued on the helper stream so far
+    int join()
+    {
+        if (!side || !busy) return SKA_OK;
+        busy = false;
+        if (hipEventRecord(side->join_ev, side->s) != hipSuccess || hipStreamWaitEvent(st, side->join_ev, 0) != hipSuccess)
+            return SKA_EHIP;
+        return SKA_OK;
+    }
 };
 
-template <typename T, int D> int sweep(int mode, const SweepArgs &a, int N, hipStream_t st)
+template <typename T, int D> int sweep(Call &cx, int mode, const SweepArgs &a, int N)
 {
-    if (!g_cur_side || N < 2) return sweep_one<T, D>(mode, a, N, st);
+    if (!cx.side || N < 2) return sweep_one<T, D>(mode, a, N, cx.st, cx.dev);
     const int n0 = N / 2;
     SweepArgs b = a;
     const long mb = (long)n0 * a.L * D * (long)sizeof(T);
@@ -324,14 +339,17 @@ template <typename T, int D> int sweep(int mode, const SweepArgs &a, int N, hipS
     if (a.qtA) b.qtA = reinterpret_cast<const unsigned char *>(a.qtA) + (long)n0 * a.ldp * 32;
     if (a.pay_db) b.pay_db = a.pay_db + (long)n0 * D;
     b.n0 = a.n0 + n0;
-    SKA_TRY((sweep_one<T, D>(mode, a, n0, st)));
-    g_side_busy = true;
-    return sweep_one<T, D>(mode, b, N - n0, g_cur_side->s);
+    SKA_TRY((sweep_one<T, D>(mode, a, n0, cx.st, cx.dev)));
+    cx.busy = true;
+    return sweep_one<T, D>(mode, b, N - n0, cx.side->s, cx.dev);
 }
 
-// benchmark hooks: while enabled, every phase of a call is bracketed by two events on the
-// call's stream, so that the phases can be timed in place inside a larger timed region
-struct ProfSpan { hipEvent_t a, b; int phase; long launches; };
+// benchmark hooks: while enabled, every phase of a call is bracketed by events on the call's
+// streams, so that the phases can be timed in place inside a larger timed region.  Level 1 (the
+// run of scaling sweeps only) leaves the schedule as it is: the span ends with one event on each
+// of the two streams and its time is the later of the two.  Level 2 (every phase) joins the
+// helper stream at the end of each phase so that the phases do not overlap.
+struct ProfSpan { hipEvent_t a, b, b2; int phase; long launches; };
 int g_prof_on = 0;   // 0 off, 1 the scaling-sweep run only, 2 every phase
 constexpr int PROF_MAX = 4096;
 ProfSpan g_prof[PROF_MAX];
@@ -339,16 +357,17 @@ int g_prof_n = 0;
 
 struct PhaseTimer {
     ProfSpan *sp = nullptr;
-    hipStream_t st;
-    PhaseTimer(int phase, hipStream_t st_) : st(st_)
+    Call &cx;
+    PhaseTimer(int phase, Call &cx_) : cx(cx_)
     {
         if (g_prof_on < (phase == SKA_PH_SCALING ? 1 : 2) || g_prof_n >= PROF_MAX) return;
         ProfSpan *c = &g_prof[g_prof_n];
+        c->b2 = nullptr;
         if (hipEventCreate(&c->a) != hipSuccess) return;
         if (hipEventCreate(&c->b) != hipSuccess) { (void)hipEventDestroy(c->a); return; }
         c->phase = phase;
         c->launches = 0;
-        (void)hipEventRecord(c->a, st);
+        (void)hipEventRecord(c->a, cx.st);
         sp = c;
         ++g_prof_n;
     }
@@ -356,8 +375,9 @@ struct PhaseTimer {
     void end()
     {
         if (!sp) return;
-        (void)side_join(st);   // the span covers the helper stream's share of the phase as well
-        (void)hipEventRecord(sp->b, st);
+        if (g_prof_on >= 2) (void)cx.join();   // the span covers the helper stream's share of the phase as well
+        else if (cx.side && cx.busy && hipEventCreate(&sp->b2) == hipSuccess) (void)hipEventRecord(sp->b2, cx.side->s);
+        (void)hipEventRecord(sp->b, cx.st);
         sp = nullptr;
     }
     ~PhaseTimer() { end(); }
@@ -365,9 +385,10 @@ struct PhaseTimer {
 
 
 template <typename T, int D>
-int fwd_impl(const Problem &p, const void *Qin, const void *K, const void *V, void *O, float *UV,
-             void *ws, hipStream_t st, bool fused = false)
+int fwd_impl(Call &cx, const Problem &p, const void *Qin, const void *K, const void *V, void *O, float *UV,
+             void *ws, bool fused = false)
 {
+    const hipStream_t st = cx.st;
     // fused: the backward of the same call follows (sinkhorn_attn_step).  The prescaled operand
     // then goes where the backward expects it, and the helper stream is not joined at the end:
     // each half of the problems runs its forward and backward as one uninterrupted chain.
@@ -375,7 +396,7 @@ int fwd_impl(const Problem &p, const void *Qin, const void *K, const void *V, vo
     const void *Q = nullptr;
     float c2 = 0.f;
     {
-        PhaseTimer pt(SKA_PH_PRESCALE, st);
+        PhaseTimer pt(SKA_PH_PRESCALE, cx);
         void *ws_q = fused ? reinterpret_cast<unsigned char *>(ws) + ws_vec_bytes(p) : ws;
         SKA_TRY((make_scores_operand<T>(p, p.n_stages ? p.eps_stage[0] : p.eps, Qin, ws_q, &Q, &c2, st)));
         pt.launched(sizeof(T) == 2 ? 1 : 0);
@@ -409,7 +430,7 @@ int fwd_impl(const Problem &p, const void *Qin, const void *K, const void *V, vo
     // too: after these two every token's activity is settled, and an empty sum later is an error.
     int cold = (p.mask_q || p.mask_k) ? 2 : 1;
     int nlaunch = 0;
-    PhaseTimer pt_first(SKA_PH_FIRST, st);   // the two cold launches are the other (max-tracking) kernel
+    PhaseTimer pt_first(SKA_PH_FIRST, cx);   // the two cold launches are the other (max-tracking) kernel
     PhaseTimer *pt_run = nullptr;
     alignas(PhaseTimer) unsigned char pt_run_mem[sizeof(PhaseTimer)];
     // half-step: out slot <- -LSE over the band of (S + yt); prev slot only stabilises
@@ -433,12 +454,12 @@ int fwd_impl(const Problem &p, const void *Qin, const void *K, const void *V, vo
         // successive sweeps walk the blocks in opposite directions: a sweep then starts on
         // the rows its predecessor touched last, which are still in L2
         a.rev = nlaunch++ & 1;
-        SKA_TRY((sweep<T, D>(cold > 0 ? M_LSE_FIRST : M_LSE, a, N, st)));
+        SKA_TRY((sweep<T, D>(cx, cold > 0 ? M_LSE_FIRST : M_LSE, a, N)));
         if (cold > 0) pt_first.launched();
         else pt_run->launched();
         if (cold > 0 && --cold == 0) {   // the run of identical scaling sweeps starts after the cold launches
             pt_first.end();
-            pt_run = new (pt_run_mem) PhaseTimer(SKA_PH_SCALING, st);
+            pt_run = new (pt_run_mem) PhaseTimer(SKA_PH_SCALING, cx);
         }
         return SKA_OK;
     };
@@ -451,13 +472,13 @@ int fwd_impl(const Problem &p, const void *Qin, const void *K, const void *V, vo
             const float es = p.n_stages ? p.eps_stage[sidx] : p.eps;
             const int Ts = p.n_stages ? p.T_stage[sidx] : p.T;
             if (sidx > 0) {
-                SKA_TRY(side_join(st));
+                SKA_TRY(cx.join());
                 const float ratio = p.eps_stage[sidx - 1] / es;
                 long tot = 2L * Lp * N;
                 hipLaunchKernelGGL(scale_kernel, dim3((tot + 255) / 256), dim3(256), 0, st, UV, 2L * Lp, us, N, ratio);
                 if (hipGetLastError() != hipSuccess) return SKA_EHIP;
                 SKA_TRY((make_scores_operand<T>(p, es, Qin, ws, &Q, &stage_c2, st)));
-                SKA_TRY(side_fork(st));
+                SKA_TRY(cx.fork());
             }
             stage_sdb2 = p.sdb * (p.eps / es) * LOG2E;
             for (int t = 0; t < Ts; ++t) {
@@ -473,28 +494,29 @@ int fwd_impl(const Problem &p, const void *Qin, const void *K, const void *V, vo
         }
         return SKA_OK;
     };
-    SKA_TRY(side_fork(st));   // everything above ran for all problems on st
+    SKA_TRY(cx.fork());   // everything above ran for all problems on st
     const int rc_halves = halves();
     if (pt_run) pt_run->~PhaseTimer();
     SKA_TRY(rc_halves);
     // output map with the terminal plan
-    PhaseTimer pt_out(SKA_PH_OUTPUT, st);
+    PhaseTimer pt_out(SKA_PH_OUTPUT, cx);
     SweepArgs a = base;
     a.X = Q; a.Y = K; a.Pay = V; a.out_mat = O; a.xs = vec(2 * R); a.yt = vec(2 * R + 1);
     a.len_own = p.len_q; a.len_oth = p.len_k;
     if (p.token()) { a.spoke_own = SQ; a.pay_db = p.v_db; }   // O_i += P(i, d_k) v_db
     a.rev = nlaunch & 1;
     pt_out.launched();
-    SKA_TRY((sweep<T, D>(M_APPLY, a, N, st)));
+    SKA_TRY((sweep<T, D>(cx, M_APPLY, a, N)));
     pt_out.end();
-    return fused ? SKA_OK : side_join(st);
+    return fused ? SKA_OK : cx.join();
 }
 
 template <typename T, int D>
-int bwd_impl(const Problem &p, const void *Qin, const void *K, const void *V, const void *O,
+int bwd_impl(Call &cx, const Problem &p, const void *Qin, const void *K, const void *V, const void *O,
              const void *G, const float *UV, void *dQ, void *dK, void *dV, float *eta0, void *ws,
-             hipStream_t st, const float *seed = nullptr, bool fused = false)
+             const float *seed = nullptr, bool fused = false)
 {
+    const hipStream_t st = cx.st;
     // fused: the forward of the same call has just run (sinkhorn_attn_step): its prescaled operand
     // is in place, and the helper stream is still running its half of the problems.
     // seed != null: no output map at the end of the chain.  The reverse recurrences start from
@@ -508,7 +530,7 @@ int bwd_impl(const Problem &p, const void *Qin, const void *K, const void *V, co
         Q = (sizeof(T) == 2) ? reinterpret_cast<unsigned char *>(ws) + ws_vec_bytes(p) : Qin;
         c2 = (sizeof(T) == 2) ? 1.f : LOG2E / (p.eps * sqrtf((float)p.d));
     } else {
-        PhaseTimer pt(SKA_PH_PRESCALE, st);
+        PhaseTimer pt(SKA_PH_PRESCALE, cx);
         SKA_TRY((make_scores_operand<T>(p, p.eps, Qin, reinterpret_cast<unsigned char *>(ws) + ws_vec_bytes(p), &Q, &c2, st)));
         pt.launched(sizeof(T) == 2 ? 1 : 0);
     }
@@ -546,8 +568,8 @@ int bwd_impl(const Problem &p, const void *Qin, const void *K, const void *V, co
     const int nchunk = ws_chunks(p);
     // the kernels before the sweeps take all problems on st -- except the plain row dot of a fused
     // step, which each stream does for its own half so that the two chains stay apart
-    const bool own_halves = fused && g_cur_side && !seed && !p.dustbin;
-    if (fused && !own_halves) SKA_TRY(side_join(st));
+    const bool own_halves = fused && cx.side && !seed && !p.dustbin;
+    if (fused && !own_halves) SKA_TRY(cx.join());
     if (p.token()) {
         SQ = Vec{tok, ldw};
         SK = Vec{tok + nldp, ldw};
@@ -555,7 +577,7 @@ int bwd_impl(const Problem &p, const void *Qin, const void *K, const void *V, co
     }
 
     // g_u = <dO_i, O_i> (= (P22 . Z) 1); dustbin row has dO = 0
-    PhaseTimer pt_gu(SKA_PH_ROWDOT, st);
+    PhaseTimer pt_gu(SKA_PH_ROWDOT, cx);
     pt_gu.launched();
     constexpr int LPR = D * (int)sizeof(T) / 16;
     if (seed) {
@@ -568,7 +590,7 @@ int bwd_impl(const Problem &p, const void *Qin, const void *K, const void *V, co
                            reinterpret_cast<const T *>(O), gu, ldw, L, Lp, p.len_q, p.H, 0);
         if (N > n1)
             hipLaunchKernelGGL((rowdot_kernel<T, D>), dim3(((long)Lp * LPR + 255) / 256, N - n1), dim3(256), 0,
-                               g_cur_side->s, reinterpret_cast<const T *>(G) + (long)n1 * L * D,
+                               cx.side->s, reinterpret_cast<const T *>(G) + (long)n1 * L * D,
                                reinterpret_cast<const T *>(O) + (long)n1 * L * D, gu + n1 * ldw, ldw, L, Lp, p.len_q,
                                p.H, n1);
         if (hipGetLastError() != hipSuccess) return SKA_EHIP;
@@ -585,10 +607,10 @@ int bwd_impl(const Problem &p, const void *Qin, const void *K, const void *V, co
         }
     }
     pt_gu.end();
-    if (!own_halves) SKA_TRY(side_fork(st));   // everything above ran for all problems on st
+    if (!own_halves) SKA_TRY(cx.fork());   // everything above ran for all problems on st
     // dV_j = sum_i P_RR,ij dO_i ; vbar_R,j = <V_j, dV_j>  (column-oriented)
     if (!seed) {
-        PhaseTimer pt(SKA_PH_DV, st);
+        PhaseTimer pt(SKA_PH_DV, cx);
         pt.launched();
         SweepArgs a = base;
         a.X = K; a.Y = Q; a.Pay = G; a.out_mat = dV; a.xs = uv(2 * R + 1); a.yt = uv(2 * R);
@@ -596,7 +618,7 @@ int bwd_impl(const Problem &p, const void *Qin, const void *K, const void *V, co
         a.len_own = p.len_k; a.len_oth = p.len_q;
         a.olog = Vec{p.log_b, (long)Lp};   // the workspace holds vbar / b and ubar / a (general marginals)
         a.rev = nlaunch++ & 1;
-        SKA_TRY((sweep<T, D>(M_APPLY, a, N, st)));
+        SKA_TRY((sweep<T, D>(cx, M_APPLY, a, N)));
     }
     // reverse recurrences of Prop. 1, each one band mat-vec with a staircase factor
     // written as P22 times row/column modifiers folded into the exponent (Prop. 2)
@@ -608,11 +630,11 @@ int bwd_impl(const Problem &p, const void *Qin, const void *K, const void *V, co
         a.len_own = row ? p.len_q : p.len_k; a.len_oth = row ? p.len_k : p.len_q;
         a.spoke_own = row ? SQ : SK; a.spoke_oth = row ? SK : SQ;
         a.rev = nlaunch++ & 1;
-        SKA_TRY((sweep<T, D>(M_MATVEC, a, N, st)));
+        SKA_TRY((sweep<T, D>(cx, M_MATVEC, a, N)));
         return SKA_OK;
     };
     {
-        PhaseTimer pt(SKA_PH_MATVEC, st);
+        PhaseTimer pt(SKA_PH_MATVEC, cx);
         pt.launched(2 * R - 1 + (eta0 ? 1 : 0));
         // ubar_R = g_u - P_RR vbar_R
         SKA_TRY(matvec(true, uv(2 * R), uv(2 * R + 1), vbar(R), seed ? nullptr : gu, wo(ubar(R))));
@@ -624,14 +646,14 @@ int bwd_impl(const Problem &p, const void *Qin, const void *K, const void *V, co
             if (t >= 2) SKA_TRY(matvec(true, uv(2 * t - 2), uv(2 * t - 1), vbar(t - 1), nullptr, wo(ubar(t - 1))));
         }
     }
-    PhaseTimer pt_final(SKA_PH_FINAL, st);   // modifier packs and the two final sweeps
+    PhaseTimer pt_final(SKA_PH_FINAL, cx);   // modifier packs and the two final sweeps
     pt_final.launched(2 * ((nq + MAXNQ - 1) / MAXNQ));
     {   // a problem's packs need only its own recurrences: each stream writes those of its half
-        const int n1 = (g_cur_side && N >= 2) ? N / 2 : N;
+        const int n1 = (cx.side && N >= 2) ? N / 2 : N;
         for (int part = 0; part < 2; ++part) {
             const int nb = part ? n1 : 0, cnt = part ? N - n1 : n1;
             if (cnt == 0) continue;
-            hipLaunchKernelGGL(packs_kernel, dim3((Lp + 255) / 256, cnt), dim3(256), 0, part ? g_cur_side->s : st,
+            hipLaunchKernelGGL(packs_kernel, dim3((Lp + 255) / 256, cnt), dim3(256), 0, part ? cx.side->s : st,
                                UV + (long)nb * us, Lp, R, wf + nb * ldw, nldp, ldw,
                                reinterpret_cast<float *>(rowp) + nb * ldw * 4L * nq,
                                reinterpret_cast<float *>(colp) + nb * ldw * 4L * nq, nq,
@@ -653,7 +675,7 @@ int bwd_impl(const Problem &p, const void *Qin, const void *K, const void *V, co
             if (seed) { a.A = Q; a.Bm = K; a.skipz = 1; }   // Z = 0; the factors are fetched but unused
             if (AUG) { a.poB = aug + 1 * nldp * 16; a.qtA = aug + 2 * nldp * 16; }   // rows own, columns stream
             a.rev = nlaunch++ & 1;
-            SKA_TRY((sweep<T, D>(final_mode, a, N, st)));
+            SKA_TRY((sweep<T, D>(cx, final_mode, a, N)));
         }
         {
             SweepArgs a = base;
@@ -667,11 +689,11 @@ int bwd_impl(const Problem &p, const void *Qin, const void *K, const void *V, co
             // payload rows are Qs = (cs log2 e) Q when prescaled: cs sum Sbar^T Q = ln 2 sum Sbar^T Qs
             if (sizeof(T) == 2) a.cs = LN2;
             a.rev = nlaunch++ & 1;
-            SKA_TRY((sweep<T, D>(final_mode, a, N, st)));
+            SKA_TRY((sweep<T, D>(cx, final_mode, a, N)));
         }
     }
     pt_final.end();
-    SKA_TRY(side_join(st));
+    SKA_TRY(cx.join());
     if (p.token()) {
         // the spokes' share (Prop. 2 on the augmented support): cotangents of the 2L + 1 spoke
         // scores, then their chain rule to Q, K (rank-1 updates) and to the tokens (weighted sums)
@@ -749,9 +771,9 @@ static int fwd_call(const Problem &p, const void *Q, const void *K, const void *
     if (ws_qs_bytes(p) && (!workspace || workspace_bytes < ws_qs_bytes(p))) return SKA_EWORKSPACE;
     if (p.token() && (!workspace || workspace_bytes < ws_bytes(p))) return SKA_EWORKSPACE;
     if (reinterpret_cast<uintptr_t>(workspace) & 15) return SKA_EINVAL;
-    hipStream_t st = reinterpret_cast<hipStream_t>(stream);
-    SideScope split(p.N(), p.L, p.W);
-#define SKA_FWD(TT_, DD_) return fwd_impl<TT_, DD_>(p, Q, K, V, O, UV, workspace, st)
+    Call cx(stream, p.N(), p.L, p.W);
+    if (cx.rc != SKA_OK) return cx.rc;
+#define SKA_FWD(TT_, DD_) return fwd_impl<TT_, DD_>(cx, p, Q, K, V, O, UV, workspace)
     if (dtype == SKA_F32) {
         if (d == 32) SKA_FWD(float, 32);
         if (d == 64) SKA_FWD(float, 64);
@@ -871,9 +893,9 @@ static int bwd_problem(const Problem &p, const void *Q, const void *K, const voi
     if (rc != SKA_OK) return rc;
     if (!workspace || workspace_bytes < ws_bytes(p)) return SKA_EWORKSPACE;
     if (reinterpret_cast<uintptr_t>(workspace) & 15) return SKA_EINVAL;
-    hipStream_t st = reinterpret_cast<hipStream_t>(stream);
-    SideScope split(p.N(), p.L, p.W);
-#define SKA_BWD(TT_, DD_) return bwd_impl<TT_, DD_>(p, Q, K, V, O, dO, UV, dQ, dK, dV, eta0, workspace, st)
+    Call cx(stream, p.N(), p.L, p.W);
+    if (cx.rc != SKA_OK) return cx.rc;
+#define SKA_BWD(TT_, DD_) return bwd_impl<TT_, DD_>(cx, p, Q, K, V, O, dO, UV, dQ, dK, dV, eta0, workspace)
     if (dtype == SKA_F32) {
         if (d == 32) SKA_BWD(float, 32);
         if (d == 64) SKA_BWD(float, 64);
@@ -899,10 +921,10 @@ int sinkhorn_attn_base_vjp(const void *Q, const void *K, const float *log_a, con
     if (rc != SKA_OK) return rc;
     if (!workspace || workspace_bytes < ws_bytes(p)) return SKA_EWORKSPACE;
     if (reinterpret_cast<uintptr_t>(workspace) & 15) return SKA_EINVAL;
-    hipStream_t st = reinterpret_cast<hipStream_t>(stream);
-    SideScope split(p.N(), p.L, p.W);
+    Call cx(stream, p.N(), p.L, p.W);
+    if (cx.rc != SKA_OK) return cx.rc;
 #define SKA_VJP(TT_, DD_) \
-    return bwd_impl<TT_, DD_>(p, Q, K, nullptr, nullptr, nullptr, UV, dQ, dK, nullptr, nullptr, workspace, st, eta)
+    return bwd_impl<TT_, DD_>(cx, p, Q, K, nullptr, nullptr, nullptr, UV, dQ, dK, nullptr, nullptr, workspace, eta)
     if (dtype == SKA_F32) {
         if (d == 32) SKA_VJP(float, 32);
         if (d == 64) SKA_VJP(float, 64);
@@ -951,14 +973,13 @@ int sinkhorn_attn_step(const void *Q, const void *K, const void *V, const void *
     if (rc != SKA_OK) return rc;
     if (!workspace || workspace_bytes < ws_bytes(p)) return SKA_EWORKSPACE;
     if (reinterpret_cast<uintptr_t>(workspace) & 15) return SKA_EINVAL;
-    hipStream_t st = reinterpret_cast<hipStream_t>(stream);
-    SideScope split(p.N(), p.L, p.W);
+    Call cx(stream, p.N(), p.L, p.W);
+    if (cx.rc != SKA_OK) return cx.rc;
 #define SKA_STEP(TT_, DD_)                                                                              \
     do {                                                                                                \
-        rc = fwd_impl<TT_, DD_>(p, Q, K, V, O, UV, workspace, st, true);                                \
+        rc = fwd_impl<TT_, DD_>(cx, p, Q, K, V, O, UV, workspace, true);                                \
         if (rc == SKA_OK)                                                                               \
-            rc = bwd_impl<TT_, DD_>(p, Q, K, V, O, dO, UV, dQ, dK, dV, eta0, workspace, st, nullptr, true); \
-        if (rc != SKA_OK) (void)side_join(st);                                                          \
+            rc = bwd_impl<TT_, DD_>(cx, p, Q, K, V, O, dO, UV, dQ, dK, dV, eta0, workspace, nullptr, true); \
         return rc;                                                                                      \
     } while (0)
     if (dtype == SKA_F32) {
@@ -1100,6 +1121,7 @@ int sinkhorn_attn_probe_issue(float *scratch, size_t scratch_bytes, int tiles, i
 int sinkhorn_attn_set_streams(int n)
 {
     if (n != 1 && n != 2) return SKA_EINVAL;
+    std::lock_guard<std::mutex> lk(g_mutex);
     g_streams = n;
     return SKA_OK;
 }
@@ -1107,12 +1129,14 @@ int sinkhorn_attn_set_streams(int n)
 int sinkhorn_attn_set_split_min_edges(double edges)
 {
     if (!(edges >= 0.0)) return SKA_EINVAL;
+    std::lock_guard<std::mutex> lk(g_mutex);
     g_split_min_edges = edges;
     return SKA_OK;
 }
 
 int sinkhorn_attn_profile_enable(int on)
 {
+    std::lock_guard<std::mutex> lk(g_mutex);
     g_prof_on = on < 0 ? 0 : (on > 2 ? 2 : on);
     return SKA_OK;
 }
@@ -1122,11 +1146,19 @@ int sinkhorn_attn_profile_read_phases(double *elapsed_ms, long *launches)
     if (!elapsed_ms || !launches) return SKA_EINVAL;
     for (int k = 0; k < SKA_PH_COUNT; ++k) { elapsed_ms[k] = 0.0; launches[k] = 0; }
     int rc = SKA_OK;
+    std::lock_guard<std::mutex> lk(g_mutex);
     for (int i = 0; i < g_prof_n; ++i) {
-        float t = 0.f;
+        float t = 0.f, t2 = 0.f;
         if (hipEventSynchronize(g_prof[i].b) != hipSuccess ||
             hipEventElapsedTime(&t, g_prof[i].a, g_prof[i].b) != hipSuccess)
             rc = SKA_EHIP;
+        if (g_prof[i].b2) {   // the helper stream's end of the span: the later of the two counts
+            if (hipEventSynchronize(g_prof[i].b2) != hipSuccess ||
+                hipEventElapsedTime(&t2, g_prof[i].a, g_prof[i].b2) != hipSuccess)
+                rc = SKA_EHIP;
+            (void)hipEventDestroy(g_prof[i].b2);
+            if (t2 > t) t = t2;
+        }
         elapsed_ms[g_prof[i].phase] += t;
         launches[g_prof[i].phase] += g_prof[i].launches;
         (void)hipEventDestroy(g_prof[i].a);
