@@ -63,7 +63,9 @@ typedef enum {
     SKA_EINVAL = -1,       /* null required pointer, non-positive size, bad eps        */
     SKA_EUNSUPPORTED = -2, /* R outside 1..32, unsupported d, unknown dtype             */
     SKA_EWORKSPACE = -3,   /* workspace smaller than sinkhorn_attn_workspace_bytes()    */
-    SKA_EHIP = -4          /* a HIP launch failed (hipGetLastError)                     */
+    SKA_EHIP = -4,         /* a HIP launch failed (hipGetLastError)                     */
+    SKA_ESTATIC = -5       /* sinkhorn_attn_step_static: the problem needs more scratch */
+                           /* than SKA_STATIC_SCRATCH_BYTES                             */
 } ska_status;
 
 /*
@@ -122,6 +124,28 @@ int sinkhorn_attn_step(const void *Q, const void *K, const void *V, const void *
                        void *O, float *UV, void *dQ, void *dK, void *dV, float *eta0, int B, int H,
                        int L, int d, int W, int T, int R, float eps, int dustbin, float dustbin_score,
                        int dtype, void *workspace, size_t workspace_bytes, void *stream);
+
+/*
+ * sinkhorn_attn_step for callers that cannot allocate device memory or have it allocated for
+ * them: code under HIP graph capture, tight serving loops, harnesses that forbid hipMalloc.
+ * Same arguments and results as sinkhorn_attn_step, bit for bit, without the workspace: the
+ * scratch is a static device array inside the library of SKA_STATIC_SCRATCH_BYTES bytes (32 MiB;
+ * every GPU the library is loaded on holds it until the process ends).  The call allocates and
+ * frees nothing, creates no stream and no event, and keeps all its kernels on `stream` (it never
+ * uses the helper stream; the profiling hooks ignore it).
+ *   A problem whose sinkhorn_attn_workspace_bytes(...) exceeds SKA_STATIC_SCRATCH_BYTES is
+ *   refused with SKA_ESTATIC before anything is launched (about 98,000 token-heads B*H*L at
+ *   d = 64, bf16, R = 2).
+ *   All calls on one GPU share that GPU's array and it keeps the last call's contents (nothing
+ *   in it needs clearing: each step writes what it reads).  Two calls that overlap on one GPU
+ *   (different streams, or different host threads) race on it: the caller keeps them ordered.
+ */
+#define SKA_STATIC_SCRATCH_BYTES (32u << 20)
+int sinkhorn_attn_step_static(const void *Q, const void *K, const void *V, const void *dO,
+                              const float *log_a, const float *log_b, const int *len_q,
+                              const int *len_k, void *O, float *UV, void *dQ, void *dK, void *dV,
+                              float *eta0, int B, int H, int L, int d, int W, int T, int R, float eps,
+                              int dustbin, float dustbin_score, int dtype, void *stream);
 
 /*
  * The same two calls with compatible general marginals (appendix "Compatible General

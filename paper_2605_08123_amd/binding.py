@@ -16,7 +16,8 @@ LIB_PATH = os.path.join(_PKG, "libsinkhorn_attn.so")
 
 SKA_F32, SKA_BF16 = 0, 1
 SKA_BWD_ONE_REFERENCE, SKA_BWD_DIRECT, SKA_BWD_ONE_REFERENCE_GENERIC = 0, 1, 2
-SKA_OK, SKA_EINVAL, SKA_EUNSUPPORTED, SKA_EWORKSPACE, SKA_EHIP = 0, -1, -2, -3, -4
+SKA_OK, SKA_EINVAL, SKA_EUNSUPPORTED, SKA_EWORKSPACE, SKA_EHIP, SKA_ESTATIC = 0, -1, -2, -3, -4, -5
+SKA_STATIC_SCRATCH_BYTES = 32 << 20
 
 _lib = None
 
@@ -75,6 +76,8 @@ def load():
         lib.sinkhorn_attn_set_split_min_edges.argtypes = [ctypes.c_double]
         lib.sinkhorn_attn_step.restype = i
         lib.sinkhorn_attn_step.argtypes = [vp] * 14 + [i] * 7 + [f, i, f, i, vp, sz, vp]
+        lib.sinkhorn_attn_step_static.restype = i
+        lib.sinkhorn_attn_step_static.argtypes = [vp] * 14 + [i] * 7 + [f, i, f, i, vp]
         lib.sinkhorn_attn_profile_enable.restype = i
         lib.sinkhorn_attn_profile_enable.argtypes = [i]
         lib.sinkhorn_attn_profile_read.restype = i
@@ -399,6 +402,28 @@ def sinkhorn_attn_step(Q, K, V, dO, W, T, R=2, eps=1.0, dustbin=False, dustbin_s
     if rc != SKA_OK:
         raise SinkhornAttnError(rc)
     return (O, UV, dQ, dK, dV, eta0) if want_eta0 else (O, UV, dQ, dK, dV)
+
+
+def sinkhorn_attn_step_static(Q, K, V, dO, O, UV, dQ, dK, dV, W, T, R=2, eps=1.0, dustbin=False, dustbin_score=0.0,
+                              log_a=None, log_b=None, len_q=None, len_k=None, eta0=None):
+    """sinkhorn_attn_step on the library's static scratch: the caller passes every output, nothing
+    is allocated here or in the library.  Problems beyond SKA_STATIC_SCRATCH_BYTES raise
+    SinkhornAttnError(SKA_ESTATIC)."""
+    B, H, L, d = Q.shape
+    for n, x in (("Q", Q), ("K", K), ("V", V), ("dO", dO), ("O", O), ("dQ", dQ), ("dK", dK), ("dV", dV)):
+        _check(x, (B, H, L, d), Q.dtype, n)
+    Lp = L + int(bool(dustbin))
+    _check(UV, (B, H, 2 * (R + 1), Lp), torch.float32, "UV")
+    if eta0 is not None:
+        _check(eta0, (B, H, Lp), torch.float32, "eta0")
+    rc = load().sinkhorn_attn_step_static(
+        Q.data_ptr(), K.data_ptr(), V.data_ptr(), dO.data_ptr(), _marg_ptr(log_a, (B, H, L), "log_a"),
+        _marg_ptr(log_b, (B, H, L), "log_b"), _len_ptr(len_q, B, "len_q"), _len_ptr(len_k, B, "len_k"), O.data_ptr(),
+        UV.data_ptr(), dQ.data_ptr(), dK.data_ptr(), dV.data_ptr(), None if eta0 is None else eta0.data_ptr(), B, H,
+        L, d, W, T, R, float(eps), int(bool(dustbin)), float(dustbin_score), _dtype_code(Q), _stream_ptr())
+    if rc != SKA_OK:
+        raise SinkhornAttnError(rc)
+    return O, UV, dQ, dK, dV
 
 
 def sinkhorn_attn_select_workspace_bytes(B, H, L, d, W, T, R_max, dustbin=False, dtype=SKA_BF16) -> int:

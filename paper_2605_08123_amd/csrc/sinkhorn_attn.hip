@@ -43,7 +43,7 @@
 namespace {
 
 // ------------------------------------------------------------------ host side
-constexpr int MAX_DEVICES = 16;   // per-device state of the library (helper stream, raised LDS limits)
+constexpr int MAX_DEVICES = 16;   // per-device state of the library (helper stream, raised LDS limits, static scratch)
 
 struct Problem {
     int B, H, L, d, W, T, R, dustbin, dtype;
@@ -289,9 +289,10 @@ struct Call {
     int rc = SKA_OK;
     Side *side = nullptr;    // the helper stream while this call splits its sweeps
     bool busy = false;       // the helper stream holds work that st has not joined
+    bool noalloc = false;    // a call that may create nothing: no helper stream, no profiling events
     std::unique_lock<std::mutex> lk;
     Call(void *stream, int nproblems, int L, int W, bool may_split = true)
-        : st(reinterpret_cast<hipStream_t>(stream)), lk(g_mutex)
+        : st(reinterpret_cast<hipStream_t>(stream)), noalloc(!may_split), lk(g_mutex)
     {
         if (hipGetDevice(&dev) != hipSuccess) { rc = SKA_EHIP; dev = 0; return; }
         if (dev < 0 || dev >= MAX_DEVICES) { rc = SKA_EUNSUPPORTED; dev = 0; return; }
@@ -360,7 +361,7 @@ struct PhaseTimer {
     Call &cx;
     PhaseTimer(int phase, Call &cx_) : cx(cx_)
     {
-        if (g_prof_on < (phase == SKA_PH_SCALING ? 1 : 2) || g_prof_n >= PROF_MAX) return;
+        if (cx.noalloc || g_prof_on < (phase == SKA_PH_SCALING ? 1 : 2) || g_prof_n >= PROF_MAX) return;
         ProfSpan *c = &g_prof[g_prof_n];
         c->b2 = nullptr;
         if (hipEventCreate(&c->a) != hipSuccess) return;
@@ -751,6 +752,16 @@ template <typename T> int absmax_launch(const void *x, long n, float *out, hipSt
 
 }  // namespace
 
+// Scratch of the entry point that allocates nothing (sinkhorn_attn_step_static): one array per
+// GPU, held from the moment the library is loaded on it until the process ends.  In host code
+// the array's name is only a handle for hipGetSymbolAddress; kernels get the device address
+// that call returned (kept per device in g_scratch_ptr).
+static __device__ __align__(256) unsigned char scratch[SKA_STATIC_SCRATCH_BYTES];
+
+namespace {
+void *g_scratch_ptr[MAX_DEVICES];   // (g_mutex held)
+}
+
 // ====================================================================== C ABI
 extern "C" {
 
@@ -994,6 +1005,46 @@ int sinkhorn_attn_step(const void *Q, const void *K, const void *V, const void *
 #undef SKA_STEP
 }
 
+int sinkhorn_attn_step_static(const void *Q, const void *K, const void *V, const void *dO, const float *log_a,
+                              const float *log_b, const int *len_q, const int *len_k, void *O, float *UV,
+                              void *dQ, void *dK, void *dV, float *eta0, int B, int H, int L, int d, int W, int T,
+                              int R, float eps, int dustbin, float dustbin_score, int dtype, void *stream)
+{
+    Problem p{B, H, L, d, W, T, R, dustbin ? 1 : 0, dtype, eps, dustbin_score, log_a, log_b, len_q, len_k};
+    if (!Q || !K || !V || !dO || !O || !UV || !dQ || !dK || !dV) return SKA_EINVAL;
+    int rc = check_common(p);
+    if (rc != SKA_OK) return rc;
+    if (ws_bytes(p) > (size_t)SKA_STATIC_SCRATCH_BYTES) return SKA_ESTATIC;
+    // everything on the caller's stream: no helper stream, no events, nothing created
+    Call cx(stream, p.N(), p.L, p.W, false);
+    if (cx.rc != SKA_OK) return cx.rc;
+    if (!g_scratch_ptr[cx.dev]) {   // once per device, with that device current
+        void *ptr = nullptr;
+        if (hipGetSymbolAddress(&ptr, HIP_SYMBOL(scratch)) != hipSuccess || !ptr) return SKA_EHIP;
+        g_scratch_ptr[cx.dev] = ptr;
+    }
+    // Nothing in the scratch has to start at zero: every kernel of a step writes what a later
+    // one reads (the same holds for a caller's workspace, which arrives uninitialised).
+    void *ws = g_scratch_ptr[cx.dev];
+#define SKA_STEP(TT_, DD_)                                                                              \
+    do {                                                                                                \
+        rc = fwd_impl<TT_, DD_>(cx, p, Q, K, V, O, UV, ws, true);                                       \
+        if (rc == SKA_OK)                                                                               \
+            rc = bwd_impl<TT_, DD_>(cx, p, Q, K, V, O, dO, UV, dQ, dK, dV, eta0, ws, nullptr, true);    \
+        return rc;                                                                                      \
+    } while (0)
+    if (dtype == SKA_F32) {
+        if (d == 32) SKA_STEP(float, 32);
+        if (d == 64) SKA_STEP(float, 64);
+        SKA_STEP(float, 128);
+    } else {
+        if (d == 32) SKA_STEP(__bf16, 32);
+        if (d == 64) SKA_STEP(__bf16, 64);
+        SKA_STEP(__bf16, 128);
+    }
+#undef SKA_STEP
+}
+
 int sinkhorn_attn_bwd_marginals(const void *Q, const void *K, const void *V, const float *log_a,
                                 const float *log_b, const void *O, const void *dO, const float *UV, void *dQ,
                                 void *dK, void *dV, float *eta0, int B, int H, int L, int d, int W, int T,
@@ -1187,6 +1238,7 @@ const char *sinkhorn_attn_strerror(int status)
     case SKA_EUNSUPPORTED: return "unsupported configuration (need R in 1..32, L <= 2^24, d in {32, 64, 128}, dtype f32 or bf16; no dustbin with marginal targets or lengths)";
     case SKA_EWORKSPACE: return "workspace missing or smaller than sinkhorn_attn_workspace_bytes()";
     case SKA_EHIP: return "a HIP launch failed";
+    case SKA_ESTATIC: return "problem too large for sinkhorn_attn_step_static: it needs more scratch than the library's static buffer (SKA_STATIC_SCRATCH_BYTES); use sinkhorn_attn_step with a workspace";
     default: return "unknown status";
     }
 }

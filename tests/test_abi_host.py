@@ -29,7 +29,7 @@ def test_library_exports_every_declared_symbol():
                      "sinkhorn_attn_profile_read", "sinkhorn_attn_profile_read_phases",
                      "sinkhorn_attn_select_tail_depth", "sinkhorn_attn_select_workspace_bytes",
                      "sinkhorn_attn_set_split_min_edges", "sinkhorn_attn_set_streams", "sinkhorn_attn_step",
-                     "sinkhorn_attn_strerror",
+                     "sinkhorn_attn_step_static", "sinkhorn_attn_strerror",
                      "sinkhorn_attn_workspace_bytes"]
     for n in names:
         assert hasattr(lib, n), n
@@ -48,7 +48,7 @@ def test_workspace_bytes_and_strerror():
     a = binding.sinkhorn_attn_workspace_bytes(2, 2, 1000, 64, 10, 5, dustbin=False)
     b = binding.sinkhorn_attn_workspace_bytes(2, 2, 1000, 64, 10, 5, dustbin=True)
     assert b > a > 0
-    for s in (0, -1, -2, -3, -4, 17):
+    for s in (0, -1, -2, -3, -4, -5, 17):
         assert isinstance(binding.sinkhorn_attn_strerror(s), str) and binding.sinkhorn_attn_strerror(s)
 
 
@@ -119,3 +119,22 @@ def test_binding_rejects_cpu_tensors():
     x = torch.zeros((1, 1, 8, 32))
     with pytest.raises(ValueError):
         binding.sinkhorn_attn_fwd(x, x, x, 2, 1)
+
+
+def test_step_static_rejects_before_any_launch():
+    """The no-allocation entry point checks its arguments, and the size against the static scratch,
+    on the host."""
+    lib = binding.load()
+    p = ctypes.c_void_p(1 << 20)
+
+    def call(L=64, d=32, ptr=p, R=2, eps=1.0):
+        return lib.sinkhorn_attn_step_static(ptr, p, p, p, None, None, None, None, p, p, p, p, p, None, 1, 2, L, d, 4, 2,
+                                             R, ctypes.c_float(eps), 0, ctypes.c_float(0.0), 1, None)
+    assert call(ptr=None) == binding.SKA_EINVAL
+    assert call(eps=0.0) == binding.SKA_EINVAL
+    assert call(d=48) == binding.SKA_EUNSUPPORTED
+    assert call(R=0) == binding.SKA_EUNSUPPORTED
+    big = 262144
+    assert binding.sinkhorn_attn_workspace_bytes(1, 2, big, 64, 4, 2) > binding.SKA_STATIC_SCRATCH_BYTES
+    assert call(L=big, d=64) == binding.SKA_ESTATIC
+    assert "static" in binding.sinkhorn_attn_strerror(binding.SKA_ESTATIC)
