@@ -111,10 +111,13 @@ int sinkhorn_attn_bwd(const void *Q, const void *K, const void *V, const void *O
 /*
  * Forward and backward in one call, for a cotangent dO that is known beforehand (the paper's
  * "complete-step executable": output plus the Q/K/V VJP for a given output cotangent, which is
- * what its throughput is quoted on).  Results are those of sinkhorn_attn_fwd_varlen followed by
- * sinkhorn_attn_bwd_varlen, bit for bit; what the single call saves is the second prescale of Q
- * and the joining of the two streams between the two directions: each half of the problems runs
- * its forward and its backward as one uninterrupted chain.
+ * what its throughput is quoted on).  O, UV and dV are those of sinkhorn_attn_fwd_varlen followed
+ * by sinkhorn_attn_bwd_varlen bit for bit; dQ, dK and eta0 agree with them to rounding: without a
+ * dustbin the seed g_u = <dO_i, O_i> (Sec. 2.2) is taken from the output map's fp32 accumulators
+ * instead of from the stored, dtype-rounded O (with a dustbin they too are bit for bit).  What the
+ * single call saves is the second prescale of Q, the pass over O and dO for g_u, and the joining
+ * of the two streams between the two directions: each half of the problems runs its forward and
+ * its backward as one uninterrupted chain.
  *   in : Q, K, V, dO; log_a, log_b, len_q, len_k as in those calls (may be NULL)
  *   out: O, UV, dQ, dK, dV, eta0 (may be NULL)
  *   workspace: sinkhorn_attn_workspace_bytes(...) bytes, 16-byte aligned.

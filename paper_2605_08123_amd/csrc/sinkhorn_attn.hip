@@ -385,14 +385,21 @@ struct PhaseTimer {
 };
 
 
+// one-call step without a dustbin: the forward's output map writes g_u (the dustbin's extra row
+// needs a zero there that only the row-dot kernel writes)
+inline bool fused_gu(const Problem &p, bool fused, const void *G) { return fused && G && !p.dustbin; }
+
 template <typename T, int D>
 int fwd_impl(Call &cx, const Problem &p, const void *Qin, const void *K, const void *V, void *O, float *UV,
-             void *ws, bool fused = false)
+             void *ws, bool fused = false, const void *G = nullptr)
 {
     const hipStream_t st = cx.st;
     // fused: the backward of the same call follows (sinkhorn_attn_step).  The prescaled operand
     // then goes where the backward expects it, and the helper stream is not joined at the end:
     // each half of the problems runs its forward and backward as one uninterrupted chain.
+    // G (fused, no dustbin): the output cotangent; the output map then also leaves
+    // g_u = <dO_i, O_i> (Sec. 2.2), taken from its fp32 accumulators, in the backward's first
+    // workspace vector, so that the backward needs no pass over O and dO for it.
     // Q below is the score operand: for bf16 storage the prescaled copy, with c2 = 1
     const void *Q = nullptr;
     float c2 = 0.f;
@@ -505,6 +512,7 @@ int fwd_impl(Call &cx, const Problem &p, const void *Qin, const void *K, const v
     a.X = Q; a.Y = K; a.Pay = V; a.out_mat = O; a.xs = vec(2 * R); a.yt = vec(2 * R + 1);
     a.len_own = p.len_q; a.len_oth = p.len_k;
     if (p.token()) { a.spoke_own = SQ; a.pay_db = p.v_db; }   // O_i += P(i, d_k) v_db
+    if (fused_gu(p, fused, G)) { a.dot_mat = G; a.dot_out = VecOut{reinterpret_cast<float *>(ws), p.ldw()}; }
     a.rev = nlaunch & 1;
     pt_out.launched();
     SKA_TRY((sweep<T, D>(cx, M_APPLY, a, N)));
@@ -579,11 +587,13 @@ int bwd_impl(Call &cx, const Problem &p, const void *Qin, const void *K, const v
 
     // g_u = <dO_i, O_i> (= (P22 . Z) 1); dustbin row has dO = 0
     PhaseTimer pt_gu(SKA_PH_ROWDOT, cx);
-    pt_gu.launched();
+    if (seed || !fused_gu(p, fused, G)) pt_gu.launched();
     constexpr int LPR = D * (int)sizeof(T) / 16;
     if (seed) {
         hipLaunchKernelGGL(seed_kernel, vgrid, dim3(256), 0, st, seed, p.log_b, vbar(R), ldw, Lp);
         if (hipGetLastError() != hipSuccess) return SKA_EHIP;
+    } else if (fused_gu(p, fused, G)) {
+        // the forward's output map has left g_u in place (from its fp32 accumulators)
     } else {
         const int n1 = own_halves ? N / 2 : N;
         hipLaunchKernelGGL((rowdot_kernel<T, D>), dim3(((long)Lp * LPR + 255) / 256, n1), dim3(256), 0, st,
@@ -988,7 +998,7 @@ int sinkhorn_attn_step(const void *Q, const void *K, const void *V, const void *
     if (cx.rc != SKA_OK) return cx.rc;
 #define SKA_STEP(TT_, DD_)                                                                              \
     do {                                                                                                \
-        rc = fwd_impl<TT_, DD_>(cx, p, Q, K, V, O, UV, workspace, true);                                \
+        rc = fwd_impl<TT_, DD_>(cx, p, Q, K, V, O, UV, workspace, true, dO);                            \
         if (rc == SKA_OK)                                                                               \
             rc = bwd_impl<TT_, DD_>(cx, p, Q, K, V, O, dO, UV, dQ, dK, dV, eta0, workspace, nullptr, true); \
         return rc;                                                                                      \
@@ -1028,7 +1038,7 @@ int sinkhorn_attn_step_static(const void *Q, const void *K, const void *V, const
     void *ws = g_scratch_ptr[cx.dev];
 #define SKA_STEP(TT_, DD_)                                                                              \
     do {                                                                                                \
-        rc = fwd_impl<TT_, DD_>(cx, p, Q, K, V, O, UV, ws, true);                                       \
+        rc = fwd_impl<TT_, DD_>(cx, p, Q, K, V, O, UV, ws, true, dO);                                   \
         if (rc == SKA_OK)                                                                               \
             rc = bwd_impl<TT_, DD_>(cx, p, Q, K, V, O, dO, UV, dQ, dK, dV, eta0, ws, nullptr, true);    \
         return rc;                                                                                      \

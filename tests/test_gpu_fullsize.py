@@ -7,7 +7,9 @@ therefore run on windows of the sequence (a window's own ends behave like
 sequence ends, which is exact when the window touches a real end) and compared
 on the window's centre, element by element, with the GPU result of the whole
 problem.  The dustbin couples all positions through its extra row and column, so
-that configuration is compared on whole problems instead.
+that configuration is compared on whole problems instead.  Where the oracle is cheap the
+comparison is not sampled at all: every problem of the Mid, Dustbin and Long configurations and
+both heads of the benchmark workload are compared whole, each of O, dQ, dK, dV by itself.
 """
 import sys
 
@@ -16,6 +18,7 @@ import pytest
 
 import oracle
 from paper_2605_08123_amd.workloads import CONFIGS, make_inputs
+from tests.measures import assert_per_tensor, floors
 from tests.test_gpu_parity import TOL, run_gpu
 
 pytestmark = pytest.mark.gpu
@@ -39,7 +42,28 @@ def window_check(w, got, arrays, b, h, c0, c1):
         assert e <= TOL[w.dtype], (name, e)
 
 
-@pytest.mark.parametrize("name", ["paper", "long", "paper_w1024"])
+def whole_problems(w, dustbin=False):
+    """Every (batch, head) problem of the configuration, whole, against the oracle."""
+    arrays = make_inputs(w)
+    got = run_gpu(w, arrays, one_call=True)   # the one-call step is what bench.py times
+    worst = {}
+    for b in range(w.B):
+        for h in range(w.H):
+            q, k, v, g = (x[b, h] for x in arrays)
+            ref = oracle.band(q, k, v, g, w.W, w.T, w.R, w.eps, dustbin, w.dustbin_score)
+            res = assert_per_tensor({n: got[n][b, h] for n in ("O", "dQ", "dK", "dV")}, ref, w.dtype,
+                                    floors(w.dtype, q, k, v, g, ref["O"], w.eps), where=f"{w.name} ({b},{h})")
+            for n, r in res.items():
+                assert r[2] <= TOL[w.dtype], (b, h, n, r[2])   # nothing cancels here: the relative bar itself
+                worst[n] = max(worst.get(n, 0.0), r[2])
+            for t in range(w.R + 1):
+                s_got = got["UV"][b, h, 2 * t] + got["UV"][b, h, 2 * t + 1]
+                s_ref = ref["UV"][2 * t] + ref["UV"][2 * t + 1]
+                assert np.abs(s_got - s_ref).max() < 2e-2, (b, h, t)
+    print(f"   worst rel-L2 over {w.B * w.H} whole problems:", {n: f"{e:.2e}" for n, e in worst.items()}, flush=True)
+
+
+@pytest.mark.parametrize("name", ["paper", "paper_w1024"])
 def test_full_size_windows(name):
     w = CONFIGS[name]
     print(f"\n[case] {w}", flush=True)
@@ -64,33 +88,24 @@ def test_full_size_windows(name):
 
 
 def test_dustbin_config_full_size():
-    """Dustbin configuration at its full size; the oracle checks two of the eight problems."""
+    """Dustbin configuration at its full size, all eight problems whole."""
     w = CONFIGS["dustbin"]
     print(f"\n[case] {w}", flush=True)
-    arrays = make_inputs(w)
-    got = run_gpu(w, arrays)
-    for (b, h) in ((0, 0), (1, 3)):
-        q, k, v, g = (x[b, h] for x in arrays)
-        ref = oracle.band(q, k, v, g, w.W, w.T, w.R, w.eps, True, w.dustbin_score)
-        errs = {n: float(np.linalg.norm(got[n][b, h] - ref[n]) / np.linalg.norm(ref[n]))
-                for n in ("O", "dQ", "dK", "dV")}
-        print(f"   ({b},{h}):", {k: f"{e:.2e}" for k, e in errs.items()}, flush=True)
-        for n, e in errs.items():
-            assert e <= TOL[w.dtype], (n, e)
+    whole_problems(w, dustbin=True)
 
 
 def test_mid_config_full_size():
-    """Mid configuration, all 32 problems on the GPU; the oracle checks four of them."""
+    """Mid configuration at its full size, all 32 problems whole."""
     w = CONFIGS["mid"]
     print(f"\n[case] {w}", flush=True)
-    arrays = make_inputs(w)
-    got = run_gpu(w, arrays)
-    for (b, h) in ((0, 0), (1, 5), (2, 2), (3, 7)):
-        q, k, v, g = (x[b, h] for x in arrays)
-        ref = oracle.band(q, k, v, g, w.W, w.T, w.R, w.eps)
-        for n in ("O", "dQ", "dK", "dV"):
-            e = float(np.linalg.norm(got[n][b, h] - ref[n]) / np.linalg.norm(ref[n]))
-            assert e <= TOL[w.dtype], (b, h, n, e)
+    whole_problems(w)
+
+
+def test_long_config_full_size():
+    """Long configuration at its full size, all four heads whole."""
+    w = CONFIGS["long"]
+    print(f"\n[case] {w}", flush=True)
+    whole_problems(w)
 
 
 def test_full_size_padded_lengths():
@@ -164,35 +179,22 @@ def test_dustbin_config_with_learned_tokens():
     b, h = 1, 2
     q, k, v, g = (x[b, h] for x in arrays)
     ref = oracle.band_dustbin_token(q, k, v, g, toks[0][b, h], toks[1][b, h], toks[2][b, h], w.W, w.T, w.R, w.eps)
-    errs = {n: float(np.linalg.norm(got[n][b, h] - ref[n]) / np.linalg.norm(ref[n])) for n in got}
-    print(f"   ({b},{h}):", {n: f"{e:.2e}" for n, e in errs.items()}, flush=True)
-    for n in ("O", "dQ", "dK", "dV"):
-        assert np.isfinite(got[n]).all() and errs[n] <= TOL[w.dtype], (n, errs[n])
-    # a token's gradient is one d-vector summed over all L spokes with heavy cancellation (here
-    # |dq_db| is 0.8 against 3.5 and 3.2 for the other two), so the three are measured together
-    tok = ("dq_db", "dk_db", "dv_db")
-    num = np.sqrt(sum(np.linalg.norm(got[n][b, h] - ref[n]) ** 2 for n in tok))
-    den = np.sqrt(sum(np.linalg.norm(ref[n]) ** 2 for n in tok))
-    assert all(np.isfinite(got[n]).all() for n in tok) and num / den <= TOL[w.dtype], num / den
+    # every tensor by itself.  A token's gradient is one d-vector summed over all L spokes with
+    # heavy cancellation (here |dq_db| is 0.8 against 3.5 and 3.2 for the other two): the rounding
+    # floor of tests/measures.py is what bounds it, and the print says when it is used
+    res = assert_per_tensor({n: got[n][b, h] for n in got}, ref, w.dtype,
+                            floors(w.dtype, q, k, v, g, ref["O"], w.eps), tuple(got), where=f"dustbin tokens ({b},{h})")
+    print(f"   ({b},{h}):", {n: f"{r[2]:.2e}" for n, r in res.items()}, flush=True)
+    for n in ("O", "dQ", "dK", "dV", "dk_db", "dv_db"):
+        assert res[n][2] <= TOL[w.dtype], (n, res[n][2])
 
 
-def test_paper_scale_one_full_head():
-    """One whole head of the benchmark workload (262144 tokens) against the oracle run on the
-    whole head: rel-L2 over the full tensors, no windows (about half a minute of CPU)."""
+def test_paper_scale_full_heads():
+    """Both heads of the benchmark workload (262144 tokens each) against the oracle run on the
+    whole head: rel-L2 over the full tensors, no windows (about a minute of CPU)."""
     w = CONFIGS["paper"]
-    print(f"\n[case] {w}: full head 0 against the oracle", flush=True)
-    arrays = make_inputs(w)
-    got = run_gpu(w, arrays)
-    q, k, v, g = (x[0, 0] for x in arrays)
-    ref = oracle.band(q, k, v, g, w.W, w.T, w.R, w.eps)
-    errs = {n: float(np.linalg.norm(got[n][0, 0] - ref[n]) / np.linalg.norm(ref[n])) for n in ("O", "dQ", "dK", "dV")}
-    print("   rel-L2 over the whole head:", {n: f"{e:.2e}" for n, e in errs.items()}, flush=True)
-    for n, e in errs.items():
-        assert e <= TOL[w.dtype], (n, e)
-    for t in range(w.R + 1):
-        s_got = got["UV"][0, 0, 2 * t] + got["UV"][0, 0, 2 * t + 1]
-        s_ref = ref["UV"][2 * t] + ref["UV"][2 * t + 1]
-        assert np.abs(s_got - s_ref).max() < 2e-2, t
+    print(f"\n[case] {w}: both heads whole against the oracle", flush=True)
+    whole_problems(w)
 
 
 def test_four_million_tokens():

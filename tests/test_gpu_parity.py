@@ -9,6 +9,7 @@ import pytest
 
 import oracle
 from paper_2605_08123_amd.workloads import CONFIGS, Workload, make_inputs
+from tests.measures import assert_per_tensor, floors
 
 pytestmark = pytest.mark.gpu
 
@@ -30,16 +31,21 @@ def rel(a, b):
     return float(np.linalg.norm(a - b) / max(np.linalg.norm(b), 1e-300))
 
 
-def run_gpu(w: Workload, arrays, want_eta0=False):
+def run_gpu(w: Workload, arrays, want_eta0=False, one_call=False):
+    """Forward then backward (two calls), or the one-call step the benchmark times."""
     import torch
 
     import paper_2605_08123_amd as ska
     dev = torch.device("cuda:0")
     td = torch.float32 if w.dtype == "f32" else torch.bfloat16
     Q, K, V, G = (torch.from_numpy(x).to(dev).to(td) for x in arrays)
-    O, UV = ska.sinkhorn_attn_fwd(Q, K, V, w.W, w.T, w.R, w.eps, w.dustbin, w.dustbin_score)
-    res = ska.sinkhorn_attn_bwd(Q, K, V, O, G, UV, w.W, w.T, w.R, w.eps, w.dustbin, w.dustbin_score,
-                                want_eta0=want_eta0)
+    if one_call:
+        O, UV, *res = ska.sinkhorn_attn_step(Q, K, V, G, w.W, w.T, w.R, w.eps, w.dustbin, w.dustbin_score,
+                                             want_eta0=want_eta0)
+    else:
+        O, UV = ska.sinkhorn_attn_fwd(Q, K, V, w.W, w.T, w.R, w.eps, w.dustbin, w.dustbin_score)
+        res = ska.sinkhorn_attn_bwd(Q, K, V, O, G, UV, w.W, w.T, w.R, w.eps, w.dustbin, w.dustbin_score,
+                                    want_eta0=want_eta0)
     torch.cuda.synchronize()
     out = dict(O=O, UV=UV, dQ=res[0], dK=res[1], dV=res[2])
     if want_eta0:
@@ -53,14 +59,10 @@ def check(w: Workload, seed=None, want_eta0=False, uv_atol=None):
     arrays = make_inputs(w, seed)
     got = run_gpu(w, arrays, want_eta0)
     ref = oracle.band_batched(*arrays, w.W, w.T, w.R, w.eps, w.dustbin, w.dustbin_score)
-    tol = TOL[w.dtype]
-    # a reference that is identically zero (W = 0 gives dQ = dK = 0) is measured
-    # against the size of the other gradients instead of its own norm
-    big = max(np.linalg.norm(ref[k]) for k in ("O", "dQ", "dK", "dV"))
-    den = {k: (np.linalg.norm(ref[k]) if np.linalg.norm(ref[k]) > 1e-9 * big else big)
-           for k in ("O", "dQ", "dK", "dV")}
-    errs = {k: float(np.linalg.norm(got[k] - ref[k]) / den[k]) for k in den}
-    print("   rel-L2:", {k: f"{v:.2e}" for k, v in errs.items()}, flush=True)
+    # every tensor by itself; where the reference vanishes by cancellation (W = 0 gives
+    # dQ = dK = 0) the rounding floor of tests/measures.py takes over from the relative bar
+    res = assert_per_tensor(got, ref, w.dtype, floors(w.dtype, *arrays, ref["O"], w.eps), where=w.name)
+    print("   rel-L2:", {k: f"{r[2]:.2e}" for k, r in res.items()}, flush=True)
     # potentials: both sides iterate the same ungauged map from v = 0, so the raw
     # vectors agree; compared through the gauge-free sums u^(t) + v^(t)
     # (bf16 storage: the score scale is folded into a bf16 copy of Q, which perturbs every
@@ -70,9 +72,6 @@ def check(w: Workload, seed=None, want_eta0=False, uv_atol=None):
         s_got = got["UV"][:, :, 2 * t] + got["UV"][:, :, 2 * t + 1]
         s_ref = ref["UV"][:, :, 2 * t] + ref["UV"][:, :, 2 * t + 1]
         assert np.abs(s_got - s_ref).max() < uv_atol, (t, np.abs(s_got - s_ref).max())
-    for k, e in errs.items():
-        assert np.isfinite(got[k]).all(), k
-        assert e <= tol, (k, e)
     return got, ref
 
 
@@ -103,7 +102,8 @@ def test_fp32_w0_is_identity():
     got, _ = check(w, seed=3)
     _, _, v, g = make_inputs(w, 3)
     assert np.abs(got["O"] - v).max() < 1e-5 and np.abs(got["dV"] - g).max() < 1e-5
-    assert np.abs(got["dQ"]).max() < 1e-4 and np.abs(got["dK"]).max() < 1e-4
+    # dQ = dK = 0 exactly; what the kernels return is bounded by the rounding floor inside check()
+    # (8 * 2^-24 * c * |(|dO_i| |O_i|)_i| * max|K_j|, Frobenius norm over the whole tensor)
 
 
 @pytest.mark.parametrize("L,d,W,T,eps", [
@@ -535,7 +535,9 @@ def test_degenerate_lengths_and_masks(dtype, d):
                                           ("f32", 64, "marginals"), ("bf16", 128, "varlen")])
 def test_step_is_forward_then_backward(dtype, d, kind):
     """The one-call step (forward + backward for a given cotangent) gives the results of the two
-    separate calls bit for bit."""
+    separate calls: O, UV, dV bit for bit; dQ, dK, eta0 bit for bit with the dustbin and to rounding
+    without it (the step takes g_u = <dO, O> from the output map's fp32 accumulators, the backward
+    call from the stored O)."""
     import torch
 
     import paper_2605_08123_amd as ska
@@ -560,7 +562,11 @@ def test_step_is_forward_then_backward(dtype, d, kind):
     torch.cuda.synchronize()
     assert torch.equal(O, O0) and torch.equal(UV, UV0)
     for name, x, y in zip(("dQ", "dK", "dV", "eta0"), (dQ, dK, dV, eta), g0):
-        assert torch.equal(x, y), name
+        if db or name == "dV":
+            assert torch.equal(x, y), name
+        else:
+            num, den = (x.float() - y.float()).norm().item(), y.float().norm().item()
+            assert num <= (1e-5 if dtype == "f32" else 1e-2) * den, (name, num / den)
 
 
 def test_caller_streams_and_ordering():

@@ -2,29 +2,22 @@
 depth, batch, heads, storage type, eps and the dustbin drawn at random (fixed seeds, so the
 cases are the same on every run), each against the fp64 CPU oracle.  The hand-picked cases of
 test_gpu_parity.py sit on the tile boundaries; these fill the space between them.  The same
-tolerances: rel-L2 <= 1e-4 (fp32 storage), <= 2e-2 (bf16 storage).
-
-Measures: O and dV by their own norms; dQ and dK jointly (one norm over both), because a
-configuration can leave one of them tiny next to the other.  Configurations whose score
-gradient vanishes identically (window 0, a single query or key) are not drawn: they have
-dedicated cases in test_gpu_parity.py.
+tolerances: rel-L2 <= 1e-4 (fp32 storage), <= 2e-2 (bf16 storage), asserted for each of O, dQ,
+dK, dV (and each token gradient) by itself.  The draw includes the supports on which the score
+gradient cancels structurally (window 0, 1-wide windows under heavy masks, items with a single
+query or key); there, and only there, the rounding floor of tests/measures.py takes over from
+the relative bar.
 """
 import numpy as np
 import pytest
 
 import oracle
 from paper_2605_08123_amd.workloads import Workload, make_inputs
+from tests.measures import assert_per_tensor, floors, worst_ratio
 
 pytestmark = pytest.mark.gpu
 
-TOL = {"f32": 1e-4, "bf16": 2e-2}
-WINDOWS = [1, 5, 31, 32, 33, 64, 100, 255, 256, 300, 2000]
-
-
-def joint(got, ref, keys):
-    num = sum(np.linalg.norm(got[k] - ref[k]) ** 2 for k in keys) ** 0.5
-    den = sum(np.linalg.norm(ref[k]) ** 2 for k in keys) ** 0.5
-    return float(num / max(den, 1e-300))
+WINDOWS = [0, 1, 5, 31, 32, 33, 64, 100, 255, 256, 300, 2000]
 
 
 def draw(rng, lo=8, hi=1400):
@@ -47,8 +40,11 @@ def to_np(**kw):
     return {n: x.float().cpu().numpy().astype(np.float64) for n, x in kw.items()}
 
 
-def worst_of(got, ref):
-    return max(joint(got, ref, ["O"]), joint(got, ref, ["dV"]), joint(got, ref, ["dQ", "dK"]))
+def measure(got, ref, c, eps, q, k, v, g, where, names=("O", "dQ", "dK", "dV")):
+    """Every tensor by itself against max(tol |ref|, rounding floor); returns the worst error / bound."""
+    fl = floors(c["dtype"], q, k, v, g, ref["O"], eps)
+    res = assert_per_tensor(got, ref, c["dtype"], fl, names, where)
+    return worst_ratio(res), res
 
 
 @pytest.mark.parametrize("split", [False, True])
@@ -60,6 +56,8 @@ def test_random_step(case, split):
     import paper_2605_08123_amd as ska
     rng = np.random.default_rng(9100 + case)
     c = draw(rng)
+    if case % 8 == 7:
+        c["L"] = int(rng.integers(1, 5))   # every eighth case is a handful of tokens
     db = bool(rng.integers(4) == 0)
     score = float(rng.normal()) * 0.3
     w = Workload("random", 7, c["B"], c["H"], c["L"], c["d"], c["W"], c["T"], c["R"], c["eps"], c["dtype"],
@@ -74,9 +72,8 @@ def test_random_step(case, split):
         ska.sinkhorn_attn_set_split_min_edges(5e7)
     got = to_np(O=O, dQ=dQ, dK=dK, dV=dV)
     ref = oracle.band_batched(*rounded, w.W, w.T, w.R, w.eps, db, score)
-    e = worst_of(got, ref)
-    print(f"   worst rel-L2 {e:.2e}", flush=True)
-    assert all(np.isfinite(x).all() for x in got.values()) and e <= TOL[c["dtype"]], e
+    e, res = measure(got, ref, c, w.eps, *rounded, where=str(w))
+    print("   rel-L2 " + " ".join(f"{n} {r[2]:.2e}" for n, r in res.items()) + f"; worst error/bound {e:.2f}", flush=True)
 
 
 @pytest.mark.parametrize("case", range(10))
@@ -94,6 +91,8 @@ def test_random_lengths(case):
     lk = rng.integers(8, L + 1, size=B).astype(np.int32)
     if case % 5 == 0:
         (lq if case % 2 else lk)[0] = 0
+    if case % 5 == 1:
+        (lq if case % 2 else lk)[B - 1] = 1   # an item with a single query or a single key
     print(f"\n[case] {w} lengths q={lq.tolist()} k={lk.tolist()}", flush=True)
     (Q, K, V, G), (q, k, v, g) = on_device(c, make_inputs(w, 9400 + case))
     tq, tk = (torch.from_numpy(x).to(Q.device) for x in (lq, lk))
@@ -111,18 +110,17 @@ def test_random_lengths(case):
                 continue
             ref = oracle.band_rect(q[b, h, :a], k[b, h, :n], v[b, h, :n], g[b, h, :a], w.W, w.T, w.R, w.eps)
             mine = dict(O=got["O"][b, h, :a], dQ=got["dQ"][b, h, :a], dK=got["dK"][b, h, :n], dV=got["dV"][b, h, :n])
-            worst = max(worst, worst_of(mine, ref))
+            worst = max(worst, measure(mine, ref, c, w.eps, q[b, h, :a], k[b, h, :n], v[b, h, :n], g[b, h, :a],
+                                       where=f"{w} item {b} head {h}")[0])
             assert np.all(got["O"][b, h, a:] == 0.0) and np.all(got["dK"][b, h, n:] == 0.0)
-    print(f"   worst rel-L2 {worst:.2e}", flush=True)
-    assert worst <= TOL[c["dtype"]], worst
+    print(f"   worst error/bound {worst:.2f}", flush=True)
 
 
 @pytest.mark.parametrize("case", range(10))
 def test_random_masks(case):
-    """Independent random activity masks at 5 %, 30 % or 70 % inactive tokens.  At 70 % the
-    window is at least 31: in a narrower one most active rows keep a single partner, whose plan
-    entry the marginal fixes, so the score gradient nearly cancels and its relative error
-    measures the cancellation, not the kernels."""
+    """Independent random activity masks at 5 %, 30 % or 70 % inactive tokens, any window (in a
+    1-wide window under a 70 % mask most active rows keep a single partner, whose plan entry the
+    marginal fixes: the score gradient nearly cancels there and the rounding floor applies)."""
     import torch
 
     import paper_2605_08123_amd as ska
@@ -131,8 +129,8 @@ def test_random_masks(case):
     B, H, L = c["B"], c["H"], c["L"]
     w = Workload("random", 7, B, H, L, c["d"], c["W"], c["T"], c["R"], c["eps"], c["dtype"])
     p = float(rng.choice([0.05, 0.3, 0.7]))
-    W = max(c["W"], 31) if p == 0.7 else c["W"]
-    w = Workload("random", 7, B, H, L, c["d"], W, c["T"], c["R"], c["eps"], c["dtype"])
+    if case >= 8:   # the two last cases: a 1-wide window under the heaviest mask
+        p, w = 0.7, Workload("random", 7, B, H, L, c["d"], 1, c["T"], c["R"], c["eps"], c["dtype"])
     mq, mk = rng.random((B, L)) > p, rng.random((B, L)) > p
     print(f"\n[case] {w} inactive fraction {p}", flush=True)
     (Q, K, V, G), (q, k, v, g) = on_device(c, make_inputs(w, 9600 + case))
@@ -147,15 +145,14 @@ def test_random_masks(case):
     for b in range(B):
         for h in range(H):
             ref = oracle.band_masked(q[b, h], k[b, h], v[b, h], g[b, h], mq[b], mk[b], w.W, w.T, w.R, w.eps)
-            worst = max(worst, worst_of({m: got[m][b, h] for m in got}, ref))
-    print(f"   worst rel-L2 {worst:.2e}", flush=True)
-    assert worst <= TOL[c["dtype"]], worst
+            worst = max(worst, measure({m: got[m][b, h] for m in got}, ref, c, w.eps, q[b, h], k[b, h], v[b, h],
+                                       g[b, h], where=f"{w} item {b} head {h}")[0])
+    print(f"   worst error/bound {worst:.2f}", flush=True)
 
 
 @pytest.mark.parametrize("case", range(8))
 def test_random_learned_tokens(case):
-    """Learned dustbin token per side: the six gradients, those of the tokens measured jointly
-    with the ordinary ones of the same kind."""
+    """Learned dustbin token per side: the six gradients, each by itself."""
     import torch
 
     import paper_2605_08123_amd as ska
@@ -178,7 +175,7 @@ def test_random_learned_tokens(case):
             ref = oracle.band_dustbin_token(q[b, h], k[b, h], v[b, h], g[b, h], toks[0][b, h], toks[1][b, h],
                                             toks[2][b, h], w.W, w.T, w.R, w.eps)
             mine = {m: got[m][b, h] for m in got}
-            worst = max(worst, joint(mine, ref, ["O"]), joint(mine, ref, ["dV", "dv_db"]),
-                        joint(mine, ref, ["dQ", "dK", "dq_db", "dk_db"]))
-    print(f"   worst rel-L2 {worst:.2e}", flush=True)
-    assert worst <= TOL[c["dtype"]], worst
+            worst = max(worst, measure(mine, ref, c, w.eps, q[b, h], k[b, h], v[b, h], g[b, h],
+                                       where=f"{w} item {b} head {h}",
+                                       names=("O", "dQ", "dK", "dV", "dq_db", "dk_db", "dv_db"))[0])
+    print(f"   worst error/bound {worst:.2f}", flush=True)
