@@ -98,6 +98,13 @@ def main() -> int:
     ap.add_argument("--separate-calls", action="store_true",
                     help="a step as two library calls (sinkhorn_attn_fwd, then the backward) instead of the "
                          "one-call step")
+    ap.add_argument("--graph", action="store_true",
+                    help="capture one step into a HIP graph and time its replays (the small workloads, whose "
+                         "~50 launches of 10-20 us each are bound by the host's enqueue rate otherwise); the "
+                         "scaling sweep is then timed in a short eager pass of its own")
+    ap.add_argument("--fused", type=int, default=0, choices=[0, 1, 2],
+                    help="fused half-steps (sinkhorn_attn_set_fused_half_steps): 1 the tail's 2R half-steps in one "
+                         "launch, 2 all half-steps after the first in one launch")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-tokens", type=int, default=262144)
     ap.add_argument("--calibrate-copy", action="store_true",
@@ -129,6 +136,7 @@ def main() -> int:
     wsp = torch.empty(wsb, device=dev, dtype=torch.uint8)
 
     ska.sinkhorn_attn_set_streams(args.streams)
+    ska.sinkhorn_attn_set_fused_half_steps(args.fused)
     variant = {"one_reference": 0, "direct": 1, "one_reference_generic": 2}[args.backward]
 
     def step():
@@ -150,12 +158,36 @@ def main() -> int:
     for _ in range(args.warmup):
         step()
     torch.cuda.synchronize()
-    ska.sinkhorn_attn_profile_enable(1)
-    t0 = time.perf_counter()
-    for _ in range(args.steps):
-        step()
-    torch.cuda.synchronize()
-    dt = time.perf_counter() - t0
+    if args.graph:
+        side = torch.cuda.Stream()
+        side.wait_stream(torch.cuda.current_stream())
+        with torch.cuda.stream(side):
+            step()                              # warm-up on the capture stream
+        torch.cuda.current_stream().wait_stream(side)
+        graph = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(graph, stream=side):
+            step()
+        graph.replay()
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for _ in range(args.steps):
+            graph.replay()
+        torch.cuda.synchronize()
+        dt = time.perf_counter() - t0
+        # the sweep's launch time: HIP events cannot sit inside a replayed graph, so a few eager steps
+        ska.sinkhorn_attn_profile_enable(1)
+        for _ in range(min(args.steps, 3)):
+            step()
+        torch.cuda.synchronize()
+    else:
+        # level 1: two events per forward call around its run of identical scaling sweeps, on the
+        # streams the sweeps run on; the schedule of the call is unchanged
+        ska.sinkhorn_attn_profile_enable(1)
+        t0 = time.perf_counter()
+        for _ in range(args.steps):
+            step()
+        torch.cuda.synchronize()
+        dt = time.perf_counter() - t0
     ska.sinkhorn_attn_profile_enable(0)
     sweep_ms, launches = ska.sinkhorn_attn_profile_read()
     # per-phase times from a short pass of their own (two events per phase are too many to
@@ -188,11 +220,16 @@ def main() -> int:
     tokens_per_s = w.B * w.L * args.steps / dt
     avg_s = 1e-3 * sweep_ms / max(launches, 1)
     achieved = algorithmic_bytes_per_sweep(w) / avg_s / 1e9
-    traffic = None
+    # HBM bytes per sweep beyond L2: not measurable from inside this process (rocprofv3 --pmc reads
+    # FETCH_SIZE / WRITE_SIZE in runs of their own); the stored reading of those runs, with its source
+    traffic, traffic_source = None, None
     tpath = os.path.join(ROOT, "profiles", f"lse_sweep_{w.name}_traffic.json")
     if os.path.exists(tpath):
         with open(tpath) as f:
-            traffic = json.load(f).get("hbm_bytes_per_launch")
+            tj = json.load(f)
+        traffic = tj.get("hbm_bytes_per_launch")
+        traffic_source = (f"stored reading, profiles/lse_sweep_{w.name}_traffic.json (rocprofv3 --pmc FETCH_SIZE, "
+                          f"WRITE_SIZE on build {tj.get('build', 'unrecorded')}); not re-measured in this run")
     dt_name = "bf16" if w.dtype == "bf16" else "f32"
     E = edges(w)
     model = phase_model(w)
@@ -213,13 +250,14 @@ def main() -> int:
         "dtype": dt_name, "data": "synthetic",
         "config": {"workload": w.name, "B": w.B, "H": w.H, "L": w.L, "d": w.d, "W": w.W, "T": w.T,
                    "R": w.R, "eps": w.eps, "dustbin": w.dustbin, "backward": args.backward,
-                   "streams": args.streams, "calls_per_step": 2 if (args.separate_calls or variant) else 1},
+                   "streams": args.streams, "calls_per_step": 2 if (args.separate_calls or variant) else 1,
+                   "graph_replay": bool(args.graph), "fused_half_steps": args.fused},
         # the scaling sweep against its three ceilings; the one that binds (the largest lower bound on
-        # a launch's time: 20.5 us ALU, 17.3 us HBM, 13.8 us MFMA at this workload) is the plain-ALU
+        # a launch's time: 17.1 us ALU, 17.3 us HBM, 13.8 us MFMA at the paper workload) is the plain-ALU
         # issue rate of one exp2 and one add per band edge
         "roofline": {"kernel": "scaling sweep (row/column half-step, Eq. 1-2)", "bound": "alu",
                      "achieved": alu_tflops, "peak": ALU_PEAK_TFLOPS, "unit": "TFLOP/s",
-                     "frac": alu_tflops / ALU_PEAK_TFLOPS, "traffic": traffic,
+                     "frac": alu_tflops / ALU_PEAK_TFLOPS, "traffic": traffic, "traffic_source": traffic_source,
                      "flops": "one exp2 + one add per band edge; v_exp_f32 issues at quarter rate",
                      "launches_timed": launches, "avg_launch_us": 1e6 * avg_s,
                      "hbm": {"achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",

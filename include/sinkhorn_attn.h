@@ -71,7 +71,8 @@ typedef enum {
 /*
  * Bytes of device scratch that sinkhorn_attn_bwd needs for these sizes; the
  * forward is content with the same buffer (it needs B*H*L*d*2 bytes for bf16
- * storage, none for fp32).  Host-only, no GPU call.  Returns 0 on invalid sizes.
+ * storage, none for fp32; with all of it, it can fuse half-steps, see
+ * sinkhorn_attn_set_fused_half_steps).  Host-only, no GPU call.  Returns 0 on invalid sizes.
  */
 size_t sinkhorn_attn_workspace_bytes(int B, int H, int L, int d, int W, int T, int R, int dustbin,
                                      int dtype);
@@ -355,6 +356,29 @@ int sinkhorn_attn_bwd_variant(int variant, const void *Q, const void *K, const v
  * top) or 1.  Process-wide.  Returns SKA_OK, or SKA_EINVAL for any other number.
  */
 int sinkhorn_attn_set_streams(int n);
+/*
+ * Fused half-steps (Sec. 2.2: the differentiable tail; App. "Algorithm Sketch": the tail line).
+ * mode 0 (default): every half-step of Eq. 1-2 is a launch of its own.  mode 1: the 2R half-steps
+ * of the tail run as ONE launch.  mode 2: all half-steps after the first one (base solve and
+ * tail) run as one launch.  Inside such a launch the blocks of consecutive half-steps are chained
+ * by per-block counters instead of kernel boundaries (a block starts half-step h when the blocks
+ * within the band's reach have finished h - 1), the workgroups being co-resident (cooperative
+ * launch); the arithmetic per block is that of the separate launches, so results are identical
+ * bit for bit.  It trades the launch-to-launch latency and the ramp of every launch for a
+ * counter hand-over between neighbouring blocks through memory that all XCDs see; on MI355X the
+ * two cost about the same (measured: a half-step takes 16 us fused against 13 us in launches of
+ * its own at B*H*L = 131072, 60 us against 59 us at 524288 on one stream), so the default is 0.
+ *   It applies to forward calls (and the forward half of sinkhorn_attn_step) without a dustbin and
+ * without a continuation schedule, outside stream capture, whose workspace has
+ * sinkhorn_attn_workspace_bytes() bytes (the counters live at its end); other calls run unfused.
+ * The fused launch takes all problems on the caller's stream.  At most one call with fused
+ * half-steps may be in flight on a device at a time (two such launches can hold each other's
+ * workgroups out).  Every wait inside the launch is bounded by spin_limit polls (0: the default,
+ * 2^18, about a tenth of a second): a wait that runs out stops waiting and writes NaN into its block of the
+ * potentials, which reaches every output depending on it, and the launch ends normally.
+ * Process-wide.  Returns SKA_OK, or SKA_EINVAL for another mode.
+ */
+int sinkhorn_attn_set_fused_half_steps(int mode, unsigned spin_limit);
 /*
  * The least number of band edges per dispatch (half of a call's problems times L times 2W + 1)
  * from which a call uses the helper stream; default 5e7.  0 makes every call on two or more

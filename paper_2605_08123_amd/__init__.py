@@ -9,6 +9,6 @@ from .binding import (SinkhornAttnError, sinkhorn_attn_base_vjp, sinkhorn_attn_b
                       sinkhorn_attn_fwd_eps_schedule, sinkhorn_attn_fwd_masked, sinkhorn_attn_fwd_varlen,
                       sinkhorn_attn_probe_issue, sinkhorn_attn_profile_enable, sinkhorn_attn_profile_read,
                       sinkhorn_attn_profile_read_phases,
-                      sinkhorn_attn_select_tail_depth, sinkhorn_attn_select_workspace_bytes, sinkhorn_attn_set_split_min_edges, sinkhorn_attn_set_streams, sinkhorn_attn_step,
+                      sinkhorn_attn_select_tail_depth, sinkhorn_attn_select_workspace_bytes, sinkhorn_attn_set_fused_half_steps, sinkhorn_attn_set_split_min_edges, sinkhorn_attn_set_streams, sinkhorn_attn_step,
                       sinkhorn_attn_step_static,
                       sinkhorn_attn_strerror, sinkhorn_attn_workspace_bytes)

@@ -72,6 +72,8 @@ def load():
         lib.sinkhorn_attn_probe_issue.argtypes = [vp, sz, i, i, ctypes.POINTER(ctypes.c_double), vp]
         lib.sinkhorn_attn_set_streams.restype = i
         lib.sinkhorn_attn_set_streams.argtypes = [i]
+        lib.sinkhorn_attn_set_fused_half_steps.restype = i
+        lib.sinkhorn_attn_set_fused_half_steps.argtypes = [i, ctypes.c_uint]
         lib.sinkhorn_attn_set_split_min_edges.restype = i
         lib.sinkhorn_attn_set_split_min_edges.argtypes = [ctypes.c_double]
         lib.sinkhorn_attn_step.restype = i
@@ -119,6 +121,14 @@ def sinkhorn_attn_set_streams(n: int) -> None:
     """2 (default): a call on several problems runs half of its sweeps on the library's helper
     stream; 1: everything on the caller's stream."""
     rc = load().sinkhorn_attn_set_streams(int(n))
+    if rc != SKA_OK:
+        raise SinkhornAttnError(rc)
+
+
+def sinkhorn_attn_set_fused_half_steps(mode: int, spin_limit: int = 0) -> None:
+    """0 (default): one launch per half-step; 1: the tail's 2R half-steps in one launch; 2: all
+    half-steps after the first in one launch.  spin_limit bounds the waits inside it (0: default)."""
+    rc = load().sinkhorn_attn_set_fused_half_steps(int(mode), int(spin_limit))
     if rc != SKA_OK:
         raise SinkhornAttnError(rc)
 

@@ -55,6 +55,7 @@ struct Problem {
     const float *q_db = nullptr, *k_db = nullptr, *v_db = nullptr;   // learned dustbin tokens [N][d] fp32, or null
     float *dq_db = nullptr, *dk_db = nullptr, *dv_db = nullptr;      //   and their gradients (backward)
     bool token() const { return q_db != nullptr; }
+    size_t ws_given = 0;                              // bytes of the caller's workspace (forward: room for the chain's counters?)
     int n_stages = 0;                                 // forward: continuation schedule of the base solve
     const float *eps_stage = nullptr;                 //   (host arrays; 0 stages: T steps at eps)
     const int *T_stage = nullptr;
@@ -85,7 +86,10 @@ size_t ws_tok_bytes(const Problem &p)
 {
     return p.dustbin ? ((size_t)4 * p.N() * p.ldw() + (size_t)p.N() * ws_chunks(p) * p.d) * sizeof(float) : 0;
 }
-size_t ws_bytes(const Problem &p) { return ws_vec_bytes(p) + ws_qs_bytes(p) + ws_tok_bytes(p); }
+// counters of a fused chain of half-steps (one int per block of 128 owner rows, the smallest block)
+size_t ws_chain_bytes(const Problem &p) { return ((size_t)p.N() * ((p.L + 127) / 128) * sizeof(int) + 255) / 256 * 256; }
+size_t ws_core_bytes(const Problem &p) { return (ws_vec_bytes(p) + ws_qs_bytes(p) + ws_tok_bytes(p) + 255) / 256 * 256; }
+size_t ws_bytes(const Problem &p) { return ws_core_bytes(p) + ws_chain_bytes(p); }
 inline float *ws_tok(const Problem &p, void *ws)
 {
     return reinterpret_cast<float *>(reinterpret_cast<unsigned char *>(ws) + ws_vec_bytes(p) + ws_qs_bytes(p));
@@ -261,6 +265,9 @@ struct Side {
 std::mutex g_mutex;
 Side g_side[MAX_DEVICES];
 int g_streams = 2;            // sinkhorn_attn_set_streams: 1 = everything on the caller's stream
+int g_fuse = 0;               // sinkhorn_attn_set_fused_half_steps: 0 off, 1 the tail, 2 all but the first half-step
+unsigned g_spin_limit = 1u << 18;   // polls of a chain's wait before it gives up (a poll is a few hundred cycles: about 0.1 s)
+int g_chain_cap[MAX_DEVICES][8];    // workgroups of a chain kernel the device holds at once (0: not asked yet)
 double g_split_min_edges = 50e6;   // sinkhorn_attn_set_split_min_edges
 
 Side *side_for_device(int dev)   // (g_mutex held)
@@ -319,6 +326,40 @@ struct Call {
         return SKA_OK;
     }
 };
+
+// A chain of half-steps in one cooperative launch (vchain_kernel); returns SKA_EUNSUPPORTED if the
+// device cannot hold a useful grid, so that the caller launches the half-steps one by one instead.
+template <typename T, int D, int FR> int launch_vchain(ChainArgs &c, int N, hipStream_t st, int dev, int slot)
+{
+    constexpr int BM = NWAVES * FR * 32;
+    c.base.nbp = (c.base.L + BM - 1) / BM;
+    c.base.nb_total = c.base.nbp * N;
+    c.base.lead = 0;
+    constexpr int LDS = VRing<T, D, M_LSE, FR>::BYTES;
+    const void *fn = reinterpret_cast<const void *>(&vchain_kernel<T, D, FR>);
+    static bool raised[MAX_DEVICES];
+    if (LDS > 48 * 1024 && !raised[dev]) {
+        if (hipFuncSetAttribute(fn, hipFuncAttributeMaxDynamicSharedMemorySize, LDS) != hipSuccess) return SKA_EHIP;
+        raised[dev] = true;
+    }
+    int &cap = g_chain_cap[dev][slot];
+    if (cap == 0) {
+        int per_cu = 0, cus = 0;
+        if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, fn, NTHREADS, LDS) != hipSuccess ||
+            hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess)
+            return SKA_EHIP;
+        cap = per_cu * cus > 0 ? per_cu * cus : -1;
+    }
+    const int want = (c.base.nb_total + 7) / 8 * 8;
+    const int grid = want < cap ? want : cap / 8 * 8;   // a multiple of eight: a workgroup's blocks stay on its XCD
+    if (grid < 8) return SKA_EUNSUPPORTED;
+    void *args[] = {&c};
+    if (hipLaunchCooperativeKernel(fn, dim3(grid), dim3(NTHREADS), args, LDS, st) != hipSuccess) {
+        (void)hipGetLastError();
+        return SKA_EUNSUPPORTED;
+    }
+    return SKA_OK;
+}
 
 template <typename T, int D> int sweep(Call &cx, int mode, const SweepArgs &a, int N)
 {
@@ -451,7 +492,73 @@ int fwd_impl(Call &cx, const Problem &p, const void *Qin, const void *K, const v
         SKA_TRY((spoke_scores<T, D>(p, Qin, K, tok, tok + (long)N * p.ldw(), st)));
     }
     float stage_c2 = c2, stage_sdb2 = base.sdb2;   // (a continuation stage has its own score scale)
+    // Fused half-steps (sinkhorn_attn_set_fused_half_steps): the half-steps after the cold ones, or
+    // only those of the tail, are queued and run as one launch (vchain_kernel) on the caller's
+    // stream for all problems.  Not with the dustbin (its extra element depends on every block
+    // of the half-step before), not with a continuation schedule (a prescale between stages), not
+    // under stream capture, and only if the workspace has room for the block counters.
+    ChainArgs chain{};
+    int *chain_done = nullptr;
+    bool tail_now = false;
+    {
+        hipStreamCaptureStatus cap = hipStreamCaptureStatusNone;
+        const bool capturing = hipStreamIsCapturing(st, &cap) != hipSuccess || cap != hipStreamCaptureStatusNone;
+        const size_t off = fused ? ws_core_bytes(p) : (ws_qs_bytes(p) + 255) / 256 * 256;
+        if (g_fuse && !cx.noalloc && !capturing && !p.dustbin && !p.n_stages && ws && p.ws_given >= off + ws_chain_bytes(p))
+            chain_done = reinterpret_cast<int *>(reinterpret_cast<unsigned char *>(ws) + off);
+    }
+    // the block size of the separate launches (sweep_one: 128 rows while a dispatch has few rows, else
+    // 256) is taken per dispatch; the chain is one launch, so it needs the two halves of a split call
+    // to agree (they differ only for an odd number of problems around the threshold): results stay
+    // those of the separate launches bit for bit
+    constexpr long SMALL_ROWS = 3L * 256 * 256;
+    const int n_half = (cx.side && N >= 2) ? N / 2 : N;
+    const bool chain_fr1 = sizeof(T) == 4 || (long)n_half * L <= SMALL_ROWS;
+    if (chain_fr1 != (sizeof(T) == 4 || (long)(N - n_half ? N - n_half : N) * L <= SMALL_ROWS)) chain_done = nullptr;
+    auto flush_chain = [&]() -> int {
+        if (chain.nsteps == 0) return SKA_OK;
+        SKA_TRY(cx.join());   // the chain takes all problems on the caller's stream
+        chain.base = base;
+        chain.base.c2 = stage_c2; chain.base.sdb2 = stage_sdb2;
+        chain.Q = Q; chain.K = K; chain.UV = UV; chain.us = us; chain.Lp = Lp;
+        chain.log_a = p.log_a; chain.log_b = p.log_b; chain.len_q = p.len_q; chain.len_k = p.len_k;
+        chain.done = chain_done; chain.spin_limit = g_spin_limit;
+        chain.rev0 = nlaunch & 1;
+        const bool fr1 = chain_fr1;
+        const long nflag = (long)N * ((L + 127) / 128);
+        hipLaunchKernelGGL(fill_kernel, dim3((unsigned)((nflag + 255) / 256)), dim3(256), 0, st,
+                           reinterpret_cast<float *>(chain_done), nflag, nflag, 1, 0.f);
+        if (hipGetLastError() != hipSuccess) return SKA_EHIP;
+        int rc;
+        if constexpr (sizeof(T) == 2) rc = fr1 ? launch_vchain<T, D, 1>(chain, N, st, cx.dev, 0) : launch_vchain<T, D, 2>(chain, N, st, cx.dev, 1);
+        else rc = launch_vchain<T, D, 1>(chain, N, st, cx.dev, 0);
+        if (rc == SKA_EUNSUPPORTED) {   // the device cannot hold the grid: one launch per half-step after all
+            for (int i = 0; i < chain.nsteps; ++i) {
+                const unsigned code = chain.code[i];
+                const bool row = code & 1;
+                SweepArgs a = base;
+                a.c2 = stage_c2; a.sdb2 = stage_sdb2;
+                a.X = row ? Q : K; a.Y = row ? K : Q;
+                a.yt = vec((code >> 8) & 255); a.xs = vec((code >> 16) & 255); a.out_vec = vout(code >> 24);
+                a.olog = Vec{row ? p.log_a : p.log_b, (long)Lp};
+                a.len_own = row ? p.len_q : p.len_k; a.len_oth = row ? p.len_k : p.len_q;
+                a.rev = (chain.rev0 + i) & 1;
+                SKA_TRY((sweep_one<T, D>(M_LSE, a, N, st, cx.dev)));
+            }
+            rc = SKA_OK;
+        }
+        nlaunch += chain.nsteps;
+        if (pt_run) pt_run->launched(chain.nsteps);
+        chain.nsteps = 0;
+        SKA_TRY(rc);
+        return cx.fork();
+    };
     auto half = [&](bool row, int yslot, int prevslot, int outslot) -> int {
+        if (chain_done && cold == 0 && (g_fuse >= 2 || tail_now)) {
+            if (chain.nsteps == MAXCHAIN) SKA_TRY(flush_chain());
+            chain.code[chain.nsteps++] = (row ? 1u : 0u) | ((unsigned)yslot << 8) | ((unsigned)prevslot << 16) | ((unsigned)outslot << 24);
+            return SKA_OK;
+        }
         SweepArgs a = base;
         a.c2 = stage_c2; a.sdb2 = stage_sdb2;
         a.spoke_own = row ? SQ : SK; a.spoke_oth = row ? SK : SQ;
@@ -496,11 +603,12 @@ int fwd_impl(Call &cx, const Problem &p, const void *Qin, const void *K, const v
         }
         stage_c2 = base.c2 = (sizeof(T) == 2) ? 1.f : base.cs * LOG2E;   // the tail runs at eps (= the last stage's)
         stage_sdb2 = base.sdb2;
+        tail_now = true;
         for (int t = 1; t <= R; ++t) {
             SKA_TRY(half(true, 2 * t - 1, 2 * t - 2, 2 * t));    // u_t from v_{t-1}
             SKA_TRY(half(false, 2 * t, 2 * t - 1, 2 * t + 1));   // v_t from u_t
         }
-        return SKA_OK;
+        return flush_chain();
     };
     SKA_TRY(cx.fork());   // everything above ran for all problems on st
     const int rc_halves = halves();
@@ -782,9 +890,11 @@ size_t sinkhorn_attn_workspace_bytes(int B, int H, int L, int d, int W, int T, i
     return ws_bytes(p);
 }
 
-static int fwd_call(const Problem &p, const void *Q, const void *K, const void *V, void *O, float *UV,
+static int fwd_call(const Problem &p_in, const void *Q, const void *K, const void *V, void *O, float *UV,
                     void *workspace, size_t workspace_bytes, void *stream)
 {
+    Problem p = p_in;
+    p.ws_given = workspace ? workspace_bytes : 0;
     const int d = p.d, dtype = p.dtype;
     if (!Q || !K || !V || !O || !UV) return SKA_EINVAL;
     int rc = check_common(p);
@@ -989,6 +1099,7 @@ int sinkhorn_attn_step(const void *Q, const void *K, const void *V, const void *
                        void *stream)
 {
     Problem p{B, H, L, d, W, T, R, dustbin ? 1 : 0, dtype, eps, dustbin_score, log_a, log_b, len_q, len_k};
+    p.ws_given = workspace_bytes;
     if (!Q || !K || !V || !dO || !O || !UV || !dQ || !dK || !dV) return SKA_EINVAL;
     int rc = check_common(p);
     if (rc != SKA_OK) return rc;
@@ -1184,6 +1295,15 @@ int sinkhorn_attn_set_streams(int n)
     if (n != 1 && n != 2) return SKA_EINVAL;
     std::lock_guard<std::mutex> lk(g_mutex);
     g_streams = n;
+    return SKA_OK;
+}
+
+int sinkhorn_attn_set_fused_half_steps(int mode, unsigned spin_limit)
+{
+    if (mode < 0 || mode > 2) return SKA_EINVAL;
+    std::lock_guard<std::mutex> lk(g_mutex);
+    g_fuse = mode;
+    g_spin_limit = spin_limit ? spin_limit : (1u << 18);
     return SKA_OK;
 }
 

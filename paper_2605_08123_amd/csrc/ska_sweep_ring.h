@@ -27,8 +27,23 @@ template <typename T, int D, int MODE, int FR> struct VRing {
     static constexpr int BYTES = NSLOT * SLOT;
 };
 
-template <typename T, int D, int MODE, int FR>
-__global__ __launch_bounds__(NTHREADS) void vsweep_kernel(const SweepArgs a)
+// One block of owner rows (logical block lb of the launch) of a vector sweep; the whole workgroup
+// calls it.  smem: the ring (VRing::BYTES), red: NWAVES floats of LDS.
+// COH: the potentials (the only data one block of a chain hands to another) are read and written
+// with accesses that are coherent across the XCDs' L2 caches.
+template <bool COH> __device__ __forceinline__ float ld_pot(const float *p)
+{
+    if constexpr (COH) return __hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    else return *p;
+}
+template <bool COH> __device__ __forceinline__ void st_pot(float *p, float v)
+{
+    if constexpr (COH) __hip_atomic_store(p, v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    else *p = v;
+}
+
+template <typename T, int D, int MODE, int FR, bool COH = false>
+__device__ __forceinline__ void vsweep_block(const SweepArgs &a, const int lb, unsigned char *smem, float *red)
 {
     using TL = Tile<T, D>;
     using RG = VRing<T, D, MODE, FR>;
@@ -40,19 +55,6 @@ __global__ __launch_bounds__(NTHREADS) void vsweep_kernel(const SweepArgs a)
     // vector xs, when given, only carries the marks of inactive tokens.
     constexpr bool FIRST = (MODE == M_LSE_FIRST);
 
-    extern __shared__ __align__(16) unsigned char smem[];
-    __shared__ float red[NWAVES];
-
-    const int chunk = (a.nb_total + 7) >> 3;
-    // a.lead workgroups come first (a multiple of 8, so the XCD of a sweep block is unchanged): one
-    // per problem for the dustbin element, started first so that it ends under the sweep
-    if ((int)blockIdx.x < a.lead) {
-        if ((int)blockIdx.x < a.nb_total / a.nbp) dustbin_element(a, blockIdx.x, MODE == M_MATVEC);
-        return;
-    }
-    const int bx = (int)blockIdx.x - a.lead;
-    const int lb = (bx & 7) * chunk + (a.rev ? chunk - 1 - (bx >> 3) : (bx >> 3));
-    if (lb >= a.nb_total) return;
     const int n = lb / a.nbp;
     const int o_blk = (lb % a.nbp) * BM;
 
@@ -76,7 +78,7 @@ __global__ __launch_bounds__(NTHREADS) void vsweep_kernel(const SweepArgs a)
 
     // stabiliser input first, so that waiting for it waits for nothing else
     static_assert(BM <= NTHREADS, "one owner-side potential per thread");
-    float mraw = FIRST ? 0.f : xsp[min(o_blk + min(tid, BM - 1), Le - 1)];   // clamped repeats are harmless
+    float mraw = FIRST ? 0.f : ld_pot<COH>(xsp + min(o_blk + min(tid, BM - 1), Le - 1));   // clamped repeats are harmless
     float mblk = 0.f, m2 = 0.f;
     OwnerFrag<T, D> xf[FR];
     int o_frag[FR];
@@ -125,7 +127,7 @@ __global__ __launch_bounds__(NTHREADS) void vsweep_kernel(const SweepArgs a)
 #pragma unroll
         for (int q = 0; q < TL::CPT; ++q) g.y[q] = *reinterpret_cast<const uint4 *>(tb + min(goff[q], lim));
         const unsigned vo = min(vrow, (unsigned)(rows - 1)) * 4;
-        g.vy = *reinterpret_cast<const float *>(reinterpret_cast<const unsigned char *>(ytp + kc * TT) + vo);
+        g.vy = ld_pot<COH>(reinterpret_cast<const float *>(reinterpret_cast<const unsigned char *>(ytp + kc * TT) + vo));
         g.vw = 0.f;
         if constexpr (MODE == M_MATVEC)
             g.vw = *reinterpret_cast<const float *>(reinterpret_cast<const unsigned char *>(wp + kc * TT) + vo);
@@ -298,7 +300,7 @@ __global__ __launch_bounds__(NTHREADS) void vsweep_kernel(const SweepArgs a)
             float r;
             if (o >= Le) {
                 r = 0.f;   // rows beyond the valid length
-            } else if (xsp[o] == -INFINITY) {
+            } else if (ld_pot<COH>(xsp + o) == -INFINITY) {
                 r = (MODE == M_LSE) ? -INFINITY : 0.f;   // inactive token: stays so
             } else if (MODE == M_LSE && !(tot > 0.f && tot < INFINITY)) {
                 // An active token has active partners (activity is settled by the two cold
@@ -314,7 +316,119 @@ __global__ __launch_bounds__(NTHREADS) void vsweep_kernel(const SweepArgs a)
                 r = pre - fast_exp2((xsp[o] - mblk) * LOG2E) * tot;
                 if (a.olog.p) r *= __expf(-a.olog.p[n * a.olog.stride + o]);
             }
-            a.out_vec.p[n * a.out_vec.stride + o] = r;
+            st_pot<COH>(a.out_vec.p + n * a.out_vec.stride + o, r);
+        }
+    }
+}
+
+// Workgroup -> block of a launch: each XCD (workgroups are dealt round-robin to the eight of them)
+// takes a contiguous eighth of the block sequence, walked forwards or backwards.
+__device__ __forceinline__ int xcd_block(int bx, int nb_total, int rev)
+{
+    const int chunk = (nb_total + 7) >> 3;
+    return (bx & 7) * chunk + (rev ? chunk - 1 - (bx >> 3) : (bx >> 3));
+}
+
+template <typename T, int D, int MODE, int FR>
+__global__ __launch_bounds__(NTHREADS) void vsweep_kernel(const SweepArgs a)
+{
+    extern __shared__ __align__(16) unsigned char smem[];
+    __shared__ float red[NWAVES];
+    // a.lead workgroups come first (a multiple of 8, so the XCD of a sweep block is unchanged): one
+    // per problem for the dustbin element, started first so that it ends under the sweep
+    if ((int)blockIdx.x < a.lead) {
+        if ((int)blockIdx.x < a.nb_total / a.nbp) dustbin_element(a, blockIdx.x, MODE == M_MATVEC);
+        return;
+    }
+    const int lb = xcd_block((int)blockIdx.x - a.lead, a.nb_total, a.rev);
+    if (lb >= a.nb_total) return;
+    vsweep_block<T, D, MODE, FR>(a, lb, smem, red);
+}
+
+// ------------------------------------------------------------------ several half-steps in one launch
+// The half-steps of Eq. 1-2 depend on each other only through the band: block b of half-step h
+// reads the potentials that blocks b - reach ... b + reach wrote in half-step h - 1.  One launch of
+// co-resident workgroups can therefore run a whole chain of half-steps (the differentiable tail
+// of Sec. 2.2, or the base solve and the tail together) with no kernel boundary and no grid-wide
+// barrier in between: every block publishes the number of half-steps it has completed, and a
+// block starts half-step h as soon as its neighbourhood has published h.  The same blocks run
+// the same arithmetic as in separate launches (vsweep_block), so results are identical.
+//   Workgroups are persistent (a cooperative launch sized to what the device holds at once; a
+// workgroup takes every gridDim.x-th block of each half-step) and only ever wait for half-steps
+// with a smaller index, so some workgroup can always proceed.  Waits are bounded all the same:
+// a wait that runs out (another spinning kernel holding the device, a lost workgroup) stops
+// waiting, writes NaN into its block of the result, which reaches every output it feeds, and
+// goes on, so the kernel always ends.
+//   Potentials cross XCDs, whose L2 caches are not coherent with each other: inside a chain they
+// are read and written with agent-coherent accesses (vsweep_block<..., COH = true>), as are the
+// counters; a block raises its counter after all its threads' stores have been acknowledged, and
+// a waiting workgroup issues its reads after it has seen the counters.  (Fences at agent scope
+// would do too, but they write back and invalidate the whole L2, operand tiles included.)
+constexpr int MAXCHAIN = 96;
+struct ChainArgs {
+    SweepArgs base;            // sizes, scales, nbp / nb_total; X, Y, vectors are set per half-step
+    const void *Q, *K;         // score operands: a row half-step owns Q and streams K, a column one the reverse
+    float *UV;                 // potentials: slot s of problem n at UV + n us + s Lp
+    long us;
+    int Lp;
+    const float *log_a, *log_b;
+    const int *len_q, *len_k;
+    int nsteps;
+    int rev0;                  // direction of the first half-step's walk over the blocks (alternates)
+    int *done;                 // [nb_total] half-steps completed per block, zero at launch
+    unsigned spin_limit;       // polls of a wait before it gives up
+    unsigned code[MAXCHAIN];   // per half-step: bit 0 row step; bits 8-15, 16-23, 24-31 slots of yt, xs, out
+};
+
+template <typename T, int D, int FR>
+__global__ __launch_bounds__(NTHREADS) void vchain_kernel(const ChainArgs c)
+{
+    constexpr int BM = NWAVES * FR * 32;
+    extern __shared__ __align__(16) unsigned char smem[];
+    __shared__ float red[NWAVES];
+    const int tid = threadIdx.x;
+    const int nb = c.base.nb_total, nbp = c.base.nbp;
+    const int reach = (c.base.W + BM - 1) / BM;   // blocks on either side whose potentials a block reads
+    const int slots = ((nb + 7) >> 3) * 8;
+    for (int hs = 0; hs < c.nsteps; ++hs) {
+        const unsigned code = c.code[hs];
+        const bool row = code & 1;
+        SweepArgs a = c.base;
+        a.X = row ? c.Q : c.K; a.Y = row ? c.K : c.Q;
+        a.yt = Vec{c.UV + (long)((code >> 8) & 255) * c.Lp, c.us};
+        a.xs = Vec{c.UV + (long)((code >> 16) & 255) * c.Lp, c.us};
+        a.out_vec = VecOut{c.UV + (long)(code >> 24) * c.Lp, c.us};
+        a.olog = Vec{row ? c.log_a : c.log_b, (long)c.Lp};
+        a.len_own = row ? c.len_q : c.len_k; a.len_oth = row ? c.len_k : c.len_q;
+        a.rev = (c.rev0 + hs) & 1;
+        for (int bx = blockIdx.x; bx < slots; bx += gridDim.x) {
+            const int lb = xcd_block(bx, nb, a.rev);
+            if (lb >= nb) continue;   // (uniform)
+            const int n = lb / nbp, bi = lb % nbp;
+            const int lo = n * nbp + max(bi - reach, 0), hi = n * nbp + min(bi + reach, nbp - 1);
+            // wait until the neighbourhood (this block included: it reads its own previous iterate)
+            // has completed hs half-steps; then acquire what they released
+            bool ok = true;
+            if (hs > 0) {
+                unsigned polls = 0;
+                for (;;) {
+                    bool mine = true;
+                    for (int j = lo + tid; j <= hi; j += NTHREADS)
+                        mine = mine && __hip_atomic_load(c.done + j, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) >= hs;
+                    ok = __syncthreads_and(mine);   // (the counters' values have arrived: later loads are issued after them)
+                    if (ok || ++polls > c.spin_limit) break;
+                    __builtin_amdgcn_s_sleep(4);
+                }
+            }
+            if (ok) {
+                vsweep_block<T, D, M_LSE, FR, true>(a, lb, smem, red);
+            } else {   // gave up: poison this block's result
+                for (int i = tid; i < BM; i += NTHREADS)
+                    if (bi * BM + i < a.L) st_pot<true>(a.out_vec.p + n * a.out_vec.stride + bi * BM + i, __builtin_nanf(""));
+            }
+            asm volatile("s_waitcnt vmcnt(0)" ::: "memory");   // this thread's stores are acknowledged ...
+            __syncthreads();                                   // ... and so are everybody's
+            if (tid == 0) __hip_atomic_store(c.done + lb, hs + 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
         }
     }
 }
