@@ -285,7 +285,11 @@ int sinkhorn_attn_base_vjp(const void *Q, const void *K, const float *log_a, con
  * Certified tail-depth selection (Cor. "Certified Tail-Depth Selection"): for R = 1, 2, ...,
  * R_max run the forward and the stopped-base backward of depth R, take eta_R from it, evaluate
  * the certificate e_R = (D_x z_T)^T eta_R with sinkhorn_attn_base_vjp, and stop at the first R
- * whose largest absolute entry over (dQ, dK) parts of e_R is <= tau.  Then the gradient left in
+ * whose largest absolute entry over (dQ, dK) parts of e_R is <= tau.  The T-step base solve runs
+ * once (all its iterates are kept for the certificate) and depth R + 1 adds one tail step and an
+ * output map to the iterates of depth R; per depth that leaves the depth-R backward and the
+ * certificate's own T-deep vector-Jacobian product, which is most of the time (trying four depths
+ * at T = 15 costs about six (T, 4) steps).  Then the gradient left in
  * dQ, dK, dV differs from full backpropagation through the same T-step base solve by at most
  * tau in every entry (the dV part of the gap is zero: V does not enter the base solve).
  *   Q, K, V, dO in; O, dQ, dK, dV out: results of the selected depth (of R_max if none passes).

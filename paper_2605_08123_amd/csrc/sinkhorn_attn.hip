@@ -55,6 +55,9 @@ struct Problem {
     const float *q_db = nullptr, *k_db = nullptr, *v_db = nullptr;   // learned dustbin tokens [N][d] fp32, or null
     float *dq_db = nullptr, *dk_db = nullptr, *dv_db = nullptr;      //   and their gradients (backward)
     bool token() const { return q_db != nullptr; }
+    long uv_us = 0;                                   // floats between the UV blocks of consecutive problems (0: dense, 2(R+1) Lp)
+    int resume_t = 0;                                 // forward: UV holds the iterates up to tail step resume_t - 1; run that
+                                                      //   tail step and the output map only (the depth selector's increments)
     size_t ws_given = 0;                              // bytes of the caller's workspace (forward: room for the chain's counters?)
     int n_stages = 0;                                 // forward: continuation schedule of the base solve
     const float *eps_stage = nullptr;                 //   (host arrays; 0 stages: T steps at eps)
@@ -452,7 +455,7 @@ int fwd_impl(Call &cx, const Problem &p, const void *Qin, const void *K, const v
     }
     const int N = p.N(), L = p.L, Lp = p.Lp();
     const int R = p.R;
-    const long us = 2L * (R + 1) * Lp;
+    const long us = p.uv_us ? p.uv_us : 2L * (R + 1) * Lp;
     auto vec = [&](int k) { return Vec{UV + (long)k * Lp, us}; };   // slot 2t: u_t, slot 2t + 1: v_t
     auto vout = [&](int k) { return VecOut{UV + (long)k * Lp, us}; };
     SweepArgs base{};
@@ -463,7 +466,7 @@ int fwd_impl(Call &cx, const Problem &p, const void *Qin, const void *K, const v
     base.nh = p.H;
 
     // u0 = v0 = 0: the base solve starts from v = 0
-    {
+    if (!p.resume_t) {
         long tot = 2L * Lp * N;
         hipLaunchKernelGGL(fill_kernel, dim3((tot + 255) / 256), dim3(256), 0, st, UV, 2L * Lp, us, N, 0.f);
         if (hipGetLastError() != hipSuccess) return SKA_EHIP;
@@ -477,11 +480,15 @@ int fwd_impl(Call &cx, const Problem &p, const void *Qin, const void *K, const v
     // that tracks a running maximum, which is exact whatever the scores are and tells an empty sum
     // (no active partner) from a small one.  With token masks the first column half-step does so
     // too: after these two every token's activity is settled, and an empty sum later is an error.
-    int cold = (p.mask_q || p.mask_k) ? 2 : 1;
+    int cold = p.resume_t ? 0 : (p.mask_q || p.mask_k) ? 2 : 1;
     int nlaunch = 0;
     PhaseTimer pt_first(SKA_PH_FIRST, cx);   // the two cold launches are the other (max-tracking) kernel
     PhaseTimer *pt_run = nullptr;
     alignas(PhaseTimer) unsigned char pt_run_mem[sizeof(PhaseTimer)];
+    if (cold == 0) {
+        pt_first.end();
+        pt_run = new (pt_run_mem) PhaseTimer(SKA_PH_SCALING, cx);
+    }
     // half-step: out slot <- -LSE over the band of (S + yt); prev slot only stabilises
     // learned dustbin tokens: spoke score vectors instead of the scalar score
     Vec SQ{nullptr, 0}, SK{nullptr, 0};
@@ -582,7 +589,7 @@ int fwd_impl(Call &cx, const Problem &p, const void *Qin, const void *K, const v
         // base solve: T steps at eps, or the stages of the continuation schedule (remark
         // "Fixed-Budget eps-Scaling"): stage s runs on the scores A / eps_s; between stages both
         // potentials are carried in cost units, x -> x eps_s / eps_{s+1} (u only stabilises)
-        const int nst = p.n_stages ? p.n_stages : 1;
+        const int nst = p.resume_t ? 0 : p.n_stages ? p.n_stages : 1;
         for (int sidx = 0; sidx < nst; ++sidx) {
             const float es = p.n_stages ? p.eps_stage[sidx] : p.eps;
             const int Ts = p.n_stages ? p.T_stage[sidx] : p.T;
@@ -604,7 +611,7 @@ int fwd_impl(Call &cx, const Problem &p, const void *Qin, const void *K, const v
         stage_c2 = base.c2 = (sizeof(T) == 2) ? 1.f : base.cs * LOG2E;   // the tail runs at eps (= the last stage's)
         stage_sdb2 = base.sdb2;
         tail_now = true;
-        for (int t = 1; t <= R; ++t) {
+        for (int t = p.resume_t ? p.resume_t : 1; t <= R; ++t) {
             SKA_TRY(half(true, 2 * t - 1, 2 * t - 2, 2 * t));    // u_t from v_{t-1}
             SKA_TRY(half(false, 2 * t, 2 * t - 1, 2 * t + 1));   // v_t from u_t
         }
@@ -653,7 +660,7 @@ int bwd_impl(Call &cx, const Problem &p, const void *Qin, const void *K, const v
     }
     const int N = p.N(), L = p.L, Lp = p.Lp();
     const int R = p.R, nq = p.direct() ? R : pack_groups(R);
-    const long us = 2L * (R + 1) * Lp, ldw = p.ldw();
+    const long us = p.uv_us ? p.uv_us : 2L * (R + 1) * Lp, ldw = p.ldw();
     const long nldp = (long)N * ldw;
     auto uv = [&](int k) { return Vec{UV + (long)k * Lp, us}; };   // slot 2t: u_t, slot 2t + 1: v_t
     float *wf = reinterpret_cast<float *>(ws);
@@ -843,7 +850,7 @@ int bwd_impl(Call &cx, const Problem &p, const void *Qin, const void *K, const v
 // the tail-depth selector's scratch, carved out of one workspace
 size_t up256(size_t x) { return (x + 255) / 256 * 256; }
 struct SelectLayout {
-    size_t core, eq, ek, uvb, eta, norm, total;
+    size_t core, eq, ek, uvb, uvx, eta, norm, total;
 };
 SelectLayout select_layout(const Problem &p, int T, int R_max)
 {
@@ -855,7 +862,8 @@ SelectLayout select_layout(const Problem &p, int T, int R_max)
     l.eq = up256(ws_bytes(q));
     l.ek = l.eq + up256(mat);
     l.uvb = l.ek + up256(mat);
-    l.eta = l.uvb + up256((size_t)p.N() * 2 * (T + 1) * p.Lp() * sizeof(float));
+    l.uvx = l.uvb + up256((size_t)p.N() * 2 * (T + 1) * p.Lp() * sizeof(float));
+    l.eta = l.uvx + up256((size_t)p.N() * 2 * (R_max + 1) * p.Lp() * sizeof(float));
     l.norm = l.eta + up256((size_t)p.N() * p.Lp() * sizeof(float));
     l.total = l.norm + 256;
     return l;
@@ -1225,11 +1233,25 @@ int sinkhorn_attn_select_tail_depth(const void *Q, const void *K, const void *V,
     // all iterates of the base solve, once (O is scratch here)
     SKA_TRY(sinkhorn_attn_fwd_varlen(Q, K, V, log_a, log_b, len_q, len_k, O, UVb, B, H, L, d, W, 0, T, eps, dustbin,
                                      dustbin_score, dtype, w, l.eq, stream));
+    // Depth R + 1 shares the base state and the tail steps 1 .. R with depth R, so nothing is solved
+    // twice: UVx holds the iterates of the deepest tail so far at the stride of depth R_max, its
+    // slots 0, 1 are the base state (u_T, v_T) the run above ended in, and depth R adds one tail
+    // step (two half-steps) and an output map to it.
+    float *UVx = reinterpret_cast<float *>(w + l.uvx);
+    const int Lp = p.Lp(), N = p.N();
+    const long usx = 2L * (R_max + 1) * Lp;
+    hipLaunchKernelGGL(slots_copy_kernel, dim3((unsigned)((2L * Lp + 255) / 256), N), dim3(256), 0, st, UVb,
+                       2L * (T + 1) * Lp, 2 * T, UVx, usx, 0, 2, Lp);
+    if (hipGetLastError() != hipSuccess) return SKA_EHIP;
+    int R_last = 0;
     for (int R = 1; R <= R_max; ++R) {
-        SKA_TRY(sinkhorn_attn_fwd_varlen(Q, K, V, log_a, log_b, len_q, len_k, O, UV, B, H, L, d, W, T, R, eps,
-                                         dustbin, dustbin_score, dtype, w, l.eq, stream));
-        SKA_TRY(sinkhorn_attn_bwd_varlen(Q, K, V, log_a, log_b, len_q, len_k, O, dO, UV, dQ, dK, dV, eta, B, H, L,
-                                         d, W, T, R, eps, dustbin, dustbin_score, dtype, w, l.eq, stream));
+        R_last = R;
+        Problem q = p;
+        q.R = R; q.uv_us = usx;
+        Problem qf = q;
+        qf.resume_t = R;
+        SKA_TRY(fwd_call(qf, Q, K, V, O, UVx, w, l.eq, stream));
+        SKA_TRY(bwd_problem(q, Q, K, V, O, dO, UVx, dQ, dK, dV, eta, w, l.eq, stream));
         SKA_TRY(sinkhorn_attn_base_vjp(Q, K, log_a, log_b, len_q, len_k, UVb, eta, eQ, eK, B, H, L, d, W, T, eps,
                                        dustbin, dustbin_score, dtype, w, l.eq, stream));
         hipLaunchKernelGGL(fill_kernel, dim3(1), dim3(64), 0, st, norm, 2L, 2L, 1, 0.f);
@@ -1249,10 +1271,13 @@ int sinkhorn_attn_select_tail_depth(const void *Q, const void *K, const void *V,
         if (eta_absmax) eta_absmax[R - 1] = host[1];
         if (host[0] <= tau) {
             *R_selected = R;
-            return SKA_OK;
+            break;
         }
     }
-    return SKA_OK;
+    // the caller's UV: the iterates of the depth whose results are left in O, dQ, dK, dV, densely packed
+    hipLaunchKernelGGL(slots_copy_kernel, dim3((unsigned)((2L * (R_last + 1) * Lp + 255) / 256), N), dim3(256), 0, st,
+                       UVx, usx, 0, UV, 2L * (R_last + 1) * Lp, 0, 2 * (R_last + 1), Lp);
+    return hipGetLastError() == hipSuccess ? SKA_OK : SKA_EHIP;
 }
 
 int sinkhorn_attn_probe_issue(float *scratch, size_t scratch_bytes, int tiles, int waves_per_simd, double *ms6,

@@ -262,6 +262,16 @@ __global__ void mask_fill_kernel(float *UV, long us, int Lp, int L, const unsign
     if (mk && !mk[m]) UV[n * us + Lp + i] = -INFINITY;
 }
 
+// dst[n][dslot0 + s][:] = src[n][sslot0 + s][:] for s < nslots: potential vectors between two UV arrays
+// of different depth (problem strides sstride, dstride floats; a slot is Lp floats)
+__global__ void slots_copy_kernel(const float *src, long sstride, int sslot0, float *dst, long dstride, int dslot0,
+                                  int nslots, int Lp)
+{
+    const int n = blockIdx.y;
+    const long i = (long)blockIdx.x * blockDim.x + threadIdx.x;
+    if (i < (long)nslots * Lp) dst[n * dstride + (long)dslot0 * Lp + i] = src[n * sstride + (long)sslot0 * Lp + i];
+}
+
 // p[n][j] *= f for j < per (the base potentials between two stages of a continuation schedule)
 __global__ void scale_kernel(float *p, long per, long stride, int nprob, float f)
 {
