@@ -118,6 +118,33 @@ __device__ __forceinline__ void vsweep_block(const SweepArgs &a, const int lb, u
         float vy, vw;
         int rows;          // valid rows of the tile: 32 = whole, 0 = outside the matrix (uniform)
     };
+    // A block whose every tile (the prefetched ones included) is a whole tile inside the matrix and
+    // whose owner rows are all valid takes the loop with no clamps, no zeroing and no validity
+    // tests (FAST): all but the blocks at the two ends of a sequence.
+    const bool fast_blk = kbase >= 0 && (long)(kbase + S + RG::LEAD + 1) * TT <= Lt && o_blk + BM <= Le;
+    const unsigned char *ybytes = reinterpret_cast<const unsigned char *>(Yb);
+    const unsigned char *ytbytes = reinterpret_cast<const unsigned char *>(ytp) + vrow * 4;
+    const unsigned char *wbytes = (MODE == M_MATVEC) ? reinterpret_cast<const unsigned char *>(wp) + vrow * 4 : nullptr;
+    auto g_load_fast = [&](Inflight &g, int k) {   // 0 <= k, tile k whole
+        g.rows = TT;
+        const unsigned char *tb = ybytes + (long)k * TILE_BYTES;
+#pragma unroll
+        for (int q = 0; q < TL::CPT; ++q) g.y[q] = *reinterpret_cast<const uint4 *>(tb + goff[q]);
+        g.vy = ld_pot<COH>(reinterpret_cast<const float *>(ytbytes + (long)k * (TT * 4)));
+        g.vw = 0.f;
+        if constexpr (MODE == M_MATVEC) g.vw = *reinterpret_cast<const float *>(wbytes + (long)k * (TT * 4));
+    };
+    auto s_store_fast = [&](Inflight &g, int j) {
+        unsigned char *sl = smem + (j & (RG::NSLOT - 1)) * RG::SLOT;
+#pragma unroll
+        for (int q = 0; q < TL::CPT; ++q)
+            if (TL::CHUNKS % NTHREADS == 0 || tid + q * NTHREADS < TL::CHUNKS)
+                *reinterpret_cast<uint4 *>(sl + soff[q]) = g.y[q];
+        if (tid < TT) {
+            reinterpret_cast<float *>(sl + RG::OFF_VY)[tid] = fmaf(g.vy, LOG2E, m2);
+            if constexpr (MODE == M_MATVEC) reinterpret_cast<float *>(sl + RG::OFF_VW)[tid] = g.vw;
+        }
+    };
     auto g_load = [&](Inflight &g, int k) {
         const int kc = min(max(k, 0), klast);
         const int rows = min(TT, Lt - kc * TT);   // >= 1
@@ -171,95 +198,113 @@ __device__ __forceinline__ void vsweep_block(const SweepArgs &a, const int lb, u
     for (int j = 0; j <= RG::LEAD; ++j) s_store(fill[j], j);
     __syncthreads();
     Inflight nxt;
-
-    for (int s = 0; s < S; ++s) {
-        // the next tile is requested in every step, also when no later step reads it (its
-        // address is clamped, its ring slot is free): a load under a condition would make
-        // the compiler wait for it at once instead of at the store below
-        const int jnew = s + 1 + RG::LEAD;
-        g_load(nxt, kbase + jnew);
-
-        const int j = s + wave * FR;
-        const int k = kbase + j;
-        if (k >= 0 && k <= klast) {
-            const unsigned char *sl = smem + (j & (RG::NSLOT - 1)) * RG::SLOT;
-            const int t0 = k * TT;
-            bool use[FR], interior[FR];
-            f32x16 acc[FR];
-            // the staged potentials are the MFMA's initial accumulator when the score operand
-            // carries the scale already (bf16 storage: make_scores_operand)
-            float yv[16];
+    // Which fragment uses the tile of step s, and whether that tile lies wholly inside its band,
+    // depends on d = s - f alone: with r0 the offset of the band's first column inside tile kbase,
+    // the tile of step s starts 32 d - W - r0 columns from the fragment's first row.  Used for
+    // 0 <= d <= dhi, inside the band for ilo <= d <= ihi.
+    const int r0 = o_blk - W - kbase * TT;   // 0 .. 31
+    const int dhi = (31 + 2 * W + r0) / TT, ilo = (31 + r0 + TT - 1) / TT;
+    const int ihi = (2 * W - 31 + r0) >= 0 ? (2 * W - 31 + r0) / TT : -1;
+    bool fvalid[FR];
 #pragma unroll
-            for (int q = 0; q < 4; ++q) {
-                float4 v4 = *reinterpret_cast<const float4 *>(sl + RG::OFF_VY + (8 * q + 4 * h) * 4);
-                yv[4 * q + 0] = v4.x; yv[4 * q + 1] = v4.y; yv[4 * q + 2] = v4.z; yv[4 * q + 3] = v4.w;
-            }
-#pragma unroll
-            for (int f = 0; f < FR; ++f) {
-                const int of = o_frag[f];
-                use[f] = !(of >= Le || t0 + TT - 1 < of - W || t0 > of + 31 + W);
-                interior[f] = (of + 31 - t0 <= W) && (t0 + TT - 1 - of <= W);
-#pragma unroll
-                for (int r = 0; r < 16; ++r) acc[f][r] = PRE ? yv[r] : 0.f;
-            }
-            ring_dot_multi<D, FR, RG::ROWB>(sl, xf, lane, acc);   // unconditional: an unused tile costs MFMA only
+    for (int f = 0; f < FR; ++f) fvalid[f] = o_frag[f] < Le;
 
-            float wv[MODE == M_MATVEC ? 16 : 1];
-            if constexpr (MODE == M_MATVEC) {
+    auto run = [&](auto fast_c) {
+        constexpr bool FAST = decltype(fast_c)::value;
+        for (int s = 0; s < S; ++s) {
+            // the next tile is requested in every step, also when no later step reads it (its
+            // address is clamped, its ring slot is free): a load under a condition would make
+            // the compiler wait for it at once instead of at the store below
+            const int jnew = s + 1 + RG::LEAD;
+            if constexpr (FAST) g_load_fast(nxt, kbase + jnew);
+            else g_load(nxt, kbase + jnew);
+
+            const int j = s + wave * FR;
+            const int k = kbase + j;
+            if (FAST || (k >= 0 && k <= klast)) {
+                const unsigned char *sl = smem + (j & (RG::NSLOT - 1)) * RG::SLOT;
+                const int t0 = k * TT;
+                bool use[FR], interior[FR];
+                f32x16 acc[FR];
+                // the staged potentials are the MFMA's initial accumulator when the score operand
+                // carries the scale already (bf16 storage: make_scores_operand)
+                float yv[16];
 #pragma unroll
                 for (int q = 0; q < 4; ++q) {
-                    float4 w4 = *reinterpret_cast<const float4 *>(sl + RG::OFF_VW + (8 * q + 4 * h) * 4);
-                    wv[4 * q + 0] = w4.x; wv[4 * q + 1] = w4.y; wv[4 * q + 2] = w4.z; wv[4 * q + 3] = w4.w;
+                    float4 v4 = *reinterpret_cast<const float4 *>(sl + RG::OFF_VY + (8 * q + 4 * h) * 4);
+                    yv[4 * q + 0] = v4.x; yv[4 * q + 1] = v4.y; yv[4 * q + 2] = v4.z; yv[4 * q + 3] = v4.w;
+                }
+#pragma unroll
+                for (int f = 0; f < FR; ++f) {
+                    // (t0 - o_frag[f] = 32 (s - f) - W - r0: the wavefront's skew cancels)
+                    const int dd = s - f;
+                    use[f] = fvalid[f] && dd >= 0 && dd <= dhi;
+                    interior[f] = dd >= ilo && dd <= ihi;
+#pragma unroll
+                    for (int r = 0; r < 16; ++r) acc[f][r] = PRE ? yv[r] : 0.f;
+                }
+                ring_dot_multi<D, FR, RG::ROWB>(sl, xf, lane, acc);   // unconditional: an unused tile costs MFMA only
+
+                float wv[MODE == M_MATVEC ? 16 : 1];
+                if constexpr (MODE == M_MATVEC) {
+#pragma unroll
+                    for (int q = 0; q < 4; ++q) {
+                        float4 w4 = *reinterpret_cast<const float4 *>(sl + RG::OFF_VW + (8 * q + 4 * h) * 4);
+                        wv[4 * q + 0] = w4.x; wv[4 * q + 1] = w4.y; wv[4 * q + 2] = w4.z; wv[4 * q + 3] = w4.w;
+                    }
+                }
+#pragma unroll
+                for (int f = 0; f < FR; ++f) {
+                    if (!use[f]) continue;
+                    float e[16];
+#pragma unroll
+                    for (int r = 0; r < 16; ++r) e[r] = PRE ? acc[f][r] : fmaf(acc[f][r], a.c2, yv[r]);
+                    if (!interior[f]) {
+                        // keep (o, t) iff -W <= t - o <= W; with t = t0 + 4h + off_r (off_r a
+                        // constant of register r) this is lo <= off_r <= lo + 2W for the lane's
+                        // lo = o - W - t0 - 4h.  A tile crosses the lower edge, the upper edge
+                        // or (narrow bands) both: one compare against a constant per edge.
+                        const int lo = o_frag[f] + c - W - t0 - 4 * h;
+                        const int hi = lo + 2 * W;
+                        if (o_frag[f] + 31 - t0 > W) {
+#pragma unroll
+                            for (int r = 0; r < 16; ++r)
+                                if (lo > 8 * (r >> 2) + (r & 3)) e[r] = -INFINITY;
+                        }
+                        if (t0 + TT - 1 - o_frag[f] > W) {
+#pragma unroll
+                            for (int r = 0; r < 16; ++r)
+                                if (hi < 8 * (r >> 2) + (r & 3)) e[r] = -INFINITY;
+                        }
+                    }
+                    if constexpr (FIRST) {
+                        float tm = e[0];
+#pragma unroll
+                        for (int r = 1; r < 16; ++r) tm = fmaxf(tm, e[r]);
+                        const float mn = fmaxf(mx[f], tm);
+                        const float ms = (mn == -INFINITY) ? 0.f : mn;
+                        float sacc = sum[f] * fast_exp2(mx[f] - ms);
+#pragma unroll
+                        for (int r = 0; r < 16; ++r) sacc += fast_exp2(e[r] - ms);
+                        sum[f] = sacc;
+                        mx[f] = mn;
+                    } else {
+#pragma unroll
+                        for (int r = 0; r < 16; ++r) {
+                            const float p = fast_exp2(e[r]);
+                            if constexpr (MODE == M_MATVEC) sum[f] = fmaf(p, wv[r], sum[f]);
+                            else sum[f] += p;
+                        }
+                    }
                 }
             }
-#pragma unroll
-            for (int f = 0; f < FR; ++f) {
-                if (!use[f]) continue;
-                float e[16];
-#pragma unroll
-                for (int r = 0; r < 16; ++r) e[r] = PRE ? acc[f][r] : fmaf(acc[f][r], a.c2, yv[r]);
-                if (!interior[f]) {
-                    // keep (o, t) iff -W <= t - o <= W; with t = t0 + 4h + off_r (off_r a
-                    // constant of register r) this is lo <= off_r <= lo + 2W for the lane's
-                    // lo = o - W - t0 - 4h.  A tile crosses the lower edge, the upper edge
-                    // or (narrow bands) both: one compare against a constant per edge.
-                    const int lo = o_frag[f] + c - W - t0 - 4 * h;
-                    const int hi = lo + 2 * W;
-                    if (o_frag[f] + 31 - t0 > W) {
-#pragma unroll
-                        for (int r = 0; r < 16; ++r)
-                            if (lo > 8 * (r >> 2) + (r & 3)) e[r] = -INFINITY;
-                    }
-                    if (t0 + TT - 1 - o_frag[f] > W) {
-#pragma unroll
-                        for (int r = 0; r < 16; ++r)
-                            if (hi < 8 * (r >> 2) + (r & 3)) e[r] = -INFINITY;
-                    }
-                }
-                if constexpr (FIRST) {
-                    float tm = e[0];
-#pragma unroll
-                    for (int r = 1; r < 16; ++r) tm = fmaxf(tm, e[r]);
-                    const float mn = fmaxf(mx[f], tm);
-                    const float ms = (mn == -INFINITY) ? 0.f : mn;
-                    float sacc = sum[f] * fast_exp2(mx[f] - ms);
-#pragma unroll
-                    for (int r = 0; r < 16; ++r) sacc += fast_exp2(e[r] - ms);
-                    sum[f] = sacc;
-                    mx[f] = mn;
-                } else {
-#pragma unroll
-                    for (int r = 0; r < 16; ++r) {
-                        const float p = fast_exp2(e[r]);
-                        if constexpr (MODE == M_MATVEC) sum[f] = fmaf(p, wv[r], sum[f]);
-                        else sum[f] += p;
-                    }
-                }
-            }
+            if constexpr (FAST) s_store_fast(nxt, jnew);
+            else s_store(nxt, jnew);
+            __syncthreads();
         }
-        s_store(nxt, jnew);
-        __syncthreads();
-    }
+    };
+    if (fast_blk) run(std::true_type{});
+    else run(std::false_type{});
 
 #pragma unroll
     for (int f = 0; f < FR; ++f) {
