@@ -290,7 +290,8 @@ def main() -> int:
             ms, _ = ska.sinkhorn_attn_probe_issue(tiles, wps)
             # cycles one SIMD spends per tile of one wavefront, at the nominal 2.4 GHz
             probe[f"waves_per_simd_{wps}"] = {k: round(1e-3 * t * 2.4e9 / (tiles * wps), 1) for k, t in
-                                              zip(("exp_add", "mfma", "mfma_exp_add", "mfma_add", "mfma_exp", "add"), ms)}
+                                              zip(("exp_add", "mfma", "mfma_exp_add", "mfma_add", "mfma_exp", "add", "mfma_polyexp_add",
+                                                   "mfma_halfpolyexp_add"), ms)}
         out["issue_probe_cycles_per_tile"] = probe
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(w, min(args.cpu_tokens, w.L))

@@ -391,17 +391,20 @@ int sinkhorn_attn_set_fused_half_steps(int mode, unsigned spin_limit);
 int sinkhorn_attn_set_split_min_edges(double edges);
 
 /*
- * Issue-rate probe (benchmark hook, no part of the operator): runs six register-only kernels
+ * Issue-rate probe (benchmark hook, no part of the operator): runs eight register-only kernels
  * with parts of the instruction mix of one scaling-sweep tile per loop iteration -- M: four
  * dependent 32x32x16 bf16 MFMAs, E: 16 exp2, A: 16 adds, the VALU work consuming the MFMA result;
- * 0: E + A, 1: M, 2: M + E + A (the sweep's mix), 3: M + A, 4: M + E, 5: A --
+ * 0: E + A, 1: M, 2: M + E + A (the sweep's mix), 3: M + A, 4: M + E, 5: A, and the sweep's mix
+ * with the exponentials computed on the plain ALUs (fract, floor, a cubic, ldexp) instead of the
+ * transcendental unit: 6: all sixteen, 7: every second one --
  * with waves_per_simd (1..8) wavefronts resident on every SIMD of the current device, `tiles`
- * iterations each, and returns their elapsed milliseconds in ms6[0..5] (host array).  It shows
- * how far MFMA, transcendental and plain VALU work of different wavefronts overlap on one SIMD.  scratch: device
+ * iterations each, and returns their elapsed milliseconds in ms8[0..7] (host array).  It shows
+ * how far MFMA, transcendental and plain VALU work of different wavefronts overlap on one SIMD,
+ * and whether moving exponentials off the transcendental unit would pay.  scratch: device
  * buffer of at least CUs * waves_per_simd * 256 floats.  Synchronises the stream.
  */
 int sinkhorn_attn_probe_issue(float *scratch, size_t scratch_bytes, int tiles, int waves_per_simd,
-                              double *ms6, void *stream);
+                              double *ms8, void *stream);
 
 typedef enum {
     SKA_PH_PRESCALE = 0, /* bf16 storage: copy of Q with the score scale folded in (fwd and bwd) */

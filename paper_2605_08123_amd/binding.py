@@ -105,16 +105,17 @@ def sinkhorn_attn_strerror(status: int) -> str:
 
 
 def sinkhorn_attn_probe_issue(tiles=4000, waves_per_simd=4):
-    """Milliseconds of the six issue-rate probe kernels (exp2 + add, MFMA, all three, MFMA + add,
-    MFMA + exp2, add) and the number of SIMDs they ran on."""
+    """Milliseconds of the eight issue-rate probe kernels (exp2 + add, MFMA, all three, MFMA + add,
+    MFMA + exp2, add, and all three with all or half of the exponentials as a cubic on the plain
+    ALUs) and the number of SIMDs they ran on."""
     cus = torch.cuda.get_device_properties(0).multi_processor_count
     scratch = torch.empty(cus * waves_per_simd * 256, device="cuda", dtype=torch.float32)
-    ms = (ctypes.c_double * 6)()
+    ms = (ctypes.c_double * 8)()
     rc = load().sinkhorn_attn_probe_issue(scratch.data_ptr(), scratch.numel() * 4, int(tiles), int(waves_per_simd), ms,
                                           _stream_ptr())
     if rc != SKA_OK:
         raise SinkhornAttnError(rc)
-    return [ms[k] for k in range(6)], 4 * cus
+    return [ms[k] for k in range(8)], 4 * cus
 
 
 def sinkhorn_attn_set_streams(n: int) -> None:

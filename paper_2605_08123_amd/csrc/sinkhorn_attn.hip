@@ -1280,10 +1280,10 @@ int sinkhorn_attn_select_tail_depth(const void *Q, const void *K, const void *V,
     return hipGetLastError() == hipSuccess ? SKA_OK : SKA_EHIP;
 }
 
-int sinkhorn_attn_probe_issue(float *scratch, size_t scratch_bytes, int tiles, int waves_per_simd, double *ms6,
+int sinkhorn_attn_probe_issue(float *scratch, size_t scratch_bytes, int tiles, int waves_per_simd, double *ms8,
                               void *stream)
 {
-    if (!scratch || !ms6 || tiles < 1 || tiles > (1 << 20) || waves_per_simd < 1 || waves_per_simd > 8) return SKA_EINVAL;
+    if (!scratch || !ms8 || tiles < 1 || tiles > (1 << 20) || waves_per_simd < 1 || waves_per_simd > 8) return SKA_EINVAL;
     int dev = 0, cus = 0;
     if (hipGetDevice(&dev) != hipSuccess || hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess)
         return SKA_EHIP;
@@ -1294,7 +1294,7 @@ int sinkhorn_attn_probe_issue(float *scratch, size_t scratch_bytes, int tiles, i
     if (hipEventCreate(&e0) != hipSuccess) return SKA_EHIP;
     if (hipEventCreate(&e1) != hipSuccess) { (void)hipEventDestroy(e0); return SKA_EHIP; }
     int rc = SKA_OK;
-    for (int what = 0; what < 6 && rc == SKA_OK; ++what) {
+    for (int what = 0; what < 8 && rc == SKA_OK; ++what) {
         for (int rep = 0; rep < 2; ++rep) {   // the second launch is the timed one
             if (rep == 1) (void)hipEventRecord(e0, st);
             if (what == 0) hipLaunchKernelGGL(issue_probe_kernel<0>, dim3(nblk), dim3(256), 0, st, scratch, tiles);
@@ -1303,12 +1303,14 @@ int sinkhorn_attn_probe_issue(float *scratch, size_t scratch_bytes, int tiles, i
             if (what == 3) hipLaunchKernelGGL(issue_probe_kernel<3>, dim3(nblk), dim3(256), 0, st, scratch, tiles);
             if (what == 4) hipLaunchKernelGGL(issue_probe_kernel<4>, dim3(nblk), dim3(256), 0, st, scratch, tiles);
             if (what == 5) hipLaunchKernelGGL(issue_probe_kernel<5>, dim3(nblk), dim3(256), 0, st, scratch, tiles);
+            if (what == 6) hipLaunchKernelGGL(issue_probe_kernel<6>, dim3(nblk), dim3(256), 0, st, scratch, tiles);
+            if (what == 7) hipLaunchKernelGGL(issue_probe_kernel<7>, dim3(nblk), dim3(256), 0, st, scratch, tiles);
         }
         float ms = 0.f;
         if (hipEventRecord(e1, st) != hipSuccess || hipEventSynchronize(e1) != hipSuccess ||
             hipEventElapsedTime(&ms, e0, e1) != hipSuccess || hipGetLastError() != hipSuccess)
             rc = SKA_EHIP;
-        ms6[what] = ms;
+        ms8[what] = ms;
     }
     (void)hipEventDestroy(e0);
     (void)hipEventDestroy(e1);

@@ -46,12 +46,26 @@ __global__ void rowdot_kernel(const T *A, const T *Bm, float *g, long gstride, i
 // four dependent 32x32x16 bf16 MFMAs (M), 16 exp2 (E) and 16 adds (A), the VALU work consuming the
 // MFMA result as in the sweep (other wavefronts of the SIMD are free to fill the gaps):
 //   0: E + A   1: M   2: M + E + A (the sweep's pattern)   3: M + A   4: M + E   5: A
+//   6: M + P + A and 7: M + 8 E + 8 P + A, where P is exp2 on the plain ALUs instead of the
+//      transcendental unit: 2^x = ldexp(p(fract x), floor x) with a cubic p (six instructions:
+//      v_fract_f32, v_cvt_flr_i32_f32, three FMAs, v_ldexp_f32; relative error 1e-4)
 // Without adds the 16 values are folded by eight max3 instead.  One float per thread is written.
+__device__ __forceinline__ float poly_exp2(float x)
+{
+    const float f = __builtin_amdgcn_fractf(x);
+    int i;
+    asm("v_cvt_flr_i32_f32 %0, %1" : "=v"(i) : "v"(x));
+    float p = fmaf(f, 0.0790210f, 0.2240918f);
+    p = fmaf(p, f, 0.6964571f);
+    p = fmaf(p, f, 0.9998931f);
+    return ldexpf(p, i);
+}
 template <int WHAT>
 __global__ __launch_bounds__(256) void issue_probe_kernel(float *out, int tiles)
 {
-    constexpr bool M = (WHAT >= 1 && WHAT <= 4), E = (WHAT == 0 || WHAT == 2 || WHAT == 4);
-    constexpr bool A = (WHAT == 0 || WHAT == 2 || WHAT == 3 || WHAT == 5);
+    constexpr bool M = (WHAT >= 1 && WHAT <= 4) || WHAT >= 6, E = (WHAT == 0 || WHAT == 2 || WHAT == 4 || WHAT >= 6);
+    constexpr bool A = (WHAT == 0 || WHAT == 2 || WHAT == 3 || WHAT >= 5);
+    constexpr int NPOLY = WHAT == 6 ? 16 : WHAT == 7 ? 8 : 0;   // how many of the 16 exponentials go the polynomial way
     bf16x8 a, b;
 #pragma unroll
     for (int i = 0; i < 8; ++i) { a[i] = (__bf16)(threadIdx.x * 0.01f); b[i] = (__bf16)(i * 0.1f); }
@@ -77,7 +91,7 @@ __global__ __launch_bounds__(256) void issue_probe_kernel(float *out, int tiles)
         } else {
             float e[16];
 #pragma unroll
-            for (int r = 0; r < 16; ++r) e[r] = E ? fast_exp2(c[r]) : c[r];
+            for (int r = 0; r < 16; ++r) e[r] = !E ? c[r] : (NPOLY == 16 || (NPOLY == 8 && (r & 1))) ? poly_exp2(c[r]) : fast_exp2(c[r]);
             if constexpr (A) {
 #pragma unroll
                 for (int r = 0; r < 16; ++r) sum += e[r];

@@ -841,14 +841,14 @@ def test_error_codes_on_device():
 
 
 def test_issue_probe_hook():
-    """The register-only probe returns six positive times; MFMA and VALU work together cost at
+    """The register-only probe returns eight positive times; MFMA and VALU work together cost at
     least as much as either alone and at most their sum (with some slack for clocks and launch
     overhead), and leaving the exponentials or the adds out does not cost more than the full mix."""
     import paper_2605_08123_amd as ska
     ms, simds = ska.sinkhorn_attn_probe_issue(tiles=2000, waves_per_simd=4)
     print(f"\n[case] issue probe: {ms} ms on {simds} SIMDs", flush=True)
     assert simds >= 4 and all(t > 0.0 for t in ms)
-    assert len(ms) == 6
+    assert len(ms) == 8
     assert max(ms[0], ms[1]) * 0.9 <= ms[2] <= (ms[0] + ms[1]) * 1.25
     assert ms[3] <= ms[2] * 1.1 and ms[4] <= ms[2] * 1.1 and ms[5] <= ms[0] * 1.1
     with pytest.raises(ska.SinkhornAttnError):
