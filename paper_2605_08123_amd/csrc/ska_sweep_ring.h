@@ -753,7 +753,23 @@ __global__ __launch_bounds__(NTHREADS) void msweep_kernel(const SweepArgs a)
         __syncthreads();
     }
 
-    // epilogue: owner-side factor, store (and the <dot_mat_o, out_o> reduction for dV)
+    // epilogue: owner-side factor, store (and the <dot_mat_o, out_o> reduction for dV).  The rows
+    // of dot_mat are requested first, for all fragments at once: behind the stores they would wait
+    // for every store before them to be acknowledged.
+    uint2 draw[MODE == M_APPLY ? FR : 1][D / 32][4];
+    if constexpr (MODE == M_APPLY) {
+        if (a.dot_mat) {
+#pragma unroll
+            for (int f = 0; f < FR; ++f) {
+                const T *drow = reinterpret_cast<const T *>(a.dot_mat) + moff + (long)min(o_w + 32 * f + c, L - 1) * D;
+#pragma unroll
+                for (int j = 0; j < D / 32; ++j)
+#pragma unroll
+                    for (int q = 0; q < 4; ++q)
+                        draw[f][j][q] = *reinterpret_cast<const uint2 *>(drow + 32 * j + 8 * q + 4 * h);
+            }
+        }
+    }
 #pragma unroll
     for (int f = 0; f < FR; ++f) {
         const int o = o_w + 32 * f + c;
@@ -766,7 +782,6 @@ __global__ __launch_bounds__(NTHREADS) void msweep_kernel(const SweepArgs a)
         if constexpr (MODE == M_APPLY)
             if (a.pay_db) pdb = __expf(a.spoke_own.p[n * a.spoke_own.stride + oc] + xsp[oc] + ytp[L]);
         T *orow = reinterpret_cast<T *>(a.out_mat) + moff + (long)oc * D;
-        const T *drow = a.dot_mat ? reinterpret_cast<const T *>(a.dot_mat) + moff + (long)oc * D : nullptr;
         float dot = 0.f;
 #pragma unroll
         for (int j = 0; j < D / 32; ++j)
@@ -786,10 +801,11 @@ __global__ __launch_bounds__(NTHREADS) void msweep_kernel(const SweepArgs a)
                 if (o < L) {
                     store4<T>(orow + dv, v0, v1, v2, v3);
                     if constexpr (MODE == M_APPLY) {
-                        if (drow && !dead) {
-                            float dd[4];
-                            load4<T>(drow + dv, dd);
-                            dot += dd[0] * v0 + dd[1] * v1 + dd[2] * v2 + dd[3] * v3;
+                        if (a.dot_mat && !dead) {
+                            const uint2 u = draw[f][j][q];   // four bf16: the upper half of a float each
+                            const float d0 = __uint_as_float(u.x << 16), d1 = __uint_as_float(u.x & 0xffff0000u);
+                            const float d2 = __uint_as_float(u.y << 16), d3 = __uint_as_float(u.y & 0xffff0000u);
+                            dot += d0 * v0 + d1 * v1 + d2 * v2 + d3 * v3;
                         }
                     }
                 }
